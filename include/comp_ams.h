@@ -1,0 +1,134 @@
+/*
+ * comp_ams.h - C ABI of the MI355X (gfx950) library for communication-compressed
+ * AMSGrad with error feedback, n workers simulated as a batch on one GPU.
+ *
+ * One step (comp_ams_step) computes, for gradients g_i (i = 0..n-1), each of d fp32:
+ *   x_i     = g_i + e_i                      error feedback, Section 4 ("Error feedback for SGD")
+ *   ghat_i  = C(x_i)                         Top-k or scaled sign, Appendix A
+ *   e_i     = x_i - ghat_i                   Section 4
+ *   gbar    = (1/n) sum_i ghat_i             server aggregation, Section 3
+ *   m       = beta1 m + (1-beta1) gbar       AMSGrad, Section 3 / Algorithm 1 update lines
+ *   v       = beta2 v + (1-beta2) gbar^2
+ *   vhat    = max(vhat, v)
+ *   theta   = theta - lr m / (sqrt(vhat) + eps)        [eps mode 0]
+ *           = theta - lr m / sqrt(vhat + eps)          [eps mode 1, the paper's Vhat = diag(vhat + nu)]
+ * All arithmetic is fp32, one rounding per operation, no fused multiply-add; the sum over
+ * workers runs in ascending worker order.  There is no bias correction (the paper has none).
+ *
+ * Conventions
+ *  - Every function returns a status code; nothing throws or aborts.  On failure outputs
+ *    are left untouched and comp_ams_last_error() describes the reason.
+ *  - The handle owns all optimiser state and scratch in device memory.  It is allocated in
+ *    comp_ams_create (and comp_ams_set_blocks); comp_ams_step allocates nothing.
+ *  - "dev" pointers are device pointers on the GPU that was current when the handle was
+ *    created; "host" pointers are ordinary host memory.  Where a function takes
+ *    `on_device`, 0 means the buffer is host memory and non-zero means device memory.
+ *  - comp_ams_step is asynchronous on the given HIP stream.  Getters and setters run on the
+ *    stream of the most recent step (the null stream before the first) and return after
+ *    their copy has completed.
+ *  - A handle must not be used from two threads at once.
+ *  - Arguments are validated on the host before any device call, so invalid arguments are
+ *    reported as COMP_AMS_EINVAL also on a machine without a GPU.
+ */
+#ifndef COMP_AMS_H
+#define COMP_AMS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct comp_ams comp_ams_t;
+
+enum { COMP_AMS_TOPK = 0, COMP_AMS_BLOCKSIGN = 1 };
+
+enum {
+    COMP_AMS_OK = 0,
+    COMP_AMS_EINVAL = -1,  /* bad argument (range, NULL, inconsistent block table) */
+    COMP_AMS_ENOMEM = -2,  /* device or host allocation failed */
+    COMP_AMS_EDEVICE = -3, /* a HIP call failed (no device, launch error, copy error) */
+    COMP_AMS_ESTATE = -4   /* call does not apply to this handle (wrong compressor kind, no step yet) */
+};
+
+/*
+ * Problem statement of Section 3: model dimension d >= 1, n >= 1 workers; hyper-parameters of
+ * Algorithm 1's input line: beta1, beta2 in [0,1), eps (the paper's nu) > 0, lr (alpha) > 0.
+ *   compressor = COMP_AMS_TOPK:      k_or_block = k, 1 <= k <= d  (Appendix A, "Top-k").
+ *   compressor = COMP_AMS_BLOCKSIGN: k_or_block = B >= 1, contiguous blocks of B coordinates,
+ *                                    the last one partial; B >= d is the whole-vector scaled
+ *                                    sign of Appendix A.  d < 2^31 and n*d < 2^40.
+ * theta starts at zero until comp_ams_set_theta; m, v, vhat and every e_i start at zero.
+ * On success *out receives the handle.
+ */
+int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, int64_t k_or_block,
+                    float beta1, float beta2, float eps, float lr);
+
+/* Frees the handle and everything it owns (waits for pending work).  NULL is a no-op. */
+void comp_ams_destroy(comp_ams_t *h);
+
+/*
+ * Replace the uniform blocks of a BLOCKSIGN handle by n_blocks contiguous blocks of arbitrary
+ * length ("per-layer" scaled sign): host array offsets[0..n_blocks] with offsets[0] = 0,
+ * strictly increasing, offsets[n_blocks] = d.  Each block is compressed by Appendix A's scaled
+ * sign with the block's own length as divisor.  ESTATE on a TOPK handle.
+ */
+int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_blocks);
+
+/* Initial model x_1 (d floats, copied). */
+int comp_ams_set_theta(comp_ams_t *h, const float *theta, int on_device);
+
+/* Step size alpha_t for the following steps (Algorithm 1 allows a non-increasing schedule). */
+int comp_ams_set_lr(comp_ams_t *h, float lr);
+
+/* 0 (default): theta -= lr m/(sqrt(vhat)+eps).  1: theta -= lr m/sqrt(vhat+eps), Section 3. */
+int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
+
+/*
+ * One optimisation step on grads_dev: n*d floats in device memory, row-major [n][d]
+ * (worker i at grads_dev + i*d), read-only, owned by the caller and borrowed until the work
+ * enqueued on `hip_stream` (a hipStream_t, NULL = the null stream) has completed.
+ * The base pointer must be 4-byte aligned; 16-byte alignment gives the fast path.
+ */
+int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream);
+
+/* State getters: d floats each, copied to `out` (host or device memory per on_device). */
+int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device);
+int comp_ams_get_m(comp_ams_t *h, float *out, int on_device);
+int comp_ams_get_v(comp_ams_t *h, float *out, int on_device);
+int comp_ams_get_vhat(comp_ams_t *h, float *out, int on_device);
+
+/* Error memory e_i of worker i in [0,n): d floats. */
+int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device);
+
+/*
+ * TOPK handles, after at least one step: the k coordinates worker i kept in the last step, as
+ * host arrays idx_host[k] (ascending) and val_host[k] (the kept values x_i[idx]); either may be
+ * NULL.  Among equal magnitudes the lower index is kept; magnitude order is the order of the
+ * fp32 bit pattern with the sign bit cleared.
+ */
+int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host);
+
+/* BLOCKSIGN handles, after at least one step: the scales of the last step, host array
+ * [n][n_blocks] row-major, scale = (sum over the block of |x|) / block length. */
+int comp_ams_get_scales(comp_ams_t *h, float *out_host);
+
+/* Number of blocks of a BLOCKSIGN handle (0 for TOPK, negative status on error). */
+int32_t comp_ams_n_blocks(comp_ams_t *h);
+
+/* Restore optimiser state (checkpoint resume): m, v, vhat of d floats and e of n*d floats
+ * ([n][d] row-major); any pointer may be NULL to leave that array as it is. */
+int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const float *vhat, const float *e,
+                       int on_device);
+
+/* Waits until all work enqueued by this handle has completed. */
+int comp_ams_sync(comp_ams_t *h);
+
+/* Message of the last failure on this handle (or of the last failed comp_ams_create when
+ * h is NULL).  The string stays valid until the next failing call. */
+const char *comp_ams_last_error(const comp_ams_t *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMP_AMS_H */

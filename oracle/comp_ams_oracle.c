@@ -1,0 +1,245 @@
+/*
+ * CPU oracle for error-feedback-compressed distributed AMSGrad.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the HIP
+ * library is checked against.  It shares no code with the HIP path and must never
+ * be called from it; only tests, the smoke check and the benchmark's CPU-baseline
+ * leg may load it.
+ *
+ * Every function is the definition in the paper written out, in fp32 with one
+ * rounding per operation (build with -ffp-contract=off, no fast-math):
+ *
+ *   error feedback      Section 4, "Error feedback for SGD":
+ *                         x_i = g_i + delta_i ; ghat_i = C(x_i) ; delta_i = x_i - ghat_i
+ *   Top-k               Appendix A, "Top-k": keep the k coordinates of largest
+ *                         magnitude, zero the rest (full sort, ties -> lower index)
+ *   scaled sign         Appendix A, "Scaled sign": C(x) = ||x||_1 sign(x) / d,
+ *                         applied per contiguous block with the block's own length
+ *   server average      Section 3: gbar = (1/n) sum_i ghat_i
+ *   AMSGrad             Section 3: m, v, vhat = max(vhat, v), x -= alpha Vhat^{-1/2} m
+ *
+ * Readings where the paper is silent are listed next to the code that takes them.
+ * Pins: tests/test_oracle_pins.py (all functions here are pinned).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_TOPK = 0, ORACLE_BLOCKSIGN = 1 };
+
+typedef struct oracle {
+    int64_t d;
+    int32_t n;
+    int32_t compressor;
+    int64_t k;          /* Top-k */
+    int32_t n_blocks;   /* block sign */
+    int64_t *offsets;   /* n_blocks + 1 */
+    float beta1, beta2, eps, lr;
+    int32_t eps_mode;   /* 0: m/(sqrt(vhat)+eps)   1: m/sqrt(vhat+eps) */
+    float *theta, *m, *v, *vhat; /* d */
+    float *e;           /* n*d   error memory delta_i */
+    float *c;           /* n*d   compressed vectors ghat_i of the last step */
+    float *gbar;        /* d     their average */
+    uint32_t *sel;      /* n*k   Top-k: selected indices, ascending, last step */
+    float *scales;      /* n*n_blocks  block sign: scale per (worker, block), last step */
+} oracle_t;
+
+/* ---- magnitude key ------------------------------------------------------------
+ * Magnitude order is the order of the IEEE-754 bit pattern with the sign bit
+ * cleared, read as an unsigned integer.  For finite values this is exactly the
+ * order of |x| (Appendix A orders coordinates by |x_(1)| <= ... <= |x_(d)|);
+ * +0 and -0 are equal, denormals are kept, Inf > finite, NaN > Inf. */
+static uint32_t magnitude_key(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, sizeof u);
+    return u & 0x7fffffffu;
+}
+
+static int cmp_u64(const void *a, const void *b)
+{
+    uint64_t x = *(const uint64_t *)a, y = *(const uint64_t *)b;
+    return (x > y) - (x < y);
+}
+
+static int cmp_u32(const void *a, const void *b)
+{
+    uint32_t x = *(const uint32_t *)a, y = *(const uint32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Top-k (Appendix A).  c[j] = x[j] on the k coordinates of largest magnitude and
+ * +0.0 elsewhere.  The paper is silent on ties: the coordinate of lower index wins.
+ * sel_out (may be NULL) receives the k selected indices in ascending order.
+ * Method: sort all d (magnitude descending, index ascending) and take the first k. */
+void oracle_topk(const float *x, int64_t d, int64_t k, float *c, uint32_t *sel_out)
+{
+    uint64_t *rec = (uint64_t *)malloc((size_t)d * sizeof *rec);
+    for (int64_t j = 0; j < d; ++j) {
+        /* ascending order of (inverted key, index) == key descending, index ascending */
+        uint64_t inv = (uint64_t)(0x7fffffffu - magnitude_key(x[j]));
+        rec[j] = (inv << 32) | (uint64_t)(uint32_t)j;
+    }
+    qsort(rec, (size_t)d, sizeof *rec, cmp_u64);
+    for (int64_t j = 0; j < d; ++j) c[j] = 0.0f;
+    for (int64_t r = 0; r < k; ++r) {
+        uint32_t j = (uint32_t)(rec[r] & 0xffffffffu);
+        c[j] = x[j];
+        if (sel_out) sel_out[r] = j;
+    }
+    if (sel_out) qsort(sel_out, (size_t)k, sizeof *sel_out, cmp_u32);
+    free(rec);
+}
+
+/* Scaled sign (Appendix A) on each contiguous block [off[b], off[b+1]):
+ *   s_b = (sum_{j in b} |x_j|) / |b| ,  c_j = s_b * sign(x_j).
+ * The sum runs in index order in fp64 and is rounded to fp32 once, after the
+ * division.  sign(x) is the IEEE sign bit (so +0 -> +s, -0 -> -s): every entry of
+ * C(x) then has magnitude s_b, which is what makes ||C(x)||_1 = ||x||_1. */
+void oracle_blocksign(const float *x, const int64_t *off, int32_t n_blocks, float *c, float *scales)
+{
+    for (int32_t b = 0; b < n_blocks; ++b) {
+        double S = 0.0;
+        for (int64_t j = off[b]; j < off[b + 1]; ++j) S += (double)fabsf(x[j]);
+        float s = (float)(S / (double)(off[b + 1] - off[b]));
+        if (scales) scales[b] = s;
+        for (int64_t j = off[b]; j < off[b + 1]; ++j) c[j] = copysignf(s, x[j]);
+    }
+}
+
+/* AMSGrad (Section 3; Algorithm 1, the four update lines) on one coordinate range.
+ * No bias correction (the paper has none).  eps_mode 1 is the paper's
+ * Vhat = diag(vhat + nu); eps_mode 0 puts the constant outside the root. */
+void oracle_amsgrad(float *theta, float *m, float *v, float *vhat, const float *gbar, int64_t d,
+                    float beta1, float beta2, float eps, float lr, int32_t eps_mode)
+{
+    const float omb1 = 1.0f - beta1;
+    const float omb2 = 1.0f - beta2;
+    for (int64_t j = 0; j < d; ++j) {
+        float g = gbar[j];
+        float mj = (beta1 * m[j]) + (omb1 * g);
+        float vj = (beta2 * v[j]) + (omb2 * (g * g));
+        float vh = fmaxf(vhat[j], vj);
+        float den = eps_mode ? sqrtf(vh + eps) : (sqrtf(vh) + eps);
+        m[j] = mj;
+        v[j] = vj;
+        vhat[j] = vh;
+        theta[j] = theta[j] - (lr * mj) / den;
+    }
+}
+
+/* ---- stateful optimiser -------------------------------------------------------- */
+
+oracle_t *oracle_create(int64_t d, int32_t n, int32_t compressor, int64_t k_or_block, float beta1,
+                        float beta2, float eps, float lr)
+{
+    oracle_t *o = (oracle_t *)calloc(1, sizeof *o);
+    o->d = d;
+    o->n = n;
+    o->compressor = compressor;
+    o->beta1 = beta1;
+    o->beta2 = beta2;
+    o->eps = eps;
+    o->lr = lr;
+    o->theta = (float *)calloc((size_t)d, sizeof(float));
+    o->m = (float *)calloc((size_t)d, sizeof(float));
+    o->v = (float *)calloc((size_t)d, sizeof(float));
+    o->vhat = (float *)calloc((size_t)d, sizeof(float));
+    o->gbar = (float *)calloc((size_t)d, sizeof(float));
+    o->e = (float *)calloc((size_t)n * (size_t)d, sizeof(float));
+    o->c = (float *)calloc((size_t)n * (size_t)d, sizeof(float));
+    if (compressor == ORACLE_TOPK) {
+        o->k = k_or_block;
+        o->sel = (uint32_t *)calloc((size_t)n * (size_t)o->k, sizeof(uint32_t));
+    } else {
+        /* uniform contiguous blocks of length B, the last one partial; a block
+         * longer than d is the whole vector */
+        int64_t B = k_or_block;
+        int64_t nb = (d + B - 1) / B;
+        o->n_blocks = (int32_t)nb;
+        o->offsets = (int64_t *)malloc((size_t)(nb + 1) * sizeof(int64_t));
+        for (int64_t b = 0; b <= nb; ++b) o->offsets[b] = (b * B < d) ? b * B : d;
+        o->scales = (float *)calloc((size_t)n * (size_t)nb, sizeof(float));
+    }
+    return o;
+}
+
+void oracle_set_blocks(oracle_t *o, const int64_t *offsets, int32_t n_blocks)
+{
+    free(o->offsets);
+    free(o->scales);
+    o->n_blocks = n_blocks;
+    o->offsets = (int64_t *)malloc((size_t)(n_blocks + 1) * sizeof(int64_t));
+    memcpy(o->offsets, offsets, (size_t)(n_blocks + 1) * sizeof(int64_t));
+    o->scales = (float *)calloc((size_t)o->n * (size_t)n_blocks, sizeof(float));
+}
+
+void oracle_set_theta(oracle_t *o, const float *theta) { memcpy(o->theta, theta, (size_t)o->d * sizeof(float)); }
+void oracle_set_lr(oracle_t *o, float lr) { o->lr = lr; }
+void oracle_set_eps_mode(oracle_t *o, int32_t mode) { o->eps_mode = mode; }
+
+/* One step on gradients g[n][d] (row-major).  Workers are independent until the
+ * average, so the loop over workers may run on several threads; no sum is split
+ * across threads, hence the result does not depend on the thread count. */
+void oracle_step(oracle_t *o, const float *g)
+{
+    const int64_t d = o->d;
+    const int32_t n = o->n;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < n; ++i) {
+        float *e = o->e + (size_t)i * (size_t)d;
+        float *c = o->c + (size_t)i * (size_t)d;
+        const float *gi = g + (size_t)i * (size_t)d;
+        /* x_i = g_i + delta_i, kept in e until the error is written */
+        for (int64_t j = 0; j < d; ++j) e[j] = gi[j] + e[j];
+        if (o->compressor == ORACLE_TOPK) {
+            oracle_topk(e, d, o->k, c, o->sel + (size_t)i * (size_t)o->k);
+            /* delta_i = x_i - C(x_i): +0.0 where selected (x - x), x elsewhere (x - 0) */
+            const uint32_t *sel = o->sel + (size_t)i * (size_t)o->k;
+            for (int64_t r = 0; r < o->k; ++r) e[sel[r]] = 0.0f;
+        } else {
+            oracle_blocksign(e, o->offsets, o->n_blocks, c, o->scales + (size_t)i * (size_t)o->n_blocks);
+            for (int64_t j = 0; j < d; ++j) e[j] = e[j] - c[j];
+        }
+    }
+
+    /* gbar = (1/n) sum_i ghat_i : fp32 adds in ascending worker order, then one
+     * division by n (always n, also where few or no workers contributed) */
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t i = 0; i < n; ++i) acc += o->c[(size_t)i * (size_t)d + (size_t)j];
+        o->gbar[j] = acc / (float)n;
+    }
+
+    /* worker-side AMSGrad update; all replicas are identical, one is kept */
+    const int64_t chunk = 1 << 16;
+    const int64_t n_chunks = (d + chunk - 1) / chunk;
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < n_chunks; ++q) {
+        int64_t lo = q * chunk, len = (lo + chunk <= d) ? chunk : d - lo;
+        oracle_amsgrad(o->theta + lo, o->m + lo, o->v + lo, o->vhat + lo, o->gbar + lo, len, o->beta1,
+                       o->beta2, o->eps, o->lr, o->eps_mode);
+    }
+}
+
+float *oracle_theta(oracle_t *o) { return o->theta; }
+float *oracle_m(oracle_t *o) { return o->m; }
+float *oracle_v(oracle_t *o) { return o->v; }
+float *oracle_vhat(oracle_t *o) { return o->vhat; }
+float *oracle_gbar(oracle_t *o) { return o->gbar; }
+float *oracle_error(oracle_t *o) { return o->e; }
+float *oracle_compressed(oracle_t *o) { return o->c; }
+uint32_t *oracle_selected(oracle_t *o) { return o->sel; }
+float *oracle_scales(oracle_t *o) { return o->scales; }
+int32_t oracle_n_blocks(oracle_t *o) { return o->n_blocks; }
+
+void oracle_destroy(oracle_t *o)
+{
+    if (!o) return;
+    free(o->theta); free(o->m); free(o->v); free(o->vhat); free(o->gbar);
+    free(o->e); free(o->c); free(o->sel); free(o->scales); free(o->offsets);
+    free(o);
+}

@@ -1,0 +1,358 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the oracle.
+
+Each test checks oracle/comp_ams_oracle.c against something that is not the oracle:
+hand-derived worked examples (tests/golden), brute force on tiny inputs, closed forms,
+invariants, and the special case k = d that reduces to vanilla distributed AMSGrad.
+"""
+import ctypes
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+f32 = np.float32
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def brute_topk(x, k):
+    """Definition of Top-k with the lower-index tie rule, by Python sorting."""
+    mag = [abs(float(v)) for v in x]          # fp32 -> python float is exact, |+-0| = 0
+    order = sorted(range(len(x)), key=lambda j: (-mag[j], j))
+    return sorted(order[:k])
+
+
+# ----------------------------------------------------------------------------- Top-k
+
+@pytest.mark.parametrize("seed", range(40))
+def test_topk_matches_bruteforce_tiny(seed):
+    rng = np.random.default_rng(seed)
+    d = int(rng.integers(1, 65))
+    k = int(rng.integers(1, d + 1))
+    pool = np.array([0.0, -0.0, 1.0, -1.0, 0.5, 2.0, -2.0, 3.5, 1e-40, -1e-40, 1e-45, 7.25, -7.25],
+                    dtype=np.float32)
+    if seed % 2:
+        x = pool[rng.integers(0, pool.size, d)]           # many ties, +-0, denormals
+    else:
+        x = rng.standard_normal(d).astype(np.float32)
+    c, sel = O.topk(x, k)
+    want = brute_topk(x, k)
+    assert sel.tolist() == want
+    mask = np.zeros(d, bool)
+    mask[want] = True
+    assert np.array_equal(bits(c)[mask], bits(x)[mask])     # kept values are x itself
+    assert np.all(bits(c)[~mask] == 0)                      # the rest is +0.0
+
+
+def test_topk_degenerate_inputs():
+    # all equal -> the k lowest indices
+    c, sel = O.topk(np.full(17, -3.0, f32), 5)
+    assert sel.tolist() == [0, 1, 2, 3, 4]
+    # all zero (mixed signs) -> still the k lowest indices, kept value is the signed zero
+    x = np.array([0.0, -0.0, 0.0, -0.0], f32)
+    c, sel = O.topk(x, 2)
+    assert sel.tolist() == [0, 1] and np.array_equal(bits(c), bits([0.0, -0.0, 0.0, 0.0]))
+    # k = 1 picks the largest magnitude whatever its sign
+    c, sel = O.topk(np.array([1.0, -9.0, 8.0], f32), 1)
+    assert sel.tolist() == [1] and c.tolist() == [0.0, -9.0, 0.0]
+    # k = d is the identity
+    x = np.array([0.5, -0.0, 3.0, 1e-42], f32)
+    c, sel = O.topk(x, 4)
+    assert sel.tolist() == [0, 1, 2, 3] and np.array_equal(bits(c), bits(x))
+    # denormals order correctly and are not flushed
+    x = np.array([1, 3, 2, 0], np.uint32).view(f32)        # 1, 3 and 2 denormal ulps
+    c, sel = O.topk(x, 2)
+    assert sel.tolist() == [1, 2]
+    # a tie exactly at rank k: lower index wins
+    x = np.array([5.0, 2.0, -2.0, 2.0, 7.0], f32)
+    c, sel = O.topk(x, 3)
+    assert sel.tolist() == [0, 1, 4]
+    # Inf sorts above every finite value
+    c, sel = O.topk(np.array([1e38, -np.inf, 3.0], f32), 1)
+    assert sel.tolist() == [1]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_topk_contraction_and_norm_bound(seed):
+    """||C(x)-x||^2 <= (1-k/d)||x||^2 (Appendix A, squared form as for Rand-k) and
+    ||C(x)|| <= (1+sqrt(pi))||x|| (Lemma 1's first bound)."""
+    rng = np.random.default_rng(100 + seed)
+    d = 1000
+    k = int(rng.integers(1, d))
+    x = (rng.standard_normal(d) * np.exp(rng.uniform(-5, 2, d))).astype(f32)
+    c, _ = O.topk(x, k)
+    xd, cd = x.astype(np.float64), c.astype(np.float64)
+    pi = 1.0 - k / d
+    assert np.sum((cd - xd) ** 2) <= pi * np.sum(xd ** 2) * (1 + 1e-12)
+    assert np.linalg.norm(cd) <= (1 + math.sqrt(pi)) * np.linalg.norm(xd)
+
+
+# ----------------------------------------------------------------------------- scaled sign
+
+def test_scaled_sign_golden_example_b():
+    g = json.load(open(os.path.join(GOLD, "example_b_scaled_sign.json")))
+    x = np.array(g["x"], f32)
+    c, s = O.blocksign(x, [0, x.size])
+    assert s.tolist() == [g["scale"]]
+    assert c.tolist() == g["c"]
+    e = x - c
+    assert e.tolist() == g["error"]
+    assert float(np.abs(c).sum()) == g["l1_c"] == g["l1_x"]
+    assert float((e.astype(np.float64) ** 2).sum()) == g["err_sq"]
+    assert g["err_sq"] == g["x_sq"] - g["l1_x"] ** 2 / x.size        # the appendix identity
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_scaled_sign_whole_vector_formula_and_identities(seed):
+    rng = np.random.default_rng(200 + seed)
+    d = int(rng.integers(2, 3000))
+    x = rng.laplace(0, 1, d).astype(f32) * np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    c, s = O.blocksign(x, [0, d])
+    xd = x.astype(np.float64)
+    l1 = np.abs(xd).sum()
+    # literal definition ||x||_1 sign(x) / d
+    want = l1 * np.sign(xd) / d
+    assert np.allclose(c.astype(np.float64), want, rtol=2 ** -23, atol=0)
+    # every entry has magnitude s  =>  ||C(x)||_1 = d*s = ||x||_1
+    assert np.all(np.abs(c) == s[0])
+    assert abs(d * float(s[0]) - l1) <= 1e-6 * l1
+    # ||C(x)-x||^2 = ||x||^2 - ||x||_1^2/d = (1 - ||x||_1^2/(d||x||^2)) ||x||^2
+    err = np.sum((c.astype(np.float64) - xd) ** 2)
+    closed = np.sum(xd ** 2) - l1 ** 2 / d
+    assert abs(err - closed) <= 1e-5 * np.sum(xd ** 2)
+    pi = 1 - l1 ** 2 / (d * np.sum(xd ** 2))
+    assert np.linalg.norm(c.astype(np.float64)) <= (1 + math.sqrt(pi)) * np.linalg.norm(xd) * (1 + 1e-6)
+
+
+def test_scaled_sign_blocks_partial_tail_and_zero_sign():
+    x = np.array([1, -3, 2, 2, -0.0, 0.0, 8], f32)
+    # blocks [0,2) [2,4) [4,6) [6,7): every block uses its own length as divisor
+    c, s = O.blocksign(x, [0, 2, 4, 6, 7])
+    assert s.tolist() == [2.0, 2.0, 0.0, 8.0]
+    assert np.array_equal(bits(c), bits([2, -2, 2, 2, -0.0, 0.0, 8]))   # sign = IEEE sign bit
+    # per-block L1 norm is preserved
+    for lo, hi in [(0, 2), (2, 4), (4, 6), (6, 7)]:
+        assert np.abs(c[lo:hi]).sum() == np.abs(x[lo:hi]).sum()
+    # an all-(-0) block with a non-zero neighbour: -0 takes -s
+    c, s = O.blocksign(np.array([-0.0, 4.0], f32), [0, 2])
+    assert c.tolist() == [-2.0, 2.0] and math.copysign(1, c[0]) == -1
+
+
+def test_uniform_blocks_of_create_clip_and_partial_last():
+    d, n = 10, 1
+    x = np.arange(1, 11, dtype=f32)[None, :]
+    o = O.Oracle(d, n, O.BLOCKSIGN, 4, 0.9, 0.999, 1e-8, 1e-3)
+    o.step(x)
+    assert o.n_blocks == 3
+    assert o.scales[0].tolist() == [2.5, 6.5, 9.5]          # (1+2+3+4)/4, (5..8)/4, (9+10)/2
+    o.close()
+    o = O.Oracle(d, n, O.BLOCKSIGN, 64, 0.9, 0.999, 1e-8, 1e-3)     # block longer than d
+    o.step(x)
+    assert o.n_blocks == 1 and o.scales[0].tolist() == [5.5]
+    o.close()
+
+
+# ----------------------------------------------------------------------------- AMSGrad
+
+def test_amsgrad_constant_gradient_closed_form():
+    """With gbar = c at every step the recursions have closed forms:
+    m_t = c(1-beta1^t), v_t = c^2(1-beta2^t) (increasing, so vhat_t = v_t)."""
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    cvals = np.array([0.3, -2.0, 1e-3, 0.0], np.float64)
+    d = cvals.size
+    th, m, v, vh = (np.zeros(d, f32) for _ in range(4))
+    th[:] = 1.0
+    want_th = np.ones(d)
+    for t in range(1, 201):
+        th, m, v, vh = O.amsgrad(th, m, v, vh, cvals.astype(f32), b1, b2, eps, lr, 0)
+        mt = cvals * (1 - b1 ** t)
+        vt = cvals ** 2 * (1 - b2 ** t)
+        want_th = want_th - lr * mt / (np.sqrt(vt) + eps)
+        if t in (1, 2, 10, 200):
+            assert np.allclose(m, mt, rtol=2e-5, atol=0)
+            assert np.allclose(v, vt, rtol=2e-5, atol=0)
+            assert np.array_equal(vh, v)
+            assert np.allclose(th, want_th, rtol=2e-5, atol=0)
+    # sign: a positive gradient moves theta down, a negative one up, zero leaves it alone
+    assert th[0] < 1 and th[1] > 1 and th[3] == 1.0
+
+
+def test_amsgrad_vhat_keeps_the_running_max():
+    b1, b2 = 0.5, 0.5
+    th, m, v, vh = (np.zeros(1, f32) for _ in range(4))
+    seq = [4.0, 0.0, 0.0, 1.0]
+    vs, vhs = [], []
+    for g in seq:
+        th, m, v, vh = O.amsgrad(th, m, v, vh, np.array([g], f32), b1, b2, 0.25, 1.0, 0)
+        vs.append(float(v[0]))
+        vhs.append(float(vh[0]))
+    assert vs == [8.0, 4.0, 2.0, 1.5]                 # v decays
+    assert vhs == [8.0, 8.0, 8.0, 8.0]                # vhat does not
+
+
+def test_amsgrad_eps_placement_modes():
+    """mode 0: m/(sqrt(vhat)+eps); mode 1 (the paper's Vhat = diag(vhat+nu)): m/sqrt(vhat+eps).
+    Checked against fp64 where vhat ~ eps, where the two differ by a large factor."""
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    g = np.array([1e-3, 1e-5, 3e-2, -1e-4], f32)
+    z = np.zeros(4, f32)
+    gd = g.astype(np.float64)
+    md, vd = (1 - b1) * gd, (1 - b2) * gd ** 2
+    th0, *_ = O.amsgrad(z, z, z, z, g, b1, b2, eps, lr, 0)
+    th1, *_ = O.amsgrad(z, z, z, z, g, b1, b2, eps, lr, 1)
+    assert np.allclose(th0, -lr * md / (np.sqrt(vd) + eps), rtol=1e-5, atol=0)
+    assert np.allclose(th1, -lr * md / np.sqrt(vd + eps), rtol=1e-5, atol=0)
+    assert abs(th0[1] / th1[1]) > 100            # materially different where vhat << eps
+
+
+# ----------------------------------------------------------------------------- whole step
+
+def test_golden_example_a_two_steps():
+    gold = json.load(open(os.path.join(GOLD, "example_a_topk_ef_amsgrad.json")))
+    g = np.array(gold["grads_every_step"], f32)
+    for mode in (0, 1):
+        o = O.Oracle(gold["d"], gold["n"], O.TOPK, gold["k"], gold["beta1"], gold["beta2"], gold["eps"],
+                     gold["lr"])
+        o.set_theta(np.array(gold["theta0"], f32))
+        o.set_eps_mode(mode)
+        for t, want in enumerate(gold["steps"]):
+            o.step(g)
+            assert o.selected.tolist() == want["selected"]
+            assert np.array_equal(bits(o.error), bits(want["error"]))     # incl. +0.0 where selected
+            assert o.gbar.tolist() == want["gbar"]
+            assert o.m.tolist() == want["m"]
+            assert o.v.tolist() == want["v"]
+            assert o.vhat.tolist() == want["vhat"]
+            key = f"theta_mode{mode}"
+            if key in want:
+                assert np.allclose(o.theta, want[key], rtol=3e-7, atol=0)
+        o.close()
+
+
+def vanilla_amsgrad_numpy(theta0, grads_by_step, b1, b2, eps, lr):
+    """Independent vanilla distributed AMSGrad (Section 3): gbar = (1/n) sum_i g_i with
+    fp32 adds in worker order, then the recursion, one fp32 rounding per operation."""
+    b1, b2, eps, lr = f32(b1), f32(b2), f32(eps), f32(lr)
+    omb1, omb2 = f32(1) - b1, f32(1) - b2
+    th = theta0.astype(f32).copy()
+    m = np.zeros_like(th)
+    v = np.zeros_like(th)
+    vh = np.zeros_like(th)
+    for g in grads_by_step:
+        acc = np.zeros_like(th)
+        for i in range(g.shape[0]):
+            acc = acc + g[i]
+        gb = acc / f32(g.shape[0])
+        m = b1 * m + omb1 * gb
+        v = b2 * v + omb2 * (gb * gb)
+        vh = np.maximum(vh, v)
+        th = th - (lr * m) / (np.sqrt(vh) + eps)
+    return th, m, v, vh
+
+
+def test_topk_with_k_equal_d_is_vanilla_amsgrad_bit_for_bit():
+    rng = np.random.default_rng(7)
+    n, d, T = 5, 777, 12
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gs = [(rng.standard_normal((n, d)) * np.exp(rng.uniform(-6, 0, d))).astype(f32) for _ in range(T)]
+    o = O.Oracle(d, n, O.TOPK, d, b1, b2, eps, lr)
+    o.set_theta(theta0)
+    for g in gs:
+        o.step(g)
+        assert not o.error.any()                       # pi = 0: nothing is left behind
+    th, m, v, vh = vanilla_amsgrad_numpy(theta0, gs, b1, b2, eps, lr)
+    assert np.array_equal(bits(o.theta), bits(th))
+    assert np.array_equal(bits(o.m), bits(m))
+    assert np.array_equal(bits(o.v), bits(v))
+    assert np.array_equal(bits(o.vhat), bits(vh))
+    o.close()
+
+
+def test_average_order_and_divisor():
+    # ascending-worker fp32 accumulation: ((1e8 + 1) - 1e8) = 0 in fp32, any other order gives 1
+    g = np.array([[1e8], [1.0], [-1e8]], f32)
+    o = O.Oracle(1, 3, O.TOPK, 1, 0.9, 0.999, 1e-8, 1e-3)
+    o.step(g)
+    assert o.gbar.tolist() == [0.0]
+    o.close()
+    # the divisor is n even where a single worker contributed
+    g = np.array([[8.0, 1.0], [1.0, 2.0], [1.0, 1.0], [1.0, 1.0]], f32)
+    o = O.Oracle(2, 4, O.TOPK, 1, 0.9, 0.999, 1e-8, 1e-3)
+    o.step(g)
+    assert o.selected.tolist() == [[0], [1], [0], [0]]
+    assert o.gbar.tolist() == [(8.0 + 1.0 + 1.0) / 4, 2.0 / 4]
+    o.close()
+
+
+@pytest.mark.parametrize("comp", [O.TOPK, O.BLOCKSIGN])
+def test_error_feedback_bookkeeping_monotone_vhat_and_telescoping(comp):
+    rng = np.random.default_rng(11 + comp)
+    n, d, T = 3, 500, 8
+    kb = 7 if comp == O.TOPK else 64
+    o = O.Oracle(d, n, comp, kb, 0.9, 0.999, 1e-8, 1e-3)
+    e_prev = np.zeros((n, d), f32)
+    vhat_prev = np.zeros(d, f32)
+    sum_g = np.zeros((n, d))
+    sum_c = np.zeros((n, d))
+    for t in range(T):
+        g = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-4, 0, d))).astype(f32)
+        o.step(g)
+        x = g + e_prev                                   # one fp32 add
+        c, e = o.compressed.copy(), o.error.copy()
+        if comp == O.TOPK:
+            # e_new + C(x) == x exactly: one of the two is always zero
+            assert np.array_equal(e + c, x)
+            assert np.all((c != 0).sum(axis=1) <= kb)
+            for i in range(n):
+                assert o.selected[i].tolist() == brute_topk(x[i], kb)
+        else:
+            assert np.array_equal(bits(e), bits(x - c))   # delta = fl(x - C(x))
+            ulp = np.spacing(np.maximum(np.abs(x), np.abs(c)))
+            assert np.all(np.abs((e + c) - x) <= ulp)
+            # per-block L1 norm preserved (up to the one rounding of the scale)
+            nb = o.n_blocks
+            for i in range(n):
+                for b in range(nb):
+                    lo, hi = b * kb, min((b + 1) * kb, d)
+                    l1 = np.abs(x[i, lo:hi].astype(np.float64)).sum()
+                    assert abs(np.abs(c[i, lo:hi].astype(np.float64)).sum() - l1) <= 1e-6 * l1
+        # average: fp32, ascending workers, divided by n
+        acc = np.zeros(d, f32)
+        for i in range(n):
+            acc = acc + c[i]
+        assert np.array_equal(bits(o.gbar), bits(acc / f32(n)))
+        # vhat is monotone and dominates v
+        assert np.all(o.vhat >= vhat_prev) and np.all(o.vhat >= o.v)
+        vhat_prev = o.vhat.copy()
+        e_prev = e
+        sum_g += g
+        sum_c += c
+    # telescoping of delta_t = g_t + delta_{t-1} - ghat_t :  sum_t ghat_t + delta_T = sum_t g_t
+    assert np.allclose(sum_c + e_prev, sum_g, rtol=0, atol=1e-5 * np.abs(sum_g).max())
+    o.close()
+
+
+def test_result_does_not_depend_on_thread_count():
+    gomp = ctypes.CDLL("libgomp.so.1")
+    rng = np.random.default_rng(3)
+    n, d = 6, 3000
+    g = [rng.standard_normal((n, d)).astype(f32) for _ in range(3)]
+    outs = []
+    for threads in (1, 5):
+        gomp.omp_set_num_threads(threads)
+        o = O.Oracle(d, n, O.TOPK, 30, 0.9, 0.999, 1e-8, 1e-3)
+        for gi in g:
+            o.step(gi)
+        outs.append((o.theta.copy(), o.error.copy(), o.selected.copy()))
+        o.close()
+    gomp.omp_set_num_threads(os.cpu_count() or 1)
+    for a, b in zip(*outs):
+        assert np.array_equal(bits(a) if a.dtype == f32 else a, bits(b) if b.dtype == f32 else b)
