@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the error-feedback AMSGrad step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config IDX]
+
+One "step" is one pass of the whole hot path (error-feedback add, compression, error update,
+average over the n simulated workers, AMSGrad update) over one batch of synthetic gradients that
+is already resident in HBM.  Prints ONE JSON line:
+  value        coordinates/s = n*d / step time over K timed steps (profiling off)
+  roofline     the dominant kernel's algorithmic bytes / its average duration measured with HIP
+               events on the step's stream (a second run of K steps with per-kernel events on)
+  cpu_baseline the CPU oracle timed on this machine's host cores on a bounded number of steps
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# (workload name, kernel); absent = not measured.
+MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {}
+
+
+def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:
+    """Bytes a kernel's own part of the method must move, per launch."""
+    nd = n * d
+    return {
+        "bs_fused": 12 * nd + 32 * d,      # read g, read e, write e; read+write theta, m, v, vhat
+        "bs_apply": 12 * nd + 32 * d,
+        "bs_partial": 8 * nd,              # read g, read e
+        "tk_pass1": 12 * nd,               # read g, read e, write x over e
+        "tk_collect": 4 * nd,
+        "tk_final": 32 * d,                # state read+write (candidates are a few per cent more)
+    }.get(name, 0)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="index into the five named workloads")
+    ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all n workers are simulated as a batch on it); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2111_00705_amd as P
+    import workloads as W
+
+    w = W.get(args.config)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    scales = w.scales()
+    nbuf = max(1, min(args.buffers, args.steps))
+    host_grads = [w.grads(t, scales=scales) for t in range(nbuf)]
+    dev_grads = [torch.from_numpy(g).cuda() for g in host_grads]
+
+    kb = w.k if w.compressor == W.TOPK else (w.block if w.block else w.d)
+    h = P.CompAms(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
+    if w.compressor == W.BLOCKSIGN and w.layer_blocks:
+        h.set_blocks(w.block_offsets())
+    h.set_theta(w.theta0())
+
+    def run(k0, count):
+        for t in range(k0, k0 + count):
+            h.step_ptr(dev_grads[t % nbuf].data_ptr(), stream)
+
+    run(0, args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.warmup, args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    coords_per_s = w.n * w.d / (ms_per_step * 1e-3)
+
+    # per-kernel durations: the same K steps again with HIP events around every launch
+    h.profile(True)
+    run(args.warmup + args.steps, args.steps)
+    prof = h.profile_read()
+    h.profile(False)
+    kernels = {name: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.steps,
+                      "us_per_step": ms * 1e3 / args.steps} for name, (ms, cnt) in prof.items()}
+    dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d)
+    dom_us = kernels[dom]["avg_us"]
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
+    step_gbs = w.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import oracle as O
+        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
+        if w.compressor == W.BLOCKSIGN and w.layer_blocks:
+            ora.set_blocks(w.block_offsets())
+        ora.set_theta(w.theta0())
+        ora.step(host_grads[0])                       # warm: first-touch of the oracle's arrays
+        done, spent = 0, 0.0
+        while done < max(1, w.steps) and spent < args.cpu_seconds:
+            c0 = time.perf_counter()
+            ora.step(host_grads[(done + 1) % nbuf])
+            spent += time.perf_counter() - c0
+            done += 1
+        ora.close()
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": w.n * w.d / (spent / done), "unit": "coords/s", "cores": cores, "kind": "oracle",
+               "sample": f"{done} full steps of {w.name} after one warm step, {spent / done * 1e3:.1f} ms/step"}
+
+    out = {
+        "metric": "coords/sec (n*d) per COMP-AMS step",
+        "value": coords_per_s,
+        "unit": "coords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_workers": w.n, "d": w.d,
+                   "compressor": "topk" if w.compressor == W.TOPK else "blocksign",
+                   "k": w.k, "block": w.block, "layer_blocks": w.layer_blocks, "gradient_buffers": nbuf},
+        "roofline": roofline,
+        "step_algorithmic_gbs": round(step_gbs, 1),
+        "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "kernels": {k: {a: round(b, 3) for a, b in v.items()} for k, v in kernels.items()},
+        "cpu_baseline": cpu,
+    }
+    h.destroy()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

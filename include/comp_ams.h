@@ -124,6 +124,22 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
 /* Waits until all work enqueued by this handle has completed. */
 int comp_ams_sync(comp_ams_t *h);
 
+/*
+ * Per-kernel timing for measurement (Section-independent; a benchmark aid).  While enabled, every
+ * kernel that comp_ams_step launches is bracketed by two HIP events recorded on the step's
+ * stream; event creation makes such steps slower and allocate, so keep it off otherwise.
+ * Enabling or disabling waits for pending work and discards earlier recordings.
+ */
+int comp_ams_profile(comp_ams_t *h, int enable);
+
+/*
+ * Reads one timing slot (slots are numbered from 0; one per kernel of the library): *name
+ * receives a static string, *total_ms the summed event time of all recorded launches,
+ * *launches their count; any output pointer may be NULL.  Waits for pending work.  Returns 1 (not
+ * an error) when slot is past the last one.
+ */
+int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches);
+
 /* Message of the last failure on this handle (or of the last failed comp_ams_create when
  * h is NULL).  The string stays valid until the next failing call. */
 const char *comp_ams_last_error(const comp_ams_t *h);

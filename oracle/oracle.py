@@ -115,7 +115,10 @@ class Oracle:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the library may already be gone
+            pass
 
     def set_blocks(self, offsets):
         off = np.ascontiguousarray(offsets, dtype=np.int64)

@@ -1,0 +1,208 @@
+"""Thin ctypes binding of include/comp_ams.h.
+
+Argument marshalling only: every step of the method runs in the HIP kernels of
+libcomp_ams.so.  Tensors are torch CUDA(HIP) tensors used as device memory; the
+current torch stream is passed through as the HIP stream.  If the library has
+not been built the import of the library raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+TOPK = 0
+BLOCKSIGN = 1
+
+OK, EINVAL, ENOMEM, EDEVICE, ESTATE = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "comp_ams_create", "comp_ams_destroy", "comp_ams_set_blocks", "comp_ams_set_theta", "comp_ams_set_lr",
+    "comp_ams_set_eps_mode", "comp_ams_step", "comp_ams_get_theta", "comp_ams_get_m", "comp_ams_get_v",
+    "comp_ams_get_vhat", "comp_ams_get_error", "comp_ams_get_selected", "comp_ams_get_scales",
+    "comp_ams_n_blocks", "comp_ams_set_state", "comp_ams_sync", "comp_ams_last_error", "comp_ams_profile",
+    "comp_ams_profile_read",
+]
+
+
+class CompAmsError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"comp_ams status {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads the in-tree HIP library (building it only if no build exists)."""
+    global _lib
+    if _lib is None:
+        # torch ships its own HIP runtime; importing it first makes this library bind to that same
+        # copy (matched by soname) instead of bringing a second runtime into the process
+        import torch  # noqa: F401
+        if not os.path.exists(_build.LIB):
+            _build.build(force=True)
+        L = C.CDLL(_build.LIB)
+        vp, fp, i64p, u32p = C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_uint32)
+        L.comp_ams_create.argtypes = [C.POINTER(vp), C.c_int64, C.c_int32, C.c_int32, C.c_int64, C.c_float,
+                                      C.c_float, C.c_float, C.c_float]
+        L.comp_ams_destroy.argtypes = [vp]
+        L.comp_ams_destroy.restype = None
+        L.comp_ams_set_blocks.argtypes = [vp, i64p, C.c_int32]
+        L.comp_ams_set_theta.argtypes = [vp, fp, C.c_int]
+        L.comp_ams_set_lr.argtypes = [vp, C.c_float]
+        L.comp_ams_set_eps_mode.argtypes = [vp, C.c_int32]
+        L.comp_ams_step.argtypes = [vp, fp, vp]
+        for name in ("theta", "m", "v", "vhat"):
+            getattr(L, "comp_ams_get_" + name).argtypes = [vp, fp, C.c_int]
+        L.comp_ams_get_error.argtypes = [vp, C.c_int32, fp, C.c_int]
+        L.comp_ams_get_selected.argtypes = [vp, C.c_int32, u32p, fp]
+        L.comp_ams_get_scales.argtypes = [vp, fp]
+        L.comp_ams_n_blocks.argtypes = [vp]
+        L.comp_ams_n_blocks.restype = C.c_int32
+        L.comp_ams_set_state.argtypes = [vp, fp, fp, fp, fp, C.c_int]
+        L.comp_ams_sync.argtypes = [vp]
+        L.comp_ams_profile.argtypes = [vp, C.c_int]
+        L.comp_ams_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
+                                            C.POINTER(C.c_int64)]
+        L.comp_ams_last_error.argtypes = [vp]
+        L.comp_ams_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    """(pointer, on_device) of a torch tensor or a numpy float32 array."""
+    if a is None:
+        return None, 0
+    if isinstance(a, np.ndarray):
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+        return a.ctypes.data, 0
+    assert a.dtype.is_floating_point and a.element_size() == 4 and a.is_contiguous()
+    return a.data_ptr(), 1 if a.is_cuda else 0
+
+
+class CompAms:
+    """comp_ams_create / comp_ams_step / getters, same names as the C ABI."""
+
+    def __init__(self, d, n, compressor, k_or_block, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3):
+        self._h = C.c_void_p()
+        self.d, self.n, self.compressor = int(d), int(n), int(compressor)
+        self.k = int(k_or_block) if compressor == TOPK else 0
+        rc = lib().comp_ams_create(C.byref(self._h), d, n, compressor, k_or_block, beta1, beta2, eps, lr)
+        if rc != OK:
+            self._h = C.c_void_p()
+            raise CompAmsError(rc, lib().comp_ams_last_error(None).decode())
+
+    def _check(self, rc):
+        if rc != OK:
+            raise CompAmsError(rc, lib().comp_ams_last_error(self._h).decode())
+
+    def destroy(self):
+        if self._h:
+            lib().comp_ams_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def set_blocks(self, offsets):
+        off = np.ascontiguousarray(offsets, dtype=np.int64)
+        self._check(lib().comp_ams_set_blocks(self._h, off.ctypes.data_as(C.POINTER(C.c_int64)), off.size - 1))
+
+    def set_theta(self, theta):
+        p, dev = _ptr(theta)
+        self._check(lib().comp_ams_set_theta(self._h, p, dev))
+
+    def set_lr(self, lr):
+        self._check(lib().comp_ams_set_lr(self._h, lr))
+
+    def set_eps_mode(self, mode):
+        self._check(lib().comp_ams_set_eps_mode(self._h, mode))
+
+    def step(self, grads, stream=None):
+        """grads: torch float32 tensor [n, d] on the GPU.  stream: raw hipStream_t value
+        (int) or None for torch's current stream."""
+        import torch
+        assert grads.is_cuda and grads.dtype == torch.float32 and grads.is_contiguous()
+        assert grads.numel() == self.n * self.d
+        if stream is None:
+            stream = torch.cuda.current_stream(grads.device).cuda_stream
+        self._check(lib().comp_ams_step(self._h, grads.data_ptr(), stream))
+
+    def step_ptr(self, grads_ptr, stream=0):
+        self._check(lib().comp_ams_step(self._h, grads_ptr, stream))
+
+    def _get_vec(self, fn, out):
+        if out is None:
+            out = np.empty(self.d, dtype=np.float32)
+        p, dev = _ptr(out)
+        self._check(fn(self._h, p, dev))
+        return out
+
+    def get_theta(self, out=None):
+        return self._get_vec(lib().comp_ams_get_theta, out)
+
+    def get_m(self, out=None):
+        return self._get_vec(lib().comp_ams_get_m, out)
+
+    def get_v(self, out=None):
+        return self._get_vec(lib().comp_ams_get_v, out)
+
+    def get_vhat(self, out=None):
+        return self._get_vec(lib().comp_ams_get_vhat, out)
+
+    def get_error(self, worker, out=None):
+        if out is None:
+            out = np.empty(self.d, dtype=np.float32)
+        p, dev = _ptr(out)
+        self._check(lib().comp_ams_get_error(self._h, worker, p, dev))
+        return out
+
+    def get_selected(self, worker):
+        idx = np.empty(self.k, dtype=np.uint32)
+        val = np.empty(self.k, dtype=np.float32)
+        self._check(lib().comp_ams_get_selected(self._h, worker, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                                val.ctypes.data))
+        return idx, val
+
+    def n_blocks(self):
+        return lib().comp_ams_n_blocks(self._h)
+
+    def get_scales(self):
+        out = np.empty((self.n, self.n_blocks()), dtype=np.float32)
+        self._check(lib().comp_ams_get_scales(self._h, out.ctypes.data))
+        return out
+
+    def set_state(self, m=None, v=None, vhat=None, e=None):
+        ptrs = [_ptr(a) for a in (m, v, vhat, e)]
+        devs = {dev for p, dev in ptrs if p is not None}
+        assert len(devs) <= 1, "all arrays must live on the same side"
+        self._check(lib().comp_ams_set_state(self._h, *[p for p, _ in ptrs], devs.pop() if devs else 0))
+
+    def profile(self, enable):
+        self._check(lib().comp_ams_profile(self._h, 1 if enable else 0))
+
+    def profile_read(self):
+        """{kernel name: (total_ms, launches)} of the launches recorded since profile(True)."""
+        out = {}
+        slot = 0
+        while True:
+            name, ms, cnt = C.c_char_p(), C.c_double(), C.c_int64()
+            rc = lib().comp_ams_profile_read(self._h, slot, C.byref(name), C.byref(ms), C.byref(cnt))
+            if rc == 1:
+                return out
+            self._check(rc)
+            if cnt.value:
+                out[name.value.decode()] = (ms.value, cnt.value)
+            slot += 1
+
+    def sync(self):
+        self._check(lib().comp_ams_sync(self._h))

@@ -1,0 +1,119 @@
+// Device helpers shared by the gfx950 kernels: vector loads of caller-owned gradient rows
+// of any alignment, wavefront reductions with a fixed tree, and the AMSGrad update line.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cams {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kThreads = 256;      // workgroup size of every streaming kernel (4 waves)
+constexpr int kTile = 4096;        // coordinates per tile; rows of library-owned arrays are padded to it
+
+// fp32 operations with one IEEE rounding each.  The translation unit is built with
+// -ffp-contract=off and the pragma below repeats it, so a*b+c is never fused; `/` and sqrtf are
+// the correctly rounded forms (hipcc's default for fp32; the __fsqrt_rn intrinsic is NOT: it maps
+// to the approximate native square root).
+#pragma clang fp contract(off)
+__device__ __forceinline__ float fadd(float a, float b) { return a + b; }
+__device__ __forceinline__ float fsub(float a, float b) { return a - b; }
+__device__ __forceinline__ float fmul(float a, float b) { return a * b; }
+__device__ __forceinline__ float fdiv(float a, float b) { return a / b; }
+__device__ __forceinline__ float fsqrt(float a) { return sqrtf(a); }
+
+// Hyper-parameters of the AMSGrad recursion (Section 3), fp32, prepared on the host.
+struct AmsParams {
+    float beta1, beta2, omb1, omb2;   // omb = 1 - beta, rounded once to fp32
+    float eps, lr;
+    int32_t eps_mode;                 // 0: sqrt(vhat)+eps   1: sqrt(vhat+eps)
+    float n_workers;                  // divisor of the server average
+};
+
+// m, v, vhat, theta update on one coordinate; every operation rounds to fp32 on its own
+// (no fused multiply-add).
+__device__ __forceinline__ void amsgrad_update(float &theta, float &m, float &v, float &vhat, float gbar,
+                                               const AmsParams &p)
+{
+    m = fadd(fmul(p.beta1, m), fmul(p.omb1, gbar));
+    v = fadd(fmul(p.beta2, v), fmul(p.omb2, fmul(gbar, gbar)));
+    vhat = fmaxf(vhat, v);
+    float den = p.eps_mode ? fsqrt(fadd(vhat, p.eps)) : fadd(fsqrt(vhat), p.eps);
+    theta = fsub(theta, fdiv(fmul(p.lr, m), den));
+}
+
+__device__ __forceinline__ void amsgrad_update4(float4 &th, float4 &m, float4 &v, float4 &vh, const float4 &g,
+                                                const AmsParams &p)
+{
+    amsgrad_update(th.x, m.x, v.x, vh.x, g.x, p);
+    amsgrad_update(th.y, m.y, v.y, vh.y, g.y, p);
+    amsgrad_update(th.z, m.z, v.z, vh.z, g.z, p);
+    amsgrad_update(th.w, m.w, v.w, vh.w, g.w, p);
+}
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// Streaming (read-once) loads: the gradient is never read again by the same step.
+__device__ __forceinline__ float4 stream_load4(const float *p)
+{
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ float2 stream_load2(const float *p)
+{
+    const v2f t = __builtin_nontemporal_load(reinterpret_cast<const v2f *>(p));
+    return make_float2(t.x, t.y);
+}
+
+// Four consecutive gradient coordinates row[j..j+3], j a multiple of 4.  The row is caller
+// memory of length d whose start may be 16-, 8- or 4-byte aligned (row i of a dense [n][d]
+// array starts at i*d floats); coordinates at or beyond d read as zero.  The alignment test is
+// uniform across a wavefront.
+__device__ __forceinline__ float4 load_grad4(const float *__restrict__ row, int64_t j, int64_t d)
+{
+    const float *p = row + j;
+    if (j + 4 <= d) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(p) & 15u;
+        if (a == 0) return stream_load4(p);
+        if (a == 8) {
+            const float2 lo = stream_load2(p);
+            const float2 hi = stream_load2(p + 2);
+            return make_float4(lo.x, lo.y, hi.x, hi.y);
+        }
+        return make_float4(p[0], p[1], p[2], p[3]);
+    }
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d) r.x = p[0];
+    if (j + 1 < d) r.y = p[1];
+    if (j + 2 < d) r.z = p[2];
+    if (j + 3 < d) r.w = p[3];
+    return r;
+}
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ void st4(float *p, const float4 &v) { *reinterpret_cast<float4 *>(p) = v; }
+
+__device__ __forceinline__ uint32_t mag_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
+
+// Sum over the 64 lanes with a fixed butterfly; every lane receives the same result, and the
+// result depends only on the lane values, not on timing.
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Sum over a 256-thread workgroup in a fixed order; valid in every thread.  `scratch` holds
+// at least 4 doubles of LDS.  Contains two barriers.
+__device__ __forceinline__ double block_sum(double v, double *scratch)
+{
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[wave] = v;
+    __syncthreads();
+    return ((scratch[0] + scratch[1]) + scratch[2]) + scratch[3];
+}
+
+}  // namespace cams

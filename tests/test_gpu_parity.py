@@ -1,0 +1,287 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bars are stated in tests/parity_util.py."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import paper_2111_00705_amd as P
+import workloads as W
+from oracle import oracle as O
+from parity_util import bits, compare, make_pair, pair_for, run_steps
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def torch_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------------------- worked example
+
+def test_golden_example_a_on_gpu():
+    gold = json.load(open(os.path.join(GOLD, "example_a_topk_ef_amsgrad.json")))
+    g = np.array(gold["grads_every_step"], f32)
+    for mode in (0, 1):
+        announce(f"golden example A, eps mode {mode}")
+        h = P.CompAms(gold["d"], gold["n"], P.TOPK, gold["k"], gold["beta1"], gold["beta2"], gold["eps"], gold["lr"])
+        h.set_eps_mode(mode)
+        gd = torch_dev(g)
+        for want in gold["steps"]:
+            h.step(gd)
+            for i in range(gold["n"]):
+                idx, _ = h.get_selected(i)
+                assert idx.tolist() == want["selected"][i]
+                assert np.array_equal(bits(h.get_error(i)), bits(want["error"][i]))
+            assert h.get_m().tolist() == want["m"]
+            assert h.get_v().tolist() == want["v"]
+            assert h.get_vhat().tolist() == want["vhat"]
+            key = f"theta_mode{mode}"
+            if key in want:
+                assert np.allclose(h.get_theta(), want[key], rtol=3e-7, atol=0)
+        h.destroy()
+
+
+# ------------------------------------------------------------------------------- Top-k, small
+
+@pytest.mark.parametrize("d,n,k", [(1, 1, 1), (3, 2, 1), (5, 3, 5), (63, 2, 7), (257, 3, 100), (4097, 2, 41),
+                                   (10007, 5, 100), (3 * 4096, 4, 123), (20000, 3, 20000)])
+def test_topk_small_shapes(d, n, k):
+    announce(f"topk small d={d} n={n} k={k}")
+    rng = np.random.default_rng(d * 31 + n)
+    scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gpu, ora = make_pair(d, n, P.TOPK, k, theta0=theta0)
+    run_steps(gpu, ora, lambda t: (np.random.default_rng([d, t]).standard_normal((n, d)) * scale).astype(f32),
+              steps=4, tag=f"d={d}")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("case", ["all_equal", "all_zero", "signed_zero_mix", "denormals", "ties_at_rank_k",
+                                  "few_nonzero", "huge_and_inf"])
+def test_topk_degenerate_inputs(case):
+    announce(f"topk degenerate {case}")
+    d, n, k = 9001, 3, 500
+    rng = np.random.default_rng(5)
+    if case == "all_equal":
+        g = np.full((n, d), -2.5, f32)
+    elif case == "all_zero":
+        g = np.zeros((n, d), f32)
+    elif case == "signed_zero_mix":
+        g = np.where(rng.random((n, d)) < 0.5, f32(0.0), f32(-0.0)).astype(f32)
+        g[:, ::97] = 1.0
+    elif case == "denormals":
+        g = rng.integers(0, 50, (n, d)).astype(np.uint32).view(f32).copy()      # 0 .. 49 denormal ulps
+        g[:, ::2] *= -1
+    elif case == "ties_at_rank_k":
+        g = rng.choice(np.array([0.25, -0.25, 0.5, -0.5, 1.0, 3.0], f32), (n, d))
+    elif case == "few_nonzero":
+        g = np.zeros((n, d), f32)
+        g[:, 10:20] = rng.standard_normal((n, 10)).astype(f32)
+    else:
+        g = rng.standard_normal((n, d)).astype(f32) * f32(1e30)
+        g[0, 17] = np.inf
+        g[1, 4000] = -np.inf
+    gpu, ora = make_pair(d, n, P.TOPK, k)
+    # theta would become NaN with Inf gradients on both sides; the comparison below treats NaN == NaN
+    steps = 3
+    import torch
+    for t in range(steps):
+        gd = torch_dev(g)
+        gpu.step(gd)
+        e_prev = ora.error.copy()
+        ora.step(g)
+        for i in range(n):
+            idx, val = gpu.get_selected(i)
+            assert np.array_equal(idx, ora.selected[i]), f"{case} step {t} worker {i}"
+            assert np.array_equal(bits(val), bits((g + e_prev)[i][idx]))
+            assert np.array_equal(bits(gpu.get_error(i)), bits(ora.error[i]))
+        if case != "huge_and_inf":
+            compare(gpu, ora, tag=f"{case} step {t}")
+        else:
+            assert np.array_equal(bits(gpu.get_m()), bits(ora.m))
+            assert np.array_equal(bits(gpu.get_vhat()), bits(ora.vhat))
+    gpu.destroy()
+
+
+def test_topk_k_equal_d_is_vanilla_amsgrad_on_gpu():
+    announce("topk k=d")
+    n, d = 4, 6000
+    rng = np.random.default_rng(9)
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gpu, ora = make_pair(d, n, P.TOPK, d, theta0=theta0)
+    stats = run_steps(gpu, ora, lambda t: np.random.default_rng([9, t]).standard_normal((n, d)).astype(f32), 5)
+    for i in range(n):
+        assert not gpu.get_error(i).any()
+    assert all(s["theta_bit_identical"] for s in stats)
+    gpu.destroy()
+
+
+def test_gradient_base_pointer_alignment_classes():
+    """Rows of a dense [n][d] array start 16-, 8- or 4-byte aligned depending on d and on the base."""
+    import torch
+    for d, shift in [(1001, 0), (1002, 0), (1002, 1), (1004, 2), (1003, 3), (8191, 1)]:
+        for comp, kb in [(P.TOPK, 37), (P.BLOCKSIGN, 200)]:
+            announce(f"alignment d={d} shift={shift} comp={comp}")
+            n = 4
+            g = np.random.default_rng([d, shift]).standard_normal((n, d)).astype(f32)
+            buf = torch.zeros(n * d + 8, dtype=torch.float32, device="cuda")
+            view = buf[shift:shift + n * d]
+            view.copy_(torch.from_numpy(g).reshape(-1))
+            gpu, ora = make_pair(d, n, comp, kb)
+            for t in range(2):
+                gpu.step_ptr(view.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                ora.step(g)
+                compare(gpu, ora, tag=f"d={d} shift={shift} comp={comp} step {t}")
+            gpu.destroy()
+
+
+# ------------------------------------------------------------------------------- block sign, small
+
+@pytest.mark.parametrize("d,n,B", [(1, 1, 1), (7, 2, 3), (64, 2, 64), (1000, 3, 4096), (4096, 2, 4096),
+                                   (4097, 2, 4096), (10007, 5, 1000), (50001, 4, 4096), (30000, 3, 7)])
+def test_blocksign_uniform_small_shapes(d, n, B):
+    announce(f"blocksign small d={d} n={n} B={B}")
+    rng = np.random.default_rng(d + B)
+    scale = np.exp(rng.uniform(-7, -1, d)).astype(f32)
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gpu, ora = make_pair(d, n, P.BLOCKSIGN, B, theta0=theta0)
+    off = np.minimum(np.arange(0, d + B, B), d)
+    off = off[: (d + B - 1) // B + 1]
+    stats = run_steps(gpu, ora, lambda t: (np.random.default_rng([d, B, t]).laplace(0, 1, (n, d)) * scale).astype(f32),
+                      steps=4, tag=f"d={d} B={B}", offsets=off)
+    assert gpu.n_blocks() == ora.n_blocks == off.size - 1
+    assert sum(s["scales_not_bit_identical"] for s in stats) == 0
+    gpu.destroy()
+
+
+def test_blocksign_layer_blocks_and_degenerate_values():
+    announce("blocksign layer table")
+    d, n = 70001, 3
+    off = np.array([0, 1, 3, 64, 5000, 5001, 20000, 69999, 70001], np.int64)
+    gpu, ora = make_pair(d, n, P.BLOCKSIGN, d, offsets=off)
+    rng = np.random.default_rng(77)
+
+    def grads(t):
+        g = rng.standard_normal((n, d)).astype(f32)
+        g[:, 3:64] = 0.0                       # an all-zero block: scale 0, C(x) = +-0
+        g[0, 5:30] = -0.0
+        g[:, 5000] = 1e-41                      # one-element block holding a denormal
+        return g
+
+    run_steps(gpu, ora, grads, steps=3, tag="layers", offsets=off)
+    gpu.destroy()
+
+
+# ------------------------------------------------------------------------------- API behaviour on the GPU
+
+def test_determinism_resume_lr_and_error_codes():
+    import torch
+    announce("determinism / resume / set_lr / status codes")
+    w = W.get(0).scaled(30_011, n=3)
+    s = w.scales()
+    grads = [w.grads(t, scales=s) for t in range(6)]
+
+    def run(h, ts):
+        for t in ts:
+            if t == 3:
+                h.set_lr(5e-4)
+            h.step(torch_dev(grads[t]))
+
+    def state(h):
+        return [h.get_theta(), h.get_m(), h.get_v(), h.get_vhat()] + [h.get_error(i) for i in range(w.n)]
+
+    a = P.CompAms(w.d, w.n, P.TOPK, w.k)
+    a.set_theta(w.theta0())
+    run(a, range(6))
+    b = P.CompAms(w.d, w.n, P.TOPK, w.k)
+    b.set_theta(w.theta0())
+    run(b, range(3))
+    saved = state(b)
+    b.destroy()
+    c = P.CompAms(w.d, w.n, P.TOPK, w.k)                    # resume from the saved state
+    c.set_theta(saved[0])
+    c.set_state(m=saved[1], v=saved[2], vhat=saved[3], e=np.stack(saved[4:]))
+    run(c, range(3, 6))
+    for x, y in zip(state(a), state(c)):
+        assert np.array_equal(bits(x), bits(y))
+    # the oracle agrees with the lr change too
+    o = O.Oracle(w.d, w.n, O.TOPK, w.k, w.beta1, w.beta2, w.eps, w.lr)
+    o.set_theta(w.theta0())
+    for t in range(6):
+        if t == 3:
+            o.set_lr(5e-4)
+        o.step(grads[t])
+    compare(a, o, tag="lr schedule")
+    # status codes
+    with pytest.raises(P.CompAmsError) as ei:
+        a.get_scales()
+    assert ei.value.code == P.ESTATE
+    with pytest.raises(P.CompAmsError) as ei:
+        a.get_error(w.n)
+    assert ei.value.code == P.EINVAL
+    with pytest.raises(P.CompAmsError) as ei:
+        a.set_blocks([0, w.d])
+    assert ei.value.code == P.ESTATE
+    fresh = P.CompAms(100, 2, P.BLOCKSIGN, 10)
+    with pytest.raises(P.CompAmsError) as ei:
+        fresh.get_scales()
+    assert ei.value.code == P.ESTATE
+    for bad in ([0, 50], [1, 100], [0, 60, 40, 100], [0, 50, 50, 100]):
+        with pytest.raises(P.CompAmsError) as ei:
+            fresh.set_blocks(bad)
+        assert ei.value.code == P.EINVAL
+    # device-side getters
+    out = torch.empty(w.d, dtype=torch.float32, device="cuda")
+    a.get_theta(out)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(a.get_theta()))
+    a.destroy(); c.destroy(); fresh.destroy()
+
+
+def test_eps_mode_one_matches_the_papers_placement():
+    announce("eps mode 1")
+    w = W.get(1).scaled(20_003, n=4)
+    gpu, ora = make_pair(w.d, w.n, P.BLOCKSIGN, 4096, theta0=w.theta0(), eps_mode=1)
+    s = w.scales()
+    run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=3, tag="eps1", offsets=w.block_offsets())
+    gpu.destroy()
+
+
+# ------------------------------------------------------------------------------- the five workloads
+
+def test_cfg0_full_all_steps():
+    w = W.get(0)
+    announce(w.name)
+    gpu, ora = pair_for(w)
+    s = w.scales()
+    run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name)
+    gpu.destroy()
+
+
+def test_cfg1_full_all_steps():
+    w = W.get(1)
+    announce(w.name)
+    gpu, ora = pair_for(w)
+    s = w.scales()
+    stats = run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name, check_every=5,
+                      offsets=w.block_offsets())
+    print("cfg1 stats", stats[-1], flush=True)
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("idx,d,n", [(2, 300_003, 16), (3, 400_001, 8), (4, 500_002, 8)])
+def test_cfg2_3_4_scaled(idx, d, n):
+    w = W.get(idx).scaled(d, n=n, steps=5)
+    announce(w.name)
+    gpu, ora = pair_for(w)
+    s = w.scales()
+    run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name, offsets=w.block_offsets())
+    gpu.destroy()
