@@ -1,58 +1,135 @@
 // Scaled-sign compression per contiguous block (Appendix A, "Scaled sign"), with error feedback
-// (Section 4), the server average and the AMSGrad update (Section 3) fused behind it.
+// (Section 4), the server average and the AMSGrad update (Section 3).
 //
-// General path (any block table), three launches:
-//   bs_partial   per (segment, worker): fp64 sum of |g+e| over one piece (<= 4096) of a block
-//   bs_scale     per (block, worker):   fixed-order fp64 sum of the pieces, s = fl32(S / len)
-//   bs_apply     per 1024 coordinates:  loop over workers in ascending order,
-//                x = g+e, c = copysign(s,x), e = x-c, acc += c; then gbar = acc/n and AMSGrad
-// Fused path (uniform blocks that fit one workgroup's registers), one launch:
-//   bs_fused     per block: for each worker, hold x of the whole block in registers, reduce
-//                sum|x| in the workgroup, then finish as above - g and e are read once and e is
-//                written once, which is the algorithmic minimum of 12 bytes per (worker, coordinate).
+// The error memory is kept in deferred form.  After a step the library stores x_i = g_i + e_i (the
+// vector that was compressed) together with that step's block scales s_i; the error itself,
+//     e_i[j] = fl32( x_i[j] - copysign(s_i[block(j)], x_i[j]) ),
+// is formed on the fly when the next step (or a getter) reads x_i.  The arithmetic is exactly the
+// one of the definition, but one step needs a single pass over g and the stored vector:
+//
+//   bs_pass     per (tile of 4096 coordinates, worker): e = stored x minus its sign compression
+//               (previous scales), x = g + e, store x, write the sign bits of x as a bitmap
+//               (1 bit per coordinate), fp64 partial sums of |x| per piece (tile x block)
+//   bs_scale    per (block, worker): fixed-order fp64 sum of the pieces, s = fl32(S / block length)
+//   bs_update   per tile: gbar[j] = (sum_i +-s_i[block(j)]) / n, signs from the bitmaps, workers in
+//               ascending order; then the AMSGrad update of theta, m, v, vhat
+//
+// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written + 2 x 1/8 B of sign
+// bits, for any block size; plus 32 B per coordinate of optimiser state.
 #pragma once
 #include "device_utils.h"
 
 namespace cams {
 
-// Block table on the device.  Segments cut every block into pieces of at most kTile
-// coordinates, counted from the block's own start.
+// Block table on the device.  A "piece" is the intersection of one block with one 4096-aligned
+// tile; pieces are numbered in coordinate order, so the pieces of a tile and the pieces of a
+// block are both contiguous ranges.
 struct BsTable {
     const int32_t *offsets;      // [n_blocks+1] block boundaries
-    const int32_t *seg_lo;       // [n_segs] first coordinate of a segment
-    const int32_t *seg_hi;       // [n_segs] one past its last coordinate
-    const int32_t *block_seg0;   // [n_blocks+1] first segment of each block
-    const int32_t *tile_block;   // [ld/1024] block that holds coordinate 1024*t (clamped to the last block)
+    const int32_t *piece_hi;     // [n_pieces]   one past the last coordinate of a piece
+    const int32_t *piece_blk;    // [n_pieces]   block of a piece
+    const int32_t *tile_piece0;  // [n_tiles+1]  first piece of a tile
+    const int32_t *block_piece0; // [n_blocks+1] first piece of a block
     int32_t n_blocks;
-    int32_t n_segs;
-    int32_t uniform;             // >0: all blocks have this length (the last may be shorter)
+    int32_t n_pieces;
 };
 
-__global__ __launch_bounds__(kThreads) void bs_partial(const float *__restrict__ g, const float *__restrict__ e,
-                                                       int64_t d, int64_t ld, BsTable tb,
-                                                       double *__restrict__ partial)
+// Sign bitmap layout: per worker, per tile, 64 words of 64 bits.  Word (r*4 + wave)*4 + c holds,
+// at bit `lane`, the sign of the coordinate  tile*4096 + 4*(256*r + 64*wave + lane) + c,
+// i.e. the c-th component of the r-th float4 that thread (wave, lane) handles in the tile.
+constexpr int kSignWordsPerTile = kTile / 64;
+
+__device__ __forceinline__ float deferred_sign_error(float xs, float s_prev)
+{
+    return fsub(xs, copysignf(s_prev, xs));
+}
+
+template <bool kPending>
+__global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g, float *__restrict__ xs,
+                                                    int64_t d, int64_t ld, BsTable tb,
+                                                    const float *__restrict__ s_prev,
+                                                    uint64_t *__restrict__ signs,
+                                                    double *__restrict__ partial)
 {
     __shared__ double scratch[4];
-    const int s = blockIdx.x;
+    const int t = blockIdx.x;
     const int i = blockIdx.y;
-    const int lo = tb.seg_lo[s], hi = tb.seg_hi[s];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t base = (int64_t)t * kTile;
     const float *grow = g + (int64_t)i * d;
-    const float *erow = e + (int64_t)i * ld;
-    const int q1 = (hi + 3) >> 2;
-    double acc = 0.0;
-    for (int q = (lo >> 2) + (int)threadIdx.x; q < q1; q += kThreads) {
-        const int j = q << 2;
-        const float4 gv = load_grad4(grow, j, d);
-        const float4 ev = ld4(erow + j);
-        const float x0 = fadd(gv.x, ev.x), x1 = fadd(gv.y, ev.y);
-        const float x2 = fadd(gv.z, ev.z), x3 = fadd(gv.w, ev.w);
-        if (j >= lo && j < hi) acc += (double)fabsf(x0);
-        if (j + 1 >= lo && j + 1 < hi) acc += (double)fabsf(x1);
-        if (j + 2 >= lo && j + 2 < hi) acc += (double)fabsf(x2);
-        if (j + 3 >= lo && j + 3 < hi) acc += (double)fabsf(x3);
+    float *xrow = xs + (int64_t)i * ld;
+    const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
+    const float *sp = s_prev + (int64_t)i * tb.n_blocks;
+    uint64_t *srow = signs + ((int64_t)i * (ld / kTile) + t) * kSignWordsPerTile;
+
+    float4 gv[4], xv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        gv[r] = load_grad4(grow, j, d);
+        xv[r] = ld4(xrow + j);
     }
-    const double S = block_sum(acc, scratch);
-    if (threadIdx.x == 0) partial[(int64_t)i * tb.n_segs + s] = S;
+    float x[4][4];
+    int piece[4];     // piece of the first coordinate of each float4 (multi-piece tiles only)
+    const bool single = (p1 - p0 == 1);
+    const float s_single = (kPending && single) ? sp[tb.piece_blk[p0]] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+        const float xx[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+        int p = p0;
+        if (!single) {
+            while (p + 1 < p1 && j >= tb.piece_hi[p]) ++p;
+            piece[r] = p;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float e = xx[c];
+            if (kPending) {
+                float s = s_single;
+                if (!single) {
+                    while (p + 1 < p1 && j + c >= tb.piece_hi[p]) ++p;
+                    s = sp[tb.piece_blk[p]];
+                }
+                e = deferred_sign_error(xx[c], s);
+            }
+            x[r][c] = (j + c < d) ? fadd(gg[c], e) : 0.f;
+        }
+        st4(xrow + j, make_float4(x[r][0], x[r][1], x[r][2], x[r][3]));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint64_t w = __ballot(__float_as_uint(x[r][c]) >> 31);
+            if (lane == 0) srow[(r * 4 + wave) * 4 + c] = w;
+        }
+    }
+
+    if (single) {
+        double acc = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc += (double)fabsf(x[r][c]);   // padding coordinates hold 0
+        const double S = block_sum(acc, scratch);
+        if (tid == 0) partial[(int64_t)i * tb.n_pieces + p0] = S;
+    } else {
+        for (int p = p0; p < p1; ++p) {
+            const int lo = (p == p0) ? (int)base : tb.piece_hi[p - 1];
+            const int hi = tb.piece_hi[p];
+            double acc = 0.0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = (int)base + 4 * (tid + kThreads * r);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j + c >= lo && j + c < hi) acc += (double)fabsf(x[r][c]);
+            }
+            const double S = block_sum(acc, scratch);
+            if (tid == 0) partial[(int64_t)i * tb.n_pieces + p] = S;
+        }
+        (void)piece;
+    }
 }
 
 // One wavefront per (block, worker).
@@ -61,10 +138,10 @@ __global__ __launch_bounds__(kWave) void bs_scale(const double *__restrict__ par
 {
     const int b = blockIdx.x;
     const int i = blockIdx.y;
-    const int s0 = tb.block_seg0[b], s1 = tb.block_seg0[b + 1];
-    const double *row = partial + (int64_t)i * tb.n_segs;
+    const int q0 = tb.block_piece0[b], q1 = tb.block_piece0[b + 1];
+    const double *row = partial + (int64_t)i * tb.n_pieces;
     double acc = 0.0;
-    for (int s = s0 + (int)threadIdx.x; s < s1; s += kWave) acc += row[s];
+    for (int q = q0 + (int)threadIdx.x; q < q1; q += kWave) acc += row[q];
     const double S = wave_sum(acc);
     if (threadIdx.x == 0) {
         const double len = (double)(tb.offsets[b + 1] - tb.offsets[b]);
@@ -72,79 +149,96 @@ __global__ __launch_bounds__(kWave) void bs_scale(const double *__restrict__ par
     }
 }
 
-__device__ __forceinline__ int block_of(const BsTable &tb, int j, int hint)
+__global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int n, BsTable tb,
+                                                      const float *__restrict__ scales,
+                                                      const uint64_t *__restrict__ signs,
+                                                      float *__restrict__ theta, float *__restrict__ m,
+                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
-    if (tb.uniform > 0) {
-        const int b = j / tb.uniform;
-        return b < tb.n_blocks ? b : tb.n_blocks - 1;
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t base = (int64_t)t * kTile;
+    const int n_tiles = (int)(ld / kTile);
+    const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
+    const bool single = (p1 - p0 == 1);
+
+    float4 th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        th[r] = ld4(theta + j);
+        mm[r] = ld4(m + j);
+        vv[r] = ld4(v + j);
+        vh[r] = ld4(vhat + j);
     }
-    int b = hint;
-    while (b + 1 < tb.n_blocks && j >= tb.offsets[b + 1]) ++b;
-    return b;
+    // block of every coordinate this thread owns
+    int blk[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int j = (int)base + 4 * (tid + kThreads * r);
+        int q = p0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (!single)
+                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
+            blk[r][c] = tb.piece_blk[q];
+        }
+    }
+    float acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
+
+    for (int i = 0; i < n; ++i) {
+        const uint64_t *srow = signs + ((int64_t)i * n_tiles + t) * kSignWordsPerTile;
+        const float *sc = scales + (int64_t)i * tb.n_blocks;
+        const float s_single = sc[blk[0][0]];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint64_t w = srow[(r * 4 + wave) * 4 + c];       // same address for the whole wavefront
+                const float s = single ? s_single : sc[blk[r][c]];
+                const float cj = ((w >> lane) & 1ull) ? -s : s;         // copysign(s, x) from the stored sign bit
+                acc[r][c] = fadd(acc[r][c], cj);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        // padding coordinates take no gradient
+        const float4 gbar = make_float4(j < d ? fdiv(acc[r][0], p.n_workers) : 0.f,
+                                        j + 1 < d ? fdiv(acc[r][1], p.n_workers) : 0.f,
+                                        j + 2 < d ? fdiv(acc[r][2], p.n_workers) : 0.f,
+                                        j + 3 < d ? fdiv(acc[r][3], p.n_workers) : 0.f);
+        amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
+        st4(theta + j, th[r]);
+        st4(m + j, mm[r]);
+        st4(v + j, vv[r]);
+        st4(vhat + j, vh[r]);
+    }
 }
 
-constexpr int kBsUnroll = 4;   // workers whose loads are in flight together in bs_apply
-
-__global__ __launch_bounds__(kThreads) void bs_apply(const float *__restrict__ g, float *__restrict__ e, int64_t d,
-                                                     int64_t ld, int n, BsTable tb,
-                                                     const float *__restrict__ scales, float *__restrict__ theta,
-                                                     float *__restrict__ m, float *__restrict__ v,
-                                                     float *__restrict__ vhat, AmsParams p)
+// e_i of one worker in its defined form, from the stored x and the pending scales.
+template <bool kPending>
+__global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *__restrict__ xrow, int64_t d,
+                                                                 BsTable tb, const float *__restrict__ sp,
+                                                                 float *__restrict__ out)
 {
-    const int64_t j = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;   // < ld by construction of the grid
-    const int jj = (int)j;
-    const int hint = tb.uniform > 0 ? 0 : tb.tile_block[blockIdx.x];
-    const int b0 = block_of(tb, jj, hint);
-    const int b1 = block_of(tb, jj + 1, b0);
-    const int b2 = block_of(tb, jj + 2, b1);
-    const int b3 = block_of(tb, jj + 3, b2);
-    const bool ok0 = j < d, ok1 = j + 1 < d, ok2 = j + 2 < d, ok3 = j + 3 < d;
-
-    // state loads go out first; they are not needed until the worker loop is over
-    float4 th = ld4(theta + j), mm = ld4(m + j), vv = ld4(v + j), vh = ld4(vhat + j);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-
-    for (int i0 = 0; i0 < n; i0 += kBsUnroll) {
-        float4 gv[kBsUnroll], ev[kBsUnroll], sc[kBsUnroll];
-#pragma unroll
-        for (int u = 0; u < kBsUnroll; ++u) {
-            const int i = i0 + u;
-            if (i < n) {
-                gv[u] = load_grad4(g + (int64_t)i * d, j, d);
-                ev[u] = ld4(e + (int64_t)i * ld + j);
-                const float *srow = scales + (int64_t)i * tb.n_blocks;
-                const float s0 = srow[b0];
-                sc[u] = make_float4(s0, b1 == b0 ? s0 : srow[b1], b2 == b0 ? s0 : srow[b2],
-                                    b3 == b0 ? s0 : srow[b3]);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kBsUnroll; ++u) {
-            const int i = i0 + u;
-            if (i < n) {
-                const float x0 = fadd(gv[u].x, ev[u].x), x1 = fadd(gv[u].y, ev[u].y);
-                const float x2 = fadd(gv[u].z, ev[u].z), x3 = fadd(gv[u].w, ev[u].w);
-                // C(x) = s * sign(x), sign taken from the IEEE sign bit; nothing at padding coordinates
-                const float c0 = ok0 ? copysignf(sc[u].x, x0) : 0.f;
-                const float c1 = ok1 ? copysignf(sc[u].y, x1) : 0.f;
-                const float c2 = ok2 ? copysignf(sc[u].z, x2) : 0.f;
-                const float c3 = ok3 ? copysignf(sc[u].w, x3) : 0.f;
-                st4(e + (int64_t)i * ld + j, make_float4(fsub(x0, c0), fsub(x1, c1), fsub(x2, c2),
-                                                         fsub(x3, c3)));
-                acc.x = fadd(acc.x, c0);
-                acc.y = fadd(acc.y, c1);
-                acc.z = fadd(acc.z, c2);
-                acc.w = fadd(acc.w, c3);
-            }
-        }
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j >= d) return;
+    float e = xrow[j];
+    if (kPending) {
+        const int t = (int)(j / kTile);
+        int q = tb.tile_piece0[t];
+        const int q1 = tb.tile_piece0[t + 1];
+        while (q + 1 < q1 && j >= tb.piece_hi[q]) ++q;
+        e = deferred_sign_error(e, sp[tb.piece_blk[q]]);
     }
-    const float4 gbar = make_float4(fdiv(acc.x, p.n_workers), fdiv(acc.y, p.n_workers),
-                                    fdiv(acc.z, p.n_workers), fdiv(acc.w, p.n_workers));
-    amsgrad_update4(th, mm, vv, vh, gbar, p);
-    st4(theta + j, th);
-    st4(m + j, mm);
-    st4(v + j, vv);
-    st4(vhat + j, vh);
+    out[j] = e;
 }
 
 }  // namespace cams

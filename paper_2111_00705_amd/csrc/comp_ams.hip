@@ -39,24 +39,29 @@ struct comp_ams {
 
     float *theta = nullptr, *m = nullptr, *v = nullptr, *vhat = nullptr, *e = nullptr;
 
-    // block sign
+    float *row_tmp = nullptr;                  // d floats: staging for getters that materialise e_i
+
+    // block sign: e holds x = g + e of the last step; `pending` says its scales still have to be
+    // subtracted (deferred error, see blocksign_kernels.h)
     BsTable tb{};
     std::vector<void *> tb_allocs;
     double *partial = nullptr;
     float *scales = nullptr;
+    uint64_t *signs = nullptr;
+    bool pending = false;
 
     // Top-k
     TkGeom ge{};
     TkWorker *ws = nullptr;
-    uint32_t *hist1 = nullptr, *hist2 = nullptr;
-    uint16_t *cand_idx = nullptr;
-    float *cand_val = nullptr;
-    uint32_t *cand_cnt = nullptr, *sel_cnt = nullptr;
-    uint32_t *sel_offs = nullptr, *sel_out_idx = nullptr;
+    uint32_t *hist1 = nullptr;
+    uint2 *cand = nullptr;                     // [n][wgs][4][list_cap] candidate (index, value bits)
+    uint2 *cand_dir = nullptr;                 // [n][n_tiles][4] (offset, count) of a tile's candidates in its list
+    uint32_t *list_len = nullptr;              // [n][wgs][4]
+    uint64_t *dense = nullptr;                 // [n][d] comp of the candidates in the threshold bin
+    uint32_t *dense_cnt = nullptr;             // [n]
+    uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
-    std::vector<std::pair<int, int>> levels;   // (s_hi, s_lo) of each digit after the first
-    int grid_rows = 1;                         // workgroups per worker in the row-streaming kernels
-    int grid_scan = 1;
+
 
     // optional per-kernel timing with HIP events on the step's stream
     bool prof_on = false;
@@ -65,10 +70,9 @@ struct comp_ams {
 
 namespace {
 
-enum ProfSlot { P_BS_PARTIAL, P_BS_SCALE, P_BS_APPLY, P_TK_PASS1, P_TK_FINDBIN, P_TK_COLLECT, P_TK_SCAN, P_TK_FIND,
-                P_TK_FINAL, P_SLOTS };
-const char *const kProfNames[P_SLOTS] = {"bs_partial", "bs_scale", "bs_apply", "tk_pass1", "tk_findbin",
-                                         "tk_collect", "tk_scan", "tk_find", "tk_final"};
+enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_COMPACT, P_TK_RESOLVE, P_TK_FINAL, P_SLOTS };
+const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_compact",
+                                         "tk_resolve", "tk_final"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -144,31 +148,36 @@ void free_all(std::vector<void *> &owner)
 }
 
 // Builds the device block table from host offsets[0..nb] (already validated).
-int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t uniform)
+int build_block_table(comp_ams *h, const std::vector<int64_t> &off)
 {
     const int nb = (int)off.size() - 1;
-    std::vector<int32_t> off32(nb + 1), seg_lo, seg_hi, block_seg0(nb + 1);
+    const int64_t n_tiles = h->ld / kTile;
+    std::vector<int32_t> off32(nb + 1), piece_hi, piece_blk, tile_piece0(n_tiles + 1), block_piece0(nb + 1);
     for (int b = 0; b <= nb; ++b) off32[b] = (int32_t)off[b];
-    for (int b = 0; b < nb; ++b) {
-        block_seg0[b] = (int32_t)seg_lo.size();
-        for (int64_t s = off[b]; s < off[b + 1]; s += kTile) {
-            seg_lo.push_back((int32_t)s);
-            seg_hi.push_back((int32_t)std::min<int64_t>(s + kTile, off[b + 1]));
-        }
-    }
-    block_seg0[nb] = (int32_t)seg_lo.size();
-    const int64_t n_apply_tiles = h->ld / 1024;
-    std::vector<int32_t> tile_block(n_apply_tiles);
+    // pieces = blocks cut at every multiple of kTile, in coordinate order
     {
         int b = 0;
-        for (int64_t t = 0; t < n_apply_tiles; ++t) {
-            const int64_t j = t * 1024;
-            while (b + 1 < nb && j >= off[b + 1]) ++b;
-            tile_block[t] = b;
+        int64_t pos = 0;
+        block_piece0[0] = 0;
+        for (int64_t t = 0; t < n_tiles; ++t) {
+            tile_piece0[t] = (int32_t)piece_hi.size();
+            const int64_t tile_end = std::min<int64_t>((t + 1) * kTile, h->d);
+            while (pos < tile_end) {
+                const int64_t hi = std::min(tile_end, off[b + 1]);
+                piece_hi.push_back((int32_t)hi);
+                piece_blk.push_back(b);
+                pos = hi;
+                if (pos == off[b + 1] && b + 1 < nb) {
+                    ++b;
+                    block_piece0[b] = (int32_t)piece_hi.size();
+                }
+            }
         }
+        tile_piece0[n_tiles] = (int32_t)piece_hi.size();
+        block_piece0[nb] = (int32_t)piece_hi.size();
     }
     std::vector<void *> fresh;
-    int32_t *d_off = nullptr, *d_lo = nullptr, *d_hi = nullptr, *d_s0 = nullptr, *d_tb = nullptr;
+    int32_t *d_off = nullptr, *d_hi = nullptr, *d_blk = nullptr, *d_tp = nullptr, *d_bp = nullptr;
     double *d_partial = nullptr;
     float *d_scales = nullptr;
     int rc;
@@ -178,9 +187,9 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
         HIP_TRY(h, hipMemcpy(*dst, src.data(), src.size() * sizeof(int32_t), hipMemcpyHostToDevice));
         return COMP_AMS_OK;
     };
-    if ((rc = upload(&d_off, off32)) || (rc = upload(&d_lo, seg_lo)) || (rc = upload(&d_hi, seg_hi)) ||
-        (rc = upload(&d_s0, block_seg0)) || (rc = upload(&d_tb, tile_block)) ||
-        (rc = dev_alloc_t(h, fresh, &d_partial, (size_t)h->n * seg_lo.size())) ||
+    if ((rc = upload(&d_off, off32)) || (rc = upload(&d_hi, piece_hi)) || (rc = upload(&d_blk, piece_blk)) ||
+        (rc = upload(&d_tp, tile_piece0)) || (rc = upload(&d_bp, block_piece0)) ||
+        (rc = dev_alloc_t(h, fresh, &d_partial, (size_t)h->n * piece_hi.size())) ||
         (rc = dev_alloc_t(h, fresh, &d_scales, (size_t)h->n * nb))) {
         free_all(fresh);
         return rc;
@@ -188,13 +197,12 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     free_all(h->tb_allocs);
     h->tb_allocs = std::move(fresh);
     h->tb.offsets = d_off;
-    h->tb.seg_lo = d_lo;
-    h->tb.seg_hi = d_hi;
-    h->tb.block_seg0 = d_s0;
-    h->tb.tile_block = d_tb;
+    h->tb.piece_hi = d_hi;
+    h->tb.piece_blk = d_blk;
+    h->tb.tile_piece0 = d_tp;
+    h->tb.block_piece0 = d_bp;
     h->tb.n_blocks = nb;
-    h->tb.n_segs = (int32_t)seg_lo.size();
-    h->tb.uniform = (int32_t)std::min<int64_t>(uniform, INT32_MAX);
+    h->tb.n_pieces = (int32_t)piece_hi.size();
     h->partial = d_partial;
     h->scales = d_scales;
     return COMP_AMS_OK;
@@ -228,44 +236,71 @@ int copy_in(comp_ams *h, float *dst_dev, const float *src, size_t count, int on_
 int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
-    launch_timed(h, P_BS_PARTIAL, st, [&] {
-        bs_partial<<<dim3(tb.n_segs, h->n), kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->partial);
+    const dim3 grid((unsigned)(h->ld / kTile), h->n);
+    launch_timed(h, P_BS_PASS, st, [&] {
+        if (h->pending)
+            bs_pass<true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+        else
+            bs_pass<false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     launch_timed(h, P_BS_SCALE, st, [&] {
         bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
     });
-    launch_timed(h, P_BS_APPLY, st, [&] {
-        bs_apply<<<dim3((unsigned)(h->ld / 1024)), kThreads, 0, st>>>(g, h->e, h->d, h->ld, h->n, tb, h->scales,
-                                                                      h->theta, h->m, h->v, h->vhat, h->params);
+    launch_timed(h, P_BS_UPDATE, st, [&] {
+        bs_update<<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->scales, h->signs, h->theta, h->m, h->v,
+                                              h->vhat, h->params);
     });
+    h->pending = true;
     return COMP_AMS_OK;
 }
 
 int step_topk(comp_ams *h, const float *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
-    const dim3 rows(h->grid_rows, h->n);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<<<rows, kThreads, 0, st>>>(g, h->e, ge, h->ws, h->hist1, h->cand_idx, h->cand_cnt);
+        tk_pass1<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->hist1, h->cand, h->cand_dir,
+                                                         h->list_len);
     });
-    launch_timed(h, P_TK_FINDBIN, st, [&] { tk_findbin<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist1); });
-    launch_timed(h, P_TK_COLLECT, st, [&] {
-        tk_collect<<<rows, kThreads, 0, st>>>(h->e, ge, h->ws, h->cand_idx, h->cand_cnt);
+    launch_timed(h, P_TK_COMPACT, st, [&] {
+        tk_compact<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->hist1, h->cand, h->cand_dir,
+                                                           h->list_len, h->dense, h->dense_cnt);
     });
-    for (const auto &lv : h->levels) {
-        launch_timed(h, P_TK_SCAN, st, [&] {
-            tk_scan<<<dim3(h->grid_scan, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->cand_idx, h->cand_cnt,
-                                                                  h->hist2, lv.first, lv.second);
-        });
-        launch_timed(h, P_TK_FIND, st, [&] {
-            tk_find<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist2, lv.first, lv.second);
-        });
-    }
+    launch_timed(h, P_TK_RESOLVE, st, [&] {
+        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->hist1, h->dense, h->dense_cnt);
+    });
     launch_timed(h, P_TK_FINAL, st, [&] {
-        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(h->e, ge, h->ws, h->cand_idx, h->cand_val, h->cand_cnt,
-                                                  h->sel_cnt, h->theta, h->m, h->v, h->vhat, h->params);
+        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cand_dir, h->theta, h->m, h->v, h->vhat,
+                                                  h->params);
     });
     return COMP_AMS_OK;
+}
+
+// Resets the per-worker selection records: no pending threshold, no guess.
+int reset_topk_workers(comp_ams *h)
+{
+    std::vector<TkWorker> init((size_t)h->n);
+    for (auto &w : init) {
+        std::memset(&w, 0, sizeof w);
+        w.guess = kNoGuess;
+        w.tc = kNoThreshold;
+    }
+    HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
+    return COMP_AMS_OK;
+}
+
+// Writes e_i in its defined form to dst (device memory, d floats) on the handle's stream.
+void launch_materialize(comp_ams *h, int worker, float *dst)
+{
+    const float *xrow = h->e + (size_t)worker * (size_t)h->ld;
+    const unsigned blocks = (unsigned)((h->d + kThreads - 1) / kThreads);
+    if (h->compressor == COMP_AMS_TOPK) {
+        tk_materialize_error<<<blocks, kThreads, 0, h->stream>>>(xrow, h->ge, h->ws + worker, dst);
+    } else if (h->pending) {
+        bs_materialize_error<true><<<blocks, kThreads, 0, h->stream>>>(
+            xrow, h->d, h->tb, h->scales + (size_t)worker * (size_t)h->tb.n_blocks, dst);
+    } else {
+        bs_materialize_error<false><<<blocks, kThreads, 0, h->stream>>>(xrow, h->d, h->tb, h->scales, dst);
+    }
 }
 
 }  // namespace
@@ -324,7 +359,8 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
     const size_t ld = (size_t)h->ld;
     if ((rc = dev_alloc_t(h, h->allocs, &h->theta, ld)) || (rc = dev_alloc_t(h, h->allocs, &h->m, ld)) ||
         (rc = dev_alloc_t(h, h->allocs, &h->v, ld)) || (rc = dev_alloc_t(h, h->allocs, &h->vhat, ld)) ||
-        (rc = dev_alloc_t(h, h->allocs, &h->e, ld * (size_t)n)))
+        (rc = dev_alloc_t(h, h->allocs, &h->e, ld * (size_t)n)) ||
+        (rc = dev_alloc_t(h, h->allocs, &h->row_tmp, (size_t)d)))
         return bail(rc);
 
     if (compressor == COMP_AMS_BLOCKSIGN) {
@@ -333,7 +369,8 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         std::vector<int64_t> off;
         for (int64_t s = 0; s < d; s += B) off.push_back(s);
         off.push_back(d);
-        if ((rc = build_block_table(h, off, B))) return bail(rc);
+        if ((rc = dev_alloc_t(h, h->allocs, &h->signs, ld / 64 * (size_t)n))) return bail(rc);
+        if ((rc = build_block_table(h, off))) return bail(rc);
     } else {
         h->k = k_or_block;
         TkGeom &ge = h->ge;
@@ -345,35 +382,30 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int ib = 1;
         while (((int64_t)1 << ib) < d) ++ib;
         ge.idx_bits = ib;
+        ge.n_levels = 0;
         for (int s_hi = kShift1 + ib; s_hi > 0;) {
             const int s_lo = std::max(s_hi - kDigitBits, 0);
-            h->levels.emplace_back(s_hi, s_lo);
+            ge.s_hi[ge.n_levels] = s_hi;
+            ge.s_lo[ge.n_levels] = s_lo;
+            ++ge.n_levels;
             s_hi = s_lo;
         }
-        h->grid_rows = (int)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
-        h->grid_scan = (int)std::min<int64_t>((ge.n_tiles + 3) / 4, std::max(1, 2048 / n));
+        ge.wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
+        ge.list_cap = (ge.n_tiles + ge.wgs - 1) / ge.wgs * kSub;
         const size_t segs = (size_t)n * ge.n_tiles;
+        const size_t lists = (size_t)n * ge.wgs * 4;
         if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->hist2, (size_t)n * kBins2)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand_idx, segs * kTile, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand_val, segs * kTile, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand_cnt, segs)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->sel_cnt, segs)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->sel_offs, (size_t)ge.n_tiles)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand, lists * ge.list_cap, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand_dir, segs * 4)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->list_len, lists)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense, (size_t)n * (size_t)d, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense_cnt, (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
             return bail(rc);
-        std::vector<TkWorker> init((size_t)n);
-        for (auto &w : init) {
-            std::memset(&w, 0, sizeof w);
-            w.guess = kNoGuess;
-        }
-        hipError_t e = hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice);
-        if (e != hipSuccess) {
-            fail(h, COMP_AMS_EDEVICE, "hipMemcpy failed: %s", hipGetErrorString(e));
-            return bail(COMP_AMS_EDEVICE);
-        }
+        if ((rc = reset_topk_workers(h))) return bail(rc);
     }
     {
         hipError_t e = hipDeviceSynchronize();
@@ -409,9 +441,15 @@ int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_bl
         return fail(h, COMP_AMS_EINVAL, "offsets must start at 0 and end at d");
     for (int b = 0; b < n_blocks; ++b)
         if (offsets_host[b + 1] <= offsets_host[b]) return fail(h, COMP_AMS_EINVAL, "offsets must be strictly increasing (block %d)", b);
+    if (h->pending) {
+        // the stored vectors still owe the subtraction of the old blocks' scales: do it in place
+        for (int i = 0; i < h->n; ++i) launch_materialize(h, i, h->e + (size_t)i * (size_t)h->ld);
+        HIP_TRY(h, hipGetLastError());
+        h->pending = false;
+    }
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     std::vector<int64_t> off(offsets_host, offsets_host + n_blocks + 1);
-    return build_block_table(h, off, 0);
+    return build_block_table(h, off);
 }
 
 int comp_ams_set_theta(comp_ams_t *h, const float *theta, int on_device)
@@ -483,7 +521,12 @@ int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
     int rc = check_handle(h);
     if (rc) return rc;
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
-    return copy_out(h, out, h->e + (size_t)worker * (size_t)h->ld, (size_t)h->d, on_device);
+    if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    launch_materialize(h, worker, on_device ? out : h->row_tmp);
+    HIP_TRY(h, hipGetLastError());
+    if (!on_device) return copy_out(h, out, h->row_tmp, (size_t)h->d, 0);
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return COMP_AMS_OK;
 }
 
 int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host)
@@ -494,24 +537,19 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     const TkGeom &ge = h->ge;
-    const size_t nt = (size_t)ge.n_tiles, k = (size_t)ge.k;
-    std::vector<uint32_t> cnt(nt), offs(nt);
-    HIP_TRY(h, hipMemcpyAsync(cnt.data(), h->sel_cnt + (size_t)worker * nt, nt * sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream));
-    HIP_TRY(h, hipStreamSynchronize(h->stream));
-    uint64_t total = 0;
-    for (size_t t = 0; t < nt; ++t) {
-        offs[t] = (uint32_t)total;
-        total += cnt[t];
-    }
-    if (total != k) return fail(h, COMP_AMS_EDEVICE, "internal: %llu coordinates recorded, expected k=%zu", (unsigned long long)total, k);
-    HIP_TRY(h, hipMemcpyAsync(h->sel_offs, offs.data(), nt * sizeof(uint32_t), hipMemcpyHostToDevice, h->stream));
-    tk_gather_selected<<<ge.n_tiles, kWave, 0, h->stream>>>(ge, worker, h->cand_idx, h->cand_val, h->sel_cnt,
-                                                           h->sel_offs, h->sel_out_idx, h->sel_out_val);
+    const size_t k = (size_t)ge.k;
+    HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
+    tk_gather_selected<<<ge.wgs, kThreads, 0, h->stream>>>(ge, worker, h->ws, h->cand, h->list_len, h->sel_count,
+                                                          h->sel_out_idx, h->sel_out_val);
+    HIP_TRY(h, hipGetLastError());
+    uint32_t total = 0;
     std::vector<uint32_t> idx(k);
     std::vector<float> val(k);
+    HIP_TRY(h, hipMemcpyAsync(&total, h->sel_count, sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipMemcpyAsync(idx.data(), h->sel_out_idx, k * sizeof(uint32_t), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipMemcpyAsync(val.data(), h->sel_out_val, k * sizeof(float), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (total != k) return fail(h, COMP_AMS_EDEVICE, "internal: %u coordinates kept, expected k=%zu", total, k);
     std::vector<uint32_t> order(k);
     for (size_t r = 0; r < k; ++r) order[r] = (uint32_t)r;
     std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return idx[a] < idx[b]; });
@@ -550,6 +588,9 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
                                     (size_t)h->n, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
                                     h->stream));
         HIP_TRY(h, hipStreamSynchronize(h->stream));
+        // the rows now hold e itself: nothing is pending on them
+        h->pending = false;
+        if (h->compressor == COMP_AMS_TOPK && (rc = reset_topk_workers(h))) return rc;
     }
     return COMP_AMS_OK;
 }

@@ -5,44 +5,53 @@
 //     comp = (magnitude_bits << IB) | (2^IB - 1 - index),     magnitude_bits = bits(x) & 0x7fffffff,
 // IB = number of bits of d-1.  comp is unique per element and its descending order is
 // "larger magnitude first, lower index first among equals", so Top-k is { comp >= Tc } where Tc is
-// the k-th largest comp.  Tc is found digit by digit from the top:
+// the k-th largest comp.  Tc is found digit by digit from the top (11 bits, then 12 at a time).
 //
-//   tk_pass1    streams g and e once: x = g+e is written over e, an LDS histogram of the top 11
-//               magnitude bits goes to a per-worker global histogram, and elements whose bin is at
-//               least the worker's guess (carried over from the previous step) are listed as
-//               candidates, per (worker, tile), as 16-bit positions inside the tile
-//   tk_findbin  per worker: the bin b* that holds the k-th largest and the rank left inside it;
-//               checks the guess (guess <= b* means the candidates cover every possible pick)
-//   tk_collect  only for workers whose guess failed (always on the first step): re-reads x and
-//               lists the elements with bin >= b*
-//   tk_scan / tk_find   one pair per further digit (<= 12 bits): histogram of that digit over the
-//               candidates that match the digits fixed so far, then pick the digit of the k-th
+// The error memory is kept in deferred form: after a step the library stores x_i = g_i + e_i and
+// the worker's threshold Tc_i; e_i[j] = (comp(x_i[j], j) >= Tc_i) ? +0 : x_i[j] is formed on the fly
+// when the next step (or a getter) reads x_i, so kept coordinates are never zeroed by scattered
+// writes and one step needs a single pass over g and the stored vector.  Four launches per step,
+// ordered only by kernel boundaries (no fences, no waiting inside a kernel):
+//
+//   tk_pass1    streams g and the stored x once and writes the new x; counts every element in a
+//               per-worker histogram of its top 11 magnitude bits; lists "candidates" - elements
+//               whose bin is >= the worker's guess, carried over from the previous step - as
+//               (index, value) pairs in one dense list per (worker, workgroup, wavefront), with a
+//               directory entry (offset, count) per (worker, tile, wavefront)
+//   tk_compact  every workgroup finds the bin b* of the k-th largest from the histogram; if the
+//               guess was above b* (always on the first step) the worker's candidates are listed
+//               again from the stored x with bin >= b*; candidates in bin b* are copied, as comp
+//               values, to one dense list per worker
+//   tk_resolve  one workgroup per worker: the remaining digits of Tc over the dense list
 //   tk_final    per tile, all workers: candidates with comp >= Tc are the kept coordinates; their
-//               values are summed into an LDS copy of the tile in ascending worker order, their
-//               error entries are zeroed, the kept (position, value) pairs are recorded, and the
-//               tile's theta, m, v, vhat are updated from gbar = acc / n
+//               values are added into an LDS copy of the tile in ascending worker order; then
+//               gbar = acc / n and the AMSGrad update of the tile's theta, m, v, vhat
 //
-// Apart from the candidates (a few per cent of the elements) g and e are read once and e is
-// written once.
+// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
+// (a few per cent of the elements, 8 B each, written once and read twice).
 #pragma once
 #include "device_utils.h"
 
 namespace cams {
 
-constexpr int kBins1 = 2048;      // pass-1 digit: top 11 of the 31 magnitude bits
+constexpr int kBins1 = 2048;      // first digit: top 11 of the 31 magnitude bits
 constexpr int kShift1 = 20;
 constexpr int kDigitBits = 12;    // later digits
 constexpr int kBins2 = 1 << kDigitBits;
-constexpr uint32_t kNoGuess = kBins1;   // guess that lists nothing (before the first step)
+constexpr int kMaxLevels = 5;     // ceil((20 + 31) / 12)
+constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles
+constexpr int kResolveThreads = 1024;
+constexpr uint32_t kNoGuess = kBins1;        // guess that lists nothing (before the first step)
+constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 
 struct TkWorker {
-    uint64_t prefix;        // digits of Tc fixed so far, right-aligned
-    uint64_t tc;            // threshold composite, valid once done != 0
-    uint32_t rank;          // 1-based rank (from the top) of Tc among elements matching prefix
-    uint32_t bstar;         // pass-1 bin of the k-th largest magnitude
+    uint64_t tc;            // threshold composite of the last finished step (pending selection)
     uint32_t guess;         // pass 1 lists elements with bin >= guess
-    uint32_t need_collect;  // the guess was above b*: candidates must be rebuilt
-    uint32_t done;          // Tc is final
+    // first digit of the running step, written by tk_compact, read by tk_resolve
+    uint32_t bstar;         // bin of the k-th largest magnitude
+    uint32_t rank;          // 1-based rank (from the top) of the k-th largest inside bin b*
+    uint32_t whole_bin;     // the whole bin b* is kept: Tc needs no further digit
+    uint32_t relisted;      // the guess was above b*: candidates were listed again
     uint32_t pad;
 };
 
@@ -51,6 +60,10 @@ struct TkGeom {
     int32_t n, n_tiles;
     int32_t idx_bits;       // IB
     uint32_t k;
+    int32_t wgs;            // workgroups per worker in tk_pass1 / tk_compact; tile t belongs to t % wgs
+    int32_t list_cap;       // capacity of one candidate list = ceil(n_tiles / wgs) * kSub
+    int32_t n_levels;       // digits after the first
+    int32_t s_hi[kMaxLevels], s_lo[kMaxLevels];   // bit range [s_lo, s_hi) of comp for each of them
 };
 
 __device__ __forceinline__ uint64_t composite(float x, uint32_t j, int idx_bits)
@@ -59,232 +72,288 @@ __device__ __forceinline__ uint64_t composite(float x, uint32_t j, int idx_bits)
     return ((uint64_t)mag_key(x) << idx_bits) | inv;
 }
 
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ e, TkGeom ge,
-                                                     const TkWorker *__restrict__ ws,
-                                                     uint32_t *__restrict__ hist1,
-                                                     uint16_t *__restrict__ cand_idx,
-                                                     uint32_t *__restrict__ cand_cnt)
+// Finds, in a histogram held in LDS (`bins` counters, a multiple of the workgroup size), the bin
+// of the element of 1-based rank `rank` counted from the top bin downwards, and leaves
+// {bin, elements in higher bins, the bin's count} in res[0..2] for every thread (res[3] = 1 if
+// found, which needs 1 <= rank <= total).  `part` holds one LDS counter per wavefront.
+__device__ __forceinline__ void find_rank_bin(const uint32_t *lh, uint32_t *part, uint32_t *res, int bins,
+                                              uint32_t rank)
 {
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t lcnt;
-    const int i = blockIdx.y;
-    const uint32_t guess = ws[i].guess;
-    const float *grow = g + (int64_t)i * ge.d;
-    float *erow = e + (int64_t)i * ge.ld;
-    for (int b = threadIdx.x; b < kBins1; b += kThreads) lh[b] = 0;
-
-    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
-        if (threadIdx.x == 0) lcnt = 0;
-        __syncthreads();   // also orders the histogram reset before the first tile
-        const int64_t base = (int64_t)t * kTile;
-        uint16_t *seg = cand_idx + (((int64_t)i * ge.n_tiles + t) << 12);
-        float4 gv[4], ev[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t j = base + 4 * (threadIdx.x + kThreads * r);
-            gv[r] = load_grad4(grow, j, ge.d);
-            ev[r] = ld4(erow + j);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int l = 4 * (threadIdx.x + kThreads * r);
-            const int64_t j = base + l;
-            float x[4] = {fadd(gv[r].x, ev[r].x), fadd(gv[r].y, ev[r].y), fadd(gv[r].z, ev[r].z),
-                          fadd(gv[r].w, ev[r].w)};
-            st4(erow + j, make_float4(x[0], x[1], x[2], x[3]));
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (j + c < ge.d) {
-                    const uint32_t bin = mag_key(x[c]) >> kShift1;
-                    atomicAdd(&lh[bin], 1u);
-                    if (bin >= guess) {
-                        const uint32_t slot = atomicAdd(&lcnt, 1u);   // < kTile: one slot per element
-                        seg[slot] = (uint16_t)(l + c);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) cand_cnt[(int64_t)i * ge.n_tiles + t] = lcnt;
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < kBins1; b += kThreads) {
-        const uint32_t c = lh[b];
-        if (c) atomicAdd(&hist1[(int64_t)i * kBins1 + b], c);
-    }
-}
-
-// Finds, in a histogram row of `bins` counters held in LDS, the bin of the element of 1-based rank
-// `rank` counted from the top bin downwards.  Exactly one thread gets true and receives the bin,
-// the number of elements in higher bins and the bin's own count.  Requires 1 <= rank <= total.
-// `part` holds kThreads counters of LDS; bins is a multiple of kThreads.
-__device__ __forceinline__ bool find_rank_bin(const uint32_t *lh, uint32_t *part, int bins, uint32_t rank,
-                                              uint32_t &bin_out, uint32_t &above_out, uint32_t &count_out)
-{
-    const int per = bins / kThreads;
+    const int nt = blockDim.x;
+    const int per = bins / nt;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t mine = 0;
     for (int q = 0; q < per; ++q) mine += lh[threadIdx.x * per + q];
-    part[threadIdx.x] = mine;
+    uint32_t suffix = mine;                       // sum over lanes >= this one
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t t = __shfl_down(suffix, off, kWave);
+        if (lane + off < kWave) suffix += t;
+    }
+    if (lane == 0) part[wave] = suffix;
+    if (threadIdx.x == 0) res[3] = 0;
     __syncthreads();
-    uint32_t above = 0;
-    for (int c = threadIdx.x + 1; c < kThreads; ++c) above += part[c];
-    bool found = false;
+    uint32_t above = suffix - mine;
+    for (int w = wave + 1; w < (nt >> 6); ++w) above += part[w];
     if (above < rank && above + mine >= rank) {
         for (int q = per - 1; q >= 0; --q) {
             const uint32_t c = lh[threadIdx.x * per + q];
             if (above + c >= rank) {
-                bin_out = threadIdx.x * per + q;
-                above_out = above;
-                count_out = c;
-                found = true;
+                res[0] = threadIdx.x * per + q;
+                res[1] = above;
+                res[2] = c;
+                res[3] = 1;
                 break;
             }
             above += c;
         }
     }
-    return found;
+    __syncthreads();
 }
 
-__global__ __launch_bounds__(kThreads) void tk_findbin(TkGeom ge, TkWorker *__restrict__ ws,
-                                                       uint32_t *__restrict__ hist1)
+// Appends this wavefront's flagged lanes to a list: returns the slot of the calling lane (valid
+// where flag is set) and advances count (uniform over the wavefront).
+__device__ __forceinline__ uint32_t wave_append(bool flag, uint32_t &count)
+{
+    const uint64_t mask = __ballot(flag);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t slot = count + __popcll(mask & ((1ull << lane) - 1ull));
+    count += __popcll(mask);
+    return slot;
+}
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
+                                                     const TkWorker *__restrict__ ws,
+                                                     uint32_t *__restrict__ hist1, uint2 *__restrict__ cand,
+                                                     uint2 *__restrict__ cand_dir,
+                                                     uint32_t *__restrict__ list_len)
 {
     __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t part[kThreads];
-    const int i = blockIdx.x;
-    uint32_t *row = hist1 + (int64_t)i * kBins1;
-    for (int b = threadIdx.x; b < kBins1; b += kThreads) {
-        lh[b] = row[b];
-        row[b] = 0;   // consumed: ready for the next step
-    }
-    __syncthreads();
-    uint32_t bin, above, count;
-    if (find_rank_bin(lh, part, kBins1, ge.k, bin, above, count)) {
-        TkWorker w = ws[i];
-        w.bstar = bin;
-        w.prefix = bin;
-        w.rank = ge.k - above;
-        w.need_collect = (w.guess > bin) ? 1u : 0u;
-        w.done = (count == w.rank) ? 1u : 0u;                    // the whole bin is kept
-        w.tc = (uint64_t)bin << (kShift1 + ge.idx_bits);
-        w.guess = bin >= 2 ? bin - 2 : 0;                        // next step: a quarter octave of slack
-        ws[i] = w;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void tk_collect(const float *__restrict__ e, TkGeom ge,
-                                                       const TkWorker *__restrict__ ws,
-                                                       uint16_t *__restrict__ cand_idx,
-                                                       uint32_t *__restrict__ cand_cnt)
-{
-    __shared__ uint32_t lcnt;
     const int i = blockIdx.y;
-    if (!ws[i].need_collect) return;   // uniform over the workgroup
-    const uint32_t bstar = ws[i].bstar;
-    const float *erow = e + (int64_t)i * ge.ld;
-    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
-        if (threadIdx.x == 0) lcnt = 0;
-        __syncthreads();
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const uint32_t guess = ws[i].guess;
+    const uint64_t tc_prev = ws[i].tc;
+    const float *grow = g + (int64_t)i * ge.d;
+    float *xrow = xs + (int64_t)i * ge.ld;
+    const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
+    uint2 *list = cand + list_id * ge.list_cap;
+    for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
+    __syncthreads();
+
+    uint32_t count = 0;   // length of this wavefront's list so far
+    for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
         const int64_t base = (int64_t)t * kTile;
-        uint16_t *seg = cand_idx + (((int64_t)i * ge.n_tiles + t) << 12);
-        float4 xv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) xv[r] = ld4(erow + base + 4 * (threadIdx.x + kThreads * r));
+        const uint32_t first = count;
+        float4 gv[4], xv[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int l = 4 * (threadIdx.x + kThreads * r);
-            const float x[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+            const int64_t j = base + 4 * (tid + kThreads * r);
+            gv[r] = load_grad4(grow, j, ge.d);
+            xv[r] = ld4(xrow + j);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t j = (uint32_t)base + 4 * (tid + kThreads * r);
+            const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+            const float xo[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+            float x[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if (base + l + c < ge.d && (mag_key(x[c]) >> kShift1) >= bstar) {
-                    const uint32_t slot = atomicAdd(&lcnt, 1u);
-                    seg[slot] = (uint16_t)(l + c);
-                }
+                // e = x_old - C(x_old): +0 where the previous step kept the coordinate
+                const float e = (composite(xo[c], j + c, ge.idx_bits) >= tc_prev) ? 0.f : xo[c];
+                x[c] = (j + c < ge.d) ? fadd(gg[c], e) : 0.f;
+            }
+            st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool valid = j + c < ge.d;
+                const uint32_t bin = mag_key(x[c]) >> kShift1;
+                if (valid) atomicAdd(&lh[bin], 1u);
+                const bool hit = valid && bin >= guess;
+                const uint32_t slot = wave_append(hit, count);   // < list_cap: kSub coordinates per tile
+                if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
             }
         }
-        __syncthreads();
-        if (threadIdx.x == 0) cand_cnt[(int64_t)i * ge.n_tiles + t] = lcnt;
+        if ((tid & 63) == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, count - first);
+    }
+    if ((tid & 63) == 0) list_len[list_id] = count;
+    __syncthreads();
+    uint32_t *row = hist1 + (int64_t)i * kBins1;
+    for (int b = tid; b < kBins1; b += kThreads) {
+        const uint32_t c = lh[b];
+        if (c) atomicAdd(row + b, c);
     }
 }
 
-// One digit of Tc: histogram of bits [s_lo, s_hi) of comp over the candidates whose bits above
-// s_hi equal the prefix.  One wavefront per tile.
-__global__ __launch_bounds__(kThreads) void tk_scan(const float *__restrict__ e, TkGeom ge,
-                                                    const TkWorker *__restrict__ ws,
-                                                    const uint16_t *__restrict__ cand_idx,
-                                                    const uint32_t *__restrict__ cand_cnt,
-                                                    uint32_t *__restrict__ hist2, int s_hi, int s_lo)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void tk_compact(const float *__restrict__ xs, TkGeom ge,
+                                                       TkWorker *__restrict__ ws,
+                                                       const uint32_t *__restrict__ hist1,
+                                                       uint2 *__restrict__ cand, uint2 *__restrict__ cand_dir,
+                                                       uint32_t *__restrict__ list_len,
+                                                       uint64_t *__restrict__ dense, uint32_t *__restrict__ dense_cnt)
+{
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t part[kThreads / kWave];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t wave_base[4];
+    const int i = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+
+    // first digit: identical in every workgroup of the worker
+    const uint32_t *row = hist1 + (int64_t)i * kBins1;
+    for (int b = tid; b < kBins1; b += kThreads) lh[b] = row[b];
+    __syncthreads();
+    find_rank_bin(lh, part, res, kBins1, ge.k);
+    if (!res[3]) return;                            // cannot happen: the histogram holds d >= k elements
+    const uint32_t bstar = res[0];
+    const uint32_t rank = ge.k - res[1];
+    const bool whole_bin = (res[2] == rank);
+    const bool relist = ws[i].guess > bstar;
+    if (blockIdx.x == 0 && tid == 0) {
+        ws[i].bstar = bstar;
+        ws[i].rank = rank;
+        ws[i].whole_bin = whole_bin ? 1u : 0u;
+        ws[i].relisted = relist ? 1u : 0u;
+    }
+    if (whole_bin && !relist) return;
+
+    const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
+    uint2 *list = cand + list_id * ge.list_cap;
+    uint32_t len;
+    if (relist) {
+        // the guess was too high: list this workgroup's candidates again, now with bin >= b*
+        const float *xrow = xs + (int64_t)i * ge.ld;
+        uint32_t count = 0;
+        for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
+            const int64_t base = (int64_t)t * kTile;
+            const uint32_t first = count;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t j = (uint32_t)base + 4 * (tid + kThreads * r);
+                const float4 xv = ld4(xrow + j);
+                const float x[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool hit = j + c < ge.d && (mag_key(x[c]) >> kShift1) >= bstar;
+                    const uint32_t slot = wave_append(hit, count);
+                    if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
+                }
+            }
+            if (lane == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, count - first);
+        }
+        if (lane == 0) list_len[list_id] = count;
+        len = count;
+        __syncthreads();   // the list written above is read below by other lanes
+    } else {
+        len = list_len[list_id];
+    }
+    if (whole_bin) return;
+
+    // dense list of the candidates in bin b*: count, reserve once per workgroup, then copy
+    uint32_t mine = 0;
+    for (uint32_t q = lane; q < len; q += kWave) mine += ((list[q].y & 0x7fffffffu) >> kShift1) == bstar ? 1u : 0u;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off, kWave);
+    if (lane == 0) wave_tot[wave] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        uint32_t at = total ? atomicAdd(dense_cnt + i, total) : 0u;
+        for (int w = 0; w < 4; ++w) {
+            wave_base[w] = at;
+            at += wave_tot[w];
+        }
+    }
+    __syncthreads();
+    uint32_t count = wave_base[wave];
+    uint64_t *out = dense + (int64_t)i * ge.d;
+    for (uint32_t q0 = 0; q0 < len; q0 += kWave) {
+        const uint32_t q = q0 + lane;
+        bool hit = false;
+        uint64_t comp = 0;
+        if (q < len) {
+            const uint2 c = list[q];
+            hit = ((c.y & 0x7fffffffu) >> kShift1) == bstar;
+            comp = composite(__uint_as_float(c.y), c.x, ge.idx_bits);
+        }
+        const uint32_t slot = wave_append(hit, count);
+        if (hit) out[slot] = comp;      // slot < d: every element appears at most once
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One workgroup of 1024 threads per worker: the digits of Tc after the first, over the dense list.
+// Also hands the next step its guess and clears the histogram row and the list counter.
+__global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
+                                                              uint32_t *__restrict__ hist1,
+                                                              const uint64_t *__restrict__ dense,
+                                                              uint32_t *__restrict__ dense_cnt)
 {
     __shared__ uint32_t lh[kBins2];
-    const int i = blockIdx.y;
-    if (ws[i].done) return;
-    const uint64_t prefix = ws[i].prefix;
-    const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
-    const float *erow = e + (int64_t)i * ge.ld;
-    for (int b = threadIdx.x; b < kBins2; b += kThreads) lh[b] = 0;
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int t = blockIdx.x * 4 + wave; t < ge.n_tiles; t += gridDim.x * 4) {
-        const uint32_t cnt = cand_cnt[(int64_t)i * ge.n_tiles + t];
-        const uint16_t *seg = cand_idx + (((int64_t)i * ge.n_tiles + t) << 12);
-        for (uint32_t q = lane; q < cnt; q += kWave) {
-            const uint32_t j = (uint32_t)t * kTile + seg[q];
-            const uint64_t comp = composite(erow[j], j, ge.idx_bits);
+    __shared__ uint32_t part[kResolveThreads / kWave];
+    __shared__ uint32_t res[4];
+    const int i = blockIdx.x;
+    const int tid = threadIdx.x;
+    const TkWorker w = ws[i];
+    uint64_t prefix = w.bstar;
+    uint32_t rank = w.rank;
+    bool done = w.whole_bin != 0;
+    uint64_t tc = (uint64_t)w.bstar << (kShift1 + ge.idx_bits);
+    const uint32_t cnt = dense_cnt[i];
+    const uint64_t *list = dense + (int64_t)i * ge.d;
+
+    for (int lv = 0; lv < ge.n_levels && !done; ++lv) {
+        const int s_hi = ge.s_hi[lv], s_lo = ge.s_lo[lv];
+        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
+        for (int b = tid; b < kBins2; b += kResolveThreads) lh[b] = 0;
+        __syncthreads();
+        for (uint32_t q = tid; q < cnt; q += kResolveThreads) {
+            const uint64_t comp = list[q];
             if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
         }
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < kBins2; b += kThreads) {
-        const uint32_t c = lh[b];
-        if (c) atomicAdd(&hist2[(int64_t)i * kBins2 + b], c);
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void tk_find(TkGeom ge, TkWorker *__restrict__ ws,
-                                                    uint32_t *__restrict__ hist2, int s_hi, int s_lo)
-{
-    __shared__ uint32_t lh[kBins2];
-    __shared__ uint32_t part[kThreads];
-    const int i = blockIdx.x;
-    if (ws[i].done) return;
-    uint32_t *row = hist2 + (int64_t)i * kBins2;
-    for (int b = threadIdx.x; b < kBins2; b += kThreads) {
-        lh[b] = row[b];
-        row[b] = 0;
-    }
-    __syncthreads();
-    const uint32_t rank = ws[i].rank;
-    uint32_t bin, above, count;
-    if (find_rank_bin(lh, part, kBins2, rank, bin, above, count)) {
-        TkWorker w = ws[i];
-        w.prefix = (w.prefix << (s_hi - s_lo)) | bin;
-        w.rank = rank - above;
-        if (s_lo == 0 || count == w.rank) {   // last digit, or everything under this prefix is kept
-            w.done = 1;
-            w.tc = w.prefix << s_lo;
+        __syncthreads();
+        find_rank_bin(lh, part, res, kBins2, rank);
+        if (!res[3]) break;                                    // cannot happen: rank <= matching elements
+        prefix = (prefix << (s_hi - s_lo)) | res[0];
+        rank -= res[1];
+        if (s_lo == 0 || res[2] == rank) {                     // last digit, or all under this prefix are kept
+            done = true;
+            tc = prefix << s_lo;
         }
-        ws[i] = w;
+        __syncthreads();
     }
+    if (tid == 0) {
+        ws[i].tc = tc;
+        // next step lists from one bin (an eighth of an octave) below b*; two after a miss
+        const uint32_t slack = w.relisted ? 2u : 1u;
+        ws[i].guess = w.bstar >= slack ? w.bstar - slack : 0u;
+        dense_cnt[i] = 0;
+    }
+    uint32_t *row = hist1 + (int64_t)i * kBins1;
+    for (int b = tid; b < kBins1; b += kResolveThreads) row[b] = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
 constexpr int kFinChunk = 2048;   // candidates staged in LDS at a time
 constexpr int kFinGroup = 32;     // workers whose candidate lists are flattened together
 
-__global__ __launch_bounds__(kThreads) void tk_final(float *__restrict__ e, TkGeom ge,
-                                                     const TkWorker *__restrict__ ws,
-                                                     uint16_t *__restrict__ cand_idx, float *__restrict__ cand_val,
-                                                     const uint32_t *__restrict__ cand_cnt,
-                                                     uint32_t *__restrict__ sel_cnt, float *__restrict__ theta,
-                                                     float *__restrict__ m, float *__restrict__ v,
-                                                     float *__restrict__ vhat, AmsParams p)
+__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                     const uint2 *__restrict__ cand,
+                                                     const uint2 *__restrict__ cand_dir,
+                                                     float *__restrict__ theta, float *__restrict__ m,
+                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
     __shared__ float acc[kTile];
     __shared__ float lst_v[kFinChunk];
     __shared__ uint16_t lst_l[kFinChunk];
     __shared__ uint16_t lst_w[kFinChunk];   // worker within the group, bit 15 = kept
-    __shared__ uint32_t pre[kFinGroup + 1];
-    __shared__ uint32_t selc[kFinGroup];
+    __shared__ uint32_t pre[kFinGroup * 4 + 1];
+    __shared__ uint32_t first[kFinGroup * 4];   // offset of each sub-list inside its wavefront's list
     __shared__ uint64_t tcs[kFinGroup];
 
     const int t = blockIdx.x;
@@ -305,70 +374,65 @@ __global__ __launch_bounds__(kThreads) void tk_final(float *__restrict__ e, TkGe
 
     for (int w0 = 0; w0 < ge.n; w0 += kFinGroup) {
         const int nw = min(kFinGroup, ge.n - w0);
+        const int ns = nw * 4;                      // (worker, wavefront) sub-lists in this group
         __syncthreads();
-        if (tid < nw) {
-            pre[tid + 1] = cand_cnt[(int64_t)(w0 + tid) * ge.n_tiles + t];
-            selc[tid] = 0;
-            tcs[tid] = ws[w0 + tid].tc;
+        if (tid < ns) {
+            const uint2 dir = cand_dir[((int64_t)(w0 + (tid >> 2)) * ge.n_tiles + t) * 4 + (tid & 3)];
+            first[tid] = dir.x;
+            pre[tid + 1] = dir.y;
+        }
+        if (tid < nw) tcs[tid] = ws[w0 + tid].tc;
+        __syncthreads();
+        if (tid < kWave) {
+            // inclusive prefix sum of the (at most 128) sub-list lengths, two per lane
+            const uint32_t a = (2 * tid < ns) ? pre[2 * tid + 1] : 0u;
+            const uint32_t b = (2 * tid + 1 < ns) ? pre[2 * tid + 2] : 0u;
+            uint32_t incl = a + b;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, kWave);
+                if (tid >= off) incl += up;
+            }
+            const uint32_t excl = incl - (a + b);
+            if (2 * tid < ns) pre[2 * tid + 1] = excl + a;
+            if (2 * tid + 1 < ns) pre[2 * tid + 2] = excl + a + b;
+            if (tid == 0) pre[0] = 0;
         }
         __syncthreads();
-        if (tid == 0) {
-            pre[0] = 0;
-            for (int w = 0; w < nw; ++w) pre[w + 1] += pre[w];
-        }
-        __syncthreads();
-        const uint32_t total = pre[nw];
+        const uint32_t total = pre[ns];
 
         for (uint32_t c0 = 0; c0 < total; c0 += kFinChunk) {
             const uint32_t cn = min((uint32_t)kFinChunk, total - c0);
             // 1. read the candidates of this chunk, decide which are kept
             for (uint32_t q = tid; q < cn; q += kThreads) {
                 const uint32_t gq = c0 + q;
-                int lo = 0, hi = nw;                       // largest w with pre[w] <= gq
+                int lo = 0, hi = ns;                       // largest s with pre[s] <= gq
                 while (hi - lo > 1) {
                     const int mid = (lo + hi) >> 1;
                     if (pre[mid] <= gq) lo = mid; else hi = mid;
                 }
-                const int w = lo;
-                const int i = w0 + w;
-                const int64_t seg = ((int64_t)i * ge.n_tiles + t) << 12;
-                const uint32_t l = cand_idx[seg + (gq - pre[w])];
-                const uint32_t j = (uint32_t)base + l;
-                const float x = e[(int64_t)i * ge.ld + j];
-                const bool keep = composite(x, j, ge.idx_bits) >= tcs[w];
+                const int w = lo >> 2;
+                const int64_t list_id = ((int64_t)(w0 + w) * ge.wgs + (t % ge.wgs)) * 4 + (lo & 3);
+                const uint2 c = cand[list_id * ge.list_cap + first[lo] + (gq - pre[lo])];
+                const uint32_t l = c.x - (uint32_t)base;
+                const float x = __uint_as_float(c.y);
+                const bool keep = composite(x, c.x, ge.idx_bits) >= tcs[w];
                 lst_l[q] = (uint16_t)l;
                 lst_v[q] = x;
                 lst_w[q] = (uint16_t)(w | (keep ? 0x8000 : 0));
             }
             __syncthreads();
             // 2. add kept values into the tile, one worker at a time, ascending
-            int wa = 0, wb = nw - 1;
-            while (pre[wa + 1] <= c0) ++wa;
-            while (pre[wb] >= c0 + cn) --wb;
-            for (int w = wa; w <= wb; ++w) {
+            int sa = 0, sb = ns - 1;
+            while (pre[sa + 1] <= c0) ++sa;
+            while (pre[sb] >= c0 + cn) --sb;
+            for (int w = sa >> 2; w <= (sb >> 2); ++w) {
                 const uint16_t tag = (uint16_t)(w | 0x8000);
                 for (uint32_t q = tid; q < cn; q += kThreads)
                     if (lst_w[q] == tag) acc[lst_l[q]] = fadd(acc[lst_l[q]], lst_v[q]);
                 __syncthreads();
             }
-            // 3. e = x - C(x) = +0 at kept coordinates; record (position, value) of the kept ones
-            //    over the front of the candidate segment (slots already consumed)
-            for (uint32_t q = tid; q < cn; q += kThreads) {
-                const uint16_t wt = lst_w[q];
-                if (wt & 0x8000) {
-                    const int w = wt & 0x7fff;
-                    const int i = w0 + w;
-                    const uint32_t l = lst_l[q];
-                    e[(int64_t)i * ge.ld + base + l] = 0.f;
-                    const uint32_t slot = atomicAdd(&selc[w], 1u);
-                    const int64_t seg = ((int64_t)i * ge.n_tiles + t) << 12;
-                    cand_idx[seg + slot] = (uint16_t)l;
-                    cand_val[seg + slot] = lst_v[q];
-                }
-            }
-            __syncthreads();
         }
-        if (tid < nw) sel_cnt[(int64_t)(w0 + tid) * ge.n_tiles + t] = selc[tid];
     }
     __syncthreads();
 
@@ -386,24 +450,41 @@ __global__ __launch_bounds__(kThreads) void tk_final(float *__restrict__ e, TkGe
     }
 }
 
-// Copies the kept (index, value) pairs of one worker out of the per-tile records into dense
-// arrays; `offs` is the exclusive prefix sum of the worker's per-tile counts.  One wavefront per tile.
-__global__ __launch_bounds__(kWave) void tk_gather_selected(TkGeom ge, int worker,
-                                                            const uint16_t *__restrict__ cand_idx,
-                                                            const float *__restrict__ cand_val,
-                                                            const uint32_t *__restrict__ sel_cnt,
-                                                            const uint32_t *__restrict__ offs,
-                                                            uint32_t *__restrict__ out_idx,
-                                                            float *__restrict__ out_val)
+// Getter support -------------------------------------------------------------------------------
+
+// e_i of one worker in its defined form, from the stored x and the pending threshold.
+__global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__restrict__ xrow, TkGeom ge,
+                                                                 const TkWorker *__restrict__ w,
+                                                                 float *__restrict__ out)
 {
-    const int t = blockIdx.x;
-    const uint32_t cnt = sel_cnt[(int64_t)worker * ge.n_tiles + t];
-    const int64_t seg = ((int64_t)worker * ge.n_tiles + t) << 12;
-    const uint32_t o = offs[t];
-    for (uint32_t q = threadIdx.x; q < cnt; q += kWave) {
-        if (o + q < ge.k) {
-            out_idx[o + q] = (uint32_t)t * kTile + cand_idx[seg + q];
-            out_val[o + q] = cand_val[seg + q];
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j >= ge.d) return;
+    const float x = xrow[j];
+    out[j] = (composite(x, (uint32_t)j, ge.idx_bits) >= w->tc) ? 0.f : x;
+}
+
+// The kept (index, value) pairs of one worker, in no particular order: candidates with
+// comp >= Tc.  *count must be 0 on entry and ends at k.  One wavefront per candidate list.
+__global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int worker,
+                                                               const TkWorker *__restrict__ ws,
+                                                               const uint2 *__restrict__ cand,
+                                                               const uint32_t *__restrict__ list_len,
+                                                               uint32_t *__restrict__ count,
+                                                               uint32_t *__restrict__ out_idx,
+                                                               float *__restrict__ out_val)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t tc = ws[worker].tc;
+    const int64_t list_id = ((int64_t)worker * ge.wgs + blockIdx.x) * 4 + wave;
+    const uint32_t len = list_len[list_id];
+    for (uint32_t q = lane; q < len; q += kWave) {
+        const uint2 c = cand[list_id * ge.list_cap + q];
+        if (composite(__uint_as_float(c.y), c.x, ge.idx_bits) >= tc) {
+            const uint32_t slot = atomicAdd(count, 1u);
+            if (slot < ge.k) {
+                out_idx[slot] = c.x;
+                out_val[slot] = __uint_as_float(c.y);
+            }
         }
     }
 }
