@@ -8,11 +8,13 @@
 // one of the definition, but one step needs a single pass over g and the stored vector:
 //
 //   bs_pass     per (tile of 4096 coordinates, worker): e = stored x minus its sign compression
-//               (previous scales), x = g + e, store x, write the sign bits of x as a bitmap
-//               (1 bit per coordinate), fp64 partial sums of |x| per piece (tile x block)
+//               (previous scales), x = g + e, store x, write the sign bits of x (1 bit per
+//               coordinate), fp64 partial sums of |x| per piece (tile x block)
 //   bs_scale    per (block, worker): fixed-order fp64 sum of the pieces, s = fl32(S / block length)
-//   bs_update   per tile: gbar[j] = (sum_i +-s_i[block(j)]) / n, signs from the bitmaps, workers in
-//               ascending order; then the AMSGrad update of theta, m, v, vhat
+//               (skipped when every tile lies in one block of at most 8 pieces: bs_update then
+//               adds the pieces itself)
+//   bs_update   per tile: gbar[j] = (sum_i +-s_i[block(j)]) / n, signs from the stored bits, workers
+//               in ascending order; then the AMSGrad update of theta, m, v, vhat
 //
 // Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written + 2 x 1/8 B of sign
 // bits, for any block size; plus 32 B per coordinate of optimiser state.
@@ -34,10 +36,11 @@ struct BsTable {
     int32_t n_pieces;
 };
 
-// Sign bitmap layout: per worker, per tile, 64 words of 64 bits.  Word (r*4 + wave)*4 + c holds,
-// at bit `lane`, the sign of the coordinate  tile*4096 + 4*(256*r + 64*wave + lane) + c,
-// i.e. the c-th component of the r-th float4 that thread (wave, lane) handles in the tile.
-constexpr int kSignWordsPerTile = kTile / 64;
+// Sign bits: per worker, per tile, one 16-bit word per thread of the workgroup.  Bit r*4 + c of
+// word `tid` is the sign of the coordinate  tile*4096 + 4*(tid + 256*r) + c,  i.e. of the c-th
+// component of the r-th float4 that thread tid handles in the tile (same mapping in bs_pass and
+// bs_update).
+constexpr int kMaxFusedPieces = 8;   // bs_update adds up to this many pieces of a block itself
 
 __device__ __forceinline__ float deferred_sign_error(float xs, float s_prev)
 {
@@ -48,20 +51,18 @@ template <bool kPending>
 __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g, float *__restrict__ xs,
                                                     int64_t d, int64_t ld, BsTable tb,
                                                     const float *__restrict__ s_prev,
-                                                    uint64_t *__restrict__ signs,
+                                                    uint16_t *__restrict__ signs,
                                                     double *__restrict__ partial)
 {
     __shared__ double scratch[4];
     const int t = blockIdx.x;
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
     const int64_t base = (int64_t)t * kTile;
     const float *grow = g + (int64_t)i * d;
     float *xrow = xs + (int64_t)i * ld;
     const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
     const float *sp = s_prev + (int64_t)i * tb.n_blocks;
-    uint64_t *srow = signs + ((int64_t)i * (ld / kTile) + t) * kSignWordsPerTile;
 
     float4 gv[4], xv[4];
 #pragma unroll
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
         xv[r] = ld4(xrow + j);
     }
     float x[4][4];
-    int piece[4];     // piece of the first coordinate of each float4 (multi-piece tiles only)
+    uint32_t sign_bits = 0;
     const bool single = (p1 - p0 == 1);
     const float s_single = (kPending && single) ? sp[tb.piece_blk[p0]] : 0.f;
 #pragma unroll
@@ -80,10 +81,6 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
         const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
         const float xx[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
         int p = p0;
-        if (!single) {
-            while (p + 1 < p1 && j >= tb.piece_hi[p]) ++p;
-            piece[r] = p;
-        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float e = xx[c];
@@ -99,11 +96,9 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
         }
         st4(xrow + j, make_float4(x[r][0], x[r][1], x[r][2], x[r][3]));
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint64_t w = __ballot(__float_as_uint(x[r][c]) >> 31);
-            if (lane == 0) srow[(r * 4 + wave) * 4 + c] = w;
-        }
+        for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
     }
+    signs[((int64_t)i * (ld / kTile) + t) * kThreads + tid] = (uint16_t)sign_bits;
 
     if (single) {
         double acc = 0.0;
@@ -128,7 +123,6 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
             const double S = block_sum(acc, scratch);
             if (tid == 0) partial[(int64_t)i * tb.n_pieces + p] = S;
         }
-        (void)piece;
     }
 }
 
@@ -149,19 +143,29 @@ __global__ __launch_bounds__(kWave) void bs_scale(const double *__restrict__ par
     }
 }
 
+// copysign(s, x) for the coordinate whose sign is bit `k` of `bits`; s >= 0.
+__device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
+{
+    return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
+}
+
+// kFusedScale: every tile lies inside one block of at most kMaxFusedPieces pieces; the block's
+// scale is formed here from the partial sums (and stored by the tile at the block's start).
+template <bool kFusedScale>
 __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int n, BsTable tb,
-                                                      const float *__restrict__ scales,
-                                                      const uint64_t *__restrict__ signs,
+                                                      const double *__restrict__ partial,
+                                                      float *__restrict__ scales,
+                                                      const uint16_t *__restrict__ signs,
                                                       float *__restrict__ theta, float *__restrict__ m,
                                                       float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
     const int64_t base = (int64_t)t * kTile;
     const int n_tiles = (int)(ld / kTile);
     const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
-    const bool single = (p1 - p0 == 1);
+    const bool single = kFusedScale || (p1 - p0 == 1);
+    const int b_single = tb.piece_blk[p0];
 
     float4 th[4], mm[4], vv[4], vh[4];
 #pragma unroll
@@ -172,48 +176,78 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
         vv[r] = ld4(v + j);
         vh[r] = ld4(vhat + j);
     }
-    // block of every coordinate this thread owns
-    int blk[4][4];
+    float acc[16];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int j = (int)base + 4 * (tid + kThreads * r);
-        int q = p0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (!single)
-                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
-            blk[r][c] = tb.piece_blk[q];
-        }
-    }
-    float acc[4][4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
+    for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+    const uint16_t *srow = signs + (int64_t)t * kThreads + tid;
+    const int64_t sstride = (int64_t)n_tiles * kThreads;
 
-    for (int i = 0; i < n; ++i) {
-        const uint64_t *srow = signs + ((int64_t)i * n_tiles + t) * kSignWordsPerTile;
-        const float *sc = scales + (int64_t)i * tb.n_blocks;
-        const float s_single = sc[blk[0][0]];
+    if (single) {
+        int q0 = 0, q1 = 0;
+        double len = 1.0;
+        if (kFusedScale) {
+            q0 = tb.block_piece0[b_single];
+            q1 = tb.block_piece0[b_single + 1];
+            len = (double)(tb.offsets[b_single + 1] - tb.offsets[b_single]);
+        }
+        constexpr int U = 4;
+        for (int i0 = 0; i0 < n; i0 += U) {
+            uint32_t bits[U];
+            float s[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u;
+                bits[u] = 0;
+                s[u] = 0.f;
+                if (i < n) {
+                    bits[u] = srow[i * sstride];
+                    if (kFusedScale) {
+                        const double *prow = partial + (int64_t)i * tb.n_pieces;
+                        double S = 0.0;
+                        for (int q = q0; q < q1; ++q) S += prow[q];
+                        s[u] = (float)(S / len);
+                        if (q0 == p0 && tid == 0) scales[(int64_t)i * tb.n_blocks + b_single] = s[u];
+                    } else {
+                        s[u] = scales[(int64_t)i * tb.n_blocks + b_single];
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (i0 + u < n) {
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(s[u], bits[u], q));
+                }
+            }
+        }
+    } else {
+        // several blocks meet in this tile: look up the block of every coordinate
+        int blk[16];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
+            const int j = (int)base + 4 * (tid + kThreads * r);
+            int q = p0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const uint64_t w = srow[(r * 4 + wave) * 4 + c];       // same address for the whole wavefront
-                const float s = single ? s_single : sc[blk[r][c]];
-                const float cj = ((w >> lane) & 1ull) ? -s : s;         // copysign(s, x) from the stored sign bit
-                acc[r][c] = fadd(acc[r][c], cj);
+                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
+                blk[r * 4 + c] = tb.piece_blk[q];
             }
+        }
+        for (int i = 0; i < n; ++i) {
+            const uint32_t bits = srow[i * sstride];
+            const float *sc = scales + (int64_t)i * tb.n_blocks;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(sc[blk[q]], bits, q));
         }
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         // padding coordinates take no gradient
-        const float4 gbar = make_float4(j < d ? fdiv(acc[r][0], p.n_workers) : 0.f,
-                                        j + 1 < d ? fdiv(acc[r][1], p.n_workers) : 0.f,
-                                        j + 2 < d ? fdiv(acc[r][2], p.n_workers) : 0.f,
-                                        j + 3 < d ? fdiv(acc[r][3], p.n_workers) : 0.f);
+        const float4 gbar = make_float4(j < d ? fdiv(acc[r * 4], p.n_workers) : 0.f,
+                                        j + 1 < d ? fdiv(acc[r * 4 + 1], p.n_workers) : 0.f,
+                                        j + 2 < d ? fdiv(acc[r * 4 + 2], p.n_workers) : 0.f,
+                                        j + 3 < d ? fdiv(acc[r * 4 + 3], p.n_workers) : 0.f);
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
         st4(theta + j, th[r]);
         st4(m + j, mm[r]);

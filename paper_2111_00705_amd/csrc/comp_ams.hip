@@ -47,8 +47,9 @@ struct comp_ams {
     std::vector<void *> tb_allocs;
     double *partial = nullptr;
     float *scales = nullptr;
-    uint64_t *signs = nullptr;
+    uint16_t *signs = nullptr;                 // [n][n_tiles][256] sign bits of the stored x
     bool pending = false;
+    bool fused_scale = false;                  // bs_update forms the scales itself (see kMaxFusedPieces)
 
     // Top-k
     TkGeom ge{};
@@ -203,6 +204,12 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off)
     h->tb.block_piece0 = d_bp;
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
+    {
+        bool ok = true;
+        for (int64_t t = 0; t < n_tiles && ok; ++t) ok = (tile_piece0[t + 1] - tile_piece0[t] == 1);
+        for (int b = 0; b < nb && ok; ++b) ok = (block_piece0[b + 1] - block_piece0[b] <= kMaxFusedPieces);
+        h->fused_scale = ok;
+    }
     h->partial = d_partial;
     h->scales = d_scales;
     return COMP_AMS_OK;
@@ -243,12 +250,17 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
         else
             bs_pass<false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
-    launch_timed(h, P_BS_SCALE, st, [&] {
-        bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
-    });
+    if (!h->fused_scale)
+        launch_timed(h, P_BS_SCALE, st, [&] {
+            bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
+        });
     launch_timed(h, P_BS_UPDATE, st, [&] {
-        bs_update<<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->scales, h->signs, h->theta, h->m, h->v,
-                                              h->vhat, h->params);
+        if (h->fused_scale)
+            bs_update<true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,
+                                                        h->theta, h->m, h->v, h->vhat, h->params);
+        else
+            bs_update<false><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,
+                                                         h->theta, h->m, h->v, h->vhat, h->params);
     });
     h->pending = true;
     return COMP_AMS_OK;
@@ -369,7 +381,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         std::vector<int64_t> off;
         for (int64_t s = 0; s < d; s += B) off.push_back(s);
         off.push_back(d);
-        if ((rc = dev_alloc_t(h, h->allocs, &h->signs, ld / 64 * (size_t)n))) return bail(rc);
+        if ((rc = dev_alloc_t(h, h->allocs, &h->signs, ld / 16 * (size_t)n))) return bail(rc);
         if ((rc = build_block_table(h, off))) return bail(rc);
     } else {
         h->k = k_or_block;
