@@ -31,15 +31,16 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {}
 
 
 def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:
-    """Bytes a kernel's own part of the method must move, per launch."""
+    """Algorithmic bytes of one launch = per-unit figure x units (n*d worker-coordinates).
+    The streaming pass of either compressor carries the 12 B per (worker, coordinate) of the
+    method (read g, read stored error vector, write it back); the update kernel carries the
+    32 B per coordinate of optimiser state (read and write theta, m, v, vhat)."""
     nd = n * d
     return {
-        "bs_fused": 12 * nd + 32 * d,      # read g, read e, write e; read+write theta, m, v, vhat
-        "bs_apply": 12 * nd + 32 * d,
-        "bs_partial": 8 * nd,              # read g, read e
-        "tk_pass1": 12 * nd,               # read g, read e, write x over e
-        "tk_collect": 4 * nd,
-        "tk_final": 32 * d,                # state read+write (candidates are a few per cent more)
+        "bs_pass": 12 * nd,
+        "bs_update": 32 * d,
+        "tk_pass1": 12 * nd,
+        "tk_final": 32 * d,
     }.get(name, 0)
 
 
@@ -52,6 +53,8 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--probe-mib", type=int, default=1024,
+                    help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all n workers are simulated as a batch on it); "
@@ -110,6 +113,25 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
     step_gbs = w.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9
 
+    # plain float4 copy on the same stream: what a trivial streaming kernel reaches on this chip, and
+    # the launch that calibrates the HBM byte counters (it moves exactly 2 * probe bytes)
+    copy_ceiling = None
+    if args.probe_mib > 0:
+        count = args.probe_mib * (1 << 20) // 4
+        src = torch.empty(count, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            P.probe_copy(dst, src)
+        torch.cuda.synchronize()
+        reps = 20
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            P.probe_copy(dst, src)
+        torch.cuda.synchronize()
+        copy_ceiling = {"gbs": round(2 * count * 4 * reps / (time.perf_counter() - c0) / 1e9, 1),
+                        "bytes_per_launch": 2 * count * 4, "kernel": "probe_copy"}
+        del src, dst
+
     cpu = None
     if not args.no_cpu:
         from oracle import oracle as O
@@ -149,6 +171,7 @@ def main() -> int:
         "step_algorithmic_gbs": round(step_gbs, 1),
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "kernels": {k: {a: round(b, 3) for a, b in v.items()} for k, v in kernels.items()},
+        "copy_ceiling": copy_ceiling,
         "cpu_baseline": cpu,
     }
     h.destroy()

@@ -140,6 +140,13 @@ int comp_ams_profile(comp_ams_t *h, int enable);
  */
 int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches);
 
+/*
+ * Measurement aid, no handle needed: a plain 16-bytes-per-lane copy of `count` floats
+ * (a positive multiple of 4, both pointers 16-byte aligned, device memory) dst <- src, enqueued on
+ * hip_stream.  Benchmarks use it to calibrate HBM traffic counters and as the copy ceiling.
+ */
+int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream);
+
 /* Message of the last failure on this handle (or of the last failed comp_ams_create when
  * h is NULL).  The string stays valid until the next failing call. */
 const char *comp_ams_last_error(const comp_ams_t *h);

@@ -4,7 +4,7 @@ The work is in csrc/ (hand-written HIP kernels behind the C ABI of
 include/comp_ams.h); this package only builds and binds it.
 """
 from .binding import (BLOCKSIGN, EDEVICE, EINVAL, ENOMEM, ESTATE, EXPORTS, OK, TOPK, CompAms, CompAmsError,
-                      lib)
+                      lib, probe_copy)
 
-__all__ = ["CompAms", "CompAmsError", "lib", "TOPK", "BLOCKSIGN", "EXPORTS", "OK", "EINVAL", "ENOMEM",
+__all__ = ["CompAms", "CompAmsError", "lib", "probe_copy", "TOPK", "BLOCKSIGN", "EXPORTS", "OK", "EINVAL", "ENOMEM",
            "EDEVICE", "ESTATE"]

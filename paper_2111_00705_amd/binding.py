@@ -24,7 +24,7 @@ EXPORTS = [
     "comp_ams_set_eps_mode", "comp_ams_step", "comp_ams_get_theta", "comp_ams_get_m", "comp_ams_get_v",
     "comp_ams_get_vhat", "comp_ams_get_error", "comp_ams_get_selected", "comp_ams_get_scales",
     "comp_ams_n_blocks", "comp_ams_set_state", "comp_ams_sync", "comp_ams_last_error", "comp_ams_profile",
-    "comp_ams_profile_read",
+    "comp_ams_profile_read", "comp_ams_probe_copy",
 ]
 
 
@@ -69,6 +69,7 @@ def lib():
         L.comp_ams_profile.argtypes = [vp, C.c_int]
         L.comp_ams_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                             C.POINTER(C.c_int64)]
+        L.comp_ams_probe_copy.argtypes = [fp, fp, C.c_int64, vp]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
         _lib = L
@@ -84,6 +85,17 @@ def _ptr(a):
         return a.ctypes.data, 0
     assert a.dtype.is_floating_point and a.element_size() == 4 and a.is_contiguous()
     return a.data_ptr(), 1 if a.is_cuda else 0
+
+
+def probe_copy(dst, src, stream=None):
+    """Plain device copy dst <- src (torch float32 CUDA tensors of equal size, multiple of 4)."""
+    import torch
+    assert dst.is_cuda and src.is_cuda and dst.numel() == src.numel()
+    if stream is None:
+        stream = torch.cuda.current_stream(dst.device).cuda_stream
+    rc = lib().comp_ams_probe_copy(dst.data_ptr(), src.data_ptr(), dst.numel(), stream)
+    if rc != OK:
+        raise CompAmsError(rc, lib().comp_ams_last_error(None).decode())
 
 
 class CompAms:

@@ -149,6 +149,9 @@ __device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
     return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
 }
 
+constexpr int kScaleChunk = 1024;   // workers whose scales are staged in LDS at a time
+constexpr int kSignBatch = 8;       // workers whose sign words are loaded together
+
 // kFusedScale: every tile lies inside one block of at most kMaxFusedPieces pieces; the block's
 // scale is formed here from the partial sums (and stored by the tile at the block's start).
 template <bool kFusedScale>
@@ -159,6 +162,7 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
                                                       float *__restrict__ theta, float *__restrict__ m,
                                                       float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
+    __shared__ float s_lds[kScaleChunk];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
@@ -167,15 +171,6 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
     const bool single = kFusedScale || (p1 - p0 == 1);
     const int b_single = tb.piece_blk[p0];
 
-    float4 th[4], mm[4], vv[4], vh[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
-    }
     float acc[16];
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
@@ -190,33 +185,36 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             q1 = tb.block_piece0[b_single + 1];
             len = (double)(tb.offsets[b_single + 1] - tb.offsets[b_single]);
         }
-        constexpr int U = 4;
-        for (int i0 = 0; i0 < n; i0 += U) {
-            uint32_t bits[U];
-            float s[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u;
-                bits[u] = 0;
-                s[u] = 0.f;
-                if (i < n) {
-                    bits[u] = srow[i * sstride];
-                    if (kFusedScale) {
-                        const double *prow = partial + (int64_t)i * tb.n_pieces;
-                        double S = 0.0;
-                        for (int q = q0; q < q1; ++q) S += prow[q];
-                        s[u] = (float)(S / len);
-                        if (q0 == p0 && tid == 0) scales[(int64_t)i * tb.n_blocks + b_single] = s[u];
-                    } else {
-                        s[u] = scales[(int64_t)i * tb.n_blocks + b_single];
-                    }
+        for (int c0 = 0; c0 < n; c0 += kScaleChunk) {
+            const int cn = min(kScaleChunk, n - c0);
+            __syncthreads();
+            // one thread per worker: the scale of this tile's block
+            for (int u = tid; u < cn; u += kThreads) {
+                const int i = c0 + u;
+                float s;
+                if (kFusedScale) {
+                    const double *prow = partial + (int64_t)i * tb.n_pieces;
+                    double S = 0.0;
+                    for (int q = q0; q < q1; ++q) S += prow[q];
+                    s = (float)(S / len);
+                    if (q0 == p0) scales[(int64_t)i * tb.n_blocks + b_single] = s;   // this tile starts the block
+                } else {
+                    s = scales[(int64_t)i * tb.n_blocks + b_single];
                 }
+                s_lds[u] = s;
             }
+            __syncthreads();
+            for (int u0 = 0; u0 < cn; u0 += kSignBatch) {
+                uint32_t bits[kSignBatch];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (i0 + u < n) {
+                for (int u = 0; u < kSignBatch; ++u) bits[u] = (u0 + u < cn) ? srow[(c0 + u0 + u) * sstride] : 0u;
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(s[u], bits[u], q));
+                for (int u = 0; u < kSignBatch; ++u) {
+                    if (u0 + u < cn) {
+                        const float s = s_lds[u0 + u];
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(s, bits[u], q));
+                    }
                 }
             }
         }
@@ -239,6 +237,17 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(sc[blk[q]], bits, q));
         }
+    }
+    // the state is loaded only now: fewer live registers during the worker loop, and the other
+    // workgroups resident on the compute unit cover this latency
+    float4 th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        th[r] = ld4(theta + j);
+        mm[r] = ld4(m + j);
+        vv[r] = ld4(v + j);
+        vh[r] = ld4(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {

@@ -54,12 +54,13 @@ struct comp_ams {
     // Top-k
     TkGeom ge{};
     TkWorker *ws = nullptr;
-    uint32_t *hist1 = nullptr;
+    uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the running step
+    uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
     uint2 *cand = nullptr;                     // [n][wgs][4][list_cap] candidate (index, value bits)
     uint2 *cand_dir = nullptr;                 // [n][n_tiles][4] (offset, count) of a tile's candidates in its list
     uint32_t *list_len = nullptr;              // [n][wgs][4]
-    uint64_t *dense = nullptr;                 // [n][d] comp of the candidates in the threshold bin
-    uint32_t *dense_cnt = nullptr;             // [n]
+    uint64_t *dense = nullptr;                 // [n][wgs][4][list_cap] comp of the candidates in the threshold bin
+    uint32_t *dense_len = nullptr;             // [n][wgs][4]
     uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
 
@@ -71,9 +72,10 @@ struct comp_ams {
 
 namespace {
 
-enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_COMPACT, P_TK_RESOLVE, P_TK_FINAL, P_SLOTS };
-const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_compact",
-                                         "tk_resolve", "tk_final"};
+enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_PICK, P_TK_COMPACT, P_TK_RESOLVE, P_TK_FINAL,
+                P_SLOTS };
+const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_pick",
+                                         "tk_compact", "tk_resolve", "tk_final"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -270,15 +272,16 @@ int step_topk(comp_ams *h, const float *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->hist1, h->cand, h->cand_dir,
-                                                         h->list_len);
+        tk_pass1<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->hist1, h->histf, h->cand,
+                                                         h->cand_dir, h->list_len);
     });
+    launch_timed(h, P_TK_PICK, st, [&] { tk_pick<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf); });
     launch_timed(h, P_TK_COMPACT, st, [&] {
-        tk_compact<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->hist1, h->cand, h->cand_dir,
-                                                           h->list_len, h->dense, h->dense_cnt);
+        tk_compact<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->cand, h->cand_dir, h->list_len,
+                                                           h->dense, h->dense_len);
     });
     launch_timed(h, P_TK_RESOLVE, st, [&] {
-        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->hist1, h->dense, h->dense_cnt);
+        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf, h->dense, h->dense_len);
     });
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cand_dir, h->theta, h->m, h->v, h->vhat,
@@ -294,6 +297,7 @@ int reset_topk_workers(comp_ams *h)
     for (auto &w : init) {
         std::memset(&w, 0, sizeof w);
         w.guess = kNoGuess;
+        w.slack = kFirstSlack;
         w.tc = kNoThreshold;
     }
     HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
@@ -394,25 +398,18 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int ib = 1;
         while (((int64_t)1 << ib) < d) ++ib;
         ge.idx_bits = ib;
-        ge.n_levels = 0;
-        for (int s_hi = kShift1 + ib; s_hi > 0;) {
-            const int s_lo = std::max(s_hi - kDigitBits, 0);
-            ge.s_hi[ge.n_levels] = s_hi;
-            ge.s_lo[ge.n_levels] = s_lo;
-            ++ge.n_levels;
-            s_hi = s_lo;
-        }
         ge.wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         ge.list_cap = (ge.n_tiles + ge.wgs - 1) / ge.wgs * kSub;
         const size_t segs = (size_t)n * ge.n_tiles;
         const size_t lists = (size_t)n * ge.wgs * 4;
         if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cand, lists * ge.list_cap, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cand_dir, segs * 4)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->list_len, lists)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->dense, (size_t)n * (size_t)d, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->dense_cnt, (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense, lists * ge.list_cap, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense_len, lists)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
@@ -641,6 +638,19 @@ int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double
     if (name) *name = kProfNames[slot];
     if (total_ms) *total_ms = total;
     if (launches) *launches = (int64_t)h->prof[slot].size();
+    return COMP_AMS_OK;
+}
+
+int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream)
+{
+    if (!dst_dev || !src_dev) return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: NULL pointer");
+    if (count < 4 || (count & 3) || ((reinterpret_cast<uintptr_t>(dst_dev) | reinterpret_cast<uintptr_t>(src_dev)) & 15u))
+        return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: count must be a positive multiple of 4 and the pointers 16-byte aligned");
+    const int64_t vecs = count / 4;
+    const unsigned blocks = (unsigned)std::min<int64_t>((vecs + kThreads - 1) / kThreads, 256 * 16);
+    probe_copy<<<blocks, kThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(dst_dev, src_dev, vecs);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(nullptr, COMP_AMS_EDEVICE, "probe_copy launch failed: %s", hipGetErrorString(e));
     return COMP_AMS_OK;
 }
 

@@ -116,4 +116,14 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return ((scratch[0] + scratch[1]) + scratch[2]) + scratch[3];
 }
 
+// Plain streaming copy, 16 bytes per lane, grid-stride: the yardstick for HBM counters and for the
+// bandwidth a simple kernel reaches on this chip.
+__global__ __launch_bounds__(kThreads) void probe_copy(float *__restrict__ dst, const float *__restrict__ src,
+                                                       int64_t vecs)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < vecs; q += stride)
+        st4(dst + 4 * q, ld4(src + 4 * q));
+}
+
 }  // namespace cams

@@ -10,19 +10,23 @@
 // The error memory is kept in deferred form: after a step the library stores x_i = g_i + e_i and
 // the worker's threshold Tc_i; e_i[j] = (comp(x_i[j], j) >= Tc_i) ? +0 : x_i[j] is formed on the fly
 // when the next step (or a getter) reads x_i, so kept coordinates are never zeroed by scattered
-// writes and one step needs a single pass over g and the stored vector.  Four launches per step,
+// writes and one step needs a single pass over g and the stored vector.  Five launches per step,
 // ordered only by kernel boundaries (no fences, no waiting inside a kernel):
 //
 //   tk_pass1    streams g and the stored x once and writes the new x; counts every element in a
-//               per-worker histogram of its top 11 magnitude bits; lists "candidates" - elements
-//               whose bin is >= the worker's guess, carried over from the previous step - as
-//               (index, value) pairs in one dense list per (worker, workgroup, wavefront), with a
-//               directory entry (offset, count) per (worker, tile, wavefront)
-//   tk_compact  every workgroup finds the bin b* of the k-th largest from the histogram; if the
-//               guess was above b* (always on the first step) the worker's candidates are listed
-//               again from the stored x with bin >= b*; candidates in bin b* are copied, as comp
-//               values, to one dense list per worker
-//   tk_resolve  one workgroup per worker: the remaining digits of Tc over the dense list
+//               per-worker histogram of its top 11 magnitude bits ("coarse" bin, an eighth of an
+//               octave) and, for the two coarse bins around the worker's guess, of its top 17 bits
+//               ("fine" bin, 0.2 % wide); lists "candidates" - elements whose fine bin is >= the
+//               guess, which is carried over from the previous step's threshold minus a little
+//               slack - as (index, value) pairs in one dense list per (worker, workgroup,
+//               wavefront), with a directory entry (offset, count) per (worker, tile, wavefront)
+//   tk_pick     one workgroup per worker: the coarse (and if covered, fine) bin of the k-th
+//               largest, from the histograms
+//   tk_compact  if the guess was above that bin (always on the first step) the worker's
+//               candidates are listed again from the stored x; candidates in that bin are
+//               copied, as comp values, to one dense list per worker
+//   tk_resolve  one workgroup per worker: the remaining digits of Tc over the dense list, and
+//               the guess for the next step
 //   tk_final    per tile, all workers: candidates with comp >= Tc are the kept coordinates; their
 //               values are added into an LDS copy of the tile in ascending worker order; then
 //               gbar = acc / n and the AMSGrad update of the tile's theta, m, v, vhat
@@ -34,24 +38,29 @@
 
 namespace cams {
 
-constexpr int kBins1 = 2048;      // first digit: top 11 of the 31 magnitude bits
+constexpr int kBins1 = 2048;      // coarse bin: top 11 of the 31 magnitude bits
 constexpr int kShift1 = 20;
-constexpr int kDigitBits = 12;    // later digits
+constexpr int kFineShift = 14;    // fine bin: top 17 bits; 64 fine bins per coarse bin
+constexpr int kFinePerCoarse = 1 << (kShift1 - kFineShift);
+constexpr int kFineWindow = 2 * kFinePerCoarse;   // fine bins counted: the guess's coarse bin and the next
+constexpr int kDigitBits = 12;    // digits of the dense-list search
 constexpr int kBins2 = 1 << kDigitBits;
-constexpr int kMaxLevels = 5;     // ceil((20 + 31) / 12)
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles
 constexpr int kResolveThreads = 1024;
-constexpr uint32_t kNoGuess = kBins1;        // guess that lists nothing (before the first step)
+constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothing (before the first step)
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
+constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
 
 struct TkWorker {
     uint64_t tc;            // threshold composite of the last finished step (pending selection)
-    uint32_t guess;         // pass 1 lists elements with bin >= guess
-    // first digit of the running step, written by tk_compact, read by tk_resolve
-    uint32_t bstar;         // bin of the k-th largest magnitude
-    uint32_t rank;          // 1-based rank (from the top) of the k-th largest inside bin b*
-    uint32_t whole_bin;     // the whole bin b* is kept: Tc needs no further digit
-    uint32_t relisted;      // the guess was above b*: candidates were listed again
+    uint32_t guess;         // pass 1 lists elements with fine bin >= guess
+    uint32_t slack;         // fine bins kept between the threshold and the next guess
+    // leading digits of the running step's Tc, written by tk_compact, read by tk_resolve
+    uint32_t prefix;        // magnitude bits above pshift
+    uint32_t pshift;        // kShift1 (coarse bin known) or kFineShift (fine bin known)
+    uint32_t rank;          // 1-based rank (from the top) of the k-th largest among elements with this prefix
+    uint32_t whole;         // all elements with this prefix are kept: Tc needs no further digit
+    uint32_t relisted;      // the guess was above the threshold: candidates were listed again
     uint32_t pad;
 };
 
@@ -62,8 +71,6 @@ struct TkGeom {
     uint32_t k;
     int32_t wgs;            // workgroups per worker in tk_pass1 / tk_compact; tile t belongs to t % wgs
     int32_t list_cap;       // capacity of one candidate list = ceil(n_tiles / wgs) * kSub
-    int32_t n_levels;       // digits after the first
-    int32_t s_hi[kMaxLevels], s_lo[kMaxLevels];   // bit range [s_lo, s_hi) of comp for each of them
 };
 
 __device__ __forceinline__ uint64_t composite(float x, uint32_t j, int idx_bits)
@@ -125,21 +132,25 @@ __device__ __forceinline__ uint32_t wave_append(bool flag, uint32_t &count)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws,
-                                                     uint32_t *__restrict__ hist1, uint2 *__restrict__ cand,
+                                                     uint32_t *__restrict__ hist1,
+                                                     uint32_t *__restrict__ histf, uint2 *__restrict__ cand,
                                                      uint2 *__restrict__ cand_dir,
                                                      uint32_t *__restrict__ list_len)
 {
     __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t lf[kFineWindow];
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
+    const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
     const uint64_t tc_prev = ws[i].tc;
     const float *grow = g + (int64_t)i * ge.d;
     float *xrow = xs + (int64_t)i * ge.ld;
     const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
     uint2 *list = cand + list_id * ge.list_cap;
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
+    if (tid < kFineWindow) lf[tid] = 0;
     __syncthreads();
 
     uint32_t count = 0;   // length of this wavefront's list so far
@@ -169,9 +180,13 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const bool valid = j + c < ge.d;
-                const uint32_t bin = mag_key(x[c]) >> kShift1;
-                if (valid) atomicAdd(&lh[bin], 1u);
-                const bool hit = valid && bin >= guess;
+                const uint32_t key = mag_key(x[c]);
+                const uint32_t fine = key >> kFineShift;
+                if (valid) {
+                    atomicAdd(&lh[key >> kShift1], 1u);
+                    if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
+                }
+                const bool hit = valid && fine >= guess;
                 const uint32_t slot = wave_append(hit, count);   // < list_cap: kSub coordinates per tile
                 if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
             }
@@ -185,53 +200,95 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
         const uint32_t c = lh[b];
         if (c) atomicAdd(row + b, c);
     }
+    if (tid < kFineWindow && lf[tid]) atomicAdd(histf + (int64_t)i * kFineWindow + tid, lf[tid]);
 }
 
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void tk_compact(const float *__restrict__ xs, TkGeom ge,
-                                                       TkWorker *__restrict__ ws,
-                                                       const uint32_t *__restrict__ hist1,
-                                                       uint2 *__restrict__ cand, uint2 *__restrict__ cand_dir,
-                                                       uint32_t *__restrict__ list_len,
-                                                       uint64_t *__restrict__ dense, uint32_t *__restrict__ dense_cnt)
+// One workgroup per worker: the leading digits of Tc from the histograms of tk_pass1.
+__global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
+                                                    const uint32_t *__restrict__ hist1,
+                                                    const uint32_t *__restrict__ histf)
 {
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
     __shared__ uint32_t res[4];
-    __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t wave_base[4];
-    const int i = blockIdx.y;
+    __shared__ uint32_t fres[3];
+    const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-
-    // first digit: identical in every workgroup of the worker
     const uint32_t *row = hist1 + (int64_t)i * kBins1;
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = row[b];
     __syncthreads();
     find_rank_bin(lh, part, res, kBins1, ge.k);
     if (!res[3]) return;                            // cannot happen: the histogram holds d >= k elements
-    const uint32_t bstar = res[0];
-    const uint32_t rank = ge.k - res[1];
-    const bool whole_bin = (res[2] == rank);
-    const bool relist = ws[i].guess > bstar;
-    if (blockIdx.x == 0 && tid == 0) {
-        ws[i].bstar = bstar;
-        ws[i].rank = rank;
-        ws[i].whole_bin = whole_bin ? 1u : 0u;
-        ws[i].relisted = relist ? 1u : 0u;
+    const uint32_t guess = ws[i].guess;
+    uint32_t prefix = res[0];                       // coarse bin of the k-th largest
+    uint32_t pshift = kShift1;
+    uint32_t rank = ge.k - res[1];
+    uint32_t count = res[2];
+    const uint32_t wb = guess >> (kShift1 - kFineShift);      // first coarse bin of the fine window
+    if (prefix - wb < 2u) {
+        // the fine histogram covers this coarse bin: pick the fine bin as well (one wavefront)
+        if (wave == 0) {
+            const uint32_t c = histf[(int64_t)i * kFineWindow + (prefix - wb) * kFinePerCoarse + lane];
+            uint32_t suffix = c;                    // elements of this coarse bin in fine bins >= lane
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t t = __shfl_down(suffix, off, kWave);
+                if (lane + off < kWave) suffix += t;
+            }
+            const uint64_t reach = __ballot(suffix >= rank);  // lane 0 always reaches: suffix(0) = count >= rank
+            const int top = reach ? 63 - __builtin_clzll(reach) : 0;
+            if (lane == top) {
+                fres[0] = (uint32_t)lane;
+                fres[1] = suffix - c;
+                fres[2] = c;
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << (kShift1 - kFineShift)) | fres[0];
+        pshift = kFineShift;
+        rank -= fres[1];
+        count = fres[2];
     }
-    if (whole_bin && !relist) return;
+    if (tid == 0) {
+        ws[i].prefix = prefix;
+        ws[i].pshift = pshift;
+        ws[i].rank = rank;
+        ws[i].whole = (count == rank) ? 1u : 0u;
+        // candidates are complete iff every element at or above the prefix was listed
+        ws[i].relisted = (((uint64_t)guess << kFineShift) > ((uint64_t)prefix << pshift)) ? 1u : 0u;
+    }
+}
+
+// Lists the worker's candidates again if the guess was too high, and copies the candidates that
+// carry the prefix, as comp values, to the "dense" region of their list (same shape as the
+// candidate lists; typically a handful per list).  No atomics: tk_resolve walks the regions.
+__global__ __launch_bounds__(kThreads) void tk_compact(const float *__restrict__ xs, TkGeom ge,
+                                                       const TkWorker *__restrict__ ws,
+                                                       uint2 *__restrict__ cand, uint2 *__restrict__ cand_dir,
+                                                       uint32_t *__restrict__ list_len,
+                                                       uint64_t *__restrict__ dense, uint32_t *__restrict__ dense_len)
+{
+    const int i = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    const bool whole = ws[i].whole != 0, relist = ws[i].relisted != 0;
+    if (whole && !relist) return;
 
     const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
     uint2 *list = cand + list_id * ge.list_cap;
-    uint32_t len;
+    uint64_t *out = dense + list_id * ge.list_cap;
+    uint32_t kept = 0;   // entries of this wavefront's dense region
     if (relist) {
-        // the guess was too high: list this workgroup's candidates again, now with bin >= b*
+        // list this workgroup's candidates again, now from the prefix up; those with the prefix
+        // itself go to the dense region on the way
         const float *xrow = xs + (int64_t)i * ge.ld;
-        uint32_t count = 0;
+        uint32_t filled = 0;
         for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
             const int64_t base = (int64_t)t * kTile;
-            const uint32_t first = count;
+            const uint32_t first = filled;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const uint32_t j = (uint32_t)base + 4 * (tid + kThreads * r);
@@ -239,82 +296,91 @@ __global__ __launch_bounds__(kThreads) void tk_compact(const float *__restrict__
                 const float x[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const bool hit = j + c < ge.d && (mag_key(x[c]) >> kShift1) >= bstar;
-                    const uint32_t slot = wave_append(hit, count);
+                    const uint32_t top = mag_key(x[c]) >> pshift;
+                    const bool hit = j + c < ge.d && top >= prefix;
+                    const uint32_t slot = wave_append(hit, filled);
                     if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
+                    const bool eq = hit && top == prefix && !whole;
+                    const uint32_t at = wave_append(eq, kept);
+                    if (eq) out[at] = composite(x[c], j + c, ge.idx_bits);
                 }
             }
-            if (lane == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, count - first);
+            if (lane == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, filled - first);
         }
-        if (lane == 0) list_len[list_id] = count;
-        len = count;
-        __syncthreads();   // the list written above is read below by other lanes
+        if (lane == 0) list_len[list_id] = filled;
     } else {
-        len = list_len[list_id];
-    }
-    if (whole_bin) return;
-
-    // dense list of the candidates in bin b*: count, reserve once per workgroup, then copy
-    uint32_t mine = 0;
-    for (uint32_t q = lane; q < len; q += kWave) mine += ((list[q].y & 0x7fffffffu) >> kShift1) == bstar ? 1u : 0u;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mine += __shfl_xor(mine, off, kWave);
-    if (lane == 0) wave_tot[wave] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
-        uint32_t at = total ? atomicAdd(dense_cnt + i, total) : 0u;
-        for (int w = 0; w < 4; ++w) {
-            wave_base[w] = at;
-            at += wave_tot[w];
+        const uint32_t len = list_len[list_id];
+        for (uint32_t q0 = 0; q0 < len; q0 += kWave) {
+            const uint32_t q = q0 + lane;
+            bool eq = false;
+            uint2 c = make_uint2(0u, 0u);
+            if (q < len) {
+                c = list[q];
+                eq = ((c.y & 0x7fffffffu) >> pshift) == prefix;
+            }
+            const uint32_t at = wave_append(eq, kept);
+            if (eq) out[at] = composite(__uint_as_float(c.y), c.x, ge.idx_bits);
         }
     }
-    __syncthreads();
-    uint32_t count = wave_base[wave];
-    uint64_t *out = dense + (int64_t)i * ge.d;
-    for (uint32_t q0 = 0; q0 < len; q0 += kWave) {
-        const uint32_t q = q0 + lane;
-        bool hit = false;
-        uint64_t comp = 0;
-        if (q < len) {
-            const uint2 c = list[q];
-            hit = ((c.y & 0x7fffffffu) >> kShift1) == bstar;
-            comp = composite(__uint_as_float(c.y), c.x, ge.idx_bits);
-        }
-        const uint32_t slot = wave_append(hit, count);
-        if (hit) out[slot] = comp;      // slot < d: every element appears at most once
-    }
+    if (lane == 0) dense_len[list_id] = kept;
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup of 1024 threads per worker: the digits of Tc after the first, over the dense list.
-// Also hands the next step its guess and clears the histogram row and the list counter.
+// One workgroup of 1024 threads per worker: the digits of Tc below the prefix, over the worker's
+// dense regions.  Also hands the next step its guess and clears the histogram rows.
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
                                                               uint32_t *__restrict__ hist1,
+                                                              uint32_t *__restrict__ histf,
                                                               const uint64_t *__restrict__ dense,
-                                                              uint32_t *__restrict__ dense_cnt)
+                                                              const uint32_t *__restrict__ dense_len)
 {
     __shared__ uint32_t lh[kBins2];
+    __shared__ uint32_t pre[kResolveThreads + 1];   // exclusive prefix of the region lengths of a chunk of lists
     __shared__ uint32_t part[kResolveThreads / kWave];
     __shared__ uint32_t res[4];
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const TkWorker w = ws[i];
-    uint64_t prefix = w.bstar;
+    uint64_t prefix = w.prefix;
     uint32_t rank = w.rank;
-    bool done = w.whole_bin != 0;
-    uint64_t tc = (uint64_t)w.bstar << (kShift1 + ge.idx_bits);
-    const uint32_t cnt = dense_cnt[i];
-    const uint64_t *list = dense + (int64_t)i * ge.d;
+    int s_hi = (int)w.pshift + ge.idx_bits;
+    bool done = w.whole != 0;
+    uint64_t tc = prefix << s_hi;
+    const int n_lists = ge.wgs * 4;
+    const int64_t list0 = (int64_t)i * n_lists;
 
-    for (int lv = 0; lv < ge.n_levels && !done; ++lv) {
-        const int s_hi = ge.s_hi[lv], s_lo = ge.s_lo[lv];
+    while (!done) {
+        const int s_lo = max(s_hi - kDigitBits, 0);
         const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
         for (int b = tid; b < kBins2; b += kResolveThreads) lh[b] = 0;
-        __syncthreads();
-        for (uint32_t q = tid; q < cnt; q += kResolveThreads) {
-            const uint64_t comp = list[q];
-            if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
+        for (int c0 = 0; c0 < n_lists; c0 += kResolveThreads) {
+            // lengths of up to 1024 regions -> exclusive prefix sums in LDS
+            const uint32_t len = (c0 + tid < n_lists) ? dense_len[list0 + c0 + tid] : 0u;
+            uint32_t incl = len;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, kWave);
+                if (lane >= off) incl += up;
+            }
+            __syncthreads();                       // previous chunk's readers of pre/part are done
+            if (lane == kWave - 1) part[wave] = incl;
+            __syncthreads();
+            uint32_t before = 0;
+            for (int v = 0; v < wave; ++v) before += part[v];
+            pre[tid] = before + incl - len;
+            if (tid == kResolveThreads - 1) pre[kResolveThreads] = before + incl;
+            __syncthreads();
+            const uint32_t total = pre[kResolveThreads];
+            for (uint32_t q = tid; q < total; q += kResolveThreads) {
+                int lo = 0, hi = kResolveThreads;              // largest l with pre[l] <= q
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (pre[mid] <= q) lo = mid; else hi = mid;
+                }
+                const uint64_t comp = dense[(list0 + c0 + lo) * ge.list_cap + (q - pre[lo])];
+                if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
+            }
         }
         __syncthreads();
         find_rank_bin(lh, part, res, kBins2, rank);
@@ -325,17 +391,20 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             done = true;
             tc = prefix << s_lo;
         }
+        s_hi = s_lo;
         __syncthreads();
     }
     if (tid == 0) {
         ws[i].tc = tc;
-        // next step lists from one bin (an eighth of an octave) below b*; two after a miss
-        const uint32_t slack = w.relisted ? 2u : 1u;
-        ws[i].guess = w.bstar >= slack ? w.bstar - slack : 0u;
-        dense_cnt[i] = 0;
+        // next step lists from a few fine bins below this threshold; more after a miss
+        const uint32_t slack = w.relisted ? min(w.slack * 2u, kMaxSlack) : max(w.slack - 1u, kMinSlack);
+        const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
+        ws[i].slack = slack;
+        ws[i].guess = fine > slack ? fine - slack : 0u;
     }
     uint32_t *row = hist1 + (int64_t)i * kBins1;
     for (int b = tid; b < kBins1; b += kResolveThreads) row[b] = 0;
+    if (tid < kFineWindow) histf[(int64_t)i * kFineWindow + tid] = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
