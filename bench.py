@@ -25,9 +25,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), keyed by
+# HBM-side bytes per launch (fetched + written) of the dominant kernels, from the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (calibrated on probe_copy), keyed by
 # (workload name, kernel); absent = not measured.
-MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {}
+MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
+    ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 234.5e6,
+    ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.6e6,
+    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2244.8e6,
+    ("cfg2_topk_n16_d11173962", "tk_final"): 390.7e6,
+    ("cfg3_layersign_n32_d25557032", "bs_pass"): 9975.9e6,
+    ("cfg3_layersign_n32_d25557032", "bs_update"): 921.8e6,
+    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10644.6e6,
+    ("cfg4_topk_n8_d110000000", "tk_final"): 3614.7e6,
+}
 
 
 def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:

@@ -130,6 +130,66 @@ __device__ __forceinline__ uint32_t wave_append(bool flag, uint32_t &count)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Pending selection of the previous step in 32-bit form: the coordinate j with magnitude bits
+// `key` was kept iff  key > tkey  or  (key == tkey and j <= tj).
+struct KeptTest {
+    uint32_t tkey, tj;
+};
+__device__ __forceinline__ KeptTest kept_test(uint64_t tc, int idx_bits)
+{
+    const uint32_t imask = (uint32_t)((1ull << idx_bits) - 1ull);
+    KeptTest k;
+    k.tkey = (uint32_t)(tc >> idx_bits);            // kNoThreshold gives 0xffffffff: above every key
+    k.tj = imask - ((uint32_t)tc & imask);
+    return k;
+}
+__device__ __forceinline__ bool was_kept(const KeptTest &k, uint32_t key, uint32_t j)
+{
+    return key >= k.tkey && (key > k.tkey || j <= k.tj);
+}
+
+// One tile of tk_pass1 for one workgroup.  kFull: the whole tile lies below d.
+template <bool kFull>
+__device__ __forceinline__ void pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow, uint32_t base,
+                                           uint32_t d, const KeptTest &kt, uint32_t guess, uint32_t wbase,
+                                           uint32_t *lh, uint32_t *lf, uint2 *__restrict__ list, uint32_t &count)
+{
+    const int tid = threadIdx.x;
+    float4 gv[4], xv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t j = base + 4 * (tid + kThreads * r);
+        gv[r] = load_grad4(grow, j, d);
+        xv[r] = ld4(xrow + j);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t j = base + 4 * (tid + kThreads * r);
+        const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+        const float xo[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+        float x[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            // e = x_old - C(x_old): +0 where the previous step kept the coordinate
+            const float e = was_kept(kt, mag_key(xo[c]), j + c) ? 0.f : xo[c];
+            x[c] = (kFull || j + c < d) ? fadd(gg[c], e) : 0.f;
+        }
+        st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool valid = kFull || j + c < d;
+            const uint32_t fine = mag_key(x[c]) >> kFineShift;
+            if (valid) {
+                atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
+                if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
+            }
+            const bool hit = valid && fine >= guess;
+            const uint32_t slot = wave_append(hit, count);   // < list_cap: kSub coordinates per tile
+            if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws,
                                                      uint32_t *__restrict__ hist1,
@@ -144,7 +204,8 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
     const int wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
-    const uint64_t tc_prev = ws[i].tc;
+    const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
+    const uint32_t d = (uint32_t)ge.d;
     const float *grow = g + (int64_t)i * ge.d;
     float *xrow = xs + (int64_t)i * ge.ld;
     const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
@@ -155,42 +216,12 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
 
     uint32_t count = 0;   // length of this wavefront's list so far
     for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
-        const int64_t base = (int64_t)t * kTile;
+        const uint32_t base = (uint32_t)t * kTile;
         const uint32_t first = count;
-        float4 gv[4], xv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t j = base + 4 * (tid + kThreads * r);
-            gv[r] = load_grad4(grow, j, ge.d);
-            xv[r] = ld4(xrow + j);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t j = (uint32_t)base + 4 * (tid + kThreads * r);
-            const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
-            const float xo[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
-            float x[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                // e = x_old - C(x_old): +0 where the previous step kept the coordinate
-                const float e = (composite(xo[c], j + c, ge.idx_bits) >= tc_prev) ? 0.f : xo[c];
-                x[c] = (j + c < ge.d) ? fadd(gg[c], e) : 0.f;
-            }
-            st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bool valid = j + c < ge.d;
-                const uint32_t key = mag_key(x[c]);
-                const uint32_t fine = key >> kFineShift;
-                if (valid) {
-                    atomicAdd(&lh[key >> kShift1], 1u);
-                    if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
-                }
-                const bool hit = valid && fine >= guess;
-                const uint32_t slot = wave_append(hit, count);   // < list_cap: kSub coordinates per tile
-                if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
-            }
-        }
+        if (base + kTile <= d)
+            pass1_tile<true>(grow, xrow, base, d, kt, guess, wbase, lh, lf, list, count);
+        else
+            pass1_tile<false>(grow, xrow, base, d, kt, guess, wbase, lh, lf, list, count);
         if ((tid & 63) == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, count - first);
     }
     if ((tid & 63) == 0) list_len[list_id] = count;
@@ -408,7 +439,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
 }
 
 // ---------------------------------------------------------------------------------------------
-constexpr int kFinChunk = 2048;   // candidates staged in LDS at a time
+constexpr int kFinChunk = 1024;   // candidates staged in LDS at a time
 constexpr int kFinGroup = 32;     // workers whose candidate lists are flattened together
 
 __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
@@ -429,16 +460,6 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
     const int64_t base = (int64_t)t * kTile;
     const int tid = threadIdx.x;
 
-    // state loads first: independent of the selection
-    float4 th[4], mm[4], vv[4], vh[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
-    }
     for (int l = tid; l < kTile; l += kThreads) acc[l] = 0.f;
 
     for (int w0 = 0; w0 < ge.n; w0 += kFinGroup) {
@@ -505,6 +526,17 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
     }
     __syncthreads();
 
+    // the state is loaded only now: fewer live registers above, and the other workgroups resident
+    // on the compute unit cover this latency
+    float4 th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        th[r] = ld4(theta + j);
+        mm[r] = ld4(m + j);
+        vv[r] = ld4(v + j);
+        vh[r] = ld4(vhat + j);
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int l = 4 * (tid + kThreads * r);
@@ -529,7 +561,7 @@ __global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (j >= ge.d) return;
     const float x = xrow[j];
-    out[j] = (composite(x, (uint32_t)j, ge.idx_bits) >= w->tc) ? 0.f : x;
+    out[j] = was_kept(kept_test(w->tc, ge.idx_bits), mag_key(x), (uint32_t)j) ? 0.f : x;
 }
 
 // The kept (index, value) pairs of one worker, in no particular order: candidates with
