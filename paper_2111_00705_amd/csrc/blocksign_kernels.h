@@ -34,6 +34,8 @@ struct BsTable {
     const int32_t *block_piece0; // [n_blocks+1] first piece of a block
     int32_t n_blocks;
     int32_t n_pieces;
+    int32_t uniform_tiles;       // >0: every block spans this many whole tiles (the last block may be shorter),
+                                 // so tile t is piece t of block t / uniform_tiles: no table look-ups needed
 };
 
 // Sign bits: per worker, per tile, one 16-bit word per thread of the workgroup.  Bit r*4 + c of
@@ -61,7 +63,8 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
     const int64_t base = (int64_t)t * kTile;
     const float *grow = g + (int64_t)i * d;
     float *xrow = xs + (int64_t)i * ld;
-    const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
+    const bool uni = tb.uniform_tiles > 0;
+    const int p0 = uni ? t : tb.tile_piece0[t], p1 = uni ? t + 1 : tb.tile_piece0[t + 1];
     const float *sp = s_prev + (int64_t)i * tb.n_blocks;
 
     float4 gv[4], xv[4];
@@ -74,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
     float x[4][4];
     uint32_t sign_bits = 0;
     const bool single = (p1 - p0 == 1);
-    const float s_single = (kPending && single) ? sp[tb.piece_blk[p0]] : 0.f;
+    const float s_single = (kPending && single) ? sp[uni ? t / tb.uniform_tiles : tb.piece_blk[p0]] : 0.f;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
@@ -154,7 +157,10 @@ constexpr int kSignBatch = 8;       // workers whose sign words are loaded toget
 
 // kFusedScale: every tile lies inside one block of at most kMaxFusedPieces pieces; the block's
 // scale is formed here from the partial sums (and stored by the tile at the block's start).
-template <bool kFusedScale>
+// kEarlyState: load theta, m, v, vhat at the start (small grids: nothing else would hide that
+// latency); otherwise after the worker loop (large grids: fewer live registers, more workgroups
+// per compute unit).
+template <bool kFusedScale, bool kEarlyState>
 __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int n, BsTable tb,
                                                       const double *__restrict__ partial,
                                                       float *__restrict__ scales,
@@ -167,23 +173,54 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
     const int n_tiles = (int)(ld / kTile);
-    const int p0 = tb.tile_piece0[t], p1 = tb.tile_piece0[t + 1];
-    const bool single = kFusedScale || (p1 - p0 == 1);
-    const int b_single = tb.piece_blk[p0];
 
+    float4 th[4], mm[4], vv[4], vh[4];
+    if (kEarlyState) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t j = base + 4 * (tid + kThreads * r);
+            th[r] = ld4(theta + j);
+            mm[r] = ld4(m + j);
+            vv[r] = ld4(v + j);
+            vh[r] = ld4(vhat + j);
+        }
+    }
     float acc[16];
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
     const uint16_t *srow = signs + (int64_t)t * kThreads + tid;
     const int64_t sstride = (int64_t)n_tiles * kThreads;
 
+    // sign words of the first workers go out before anything waits
+    uint32_t bits[kSignBatch];
+#pragma unroll
+    for (int u = 0; u < kSignBatch; ++u) bits[u] = (u < n) ? srow[u * sstride] : 0u;
+
+    int p0, p1, b_single;
+    if (tb.uniform_tiles > 0) {
+        p0 = t;
+        p1 = t + 1;
+        b_single = t / tb.uniform_tiles;
+    } else {
+        p0 = tb.tile_piece0[t];
+        p1 = tb.tile_piece0[t + 1];
+        b_single = tb.piece_blk[p0];
+    }
+    const bool single = kFusedScale || (p1 - p0 == 1);
+
     if (single) {
         int q0 = 0, q1 = 0;
         double len = 1.0;
         if (kFusedScale) {
-            q0 = tb.block_piece0[b_single];
-            q1 = tb.block_piece0[b_single + 1];
-            len = (double)(tb.offsets[b_single + 1] - tb.offsets[b_single]);
+            if (tb.uniform_tiles > 0) {
+                q0 = b_single * tb.uniform_tiles;
+                q1 = min(q0 + tb.uniform_tiles, n_tiles);
+                len = (double)min((int64_t)tb.uniform_tiles * kTile, d - (int64_t)q0 * kTile);
+            } else {
+                q0 = tb.block_piece0[b_single];
+                q1 = tb.block_piece0[b_single + 1];
+                len = (double)(tb.offsets[b_single + 1] - tb.offsets[b_single]);
+            }
         }
         for (int c0 = 0; c0 < n; c0 += kScaleChunk) {
             const int cn = min(kScaleChunk, n - c0);
@@ -205,9 +242,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             }
             __syncthreads();
             for (int u0 = 0; u0 < cn; u0 += kSignBatch) {
-                uint32_t bits[kSignBatch];
+                if (c0 + u0 > 0) {
 #pragma unroll
-                for (int u = 0; u < kSignBatch; ++u) bits[u] = (u0 + u < cn) ? srow[(c0 + u0 + u) * sstride] : 0u;
+                    for (int u = 0; u < kSignBatch; ++u) bits[u] = (u0 + u < cn) ? srow[(c0 + u0 + u) * sstride] : 0u;
+                }
 #pragma unroll
                 for (int u = 0; u < kSignBatch; ++u) {
                     if (u0 + u < cn) {
@@ -232,22 +270,21 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             }
         }
         for (int i = 0; i < n; ++i) {
-            const uint32_t bits = srow[i * sstride];
+            const uint32_t w = srow[i * sstride];
             const float *sc = scales + (int64_t)i * tb.n_blocks;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(sc[blk[q]], bits, q));
+            for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(sc[blk[q]], w, q));
         }
     }
-    // the state is loaded only now: fewer live registers during the worker loop, and the other
-    // workgroups resident on the compute unit cover this latency
-    float4 th[4], mm[4], vv[4], vh[4];
+    if (!kEarlyState) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
+        for (int r = 0; r < 4; ++r) {
+            const int64_t j = base + 4 * (tid + kThreads * r);
+            th[r] = ld4(theta + j);
+            mm[r] = ld4(m + j);
+            vv[r] = ld4(v + j);
+            vh[r] = ld4(vhat + j);
+        }
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {

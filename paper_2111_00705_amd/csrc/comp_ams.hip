@@ -151,7 +151,7 @@ void free_all(std::vector<void *> &owner)
 }
 
 // Builds the device block table from host offsets[0..nb] (already validated).
-int build_block_table(comp_ams *h, const std::vector<int64_t> &off)
+int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t uniform_len)
 {
     const int nb = (int)off.size() - 1;
     const int64_t n_tiles = h->ld / kTile;
@@ -206,6 +206,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off)
     h->tb.block_piece0 = d_bp;
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
+    h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
     {
         bool ok = true;
         for (int64_t t = 0; t < n_tiles && ok; ++t) ok = (tile_piece0[t + 1] - tile_piece0[t] == 1);
@@ -257,12 +258,18 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
             bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
         });
     launch_timed(h, P_BS_UPDATE, st, [&] {
-        if (h->fused_scale)
-            bs_update<true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,
-                                                        h->theta, h->m, h->v, h->vhat, h->params);
-        else
-            bs_update<false><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,
-                                                         h->theta, h->m, h->v, h->vhat, h->params);
+        // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
+        // workgroups per compute unit
+        const bool early = grid.x < 2048;
+#define CAMS_BS_UPDATE(F, E)                                                                                  \
+    bs_update<F, E><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs, h->theta, \
+                                                 h->m, h->v, h->vhat, h->params)
+        if (h->fused_scale) {
+            if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
+        } else {
+            if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
+        }
+#undef CAMS_BS_UPDATE
     });
     h->pending = true;
     return COMP_AMS_OK;
@@ -386,7 +393,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         for (int64_t s = 0; s < d; s += B) off.push_back(s);
         off.push_back(d);
         if ((rc = dev_alloc_t(h, h->allocs, &h->signs, ld / 16 * (size_t)n))) return bail(rc);
-        if ((rc = build_block_table(h, off))) return bail(rc);
+        if ((rc = build_block_table(h, off, B))) return bail(rc);
     } else {
         h->k = k_or_block;
         TkGeom &ge = h->ge;
@@ -458,7 +465,7 @@ int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_bl
     }
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     std::vector<int64_t> off(offsets_host, offsets_host + n_blocks + 1);
-    return build_block_table(h, off);
+    return build_block_table(h, off, 0);
 }
 
 int comp_ams_set_theta(comp_ams_t *h, const float *theta, int on_device)
