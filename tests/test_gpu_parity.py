@@ -285,3 +285,63 @@ def test_cfg2_3_4_scaled(idx, d, n):
     s = w.scales()
     run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name, offsets=w.block_offsets())
     gpu.destroy()
+
+
+# ------------------------------------------------------------------------------- rarely taken Top-k paths
+
+def test_topk_threshold_jumps_and_drops_between_steps():
+    """The candidate guess is carried from step to step; a gradient scale that jumps up (threshold far
+    above the guess: coarse-bin path) or collapses (threshold below the guess: candidates are listed
+    again) must not change the result."""
+    announce("topk threshold jumps")
+    n, d, k = 4, 150_001, 1500
+    rng = np.random.default_rng(123)
+    base_scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    factors = [1.0, 1.0, 300.0, 300.0, 1e-4, 1e-4, 1.0, 1.003, 0.997, 20.0, 1.0, 1.0]
+    gpu, ora = make_pair(d, n, P.TOPK, k, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+
+    def grads(t):
+        g = np.random.default_rng([123, t]).standard_normal((n, d)).astype(f32) * base_scale
+        return (g * f32(factors[t])).astype(f32)
+
+    run_steps(gpu, ora, grads, steps=len(factors), tag="jumps")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("n,d,k", [(40, 30_011, 300), (70, 9_000, 17), (2, 1_300_003, 13_000), (1, 2_500_000, 999)])
+def test_topk_many_workers_and_many_lists(n, d, k):
+    """n > 32 walks several worker groups in tk_final; few workers with a long model give more than
+    1024 candidate lists per worker in tk_resolve."""
+    announce(f"topk n={n} d={d} k={k}")
+    rng = np.random.default_rng(n * 7 + 1)
+    scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    gpu, ora = make_pair(d, n, P.TOPK, k, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    run_steps(gpu, ora, lambda t: (np.random.default_rng([n, d, t]).standard_normal((n, d)) * scale).astype(f32),
+              steps=4, tag=f"n={n}")
+    gpu.destroy()
+
+
+def test_topk_heavy_ties_need_deep_digits_and_big_tiles():
+    """Few distinct magnitudes: the threshold magnitude is shared by thousands of coordinates, so the
+    index digits of the radix select decide, and a tile holds more candidates than one staging chunk."""
+    announce("topk heavy ties")
+    n, d, k = 3, 200_003, 50_000
+    rng = np.random.default_rng(99)
+    vals = np.array([0.125, 0.25, -0.25, 0.5, -0.5, 1.0], f32)
+    gpu, ora = make_pair(d, n, P.TOPK, k)
+    run_steps(gpu, ora, lambda t: vals[np.random.default_rng([99, t]).integers(0, vals.size, (n, d))],
+              steps=3, tag="ties")
+    gpu.destroy()
+
+
+def test_blocksign_many_workers():
+    announce("blocksign n=70")
+    n, d = 70, 20_001
+    rng = np.random.default_rng(70)
+    scale = np.exp(rng.uniform(-6, -1, d)).astype(f32)
+    for B, offsets in ((4096, None), (8192, None), (d, np.array([0, 5, 4096, 4100, 12_288, d], np.int64))):
+        gpu, ora = make_pair(d, n, P.BLOCKSIGN, B, offsets=offsets)
+        off = offsets if offsets is not None else np.minimum(np.arange(0, d + B, B), d)[: (d + B - 1) // B + 1]
+        run_steps(gpu, ora, lambda t: (np.random.default_rng([70, t]).laplace(0, 1, (n, d)) * scale).astype(f32),
+                  steps=3, tag=f"n=70 B={B}", offsets=off)
+        gpu.destroy()
