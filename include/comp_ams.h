@@ -141,6 +141,15 @@ int comp_ams_profile(comp_ams_t *h, int enable);
 int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches);
 
 /*
+ * TOPK handles: how the last step found worker i's threshold, as 8 host words - the fine-bin
+ * guess prepared for the next step, the slack (fine bins) behind it, whether the last step's guess
+ * was too high (candidates listed twice), the number of magnitude bits left open by the histogram
+ * stage, the magnitude prefix, the rank inside it, whether a whole bin was kept, and the fine bin
+ * (top 17 magnitude bits) of the threshold.  For diagnosis and tuning; not needed to use the library.
+ */
+int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_host);
+
+/*
  * Measurement aid, no handle needed: a plain 16-bytes-per-lane copy of `count` floats
  * (a positive multiple of 4, both pointers 16-byte aligned, device memory) dst <- src, enqueued on
  * hip_stream.  Benchmarks use it to calibrate HBM traffic counters and as the copy ceiling.

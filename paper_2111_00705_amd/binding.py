@@ -24,7 +24,7 @@ EXPORTS = [
     "comp_ams_set_eps_mode", "comp_ams_step", "comp_ams_get_theta", "comp_ams_get_m", "comp_ams_get_v",
     "comp_ams_get_vhat", "comp_ams_get_error", "comp_ams_get_selected", "comp_ams_get_scales",
     "comp_ams_n_blocks", "comp_ams_set_state", "comp_ams_sync", "comp_ams_last_error", "comp_ams_profile",
-    "comp_ams_profile_read", "comp_ams_probe_copy",
+    "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
 ]
 
 
@@ -70,6 +70,7 @@ def lib():
         L.comp_ams_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                             C.POINTER(C.c_int64)]
         L.comp_ams_probe_copy.argtypes = [fp, fp, C.c_int64, vp]
+        L.comp_ams_get_selection_info.argtypes = [vp, C.c_int32, u32p]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
         _lib = L
@@ -184,6 +185,12 @@ class CompAms:
         self._check(lib().comp_ams_get_selected(self._h, worker, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
                                                 val.ctypes.data))
         return idx, val
+
+    def get_selection_info(self, worker):
+        out = np.zeros(8, dtype=np.uint32)
+        self._check(lib().comp_ams_get_selection_info(self._h, worker, out.ctypes.data_as(C.POINTER(C.c_uint32))))
+        keys = ("next_guess", "slack", "relisted", "open_bits", "prefix", "rank", "whole_bin", "threshold_fine_bin")
+        return dict(zip(keys, (int(v) for v in out)))
 
     def n_blocks(self):
         return lib().comp_ams_n_blocks(self._h)

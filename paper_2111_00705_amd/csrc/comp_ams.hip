@@ -54,16 +54,17 @@ struct comp_ams {
     // Top-k
     TkGeom ge{};
     TkWorker *ws = nullptr;
-    uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the running step
+    uint2 *cand = nullptr;                     // [n][64 regions][slice_tiles * 4096] candidate (index, value bits)
+    uint32_t *cursor = nullptr;                // [n][64] entries in each region (zero between steps)
+    uint2 *tile_dir = nullptr;                 // [n][n_tiles] {offset in its region, count} of a tile's candidates
+    uint16_t *oct_rows = nullptr;              // [n][n_tiles][256] per-tile histograms of the magnitude exponent
+    uint16_t *below_rows = nullptr;            // [n][n_tiles][16] per-tile counts of the coarse bins below the guess
+    uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
-    uint2 *cand = nullptr;                     // [n][wgs][4][list_cap] candidate (index, value bits)
-    uint2 *cand_dir = nullptr;                 // [n][n_tiles][4] (offset, count) of a tile's candidates in its list
-    uint32_t *list_len = nullptr;              // [n][wgs][4]
-    uint64_t *dense = nullptr;                 // [n][wgs][4][list_cap] comp of the candidates in the threshold bin
-    uint32_t *dense_len = nullptr;             // [n][wgs][4]
+    uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
+    uint2 *dense_dir = nullptr;                // [n][64 * parts * 4] {start, count} of each wavefront's piece
     uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
-
 
     // optional per-kernel timing with HIP events on the step's stream
     bool prof_on = false;
@@ -72,10 +73,10 @@ struct comp_ams {
 
 namespace {
 
-enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_PICK, P_TK_COMPACT, P_TK_RESOLVE, P_TK_FINAL,
-                P_SLOTS };
-const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_pick",
-                                         "tk_compact", "tk_resolve", "tk_final"};
+enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
+                P_TK_RESOLVE, P_TK_FINAL, P_SLOTS };
+const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
+                                         "tk_relist", "tk_compact", "tk_resolve", "tk_final"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -278,20 +279,28 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
 int step_topk(comp_ams *h, const float *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
+    const dim3 tiles(ge.n_tiles, h->n), shared(kSlices * ge.parts, h->n);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->hist1, h->histf, h->cand,
-                                                         h->cand_dir, h->list_len);
+        tk_pass1<<<tiles, kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows,
+                                             h->below_rows);
     });
-    launch_timed(h, P_TK_PICK, st, [&] { tk_pick<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf); });
+    launch_timed(h, P_TK_HIST, st, [&] {
+        tk_hist<<<shared, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cursor, h->hist1, h->histf);
+    });
+    launch_timed(h, P_TK_PICK, st, [&] {
+        tk_pick<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf, h->cursor, h->oct_rows, h->below_rows);
+    });
+    launch_timed(h, P_TK_RELIST, st, [&] {
+        tk_relist<<<dim3(ge.relist_wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->cand, h->cursor, h->tile_dir);
+    });
     launch_timed(h, P_TK_COMPACT, st, [&] {
-        tk_compact<<<dim3(ge.wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->cand, h->cand_dir, h->list_len,
-                                                           h->dense, h->dense_len);
+        tk_compact<<<shared, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cursor, h->dense, h->dense_dir);
     });
     launch_timed(h, P_TK_RESOLVE, st, [&] {
-        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf, h->dense, h->dense_len);
+        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->dense, h->dense_dir, h->cursor);
     });
     launch_timed(h, P_TK_FINAL, st, [&] {
-        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cand_dir, h->theta, h->m, h->v, h->vhat,
+        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
     });
     return COMP_AMS_OK;
@@ -305,9 +314,11 @@ int reset_topk_workers(comp_ams *h)
         std::memset(&w, 0, sizeof w);
         w.guess = kNoGuess;
         w.slack = kFirstSlack;
+        w.last_fine = kNoGuess;
         w.tc = kNoThreshold;
     }
     HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
+    HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * kSlices * sizeof(uint32_t)));
     return COMP_AMS_OK;
 }
 
@@ -405,18 +416,23 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int ib = 1;
         while (((int64_t)1 << ib) < d) ++ib;
         ge.idx_bits = ib;
-        ge.wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
-        ge.list_cap = (ge.n_tiles + ge.wgs - 1) / ge.wgs * kSub;
+        ge.slice_tiles = (ge.n_tiles + kSlices - 1) / kSlices;
+        // tk_hist / tk_compact: about 4096 candidates per workgroup when 1.5 k of them are listed
+        ge.parts = (int32_t)std::min<int64_t>(kMaxParts,
+                                              std::max<int64_t>(1, (3 * k_or_block / 2 + kSlices * 4096 - 1) / (kSlices * 4096)));
+        ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
-        const size_t lists = (size_t)n * ge.wgs * 4;
+        const size_t region_entries = (size_t)n * kSlices * (size_t)ge.slice_tiles * kTile;
         if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * kSlices)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->oct_rows, segs * kOctaves)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->below_rows, segs * kBelow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand, lists * ge.list_cap, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand_dir, segs * 4)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->list_len, lists)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->dense, lists * ge.list_cap, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->dense_len, lists)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * kSlices * ge.parts * 4)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
@@ -555,8 +571,8 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
     const TkGeom &ge = h->ge;
     const size_t k = (size_t)ge.k;
     HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
-    tk_gather_selected<<<ge.wgs, kThreads, 0, h->stream>>>(ge, worker, h->ws, h->cand, h->list_len, h->sel_count,
-                                                          h->sel_out_idx, h->sel_out_val);
+    tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, worker, h->ws, h->cand, h->tile_dir, h->sel_count,
+                                                              h->sel_out_idx, h->sel_out_val);
     HIP_TRY(h, hipGetLastError());
     uint32_t total = 0;
     std::vector<uint32_t> idx(k);
@@ -645,6 +661,27 @@ int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double
     if (name) *name = kProfNames[slot];
     if (total_ms) *total_ms = total;
     if (launches) *launches = (int64_t)h->prof[slot].size();
+    return COMP_AMS_OK;
+}
+
+int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_host)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selection_info needs a TOPK handle");
+    if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
+    if (!out_host) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    TkWorker w;
+    HIP_TRY(h, hipMemcpyAsync(&w, h->ws + worker, sizeof w, hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    out_host[0] = w.guess;
+    out_host[1] = w.slack;
+    out_host[2] = w.relisted;
+    out_host[3] = w.pshift;
+    out_host[4] = w.prefix;
+    out_host[5] = w.rank;
+    out_host[6] = w.whole;
+    out_host[7] = (uint32_t)(w.tc >> (h->ge.idx_bits + kFineShift));
     return COMP_AMS_OK;
 }
 

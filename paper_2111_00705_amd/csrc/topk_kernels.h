@@ -5,34 +5,39 @@
 //     comp = (magnitude_bits << IB) | (2^IB - 1 - index),     magnitude_bits = bits(x) & 0x7fffffff,
 // IB = number of bits of d-1.  comp is unique per element and its descending order is
 // "larger magnitude first, lower index first among equals", so Top-k is { comp >= Tc } where Tc is
-// the k-th largest comp.  Tc is found digit by digit from the top (11 bits, then 12 at a time).
+// the k-th largest comp.  Tc is found digit by digit from the top.
 //
 // The error memory is kept in deferred form: after a step the library stores x_i = g_i + e_i and
 // the worker's threshold Tc_i; e_i[j] = (comp(x_i[j], j) >= Tc_i) ? +0 : x_i[j] is formed on the fly
 // when the next step (or a getter) reads x_i, so kept coordinates are never zeroed by scattered
-// writes and one step needs a single pass over g and the stored vector.  Five launches per step,
+// writes and one step needs a single pass over g and the stored vector.  Seven launches per step,
 // ordered only by kernel boundaries (no fences, no waiting inside a kernel):
 //
-//   tk_pass1    streams g and the stored x once and writes the new x; counts every element in a
-//               per-worker histogram of its top 11 magnitude bits ("coarse" bin, an eighth of an
-//               octave) and, for the two coarse bins around the worker's guess, of its top 17 bits
-//               ("fine" bin, 0.2 % wide); lists "candidates" - elements whose fine bin is >= the
-//               guess, which is carried over from the previous step's threshold minus a little
-//               slack - as (index, value) pairs in one dense list per (worker, workgroup,
-//               wavefront), with a directory entry (offset, count) per (worker, tile, wavefront)
-//   tk_pick     one workgroup per worker: the coarse (and if covered, fine) bin of the k-th
-//               largest, from the histograms
-//   tk_compact  if the guess was above that bin (always on the first step) the worker's
-//               candidates are listed again from the stored x; candidates in that bin are
-//               copied, as comp values, to one dense list per worker
-//   tk_resolve  one workgroup per worker: the remaining digits of Tc over the dense list, and
-//               the guess for the next step
+//   tk_pass1    one workgroup per (tile, worker): streams g and the stored x once and writes the new
+//               x; lists "candidates" - elements whose fine magnitude bin (top 17 bits, 0.2 % wide)
+//               is >= the worker's guess, which is the previous step's threshold minus a little
+//               slack - as (index, value) pairs, staged in LDS and appended densely to one of 64
+//               regions of the worker (one atomic add per tile); writes the tile's histogram of
+//               magnitude exponents (only read if the guess turns out too high).
+//               A workgroup per tile (instead of a loop over tiles) matters: on this chip a wave
+//               that loops must wait for its stores before it can use its next loads.
+//   tk_hist     histograms of the candidates: coarse bins (top 11 bits) and the fine bins of the
+//               two coarse bins around the guess
+//   tk_pick     one workgroup per worker: coarse and fine bin of the k-th largest; with fewer than
+//               k candidates (always on the first step) the guess was too high: the coarse bin is
+//               then taken from per-tile counts of the bins just below the guess, or the octave
+//               from the exponent histograms
+//   tk_relist   only for such workers: candidates are listed again from the stored x
+//   tk_compact  candidates in the threshold bin are copied, as comp values, to dense pieces (one
+//               per wavefront)
+//   tk_resolve  one workgroup per worker: the remaining digits of Tc over those pieces, and the
+//               guess for the next step
 //   tk_final    per tile, all workers: candidates with comp >= Tc are the kept coordinates; their
 //               values are added into an LDS copy of the tile in ascending worker order; then
 //               gbar = acc / n and the AMSGrad update of the tile's theta, m, v, vhat
 //
-// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
-// (a few per cent of the elements, 8 B each, written once and read twice).
+// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written + 1/8 B of exponent
+// histogram, plus the candidates (about 1.2 k per worker, 8 B each, written once, read three times).
 #pragma once
 #include "device_utils.h"
 
@@ -43,25 +48,32 @@ constexpr int kShift1 = 20;
 constexpr int kFineShift = 14;    // fine bin: top 17 bits; 64 fine bins per coarse bin
 constexpr int kFinePerCoarse = 1 << (kShift1 - kFineShift);
 constexpr int kFineWindow = 2 * kFinePerCoarse;   // fine bins counted: the guess's coarse bin and the next
-constexpr int kDigitBits = 12;    // digits of the dense-list search
+constexpr int kOctShift = 23;     // exponent ("octave") bin: top 8 bits
+constexpr int kOctaves = 256;
+constexpr int kBelow = 16;        // coarse bins counted per tile at and just below the guess (two octaves)
+constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
-constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles
+constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
+constexpr int kSlices = 64;       // candidate regions per worker
+constexpr int kMaxParts = 8;      // pieces a region is cut into for tk_hist / tk_compact
 constexpr int kResolveThreads = 1024;
 constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothing (before the first step)
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
 
+static_assert(kSlices == kWave, "tk_pick and tk_resolve handle one region cursor per lane");
+
 struct TkWorker {
     uint64_t tc;            // threshold composite of the last finished step (pending selection)
     uint32_t guess;         // pass 1 lists elements with fine bin >= guess
     uint32_t slack;         // fine bins kept between the threshold and the next guess
-    // leading digits of the running step's Tc, written by tk_compact, read by tk_resolve
+    // leading digits of the running step's Tc, written by tk_pick, read by the kernels after it
     uint32_t prefix;        // magnitude bits above pshift
-    uint32_t pshift;        // kShift1 (coarse bin known) or kFineShift (fine bin known)
+    uint32_t pshift;        // kFineShift, kShift1 or kOctShift: how many low magnitude bits are still open
     uint32_t rank;          // 1-based rank (from the top) of the k-th largest among elements with this prefix
     uint32_t whole;         // all elements with this prefix are kept: Tc needs no further digit
-    uint32_t relisted;      // the guess was above the threshold: candidates were listed again
-    uint32_t pad;
+    uint32_t relisted;      // the guess was above the threshold: candidates are listed again
+    uint32_t last_fine;     // fine bin of the previous threshold (to see how far thresholds move)
 };
 
 struct TkGeom {
@@ -69,14 +81,33 @@ struct TkGeom {
     int32_t n, n_tiles;
     int32_t idx_bits;       // IB
     uint32_t k;
-    int32_t wgs;            // workgroups per worker in tk_pass1 / tk_compact; tile t belongs to t % wgs
-    int32_t list_cap;       // capacity of one candidate list = ceil(n_tiles / wgs) * kSub
+    int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / kSlices)
+    int32_t parts;          // tk_hist / tk_compact: workgroups per region
+    int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
 };
 
 __device__ __forceinline__ uint64_t composite(float x, uint32_t j, int idx_bits)
 {
     const uint64_t inv = ((1ull << idx_bits) - 1ull) - (uint64_t)j;
     return ((uint64_t)mag_key(x) << idx_bits) | inv;
+}
+
+// Pending selection of the previous step in 32-bit form: the coordinate j with magnitude bits
+// `key` was kept iff  key > tkey  or  (key == tkey and j <= tj).
+struct KeptTest {
+    uint32_t tkey, tj;
+};
+__device__ __forceinline__ KeptTest kept_test(uint64_t tc, int idx_bits)
+{
+    const uint32_t imask = (uint32_t)((1ull << idx_bits) - 1ull);
+    KeptTest k;
+    k.tkey = (uint32_t)(tc >> idx_bits);            // kNoThreshold gives 0xffffffff: above every key
+    k.tj = imask - ((uint32_t)tc & imask);
+    return k;
+}
+__device__ __forceinline__ bool was_kept(const KeptTest &k, uint32_t key, uint32_t j)
+{
+    return key >= k.tkey && (key > k.tkey || j <= k.tj);
 }
 
 // Finds, in a histogram held in LDS (`bins` counters, a multiple of the workgroup size), the bin
@@ -129,30 +160,85 @@ __device__ __forceinline__ uint32_t wave_append(bool flag, uint32_t &count)
     return slot;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Pending selection of the previous step in 32-bit form: the coordinate j with magnitude bits
-// `key` was kept iff  key > tkey  or  (key == tkey and j <= tj).
-struct KeptTest {
-    uint32_t tkey, tj;
-};
-__device__ __forceinline__ KeptTest kept_test(uint64_t tc, int idx_bits)
+// Exclusive prefix sum of one value per thread over a 256-thread workgroup, left in pre[0..256]
+// (pre[256] = total).  `part` holds 4 LDS counters.  Three barriers.
+__device__ __forceinline__ void block_prefix(uint32_t v, uint32_t *pre, uint32_t *part)
 {
-    const uint32_t imask = (uint32_t)((1ull << idx_bits) - 1ull);
-    KeptTest k;
-    k.tkey = (uint32_t)(tc >> idx_bits);            // kNoThreshold gives 0xffffffff: above every key
-    k.tj = imask - ((uint32_t)tc & imask);
-    return k;
-}
-__device__ __forceinline__ bool was_kept(const KeptTest &k, uint32_t key, uint32_t j)
-{
-    return key >= k.tkey && (key > k.tkey || j <= k.tj);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();                       // readers of an earlier pre/part are done
+    if (lane == kWave - 1) part[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += part[w];
+    pre[threadIdx.x] = before + incl - v;
+    if (threadIdx.x == kThreads - 1) pre[kThreads] = before + incl;
+    __syncthreads();
 }
 
-// One tile of tk_pass1 for one workgroup.  kFull: the whole tile lies below d.
+// Largest l in [0, count) with pre[l] <= q, for a non-decreasing pre[0..count] with pre[count] > q.
+__device__ __forceinline__ int owner_of(const uint32_t *pre, int count, uint32_t q)
+{
+    int lo = 0, hi = count;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (pre[mid] <= q) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Where candidates live.  Each worker owns kSlices regions of the candidate array; tile t appends to
+// region t mod kSlices, so workgroups that run at the same time (neighbouring tiles) use different
+// cursors.  A tile takes its space with one atomic add on the region's cursor and records
+// {offset, count} in the tile directory.  A region can hold every coordinate of its tiles.  The order
+// of the tiles inside a region depends on timing; nothing downstream depends on it (comp values are
+// unique, the selection is a set).  Appending densely matters: per-tile fixed slots made the same
+// kernel 10 - 20 % slower (8-byte pieces scattered over gigabytes).
+__device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int slice)
+{
+    return ((int64_t)worker * kSlices + slice) * ge.slice_tiles * kTile;
+}
+
+// First half of moving a tile's staged candidates (count per wavefront, in LDS) to its region: the
+// thread `allocator` takes the space.  sh: 5 LDS words.  Ends before the barrier so that the caller
+// can put other work between the atomic and its use.
+__device__ __forceinline__ void flush_begin(uint32_t count, uint32_t *sh, int allocator, const TkGeom &ge, int i,
+                                            int t, uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir)
+{
+    const int tid = threadIdx.x;
+    if ((tid & 63) == 0) sh[tid >> 6] = count;
+    __syncthreads();
+    if (tid == allocator) {
+        const uint32_t total = sh[0] + sh[1] + sh[2] + sh[3];
+        const uint32_t at = total ? atomicAdd(cursor + i * kSlices + (t & (kSlices - 1)), total) : 0u;
+        sh[4] = at;
+        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint2(at, total);
+    }
+}
+__device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, const uint32_t *sh, const TkGeom &ge,
+                                          int i, int t, uint2 *__restrict__ cand)
+{
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t off = sh[4];
+    for (int w = 0; w < wave; ++w) off += sh[w];
+    uint2 *dst = cand + region_base(ge, i, t & (kSlices - 1)) + off;
+    // the wavefront reads back its own LDS writes: no barrier needed for those
+    for (uint32_t q = lane; q < count; q += kWave) dst[q] = stage[q];
+}
+
+// One tile of one worker.  kFull: the whole tile lies below d.  Candidates are staged in LDS (one
+// list per wavefront, which owns kSub coordinates of the tile, so it cannot overflow).
 template <bool kFull>
-__device__ __forceinline__ void pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow, uint32_t base,
-                                           uint32_t d, const KeptTest &kt, uint32_t guess, uint32_t wbase,
-                                           uint32_t *lh, uint32_t *lf, uint2 *__restrict__ list, uint32_t &count)
+__device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow,
+                                               uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
+                                               uint32_t *lh, uint2 *stage)
 {
     const int tid = threadIdx.x;
     float4 gv[4], xv[4];
@@ -162,6 +248,7 @@ __device__ __forceinline__ void pass1_tile(const float *__restrict__ grow, float
         gv[r] = load_grad4(grow, j, d);
         xv[r] = ld4(xrow + j);
     }
+    uint32_t count = 0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (tid + kThreads * r);
@@ -178,197 +265,360 @@ __device__ __forceinline__ void pass1_tile(const float *__restrict__ grow, float
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bool valid = kFull || j + c < d;
-            const uint32_t fine = mag_key(x[c]) >> kFineShift;
-            if (valid) {
-                atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
-                if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
-            }
-            const bool hit = valid && fine >= guess;
-            const uint32_t slot = wave_append(hit, count);   // < list_cap: kSub coordinates per tile
-            if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
+            const uint32_t key = mag_key(x[c]);
+            if (valid) atomicAdd(&lh[key >> kShift1], 1u);
+            const bool hit = valid && (key >> kFineShift) >= guess;
+            const uint32_t slot = wave_append(hit, count);
+            if (hit) stage[slot] = make_uint2(j + c, __float_as_uint(x[c]));
         }
     }
+    return count;
 }
 
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
-                                                     const TkWorker *__restrict__ ws,
-                                                     uint32_t *__restrict__ hist1,
-                                                     uint32_t *__restrict__ histf, uint2 *__restrict__ cand,
-                                                     uint2 *__restrict__ cand_dir,
-                                                     uint32_t *__restrict__ list_len)
+                                                     const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
+                                                     uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir,
+                                                     uint16_t *__restrict__ oct_rows,
+                                                     uint16_t *__restrict__ below_rows)
+{
+    __shared__ uint32_t lh[kBins1];   // this tile's coarse-bin histogram
+    __shared__ uint2 stage[4][kSub];
+    __shared__ uint32_t sh[5];
+    const int t = blockIdx.x;
+    const int i = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const uint32_t guess = ws[i].guess;
+    const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
+    const uint32_t d = (uint32_t)ge.d;
+    const uint32_t base = (uint32_t)t * kTile;
+    const int64_t tile_id = (int64_t)i * ge.n_tiles + t;
+    for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
+    __syncthreads();
+    uint32_t count;
+    if (base + kTile <= d)
+        count = pass1_tile<true>(g + (int64_t)i * ge.d, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
+    else
+        count = pass1_tile<false>(g + (int64_t)i * ge.d, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
+    flush_begin(count, sh, 3 * kWave, ge, i, t, cursor, tile_dir);   // barrier inside: lh is complete
+    // what is kept of the histogram (a tile holds 4096 < 65536 elements): the 256 exponent bins, and
+    // the kBelow coarse bins that end with the guess's own - enough to place a threshold that fell
+    // up to two octaves below the guess; both are read only when the guess turns out too high.
+    // One store instruction each, while another wavefront waits for the cursor.
+    if (wave == 0) {
+        // lane l: exponent bins 4l .. 4l+3, each the sum of 8 coarse bins
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = 0;
+#pragma unroll
+            for (int q = 0; q < kBins1 / kOctaves; ++q) o[e] += lh[(4 * tid + e) * (kBins1 / kOctaves) + q];
+        }
+        reinterpret_cast<uint2 *>(oct_rows + tile_id * kOctaves)[tid] =
+            make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+    } else if (wave == 1) {
+        const int l = tid & 63;
+        if (l < kBelow) {
+            const int b = (int)(min(guess, kNoGuess - 1) >> (kShift1 - kFineShift)) - (kBelow - 1) + l;
+            below_rows[tile_id * kBelow + l] = (uint16_t)(b >= 0 ? lh[b] : 0u);
+        }
+    }
+    flush_end(stage[wave], count, sh, ge, i, t, cand);
+}
+
+// ---------------------------------------------------------------------------------------------
+// How the workgroups of tk_hist and tk_compact share a worker's candidates: blockIdx.x = slice *
+// parts + part, and a part is a contiguous piece of the slice's region.
+struct Piece {
+    int slice;
+    uint32_t q0, q1;     // entries [q0, q1) of the region
+};
+__device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__restrict__ cursor, int worker)
+{
+    Piece p;
+    p.slice = blockIdx.x / ge.parts;
+    const uint32_t part = blockIdx.x % ge.parts;
+    const uint32_t count = cursor[worker * kSlices + p.slice];
+    const uint32_t chunk = (count + ge.parts - 1) / ge.parts;
+    p.q0 = min(part * chunk, count);
+    p.q1 = min(p.q0 + chunk, count);
+    return p;
+}
+
+// Histograms of the candidates of a worker: coarse bins, and the fine bins of the two coarse bins
+// that start with the guess's.  Loads are issued four at a time.
+__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                    const uint2 *__restrict__ cand,
+                                                    const uint32_t *__restrict__ cursor,
+                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf)
 {
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t lf[kFineWindow];
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
+    const Piece pc = piece_of(ge, cursor, i);
+    if (pc.q0 >= pc.q1) return;
     const uint32_t guess = ws[i].guess;
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
-    const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
-    const uint32_t d = (uint32_t)ge.d;
-    const float *grow = g + (int64_t)i * ge.d;
-    float *xrow = xs + (int64_t)i * ge.ld;
-    const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
-    uint2 *list = cand + list_id * ge.list_cap;
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
     if (tid < kFineWindow) lf[tid] = 0;
     __syncthreads();
-
-    uint32_t count = 0;   // length of this wavefront's list so far
-    for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
-        const uint32_t base = (uint32_t)t * kTile;
-        const uint32_t first = count;
-        if (base + kTile <= d)
-            pass1_tile<true>(grow, xrow, base, d, kt, guess, wbase, lh, lf, list, count);
-        else
-            pass1_tile<false>(grow, xrow, base, d, kt, guess, wbase, lh, lf, list, count);
-        if ((tid & 63) == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, count - first);
+    const uint2 *src = cand + region_base(ge, i, pc.slice);
+    for (uint32_t qb = pc.q0; qb < pc.q1; qb += 4 * kThreads) {
+        uint32_t y[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = qb + u * kThreads + tid;
+            y[u] = q < pc.q1 ? src[q].y : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (qb + u * kThreads + tid < pc.q1) {
+                const uint32_t fine = (y[u] & 0x7fffffffu) >> kFineShift;
+                atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
+                if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
+            }
+        }
     }
-    if ((tid & 63) == 0) list_len[list_id] = count;
     __syncthreads();
-    uint32_t *row = hist1 + (int64_t)i * kBins1;
     for (int b = tid; b < kBins1; b += kThreads) {
         const uint32_t c = lh[b];
-        if (c) atomicAdd(row + b, c);
+        if (c) atomicAdd(hist1 + (int64_t)i * kBins1 + b, c);
     }
     if (tid < kFineWindow && lf[tid]) atomicAdd(histf + (int64_t)i * kFineWindow + tid, lf[tid]);
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup per worker: the leading digits of Tc from the histograms of tk_pass1.
+// One workgroup per worker: the leading digits of Tc.  Consumes (and clears) the candidate
+// histograms.
 __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
-                                                    const uint32_t *__restrict__ hist1,
-                                                    const uint32_t *__restrict__ histf)
+                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
+                                                    uint32_t *__restrict__ cursor,
+                                                    const uint16_t *__restrict__ oct_rows,
+                                                    const uint16_t *__restrict__ below_rows)
 {
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
     __shared__ uint32_t res[4];
     __shared__ uint32_t fres[3];
+    __shared__ uint32_t total_sh;
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t *row = hist1 + (int64_t)i * kBins1;
-    for (int b = tid; b < kBins1; b += kThreads) lh[b] = row[b];
-    __syncthreads();
-    find_rank_bin(lh, part, res, kBins1, ge.k);
-    if (!res[3]) return;                            // cannot happen: the histogram holds d >= k elements
     const uint32_t guess = ws[i].guess;
-    uint32_t prefix = res[0];                       // coarse bin of the k-th largest
-    uint32_t pshift = kShift1;
-    uint32_t rank = ge.k - res[1];
-    uint32_t count = res[2];
-    const uint32_t wb = guess >> (kShift1 - kFineShift);      // first coarse bin of the fine window
-    if (prefix - wb < 2u) {
-        // the fine histogram covers this coarse bin: pick the fine bin as well (one wavefront)
-        if (wave == 0) {
-            const uint32_t c = histf[(int64_t)i * kFineWindow + (prefix - wb) * kFinePerCoarse + lane];
-            uint32_t suffix = c;                    // elements of this coarse bin in fine bins >= lane
+    if (wave == 0) {
+        // number of candidates of this worker = sum of its region cursors (kSlices = one per lane)
+        uint32_t c = cursor[i * kSlices + lane];
 #pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                const uint32_t t = __shfl_down(suffix, off, kWave);
-                if (lane + off < kWave) suffix += t;
+        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
+        if (lane == 0) total_sh = c;
+    }
+    __syncthreads();
+    const uint32_t total = total_sh;
+    uint32_t *row = hist1 + (int64_t)i * kBins1;
+    uint32_t *frow = histf + (int64_t)i * kFineWindow;
+    uint32_t prefix, pshift, rank, count;
+    bool relist;
+
+    if (total >= ge.k) {
+        // every element at or above the guess is listed and there are at least k of them: the k-th
+        // largest is a candidate and the candidate histograms locate it
+        for (int b = tid; b < kBins1; b += kThreads) lh[b] = row[b];
+        __syncthreads();
+        find_rank_bin(lh, part, res, kBins1, ge.k);
+        prefix = res[0];                            // coarse bin of the k-th largest
+        pshift = kShift1;
+        rank = ge.k - res[1];
+        count = res[2];
+        const uint32_t wb = guess >> (kShift1 - kFineShift);      // first coarse bin of the fine window
+        if (prefix - wb < 2u) {
+            // the fine histogram covers this coarse bin: pick the fine bin as well (one wavefront)
+            if (wave == 0) {
+                const uint32_t c = frow[(prefix - wb) * kFinePerCoarse + lane];
+                uint32_t suffix = c;                // candidates of this coarse bin in fine bins >= lane
+#pragma unroll
+                for (int off = 1; off < kWave; off <<= 1) {
+                    const uint32_t t = __shfl_down(suffix, off, kWave);
+                    if (lane + off < kWave) suffix += t;
+                }
+                const uint64_t reach = __ballot(suffix >= rank);  // lane 0 reaches: suffix(0) = count >= rank
+                const int top = reach ? 63 - __builtin_clzll(reach) : 0;
+                if (lane == top) {
+                    fres[0] = (uint32_t)lane;
+                    fres[1] = suffix - c;
+                    fres[2] = c;
+                }
             }
-            const uint64_t reach = __ballot(suffix >= rank);  // lane 0 always reaches: suffix(0) = count >= rank
-            const int top = reach ? 63 - __builtin_clzll(reach) : 0;
-            if (lane == top) {
-                fres[0] = (uint32_t)lane;
-                fres[1] = suffix - c;
-                fres[2] = c;
+            __syncthreads();
+            prefix = (prefix << (kShift1 - kFineShift)) | fres[0];
+            pshift = kFineShift;
+            rank -= fres[1];
+            count = fres[2];
+        }
+        relist = false;
+    } else {
+        // the guess was too high.  Elements above the guess's coarse bin wb are all candidates, so
+        // their counts are exact; for wb and the kBelow-1 coarse bins under it the tiles kept full
+        // counts.  If the k-th largest lies there its coarse bin is found; otherwise (a threshold
+        // that fell by more than two octaves) the exponent histograms give its octave.
+        const uint32_t wb = min(guess, kNoGuess - 1) >> (kShift1 - kFineShift);
+        uint32_t above = 0;                                   // candidates in coarse bins > wb
+        for (uint32_t b = wb + 1 + tid; b < (uint32_t)kBins1; b += kThreads) above += row[b];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) above += __shfl_xor(above, off, kWave);
+        if (lane == 0) part[wave] = above;
+        __syncthreads();
+        above = part[0] + part[1] + part[2] + part[3];
+        // thread b < kBelow: full count of coarse bin wb - b over all tiles
+        uint32_t c = 0;
+        if (tid < kBelow && guess < kNoGuess) {
+            const uint16_t *brow = below_rows + (int64_t)i * ge.n_tiles * kBelow + (kBelow - 1 - tid);
+            for (int t = 0; t < ge.n_tiles; ++t) c += brow[(int64_t)t * kBelow];
+        }
+        lh[tid] = c;
+        __syncthreads();
+        if (tid == 0) {
+            res[3] = 0;
+            uint32_t cum = above;
+            for (int b = 0; b < kBelow && (int)wb - b >= 0 && guess < kNoGuess; ++b) {
+                if (cum + lh[b] >= ge.k) {
+                    res[0] = wb - b;
+                    res[1] = cum;
+                    res[2] = lh[b];
+                    res[3] = 1;
+                    break;
+                }
+                cum += lh[b];
             }
         }
         __syncthreads();
-        prefix = (prefix << (kShift1 - kFineShift)) | fres[0];
-        pshift = kFineShift;
-        rank -= fres[1];
-        count = fres[2];
+        if (res[3]) {
+            prefix = res[0];
+            pshift = kShift1;
+        } else {
+            __syncthreads();
+            const uint16_t *orow = oct_rows + (int64_t)i * ge.n_tiles * kOctaves + tid;
+            uint32_t o = 0;
+            for (int t = 0; t < ge.n_tiles; ++t) o += orow[(int64_t)t * kOctaves];
+            lh[tid] = o;
+            __syncthreads();
+            find_rank_bin(lh, part, res, kOctaves, ge.k);   // the histograms hold all d >= k elements
+            prefix = res[0];
+            pshift = kOctShift;
+        }
+        rank = ge.k - res[1];
+        count = res[2];
+        relist = true;
     }
+    __syncthreads();   // every thread has read the histograms before they are cleared
     if (tid == 0) {
         ws[i].prefix = prefix;
         ws[i].pshift = pshift;
         ws[i].rank = rank;
         ws[i].whole = (count == rank) ? 1u : 0u;
-        // candidates are complete iff every element at or above the prefix was listed
-        ws[i].relisted = (((uint64_t)guess << kFineShift) > ((uint64_t)prefix << pshift)) ? 1u : 0u;
+        ws[i].relisted = relist ? 1u : 0u;
+    }
+    if (relist && tid < kSlices) cursor[i * kSlices + tid] = 0;   // tk_relist fills the regions anew
+    for (int b = tid; b < kBins1; b += kThreads) row[b] = 0;
+    if (tid < kFineWindow) frow[tid] = 0;
+}
+
+// Only for workers whose guess was too high: lists the elements of the stored x whose magnitude
+// bits above pshift are >= the prefix, into the (emptied) regions of the worker.  A small grid whose
+// workgroups loop over tiles: in the usual case every workgroup returns at once, and a small grid
+// does that fast.
+__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ xs, TkGeom ge,
+                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
+                                                      uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir)
+{
+    __shared__ uint2 stage[4][kSub];
+    __shared__ uint32_t sh[5];
+    const int i = blockIdx.y;
+    if (!ws[i].relisted) return;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    const uint32_t d = (uint32_t)ge.d;
+    const float *xrow = xs + (int64_t)i * ge.ld;
+    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
+        const uint32_t base = (uint32_t)t * kTile;
+        uint32_t count = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t j = base + 4 * (tid + kThreads * r);
+            const float4 xv = ld4(xrow + j);
+            const float x[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool hit = j + c < d && (mag_key(x[c]) >> pshift) >= prefix;
+                const uint32_t slot = wave_append(hit, count);
+                if (hit) stage[wave][slot] = make_uint2(j + c, __float_as_uint(x[c]));
+            }
+        }
+        flush_begin(count, sh, 0, ge, i, t, cursor, tile_dir);
+        flush_end(stage[wave], count, sh, ge, i, t, cand);
+        __syncthreads();   // sh and stage are reused by the next tile
     }
 }
 
-// Lists the worker's candidates again if the guess was too high, and copies the candidates that
-// carry the prefix, as comp values, to the "dense" region of their list (same shape as the
-// candidate lists; typically a handful per list).  No atomics: tk_resolve walks the regions.
-__global__ __launch_bounds__(kThreads) void tk_compact(const float *__restrict__ xs, TkGeom ge,
-                                                       const TkWorker *__restrict__ ws,
-                                                       uint2 *__restrict__ cand, uint2 *__restrict__ cand_dir,
-                                                       uint32_t *__restrict__ list_len,
-                                                       uint64_t *__restrict__ dense, uint32_t *__restrict__ dense_len)
+// Copies the candidates that carry the prefix, as comp values, to the dense storage.  Each wavefront
+// takes a quarter of the workgroup's piece and writes its hits from the start of that quarter
+// onwards (as many slots as it reads, so it cannot overflow), and records {start, count} relative to
+// the worker's first region; no atomics, tk_resolve walks the records.
+__global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                       const uint2 *__restrict__ cand,
+                                                       const uint32_t *__restrict__ cursor,
+                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir)
 {
     const int i = blockIdx.y;
+    if (ws[i].whole) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
-    const bool whole = ws[i].whole != 0, relist = ws[i].relisted != 0;
-    if (whole && !relist) return;
-
-    const int64_t list_id = ((int64_t)i * ge.wgs + blockIdx.x) * 4 + wave;
-    uint2 *list = cand + list_id * ge.list_cap;
-    uint64_t *out = dense + list_id * ge.list_cap;
-    uint32_t kept = 0;   // entries of this wavefront's dense region
-    if (relist) {
-        // list this workgroup's candidates again, now from the prefix up; those with the prefix
-        // itself go to the dense region on the way
-        const float *xrow = xs + (int64_t)i * ge.ld;
-        uint32_t filled = 0;
-        for (int t = blockIdx.x; t < ge.n_tiles; t += ge.wgs) {
-            const int64_t base = (int64_t)t * kTile;
-            const uint32_t first = filled;
+    const Piece pc = piece_of(ge, cursor, i);
+    const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
+    const uint32_t w0 = min(pc.q0 + wave * quarter, pc.q1), w1 = min(w0 + quarter, pc.q1);
+    const int64_t rbase = region_base(ge, i, pc.slice);
+    const uint2 *src = cand + rbase;
+    uint64_t *out = dense + rbase + w0;
+    uint32_t count = 0;
+    for (uint32_t qb = w0; qb < w1; qb += 4 * kWave) {
+        uint2 c[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t j = (uint32_t)base + 4 * (tid + kThreads * r);
-                const float4 xv = ld4(xrow + j);
-                const float x[4] = {xv.x, xv.y, xv.z, xv.w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t top = mag_key(x[c]) >> pshift;
-                    const bool hit = j + c < ge.d && top >= prefix;
-                    const uint32_t slot = wave_append(hit, filled);
-                    if (hit) list[slot] = make_uint2(j + c, __float_as_uint(x[c]));
-                    const bool eq = hit && top == prefix && !whole;
-                    const uint32_t at = wave_append(eq, kept);
-                    if (eq) out[at] = composite(x[c], j + c, ge.idx_bits);
-                }
-            }
-            if (lane == 0) cand_dir[((int64_t)i * ge.n_tiles + t) * 4 + wave] = make_uint2(first, filled - first);
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = qb + u * kWave + lane;
+            c[u] = q < w1 ? src[q] : make_uint2(0u, 0u);
         }
-        if (lane == 0) list_len[list_id] = filled;
-    } else {
-        const uint32_t len = list_len[list_id];
-        for (uint32_t q0 = 0; q0 < len; q0 += kWave) {
-            const uint32_t q = q0 + lane;
-            bool eq = false;
-            uint2 c = make_uint2(0u, 0u);
-            if (q < len) {
-                c = list[q];
-                eq = ((c.y & 0x7fffffffu) >> pshift) == prefix;
-            }
-            const uint32_t at = wave_append(eq, kept);
-            if (eq) out[at] = composite(__uint_as_float(c.y), c.x, ge.idx_bits);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool hit = qb + u * kWave + lane < w1 && ((c[u].y & 0x7fffffffu) >> pshift) == prefix;
+            const uint32_t slot = wave_append(hit, count);
+            if (hit) out[slot] = composite(__uint_as_float(c[u].y), c[u].x, ge.idx_bits);
         }
     }
-    if (lane == 0) dense_len[list_id] = kept;
+    if (lane == 0) {
+        const int64_t rec = ((int64_t)i * gridDim.x + blockIdx.x) * 4 + wave;
+        dense_dir[rec] = make_uint2((uint32_t)(rbase - region_base(ge, i, 0)) + w0, count);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup of 1024 threads per worker: the digits of Tc below the prefix, over the worker's
-// dense regions.  Also hands the next step its guess and clears the histogram rows.
+// One workgroup of 1024 threads per worker: the digits of Tc below the prefix, over the pieces
+// tk_compact filled (kSlices * parts * 4 <= 2 * kResolveThreads of them).  Hands the next step its
+// guess and empties the worker's region cursors for it.
+constexpr int kMaxPieces = kSlices * kMaxParts * 4;
+static_assert(kMaxPieces <= 2 * kResolveThreads, "two pieces per thread in the prefix sum");
+
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
-                                                              uint32_t *__restrict__ hist1,
-                                                              uint32_t *__restrict__ histf,
                                                               const uint64_t *__restrict__ dense,
-                                                              const uint32_t *__restrict__ dense_len)
+                                                              const uint2 *__restrict__ dense_dir,
+                                                              uint32_t *__restrict__ cursor)
 {
     __shared__ uint32_t lh[kBins2];
-    __shared__ uint32_t pre[kResolveThreads + 1];   // exclusive prefix of the region lengths of a chunk of lists
     __shared__ uint32_t part[kResolveThreads / kWave];
     __shared__ uint32_t res[4];
+    __shared__ uint32_t rpre[kMaxPieces + 1];
+    __shared__ uint32_t rstart[kMaxPieces];
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -378,40 +628,46 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     int s_hi = (int)w.pshift + ge.idx_bits;
     bool done = w.whole != 0;
     uint64_t tc = prefix << s_hi;
-    const int n_lists = ge.wgs * 4;
-    const int64_t list0 = (int64_t)i * n_lists;
+    const int pieces = kSlices * ge.parts * 4;
+    const uint64_t *wdense = dense + region_base(ge, i, 0);
+    uint32_t cnt = 0;
+    if (!done) {
+        // exclusive prefix sum of the piece counts, two pieces per thread
+        const uint2 a = (2 * tid < pieces) ? dense_dir[(int64_t)i * pieces + 2 * tid] : make_uint2(0u, 0u);
+        const uint2 b = (2 * tid + 1 < pieces) ? dense_dir[(int64_t)i * pieces + 2 * tid + 1] : make_uint2(0u, 0u);
+        uint32_t incl = a.y + b.y;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
+        if (lane == kWave - 1) part[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int q = 0; q < wave; ++q) before += part[q];
+        const uint32_t excl = before + incl - (a.y + b.y);
+        if (2 * tid < pieces) {
+            rpre[2 * tid] = excl;
+            rstart[2 * tid] = a.x;
+        }
+        if (2 * tid + 1 < pieces) {
+            rpre[2 * tid + 1] = excl + a.y;
+            rstart[2 * tid + 1] = b.x;
+        }
+        if (tid == kResolveThreads - 1) rpre[pieces] = before + incl;   // threads past the pieces add 0
+        __syncthreads();
+        cnt = rpre[pieces];
+    }
 
     while (!done) {
         const int s_lo = max(s_hi - kDigitBits, 0);
         const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
         for (int b = tid; b < kBins2; b += kResolveThreads) lh[b] = 0;
-        for (int c0 = 0; c0 < n_lists; c0 += kResolveThreads) {
-            // lengths of up to 1024 regions -> exclusive prefix sums in LDS
-            const uint32_t len = (c0 + tid < n_lists) ? dense_len[list0 + c0 + tid] : 0u;
-            uint32_t incl = len;
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off, kWave);
-                if (lane >= off) incl += up;
-            }
-            __syncthreads();                       // previous chunk's readers of pre/part are done
-            if (lane == kWave - 1) part[wave] = incl;
-            __syncthreads();
-            uint32_t before = 0;
-            for (int v = 0; v < wave; ++v) before += part[v];
-            pre[tid] = before + incl - len;
-            if (tid == kResolveThreads - 1) pre[kResolveThreads] = before + incl;
-            __syncthreads();
-            const uint32_t total = pre[kResolveThreads];
-            for (uint32_t q = tid; q < total; q += kResolveThreads) {
-                int lo = 0, hi = kResolveThreads;              // largest l with pre[l] <= q
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (pre[mid] <= q) lo = mid; else hi = mid;
-                }
-                const uint64_t comp = dense[(list0 + c0 + lo) * ge.list_cap + (q - pre[lo])];
-                if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
-            }
+        __syncthreads();
+        for (uint32_t q = tid; q < cnt; q += kResolveThreads) {
+            const int r = owner_of(rpre, pieces, q);
+            const uint64_t comp = wdense[rstart[r] + (q - rpre[r])];
+            if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
         }
         __syncthreads();
         find_rank_bin(lh, part, res, kBins2, rank);
@@ -425,26 +681,30 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         s_hi = s_lo;
         __syncthreads();
     }
+    if (tid < kSlices) cursor[i * kSlices + tid] = 0;          // tk_compact was their last reader
     if (tid == 0) {
         ws[i].tc = tc;
-        // next step lists from a few fine bins below this threshold; more after a miss
-        const uint32_t slack = w.relisted ? min(w.slack * 2u, kMaxSlack) : max(w.slack - 1u, kMinSlack);
+        // The next step lists from a few fine bins below this threshold: at least twice the distance
+        // the threshold just fell (a rising threshold needs no slack), never less than kMinSlack,
+        // shrinking by one bin per quiet step, doubled after a miss.
         const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
+        const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
+        uint32_t slack = w.relisted ? w.slack * 2u : w.slack - 1u;
+        slack = max(slack, 2u * fell + 2u);
+        slack = min(max(slack, kMinSlack), kMaxSlack);
         ws[i].slack = slack;
+        ws[i].last_fine = fine;
         ws[i].guess = fine > slack ? fine - slack : 0u;
     }
-    uint32_t *row = hist1 + (int64_t)i * kBins1;
-    for (int b = tid; b < kBins1; b += kResolveThreads) row[b] = 0;
-    if (tid < kFineWindow) histf[(int64_t)i * kFineWindow + tid] = 0;
 }
 
 // ---------------------------------------------------------------------------------------------
 constexpr int kFinChunk = 1024;   // candidates staged in LDS at a time
-constexpr int kFinGroup = 32;     // workers whose candidate lists are flattened together
+constexpr int kFinGroup = 64;     // workers whose candidate lists are flattened together
 
 __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
                                                      const uint2 *__restrict__ cand,
-                                                     const uint2 *__restrict__ cand_dir,
+                                                     const uint2 *__restrict__ tile_dir,
                                                      float *__restrict__ theta, float *__restrict__ m,
                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
@@ -452,71 +712,57 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
     __shared__ float lst_v[kFinChunk];
     __shared__ uint16_t lst_l[kFinChunk];
     __shared__ uint16_t lst_w[kFinChunk];   // worker within the group, bit 15 = kept
-    __shared__ uint32_t pre[kFinGroup * 4 + 1];
-    __shared__ uint32_t first[kFinGroup * 4];   // offset of each sub-list inside its wavefront's list
+    __shared__ uint32_t pre[kFinGroup + 1];
+    __shared__ uint32_t at[kFinGroup];      // offset of the worker's list for this tile inside its region
     __shared__ uint64_t tcs[kFinGroup];
 
     const int t = blockIdx.x;
+    const int slice = t & (kSlices - 1);
     const int64_t base = (int64_t)t * kTile;
     const int tid = threadIdx.x;
-
     for (int l = tid; l < kTile; l += kThreads) acc[l] = 0.f;
 
     for (int w0 = 0; w0 < ge.n; w0 += kFinGroup) {
         const int nw = min(kFinGroup, ge.n - w0);
-        const int ns = nw * 4;                      // (worker, wavefront) sub-lists in this group
-        __syncthreads();
-        if (tid < ns) {
-            const uint2 dir = cand_dir[((int64_t)(w0 + (tid >> 2)) * ge.n_tiles + t) * 4 + (tid & 3)];
-            first[tid] = dir.x;
-            pre[tid + 1] = dir.y;
-        }
-        if (tid < nw) tcs[tid] = ws[w0 + tid].tc;
         __syncthreads();
         if (tid < kWave) {
-            // inclusive prefix sum of the (at most 128) sub-list lengths, two per lane
-            const uint32_t a = (2 * tid < ns) ? pre[2 * tid + 1] : 0u;
-            const uint32_t b = (2 * tid + 1 < ns) ? pre[2 * tid + 2] : 0u;
-            uint32_t incl = a + b;
+            // inclusive prefix sum of the (at most 64) list lengths, one per lane
+            const uint2 rec = tid < nw ? tile_dir[(int64_t)(w0 + tid) * ge.n_tiles + t] : make_uint2(0u, 0u);
+            uint32_t incl = rec.y;
 #pragma unroll
             for (int off = 1; off < kWave; off <<= 1) {
                 const uint32_t up = __shfl_up(incl, off, kWave);
                 if (tid >= off) incl += up;
             }
-            const uint32_t excl = incl - (a + b);
-            if (2 * tid < ns) pre[2 * tid + 1] = excl + a;
-            if (2 * tid + 1 < ns) pre[2 * tid + 2] = excl + a + b;
+            if (tid < nw) {
+                pre[tid + 1] = incl;
+                at[tid] = rec.x;
+                tcs[tid] = ws[w0 + tid].tc;
+            }
             if (tid == 0) pre[0] = 0;
         }
         __syncthreads();
-        const uint32_t total = pre[ns];
+        const uint32_t total = pre[nw];
 
         for (uint32_t c0 = 0; c0 < total; c0 += kFinChunk) {
             const uint32_t cn = min((uint32_t)kFinChunk, total - c0);
             // 1. read the candidates of this chunk, decide which are kept
             for (uint32_t q = tid; q < cn; q += kThreads) {
                 const uint32_t gq = c0 + q;
-                int lo = 0, hi = ns;                       // largest s with pre[s] <= gq
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (pre[mid] <= gq) lo = mid; else hi = mid;
-                }
-                const int w = lo >> 2;
-                const int64_t list_id = ((int64_t)(w0 + w) * ge.wgs + (t % ge.wgs)) * 4 + (lo & 3);
-                const uint2 c = cand[list_id * ge.list_cap + first[lo] + (gq - pre[lo])];
-                const uint32_t l = c.x - (uint32_t)base;
+                const int w = owner_of(pre, nw, gq);
+                const uint2 c = cand[region_base(ge, w0 + w, slice) + at[w] + (gq - pre[w])];
                 const float x = __uint_as_float(c.y);
                 const bool keep = composite(x, c.x, ge.idx_bits) >= tcs[w];
-                lst_l[q] = (uint16_t)l;
+                lst_l[q] = (uint16_t)(c.x - (uint32_t)base);
                 lst_v[q] = x;
                 lst_w[q] = (uint16_t)(w | (keep ? 0x8000 : 0));
             }
             __syncthreads();
             // 2. add kept values into the tile, one worker at a time, ascending
-            int sa = 0, sb = ns - 1;
+            int sa = 0, sb = nw - 1;
             while (pre[sa + 1] <= c0) ++sa;
             while (pre[sb] >= c0 + cn) --sb;
-            for (int w = sa >> 2; w <= (sb >> 2); ++w) {
+            for (int w = sa; w <= sb; ++w) {
                 const uint16_t tag = (uint16_t)(w | 0x8000);
                 for (uint32_t q = tid; q < cn; q += kThreads)
                     if (lst_w[q] == tag) acc[lst_l[q]] = fadd(acc[lst_l[q]], lst_v[q]);
@@ -565,26 +811,37 @@ __global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__
 }
 
 // The kept (index, value) pairs of one worker, in no particular order: candidates with
-// comp >= Tc.  *count must be 0 on entry and ends at k.  One wavefront per candidate list.
+// comp >= Tc.  *count must be 0 on entry and ends at k.  One workgroup per tile; one atomic add
+// per wavefront that found something.
 __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int worker,
                                                                const TkWorker *__restrict__ ws,
                                                                const uint2 *__restrict__ cand,
-                                                               const uint32_t *__restrict__ list_len,
+                                                               const uint2 *__restrict__ tile_dir,
                                                                uint32_t *__restrict__ count,
                                                                uint32_t *__restrict__ out_idx,
                                                                float *__restrict__ out_val)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x;
     const uint64_t tc = ws[worker].tc;
-    const int64_t list_id = ((int64_t)worker * ge.wgs + blockIdx.x) * 4 + wave;
-    const uint32_t len = list_len[list_id];
-    for (uint32_t q = lane; q < len; q += kWave) {
-        const uint2 c = cand[list_id * ge.list_cap + q];
-        if (composite(__uint_as_float(c.y), c.x, ge.idx_bits) >= tc) {
-            const uint32_t slot = atomicAdd(count, 1u);
-            if (slot < ge.k) {
-                out_idx[slot] = c.x;
-                out_val[slot] = __uint_as_float(c.y);
+    const uint2 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
+    const uint2 *src = cand + region_base(ge, worker, t & (kSlices - 1)) + rec.x;
+    for (uint32_t q0 = 0; q0 < rec.y; q0 += kThreads) {      // uniform over the workgroup
+        const uint32_t q = q0 + threadIdx.x;
+        uint2 c = make_uint2(0u, 0u);
+        bool keep = false;
+        if (q < rec.y) {
+            c = src[q];
+            keep = composite(__uint_as_float(c.y), c.x, ge.idx_bits) >= tc;
+        }
+        const uint64_t km = __ballot(keep);
+        if (km) {
+            uint32_t at = 0;
+            if (lane == 0) at = atomicAdd(count, (uint32_t)__popcll(km));
+            at = __shfl(at, 0, kWave) + __popcll(km & ((1ull << lane) - 1ull));
+            if (keep && at < ge.k) {
+                out_idx[at] = c.x;
+                out_val[at] = __uint_as_float(c.y);
             }
         }
     }
