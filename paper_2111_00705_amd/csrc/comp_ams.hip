@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -56,7 +57,7 @@ struct comp_ams {
     TkWorker *ws = nullptr;
     uint2 *cand = nullptr;                     // [n][64 regions][slice_tiles * 4096] candidate (index, value bits)
     uint32_t *cursor = nullptr;                // [n][64] entries in each region (zero between steps)
-    uint2 *tile_dir = nullptr;                 // [n][n_tiles] {offset in its region, count} of a tile's candidates
+    uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in its region, counts per wavefront, total}
     uint16_t *oct_rows = nullptr;              // [n][n_tiles][256] per-tile histograms of the magnitude exponent
     uint16_t *below_rows = nullptr;            // [n][n_tiles][16] per-tile counts of the coarse bins below the guess
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates

@@ -196,7 +196,8 @@ __device__ __forceinline__ int owner_of(const uint32_t *pre, int count, uint32_t
 // Where candidates live.  Each worker owns kSlices regions of the candidate array; tile t appends to
 // region t mod kSlices, so workgroups that run at the same time (neighbouring tiles) use different
 // cursors.  A tile takes its space with one atomic add on the region's cursor and records
-// {offset, count} in the tile directory.  A region can hold every coordinate of its tiles.  The order
+// {offset, counts of its four wavefronts, total} in the tile directory; inside the tile's space the
+// candidates stand wavefront by wavefront.  A region can hold every coordinate of its tiles.  The order
 // of the tiles inside a region depends on timing; nothing downstream depends on it (comp values are
 // unique, the selection is a set).  Appending densely matters: per-tile fixed slots made the same
 // kernel 10 - 20 % slower (8-byte pieces scattered over gigabytes).
@@ -209,7 +210,7 @@ __device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int
 // thread `allocator` takes the space.  sh: 5 LDS words.  Ends before the barrier so that the caller
 // can put other work between the atomic and its use.
 __device__ __forceinline__ void flush_begin(uint32_t count, uint32_t *sh, int allocator, const TkGeom &ge, int i,
-                                            int t, uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir)
+                                            int t, uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     const int tid = threadIdx.x;
     if ((tid & 63) == 0) sh[tid >> 6] = count;
@@ -218,7 +219,8 @@ __device__ __forceinline__ void flush_begin(uint32_t count, uint32_t *sh, int al
         const uint32_t total = sh[0] + sh[1] + sh[2] + sh[3];
         const uint32_t at = total ? atomicAdd(cursor + i * kSlices + (t & (kSlices - 1)), total) : 0u;
         sh[4] = at;
-        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint2(at, total);
+        // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
+        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), total);
     }
 }
 __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, const uint32_t *sh, const TkGeom &ge,
@@ -277,7 +279,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
 
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
-                                                     uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir,
+                                                     uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
                                                      uint16_t *__restrict__ oct_rows,
                                                      uint16_t *__restrict__ below_rows)
 {
@@ -529,7 +531,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
 // does that fast.
 __global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ xs, TkGeom ge,
                                                       const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
-                                                      uint32_t *__restrict__ cursor, uint2 *__restrict__ tile_dir)
+                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     __shared__ uint2 stage[4][kSub];
     __shared__ uint32_t sh[5];
@@ -607,7 +609,26 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
 // tk_compact filled (kSlices * parts * 4 <= 2 * kResolveThreads of them).  Hands the next step its
 // guess and empties the worker's region cursors for it.
 constexpr int kMaxPieces = kSlices * kMaxParts * 4;
+constexpr int kFew = 256;         // at most this many elements are ranked directly instead of by further digits
 static_assert(kMaxPieces <= 2 * kResolveThreads, "two pieces per thread in the prefix sum");
+
+// Elements qb + u * kResolveThreads + tid (u < kScanUnroll) of the worker's dense set, found through
+// the prefix sums of the piece counts; the loads are independent, so they are all in flight at once.
+constexpr int kScanUnroll = 4;
+__device__ __forceinline__ void scan_load(uint64_t (&comp)[kScanUnroll], const uint64_t *__restrict__ wdense,
+                                          const uint32_t *rpre, const uint32_t *rstart, int pieces, uint32_t qb,
+                                          uint32_t cnt)
+{
+#pragma unroll
+    for (int u = 0; u < kScanUnroll; ++u) {
+        const uint32_t q = qb + u * kResolveThreads + threadIdx.x;
+        comp[u] = 0;
+        if (q < cnt) {
+            const int r = owner_of(rpre, pieces, q);
+            comp[u] = wdense[rstart[r] + (q - rpre[r])];
+        }
+    }
+}
 
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
                                                               const uint64_t *__restrict__ dense,
@@ -619,6 +640,9 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     __shared__ uint32_t res[4];
     __shared__ uint32_t rpre[kMaxPieces + 1];
     __shared__ uint32_t rstart[kMaxPieces];
+    __shared__ uint64_t few[kFew];
+    __shared__ uint32_t n_few;
+    __shared__ uint64_t tc_sh;
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -664,21 +688,47 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
         for (int b = tid; b < kBins2; b += kResolveThreads) lh[b] = 0;
         __syncthreads();
-        for (uint32_t q = tid; q < cnt; q += kResolveThreads) {
-            const int r = owner_of(rpre, pieces, q);
-            const uint64_t comp = wdense[rstart[r] + (q - rpre[r])];
-            if ((comp >> s_hi) == prefix) atomicAdd(&lh[(uint32_t)(comp >> s_lo) & mask], 1u);
+        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+            uint64_t comp[kScanUnroll];
+            scan_load(comp, wdense, rpre, rstart, pieces, qb, cnt);
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u)
+                if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                    atomicAdd(&lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
         }
         __syncthreads();
         find_rank_bin(lh, part, res, kBins2, rank);
         if (!res[3]) break;                                    // cannot happen: rank <= matching elements
         prefix = (prefix << (s_hi - s_lo)) | res[0];
         rank -= res[1];
-        if (s_lo == 0 || res[2] == rank) {                     // last digit, or all under this prefix are kept
+        const uint32_t left = res[2];                          // elements that carry the new prefix
+        s_hi = s_lo;
+        if (s_lo == 0 || left == rank) {                       // last digit, or all under this prefix are kept
             done = true;
             tc = prefix << s_lo;
+        } else if (left <= (uint32_t)kFew) {
+            // few elements left: fetch them and rank them against each other (comp values are unique)
+            if (tid == 0) n_few = 0;
+            __syncthreads();
+            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+                uint64_t comp[kScanUnroll];
+                scan_load(comp, wdense, rpre, rstart, pieces, qb, cnt);
+#pragma unroll
+                for (int u = 0; u < kScanUnroll; ++u)
+                    if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                        few[atomicAdd(&n_few, 1u)] = comp[u];
+            }
+            __syncthreads();
+            if ((uint32_t)tid < left) {
+                const uint64_t mine = few[tid];
+                uint32_t greater = 0;
+                for (uint32_t u = 0; u < left; ++u) greater += few[u] > mine ? 1u : 0u;
+                if (greater + 1 == rank) tc_sh = mine;
+            }
+            __syncthreads();
+            done = true;
+            tc = tc_sh;
         }
-        s_hi = s_lo;
         __syncthreads();
     }
     if (tid < kSlices) cursor[i * kSlices + tid] = 0;          // tk_compact was their last reader
@@ -699,81 +749,87 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
 }
 
 // ---------------------------------------------------------------------------------------------
-constexpr int kFinChunk = 1024;   // candidates staged in LDS at a time
-constexpr int kFinGroup = 64;     // workers whose candidate lists are flattened together
+// A coordinate of a tile belongs to one wavefront - the same one in tk_pass1, tk_relist and here -
+// and a tile's candidates are stored wavefront by wavefront, so each wavefront can sum the kept values
+// of its own coordinates without looking at the others: no workgroup barrier, and the ascending worker
+// order of the sum is just the order of its own instructions (within one worker the coordinates of
+// the kept candidates are distinct).
+constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in flight at a time
 
 __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
                                                      const uint2 *__restrict__ cand,
-                                                     const uint2 *__restrict__ tile_dir,
+                                                     const uint4 *__restrict__ tile_dir,
                                                      float *__restrict__ theta, float *__restrict__ m,
                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
     __shared__ float acc[kTile];
-    __shared__ float lst_v[kFinChunk];
-    __shared__ uint16_t lst_l[kFinChunk];
-    __shared__ uint16_t lst_w[kFinChunk];   // worker within the group, bit 15 = kept
-    __shared__ uint32_t pre[kFinGroup + 1];
-    __shared__ uint32_t at[kFinGroup];      // offset of the worker's list for this tile inside its region
-    __shared__ uint64_t tcs[kFinGroup];
-
     const int t = blockIdx.x;
     const int slice = t & (kSlices - 1);
     const int64_t base = (int64_t)t * kTile;
     const int tid = threadIdx.x;
-    for (int l = tid; l < kTile; l += kThreads) acc[l] = 0.f;
+    const int lane = tid & 63, wave = tid >> 6;
 
-    for (int w0 = 0; w0 < ge.n; w0 += kFinGroup) {
-        const int nw = min(kFinGroup, ge.n - w0);
-        __syncthreads();
-        if (tid < kWave) {
-            // inclusive prefix sum of the (at most 64) list lengths, one per lane
-            const uint2 rec = tid < nw ? tile_dir[(int64_t)(w0 + tid) * ge.n_tiles + t] : make_uint2(0u, 0u);
-            uint32_t incl = rec.y;
 #pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off, kWave);
-                if (tid >= off) incl += up;
-            }
-            if (tid < nw) {
-                pre[tid + 1] = incl;
-                at[tid] = rec.x;
-                tcs[tid] = ws[w0 + tid].tc;
-            }
-            if (tid == 0) pre[0] = 0;
-        }
-        __syncthreads();
-        const uint32_t total = pre[nw];
+    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 
-        for (uint32_t c0 = 0; c0 < total; c0 += kFinChunk) {
-            const uint32_t cn = min((uint32_t)kFinChunk, total - c0);
-            // 1. read the candidates of this chunk, decide which are kept
-            for (uint32_t q = tid; q < cn; q += kThreads) {
-                const uint32_t gq = c0 + q;
-                const int w = owner_of(pre, nw, gq);
-                const uint2 c = cand[region_base(ge, w0 + w, slice) + at[w] + (gq - pre[w])];
-                const float x = __uint_as_float(c.y);
-                const bool keep = composite(x, c.x, ge.idx_bits) >= tcs[w];
-                lst_l[q] = (uint16_t)(c.x - (uint32_t)base);
-                lst_v[q] = x;
-                lst_w[q] = (uint16_t)(w | (keep ? 0x8000 : 0));
+    for (int w0 = 0; w0 < ge.n; w0 += kWave) {
+        const int nw = min(kWave, ge.n - w0);
+        // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
+        uint32_t my_start = 0, my_count = 0;
+        uint64_t my_tc = kNoThreshold;
+        if (lane < nw) {
+            const uint4 rec = tile_dir[(int64_t)(w0 + lane) * ge.n_tiles + t];
+            const uint32_t c[4] = {rec.y & 0xffffu, rec.y >> 16, rec.z & 0xffffu, rec.z >> 16};
+            my_start = rec.x;
+            for (int q = 0; q < wave; ++q) my_start += c[q];
+            my_count = c[wave];
+            my_tc = ws[w0 + lane].tc;
+        }
+        for (int wb = 0; wb < nw; wb += kFinBatch) {
+            uint2 e[kFinBatch];
+            uint32_t cnt[kFinBatch];
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);           // clamped: the copies past nw are not used
+                cnt[u] = wb + u < nw ? (uint32_t)__shfl((int)my_count, w, kWave) : 0u;
+                const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
+                e[u] = make_uint2(0u, 0u);
+                if ((uint32_t)lane < cnt[u]) e[u] = cand[region_base(ge, w0 + w, slice) + start + lane];
             }
-            __syncthreads();
-            // 2. add kept values into the tile, one worker at a time, ascending
-            int sa = 0, sb = nw - 1;
-            while (pre[sa + 1] <= c0) ++sa;
-            while (pre[sb] >= c0 + cn) --sb;
-            for (int w = sa; w <= sb; ++w) {
-                const uint16_t tag = (uint16_t)(w | 0x8000);
-                for (uint32_t q = tid; q < cn; q += kThreads)
-                    if (lst_w[q] == tag) acc[lst_l[q]] = fadd(acc[lst_l[q]], lst_v[q]);
-                __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);
+                const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
+                const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
+                const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
+                if ((uint32_t)lane < cnt[u]) {
+                    const float x = __uint_as_float(e[u].y);
+                    if (composite(x, e[u].x, ge.idx_bits) >= tc) {
+                        const uint32_t l = e[u].x - (uint32_t)base;
+                        acc[l] = fadd(acc[l], x);
+                    }
+                }
+                if (cnt[u] > (uint32_t)kWave) {
+                    // more than 64 candidates of this worker in the wavefront's quarter of the tile (rare)
+                    const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
+                    const uint2 *src = cand + region_base(ge, w0 + w, slice) + start;
+                    for (uint32_t q = kWave + lane; q < cnt[u]; q += kWave) {
+                        const uint2 c = src[q];
+                        const float x = __uint_as_float(c.y);
+                        if (composite(x, c.x, ge.idx_bits) >= tc) {
+                            const uint32_t l = c.x - (uint32_t)base;
+                            acc[l] = fadd(acc[l], x);
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // next worker's adds come after these
             }
         }
     }
-    __syncthreads();
 
-    // the state is loaded only now: fewer live registers above, and the other workgroups resident
-    // on the compute unit cover this latency
+    // the state is loaded only now: fewer live registers above (more workgroups per compute unit),
+    // which measured faster than loading it first
     float4 th[4], mm[4], vv[4], vh[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -787,8 +843,9 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
     for (int r = 0; r < 4; ++r) {
         const int l = 4 * (tid + kThreads * r);
         const int64_t j = base + l;
-        const float4 gbar = make_float4(fdiv(acc[l], p.n_workers), fdiv(acc[l + 1], p.n_workers),
-                                        fdiv(acc[l + 2], p.n_workers), fdiv(acc[l + 3], p.n_workers));
+        const float4 a = ld4(acc + l);
+        const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
+                                        fdiv(a.w, p.n_workers));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
         st4(theta + j, th[r]);
         st4(m + j, mm[r]);
@@ -816,7 +873,7 @@ __global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__
 __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int worker,
                                                                const TkWorker *__restrict__ ws,
                                                                const uint2 *__restrict__ cand,
-                                                               const uint2 *__restrict__ tile_dir,
+                                                               const uint4 *__restrict__ tile_dir,
                                                                uint32_t *__restrict__ count,
                                                                uint32_t *__restrict__ out_idx,
                                                                float *__restrict__ out_val)
@@ -824,13 +881,13 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x;
     const uint64_t tc = ws[worker].tc;
-    const uint2 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
+    const uint4 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
     const uint2 *src = cand + region_base(ge, worker, t & (kSlices - 1)) + rec.x;
-    for (uint32_t q0 = 0; q0 < rec.y; q0 += kThreads) {      // uniform over the workgroup
+    for (uint32_t q0 = 0; q0 < rec.w; q0 += kThreads) {      // uniform over the workgroup
         const uint32_t q = q0 + threadIdx.x;
         uint2 c = make_uint2(0u, 0u);
         bool keep = false;
-        if (q < rec.y) {
+        if (q < rec.w) {
             c = src[q];
             keep = composite(__uint_as_float(c.y), c.x, ge.idx_bits) >= tc;
         }

@@ -308,10 +308,12 @@ def test_topk_threshold_jumps_and_drops_between_steps():
     gpu.destroy()
 
 
-@pytest.mark.parametrize("n,d,k", [(40, 30_011, 300), (70, 9_000, 17), (2, 1_300_003, 13_000), (1, 2_500_000, 999)])
+@pytest.mark.parametrize("n,d,k", [(40, 30_011, 300), (70, 9_000, 17), (2, 1_300_003, 13_000), (1, 2_500_000, 999),
+                                   (2, 600_000, 300_000)])
 def test_topk_many_workers_and_many_lists(n, d, k):
-    """n > 32 walks several worker groups in tk_final; few workers with a long model give more than
-    1024 candidate lists per worker in tk_resolve."""
+    """n > 64 walks two worker groups in tk_final; long models fill all 64 candidate regions of a
+    worker with several tiles each; a large k cuts each region into several pieces for the candidate
+    histogram and the compaction, and gives wavefronts more than 64 candidates per tile."""
     announce(f"topk n={n} d={d} k={k}")
     rng = np.random.default_rng(n * 7 + 1)
     scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
