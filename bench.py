@@ -31,12 +31,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
     ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 234.5e6,
     ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.6e6,
-    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2244.8e6,
-    ("cfg2_topk_n16_d11173962", "tk_final"): 390.7e6,
+    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2202.0e6,
+    ("cfg2_topk_n16_d11173962", "tk_final"): 391.8e6,
     ("cfg3_layersign_n32_d25557032", "bs_pass"): 9975.9e6,
     ("cfg3_layersign_n32_d25557032", "bs_update"): 921.8e6,
-    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10644.6e6,
-    ("cfg4_topk_n8_d110000000", "tk_final"): 3614.7e6,
+    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10716.4e6,
+    ("cfg4_topk_n8_d110000000", "tk_final"): 3584.2e6,
 }
 
 

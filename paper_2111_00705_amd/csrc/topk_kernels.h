@@ -471,13 +471,22 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         if (lane == 0) part[wave] = above;
         __syncthreads();
         above = part[0] + part[1] + part[2] + part[3];
-        // thread b < kBelow: full count of coarse bin wb - b over all tiles
+        // full count of coarse bin wb - b over all tiles, for b < kBelow: thread (tid / kBelow,
+        // tid % kBelow) sums every 16th tile, then lh[b] collects the 16 partial sums
         uint32_t c = 0;
-        if (tid < kBelow && guess < kNoGuess) {
-            const uint16_t *brow = below_rows + (int64_t)i * ge.n_tiles * kBelow + (kBelow - 1 - tid);
-            for (int t = 0; t < ge.n_tiles; ++t) c += brow[(int64_t)t * kBelow];
+        if (guess < kNoGuess) {
+            const uint16_t *brow = below_rows + (int64_t)i * ge.n_tiles * kBelow + (kBelow - 1 - tid % kBelow);
+#pragma unroll 4
+            for (int t = tid / kBelow; t < ge.n_tiles; t += kThreads / kBelow) c += brow[(int64_t)t * kBelow];
         }
-        lh[tid] = c;
+        __syncthreads();                       // part[] has been read
+        lh[kBelow + tid] = c;
+        __syncthreads();
+        if (tid < kBelow) {
+            uint32_t sum = 0;
+            for (int q = 0; q < kThreads / kBelow; ++q) sum += lh[kBelow + q * kBelow + tid];
+            lh[tid] = sum;
+        }
         __syncthreads();
         if (tid == 0) {
             res[3] = 0;
@@ -501,7 +510,8 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
             __syncthreads();
             const uint16_t *orow = oct_rows + (int64_t)i * ge.n_tiles * kOctaves + tid;
             uint32_t o = 0;
-            for (int t = 0; t < ge.n_tiles; ++t) o += orow[(int64_t)t * kOctaves];
+#pragma unroll 8
+            for (int t = 0; t < ge.n_tiles; ++t) o += orow[(int64_t)t * kOctaves];   // independent loads
             lh[tid] = o;
             __syncthreads();
             find_rank_bin(lh, part, res, kOctaves, ge.k);   // the histograms hold all d >= k elements
