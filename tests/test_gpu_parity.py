@@ -323,6 +323,44 @@ def test_topk_many_workers_and_many_lists(n, d, k):
     gpu.destroy()
 
 
+def test_topk_selection_info_reports_the_path_taken():
+    """The carried guess must actually be used: with a steady gradient scale the threshold is found
+    among the listed candidates (no second listing) from the second step on, a collapse of the scale
+    forces a second listing in that step only, and the reported threshold bin is the fine bin of the
+    k-th largest magnitude of g + e (taken from the oracle's kept set)."""
+    announce("topk selection info")
+    import torch
+    n, d, k = 3, 90_001, 900
+    rng = np.random.default_rng(321)
+    base_scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    factors = [1.0, 1.0, 1.0, 1.0, 1e-3, 1e-3, 1.0, 1.0]
+    gpu, ora = make_pair(d, n, P.TOPK, k)
+    relisted = []
+    guess = [1 << 17] * n                            # before the first step nothing can be listed
+    for t, f in enumerate(factors):
+        g = (np.random.default_rng([321, t]).standard_normal((n, d)).astype(f32) * base_scale * f32(f)).astype(f32)
+        x = g + ora.error
+        gpu.step(torch.from_numpy(g).cuda())
+        ora.step(g)
+        row = []
+        for i in range(n):
+            info = gpu.get_selection_info(i)
+            listed = int(np.count_nonzero(((bits(x[i]) & 0x7FFFFFFF) >> 14) >= guess[i]))
+            assert info["relisted"] == (1 if listed < k else 0), f"step {t} worker {i}: {listed} listed"
+            guess[i] = info["next_guess"]
+            kth = np.abs(x[i][ora.selected[i]]).min()
+            assert info["threshold_fine_bin"] == int(bits(np.array([kth], f32))[0] >> 14), f"step {t} worker {i}"
+            assert 8 <= info["slack"] <= 512
+            assert info["next_guess"] == max(info["threshold_fine_bin"] - info["slack"], 0)
+            row.append(info["relisted"])
+        relisted.append(row)
+        compare(gpu, ora, x_for_values=x, tag=f"info step {t}")
+    assert relisted[0] == [1] * n                    # nothing is listed before the first threshold exists
+    assert relisted[1:4] == [[0] * n] * 3            # steady: the guess holds
+    assert relisted[6] == [0] * n                    # a rising threshold needs no second listing
+    gpu.destroy()
+
+
 def test_topk_heavy_ties_need_deep_digits_and_big_tiles():
     """Few distinct magnitudes: the threshold magnitude is shared by thousands of coordinates, so the
     index digits of the radix select decide, and a tile holds more candidates than one staging chunk."""
