@@ -17,6 +17,10 @@
  *                         applied per contiguous block with the block's own length
  *   server average      Section 3: gbar = (1/n) sum_i ghat_i
  *   AMSGrad             Section 3: m, v, vhat = max(vhat, v), x -= alpha Vhat^{-1/2} m
+ *   CD-Adam             Section 5, Algorithm 1: Markov compression on the workers
+ *                         (c_i = C(g_i - ghat_i), ghat_i += c_i), on the server
+ *                         (ghat += mean c_i, c = C(ghat - gtilde), gtilde += c),
+ *                         AMSGrad on gtilde
  *
  * Readings where the paper is silent are listed next to the code that takes them.
  * Pins: tests/test_oracle_pins.py (all functions here are pinned).
@@ -27,6 +31,7 @@
 #include <string.h>
 
 enum { ORACLE_TOPK = 0, ORACLE_BLOCKSIGN = 1 };
+enum { ORACLE_EF = 0, ORACLE_CD = 1 };   /* error feedback (Section 4) / CD-Adam (Algorithm 1) */
 
 typedef struct oracle {
     int64_t d;
@@ -43,6 +48,14 @@ typedef struct oracle {
     float *gbar;        /* d     their average */
     uint32_t *sel;      /* n*k   Top-k: selected indices, ascending, last step */
     float *scales;      /* n*n_blocks  block sign: scale per (worker, block), last step */
+    /* CD-Adam (Algorithm 1) only */
+    int32_t method;
+    float *ghat_w;      /* n*d   ghat_i: Markov sequence of worker i */
+    float *ghat_s;      /* d     ghat: the server's aggregate of them */
+    float *gtil;        /* d     gtilde: Markov sequence of the aggregate, kept by server and workers */
+    float *c_s;         /* d     the server's compressed message of the last step */
+    uint32_t *sel_s;    /* k     Top-k: its selected indices */
+    float *scales_s;    /* n_blocks  block sign: its scales */
 } oracle_t;
 
 /* ---- magnitude key ------------------------------------------------------------
@@ -173,6 +186,26 @@ void oracle_set_blocks(oracle_t *o, const int64_t *offsets, int32_t n_blocks)
     o->offsets = (int64_t *)malloc((size_t)(n_blocks + 1) * sizeof(int64_t));
     memcpy(o->offsets, offsets, (size_t)(n_blocks + 1) * sizeof(int64_t));
     o->scales = (float *)calloc((size_t)o->n * (size_t)n_blocks, sizeof(float));
+    if (o->method == ORACLE_CD) {
+        free(o->scales_s);
+        o->scales_s = (float *)calloc((size_t)n_blocks, sizeof(float));
+    }
+}
+
+/* Selects the method; call before the first step.  CD-Adam starts from ghat_i = C(0) = 0 and
+ * gtilde = C(mean ghat_i) = 0 (Algorithm 1, line 1: g_0 = 0, and both compressors map 0 to 0). */
+void oracle_set_method(oracle_t *o, int32_t method)
+{
+    o->method = method;
+    if (method != ORACLE_CD || o->ghat_w) return;
+    o->ghat_w = (float *)calloc((size_t)o->n * (size_t)o->d, sizeof(float));
+    o->ghat_s = (float *)calloc((size_t)o->d, sizeof(float));
+    o->gtil = (float *)calloc((size_t)o->d, sizeof(float));
+    o->c_s = (float *)calloc((size_t)o->d, sizeof(float));
+    if (o->compressor == ORACLE_TOPK)
+        o->sel_s = (uint32_t *)calloc((size_t)o->k, sizeof(uint32_t));
+    else
+        o->scales_s = (float *)calloc((size_t)o->n_blocks, sizeof(float));
 }
 
 void oracle_set_theta(oracle_t *o, const float *theta) { memcpy(o->theta, theta, (size_t)o->d * sizeof(float)); }
@@ -182,10 +215,16 @@ void oracle_set_eps_mode(oracle_t *o, int32_t mode) { o->eps_mode = mode; }
 /* One step on gradients g[n][d] (row-major).  Workers are independent until the
  * average, so the loop over workers may run on several threads; no sum is split
  * across threads, hence the result does not depend on the thread count. */
+static void oracle_step_cd(oracle_t *o, const float *g);
+
 void oracle_step(oracle_t *o, const float *g)
 {
     const int64_t d = o->d;
     const int32_t n = o->n;
+    if (o->method == ORACLE_CD) {
+        oracle_step_cd(o, g);
+        return;
+    }
 
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t i = 0; i < n; ++i) {
@@ -225,6 +264,63 @@ void oracle_step(oracle_t *o, const float *g)
     }
 }
 
+/* C on one vector with this optimiser's compressor. */
+static void oracle_compress(oracle_t *o, const float *x, float *c, uint32_t *sel, float *scales)
+{
+    if (o->compressor == ORACLE_TOPK)
+        oracle_topk(x, o->d, o->k, c, sel);
+    else
+        oracle_blocksign(x, o->offsets, o->n_blocks, c, scales);
+}
+
+/* One iteration of Algorithm 1 (CD-Adam), in its order.  The same compressor serves both
+ * directions.  gbar receives mean_i c_i (what the server adds to ghat). */
+static void oracle_step_cd(oracle_t *o, const float *g)
+{
+    const int64_t d = o->d;
+    const int32_t n = o->n;
+
+    /* workers: c_i = C(g_i - ghat_i) ; ghat_i = ghat_i + c_i */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < n; ++i) {
+        float *gh = o->ghat_w + (size_t)i * (size_t)d;
+        float *c = o->c + (size_t)i * (size_t)d;
+        float *u = o->e + (size_t)i * (size_t)d;          /* scratch: the vector that is compressed */
+        const float *gi = g + (size_t)i * (size_t)d;
+        for (int64_t j = 0; j < d; ++j) u[j] = gi[j] - gh[j];
+        oracle_compress(o, u, c, o->sel ? o->sel + (size_t)i * (size_t)o->k : NULL,
+                        o->scales ? o->scales + (size_t)i * (size_t)o->n_blocks : NULL);
+        for (int64_t j = 0; j < d; ++j) gh[j] = gh[j] + c[j];
+    }
+
+    /* server: ghat = ghat + (1/n) sum_i c_i  (ascending worker order, one division by n) */
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t i = 0; i < n; ++i) acc += o->c[(size_t)i * (size_t)d + (size_t)j];
+        o->gbar[j] = acc / (float)n;
+        o->ghat_s[j] = o->ghat_s[j] + o->gbar[j];
+    }
+    /* server: c = C(ghat - gtilde) ; gtilde = gtilde + c  (workers do the same addition) */
+    {
+        float *w = (float *)malloc((size_t)d * sizeof(float));
+        for (int64_t j = 0; j < d; ++j) w[j] = o->ghat_s[j] - o->gtil[j];
+        oracle_compress(o, w, o->c_s, o->sel_s, o->scales_s);
+        for (int64_t j = 0; j < d; ++j) o->gtil[j] = o->gtil[j] + o->c_s[j];
+        free(w);
+    }
+
+    /* workers: AMSGrad with gtilde */
+    const int64_t chunk = 1 << 16;
+    const int64_t n_chunks = (d + chunk - 1) / chunk;
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < n_chunks; ++q) {
+        int64_t lo = q * chunk, len = (lo + chunk <= d) ? chunk : d - lo;
+        oracle_amsgrad(o->theta + lo, o->m + lo, o->v + lo, o->vhat + lo, o->gtil + lo, len, o->beta1,
+                       o->beta2, o->eps, o->lr, o->eps_mode);
+    }
+}
+
 float *oracle_theta(oracle_t *o) { return o->theta; }
 float *oracle_m(oracle_t *o) { return o->m; }
 float *oracle_v(oracle_t *o) { return o->v; }
@@ -235,11 +331,18 @@ float *oracle_compressed(oracle_t *o) { return o->c; }
 uint32_t *oracle_selected(oracle_t *o) { return o->sel; }
 float *oracle_scales(oracle_t *o) { return o->scales; }
 int32_t oracle_n_blocks(oracle_t *o) { return o->n_blocks; }
+float *oracle_ghat_workers(oracle_t *o) { return o->ghat_w; }
+float *oracle_ghat_server(oracle_t *o) { return o->ghat_s; }
+float *oracle_gtilde(oracle_t *o) { return o->gtil; }
+float *oracle_server_compressed(oracle_t *o) { return o->c_s; }
+uint32_t *oracle_server_selected(oracle_t *o) { return o->sel_s; }
+float *oracle_server_scales(oracle_t *o) { return o->scales_s; }
 
 void oracle_destroy(oracle_t *o)
 {
     if (!o) return;
     free(o->theta); free(o->m); free(o->v); free(o->vhat); free(o->gbar);
     free(o->e); free(o->c); free(o->sel); free(o->scales); free(o->offsets);
+    free(o->ghat_w); free(o->ghat_s); free(o->gtil); free(o->c_s); free(o->sel_s); free(o->scales_s);
     free(o);
 }

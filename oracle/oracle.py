@@ -18,6 +18,8 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 TOPK = 0
 BLOCKSIGN = 1
+EF = 0      # error feedback (Section 4)
+CD = 1      # CD-Adam, Algorithm 1
 
 
 def build(force: bool = True) -> str:
@@ -47,13 +49,17 @@ def lib():
         L.oracle_set_theta.argtypes = [C.c_void_p, fp]
         L.oracle_set_lr.argtypes = [C.c_void_p, C.c_float]
         L.oracle_set_eps_mode.argtypes = [C.c_void_p, C.c_int32]
+        L.oracle_set_method.argtypes = [C.c_void_p, C.c_int32]
         L.oracle_step.argtypes = [C.c_void_p, fp]
-        for name in ("theta", "m", "v", "vhat", "gbar", "error", "compressed", "scales"):
+        for name in ("theta", "m", "v", "vhat", "gbar", "error", "compressed", "scales", "ghat_workers",
+                     "ghat_server", "gtilde", "server_compressed", "server_scales"):
             f = getattr(L, "oracle_" + name)
             f.restype = fp
             f.argtypes = [C.c_void_p]
         L.oracle_selected.restype = u32p
         L.oracle_selected.argtypes = [C.c_void_p]
+        L.oracle_server_selected.restype = u32p
+        L.oracle_server_selected.argtypes = [C.c_void_p]
         L.oracle_n_blocks.restype = C.c_int32
         L.oracle_n_blocks.argtypes = [C.c_void_p]
         L.oracle_destroy.argtypes = [C.c_void_p]
@@ -102,12 +108,16 @@ def amsgrad(theta, m, v, vhat, gbar, beta1, beta2, eps, lr, eps_mode=0):
 
 
 class Oracle:
-    """Stateful error-feedback AMSGrad on n simulated workers (CPU, fp32)."""
+    """Stateful compressed AMSGrad on n simulated workers (CPU, fp32): error feedback (default)
+    or, with method=CD, CD-Adam (Algorithm 1)."""
 
-    def __init__(self, d, n, compressor, k_or_block, beta1, beta2, eps, lr):
+    def __init__(self, d, n, compressor, k_or_block, beta1, beta2, eps, lr, method=EF):
         self.d, self.n, self.compressor = int(d), int(n), int(compressor)
         self.k = int(k_or_block) if compressor == TOPK else 0
+        self.method = int(method)
         self._h = lib().oracle_create(d, n, compressor, k_or_block, beta1, beta2, eps, lr)
+        if self.method != EF:
+            lib().oracle_set_method(self._h, self.method)
 
     def close(self):
         if self._h:
@@ -158,3 +168,10 @@ class Oracle:
     compressed = property(lambda s: s._view("compressed", (s.n, s.d)))
     selected = property(lambda s: s._view("selected", (s.n, s.k)))
     scales = property(lambda s: s._view("scales", (s.n, s.n_blocks)))
+    # CD-Adam state
+    ghat_workers = property(lambda s: s._view("ghat_workers", (s.n, s.d)))
+    ghat_server = property(lambda s: s._view("ghat_server", (s.d,)))
+    gtilde = property(lambda s: s._view("gtilde", (s.d,)))
+    server_compressed = property(lambda s: s._view("server_compressed", (s.d,)))
+    server_selected = property(lambda s: s._view("server_selected", (s.k,)))
+    server_scales = property(lambda s: s._view("server_scales", (s.n_blocks,)))

@@ -356,3 +356,123 @@ def test_result_does_not_depend_on_thread_count():
     gomp.omp_set_num_threads(os.cpu_count() or 1)
     for a, b in zip(*outs):
         assert np.array_equal(bits(a) if a.dtype == f32 else a, bits(b) if b.dtype == f32 else b)
+
+
+# ----------------------------------------------------------------------------- CD-Adam (Algorithm 1)
+
+def test_cd_adam_golden_example_c_topk():
+    ex = json.load(open(os.path.join(GOLD, "example_c_cd_adam_topk.json")))
+    g = np.array(ex["g"], f32)
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    o = O.Oracle(ex["d"], ex["n"], O.TOPK, ex["k"], b1, b2, eps, lr, method=O.CD)
+    o.set_eps_mode(1)
+    th, m, v, vh = (np.zeros(ex["d"], f32) for _ in range(4))
+    for t, want in enumerate(ex["steps"]):
+        o.step(g)
+        assert np.array_equal(bits(o.compressed), bits(np.array(want["c_workers"], f32))), t
+        assert np.array_equal(bits(o.ghat_workers), bits(np.array(want["ghat_workers"], f32))), t
+        assert np.array_equal(bits(o.ghat_server), bits(np.array(want["ghat_server"], f32))), t
+        assert o.server_selected.tolist() == want["server_selected"], t
+        assert np.array_equal(bits(o.server_compressed), bits(np.array(want["c_server"], f32))), t
+        assert np.array_equal(bits(o.gtilde), bits(np.array(want["gtilde"], f32))), t
+        # the model update is AMSGrad (pinned on its own above) fed with gtilde
+        th, m, v, vh = O.amsgrad(th, m, v, vh, np.array(want["gtilde"], f32), b1, b2, eps, lr, eps_mode=1)
+        assert np.array_equal(bits(o.theta), bits(th)) and np.array_equal(bits(o.vhat), bits(vh))
+    o.close()
+
+
+def test_cd_adam_golden_example_d_scaled_sign():
+    ex = json.load(open(os.path.join(GOLD, "example_d_cd_adam_scaled_sign.json")))
+    g = np.array(ex["g"], f32)
+    o = O.Oracle(ex["d"], ex["n"], O.BLOCKSIGN, ex["d"], 0.9, 0.999, 1e-8, 1e-3, method=O.CD)
+    for t, want in enumerate(ex["steps"]):
+        o.step(g)
+        assert o.scales[:, 0].tolist() == want["scales_workers"], t
+        assert np.array_equal(bits(o.ghat_workers), bits(np.array(want["ghat_workers"], f32))), t
+        assert np.array_equal(bits(o.ghat_server), bits(np.array(want["ghat_server"], f32))), t
+        assert o.server_scales.tolist() == [want["scale_server"]], t
+        assert np.array_equal(bits(o.gtilde), bits(np.array(want["gtilde"], f32))), t
+    o.close()
+
+
+def test_cd_adam_with_k_equal_d_is_vanilla_amsgrad_bit_for_bit():
+    """pi = 0: C is the identity, so ghat_i = g_i, ghat = gtilde = mean g (Algorithm 1 reduces to the
+    vanilla distributed AMSGrad of Section 3).  Integer gradients and n = 4 keep every sum and
+    difference exact, so the identity holds bit for bit against an independent numpy AMSGrad."""
+    rng = np.random.default_rng(17)
+    n, d, T = 4, 300, 10
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gs = [rng.integers(-50, 51, (n, d)).astype(f32) for _ in range(T)]
+    o = O.Oracle(d, n, O.TOPK, d, b1, b2, eps, lr, method=O.CD)
+    o.set_theta(theta0)
+    for g in gs:
+        o.step(g)
+        assert np.array_equal(bits(o.ghat_workers), bits(g))
+        assert np.array_equal(bits(o.gtilde), bits(g.sum(axis=0, dtype=np.float64).astype(f32) / f32(n)))
+    th, m, v, vh = vanilla_amsgrad_numpy(theta0, gs, b1, b2, eps, lr)
+    assert np.array_equal(bits(o.theta), bits(th))
+    assert np.array_equal(bits(o.vhat), bits(vh))
+    o.close()
+
+
+def test_cd_adam_constant_gradients_are_recovered_in_finitely_many_steps():
+    """Markov compression of a constant sequence with Top-k: every step makes k more coordinates of
+    ghat_i exact (0 + (g - 0) = g) and they stay exact, so after ceil(d/k) steps ghat_i = g_i and the
+    workers send zeros; the server's gtilde then reaches mean_i g_i the same way."""
+    rng = np.random.default_rng(23)
+    n, d, k = 4, 40, 7
+    g = rng.integers(-64, 65, (n, d)).astype(f32)
+    g[g == 0] = 1.0
+    o = O.Oracle(d, n, O.TOPK, k, 0.9, 0.999, 1e-8, 1e-3, method=O.CD)
+    need = math.ceil(d / k)
+    for t in range(need):
+        o.step(g)
+        # exactly k*(t+1) coordinates are exact so far (none of g is 0, so exact means != 0 here)
+        assert np.count_nonzero(o.ghat_workers, axis=1).tolist() == [min(d, k * (t + 1))] * n
+    assert np.array_equal(bits(o.ghat_workers), bits(g))
+    mean = g.sum(axis=0) / f32(n)                               # exact: integers, n = 4
+    assert np.array_equal(bits(o.ghat_server), bits(mean))
+    for t in range(need):
+        o.step(g)
+        assert not o.compressed.any()                           # workers have nothing left to send
+    assert np.array_equal(bits(o.gtilde), bits(mean))
+    o.close()
+
+
+@pytest.mark.parametrize("comp", [O.TOPK, O.BLOCKSIGN])
+def test_cd_adam_markov_bookkeeping_and_contraction(comp):
+    """Per step and worker (Algorithm 1 lines 5-6, Assumption 1 with the compressor's own pi):
+    ghat_i(t) - ghat_i(t-1) = c_i(t);  ||ghat_i(t) - g_i(t)||^2 <= pi ||g_i(t) - ghat_i(t-1)||^2 with
+    pi = 1 - k/d (Top-k), and = ||u||^2 - ||u||_1^2 / |b| per block for the scaled sign (its error
+    identity, Appendix A).  Server (lines 8-10): ghat(t) = mean_i ghat_i(t) up to rounding; gtilde moves
+    by the server's message; vhat never decreases."""
+    rng = np.random.default_rng(29 + comp)
+    n, d, T = 3, 600, 8
+    kb = 9 if comp == O.TOPK else 64
+    o = O.Oracle(d, n, comp, kb, 0.9, 0.999, 1e-8, 1e-3, method=O.CD)
+    off = np.array(list(range(0, d, 64)) + [d])
+    prev_w = np.zeros((n, d), f32)
+    prev_t = np.zeros(d, f32)
+    prev_vh = np.zeros(d, f32)
+    for t in range(T):
+        g = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-4, 0, d)) + 0.3).astype(f32)
+        o.step(g)
+        gw, c = o.ghat_workers.copy(), o.compressed.copy()
+        assert np.array_equal(bits(gw), bits(prev_w + c))
+        u = g.astype(np.float64) - prev_w
+        left = ((gw.astype(np.float64) - g) ** 2)
+        if comp == O.TOPK:
+            assert np.count_nonzero(c, axis=1).max() <= kb
+            assert (left.sum(axis=1) <= (1 - kb / d) * (u ** 2).sum(axis=1) * (1 + 1e-6)).all()
+        else:
+            for b in range(off.size - 1):
+                ub = u[:, off[b]:off[b + 1]]
+                want = (ub ** 2).sum(axis=1) - np.abs(ub).sum(axis=1) ** 2 / ub.shape[1]
+                got = left[:, off[b]:off[b + 1]].sum(axis=1)
+                assert np.allclose(got, want, rtol=1e-4, atol=1e-9)
+        assert np.allclose(o.ghat_server, gw.astype(np.float64).mean(axis=0), rtol=1e-5, atol=1e-6)
+        assert np.array_equal(bits(o.gtilde), bits(prev_t + o.server_compressed))
+        assert (o.vhat >= prev_vh).all()
+        prev_w, prev_t, prev_vh = gw, o.gtilde.copy(), o.vhat.copy()
+    o.close()
