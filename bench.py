@@ -43,14 +43,18 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
 def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:
     """Algorithmic bytes of one launch = per-unit figure x units (n*d worker-coordinates).
     The streaming pass of either compressor carries the 12 B per (worker, coordinate) of the
-    method (read g, read stored error vector, write it back); the update kernel carries the
-    32 B per coordinate of optimiser state (read and write theta, m, v, vhat)."""
+    method (read g, read the stored error / Markov vector, write it back); the update kernel carries
+    the 32 B per coordinate of optimiser state (read and write theta, m, v, vhat).  CD-Adam's server
+    stage reads and writes ghat and reads gtilde (12 B per coordinate); its last kernel reads and
+    writes gtilde and the optimiser state (40 B per coordinate)."""
     nd = n * d
     return {
         "bs_pass": 12 * nd,
         "bs_update": 32 * d,
         "tk_pass1": 12 * nd,
         "tk_final": 32 * d,
+        "bs_server": 12 * d,
+        "bs_apply": 40 * d,
     }.get(name, 0)
 
 
@@ -63,6 +67,8 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--method", choices=("ef", "cd"), default="ef",
+                    help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1 (block-sign workloads)")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -92,6 +98,11 @@ def main() -> int:
     if w.compressor == W.BLOCKSIGN and w.layer_blocks:
         h.set_blocks(w.block_offsets())
     h.set_theta(w.theta0())
+    cd = args.method == "cd"
+    if cd:
+        h.set_method(P.METHOD_CD)
+        h.set_eps_mode(1)                     # Algorithm 1 keeps nu inside the root
+    step_bytes = w.algorithmic_bytes() + (20 * w.d if cd else 0)   # CD-Adam: + ghat r/w, gtilde r, gtilde r/w
 
     def run(k0, count):
         for t in range(k0, k0 + count):
@@ -119,9 +130,9 @@ def main() -> int:
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "traffic": None if cd else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
-    step_gbs = w.algorithmic_bytes() / (ms_per_step * 1e-3) / 1e9
+    step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # plain float4 copy on the same stream: what a trivial streaming kernel reaches on this chip, and
     # the launch that calibrates the HBM byte counters (it moves exactly 2 * probe bytes)
@@ -145,10 +156,12 @@ def main() -> int:
     cpu = None
     if not args.no_cpu:
         from oracle import oracle as O
-        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
+        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr, method=O.CD if cd else O.EF)
         if w.compressor == W.BLOCKSIGN and w.layer_blocks:
             ora.set_blocks(w.block_offsets())
         ora.set_theta(w.theta0())
+        if cd:
+            ora.set_eps_mode(1)
         ora.step(host_grads[0])                       # warm: first-touch of the oracle's arrays
         done, spent = 0, 0.0
         while done < max(1, w.steps) and spent < args.cpu_seconds:
@@ -162,7 +175,7 @@ def main() -> int:
                "sample": f"{done} full steps of {w.name} after one warm step, {spent / done * 1e3:.1f} ms/step"}
 
     out = {
-        "metric": "coords/sec (n*d) per COMP-AMS step",
+        "metric": "coords/sec (n*d) per CD-Adam step" if cd else "coords/sec (n*d) per COMP-AMS step",
         "value": coords_per_s,
         "unit": "coords/s",
         "n_gpus": 1,
@@ -174,7 +187,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "n_workers": w.n, "d": w.d,
+        "config": {"workload": w.name, "method": "cd_adam" if cd else "error_feedback", "n_workers": w.n, "d": w.d,
                    "compressor": "topk" if w.compressor == W.TOPK else "blocksign",
                    "k": w.k, "block": w.block, "layer_blocks": w.layer_blocks, "gradient_buffers": nbuf},
         "roofline": roofline,

@@ -43,6 +43,10 @@ typedef struct comp_ams comp_ams_t;
 
 enum { COMP_AMS_TOPK = 0, COMP_AMS_BLOCKSIGN = 1 };
 
+/* How the compressor is used: classical error feedback (Section 4; the step described above), or
+ * CD-Adam (Section 5, Algorithm 1): Markov compression in both directions. */
+enum { COMP_AMS_METHOD_EF = 0, COMP_AMS_METHOD_CD = 1 };
+
 enum {
     COMP_AMS_OK = 0,
     COMP_AMS_EINVAL = -1,  /* bad argument (range, NULL, inconsistent block table) */
@@ -120,6 +124,36 @@ int32_t comp_ams_n_blocks(comp_ams_t *h);
  * ([n][d] row-major); any pointer may be NULL to leave that array as it is. */
 int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const float *vhat, const float *e,
                        int on_device);
+
+/*
+ * CD-Adam, Section 5, Algorithm 1.  Chooses the method of a handle before its first step
+ * (COMP_AMS_ESTATE afterwards); built for BLOCKSIGN handles (COMP_AMS_EINVAL otherwise).  With
+ * COMP_AMS_METHOD_CD one comp_ams_step computes, with the handle's compressor C in both directions,
+ *   c_i     = C(g_i - ghat_i) ;  ghat_i = ghat_i + c_i          workers, lines 5-6
+ *   ghat    = ghat + (1/n) sum_i c_i                            server, line 8 (ascending i, one division)
+ *   c       = C(ghat - gtilde) ;  gtilde = gtilde + c           server and workers, lines 9-12
+ *   m, v, vhat, theta: the AMSGrad update of the step above with gtilde in the place of gbar
+ * starting from ghat_i = ghat = gtilde = 0 (line 1: both compressors map 0 to 0).  Algorithm 1
+ * places nu inside the root: that is eps mode 1, which this call does not select by itself.
+ * Allocates the server's vectors (2 d floats and d/8 bytes of sign bits); the rows that held the
+ * error memory are cleared and hold ghat_i from then on, so comp_ams_get_error and the e argument
+ * of comp_ams_set_state answer COMP_AMS_ESTATE on such a handle.
+ */
+int comp_ams_set_method(comp_ams_t *h, int32_t method);
+
+/* CD handles: ghat_i of worker i in [0,n), the server's aggregate ghat, and gtilde: d floats each. */
+int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_device);
+int comp_ams_get_ghat_server(comp_ams_t *h, float *out, int on_device);
+int comp_ams_get_gtilde(comp_ams_t *h, float *out, int on_device);
+
+/* CD handles with BLOCKSIGN, after at least one step: the n_blocks scales of the server's message
+ * c of the last step (host array); comp_ams_get_scales gives those of the workers' c_i. */
+int comp_ams_get_server_scales(comp_ams_t *h, float *out_host);
+
+/* CD handles, checkpoint resume: ghat_i as [n][d] row-major, ghat and gtilde of d floats; any
+ * pointer may be NULL to leave that array as it is (m, v, vhat go through comp_ams_set_state). */
+int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const float *ghat_server,
+                              const float *gtilde, int on_device);
 
 /* Waits until all work enqueued by this handle has completed. */
 int comp_ams_sync(comp_ams_t *h);

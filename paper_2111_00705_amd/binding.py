@@ -16,6 +16,8 @@ from . import build as _build
 
 TOPK = 0
 BLOCKSIGN = 1
+METHOD_EF = 0     # error feedback (Section 4)
+METHOD_CD = 1     # CD-Adam (Section 5, Algorithm 1)
 
 OK, EINVAL, ENOMEM, EDEVICE, ESTATE = 0, -1, -2, -3, -4
 
@@ -25,6 +27,8 @@ EXPORTS = [
     "comp_ams_get_vhat", "comp_ams_get_error", "comp_ams_get_selected", "comp_ams_get_scales",
     "comp_ams_n_blocks", "comp_ams_set_state", "comp_ams_sync", "comp_ams_last_error", "comp_ams_profile",
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
+    "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
+    "comp_ams_get_server_scales", "comp_ams_set_markov_state",
 ]
 
 
@@ -71,6 +75,12 @@ def lib():
                                             C.POINTER(C.c_int64)]
         L.comp_ams_probe_copy.argtypes = [fp, fp, C.c_int64, vp]
         L.comp_ams_get_selection_info.argtypes = [vp, C.c_int32, u32p]
+        L.comp_ams_set_method.argtypes = [vp, C.c_int32]
+        L.comp_ams_get_ghat_worker.argtypes = [vp, C.c_int32, fp, C.c_int]
+        L.comp_ams_get_ghat_server.argtypes = [vp, fp, C.c_int]
+        L.comp_ams_get_gtilde.argtypes = [vp, fp, C.c_int]
+        L.comp_ams_get_server_scales.argtypes = [vp, fp]
+        L.comp_ams_set_markov_state.argtypes = [vp, fp, fp, fp, C.c_int]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
         _lib = L
@@ -139,6 +149,37 @@ class CompAms:
 
     def set_eps_mode(self, mode):
         self._check(lib().comp_ams_set_eps_mode(self._h, mode))
+
+    def set_method(self, method):
+        self._check(lib().comp_ams_set_method(self._h, method))
+
+    def get_ghat_worker(self, worker, out=None):
+        if out is None:
+            out = np.empty(self.d, dtype=np.float32)
+        p, dev = _ptr(out)
+        self._check(lib().comp_ams_get_ghat_worker(self._h, worker, p, dev))
+        return out
+
+    def get_ghat_server(self, out=None):
+        return self._get_vec(lib().comp_ams_get_ghat_server, out)
+
+    def get_gtilde(self, out=None):
+        return self._get_vec(lib().comp_ams_get_gtilde, out)
+
+    def get_server_scales(self):
+        out = np.empty(self.n_blocks(), dtype=np.float32)
+        self._check(lib().comp_ams_get_server_scales(self._h, out.ctypes.data))
+        return out
+
+    def set_markov_state(self, ghat_workers=None, ghat_server=None, gtilde=None):
+        ptrs, devs = [], set()
+        for a in (ghat_workers, ghat_server, gtilde):
+            p, dev = _ptr(a)
+            ptrs.append(p)
+            if a is not None:
+                devs.add(dev)
+        assert len(devs) <= 1, "all arrays must live on the same side (host or device)"
+        self._check(lib().comp_ams_set_markov_state(self._h, *ptrs, devs.pop() if devs else 0))
 
     def step(self, grads, stream=None):
         """grads: torch float32 tensor [n, d] on the GPU.  stream: raw hipStream_t value

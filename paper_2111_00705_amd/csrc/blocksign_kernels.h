@@ -18,6 +18,21 @@
 //
 // Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written + 2 x 1/8 B of sign
 // bits, for any block size; plus 32 B per coordinate of optimiser state.
+//
+// CD-Adam (Section 5, Algorithm 1) runs on the same kernels.  The worker's Markov sequence ghat_i
+// takes the place of the error memory, again in deferred form: the library stores ghat_i of the step
+// before, and c_i = copysign(s_i[block], sign bit) is added when the next step (or a getter) reads
+// it.  The sign bits of c_i cannot be read off the stored vector here, so the step reads the old
+// sign word before it writes the new one.
+//
+//   bs_pass<.., true>    ghat_i += pending c_i, u = g - ghat_i, store ghat_i, sign bits and piece sums of u
+//   bs_scale             as above
+//   bs_update<.., true>  mean of the c_i as above, ghat += mean, w = ghat - gtilde, sign bits and piece
+//                        sums of w (the server's compression, lines 8-9 of Algorithm 1)
+//   bs_scale             once more, for the single vector w
+//   bs_apply             gtilde += copysign(s, w), then the AMSGrad update with gtilde
+//
+// Traffic: 12 B per (worker, coordinate) as above, plus 12 B + 40 B per coordinate.
 #pragma once
 #include "device_utils.h"
 
@@ -49,7 +64,46 @@ __device__ __forceinline__ float deferred_sign_error(float xs, float s_prev)
     return fsub(xs, copysignf(s_prev, xs));
 }
 
-template <bool kPending>
+// copysign(s, x) for the coordinate whose sign is bit `k` of `bits`; s >= 0.
+__device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
+{
+    return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
+}
+
+// Fixed-order fp64 sums of |x| over the pieces p0 .. p1-1 of the tile at `base`, one result per
+// piece written to out[p] by thread 0.  x: the 16 values of this thread (padding holds 0).
+__device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base, int p0, int p1, const BsTable &tb,
+                                           double *scratch, double *__restrict__ out)
+{
+    const int tid = threadIdx.x;
+    if (p1 - p0 == 1) {
+        double acc = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc += (double)fabsf(x[r][c]);
+        const double S = block_sum(acc, scratch);
+        if (tid == 0) out[p0] = S;
+    } else {
+        for (int p = p0; p < p1; ++p) {
+            const int lo = (p == p0) ? (int)base : tb.piece_hi[p - 1];
+            const int hi = tb.piece_hi[p];
+            double acc = 0.0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = (int)base + 4 * (tid + kThreads * r);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j + c >= lo && j + c < hi) acc += (double)fabsf(x[r][c]);
+            }
+            const double S = block_sum(acc, scratch);
+            if (tid == 0) out[p] = S;
+        }
+    }
+}
+
+// kMarkov: CD-Adam's worker stage instead of error feedback (see the head of this file).
+template <bool kPending, bool kMarkov>
 __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g, float *__restrict__ xs,
                                                     int64_t d, int64_t ld, BsTable tb,
                                                     const float *__restrict__ s_prev,
@@ -74,6 +128,8 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
         gv[r] = load_grad4(grow, j, d);
         xv[r] = ld4(xrow + j);
     }
+    uint16_t *word = signs + ((int64_t)i * (ld / kTile) + t) * kThreads + tid;
+    const uint32_t old_bits = (kMarkov && kPending) ? (uint32_t)*word : 0u;   // sign bits of the pending c_i
     float x[4][4];
     uint32_t sign_bits = 0;
     const bool single = (p1 - p0 == 1);
@@ -83,50 +139,33 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
         const int64_t j = base + 4 * (tid + kThreads * r);
         const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
         const float xx[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+        float keep[4];     // what goes back to the stored vector
         int p = p0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float e = xx[c];
-            if (kPending) {
-                float s = s_single;
-                if (!single) {
-                    while (p + 1 < p1 && j + c >= tb.piece_hi[p]) ++p;
-                    s = sp[tb.piece_blk[p]];
-                }
-                e = deferred_sign_error(xx[c], s);
+            float s = s_single;
+            if (kPending && !single) {
+                while (p + 1 < p1 && j + c >= tb.piece_hi[p]) ++p;
+                s = sp[tb.piece_blk[p]];
             }
-            x[r][c] = (j + c < d) ? fadd(gg[c], e) : 0.f;
+            if (kMarkov) {
+                // ghat_i = ghat_i + c_i (Algorithm 1, line 6, of the step before); u = g - ghat_i (line 5)
+                float gh = xx[c];
+                if (kPending && j + c < d) gh = fadd(gh, signed_scale(s, old_bits, r * 4 + c));
+                keep[c] = gh;
+                x[r][c] = (j + c < d) ? fsub(gg[c], gh) : 0.f;
+            } else {
+                const float e = kPending ? deferred_sign_error(xx[c], s) : xx[c];
+                x[r][c] = (j + c < d) ? fadd(gg[c], e) : 0.f;
+                keep[c] = x[r][c];
+            }
         }
-        st4(xrow + j, make_float4(x[r][0], x[r][1], x[r][2], x[r][3]));
+        st4(xrow + j, make_float4(keep[0], keep[1], keep[2], keep[3]));
 #pragma unroll
         for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
     }
-    signs[((int64_t)i * (ld / kTile) + t) * kThreads + tid] = (uint16_t)sign_bits;
-
-    if (single) {
-        double acc = 0.0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc += (double)fabsf(x[r][c]);   // padding coordinates hold 0
-        const double S = block_sum(acc, scratch);
-        if (tid == 0) partial[(int64_t)i * tb.n_pieces + p0] = S;
-    } else {
-        for (int p = p0; p < p1; ++p) {
-            const int lo = (p == p0) ? (int)base : tb.piece_hi[p - 1];
-            const int hi = tb.piece_hi[p];
-            double acc = 0.0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = (int)base + 4 * (tid + kThreads * r);
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (j + c >= lo && j + c < hi) acc += (double)fabsf(x[r][c]);
-            }
-            const double S = block_sum(acc, scratch);
-            if (tid == 0) partial[(int64_t)i * tb.n_pieces + p] = S;
-        }
-    }
+    *word = (uint16_t)sign_bits;
+    piece_sums(x, base, p0, p1, tb, scratch, partial + (int64_t)i * tb.n_pieces);
 }
 
 // One wavefront per (block, worker).
@@ -146,12 +185,6 @@ __global__ __launch_bounds__(kWave) void bs_scale(const double *__restrict__ par
     }
 }
 
-// copysign(s, x) for the coordinate whose sign is bit `k` of `bits`; s >= 0.
-__device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
-{
-    return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
-}
-
 constexpr int kScaleChunk = 1024;   // workers whose scales are staged in LDS at a time
 constexpr int kSignBatch = 8;       // workers whose sign words are loaded together
 
@@ -160,22 +193,35 @@ constexpr int kSignBatch = 8;       // workers whose sign words are loaded toget
 // kEarlyState: load theta, m, v, vhat at the start (small grids: nothing else would hide that
 // latency); otherwise after the worker loop (large grids: fewer live registers, more workgroups
 // per compute unit).
-template <bool kFusedScale, bool kEarlyState>
+// kMarkov: CD-Adam's server stage instead of the AMSGrad update: the mean of the c_i goes into
+// ghat (Algorithm 1, line 8), w = ghat - gtilde is formed, and its sign bits and piece sums are
+// written for the second compression (line 9).  The arrays of the Markov struct are only touched
+// then; theta, m, v, vhat only otherwise.
+struct BsMarkov {
+    float *ghat;            // [ld] the server's aggregate
+    const float *gtil;      // [ld] gtilde of the step before
+    uint16_t *signs;        // [n_tiles][256] sign bits of w
+    double *partial;        // [n_pieces] piece sums of |w|
+};
+
+template <bool kFusedScale, bool kEarlyState, bool kMarkov>
 __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int n, BsTable tb,
                                                       const double *__restrict__ partial,
                                                       float *__restrict__ scales,
                                                       const uint16_t *__restrict__ signs,
                                                       float *__restrict__ theta, float *__restrict__ m,
-                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
+                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p,
+                                                      BsMarkov mk)
 {
     __shared__ float s_lds[kScaleChunk];
+    __shared__ double scratch[4];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
     const int n_tiles = (int)(ld / kTile);
 
     float4 th[4], mm[4], vv[4], vh[4];
-    if (kEarlyState) {
+    if (kEarlyState && !kMarkov) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t j = base + 4 * (tid + kThreads * r);
@@ -276,6 +322,29 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(sc[blk[q]], w, q));
         }
     }
+    if (kMarkov) {
+        float w[4][4];
+        uint32_t sign_bits = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t j = base + 4 * (tid + kThreads * r);
+            const float4 gh4 = ld4(mk.ghat + j), gt4 = ld4(mk.gtil + j);
+            const float gh[4] = {gh4.x, gh4.y, gh4.z, gh4.w}, gt[4] = {gt4.x, gt4.y, gt4.z, gt4.w};
+            float nh[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                // padding coordinates stay 0
+                nh[c] = (j + c < d) ? fadd(gh[c], fdiv(acc[r * 4 + c], p.n_workers)) : gh[c];
+                w[r][c] = (j + c < d) ? fsub(nh[c], gt[c]) : 0.f;
+                sign_bits |= (__float_as_uint(w[r][c]) >> 31) << (r * 4 + c);
+            }
+            st4(mk.ghat + j, make_float4(nh[0], nh[1], nh[2], nh[3]));
+        }
+        mk.signs[(int64_t)t * kThreads + tid] = (uint16_t)sign_bits;
+        __syncthreads();   // s_lds readers are done before scratch is used (separate arrays; keeps phases apart)
+        piece_sums(w, base, p0, p1, tb, scratch, mk.partial);
+        return;
+    }
     if (!kEarlyState) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -319,6 +388,86 @@ __global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *__
         e = deferred_sign_error(e, sp[tb.piece_blk[q]]);
     }
     out[j] = e;
+}
+
+// CD-Adam, Algorithm 1, lines 10 and 12-16: gtilde += c with c = copysign(s[block], w) from the
+// server's sign bits and scales, then the AMSGrad update with gtilde.  One workgroup per tile.
+__global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, const float *__restrict__ scales,
+                                                     const uint16_t *__restrict__ signs, float *__restrict__ gtil,
+                                                     float *__restrict__ theta, float *__restrict__ m,
+                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
+{
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)t * kTile;
+    const uint32_t bits = signs[(int64_t)t * kThreads + tid];
+    float4 gt[4], th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        gt[r] = ld4(gtil + j);
+        th[r] = ld4(theta + j);
+        mm[r] = ld4(m + j);
+        vv[r] = ld4(v + j);
+        vh[r] = ld4(vhat + j);
+    }
+    int p0, p1;
+    if (tb.uniform_tiles > 0) {
+        p0 = t;
+        p1 = t + 1;
+    } else {
+        p0 = tb.tile_piece0[t];
+        p1 = tb.tile_piece0[t + 1];
+    }
+    const bool single = (p1 - p0 == 1);
+    const float s_single = single ? scales[tb.uniform_tiles > 0 ? t / tb.uniform_tiles : tb.piece_blk[p0]] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        const float old[4] = {gt[r].x, gt[r].y, gt[r].z, gt[r].w};
+        float nt[4];
+        int q = p0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float s = s_single;
+            if (!single) {
+                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
+                s = scales[tb.piece_blk[q]];
+            }
+            nt[c] = (j + c < d) ? fadd(old[c], signed_scale(s, bits, r * 4 + c)) : old[c];   // padding stays 0
+        }
+        const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
+        amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
+        st4(gtil + j, g4);
+        st4(theta + j, th[r]);
+        st4(m + j, mm[r]);
+        st4(v + j, vv[r]);
+        st4(vhat + j, vh[r]);
+    }
+}
+
+// ghat_i of one worker in its defined form: the stored vector plus the pending c_i.
+template <bool kPending>
+__global__ __launch_bounds__(kThreads) void bs_materialize_markov(const float *__restrict__ xrow, int64_t d,
+                                                                  BsTable tb, const float *__restrict__ sp,
+                                                                  const uint16_t *__restrict__ signs_row,
+                                                                  float *__restrict__ out)
+{
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j >= d) return;
+    float gh = xrow[j];
+    if (kPending) {
+        const int t = (int)(j / kTile);
+        int q = tb.tile_piece0[t];
+        const int q1 = tb.tile_piece0[t + 1];
+        while (q + 1 < q1 && j >= tb.piece_hi[q]) ++q;
+        // coordinate 4 * (tid + 256 * r) + c of the tile is bit r * 4 + c of the word of thread tid
+        const int l = (int)(j - (int64_t)t * kTile);
+        const int vec = l >> 2, c = l & 3;
+        const uint32_t bits = signs_row[(int64_t)t * kThreads + (vec & (kThreads - 1))];
+        gh = fadd(gh, signed_scale(sp[tb.piece_blk[q]], bits, (vec / kThreads) * 4 + c));
+    }
+    out[j] = gh;
 }
 
 }  // namespace cams

@@ -52,6 +52,14 @@ struct comp_ams {
     bool pending = false;
     bool fused_scale = false;                  // bs_update forms the scales itself (see kMaxFusedPieces)
 
+    // CD-Adam (Algorithm 1): e then holds the workers' Markov sequences ghat_i (deferred by one c_i while
+    // `pending`), and the server keeps its aggregate, gtilde and the buffers of its own compression
+    int32_t method = COMP_AMS_METHOD_EF;
+    float *ghat_srv = nullptr, *gtil = nullptr;   // [ld] each
+    uint16_t *signs_srv = nullptr;                // [n_tiles][256] sign bits of ghat - gtilde
+    double *partial_srv = nullptr;                // [n_pieces]
+    float *scales_srv = nullptr;                  // [n_blocks]
+
     // Top-k
     TkGeom ge{};
     TkWorker *ws = nullptr;
@@ -75,9 +83,10 @@ struct comp_ams {
 namespace {
 
 enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
-                P_TK_RESOLVE, P_TK_FINAL, P_SLOTS };
+                P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_SLOTS };
 const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
-                                         "tk_relist", "tk_compact", "tk_resolve", "tk_final"};
+                                         "tk_relist", "tk_compact", "tk_resolve", "tk_final", "bs_server",
+                                         "bs_scale_server", "bs_apply"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -183,8 +192,8 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     }
     std::vector<void *> fresh;
     int32_t *d_off = nullptr, *d_hi = nullptr, *d_blk = nullptr, *d_tp = nullptr, *d_bp = nullptr;
-    double *d_partial = nullptr;
-    float *d_scales = nullptr;
+    double *d_partial = nullptr, *d_partial_srv = nullptr;
+    float *d_scales = nullptr, *d_scales_srv = nullptr;
     int rc;
     auto upload = [&](int32_t **dst, const std::vector<int32_t> &src) -> int {
         int r = dev_alloc_t(h, fresh, dst, src.size(), false);
@@ -195,7 +204,9 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     if ((rc = upload(&d_off, off32)) || (rc = upload(&d_hi, piece_hi)) || (rc = upload(&d_blk, piece_blk)) ||
         (rc = upload(&d_tp, tile_piece0)) || (rc = upload(&d_bp, block_piece0)) ||
         (rc = dev_alloc_t(h, fresh, &d_partial, (size_t)h->n * piece_hi.size())) ||
-        (rc = dev_alloc_t(h, fresh, &d_scales, (size_t)h->n * nb))) {
+        (rc = dev_alloc_t(h, fresh, &d_scales, (size_t)h->n * nb)) ||
+        (rc = dev_alloc_t(h, fresh, &d_partial_srv, piece_hi.size())) ||
+        (rc = dev_alloc_t(h, fresh, &d_scales_srv, (size_t)nb))) {
         free_all(fresh);
         return rc;
     }
@@ -217,6 +228,8 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     }
     h->partial = d_partial;
     h->scales = d_scales;
+    h->partial_srv = d_partial_srv;
+    h->scales_srv = d_scales_srv;
     return COMP_AMS_OK;
 }
 
@@ -251,9 +264,9 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            bs_pass<true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<true, false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     if (!h->fused_scale)
         launch_timed(h, P_BS_SCALE, st, [&] {
@@ -264,14 +277,45 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
         // workgroups per compute unit
         const bool early = grid.x < 2048;
 #define CAMS_BS_UPDATE(F, E)                                                                                  \
-    bs_update<F, E><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs, h->theta, \
-                                                 h->m, h->v, h->vhat, h->params)
+    bs_update<F, E, false><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
+                                                        h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{})
         if (h->fused_scale) {
             if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
         } else {
             if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
         }
 #undef CAMS_BS_UPDATE
+    });
+    h->pending = true;
+    return COMP_AMS_OK;
+}
+
+// One iteration of Algorithm 1 (CD-Adam) with the block-wise scaled sign, five launches.
+int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
+{
+    const BsTable &tb = h->tb;
+    const dim3 grid((unsigned)(h->ld / kTile), h->n);
+    launch_timed(h, P_BS_PASS, st, [&] {
+        if (h->pending)
+            bs_pass<true, true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+        else
+            bs_pass<false, true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+    });
+    launch_timed(h, P_BS_SCALE, st, [&] {
+        bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
+    });
+    launch_timed(h, P_BS_SERVER, st, [&] {
+        const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv};
+        bs_update<false, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
+                                                                   h->signs, h->theta, h->m, h->v, h->vhat,
+                                                                   h->params, mk);
+    });
+    launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
+        bs_scale<<<dim3(tb.n_blocks, 1), kWave, 0, st>>>(h->partial_srv, tb, h->scales_srv);
+    });
+    launch_timed(h, P_BS_APPLY, st, [&] {
+        bs_apply<<<grid.x, kThreads, 0, st>>>(h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m, h->v,
+                                              h->vhat, h->params);
     });
     h->pending = true;
     return COMP_AMS_OK;
@@ -323,13 +367,21 @@ int reset_topk_workers(comp_ams *h)
     return COMP_AMS_OK;
 }
 
-// Writes e_i in its defined form to dst (device memory, d floats) on the handle's stream.
+// Writes e_i (error feedback) or ghat_i (CD-Adam) in its defined form to dst (device memory, d floats)
+// on the handle's stream.
 void launch_materialize(comp_ams *h, int worker, float *dst)
 {
     const float *xrow = h->e + (size_t)worker * (size_t)h->ld;
     const unsigned blocks = (unsigned)((h->d + kThreads - 1) / kThreads);
     if (h->compressor == COMP_AMS_TOPK) {
         tk_materialize_error<<<blocks, kThreads, 0, h->stream>>>(xrow, h->ge, h->ws + worker, dst);
+    } else if (h->method == COMP_AMS_METHOD_CD) {
+        const uint16_t *srow = h->signs + (size_t)worker * (size_t)(h->ld / kTile) * kThreads;
+        if (h->pending)
+            bs_materialize_markov<true><<<blocks, kThreads, 0, h->stream>>>(
+                xrow, h->d, h->tb, h->scales + (size_t)worker * (size_t)h->tb.n_blocks, srow, dst);
+        else
+            bs_materialize_markov<false><<<blocks, kThreads, 0, h->stream>>>(xrow, h->d, h->tb, h->scales, srow, dst);
     } else if (h->pending) {
         bs_materialize_error<true><<<blocks, kThreads, 0, h->stream>>>(
             xrow, h->d, h->tb, h->scales + (size_t)worker * (size_t)h->tb.n_blocks, dst);
@@ -521,7 +573,10 @@ int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream)
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         h->stream = st;
     }
-    rc = (h->compressor == COMP_AMS_TOPK) ? step_topk(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
+    if (h->compressor == COMP_AMS_TOPK)
+        rc = step_topk(h, grads_dev, st);
+    else
+        rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
     if (rc) return rc;
     HIP_TRY(h, hipGetLastError());
     ++h->steps;
@@ -553,6 +608,8 @@ int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
 {
     int rc = check_handle(h);
     if (rc) return rc;
+    if (h->method != COMP_AMS_METHOD_EF)
+        return fail(h, COMP_AMS_ESTATE, "CD-Adam keeps no error memory; see comp_ams_get_ghat_worker");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
     launch_materialize(h, worker, on_device ? out : h->row_tmp);
@@ -616,6 +673,8 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
     if (m && (rc = copy_in(h, h->m, m, d, on_device))) return rc;
     if (v && (rc = copy_in(h, h->v, v, d, on_device))) return rc;
     if (vhat && (rc = copy_in(h, h->vhat, vhat, d, on_device))) return rc;
+    if (e && h->method != COMP_AMS_METHOD_EF)
+        return fail(h, COMP_AMS_ESTATE, "CD-Adam keeps no error memory; see comp_ams_set_markov_state");
     if (e) {
         HIP_TRY(h, hipMemcpy2DAsync(h->e, (size_t)h->ld * sizeof(float), e, d * sizeof(float), d * sizeof(float),
                                     (size_t)h->n, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
@@ -683,6 +742,89 @@ int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_hos
     out_host[5] = w.rank;
     out_host[6] = w.whole;
     out_host[7] = (uint32_t)(w.tc >> (h->ge.idx_bits + kFineShift));
+    return COMP_AMS_OK;
+}
+
+int comp_ams_set_method(comp_ams_t *h, int32_t method)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (method != COMP_AMS_METHOD_EF && method != COMP_AMS_METHOD_CD) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
+    if (method == h->method) return COMP_AMS_OK;
+    if (h->steps != 0) return fail(h, COMP_AMS_ESTATE, "the method can only be chosen before the first step");
+    if (h->compressor != COMP_AMS_BLOCKSIGN)
+        return fail(h, COMP_AMS_EINVAL, "CD-Adam is built for the BLOCKSIGN compressor only");
+    if (method == COMP_AMS_METHOD_CD && !h->ghat_srv) {
+        const size_t ld = (size_t)h->ld;
+        if ((rc = dev_alloc_t(h, h->allocs, &h->ghat_srv, ld)) || (rc = dev_alloc_t(h, h->allocs, &h->gtil, ld)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->signs_srv, ld / 16)))
+            return rc;
+    }
+    // the stored rows change their meaning (error memory <-> Markov sequence): start both from zero
+    HIP_TRY(h, hipMemsetAsync(h->e, 0, (size_t)h->ld * (size_t)h->n * sizeof(float), h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    h->pending = false;
+    h->method = method;
+    return COMP_AMS_OK;
+}
+
+namespace {
+int need_cd(comp_ams *h)
+{
+    return h->method == COMP_AMS_METHOD_CD ? COMP_AMS_OK : fail(h, COMP_AMS_ESTATE, "needs a handle set to CD-Adam");
+}
+}  // namespace
+
+int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_device)
+{
+    int rc = check_handle(h);
+    if (rc || (rc = need_cd(h))) return rc;
+    if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
+    if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    launch_materialize(h, worker, on_device ? out : h->row_tmp);
+    HIP_TRY(h, hipGetLastError());
+    if (!on_device) return copy_out(h, out, h->row_tmp, (size_t)h->d, 0);
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return COMP_AMS_OK;
+}
+
+int comp_ams_get_ghat_server(comp_ams_t *h, float *out, int on_device)
+{
+    int rc = check_handle(h);
+    if (rc || (rc = need_cd(h))) return rc;
+    return copy_out(h, out, h->ghat_srv, (size_t)h->d, on_device);
+}
+
+int comp_ams_get_gtilde(comp_ams_t *h, float *out, int on_device)
+{
+    int rc = check_handle(h);
+    if (rc || (rc = need_cd(h))) return rc;
+    return copy_out(h, out, h->gtil, (size_t)h->d, on_device);
+}
+
+int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
+{
+    int rc = check_handle(h);
+    if (rc || (rc = need_cd(h))) return rc;
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    return copy_out(h, out_host, h->scales_srv, (size_t)h->tb.n_blocks, 0);
+}
+
+int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const float *ghat_server, const float *gtilde,
+                              int on_device)
+{
+    int rc = check_handle(h);
+    if (rc || (rc = need_cd(h))) return rc;
+    const size_t d = (size_t)h->d;
+    if (ghat_server && (rc = copy_in(h, h->ghat_srv, ghat_server, d, on_device))) return rc;
+    if (gtilde && (rc = copy_in(h, h->gtil, gtilde, d, on_device))) return rc;
+    if (ghat_workers) {
+        HIP_TRY(h, hipMemcpy2DAsync(h->e, (size_t)h->ld * sizeof(float), ghat_workers, d * sizeof(float),
+                                    d * sizeof(float), (size_t)h->n,
+                                    on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, h->stream));
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        h->pending = false;   // the rows hold ghat_i itself
+    }
     return COMP_AMS_OK;
 }
 
