@@ -40,7 +40,7 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
 }
 
 
-def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:
+def kernel_algorithmic_bytes(name: str, n: int, d: int, cd: bool = False) -> int:
     """Algorithmic bytes of one launch = per-unit figure x units (n*d worker-coordinates).
     The streaming pass of either compressor carries the 12 B per (worker, coordinate) of the
     method (read g, read the stored error / Markov vector, write it back); the update kernel carries
@@ -51,10 +51,14 @@ def kernel_algorithmic_bytes(name: str, n: int, d: int) -> int:
     return {
         "bs_pass": 12 * nd,
         "bs_update": 32 * d,
-        "tk_pass1": 12 * nd,
+        # CD-Adam with Top-k only reads g and ghat_i in the pass (ghat_i changes on the k kept coordinates)
+        "tk_pass1": (8 if cd else 12) * nd,
         "tk_final": 32 * d,
         "bs_server": 12 * d,
         "bs_apply": 40 * d,
+        "tk_merge": 8 * d,
+        "tk_pass1_server": 8 * d,
+        "tk_apply": 40 * d,
     }.get(name, 0)
 
 
@@ -68,7 +72,7 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--method", choices=("ef", "cd"), default="ef",
-                    help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1 (block-sign workloads)")
+                    help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -102,7 +106,9 @@ def main() -> int:
     if cd:
         h.set_method(P.METHOD_CD)
         h.set_eps_mode(1)                     # Algorithm 1 keeps nu inside the root
-    step_bytes = w.algorithmic_bytes() + (20 * w.d if cd else 0)   # CD-Adam: + ghat r/w, gtilde r, gtilde r/w
+    step_bytes = w.algorithmic_bytes()
+    if cd:                                    # + ghat r/w, gtilde r, gtilde r/w; Top-k: ghat_i is not rewritten
+        step_bytes += 20 * w.d - (4 * w.n * w.d if w.compressor == W.TOPK else 0)
 
     def run(k0, count):
         for t in range(k0, k0 + count):
@@ -125,7 +131,7 @@ def main() -> int:
     kernels = {name: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.steps,
                       "us_per_step": ms * 1e3 / args.steps} for name, (ms, cnt) in prof.items()}
     dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
-    dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d)
+    dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d, cd)
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,

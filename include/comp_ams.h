@@ -127,7 +127,7 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
 
 /*
  * CD-Adam, Section 5, Algorithm 1.  Chooses the method of a handle before its first step
- * (COMP_AMS_ESTATE afterwards); built for BLOCKSIGN handles (COMP_AMS_EINVAL otherwise).  With
+ * (COMP_AMS_ESTATE afterwards).  With
  * COMP_AMS_METHOD_CD one comp_ams_step computes, with the handle's compressor C in both directions,
  *   c_i     = C(g_i - ghat_i) ;  ghat_i = ghat_i + c_i          workers, lines 5-6
  *   ghat    = ghat + (1/n) sum_i c_i                            server, line 8 (ascending i, one division)
@@ -135,9 +135,11 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
  *   m, v, vhat, theta: the AMSGrad update of the step above with gtilde in the place of gbar
  * starting from ghat_i = ghat = gtilde = 0 (line 1: both compressors map 0 to 0).  Algorithm 1
  * places nu inside the root: that is eps mode 1, which this call does not select by itself.
- * Allocates the server's vectors (2 d floats and d/8 bytes of sign bits); the rows that held the
- * error memory are cleared and hold ghat_i from then on, so comp_ams_get_error and the e argument
- * of comp_ams_set_state answer COMP_AMS_ESTATE on such a handle.
+ * Allocates the server's vectors (2 d floats) and the buffers of its compression (d/8 bytes of sign
+ * bits, or a second set of Top-k selection buffers); the rows that held the error memory are
+ * cleared and hold ghat_i from then on, so comp_ams_get_error and the e argument of
+ * comp_ams_set_state answer COMP_AMS_ESTATE on such a handle.  comp_ams_get_selected then gives the
+ * kept coordinates of c_i (values of g_i - ghat_i).
  */
 int comp_ams_set_method(comp_ams_t *h, int32_t method);
 
@@ -149,6 +151,10 @@ int comp_ams_get_gtilde(comp_ams_t *h, float *out, int on_device);
 /* CD handles with BLOCKSIGN, after at least one step: the n_blocks scales of the server's message
  * c of the last step (host array); comp_ams_get_scales gives those of the workers' c_i. */
 int comp_ams_get_server_scales(comp_ams_t *h, float *out_host);
+
+/* CD handles with TOPK, after at least one step: the k coordinates the server kept in the last step
+ * (host arrays, ascending index; values of ghat - gtilde), as comp_ams_get_selected does for a worker. */
+int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_host);
 
 /* CD handles, checkpoint resume: ghat_i as [n][d] row-major, ghat and gtilde of d floats; any
  * pointer may be NULL to leave that array as it is (m, v, vhat go through comp_ams_set_state). */

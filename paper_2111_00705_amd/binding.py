@@ -28,7 +28,7 @@ EXPORTS = [
     "comp_ams_n_blocks", "comp_ams_set_state", "comp_ams_sync", "comp_ams_last_error", "comp_ams_profile",
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
-    "comp_ams_get_server_scales", "comp_ams_set_markov_state",
+    "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
         L.comp_ams_get_gtilde.argtypes = [vp, fp, C.c_int]
         L.comp_ams_get_server_scales.argtypes = [vp, fp]
         L.comp_ams_set_markov_state.argtypes = [vp, fp, fp, fp, C.c_int]
+        L.comp_ams_get_server_selected.argtypes = [vp, u32p, fp]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
         _lib = L
@@ -165,6 +166,13 @@ class CompAms:
 
     def get_gtilde(self, out=None):
         return self._get_vec(lib().comp_ams_get_gtilde, out)
+
+    def get_server_selected(self):
+        idx = np.empty(self.k, dtype=np.uint32)
+        val = np.empty(self.k, dtype=np.float32)
+        self._check(lib().comp_ams_get_server_selected(self._h, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                                       val.ctypes.data))
+        return idx, val
 
     def get_server_scales(self):
         out = np.empty(self.n_blocks(), dtype=np.float32)

@@ -74,6 +74,11 @@ struct comp_ams {
     uint2 *dense_dir = nullptr;                // [n][64 * parts * 4] {start, count} of each wavefront's piece
     uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
+    // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
+    TkSide srv{};
+    uint32_t *hist1_s = nullptr, *histf_s = nullptr;
+    uint64_t *dense_s = nullptr;
+    uint2 *dense_dir_s = nullptr;
 
     // optional per-kernel timing with HIP events on the step's stream
     bool prof_on = false;
@@ -83,10 +88,12 @@ struct comp_ams {
 namespace {
 
 enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
-                P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_SLOTS };
+                P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_TK_MERGE, P_TK_PASS1_SERVER,
+                P_TK_SELECT_SERVER, P_TK_APPLY, P_SLOTS };
 const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
                                          "tk_relist", "tk_compact", "tk_resolve", "tk_final", "bs_server",
-                                         "bs_scale_server", "bs_apply"};
+                                         "bs_scale_server", "bs_apply", "tk_merge", "tk_pass1_server", "tk_select_server",
+                                         "tk_apply"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -321,29 +328,43 @@ int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
     return COMP_AMS_OK;
 }
 
+// The five selection launches between the listing pass and the kernel that uses Tc: candidate
+// histograms, leading digits, second listing (rare), compaction of the threshold bin, last digits.
+// kSrc / a / b say how tk_relist forms the compressed vector again.
+template <int kSrc>
+void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
+                   uint4 *tile_dir, uint16_t *oct_rows, uint16_t *below_rows, uint32_t *hist1, uint32_t *histf,
+                   uint64_t *dense, uint2 *dense_dir, const float *a, const float *b, const int (&slot)[5])
+{
+    const dim3 shared(ge.slices * ge.parts, ge.n);
+    launch_timed(h, slot[0], st, [&] { tk_hist<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, hist1, histf); });
+    launch_timed(h, slot[1], st, [&] {
+        tk_pick<<<ge.n, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, oct_rows, below_rows);
+    });
+    launch_timed(h, slot[2], st, [&] {
+        tk_relist<kSrc><<<dim3(ge.relist_wgs, ge.n), kThreads, 0, st>>>(a, b, ge, ws, cand, cursor, tile_dir);
+    });
+    launch_timed(h, slot[3], st, [&] {
+        tk_compact<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, dense, dense_dir);
+    });
+    launch_timed(h, slot[4], st, [&] {
+        tk_resolve<<<ge.n, kResolveThreads, 0, st>>>(ge, ws, dense, dense_dir, cursor);
+    });
+}
+
+constexpr int kWorkerSelectSlots[5] = {P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT, P_TK_RESOLVE};
+constexpr int kServerSelectSlots[5] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER,
+                                       P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
+
 int step_topk(comp_ams *h, const float *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
-    const dim3 tiles(ge.n_tiles, h->n), shared(kSlices * ge.parts, h->n);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<<<tiles, kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows,
-                                             h->below_rows);
+        tk_pass1<kPassEf><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+                                                                       h->tile_dir, h->oct_rows, h->below_rows);
     });
-    launch_timed(h, P_TK_HIST, st, [&] {
-        tk_hist<<<shared, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cursor, h->hist1, h->histf);
-    });
-    launch_timed(h, P_TK_PICK, st, [&] {
-        tk_pick<<<h->n, kThreads, 0, st>>>(ge, h->ws, h->hist1, h->histf, h->cursor, h->oct_rows, h->below_rows);
-    });
-    launch_timed(h, P_TK_RELIST, st, [&] {
-        tk_relist<<<dim3(ge.relist_wgs, h->n), kThreads, 0, st>>>(h->e, ge, h->ws, h->cand, h->cursor, h->tile_dir);
-    });
-    launch_timed(h, P_TK_COMPACT, st, [&] {
-        tk_compact<<<shared, kThreads, 0, st>>>(ge, h->ws, h->cand, h->cursor, h->dense, h->dense_dir);
-    });
-    launch_timed(h, P_TK_RESOLVE, st, [&] {
-        tk_resolve<<<h->n, kResolveThreads, 0, st>>>(ge, h->ws, h->dense, h->dense_dir, h->cursor);
-    });
+    launch_select<kSrcStored>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows, h->below_rows, h->hist1,
+                              h->histf, h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
@@ -351,10 +372,49 @@ int step_topk(comp_ams *h, const float *g, hipStream_t st)
     return COMP_AMS_OK;
 }
 
-// Resets the per-worker selection records: no pending threshold, no guess.
-int reset_topk_workers(comp_ams *h)
+// One iteration of Algorithm 1 (CD-Adam) with Top-k in both directions, fourteen launches.
+int step_topk_cd(comp_ams *h, const float *g, hipStream_t st)
 {
-    std::vector<TkWorker> init((size_t)h->n);
+    const TkGeom &ge = h->ge;
+    const TkSide &sv = h->srv;
+    launch_timed(h, P_TK_PASS1, st, [&] {
+        tk_pass1<kPassCd><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+                                                                       h->tile_dir, h->oct_rows, h->below_rows);
+    });
+    launch_select<kSrcGrad>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows, h->below_rows, h->hist1,
+                            h->histf, h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
+    launch_timed(h, P_TK_MERGE, st, [&] {
+        tk_merge<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
+                                                  h->params.n_workers);
+    });
+    launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
+        tk_pass1<kPassDiff><<<dim3(ge.n_tiles, 1), kThreads, 0, st>>>(h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
+                                                                      sv.cursor, sv.tile_dir, sv.oct_rows,
+                                                                      sv.below_rows);
+    });
+    launch_select<kSrcDiff>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, sv.oct_rows, sv.below_rows,
+                            h->hist1_s, h->histf_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil,
+                            kServerSelectSlots);
+    launch_timed(h, P_TK_APPLY, st, [&] {
+        tk_apply<<<ge.n_tiles, kThreads, 0, st>>>(sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+    });
+    return COMP_AMS_OK;
+}
+
+// Candidate regions per vector and what follows from it: tiles per region, and the pieces a region
+// is cut into for tk_hist / tk_compact - about 4096 candidates per workgroup when 1.5 k of them are
+// listed, within the kMaxPieces records tk_resolve can walk.
+void set_slices(TkGeom &ge, int slices)
+{
+    ge.slices = slices;
+    ge.slice_tiles = (ge.n_tiles + slices - 1) / slices;
+    const int64_t want = (3 * (int64_t)ge.k / 2 + (int64_t)slices * 4096 - 1) / ((int64_t)slices * 4096);
+    ge.parts = (int32_t)std::min<int64_t>({(int64_t)kMaxParts, (int64_t)kMaxPieces / (4 * slices), std::max<int64_t>(1, want)});
+}
+
+// Initial selection records: no pending threshold, no guess.
+void fresh_tk_workers(std::vector<TkWorker> &init)
+{
     for (auto &w : init) {
         std::memset(&w, 0, sizeof w);
         w.guess = kNoGuess;
@@ -362,8 +422,19 @@ int reset_topk_workers(comp_ams *h)
         w.last_fine = kNoGuess;
         w.tc = kNoThreshold;
     }
+}
+
+// Resets the per-worker selection records: no pending threshold, no guess.
+int reset_topk_workers(comp_ams *h)
+{
+    std::vector<TkWorker> init((size_t)h->n);
+    fresh_tk_workers(init);
     HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
-    HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * kSlices * sizeof(uint32_t)));
+    HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * h->ge.slices * sizeof(uint32_t)));
+    if (h->srv.ws) {
+        HIP_TRY(h, hipMemcpy(h->srv.ws, init.data(), sizeof(TkWorker), hipMemcpyHostToDevice));
+        HIP_TRY(h, hipMemset(h->srv.cursor, 0, (size_t)h->srv.ge.slices * sizeof(uint32_t)));
+    }
     return COMP_AMS_OK;
 }
 
@@ -373,7 +444,10 @@ void launch_materialize(comp_ams *h, int worker, float *dst)
 {
     const float *xrow = h->e + (size_t)worker * (size_t)h->ld;
     const unsigned blocks = (unsigned)((h->d + kThreads - 1) / kThreads);
-    if (h->compressor == COMP_AMS_TOPK) {
+    if (h->compressor == COMP_AMS_TOPK && h->method == COMP_AMS_METHOD_CD) {
+        // ghat_i is stored as it is (tk_merge has already added c_i)
+        (void)hipMemcpyAsync(dst, xrow, (size_t)h->d * sizeof(float), hipMemcpyDeviceToDevice, h->stream);
+    } else if (h->compressor == COMP_AMS_TOPK) {
         tk_materialize_error<<<blocks, kThreads, 0, h->stream>>>(xrow, h->ge, h->ws + worker, dst);
     } else if (h->method == COMP_AMS_METHOD_CD) {
         const uint16_t *srow = h->signs + (size_t)worker * (size_t)(h->ld / kTile) * kThreads;
@@ -469,23 +543,20 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int ib = 1;
         while (((int64_t)1 << ib) < d) ++ib;
         ge.idx_bits = ib;
-        ge.slice_tiles = (ge.n_tiles + kSlices - 1) / kSlices;
-        // tk_hist / tk_compact: about 4096 candidates per workgroup when 1.5 k of them are listed
-        ge.parts = (int32_t)std::min<int64_t>(kMaxParts,
-                                              std::max<int64_t>(1, (3 * k_or_block / 2 + kSlices * 4096 - 1) / (kSlices * 4096)));
+        set_slices(ge, kMinSlices);
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
-        const size_t region_entries = (size_t)n * kSlices * (size_t)ge.slice_tiles * kTile;
+        const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.slice_tiles * kTile;
         if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * kSlices)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * ge.slices)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->oct_rows, segs * kOctaves)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->below_rows, segs * kBelow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * kSlices * ge.parts * 4)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * ge.slices * ge.parts * 4)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
@@ -574,7 +645,7 @@ int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream)
         h->stream = st;
     }
     if (h->compressor == COMP_AMS_TOPK)
-        rc = step_topk(h, grads_dev, st);
+        rc = (h->method == COMP_AMS_METHOD_CD) ? step_topk_cd(h, grads_dev, st) : step_topk(h, grads_dev, st);
     else
         rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
     if (rc) return rc;
@@ -619,17 +690,14 @@ int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
     return COMP_AMS_OK;
 }
 
-int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host)
+namespace {
+// The kept (index, value) pairs of one vector's last selection, sorted by index, to host arrays.
+int gather_selected(comp_ams *h, const TkGeom &ge, int worker, const TkWorker *ws, const uint2 *cand,
+                    const uint4 *tile_dir, uint32_t *idx_host, float *val_host)
 {
-    int rc = check_handle(h);
-    if (rc) return rc;
-    if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
-    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
-    if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
-    const TkGeom &ge = h->ge;
     const size_t k = (size_t)ge.k;
     HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
-    tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, worker, h->ws, h->cand, h->tile_dir, h->sel_count,
+    tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, worker, ws, cand, tile_dir, h->sel_count,
                                                               h->sel_out_idx, h->sel_out_val);
     HIP_TRY(h, hipGetLastError());
     uint32_t total = 0;
@@ -648,6 +716,27 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
         if (val_host) val_host[r] = val[order[r]];
     }
     return COMP_AMS_OK;
+}
+}  // namespace
+
+int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
+    return gather_selected(h, h->ge, worker, h->ws, h->cand, h->tile_dir, idx_host, val_host);
+}
+
+int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_host)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (h->compressor != COMP_AMS_TOPK || h->method != COMP_AMS_METHOD_CD)
+        return fail(h, COMP_AMS_ESTATE, "get_server_selected needs a TOPK handle set to CD-Adam");
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    return gather_selected(h, h->srv.ge, 0, h->srv.ws, h->srv.cand, h->srv.tile_dir, idx_host, val_host);
 }
 
 int comp_ams_get_scales(comp_ams_t *h, float *out_host)
@@ -752,14 +841,37 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
     if (method != COMP_AMS_METHOD_EF && method != COMP_AMS_METHOD_CD) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
     if (method == h->method) return COMP_AMS_OK;
     if (h->steps != 0) return fail(h, COMP_AMS_ESTATE, "the method can only be chosen before the first step");
-    if (h->compressor != COMP_AMS_BLOCKSIGN)
-        return fail(h, COMP_AMS_EINVAL, "CD-Adam is built for the BLOCKSIGN compressor only");
     if (method == COMP_AMS_METHOD_CD && !h->ghat_srv) {
         const size_t ld = (size_t)h->ld;
-        if ((rc = dev_alloc_t(h, h->allocs, &h->ghat_srv, ld)) || (rc = dev_alloc_t(h, h->allocs, &h->gtil, ld)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->signs_srv, ld / 16)))
+        if ((rc = dev_alloc_t(h, h->allocs, &h->ghat_srv, ld)) || (rc = dev_alloc_t(h, h->allocs, &h->gtil, ld)))
             return rc;
+        if (h->compressor == COMP_AMS_BLOCKSIGN) {
+            if ((rc = dev_alloc_t(h, h->allocs, &h->signs_srv, ld / 16))) return rc;
+        } else {
+            TkSide &sv = h->srv;
+            sv.ge = h->ge;
+            sv.ge.n = 1;
+            sv.ge.relist_wgs = (int32_t)std::min<int64_t>(sv.ge.n_tiles, 2048);
+            // one vector, all tiles: enough regions that a cursor sees few tens of atomic adds
+            int slices = kMinSlices;
+            while (slices < kMaxSlices && sv.ge.n_tiles / slices > 32) slices *= 2;
+            set_slices(sv.ge, slices);
+            const size_t tiles = (size_t)sv.ge.n_tiles;
+            const size_t region_entries = (size_t)sv.ge.slices * (size_t)sv.ge.slice_tiles * kTile;
+            if ((rc = dev_alloc_t(h, h->allocs, &sv.ws, 1)) ||
+                (rc = dev_alloc_t(h, h->allocs, &sv.cand, region_entries, false)) ||
+                (rc = dev_alloc_t(h, h->allocs, &sv.cursor, (size_t)sv.ge.slices)) ||
+                (rc = dev_alloc_t(h, h->allocs, &sv.tile_dir, tiles)) ||
+                (rc = dev_alloc_t(h, h->allocs, &sv.oct_rows, tiles * kOctaves)) ||
+                (rc = dev_alloc_t(h, h->allocs, &sv.below_rows, tiles * kBelow)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->hist1_s, (size_t)kBins1)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->histf_s, (size_t)kFineWindow)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->dense_s, region_entries, false)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->dense_dir_s, (size_t)sv.ge.slices * sv.ge.parts * 4)))
+                return rc;
+        }
     }
+    if (h->compressor == COMP_AMS_TOPK && (rc = reset_topk_workers(h))) return rc;
     // the stored rows change their meaning (error memory <-> Markov sequence): start both from zero
     HIP_TRY(h, hipMemsetAsync(h->e, 0, (size_t)h->ld * (size_t)h->n * sizeof(float), h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
@@ -806,6 +918,7 @@ int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
 {
     int rc = check_handle(h);
     if (rc || (rc = need_cd(h))) return rc;
+    if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_server_scales needs a BLOCKSIGN handle");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     return copy_out(h, out_host, h->scales_srv, (size_t)h->tb.n_blocks, 0);
 }
@@ -825,7 +938,7 @@ int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const fl
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         h->pending = false;   // the rows hold ghat_i itself
     }
-    return COMP_AMS_OK;
+    return COMP_AMS_OK;   // the Top-k guesses are left as they are: a guess is only a hint
 }
 
 int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream)

@@ -54,14 +54,14 @@ constexpr int kBelow = 16;        // coarse bins counted per tile at and just be
 constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
-constexpr int kSlices = 64;       // candidate regions per worker
-constexpr int kMaxParts = 8;      // pieces a region is cut into for tk_hist / tk_compact
+constexpr int kMinSlices = 64;    // candidate regions per vector: a power of two in [kMinSlices, kMaxSlices]
+constexpr int kMaxSlices = 512;
+constexpr int kMaxParts = 8;      // pieces a region is cut into for tk_hist / tk_compact, at most
 constexpr int kResolveThreads = 1024;
 constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothing (before the first step)
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
 
-static_assert(kSlices == kWave, "tk_pick and tk_resolve handle one region cursor per lane");
 
 struct TkWorker {
     uint64_t tc;            // threshold composite of the last finished step (pending selection)
@@ -81,7 +81,8 @@ struct TkGeom {
     int32_t n, n_tiles;
     int32_t idx_bits;       // IB
     uint32_t k;
-    int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / kSlices)
+    int32_t slices;         // candidate regions per vector (see region_base)
+    int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / slices)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
 };
@@ -193,9 +194,11 @@ __device__ __forceinline__ int owner_of(const uint32_t *pre, int count, uint32_t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Where candidates live.  Each worker owns kSlices regions of the candidate array; tile t appends to
-// region t mod kSlices, so workgroups that run at the same time (neighbouring tiles) use different
-// cursors.  A tile takes its space with one atomic add on the region's cursor and records
+// Where candidates live.  Each worker owns ge.slices regions of the candidate array; tile t appends
+// to region t mod slices, so workgroups that run at the same time (neighbouring tiles) use different
+// cursors.  Atomic adds on one cursor serialise at about a microsecond each, so a kernel of T tiles per
+// vector lasts at least T / slices microseconds: a single long vector (CD-Adam's server) takes more
+// regions than each of many workers.  A tile takes its space with one atomic add on the region's cursor and records
 // {offset, counts of its four wavefronts, total} in the tile directory; inside the tile's space the
 // candidates stand wavefront by wavefront.  A region can hold every coordinate of its tiles.  The order
 // of the tiles inside a region depends on timing; nothing downstream depends on it (comp values are
@@ -203,7 +206,7 @@ __device__ __forceinline__ int owner_of(const uint32_t *pre, int count, uint32_t
 // kernel 10 - 20 % slower (8-byte pieces scattered over gigabytes).
 __device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int slice)
 {
-    return ((int64_t)worker * kSlices + slice) * ge.slice_tiles * kTile;
+    return ((int64_t)worker * ge.slices + slice) * ge.slice_tiles * kTile;
 }
 
 // First half of moving a tile's staged candidates (count per wavefront, in LDS) to its region: the
@@ -217,7 +220,7 @@ __device__ __forceinline__ void flush_begin(uint32_t count, uint32_t *sh, int al
     __syncthreads();
     if (tid == allocator) {
         const uint32_t total = sh[0] + sh[1] + sh[2] + sh[3];
-        const uint32_t at = total ? atomicAdd(cursor + i * kSlices + (t & (kSlices - 1)), total) : 0u;
+        const uint32_t at = total ? atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total) : 0u;
         sh[4] = at;
         // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
         tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), total);
@@ -230,14 +233,34 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t off = sh[4];
     for (int w = 0; w < wave; ++w) off += sh[w];
-    uint2 *dst = cand + region_base(ge, i, t & (kSlices - 1)) + off;
+    uint2 *dst = cand + region_base(ge, i, t & (ge.slices - 1)) + off;
     // the wavefront reads back its own LDS writes: no barrier needed for those
     for (uint32_t q = lane; q < count; q += kWave) dst[q] = stage[q];
 }
 
+// Counts one element of the vector that is compressed in the tile's histogram and, if its fine bin
+// reaches the guess, stages it as a candidate.
+__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, uint32_t *lh, uint2 *stage,
+                                         uint32_t &count)
+{
+    const uint32_t key = mag_key(x);
+    // bin 0 (zeros and the smallest denormals) is not counted here but obtained as the remainder in
+    // finish_tile: a sparse vector would send most of a tile's atomics to that one LDS word
+    if (valid && (key >> kShift1) != 0) atomicAdd(&lh[key >> kShift1], 1u);
+    const bool hit = valid && (key >> kFineShift) >= guess;
+    const uint32_t slot = wave_append(hit, count);
+    if (hit) stage[slot] = make_uint2(j, __float_as_uint(x));
+}
+
 // One tile of one worker.  kFull: the whole tile lies below d.  Candidates are staged in LDS (one
 // list per wavefront, which owns kSub coordinates of the tile, so it cannot overflow).
-template <bool kFull>
+// Modes: kPassEf  error feedback: x = g + e, written back over the stored vector;
+//        kPassCd  CD-Adam worker (Algorithm 1, line 5): u = g - ghat_i, nothing written back (ghat_i
+//                 changes only where c_i is not zero; tk_merge does that);
+//        kPassDiff  CD-Adam server (line 9): w = ghat - gtilde, both padded rows, nothing written back.
+enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2 };
+
+template <bool kFull, int kMode>
 __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
                                                uint32_t *lh, uint2 *stage)
@@ -247,7 +270,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (tid + kThreads * r);
-        gv[r] = load_grad4(grow, j, d);
+        gv[r] = kMode == kPassDiff ? ld4(grow + j) : load_grad4(grow, j, d);
         xv[r] = ld4(xrow + j);
     }
     uint32_t count = 0;
@@ -259,24 +282,67 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
         float x[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            // e = x_old - C(x_old): +0 where the previous step kept the coordinate
-            const float e = was_kept(kt, mag_key(xo[c]), j + c) ? 0.f : xo[c];
-            x[c] = (kFull || j + c < d) ? fadd(gg[c], e) : 0.f;
+            if (kMode != kPassEf) {
+                x[c] = (kFull || j + c < d) ? fsub(gg[c], xo[c]) : 0.f;
+            } else {
+                // e = x_old - C(x_old): +0 where the previous step kept the coordinate
+                const float e = was_kept(kt, mag_key(xo[c]), j + c) ? 0.f : xo[c];
+                x[c] = (kFull || j + c < d) ? fadd(gg[c], e) : 0.f;
+            }
         }
-        st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
+        if (kMode == kPassEf) st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const bool valid = kFull || j + c < d;
-            const uint32_t key = mag_key(x[c]);
-            if (valid) atomicAdd(&lh[key >> kShift1], 1u);
-            const bool hit = valid && (key >> kFineShift) >= guess;
-            const uint32_t slot = wave_append(hit, count);
-            if (hit) stage[slot] = make_uint2(j + c, __float_as_uint(x[c]));
-        }
+        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, lh, stage, count);
     }
     return count;
 }
 
+// End of a tile, for every kernel that lists candidates with a histogram: takes the tile's space in
+// its region, writes the two small fallback rows, copies the staged candidates.
+// What is kept of the histogram (a tile holds 4096 < 65536 elements): the 256 exponent bins, and
+// the kBelow coarse bins that end with the guess's own - enough to place a threshold that fell
+// up to two octaves below the guess; both are read only when the guess turns out too high.
+// One store instruction each, while another wavefront waits for the cursor.
+__device__ __forceinline__ void finish_tile(const uint32_t *lh, const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count,
+                                            uint32_t guess, const TkGeom &ge, int i, int t,
+                                            uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
+                                            uint4 *__restrict__ tile_dir, uint16_t *__restrict__ oct_rows,
+                                            uint16_t *__restrict__ below_rows)
+{
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int64_t tile_id = (int64_t)i * ge.n_tiles + t;
+    flush_begin(count, sh, 3 * kWave, ge, i, t, cursor, tile_dir);   // barrier inside: lh is complete
+    if (wave < 2) {
+        // bin 0 = the tile's coordinates below d minus all other bins; each of the two wavefronts
+        // works it out for itself (lh[0] itself stays 0)
+        const int l = tid & 63;
+        uint32_t others = 0;
+        for (int b = l; b < kBins1; b += kWave) others += lh[b];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) others += __shfl_xor(others, off, kWave);
+        const uint32_t bin0 = (uint32_t)min((int64_t)kTile, ge.d - (int64_t)t * kTile) - others;
+        if (wave == 0) {
+            // lane l: exponent bins 4l .. 4l+3, each the sum of 8 coarse bins
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = 0;
+#pragma unroll
+                for (int q = 0; q < kBins1 / kOctaves; ++q) o[e] += lh[(4 * l + e) * (kBins1 / kOctaves) + q];
+            }
+            if (l == 0) o[0] += bin0;
+            reinterpret_cast<uint2 *>(oct_rows + tile_id * kOctaves)[l] =
+                make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+        } else if (l < kBelow) {
+            const int b = (int)(min(guess, kNoGuess - 1) >> (kShift1 - kFineShift)) - (kBelow - 1) + l;
+            below_rows[tile_id * kBelow + l] = (uint16_t)(b > 0 ? lh[b] : (b == 0 ? bin0 : 0u));
+        }
+    }
+    flush_end(stage[wave], count, sh, ge, i, t, cand);
+}
+
+template <int kMode>
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
@@ -294,38 +360,15 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
     const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
-    const int64_t tile_id = (int64_t)i * ge.n_tiles + t;
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
     __syncthreads();
     uint32_t count;
+    const float *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
-        count = pass1_tile<true>(g + (int64_t)i * ge.d, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
+        count = pass1_tile<true, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
     else
-        count = pass1_tile<false>(g + (int64_t)i * ge.d, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
-    flush_begin(count, sh, 3 * kWave, ge, i, t, cursor, tile_dir);   // barrier inside: lh is complete
-    // what is kept of the histogram (a tile holds 4096 < 65536 elements): the 256 exponent bins, and
-    // the kBelow coarse bins that end with the guess's own - enough to place a threshold that fell
-    // up to two octaves below the guess; both are read only when the guess turns out too high.
-    // One store instruction each, while another wavefront waits for the cursor.
-    if (wave == 0) {
-        // lane l: exponent bins 4l .. 4l+3, each the sum of 8 coarse bins
-        uint32_t o[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            o[e] = 0;
-#pragma unroll
-            for (int q = 0; q < kBins1 / kOctaves; ++q) o[e] += lh[(4 * tid + e) * (kBins1 / kOctaves) + q];
-        }
-        reinterpret_cast<uint2 *>(oct_rows + tile_id * kOctaves)[tid] =
-            make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
-    } else if (wave == 1) {
-        const int l = tid & 63;
-        if (l < kBelow) {
-            const int b = (int)(min(guess, kNoGuess - 1) >> (kShift1 - kFineShift)) - (kBelow - 1) + l;
-            below_rows[tile_id * kBelow + l] = (uint16_t)(b >= 0 ? lh[b] : 0u);
-        }
-    }
-    flush_end(stage[wave], count, sh, ge, i, t, cand);
+        count = pass1_tile<false, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
+    finish_tile(lh, stage, sh, count, guess, ge, i, t, cand, cursor, tile_dir, oct_rows, below_rows);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -340,7 +383,7 @@ __device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__re
     Piece p;
     p.slice = blockIdx.x / ge.parts;
     const uint32_t part = blockIdx.x % ge.parts;
-    const uint32_t count = cursor[worker * kSlices + p.slice];
+    const uint32_t count = cursor[worker * ge.slices + p.slice];
     const uint32_t chunk = (count + ge.parts - 1) / ge.parts;
     p.q0 = min(part * chunk, count);
     p.q1 = min(p.q0 + chunk, count);
@@ -409,8 +452,9 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
     if (wave == 0) {
-        // number of candidates of this worker = sum of its region cursors (kSlices = one per lane)
-        uint32_t c = cursor[i * kSlices + lane];
+        // number of candidates of this worker = sum of its region cursors
+        uint32_t c = 0;
+        for (int q = lane; q < ge.slices; q += kWave) c += cursor[i * ge.slices + q];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
         if (lane == 0) total_sh = c;
@@ -530,18 +574,26 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         ws[i].whole = (count == rank) ? 1u : 0u;
         ws[i].relisted = relist ? 1u : 0u;
     }
-    if (relist && tid < kSlices) cursor[i * kSlices + tid] = 0;   // tk_relist fills the regions anew
+    if (relist)
+        for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
     for (int b = tid; b < kBins1; b += kThreads) row[b] = 0;
     if (tid < kFineWindow) frow[tid] = 0;
 }
 
-// Only for workers whose guess was too high: lists the elements of the stored x whose magnitude
-// bits above pshift are >= the prefix, into the (emptied) regions of the worker.  A small grid whose
-// workgroups loop over tiles: in the usual case every workgroup returns at once, and a small grid
-// does that fast.
-__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ xs, TkGeom ge,
-                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
-                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
+// Only for workers whose guess was too high: lists the elements of the compressed vector whose
+// magnitude bits above pshift are >= the prefix, into the (emptied) regions of the worker.  A small
+// grid whose workgroups loop over tiles: in the usual case every workgroup returns at once, and a
+// small grid does that fast.  The vector is formed again from what is stored:
+//   kSrcStored  the stored x itself (error feedback)
+//   kSrcGrad    g - ghat_i, a = g (rows of d floats, any 4-byte alignment), b = ghat_i (CD-Adam workers)
+//   kSrcDiff    a - b, both padded rows (CD-Adam server: ghat - gtilde)
+enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2 };
+
+template <int kSrc>
+__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ a, const float *__restrict__ b,
+                                                      TkGeom ge, const TkWorker *__restrict__ ws,
+                                                      uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
+                                                      uint4 *__restrict__ tile_dir)
 {
     __shared__ uint2 stage[4][kSub];
     __shared__ uint32_t sh[5];
@@ -551,15 +603,23 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ 
     const int wave = tid >> 6;
     const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
     const uint32_t d = (uint32_t)ge.d;
-    const float *xrow = xs + (int64_t)i * ge.ld;
+    const float *arow = a + (int64_t)i * (kSrc == kSrcGrad ? ge.d : ge.ld);
+    const float *brow = kSrc == kSrcStored ? nullptr : b + (int64_t)i * ge.ld;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         uint32_t count = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t j = base + 4 * (tid + kThreads * r);
-            const float4 xv = ld4(xrow + j);
-            const float x[4] = {xv.x, xv.y, xv.z, xv.w};
+            const float4 av = kSrc == kSrcGrad ? load_grad4(arow, j, d) : ld4(arow + j);
+            float x[4] = {av.x, av.y, av.z, av.w};
+            if (kSrc != kSrcStored) {
+                const float4 bv = ld4(brow + j);
+                x[0] = fsub(x[0], bv.x);
+                x[1] = fsub(x[1], bv.y);
+                x[2] = fsub(x[2], bv.z);
+                x[3] = fsub(x[3], bv.w);
+            }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const bool hit = j + c < d && (mag_key(x[c]) >> pshift) >= prefix;
@@ -616,9 +676,9 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
 
 // ---------------------------------------------------------------------------------------------
 // One workgroup of 1024 threads per worker: the digits of Tc below the prefix, over the pieces
-// tk_compact filled (kSlices * parts * 4 <= 2 * kResolveThreads of them).  Hands the next step its
+// tk_compact filled (slices * parts * 4 <= 2 * kResolveThreads of them).  Hands the next step its
 // guess and empties the worker's region cursors for it.
-constexpr int kMaxPieces = kSlices * kMaxParts * 4;
+constexpr int kMaxPieces = 2048;   // slices * parts * 4 never exceeds this (the host picks parts accordingly)
 constexpr int kFew = 256;         // at most this many elements are ranked directly instead of by further digits
 static_assert(kMaxPieces <= 2 * kResolveThreads, "two pieces per thread in the prefix sum");
 
@@ -662,7 +722,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     int s_hi = (int)w.pshift + ge.idx_bits;
     bool done = w.whole != 0;
     uint64_t tc = prefix << s_hi;
-    const int pieces = kSlices * ge.parts * 4;
+    const int pieces = ge.slices * ge.parts * 4;
     const uint64_t *wdense = dense + region_base(ge, i, 0);
     uint32_t cnt = 0;
     if (!done) {
@@ -741,7 +801,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         }
         __syncthreads();
     }
-    if (tid < kSlices) cursor[i * kSlices + tid] = 0;          // tk_compact was their last reader
+    if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (tid == 0) {
         ws[i].tc = tc;
         // The next step lists from a few fine bins below this threshold: at least twice the distance
@@ -766,23 +826,18 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
 // the kept candidates are distinct).
 constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in flight at a time
 
-__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
-                                                     const uint2 *__restrict__ cand,
-                                                     const uint4 *__restrict__ tile_dir,
-                                                     float *__restrict__ theta, float *__restrict__ m,
-                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
+// Adds, for the calling wavefront's coordinates of tile t, the kept values (comp >= Tc_i) of all
+// workers into acc (LDS, kTile floats, zeroed by the caller for these coordinates) in ascending
+// worker order.  kScatter (CD-Adam, Algorithm 1, line 6): the kept value u = c_i[j] is also added to
+// ghat_i[j] in `rows` ([n][ld]); the old values are fetched for a whole batch before they are used.
+template <bool kScatter>
+__device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, const TkWorker *__restrict__ ws,
+                                              const uint2 *__restrict__ cand, const uint4 *__restrict__ tile_dir,
+                                              int t, float *__restrict__ rows)
 {
-    __shared__ float acc[kTile];
-    const int t = blockIdx.x;
-    const int slice = t & (kSlices - 1);
-    const int64_t base = (int64_t)t * kTile;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-
-#pragma unroll
-    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-
+    const int slice = t & (ge.slices - 1);
+    const uint32_t base = (uint32_t)t * kTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int w0 = 0; w0 < ge.n; w0 += kWave) {
         const int nw = min(kWave, ge.n - w0);
         // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
@@ -799,6 +854,8 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
         for (int wb = 0; wb < nw; wb += kFinBatch) {
             uint2 e[kFinBatch];
             uint32_t cnt[kFinBatch];
+            bool keep[kFinBatch];
+            float old[kFinBatch];
 #pragma unroll
             for (int u = 0; u < kFinBatch; ++u) {
                 const int w = min(wb + u, nw - 1);           // clamped: the copies past nw are not used
@@ -813,23 +870,36 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
                 const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
                 const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
                 const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
-                if ((uint32_t)lane < cnt[u]) {
+                keep[u] = (uint32_t)lane < cnt[u] && composite(__uint_as_float(e[u].y), e[u].x, ge.idx_bits) >= tc;
+                old[u] = 0.f;
+                if (kScatter && keep[u]) old[u] = rows[(int64_t)(w0 + w) * ge.ld + e[u].x];
+            }
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);
+                if (keep[u]) {
                     const float x = __uint_as_float(e[u].y);
-                    if (composite(x, e[u].x, ge.idx_bits) >= tc) {
-                        const uint32_t l = e[u].x - (uint32_t)base;
-                        acc[l] = fadd(acc[l], x);
-                    }
+                    const uint32_t l = e[u].x - base;
+                    acc[l] = fadd(acc[l], x);
+                    if (kScatter) rows[(int64_t)(w0 + w) * ge.ld + e[u].x] = fadd(old[u], x);
                 }
                 if (cnt[u] > (uint32_t)kWave) {
                     // more than 64 candidates of this worker in the wavefront's quarter of the tile (rare)
+                    const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
+                    const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
+                    const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
                     const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
                     const uint2 *src = cand + region_base(ge, w0 + w, slice) + start;
                     for (uint32_t q = kWave + lane; q < cnt[u]; q += kWave) {
                         const uint2 c = src[q];
                         const float x = __uint_as_float(c.y);
                         if (composite(x, c.x, ge.idx_bits) >= tc) {
-                            const uint32_t l = c.x - (uint32_t)base;
+                            const uint32_t l = c.x - base;
                             acc[l] = fadd(acc[l], x);
+                            if (kScatter) {
+                                float *gh = rows + (int64_t)(w0 + w) * ge.ld + c.x;
+                                *gh = fadd(*gh, x);
+                            }
                         }
                     }
                 }
@@ -837,6 +907,23 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
             }
         }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                     const uint2 *__restrict__ cand,
+                                                     const uint4 *__restrict__ tile_dir,
+                                                     float *__restrict__ theta, float *__restrict__ m,
+                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
+{
+    __shared__ float acc[kTile];
+    const int t = blockIdx.x;
+    const int64_t base = (int64_t)t * kTile;
+    const int tid = threadIdx.x;
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    sum_kept_tile<false>(acc, ge, ws, cand, tile_dir, t, nullptr);
 
     // the state is loaded only now: fewer live registers above (more workgroups per compute unit),
     // which measured faster than loading it first
@@ -857,6 +944,98 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
         const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
                                         fdiv(a.w, p.n_workers));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
+        st4(theta + j, th[r]);
+        st4(m + j, mm[r]);
+        st4(v + j, vv[r]);
+        st4(vhat + j, vh[r]);
+    }
+}
+
+// CD-Adam (Algorithm 1): selection buffers of the server's own Top-k - the same structures as the
+// workers', for a single vector.
+struct TkSide {
+    TkGeom ge;                 // n = 1
+    TkWorker *ws;
+    uint2 *cand;
+    uint32_t *cursor;
+    uint4 *tile_dir;
+    uint16_t *oct_rows, *below_rows;
+};
+
+// Per tile: ghat_i += c_i (line 6) and ghat += mean of the c_i (line 8).  The server's vector
+// w = ghat - gtilde (line 9) is then listed by tk_pass1<kPassDiff>.
+__global__ __launch_bounds__(kThreads) void tk_merge(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                     const uint2 *__restrict__ cand,
+                                                     const uint4 *__restrict__ tile_dir,
+                                                     float *__restrict__ ghat_rows, float *__restrict__ ghat,
+                                                     float n_workers)
+{
+    __shared__ float acc[kTile];
+    const int t = blockIdx.x;
+    const int64_t base = (int64_t)t * kTile;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    sum_kept_tile<true>(acc, ge, ws, cand, tile_dir, t, ghat_rows);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int l = 4 * (tid + kThreads * r);
+        const float4 a = ld4(acc + l), gh = ld4(ghat + base + l);
+        // padding coordinates: 0 + 0 / n
+        st4(ghat + base + l, make_float4(fadd(gh.x, fdiv(a.x, n_workers)), fadd(gh.y, fdiv(a.y, n_workers)),
+                                         fadd(gh.z, fdiv(a.z, n_workers)), fadd(gh.w, fdiv(a.w, n_workers))));
+    }
+}
+
+// CD-Adam (Algorithm 1), lines 10 and 12-16: gtilde += c, c = the kept coordinates of w, then the
+// AMSGrad update with gtilde.  Per tile; each wavefront handles its own coordinates.
+__global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restrict__ gtil, float *__restrict__ theta,
+                                                     float *__restrict__ m, float *__restrict__ v,
+                                                     float *__restrict__ vhat, AmsParams p)
+{
+    __shared__ float acc[kTile];
+    const int t = blockIdx.x;
+    const int64_t base = (int64_t)t * kTile;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    {
+        const uint4 rec = sv.tile_dir[t];
+        const uint32_t c[4] = {rec.y & 0xffffu, rec.y >> 16, rec.z & 0xffffu, rec.z >> 16};
+        uint32_t start = rec.x;
+        for (int q = 0; q < wave; ++q) start += c[q];
+        const uint64_t tc = sv.ws[0].tc;
+        const uint2 *src = sv.cand + region_base(sv.ge, 0, t & (sv.ge.slices - 1)) + start;
+        for (uint32_t q = lane; q < c[wave]; q += kWave) {
+            const uint2 e = src[q];
+            const float x = __uint_as_float(e.y);
+            if (composite(x, e.x, sv.ge.idx_bits) >= tc) acc[e.x - (uint32_t)base] = x;   // distinct coordinates
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    float4 gt[4], th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        gt[r] = ld4(gtil + j);
+        th[r] = ld4(theta + j);
+        mm[r] = ld4(m + j);
+        vv[r] = ld4(v + j);
+        vh[r] = ld4(vhat + j);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int l = 4 * (tid + kThreads * r);
+        const int64_t j = base + l;
+        const float4 c4 = ld4(acc + l);
+        // c is +0 where nothing was kept; gtilde + 0 = gtilde
+        const float4 g4 = make_float4(fadd(gt[r].x, c4.x), fadd(gt[r].y, c4.y), fadd(gt[r].z, c4.z),
+                                      fadd(gt[r].w, c4.w));
+        amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
+        st4(gtil + j, g4);
         st4(theta + j, th[r]);
         st4(m + j, mm[r]);
         st4(v + j, vv[r]);
@@ -892,7 +1071,7 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     const int t = blockIdx.x;
     const uint64_t tc = ws[worker].tc;
     const uint4 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
-    const uint2 *src = cand + region_base(ge, worker, t & (kSlices - 1)) + rec.x;
+    const uint2 *src = cand + region_base(ge, worker, t & (ge.slices - 1)) + rec.x;
     for (uint32_t q0 = 0; q0 < rec.w; q0 += kThreads) {      // uniform over the workgroup
         const uint32_t q = q0 + threadIdx.x;
         uint2 c = make_uint2(0u, 0u);

@@ -198,10 +198,6 @@ def test_cd_resume_determinism_device_getters_and_status_codes():
     with pytest.raises(P.CompAmsError) as ei:
         a.get_ghat_worker(n)
     assert ei.value.code == P.EINVAL
-    t = P.CompAms(100, 2, P.TOPK, 5)
-    with pytest.raises(P.CompAmsError) as ei:
-        t.set_method(P.METHOD_CD)
-    assert ei.value.code == P.EINVAL
     e = P.CompAms(100, 2, P.BLOCKSIGN, 10)
     for call in (lambda: e.get_gtilde(), lambda: e.get_ghat_worker(0), lambda: e.get_server_scales(),
                  lambda: e.set_markov_state(gtilde=np.zeros(100, f32))):
@@ -211,7 +207,7 @@ def test_cd_resume_determinism_device_getters_and_status_codes():
     with pytest.raises(P.CompAmsError) as ei:
         e.set_method(7)
     assert ei.value.code == P.EINVAL
-    a.destroy(); c.destroy(); t.destroy(); e.destroy()
+    a.destroy(); c.destroy(); e.destroy()
 
 
 def test_cd_block_table_change_between_steps():
@@ -231,3 +227,141 @@ def test_cd_block_table_change_between_steps():
         ora.step(g)
         exact = compare_cd(gpu, ora, f"after step {t}", exact)
     gpu.destroy()
+
+
+# ------------------------------------------------------------------------------- CD-Adam with Top-k
+# Bars: kept index sets and kept values of the workers and of the server, ghat_i, ghat and gtilde
+# bit-exact; theta, m, v, vhat within 1e-6 relative per coordinate.
+
+def make_cd_topk_pair(d, n, k, theta0=None, eps_mode=1):
+    gpu = P.CompAms(d, n, P.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR)
+    ora = O.Oracle(d, n, O.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR, method=O.CD)
+    gpu.set_method(P.METHOD_CD)
+    if theta0 is not None:
+        gpu.set_theta(np.ascontiguousarray(theta0, dtype=f32))
+        ora.set_theta(theta0)
+    gpu.set_eps_mode(eps_mode)
+    ora.set_eps_mode(eps_mode)
+    return gpu, ora
+
+
+def run_cd_topk(gpu, ora, grads_fn, steps, tag):
+    for t in range(steps):
+        g = grads_fn(t)
+        u = g - ora.ghat_workers                       # what the workers compress in this step
+        w_prev = ora.gtilde.copy()
+        gpu.step(torch_dev(g))
+        ora.step(g)
+        for i in range(gpu.n):
+            idx, val = gpu.get_selected(i)
+            assert np.array_equal(idx, ora.selected[i]), f"{tag} step {t} worker {i}: kept index set differs"
+            assert np.array_equal(bits(val), bits(u[i][idx])), f"{tag} step {t} worker {i}: kept values differ"
+            assert np.array_equal(bits(gpu.get_ghat_worker(i)), bits(ora.ghat_workers[i])), f"{tag} step {t} ghat_{i}"
+        assert np.array_equal(bits(gpu.get_ghat_server()), bits(ora.ghat_server)), f"{tag} step {t} ghat"
+        idx, val = gpu.get_server_selected()
+        assert np.array_equal(idx, ora.server_selected), f"{tag} step {t}: server's kept index set differs"
+        assert np.array_equal(bits(val), bits((ora.ghat_server - w_prev)[idx])), f"{tag} step {t}: server's kept values"
+        assert np.array_equal(bits(gpu.get_gtilde()), bits(ora.gtilde)), f"{tag} step {t} gtilde"
+        for name, got, want in (("theta", gpu.get_theta(), ora.theta), ("m", gpu.get_m(), ora.m),
+                                ("v", gpu.get_v(), ora.v), ("vhat", gpu.get_vhat(), ora.vhat)):
+            ok = rel_close(got, want, STATE_RTOL)
+            assert ok.all(), f"{tag} step {t} {name}: {np.count_nonzero(~ok)} coordinates beyond {STATE_RTOL}"
+
+
+def test_cd_topk_golden_example_c_on_gpu():
+    announce("CD-Adam golden example C (Top-k)")
+    ex = json.load(open(os.path.join(GOLD, "example_c_cd_adam_topk.json")))
+    g = np.array(ex["g"], f32)
+    h = P.CompAms(ex["d"], ex["n"], P.TOPK, ex["k"])
+    h.set_method(P.METHOD_CD)
+    gd = torch_dev(g)
+    for t, want in enumerate(ex["steps"]):
+        h.step(gd)
+        for i in range(ex["n"]):
+            assert np.array_equal(bits(h.get_ghat_worker(i)), bits(np.array(want["ghat_workers"][i], f32))), (t, i)
+        assert np.array_equal(bits(h.get_ghat_server()), bits(np.array(want["ghat_server"], f32))), t
+        assert h.get_server_selected()[0].tolist() == want["server_selected"], t
+        assert np.array_equal(bits(h.get_gtilde()), bits(np.array(want["gtilde"], f32))), t
+    h.destroy()
+
+
+@pytest.mark.parametrize("d,n,k", [(1, 1, 1), (5, 3, 5), (63, 2, 7), (4097, 2, 41), (10_007, 5, 100),
+                                   (3 * 4096, 4, 123), (20_000, 3, 20_000), (300_003, 4, 3000)])
+def test_cd_topk_small_shapes(d, n, k):
+    announce(f"CD-Adam Top-k d={d} n={n} k={k}")
+    rng = np.random.default_rng(d * 17 + n)
+    scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    gpu, ora = make_cd_topk_pair(d, n, k, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    run_cd_topk(gpu, ora, lambda t: (np.random.default_rng([d, 3, t]).standard_normal((n, d)) * scale + 0.2 * scale).astype(f32),
+                steps=5, tag=f"d={d}")
+    gpu.destroy()
+
+
+def test_cd_topk_scale_jumps_ties_and_many_workers():
+    announce("CD-Adam Top-k jumps / ties / n=70")
+    n, d, k = 4, 150_001, 1500
+    rng = np.random.default_rng(41)
+    base_scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    factors = [1.0, 1.0, 300.0, 1e-4, 1e-4, 1.0, 1.003, 20.0, 1.0]
+    gpu, ora = make_cd_topk_pair(d, n, k)
+    run_cd_topk(gpu, ora, lambda t: (np.random.default_rng([41, t]).standard_normal((n, d)).astype(f32) * base_scale
+                                     * f32(factors[t])).astype(f32), steps=len(factors), tag="jumps")
+    gpu.destroy()
+    vals = np.array([0.125, 0.25, -0.25, 0.5, -0.5, 1.0], f32)
+    n, d, k = 3, 100_003, 25_000
+    gpu, ora = make_cd_topk_pair(d, n, k, eps_mode=0)
+    run_cd_topk(gpu, ora, lambda t: vals[np.random.default_rng([42, t]).integers(0, vals.size, (n, d))], steps=3, tag="ties")
+    gpu.destroy()
+    n, d, k = 70, 9000, 17
+    gpu, ora = make_cd_topk_pair(d, n, k)
+    run_cd_topk(gpu, ora, lambda t: np.random.default_rng([43, t]).standard_normal((n, d)).astype(f32), steps=3, tag="n=70")
+    gpu.destroy()
+
+
+def test_cd_topk_on_the_resnet_sized_workload_scaled():
+    w = W.get(2).scaled(300_003, n=16)
+    announce(f"CD-Adam Top-k on {w.name}")
+    s = w.scales()
+    gpu, ora = make_cd_topk_pair(w.d, w.n, w.k, theta0=w.theta0())
+    run_cd_topk(gpu, ora, lambda t: w.grads(t, scales=s), steps=5, tag=w.name)
+    gpu.destroy()
+
+
+def test_cd_topk_resume_and_status_codes():
+    announce("CD-Adam Top-k resume")
+    d, n, k = 25_003, 3, 250
+    grads = [np.random.default_rng([6, t]).standard_normal((n, d)).astype(f32) for t in range(6)]
+
+    def fresh():
+        h = P.CompAms(d, n, P.TOPK, k)
+        h.set_method(P.METHOD_CD)
+        return h
+
+    def state(h):
+        return [h.get_theta(), h.get_m(), h.get_v(), h.get_vhat(), h.get_ghat_server(), h.get_gtilde()] + \
+               [h.get_ghat_worker(i) for i in range(n)]
+
+    a = fresh()
+    for g in grads:
+        a.step(torch_dev(g))
+    b = fresh()
+    for g in grads[:3]:
+        b.step(torch_dev(g))
+    saved = state(b)
+    b.destroy()
+    c = fresh()
+    c.set_theta(saved[0])
+    c.set_state(m=saved[1], v=saved[2], vhat=saved[3])
+    c.set_markov_state(ghat_workers=np.stack(saved[6:]), ghat_server=saved[4], gtilde=saved[5])
+    for g in grads[3:]:
+        c.step(torch_dev(g))
+    for x, y in zip(state(a), state(c)):
+        assert np.array_equal(bits(x), bits(y))
+    with pytest.raises(P.CompAmsError) as ei:
+        a.get_server_scales()
+    assert ei.value.code == P.ESTATE
+    ef = P.CompAms(d, n, P.TOPK, k)
+    with pytest.raises(P.CompAmsError) as ei:
+        ef.get_server_selected()
+    assert ei.value.code == P.ESTATE
+    a.destroy(); c.destroy(); ef.destroy()
