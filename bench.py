@@ -27,16 +27,23 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
 # HBM-side bytes per launch (fetched + written) of the dominant kernels, from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (calibrated on probe_copy), keyed by
-# (workload name, kernel); absent = not measured.
+# (workload name, kernel), CD-Adam runs by (workload name + "/cd", kernel); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
     ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 234.5e6,
     ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.6e6,
-    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2202.0e6,
+    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2201.7e6,
     ("cfg2_topk_n16_d11173962", "tk_final"): 391.8e6,
     ("cfg3_layersign_n32_d25557032", "bs_pass"): 9975.9e6,
     ("cfg3_layersign_n32_d25557032", "bs_update"): 921.8e6,
-    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10716.4e6,
-    ("cfg4_topk_n8_d110000000", "tk_final"): 3584.2e6,
+    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10716.3e6,
+    ("cfg4_topk_n8_d110000000", "tk_final"): 3584.0e6,
+    ("cfg1_blocksign4096_n16_d1199882/cd", "bs_pass"): 236.8e6,
+    ("cfg1_blocksign4096_n16_d1199882/cd", "bs_apply"): 48.4e6,
+    ("cfg2_topk_n16_d11173962/cd", "tk_pass1"): 1497.2e6,
+    ("cfg2_topk_n16_d11173962/cd", "tk_merge"): 386.0e6,
+    ("cfg2_topk_n16_d11173962/cd", "tk_apply"): 450.1e6,
+    ("cfg3_layersign_n32_d25557032/cd", "bs_pass"): 10075.4e6,
+    ("cfg3_layersign_n32_d25557032/cd", "bs_apply"): 1026.7e6,
 }
 
 
@@ -136,7 +143,7 @@ def main() -> int:
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None if cd else MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name + ("/cd" if cd else ""), dom)),
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
