@@ -66,8 +66,7 @@ struct comp_ams {
     uint2 *cand = nullptr;                     // [n][64 regions][slice_tiles * 4096] candidate (index, value bits)
     uint32_t *cursor = nullptr;                // [n][64] entries in each region (zero between steps)
     uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in its region, counts per wavefront, total}
-    uint16_t *oct_rows = nullptr;              // [n][n_tiles][256] per-tile histograms of the magnitude exponent
-    uint16_t *below_rows = nullptr;            // [n][n_tiles][16] per-tile counts of the coarse bins below the guess
+    uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
@@ -76,7 +75,7 @@ struct comp_ams {
     float *sel_out_val = nullptr;
     // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
     TkSide srv{};
-    uint32_t *hist1_s = nullptr, *histf_s = nullptr;
+    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr;
     uint64_t *dense_s = nullptr;
     uint2 *dense_dir_s = nullptr;
 
@@ -333,22 +332,25 @@ int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
 // kSrc / a / b say how tk_relist forms the compressed vector again.
 template <int kSrc>
 void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
-                   uint4 *tile_dir, uint16_t *oct_rows, uint16_t *below_rows, uint32_t *hist1, uint32_t *histf,
-                   uint64_t *dense, uint2 *dense_dir, const float *a, const float *b, const int (&slot)[5])
+                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint64_t *dense,
+                   uint2 *dense_dir, const float *a, const float *b, const int (&slot)[5])
 {
-    const dim3 shared(ge.slices * ge.parts, ge.n);
+    const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
+    // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
+    // the whole vector after a miss) are kept to about two per compute unit in total
+    const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
     launch_timed(h, slot[0], st, [&] { tk_hist<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, hist1, histf); });
     launch_timed(h, slot[1], st, [&] {
-        tk_pick<<<ge.n, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, oct_rows, below_rows);
+        tk_pick<kSrc><<<pick, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, hist_full, a, b);
     });
     launch_timed(h, slot[2], st, [&] {
-        tk_relist<kSrc><<<dim3(ge.relist_wgs, ge.n), kThreads, 0, st>>>(a, b, ge, ws, cand, cursor, tile_dir);
+        tk_relist<kSrc><<<sweep, kThreads, 0, st>>>(a, b, ge, ws, hist_full, cand, cursor, tile_dir);
     });
     launch_timed(h, slot[3], st, [&] {
         tk_compact<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, dense, dense_dir);
     });
     launch_timed(h, slot[4], st, [&] {
-        tk_resolve<<<ge.n, kResolveThreads, 0, st>>>(ge, ws, dense, dense_dir, cursor);
+        tk_resolve<<<ge.n, kResolveThreads, 0, st>>>(ge, ws, dense, dense_dir, cursor, hist_full);
     });
 }
 
@@ -361,10 +363,10 @@ int step_topk(comp_ams *h, const float *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
         tk_pass1<kPassEf><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
-                                                                       h->tile_dir, h->oct_rows, h->below_rows);
+                                                                       h->tile_dir);
     });
-    launch_select<kSrcStored>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows, h->below_rows, h->hist1,
-                              h->histf, h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
+    launch_select<kSrcStored>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                              h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
@@ -379,22 +381,20 @@ int step_topk_cd(comp_ams *h, const float *g, hipStream_t st)
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
         tk_pass1<kPassCd><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
-                                                                       h->tile_dir, h->oct_rows, h->below_rows);
+                                                                       h->tile_dir);
     });
-    launch_select<kSrcGrad>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->oct_rows, h->below_rows, h->hist1,
-                            h->histf, h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
+    launch_select<kSrcGrad>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                            h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         tk_merge<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
         tk_pass1<kPassDiff><<<dim3(ge.n_tiles, 1), kThreads, 0, st>>>(h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
-                                                                      sv.cursor, sv.tile_dir, sv.oct_rows,
-                                                                      sv.below_rows);
+                                                                      sv.cursor, sv.tile_dir);
     });
-    launch_select<kSrcDiff>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, sv.oct_rows, sv.below_rows,
-                            h->hist1_s, h->histf_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil,
-                            kServerSelectSlots);
+    launch_select<kSrcDiff>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
+                            h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         tk_apply<<<ge.n_tiles, kThreads, 0, st>>>(sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
     });
@@ -551,8 +551,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
             (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * ge.slices)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->oct_rows, segs * kOctaves)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->below_rows, segs * kBelow)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->hist_full, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
@@ -862,8 +861,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
                 (rc = dev_alloc_t(h, h->allocs, &sv.cand, region_entries, false)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.cursor, (size_t)sv.ge.slices)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.tile_dir, tiles)) ||
-                (rc = dev_alloc_t(h, h->allocs, &sv.oct_rows, tiles * kOctaves)) ||
-                (rc = dev_alloc_t(h, h->allocs, &sv.below_rows, tiles * kBelow)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->hist_full_s, (size_t)kBins1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->hist1_s, (size_t)kBins1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->histf_s, (size_t)kFineWindow)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->dense_s, region_entries, false)) ||

@@ -17,17 +17,16 @@
 //               x; lists "candidates" - elements whose fine magnitude bin (top 17 bits, 0.2 % wide)
 //               is >= the worker's guess, which is the previous step's threshold minus a little
 //               slack - as (index, value) pairs, staged in LDS and appended densely to one of 64
-//               regions of the worker (one atomic add per tile); writes the tile's histogram of
-//               magnitude exponents (only read if the guess turns out too high).
+//               regions of the worker (one atomic add per tile).
 //               A workgroup per tile (instead of a loop over tiles) matters: on this chip a wave
 //               that loops must wait for its stores before it can use its next loads.
 //   tk_hist     histograms of the candidates: coarse bins (top 11 bits) and the fine bins of the
 //               two coarse bins around the guess
-//   tk_pick     one workgroup per worker: coarse and fine bin of the k-th largest; with fewer than
-//               k candidates (always on the first step) the guess was too high: the coarse bin is
-//               then taken from per-tile counts of the bins just below the guess, or the octave
-//               from the exponent histograms
-//   tk_relist   only for such workers: candidates are listed again from the stored x
+//   tk_pick     coarse and fine bin of the k-th largest (one workgroup per worker); with fewer than
+//               k candidates (always on the first step) the guess was too high: then many workgroups
+//               count the whole vector into a full coarse histogram instead
+//   tk_relist   only for such workers: the coarse bin from that histogram, and the candidates are
+//               listed again from the stored x
 //   tk_compact  candidates in the threshold bin are copied, as comp values, to dense pieces (one
 //               per wavefront)
 //   tk_resolve  one workgroup per worker: the remaining digits of Tc over those pieces, and the
@@ -36,8 +35,8 @@
 //               values are added into an LDS copy of the tile in ascending worker order; then
 //               gbar = acc / n and the AMSGrad update of the tile's theta, m, v, vhat
 //
-// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written + 1/8 B of exponent
-// histogram, plus the candidates (about 1.2 k per worker, 8 B each, written once, read three times).
+// Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
+// (about 1.2 k per worker, 8 B each, written once, read three times).
 #pragma once
 #include "device_utils.h"
 
@@ -48,9 +47,6 @@ constexpr int kShift1 = 20;
 constexpr int kFineShift = 14;    // fine bin: top 17 bits; 64 fine bins per coarse bin
 constexpr int kFinePerCoarse = 1 << (kShift1 - kFineShift);
 constexpr int kFineWindow = 2 * kFinePerCoarse;   // fine bins counted: the guess's coarse bin and the next
-constexpr int kOctShift = 23;     // exponent ("octave") bin: top 8 bits
-constexpr int kOctaves = 256;
-constexpr int kBelow = 16;        // coarse bins counted per tile at and just below the guess (two octaves)
 constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
@@ -69,7 +65,7 @@ struct TkWorker {
     uint32_t slack;         // fine bins kept between the threshold and the next guess
     // leading digits of the running step's Tc, written by tk_pick, read by the kernels after it
     uint32_t prefix;        // magnitude bits above pshift
-    uint32_t pshift;        // kFineShift, kShift1 or kOctShift: how many low magnitude bits are still open
+    uint32_t pshift;        // kFineShift or kShift1: how many low magnitude bits are still open
     uint32_t rank;          // 1-based rank (from the top) of the k-th largest among elements with this prefix
     uint32_t whole;         // all elements with this prefix are kept: Tc needs no further digit
     uint32_t relisted;      // the guess was above the threshold: candidates are listed again
@@ -238,16 +234,10 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
     for (uint32_t q = lane; q < count; q += kWave) dst[q] = stage[q];
 }
 
-// Counts one element of the vector that is compressed in the tile's histogram and, if its fine bin
-// reaches the guess, stages it as a candidate.
-__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, uint32_t *lh, uint2 *stage,
-                                         uint32_t &count)
+// Stages one element of the vector that is compressed as a candidate if its fine bin reaches the guess.
+__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, uint2 *stage, uint32_t &count)
 {
-    const uint32_t key = mag_key(x);
-    // bin 0 (zeros and the smallest denormals) is not counted here but obtained as the remainder in
-    // finish_tile: a sparse vector would send most of a tile's atomics to that one LDS word
-    if (valid && (key >> kShift1) != 0) atomicAdd(&lh[key >> kShift1], 1u);
-    const bool hit = valid && (key >> kFineShift) >= guess;
+    const bool hit = valid && (mag_key(x) >> kFineShift) >= guess;
     const uint32_t slot = wave_append(hit, count);
     if (hit) stage[slot] = make_uint2(j, __float_as_uint(x));
 }
@@ -263,7 +253,7 @@ enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2 };
 template <bool kFull, int kMode>
 __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
-                                               uint32_t *lh, uint2 *stage)
+                                               uint2 *stage)
 {
     const int tid = threadIdx.x;
     float4 gv[4], xv[4];
@@ -292,64 +282,54 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
         }
         if (kMode == kPassEf) st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
-        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, lh, stage, count);
+        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, stage, count);
     }
     return count;
 }
 
-// End of a tile, for every kernel that lists candidates with a histogram: takes the tile's space in
-// its region, writes the two small fallback rows, copies the staged candidates.
-// What is kept of the histogram (a tile holds 4096 < 65536 elements): the 256 exponent bins, and
-// the kBelow coarse bins that end with the guess's own - enough to place a threshold that fell
-// up to two octaves below the guess; both are read only when the guess turns out too high.
-// One store instruction each, while another wavefront waits for the cursor.
-__device__ __forceinline__ void finish_tile(const uint32_t *lh, const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count,
-                                            uint32_t guess, const TkGeom &ge, int i, int t,
-                                            uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                            uint4 *__restrict__ tile_dir, uint16_t *__restrict__ oct_rows,
-                                            uint16_t *__restrict__ below_rows)
+// End of a tile in tk_pass1.  No workgroup barrier: a wavefront that is done registers itself, and
+// whichever of the four comes last does the rest for the whole tile - takes the tile's space in its
+// region (one atomic add), writes the directory record and copies all staged candidates.  The other
+// three leave at once instead of waiting for the atomic.
+// sh: 5 LDS words, sh[4] zeroed (with a barrier after it) before the first wavefront can get here.
+__device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count, const TkGeom &ge,
+                                            int i, int t, uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
+                                            uint4 *__restrict__ tile_dir)
 {
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6;
-    const int64_t tile_id = (int64_t)i * ge.n_tiles + t;
-    flush_begin(count, sh, 3 * kWave, ge, i, t, cursor, tile_dir);   // barrier inside: lh is complete
-    if (wave < 2) {
-        // bin 0 = the tile's coordinates below d minus all other bins; each of the two wavefronts
-        // works it out for itself (lh[0] itself stays 0)
-        const int l = tid & 63;
-        uint32_t others = 0;
-        for (int b = l; b < kBins1; b += kWave) others += lh[b];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) others += __shfl_xor(others, off, kWave);
-        const uint32_t bin0 = (uint32_t)min((int64_t)kTile, ge.d - (int64_t)t * kTile) - others;
-        if (wave == 0) {
-            // lane l: exponent bins 4l .. 4l+3, each the sum of 8 coarse bins
-            uint32_t o[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                o[e] = 0;
-#pragma unroll
-                for (int q = 0; q < kBins1 / kOctaves; ++q) o[e] += lh[(4 * l + e) * (kBins1 / kOctaves) + q];
-            }
-            if (l == 0) o[0] += bin0;
-            reinterpret_cast<uint2 *>(oct_rows + tile_id * kOctaves)[l] =
-                make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
-        } else if (l < kBelow) {
-            const int b = (int)(min(guess, kNoGuess - 1) >> (kShift1 - kFineShift)) - (kBelow - 1) + l;
-            below_rows[tile_id * kBelow + l] = (uint16_t)(b > 0 ? lh[b] : (b == 0 ? bin0 : 0u));
-        }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // this wavefront's staged candidates are complete before it registers
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    uint32_t arrived = 0;
+    if (lane == 0) {
+        sh[wave] = count;
+        arrived = __hip_atomic_fetch_add(&sh[4], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
-    flush_end(stage[wave], count, sh, ge, i, t, cand);
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
+    if (arrived != 3) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    const uint32_t cnt[4] = {sh[0], sh[1], sh[2], sh[3]};
+    const uint32_t total = cnt[0] + cnt[1] + cnt[2] + cnt[3];
+    uint32_t at = 0;
+    if (lane == 0) {
+        if (total) at = atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total);
+        // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
+        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), total);
+    }
+    at = __builtin_amdgcn_readfirstlane(at);
+    uint2 *dst = cand + region_base(ge, i, t & (ge.slices - 1)) + at;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        for (uint32_t q = lane; q < cnt[w]; q += kWave) dst[q] = stage[w][q];
+        dst += cnt[w];
+    }
 }
 
 template <int kMode>
 __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
-                                                     uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
-                                                     uint16_t *__restrict__ oct_rows,
-                                                     uint16_t *__restrict__ below_rows)
+                                                     uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
-    __shared__ uint32_t lh[kBins1];   // this tile's coarse-bin histogram
     __shared__ uint2 stage[4][kSub];
     __shared__ uint32_t sh[5];
     const int t = blockIdx.x;
@@ -360,15 +340,15 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
     const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
-    for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
+    if (tid == 0) sh[4] = 0;
     __syncthreads();
     uint32_t count;
     const float *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
-        count = pass1_tile<true, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
+        count = pass1_tile<true, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
     else
-        count = pass1_tile<false, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, lh, stage[wave]);
-    finish_tile(lh, stage, sh, count, guess, ge, i, t, cand, cursor, tile_dir, oct_rows, below_rows);
+        count = pass1_tile<false, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
+    finish_tile(stage, sh, count, ge, i, t, cand, cursor, tile_dir);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -434,20 +414,56 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
 }
 
 // ---------------------------------------------------------------------------------------------
-// One workgroup per worker: the leading digits of Tc.  Consumes (and clears) the candidate
-// histograms.
+// How a kernel forms the vector that is compressed again from what is stored:
+//   kSrcStored  the stored x itself (error feedback)
+//   kSrcGrad    g - ghat_i, a = g (rows of d floats, any 4-byte alignment), b = ghat_i (CD-Adam workers)
+//   kSrcDiff    a - b, both padded rows (CD-Adam server: ghat - gtilde)
+enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2 };
+
+// The 16 values of this thread in the tile at `base` (coordinates base + 4 (tid + 256 r) + c).
+template <int kSrc>
+__device__ __forceinline__ void load_source_tile(float (&x)[4][4], const float *__restrict__ arow,
+                                                 const float *__restrict__ brow, uint32_t base, uint32_t d)
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t j = base + 4 * (threadIdx.x + kThreads * r);
+        const float4 av = kSrc == kSrcGrad ? load_grad4(arow, j, d) : ld4(arow + j);
+        x[r][0] = av.x;
+        x[r][1] = av.y;
+        x[r][2] = av.z;
+        x[r][3] = av.w;
+        if (kSrc != kSrcStored) {
+            const float4 bv = ld4(brow + j);
+            x[r][0] = fsub(x[r][0], bv.x);
+            x[r][1] = fsub(x[r][1], bv.y);
+            x[r][2] = fsub(x[r][2], bv.z);
+            x[r][3] = fsub(x[r][3], bv.w);
+        }
+    }
+}
+
+// The leading digits of Tc.  Grid (P, n).  In the usual case the worker's candidates number at least k,
+// so the k-th largest is among them: workgroup 0 finds its coarse and (if the window covers it) fine
+// bin from the candidate histograms, and the other workgroups return at once.  With fewer than k
+// candidates (always on the first step, else when the threshold fell through the slack) the guess was
+// too high and nothing below it is known: then all P workgroups count the whole vector into the
+// worker's full coarse histogram, and tk_relist, which runs next, takes the coarse bin from it.
+// Bin 0 (zeros and the smallest denormals) is not counted but taken as the remainder: in a sparse
+// vector it would draw most LDS atomics of a tile to one word.
+// Consumes (and clears) the candidate histograms.
+template <int kSrc>
 __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
                                                     uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
-                                                    uint32_t *__restrict__ cursor,
-                                                    const uint16_t *__restrict__ oct_rows,
-                                                    const uint16_t *__restrict__ below_rows)
+                                                    uint32_t *__restrict__ cursor, uint32_t *__restrict__ hist_full,
+                                                    const float *__restrict__ a, const float *__restrict__ b)
 {
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
     __shared__ uint32_t res[4];
     __shared__ uint32_t fres[3];
     __shared__ uint32_t total_sh;
-    const int i = blockIdx.x;
+    const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
@@ -463,19 +479,18 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
     const uint32_t total = total_sh;
     uint32_t *row = hist1 + (int64_t)i * kBins1;
     uint32_t *frow = histf + (int64_t)i * kFineWindow;
-    uint32_t prefix, pshift, rank, count;
-    bool relist;
 
     if (total >= ge.k) {
+        if (blockIdx.x != 0) return;
         // every element at or above the guess is listed and there are at least k of them: the k-th
         // largest is a candidate and the candidate histograms locate it
-        for (int b = tid; b < kBins1; b += kThreads) lh[b] = row[b];
+        for (int q = tid; q < kBins1; q += kThreads) lh[q] = row[q];
         __syncthreads();
         find_rank_bin(lh, part, res, kBins1, ge.k);
-        prefix = res[0];                            // coarse bin of the k-th largest
-        pshift = kShift1;
-        rank = ge.k - res[1];
-        count = res[2];
+        uint32_t prefix = res[0];                   // coarse bin of the k-th largest
+        uint32_t pshift = kShift1;
+        uint32_t rank = ge.k - res[1];
+        uint32_t count = res[2];
         const uint32_t wb = guess >> (kShift1 - kFineShift);      // first coarse bin of the fine window
         if (prefix - wb < 2u) {
             // the fine histogram covers this coarse bin: pick the fine bin as well (one wavefront)
@@ -501,132 +516,110 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
             rank -= fres[1];
             count = fres[2];
         }
-        relist = false;
-    } else {
-        // the guess was too high.  Elements above the guess's coarse bin wb are all candidates, so
-        // their counts are exact; for wb and the kBelow-1 coarse bins under it the tiles kept full
-        // counts.  If the k-th largest lies there its coarse bin is found; otherwise (a threshold
-        // that fell by more than two octaves) the exponent histograms give its octave.
-        const uint32_t wb = min(guess, kNoGuess - 1) >> (kShift1 - kFineShift);
-        uint32_t above = 0;                                   // candidates in coarse bins > wb
-        for (uint32_t b = wb + 1 + tid; b < (uint32_t)kBins1; b += kThreads) above += row[b];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) above += __shfl_xor(above, off, kWave);
-        if (lane == 0) part[wave] = above;
-        __syncthreads();
-        above = part[0] + part[1] + part[2] + part[3];
-        // full count of coarse bin wb - b over all tiles, for b < kBelow: thread (tid / kBelow,
-        // tid % kBelow) sums every 16th tile, then lh[b] collects the 16 partial sums
-        uint32_t c = 0;
-        if (guess < kNoGuess) {
-            const uint16_t *brow = below_rows + (int64_t)i * ge.n_tiles * kBelow + (kBelow - 1 - tid % kBelow);
-#pragma unroll 4
-            for (int t = tid / kBelow; t < ge.n_tiles; t += kThreads / kBelow) c += brow[(int64_t)t * kBelow];
-        }
-        __syncthreads();                       // part[] has been read
-        lh[kBelow + tid] = c;
-        __syncthreads();
-        if (tid < kBelow) {
-            uint32_t sum = 0;
-            for (int q = 0; q < kThreads / kBelow; ++q) sum += lh[kBelow + q * kBelow + tid];
-            lh[tid] = sum;
-        }
-        __syncthreads();
+        __syncthreads();   // every thread has read the histograms before they are cleared
         if (tid == 0) {
-            res[3] = 0;
-            uint32_t cum = above;
-            for (int b = 0; b < kBelow && (int)wb - b >= 0 && guess < kNoGuess; ++b) {
-                if (cum + lh[b] >= ge.k) {
-                    res[0] = wb - b;
-                    res[1] = cum;
-                    res[2] = lh[b];
-                    res[3] = 1;
-                    break;
-                }
-                cum += lh[b];
-            }
+            ws[i].prefix = prefix;
+            ws[i].pshift = pshift;
+            ws[i].rank = rank;
+            ws[i].whole = (count == rank) ? 1u : 0u;
+            ws[i].relisted = 0u;
         }
-        __syncthreads();
-        if (res[3]) {
-            prefix = res[0];
-            pshift = kShift1;
-        } else {
-            __syncthreads();
-            const uint16_t *orow = oct_rows + (int64_t)i * ge.n_tiles * kOctaves + tid;
-            uint32_t o = 0;
-#pragma unroll 8
-            for (int t = 0; t < ge.n_tiles; ++t) o += orow[(int64_t)t * kOctaves];   // independent loads
-            lh[tid] = o;
-            __syncthreads();
-            find_rank_bin(lh, part, res, kOctaves, ge.k);   // the histograms hold all d >= k elements
-            prefix = res[0];
-            pshift = kOctShift;
-        }
-        rank = ge.k - res[1];
-        count = res[2];
-        relist = true;
+        for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
+        if (tid < kFineWindow) frow[tid] = 0;
+        return;
     }
-    __syncthreads();   // every thread has read the histograms before they are cleared
-    if (tid == 0) {
-        ws[i].prefix = prefix;
-        ws[i].pshift = pshift;
-        ws[i].rank = rank;
-        ws[i].whole = (count == rank) ? 1u : 0u;
-        ws[i].relisted = relist ? 1u : 0u;
-    }
-    if (relist)
-        for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
-    for (int b = tid; b < kBins1; b += kThreads) row[b] = 0;
-    if (tid < kFineWindow) frow[tid] = 0;
-}
 
-// Only for workers whose guess was too high: lists the elements of the compressed vector whose
-// magnitude bits above pshift are >= the prefix, into the (emptied) regions of the worker.  A small
-// grid whose workgroups loop over tiles: in the usual case every workgroup returns at once, and a
-// small grid does that fast.  The vector is formed again from what is stored:
-//   kSrcStored  the stored x itself (error feedback)
-//   kSrcGrad    g - ghat_i, a = g (rows of d floats, any 4-byte alignment), b = ghat_i (CD-Adam workers)
-//   kSrcDiff    a - b, both padded rows (CD-Adam server: ghat - gtilde)
-enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2 };
-
-template <int kSrc>
-__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ a, const float *__restrict__ b,
-                                                      TkGeom ge, const TkWorker *__restrict__ ws,
-                                                      uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                                      uint4 *__restrict__ tile_dir)
-{
-    __shared__ uint2 stage[4][kSub];
-    __shared__ uint32_t sh[5];
-    const int i = blockIdx.y;
-    if (!ws[i].relisted) return;
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6;
-    const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    // the guess was too high: count the whole vector (tk_relist continues from the full histogram)
+    for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
+    __syncthreads();
     const uint32_t d = (uint32_t)ge.d;
     const float *arow = a + (int64_t)i * (kSrc == kSrcGrad ? ge.d : ge.ld);
     const float *brow = kSrc == kSrcStored ? nullptr : b + (int64_t)i * ge.ld;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
-        uint32_t count = 0;
+        float x[4][4];
+        load_source_tile<kSrc>(x, arow, brow, base, d);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t j = base + 4 * (tid + kThreads * r);
-            const float4 av = kSrc == kSrcGrad ? load_grad4(arow, j, d) : ld4(arow + j);
-            float x[4] = {av.x, av.y, av.z, av.w};
-            if (kSrc != kSrcStored) {
-                const float4 bv = ld4(brow + j);
-                x[0] = fsub(x[0], bv.x);
-                x[1] = fsub(x[1], bv.y);
-                x[2] = fsub(x[2], bv.z);
-                x[3] = fsub(x[3], bv.w);
-            }
+        for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bool hit = j + c < d && (mag_key(x[c]) >> pshift) >= prefix;
-                const uint32_t slot = wave_append(hit, count);
-                if (hit) stage[wave][slot] = make_uint2(j + c, __float_as_uint(x[c]));
+                const uint32_t bin = mag_key(x[r][c]) >> kShift1;
+                if (bin != 0 && base + 4 * (tid + kThreads * r) + c < d) atomicAdd(&lh[bin], 1u);
             }
+    }
+    __syncthreads();
+    for (int q = tid; q < kBins1; q += kThreads) {
+        const uint32_t c = lh[q];
+        if (c) atomicAdd(hist_full + (int64_t)i * kBins1 + q, c);
+    }
+    if (blockIdx.x == 0) {
+        if (tid == 0) ws[i].relisted = 1u;
+        for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
+        for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
+        if (tid < kFineWindow) frow[tid] = 0;
+    }
+}
+
+// Only for workers whose guess was too high: takes the coarse bin of the k-th largest from the full
+// histogram tk_pick has just counted (every workgroup works it out for itself; workgroup 0 records
+// it) and lists the elements in that bin or above into the (emptied) regions of the worker.  A small
+// grid whose workgroups loop over tiles: in the usual case every workgroup returns at once, and a
+// small grid does that fast.
+template <int kSrc>
+__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ a, const float *__restrict__ b,
+                                                      TkGeom ge, TkWorker *__restrict__ ws,
+                                                      const uint32_t *__restrict__ hist_full,
+                                                      uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
+                                                      uint4 *__restrict__ tile_dir)
+{
+    __shared__ uint2 stage[4][kSub];
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t part[kThreads / kWave];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t sh[5];
+    const int i = blockIdx.y;
+    if (!ws[i].relisted) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const uint32_t d = (uint32_t)ge.d;
+    {
+        uint32_t counted = 0;
+        for (int q = tid; q < kBins1; q += kThreads) {
+            const uint32_t c = hist_full[(int64_t)i * kBins1 + q];
+            lh[q] = c;
+            counted += c;
         }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) counted += __shfl_xor(counted, off, kWave);
+        if (lane == 0) part[wave] = counted;
+        __syncthreads();
+        if (tid == 0) lh[0] = d - (part[0] + part[1] + part[2] + part[3]);   // bin 0 is the remainder
+        __syncthreads();
+        find_rank_bin(lh, part, res, kBins1, ge.k);        // the histogram holds all d >= k elements
+    }
+    const uint32_t prefix = res[0];
+    if (blockIdx.x == 0 && tid == 0) {
+        ws[i].prefix = prefix;
+        ws[i].pshift = kShift1;
+        ws[i].rank = ge.k - res[1];
+        ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
+    }
+    const float *arow = a + (int64_t)i * (kSrc == kSrcGrad ? ge.d : ge.ld);
+    const float *brow = kSrc == kSrcStored ? nullptr : b + (int64_t)i * ge.ld;
+    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
+        const uint32_t base = (uint32_t)t * kTile;
+        float x[4][4];
+        load_source_tile<kSrc>(x, arow, brow, base, d);
+        uint32_t count = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t j = base + 4 * (tid + kThreads * r) + c;
+                const bool hit = j < d && (mag_key(x[r][c]) >> kShift1) >= prefix;
+                const uint32_t slot = wave_append(hit, count);
+                if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
+            }
         flush_begin(count, sh, 0, ge, i, t, cursor, tile_dir);
         flush_end(stage[wave], count, sh, ge, i, t, cand);
         __syncthreads();   // sh and stage are reused by the next tile
@@ -703,7 +696,8 @@ __device__ __forceinline__ void scan_load(uint64_t (&comp)[kScanUnroll], const u
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
                                                               const uint64_t *__restrict__ dense,
                                                               const uint2 *__restrict__ dense_dir,
-                                                              uint32_t *__restrict__ cursor)
+                                                              uint32_t *__restrict__ cursor,
+                                                              uint32_t *__restrict__ hist_full)
 {
     __shared__ uint32_t lh[kBins2];
     __shared__ uint32_t part[kResolveThreads / kWave];
@@ -802,6 +796,8 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         __syncthreads();
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
+    if (w.relisted)                                            // tk_relist was its last reader
+        for (int q = tid; q < kBins1; q += kResolveThreads) hist_full[(int64_t)i * kBins1 + q] = 0;
     if (tid == 0) {
         ws[i].tc = tc;
         // The next step lists from a few fine bins below this threshold: at least twice the distance
@@ -959,7 +955,6 @@ struct TkSide {
     uint2 *cand;
     uint32_t *cursor;
     uint4 *tile_dir;
-    uint16_t *oct_rows, *below_rows;
 };
 
 // Per tile: ghat_i += c_i (line 6) and ghat += mean of the c_i (line 8).  The server's vector
