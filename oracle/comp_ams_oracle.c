@@ -17,6 +17,8 @@
  *                         applied per contiguous block with the block's own length
  *   server average      Section 3: gbar = (1/n) sum_i ghat_i
  *   AMSGrad             Section 3: m, v, vhat = max(vhat, v), x -= alpha Vhat^{-1/2} m
+ *   naive compression   Section 4, "Naive compression": ghat_i = C(g_i), no memory
+ *   no compression      Section 3: gbar = (1/n) sum_i g_i (vanilla distributed AMSGrad)
  *   CD-Adam             Section 5, Algorithm 1: Markov compression on the workers
  *                         (c_i = C(g_i - ghat_i), ghat_i += c_i), on the server
  *                         (ghat += mean c_i, c = C(ghat - gtilde), gtilde += c),
@@ -31,7 +33,10 @@
 #include <string.h>
 
 enum { ORACLE_TOPK = 0, ORACLE_BLOCKSIGN = 1 };
-enum { ORACLE_EF = 0, ORACLE_CD = 1 };   /* error feedback (Section 4) / CD-Adam (Algorithm 1) */
+/* error feedback (Section 4) / CD-Adam (Algorithm 1) / naive compression (Section 4, first
+ * paragraph, with AMSGrad in the place of SGD as in the paper's comparison) / no compression
+ * (vanilla distributed AMSGrad, Section 3) */
+enum { ORACLE_EF = 0, ORACLE_CD = 1, ORACLE_NAIVE = 2, ORACLE_NONE = 3 };
 
 typedef struct oracle {
     int64_t d;
@@ -225,14 +230,23 @@ void oracle_step(oracle_t *o, const float *g)
         oracle_step_cd(o, g);
         return;
     }
+    const int memory = (o->method == ORACLE_EF);      /* naive compression: delta_i stays 0 */
+    const int compress = (o->method != ORACLE_NONE);  /* no compression: ghat_i = g_i */
 
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t i = 0; i < n; ++i) {
         float *e = o->e + (size_t)i * (size_t)d;
         float *c = o->c + (size_t)i * (size_t)d;
         const float *gi = g + (size_t)i * (size_t)d;
+        if (!compress) {
+            memcpy(c, gi, (size_t)d * sizeof(float));
+            continue;
+        }
         /* x_i = g_i + delta_i, kept in e until the error is written */
-        for (int64_t j = 0; j < d; ++j) e[j] = gi[j] + e[j];
+        if (memory)
+            for (int64_t j = 0; j < d; ++j) e[j] = gi[j] + e[j];
+        else
+            memcpy(e, gi, (size_t)d * sizeof(float));
         if (o->compressor == ORACLE_TOPK) {
             oracle_topk(e, d, o->k, c, o->sel + (size_t)i * (size_t)o->k);
             /* delta_i = x_i - C(x_i): +0.0 where selected (x - x), x elsewhere (x - 0) */
@@ -242,6 +256,7 @@ void oracle_step(oracle_t *o, const float *g)
             oracle_blocksign(e, o->offsets, o->n_blocks, c, o->scales + (size_t)i * (size_t)o->n_blocks);
             for (int64_t j = 0; j < d; ++j) e[j] = e[j] - c[j];
         }
+        if (!memory) memset(e, 0, (size_t)d * sizeof(float));   /* what was not sent is forgotten */
     }
 
     /* gbar = (1/n) sum_i ghat_i : fp32 adds in ascending worker order, then one

@@ -20,6 +20,8 @@ TOPK = 0
 BLOCKSIGN = 1
 EF = 0      # error feedback (Section 4)
 CD = 1      # CD-Adam, Algorithm 1
+NAIVE = 2   # naive compression (Section 4), no memory
+NONE = 3    # no compression: vanilla distributed AMSGrad (Section 3)
 
 
 def build(force: bool = True) -> str:

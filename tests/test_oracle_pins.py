@@ -476,3 +476,55 @@ def test_cd_adam_markov_bookkeeping_and_contraction(comp):
         assert (o.vhat >= prev_vh).all()
         prev_w, prev_t, prev_vh = gw, o.gtilde.copy(), o.vhat.copy()
     o.close()
+
+
+# ----------------------------------------------------------------------------- comparison arms (Section 3, Section 4)
+
+def test_uncompressed_method_is_vanilla_distributed_amsgrad_bit_for_bit():
+    rng = np.random.default_rng(31)
+    n, d, T = 5, 400, 9
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gs = [(rng.standard_normal((n, d)) * np.exp(rng.uniform(-5, 0, d))).astype(f32) for _ in range(T)]
+    for comp, kb in ((O.TOPK, 3), (O.BLOCKSIGN, 50)):          # the compressor must not matter
+        o = O.Oracle(d, n, comp, kb, b1, b2, eps, lr, method=O.NONE)
+        o.set_theta(theta0)
+        for g in gs:
+            o.step(g)
+        th, m, v, vh = vanilla_amsgrad_numpy(theta0, gs, b1, b2, eps, lr)
+        assert np.array_equal(bits(o.theta), bits(th)) and np.array_equal(bits(o.m), bits(m))
+        assert np.array_equal(bits(o.v), bits(v)) and np.array_equal(bits(o.vhat), bits(vh))
+        o.close()
+
+
+@pytest.mark.parametrize("comp", [O.TOPK, O.BLOCKSIGN])
+def test_naive_compression_has_no_memory(comp):
+    """Section 4, "Naive compression": ghat_i = C(g_i) every step, whatever came before.  The averaged
+    message of step t therefore equals what the (separately pinned) compressor gives on g_t alone,
+    averaged in ascending worker order, and the model follows AMSGrad (pinned above) on it; it also
+    equals the first step of error feedback, whose memory is still empty."""
+    rng = np.random.default_rng(37 + comp)
+    n, d, T = 3, 300, 6
+    kb = 11 if comp == O.TOPK else 64
+    b1, b2, eps, lr = 0.9, 0.999, 1e-8, 1e-3
+    off = np.array(list(range(0, d, 64)) + [d])
+    o = O.Oracle(d, n, comp, kb, b1, b2, eps, lr, method=O.NAIVE)
+    th, m, v, vh = (np.zeros(d, f32) for _ in range(4))
+    for t in range(T):
+        g = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-4, 0, d))).astype(f32)
+        o.step(g)
+        c = np.stack([O.topk(g[i], kb)[0] if comp == O.TOPK else O.blocksign(g[i], off)[0] for i in range(n)])
+        acc = np.zeros(d, f32)
+        for i in range(n):
+            acc = acc + c[i]
+        gbar = acc / f32(n)
+        assert np.array_equal(bits(o.compressed), bits(c)), t
+        assert np.array_equal(bits(o.gbar), bits(gbar)), t
+        assert not o.error.any()
+        th, m, v, vh = O.amsgrad(th, m, v, vh, gbar, b1, b2, eps, lr)
+        assert np.array_equal(bits(o.theta), bits(th)) and np.array_equal(bits(o.vhat), bits(vh))
+        ef = O.Oracle(d, n, comp, kb, b1, b2, eps, lr)          # first step of error feedback: same message
+        ef.step(g)
+        assert np.array_equal(bits(ef.gbar), bits(gbar))
+        ef.close()
+    o.close()
