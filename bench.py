@@ -47,7 +47,7 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
 }
 
 
-def kernel_algorithmic_bytes(name: str, n: int, d: int, cd: bool = False) -> int:
+def kernel_algorithmic_bytes(name: str, n: int, d: int, method: str = "ef") -> int:
     """Algorithmic bytes of one launch = per-unit figure x units (n*d worker-coordinates).
     The streaming pass of either compressor carries the 12 B per (worker, coordinate) of the
     method (read g, read the stored error / Markov vector, write it back); the update kernel carries
@@ -55,17 +55,19 @@ def kernel_algorithmic_bytes(name: str, n: int, d: int, cd: bool = False) -> int
     stage reads and writes ghat and reads gtilde (12 B per coordinate); its last kernel reads and
     writes gtilde and the optimiser state (40 B per coordinate)."""
     nd = n * d
+    naive = method == "naive"         # naive compression reads g only
     return {
-        "bs_pass": 12 * nd,
+        "bs_pass": (4 if naive else 12) * nd,
         "bs_update": 32 * d,
         # CD-Adam with Top-k only reads g and ghat_i in the pass (ghat_i changes on the k kept coordinates)
-        "tk_pass1": (8 if cd else 12) * nd,
+        "tk_pass1": (4 if naive else 8 if method == "cd" else 12) * nd,
         "tk_final": 32 * d,
         "bs_server": 12 * d,
         "bs_apply": 40 * d,
         "tk_merge": 8 * d,
         "tk_pass1_server": 8 * d,
         "tk_apply": 40 * d,
+        "plain_update": 4 * nd + 32 * d,
     }.get(name, 0)
 
 
@@ -78,8 +80,9 @@ def main() -> int:
     ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--method", choices=("ef", "cd"), default="ef",
-                    help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1")
+    ap.add_argument("--method", choices=("ef", "cd", "naive", "none"), default="ef",
+                    help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1; naive: compression "
+                         "without memory; none: no compression")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -113,9 +116,13 @@ def main() -> int:
     if cd:
         h.set_method(P.METHOD_CD)
         h.set_eps_mode(1)                     # Algorithm 1 keeps nu inside the root
+    elif args.method != "ef":
+        h.set_method(P.METHOD_NAIVE if args.method == "naive" else P.METHOD_NONE)
     step_bytes = w.algorithmic_bytes()
     if cd:                                    # + ghat r/w, gtilde r, gtilde r/w; Top-k: ghat_i is not rewritten
         step_bytes += 20 * w.d - (4 * w.n * w.d if w.compressor == W.TOPK else 0)
+    elif args.method != "ef":                 # g is read, nothing is stored per worker
+        step_bytes -= 8 * w.n * w.d
 
     def run(k0, count):
         for t in range(k0, k0 + count):
@@ -138,7 +145,7 @@ def main() -> int:
     kernels = {name: {"avg_us": ms * 1e3 / cnt, "launches_per_step": cnt / args.steps,
                       "us_per_step": ms * 1e3 / args.steps} for name, (ms, cnt) in prof.items()}
     dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
-    dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d, cd)
+    dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d, args.method)
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -169,7 +176,8 @@ def main() -> int:
     cpu = None
     if not args.no_cpu:
         from oracle import oracle as O
-        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr, method=O.CD if cd else O.EF)
+        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr,
+                       method={"ef": O.EF, "cd": O.CD, "naive": O.NAIVE, "none": O.NONE}[args.method])
         if w.compressor == W.BLOCKSIGN and w.layer_blocks:
             ora.set_blocks(w.block_offsets())
         ora.set_theta(w.theta0())
@@ -188,7 +196,9 @@ def main() -> int:
                "sample": f"{done} full steps of {w.name} after one warm step, {spent / done * 1e3:.1f} ms/step"}
 
     out = {
-        "metric": "coords/sec (n*d) per CD-Adam step" if cd else "coords/sec (n*d) per COMP-AMS step",
+        "metric": {"ef": "coords/sec (n*d) per COMP-AMS step", "cd": "coords/sec (n*d) per CD-Adam step",
+                   "naive": "coords/sec (n*d) per naively compressed AMSGrad step",
+                   "none": "coords/sec (n*d) per uncompressed AMSGrad step"}[args.method],
         "value": coords_per_s,
         "unit": "coords/s",
         "n_gpus": 1,
@@ -200,7 +210,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "method": "cd_adam" if cd else "error_feedback", "n_workers": w.n, "d": w.d,
+        "config": {"workload": w.name, "method": {"ef": "error_feedback", "cd": "cd_adam", "naive": "naive_compression",
+                                                   "none": "no_compression"}[args.method], "n_workers": w.n, "d": w.d,
                    "compressor": "topk" if w.compressor == W.TOPK else "blocksign",
                    "k": w.k, "block": w.block, "layer_blocks": w.layer_blocks, "gradient_buffers": nbuf},
         "roofline": roofline,

@@ -43,9 +43,11 @@ typedef struct comp_ams comp_ams_t;
 
 enum { COMP_AMS_TOPK = 0, COMP_AMS_BLOCKSIGN = 1 };
 
-/* How the compressor is used: classical error feedback (Section 4; the step described above), or
- * CD-Adam (Section 5, Algorithm 1): Markov compression in both directions. */
-enum { COMP_AMS_METHOD_EF = 0, COMP_AMS_METHOD_CD = 1 };
+/* How the compressor is used: classical error feedback (Section 4; the step described above);
+ * CD-Adam (Section 5, Algorithm 1): Markov compression in both directions; naive compression
+ * (Section 4, "Naive compression": ghat_i = C(g_i), nothing is remembered); or not at all (vanilla
+ * distributed AMSGrad, Section 3: gbar = (1/n) sum_i g_i) - the arms of the paper's comparison. */
+enum { COMP_AMS_METHOD_EF = 0, COMP_AMS_METHOD_CD = 1, COMP_AMS_METHOD_NAIVE = 2, COMP_AMS_METHOD_NONE = 3 };
 
 enum {
     COMP_AMS_OK = 0,
@@ -126,8 +128,12 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
                        int on_device);
 
 /*
- * CD-Adam, Section 5, Algorithm 1.  Chooses the method of a handle before its first step
- * (COMP_AMS_ESTATE afterwards).  With
+ * Chooses the method of a handle before its first step (COMP_AMS_ESTATE afterwards).
+ * COMP_AMS_METHOD_NAIVE and COMP_AMS_METHOD_NONE run the step described at the top with e_i = 0
+ * throughout, respectively with ghat_i = g_i (the compressor of the handle is then not used);
+ * both leave no error memory to read or restore (COMP_AMS_ESTATE), and NONE has no kept
+ * coordinates or scales either.
+ * CD-Adam, Section 5, Algorithm 1.  With
  * COMP_AMS_METHOD_CD one comp_ams_step computes, with the handle's compressor C in both directions,
  *   c_i     = C(g_i - ghat_i) ;  ghat_i = ghat_i + c_i          workers, lines 5-6
  *   ghat    = ghat + (1/n) sum_i c_i                            server, line 8 (ascending i, one division)

@@ -18,6 +18,8 @@ TOPK = 0
 BLOCKSIGN = 1
 METHOD_EF = 0     # error feedback (Section 4)
 METHOD_CD = 1     # CD-Adam (Section 5, Algorithm 1)
+METHOD_NAIVE = 2  # naive compression (Section 4), no memory
+METHOD_NONE = 3   # no compression (vanilla distributed AMSGrad, Section 3)
 
 OK, EINVAL, ENOMEM, EDEVICE, ESTATE = 0, -1, -2, -3, -4
 

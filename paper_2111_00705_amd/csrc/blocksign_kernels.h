@@ -102,8 +102,11 @@ __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base,
     }
 }
 
-// kMarkov: CD-Adam's worker stage instead of error feedback (see the head of this file).
-template <bool kPending, bool kMarkov>
+// kMode: kBsEf error feedback; kBsCd CD-Adam's worker stage (see the head of this file); kBsNaive naive
+// compression (Section 4): x = g, nothing is read from or written to the stored rows.
+enum { kBsEf = 0, kBsCd = 1, kBsNaive = 2 };
+
+template <bool kPending, int kMode>
 __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g, float *__restrict__ xs,
                                                     int64_t d, int64_t ld, BsTable tb,
                                                     const float *__restrict__ s_prev,
@@ -126,10 +129,10 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gv[r] = load_grad4(grow, j, d);
-        xv[r] = ld4(xrow + j);
+        xv[r] = kMode == kBsNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4(xrow + j);
     }
     uint16_t *word = signs + ((int64_t)i * (ld / kTile) + t) * kThreads + tid;
-    const uint32_t old_bits = (kMarkov && kPending) ? (uint32_t)*word : 0u;   // sign bits of the pending c_i
+    const uint32_t old_bits = (kMode == kBsCd && kPending) ? (uint32_t)*word : 0u;   // sign bits of the pending c_i
     float x[4][4];
     uint32_t sign_bits = 0;
     const bool single = (p1 - p0 == 1);
@@ -148,19 +151,22 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
                 while (p + 1 < p1 && j + c >= tb.piece_hi[p]) ++p;
                 s = sp[tb.piece_blk[p]];
             }
-            if (kMarkov) {
+            if (kMode == kBsCd) {
                 // ghat_i = ghat_i + c_i (Algorithm 1, line 6, of the step before); u = g - ghat_i (line 5)
                 float gh = xx[c];
                 if (kPending && j + c < d) gh = fadd(gh, signed_scale(s, old_bits, r * 4 + c));
                 keep[c] = gh;
                 x[r][c] = (j + c < d) ? fsub(gg[c], gh) : 0.f;
+            } else if (kMode == kBsNaive) {
+                x[r][c] = (j + c < d) ? gg[c] : 0.f;
+                keep[c] = 0.f;
             } else {
                 const float e = kPending ? deferred_sign_error(xx[c], s) : xx[c];
                 x[r][c] = (j + c < d) ? fadd(gg[c], e) : 0.f;
                 keep[c] = x[r][c];
             }
         }
-        st4(xrow + j, make_float4(keep[0], keep[1], keep[2], keep[3]));
+        if (kMode != kBsNaive) st4(xrow + j, make_float4(keep[0], keep[1], keep[2], keep[3]));
 #pragma unroll
         for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
     }

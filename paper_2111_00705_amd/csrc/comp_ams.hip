@@ -18,6 +18,7 @@
 
 #include "blocksign_kernels.h"
 #include "topk_kernels.h"
+#include "plain_kernels.h"
 
 using namespace cams;
 
@@ -88,11 +89,11 @@ namespace {
 
 enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
                 P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_TK_MERGE, P_TK_PASS1_SERVER,
-                P_TK_SELECT_SERVER, P_TK_APPLY, P_SLOTS };
+                P_TK_SELECT_SERVER, P_TK_APPLY, P_PLAIN_UPDATE, P_SLOTS };
 const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
                                          "tk_relist", "tk_compact", "tk_resolve", "tk_final", "bs_server",
                                          "bs_scale_server", "bs_apply", "tk_merge", "tk_pass1_server", "tk_select_server",
-                                         "tk_apply"};
+                                         "tk_apply", "plain_update"};
 
 // Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
 template <typename F>
@@ -269,10 +270,12 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
     const BsTable &tb = h->tb;
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
-        if (h->pending)
-            bs_pass<true, false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+        if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
+            bs_pass<false, kBsNaive><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+        else if (h->pending)
+            bs_pass<true, kBsEf><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, false><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, kBsEf><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     if (!h->fused_scale)
         launch_timed(h, P_BS_SCALE, st, [&] {
@@ -292,7 +295,7 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
         }
 #undef CAMS_BS_UPDATE
     });
-    h->pending = true;
+    h->pending = (h->method == COMP_AMS_METHOD_EF);
     return COMP_AMS_OK;
 }
 
@@ -303,9 +306,9 @@ int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            bs_pass<true, true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<true, kBsCd><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, true><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, kBsCd><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     launch_timed(h, P_BS_SCALE, st, [&] {
         bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
@@ -370,6 +373,33 @@ int step_topk(comp_ams *h, const float *g, hipStream_t st)
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
+    });
+    return COMP_AMS_OK;
+}
+
+// Naive compression (Section 4) with Top-k: as step_topk, on g itself.
+int step_topk_naive(comp_ams *h, const float *g, hipStream_t st)
+{
+    const TkGeom &ge = h->ge;
+    launch_timed(h, P_TK_PASS1, st, [&] {
+        tk_pass1<kPassNaive><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+                                                                          h->tile_dir);
+    });
+    launch_select<kSrcGradOnly>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                                h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
+    launch_timed(h, P_TK_FINAL, st, [&] {
+        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+                                                  h->params);
+    });
+    return COMP_AMS_OK;
+}
+
+// Vanilla distributed AMSGrad (Section 3): no compression.
+int step_plain(comp_ams *h, const float *g, hipStream_t st)
+{
+    launch_timed(h, P_PLAIN_UPDATE, st, [&] {
+        plain_update<<<(unsigned)(h->ld / kTile), kThreads, 0, st>>>(g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
+                                                                     h->params);
     });
     return COMP_AMS_OK;
 }
@@ -643,8 +673,12 @@ int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream)
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         h->stream = st;
     }
-    if (h->compressor == COMP_AMS_TOPK)
-        rc = (h->method == COMP_AMS_METHOD_CD) ? step_topk_cd(h, grads_dev, st) : step_topk(h, grads_dev, st);
+    if (h->method == COMP_AMS_METHOD_NONE)
+        rc = step_plain(h, grads_dev, st);
+    else if (h->compressor == COMP_AMS_TOPK)
+        rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
+             : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
+                                                    : step_topk(h, grads_dev, st);
     else
         rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
     if (rc) return rc;
@@ -679,7 +713,7 @@ int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
     int rc = check_handle(h);
     if (rc) return rc;
     if (h->method != COMP_AMS_METHOD_EF)
-        return fail(h, COMP_AMS_ESTATE, "CD-Adam keeps no error memory; see comp_ams_get_ghat_worker");
+        return fail(h, COMP_AMS_ESTATE, "this method keeps no error memory (CD-Adam: see comp_ams_get_ghat_worker)");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
     launch_materialize(h, worker, on_device ? out : h->row_tmp);
@@ -723,6 +757,7 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
     int rc = check_handle(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
+    if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     return gather_selected(h, h->ge, worker, h->ws, h->cand, h->tile_dir, idx_host, val_host);
@@ -743,6 +778,7 @@ int comp_ams_get_scales(comp_ams_t *h, float *out_host)
     int rc = check_handle(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_scales needs a BLOCKSIGN handle");
+    if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     return copy_out(h, out_host, h->scales, (size_t)h->n * (size_t)h->tb.n_blocks, 0);
 }
@@ -762,7 +798,7 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
     if (v && (rc = copy_in(h, h->v, v, d, on_device))) return rc;
     if (vhat && (rc = copy_in(h, h->vhat, vhat, d, on_device))) return rc;
     if (e && h->method != COMP_AMS_METHOD_EF)
-        return fail(h, COMP_AMS_ESTATE, "CD-Adam keeps no error memory; see comp_ams_set_markov_state");
+        return fail(h, COMP_AMS_ESTATE, "this method keeps no error memory (CD-Adam: see comp_ams_set_markov_state)");
     if (e) {
         HIP_TRY(h, hipMemcpy2DAsync(h->e, (size_t)h->ld * sizeof(float), e, d * sizeof(float), d * sizeof(float),
                                     (size_t)h->n, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
@@ -837,7 +873,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    if (method != COMP_AMS_METHOD_EF && method != COMP_AMS_METHOD_CD) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
+    if (method < COMP_AMS_METHOD_EF || method > COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
     if (method == h->method) return COMP_AMS_OK;
     if (h->steps != 0) return fail(h, COMP_AMS_ESTATE, "the method can only be chosen before the first step");
     if (method == COMP_AMS_METHOD_CD && !h->ghat_srv) {

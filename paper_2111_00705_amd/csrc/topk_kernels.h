@@ -247,8 +247,9 @@ __device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32
 // Modes: kPassEf  error feedback: x = g + e, written back over the stored vector;
 //        kPassCd  CD-Adam worker (Algorithm 1, line 5): u = g - ghat_i, nothing written back (ghat_i
 //                 changes only where c_i is not zero; tk_merge does that);
-//        kPassDiff  CD-Adam server (line 9): w = ghat - gtilde, both padded rows, nothing written back.
-enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2 };
+//        kPassDiff  CD-Adam server (line 9): w = ghat - gtilde, both padded rows, nothing written back;
+//        kPassNaive  naive compression (Section 4): x = g, the stored rows are not touched.
+enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2, kPassNaive = 3 };
 
 template <bool kFull, int kMode>
 __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow,
@@ -261,7 +262,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (tid + kThreads * r);
         gv[r] = kMode == kPassDiff ? ld4(grow + j) : load_grad4(grow, j, d);
-        xv[r] = ld4(xrow + j);
+        xv[r] = kMode == kPassNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4(xrow + j);
     }
     uint32_t count = 0;
 #pragma unroll
@@ -272,7 +273,9 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
         float x[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (kMode != kPassEf) {
+            if (kMode == kPassNaive) {
+                x[c] = (kFull || j + c < d) ? gg[c] : 0.f;
+            } else if (kMode != kPassEf) {
                 x[c] = (kFull || j + c < d) ? fsub(gg[c], xo[c]) : 0.f;
             } else {
                 // e = x_old - C(x_old): +0 where the previous step kept the coordinate
@@ -418,7 +421,8 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
 //   kSrcStored  the stored x itself (error feedback)
 //   kSrcGrad    g - ghat_i, a = g (rows of d floats, any 4-byte alignment), b = ghat_i (CD-Adam workers)
 //   kSrcDiff    a - b, both padded rows (CD-Adam server: ghat - gtilde)
-enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2 };
+//   kSrcGradOnly  a = g itself (naive compression)
+enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2, kSrcGradOnly = 3 };
 
 // The 16 values of this thread in the tile at `base` (coordinates base + 4 (tid + 256 r) + c).
 template <int kSrc>
@@ -428,12 +432,12 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const float *
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (threadIdx.x + kThreads * r);
-        const float4 av = kSrc == kSrcGrad ? load_grad4(arow, j, d) : ld4(arow + j);
+        const float4 av = (kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? load_grad4(arow, j, d) : ld4(arow + j);
         x[r][0] = av.x;
         x[r][1] = av.y;
         x[r][2] = av.z;
         x[r][3] = av.w;
-        if (kSrc != kSrcStored) {
+        if (kSrc == kSrcGrad || kSrc == kSrcDiff) {
             const float4 bv = ld4(brow + j);
             x[r][0] = fsub(x[r][0], bv.x);
             x[r][1] = fsub(x[r][1], bv.y);
@@ -533,8 +537,8 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
     for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
     __syncthreads();
     const uint32_t d = (uint32_t)ge.d;
-    const float *arow = a + (int64_t)i * (kSrc == kSrcGrad ? ge.d : ge.ld);
-    const float *brow = kSrc == kSrcStored ? nullptr : b + (int64_t)i * ge.ld;
+    const float *arow = a + (int64_t)i * ((kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? ge.d : ge.ld);
+    const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
@@ -604,8 +608,8 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ 
         ws[i].rank = ge.k - res[1];
         ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
     }
-    const float *arow = a + (int64_t)i * (kSrc == kSrcGrad ? ge.d : ge.ld);
-    const float *brow = kSrc == kSrcStored ? nullptr : b + (int64_t)i * ge.ld;
+    const float *arow = a + (int64_t)i * ((kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? ge.d : ge.ld);
+    const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];

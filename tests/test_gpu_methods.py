@@ -1,0 +1,120 @@
+"""GPU parity of the paper's comparison arms - naive compression (Section 4) and no compression
+(vanilla distributed AMSGrad, Section 3) - against the CPU oracle, element by element.
+Bars as in tests/parity_util.py: kept index sets and kept values bit-exact, block scales within
+1e-5 relative, theta, m, v, vhat within 1e-6 relative per coordinate."""
+import numpy as np
+import pytest
+
+import paper_2111_00705_amd as P
+import workloads as W
+from oracle import oracle as O
+from parity_util import SCALE_RTOL, STATE_RTOL, bits, rel_close
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+def torch_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def make(d, n, comp, kb, method, theta0=None, offsets=None):
+    gpu = P.CompAms(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR)
+    ora = O.Oracle(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR, method=method)
+    gpu.set_method(method)
+    if offsets is not None:
+        gpu.set_blocks(offsets)
+        ora.set_blocks(offsets)
+    if theta0 is not None:
+        gpu.set_theta(np.ascontiguousarray(theta0, dtype=f32))
+        ora.set_theta(theta0)
+    return gpu, ora
+
+
+def run(gpu, ora, grads_fn, steps, tag):
+    for t in range(steps):
+        g = grads_fn(t)
+        gpu.step(torch_dev(g))
+        ora.step(g)
+        if ora.method == O.NAIVE and gpu.compressor == P.TOPK:
+            for i in range(gpu.n):
+                idx, val = gpu.get_selected(i)
+                assert np.array_equal(idx, ora.selected[i]), f"{tag} step {t} worker {i}: kept index set differs"
+                assert np.array_equal(bits(val), bits(g[i][idx])), f"{tag} step {t} worker {i}: kept values differ"
+        if ora.method == O.NAIVE and gpu.compressor == P.BLOCKSIGN:
+            assert rel_close(gpu.get_scales(), ora.scales, SCALE_RTOL).all(), f"{tag} step {t}: scales"
+        for name, got, want in (("theta", gpu.get_theta(), ora.theta), ("m", gpu.get_m(), ora.m),
+                                ("v", gpu.get_v(), ora.v), ("vhat", gpu.get_vhat(), ora.vhat)):
+            ok = rel_close(got, want, STATE_RTOL)
+            assert ok.all(), f"{tag} step {t} {name}: {np.count_nonzero(~ok)} coordinates beyond {STATE_RTOL}"
+
+
+def noise(seed, n, d, scale):
+    return lambda t: (np.random.default_rng([seed, t]).standard_normal((n, d)) * scale).astype(f32)
+
+
+@pytest.mark.parametrize("d,n", [(1, 1), (5, 3), (4097, 2), (10_007, 5), (3 * 4096, 4), (150_001, 16), (9000, 70)])
+def test_uncompressed_amsgrad(d, n):
+    announce(f"no compression d={d} n={n}")
+    rng = np.random.default_rng(d + n)
+    scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    gpu, ora = make(d, n, P.TOPK, 1, P.METHOD_NONE, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    run(gpu, ora, noise(d, n, d, scale), steps=4, tag=f"none d={d}")
+    for call in (lambda: gpu.get_selected(0), lambda: gpu.get_error(0)):
+        with pytest.raises(P.CompAmsError) as ei:
+            call()
+        assert ei.value.code == P.ESTATE
+    gpu.destroy()
+
+
+def test_uncompressed_amsgrad_any_gradient_alignment():
+    import torch
+    announce("no compression, unaligned gradient rows")
+    d, n = 10_001, 3                      # odd d: rows start at every 4-byte alignment class
+    gpu, ora = make(d, n, P.BLOCKSIGN, 64, P.METHOD_NONE)
+    for t in range(3):
+        g = np.random.default_rng([77, t]).standard_normal((n, d)).astype(f32)
+        buf = torch.empty(n * d + 3, dtype=torch.float32, device="cuda")
+        view = buf[1 + t % 3: 1 + t % 3 + n * d]
+        view.copy_(torch.from_numpy(g).reshape(-1))
+        gpu.step_ptr(view.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        ora.step(g)
+        assert rel_close(gpu.get_theta(), ora.theta, STATE_RTOL).all()
+        assert np.array_equal(bits(gpu.get_vhat()), bits(ora.vhat))
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("d,n,k", [(1, 1, 1), (63, 2, 7), (4097, 2, 41), (10_007, 5, 100), (20_000, 3, 20_000),
+                                   (300_003, 8, 3000)])
+def test_naive_topk(d, n, k):
+    announce(f"naive Top-k d={d} n={n} k={k}")
+    rng = np.random.default_rng(d * 3 + n)
+    scale = np.exp(rng.uniform(-6, 0, d)).astype(f32)
+    gpu, ora = make(d, n, P.TOPK, k, P.METHOD_NAIVE, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    factors = [1.0, 1.0, 50.0, 1e-3, 1.0]           # the carried guess must survive scale changes here too
+    run(gpu, ora, lambda t: noise(d, n, d, scale)(t) * f32(factors[t]), steps=5, tag=f"naive topk d={d}")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("d,n,B", [(7, 2, 3), (4096, 2, 4096), (10_007, 5, 100), (3 * 4096 + 5, 4, 8192), (150_001, 16, 4096)])
+def test_naive_blocksign(d, n, B):
+    announce(f"naive block sign d={d} n={n} B={B}")
+    rng = np.random.default_rng(d * 5 + n)
+    scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    gpu, ora = make(d, n, P.BLOCKSIGN, B, P.METHOD_NAIVE, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    run(gpu, ora, noise(d + 1, n, d, scale), steps=4, tag=f"naive sign d={d}")
+    gpu.destroy()
+
+
+def test_naive_blocksign_layer_blocks():
+    announce("naive block sign, layer blocks")
+    d, n = 70_003, 3
+    offsets = [0, 1, 2, 300, 4096, 4097, 9000, 30_000, 30_001, 65_536, d]
+    gpu, ora = make(d, n, P.BLOCKSIGN, d, P.METHOD_NAIVE, offsets=offsets)
+    run(gpu, ora, noise(9, n, d, f32(1.0)), steps=3, tag="naive layers")
+    gpu.destroy()
