@@ -167,6 +167,18 @@ int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_h
 int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const float *ghat_server,
                               const float *gtilde, int on_device);
 
+/*
+ * Communication cost of one step in bits, by the accounting of Section 5 (footnote to the
+ * algorithm overview) and of the table "Average runtime and total bits": a scaled-sign message costs
+ * 1 bit per coordinate plus 32 bits per scale (32 + d for the whole vector), a Top-k message 32 bits
+ * of index plus 32 bits of value per kept coordinate, an uncompressed vector 32 d.
+ * *uplink_per_worker: what one worker sends.  *downlink: what the server sends back to each worker -
+ * a compressed message with CD-Adam, the dense average (32 d) with every other method (error
+ * feedback and naive compression compress the workers' messages only).  Either pointer may be NULL.
+ * Needs no GPU.
+ */
+int comp_ams_message_bits(comp_ams_t *h, uint64_t *uplink_per_worker, uint64_t *downlink);
+
 /* Waits until all work enqueued by this handle has completed. */
 int comp_ams_sync(comp_ams_t *h);
 

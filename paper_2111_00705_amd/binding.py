@@ -31,6 +31,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
+    "comp_ams_message_bits",
 ]
 
 
@@ -84,6 +85,7 @@ def lib():
         L.comp_ams_get_server_scales.argtypes = [vp, fp]
         L.comp_ams_set_markov_state.argtypes = [vp, fp, fp, fp, C.c_int]
         L.comp_ams_get_server_selected.argtypes = [vp, u32p, fp]
+        L.comp_ams_message_bits.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
         _lib = L
@@ -175,6 +177,12 @@ class CompAms:
         self._check(lib().comp_ams_get_server_selected(self._h, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
                                                        val.ctypes.data))
         return idx, val
+
+    def message_bits(self):
+        """(bits one worker sends, bits the server sends back to each worker) per step."""
+        up, down = C.c_uint64(), C.c_uint64()
+        self._check(lib().comp_ams_message_bits(self._h, C.byref(up), C.byref(down)))
+        return up.value, down.value
 
     def get_server_scales(self):
         out = np.empty(self.n_blocks(), dtype=np.float32)

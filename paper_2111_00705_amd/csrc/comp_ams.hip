@@ -975,6 +975,17 @@ int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const fl
     return COMP_AMS_OK;   // the Top-k guesses are left as they are: a guess is only a hint
 }
 
+int comp_ams_message_bits(comp_ams_t *h, uint64_t *uplink_per_worker, uint64_t *downlink)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    const uint64_t dense = 32ull * (uint64_t)h->d;
+    const uint64_t packed = h->compressor == COMP_AMS_TOPK ? 64ull * (uint64_t)h->k
+                                                           : (uint64_t)h->d + 32ull * (uint64_t)h->tb.n_blocks;
+    if (uplink_per_worker) *uplink_per_worker = h->method == COMP_AMS_METHOD_NONE ? dense : packed;
+    if (downlink) *downlink = h->method == COMP_AMS_METHOD_CD ? packed : dense;
+    return COMP_AMS_OK;
+}
+
 int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream)
 {
     if (!dst_dev || !src_dev) return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: NULL pointer");

@@ -118,3 +118,59 @@ def test_naive_blocksign_layer_blocks():
     gpu, ora = make(d, n, P.BLOCKSIGN, d, P.METHOD_NAIVE, offsets=offsets)
     run(gpu, ora, noise(9, n, d, f32(1.0)), steps=3, tag="naive layers")
     gpu.destroy()
+
+
+def test_case_study_ordering_of_the_four_strategies_on_gpu():
+    """Section 6.1 on the GPU library: same problem, same settings and same assertion as the oracle's
+    test of that name; the models must also agree with the oracle's at the end."""
+    announce("logistic regression case study")
+    a, y = W.logreg_problem()
+    n, _, d = a.shape
+    norm = {}
+    for name, method in (("none", P.METHOD_NONE), ("cd", P.METHOD_CD), ("ef", P.METHOD_EF), ("naive", P.METHOD_NAIVE)):
+        gpu = P.CompAms(d, n, P.BLOCKSIGN, 16, 0.9, 0.999, 1e-3, 0.003)
+        ora = O.Oracle(d, n, O.BLOCKSIGN, 16, 0.9, 0.999, 1e-3, 0.003, method=method)
+        gpu.set_method(method)
+        gpu.set_eps_mode(1)
+        ora.set_eps_mode(1)
+        theta = np.zeros(d, f32)
+        for _ in range(1500):
+            g = W.logreg_grads(a, y, theta)
+            gpu.step(torch_dev(g))
+            theta = gpu.get_theta()
+        for _ in range(1500):
+            ora.step(W.logreg_grads(a, y, ora.theta))
+        norm[name] = float(np.linalg.norm(W.logreg_grads(a, y, theta).astype(np.float64).mean(axis=0)))
+        assert np.allclose(theta, ora.theta, rtol=1e-3, atol=1e-5), name
+        gpu.destroy()
+        ora.close()
+    assert norm["none"] < 1e-6
+    assert norm["cd"] < 1e-2 * norm["ef"], norm
+    assert norm["ef"] < 1e-1 * norm["naive"], norm
+
+
+def test_message_bits_follow_the_papers_accounting():
+    """The table "Average runtime and total bits": uncompressed 32 d per direction, CD-Adam with the
+    whole-vector scaled sign (32 + d) per direction, Top-k about 64 k per message."""
+    announce("message bits")
+    d, n, k = 10_000, 4, 160
+    h = P.CompAms(d, n, P.BLOCKSIGN, d)
+    assert h.message_bits() == (32 + d, 32 * d)                   # error feedback: only the upload is compressed
+    h.set_method(P.METHOD_CD)
+    assert h.message_bits() == (32 + d, 32 + d)
+    h.destroy()
+    h = P.CompAms(d, n, P.BLOCKSIGN, 4096)
+    h.set_method(P.METHOD_CD)
+    assert h.message_bits() == (d + 32 * 3, d + 32 * 3)           # three blocks, three scales
+    h.set_blocks([0, 10, 20, 30, d])
+    assert h.message_bits() == (d + 32 * 4, d + 32 * 4)
+    h.destroy()
+    h = P.CompAms(d, n, P.TOPK, k)
+    assert h.message_bits() == (64 * k, 32 * d)
+    h.set_method(P.METHOD_NAIVE)
+    assert h.message_bits() == (64 * k, 32 * d)
+    h.set_method(P.METHOD_CD)
+    assert h.message_bits() == (64 * k, 64 * k)
+    h.set_method(P.METHOD_NONE)
+    assert h.message_bits() == (32 * d, 32 * d)
+    h.destroy()

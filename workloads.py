@@ -160,3 +160,28 @@ CONFIGS = [
 
 def get(idx: int) -> Workload:
     return CONFIGS[idx]
+
+
+# ----------------------------------------------------------------------------------------------
+# Nonconvex logistic regression (Section 6.1, eq. (7)): log-loss plus lam * sum x_j^2 / (1 + x_j^2),
+# n workers with equal shares of the samples, full-batch local gradients.  The LibSVM sets of the
+# paper are not available here; the data below only imitate their shape (a few hundred binary
+# features, about a dozen set per sample, +-1 labels from a noisy linear rule).  This produces the
+# inputs g_i of a step from the current model; none of the optimiser's arithmetic lives here.
+
+def logreg_problem(seed: int = 0, samples: int = 4000, d: int = 300, n: int = 20, density: float = 0.04):
+    rng = np.random.default_rng([seed, 7])
+    a = (rng.random((samples, d)) < density).astype(np.float64)
+    x_true = rng.standard_normal(d)
+    score = a @ x_true
+    y = np.where(score + 0.1 * rng.standard_normal(samples) > np.median(score), 1.0, -1.0)
+    return a.reshape(n, samples // n, d), y.reshape(n, samples // n)
+
+
+def logreg_grads(a: np.ndarray, y: np.ndarray, x: np.ndarray, lam: float = 0.1) -> np.ndarray:
+    """Local full-batch gradients [n, d] (float32) of eq. (7) at the model x."""
+    x = np.asarray(x, dtype=np.float64)
+    z = -y * (a @ x)
+    s = 1.0 / (1.0 + np.exp(-z))
+    g = -(a * (y * s)[..., None]).mean(axis=1)
+    return (g + lam * 2.0 * x / (1.0 + x * x) ** 2).astype(np.float32)
