@@ -150,8 +150,13 @@ def main() -> int:
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name + ("/cd" if cd else ""), dom)),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name + ("/cd" if cd else ""), dom))
+                if args.method in ("ef", "cd") else None,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
+    if roofline["traffic"]:
+        # bytes the counters saw per launch over the same live duration: the rate the memory system ran at
+        roofline["traffic_gbs"] = round(roofline["traffic"] / (dom_us * 1e-6) / 1e9, 1)
+        roofline["traffic_frac"] = round(roofline["traffic_gbs"] / HBM_PEAK_GBS, 4)
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # plain float4 copy on the same stream: what a trivial streaming kernel reaches on this chip, and

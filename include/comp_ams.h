@@ -119,6 +119,17 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
  * [n][n_blocks] row-major, scale = (sum over the block of |x|) / block length. */
 int comp_ams_get_scales(comp_ams_t *h, float *out_host);
 
+/*
+ * BLOCKSIGN handles, after at least one step: the sign bits of worker i's message of the last step,
+ * packed in coordinate order into (d + 7) / 8 host bytes (bit j % 8 of byte j / 8 is set iff
+ * coordinate j is negative, by the IEEE sign bit; the unused high bits of the last byte are 0).
+ * Together with the worker's row of comp_ams_get_scales this is the whole message:
+ * C(x)_j = (bit ? -1 : +1) * scale[block(j)] (Appendix A, "Scaled sign"; 1 bit per coordinate plus
+ * 32 bits per scale).  worker = n on a CD handle gives the server's message instead (with
+ * comp_ams_get_server_scales).
+ */
+int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host);
+
 /* Number of blocks of a BLOCKSIGN handle (0 for TOPK, negative status on error). */
 int32_t comp_ams_n_blocks(comp_ams_t *h);
 

@@ -31,7 +31,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
-    "comp_ams_message_bits",
+    "comp_ams_message_bits", "comp_ams_get_signs",
 ]
 
 
@@ -85,6 +85,7 @@ def lib():
         L.comp_ams_get_server_scales.argtypes = [vp, fp]
         L.comp_ams_set_markov_state.argtypes = [vp, fp, fp, fp, C.c_int]
         L.comp_ams_get_server_selected.argtypes = [vp, u32p, fp]
+        L.comp_ams_get_signs.argtypes = [vp, C.c_int32, C.c_void_p]
         L.comp_ams_message_bits.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.comp_ams_last_error.argtypes = [vp]
         L.comp_ams_last_error.restype = C.c_char_p
@@ -177,6 +178,13 @@ class CompAms:
         self._check(lib().comp_ams_get_server_selected(self._h, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
                                                        val.ctypes.data))
         return idx, val
+
+    def get_signs(self, worker):
+        """Packed sign bits (numpy uint8, (d + 7) // 8 bytes, coordinate order) of a worker's last message;
+        worker = n on a CD handle: the server's."""
+        out = np.zeros((self.d + 7) // 8, dtype=np.uint8)
+        self._check(lib().comp_ams_get_signs(self._h, worker, out.ctypes.data))
+        return out
 
     def message_bits(self):
         """(bits one worker sends, bits the server sends back to each worker) per step."""

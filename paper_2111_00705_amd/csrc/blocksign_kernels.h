@@ -294,10 +294,11 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             }
             __syncthreads();
             for (int u0 = 0; u0 < cn; u0 += kSignBatch) {
-                if (c0 + u0 > 0) {
+                // the sign words of the batch after this one go out before this one is used
+                uint32_t next[kSignBatch];
+                const int w1 = c0 + u0 + kSignBatch;       // first worker of the next batch (may be in the next chunk)
 #pragma unroll
-                    for (int u = 0; u < kSignBatch; ++u) bits[u] = (u0 + u < cn) ? srow[(c0 + u0 + u) * sstride] : 0u;
-                }
+                for (int u = 0; u < kSignBatch; ++u) next[u] = (w1 + u < n) ? srow[(w1 + u) * sstride] : 0u;
 #pragma unroll
                 for (int u = 0; u < kSignBatch; ++u) {
                     if (u0 + u < cn) {
@@ -306,6 +307,8 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
                         for (int q = 0; q < 16; ++q) acc[q] = fadd(acc[q], signed_scale(s, bits[u], q));
                     }
                 }
+#pragma unroll
+                for (int u = 0; u < kSignBatch; ++u) bits[u] = next[u];
             }
         }
     } else {

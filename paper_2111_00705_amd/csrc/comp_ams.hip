@@ -783,6 +783,32 @@ int comp_ams_get_scales(comp_ams_t *h, float *out_host)
     return copy_out(h, out_host, h->scales, (size_t)h->n * (size_t)h->tb.n_blocks, 0);
 }
 
+int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_signs needs a BLOCKSIGN handle");
+    if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    const bool server = (h->method == COMP_AMS_METHOD_CD && worker == h->n);
+    if (!server && (worker < 0 || worker >= h->n)) return fail(h, COMP_AMS_EINVAL, "worker %d out of range", worker);
+    if (!bits_host) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    const size_t words = (size_t)h->ld / 16;
+    std::vector<uint16_t> w(words);
+    const uint16_t *src = server ? h->signs_srv : h->signs + (size_t)worker * words;
+    HIP_TRY(h, hipMemcpyAsync(w.data(), src, words * sizeof(uint16_t), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    // coordinate 4 * (tid + 256 * r) + c of a tile is bit r * 4 + c of the tile's word number tid
+    std::memset(bits_host, 0, ((size_t)h->d + 7) / 8);
+    for (int64_t j = 0; j < h->d; ++j) {
+        const int64_t t = j / kTile;
+        const int l = (int)(j - t * kTile), vec = l >> 2;
+        const uint16_t word = w[(size_t)t * kThreads + (size_t)(vec & (kThreads - 1))];
+        if ((word >> ((vec / kThreads) * 4 + (l & 3))) & 1u) bits_host[j >> 3] |= (uint8_t)(1u << (j & 7));
+    }
+    return COMP_AMS_OK;
+}
+
 int32_t comp_ams_n_blocks(comp_ams_t *h)
 {
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");

@@ -174,3 +174,35 @@ def test_message_bits_follow_the_papers_accounting():
     h.set_method(P.METHOD_NONE)
     assert h.message_bits() == (32 * d, 32 * d)
     h.destroy()
+
+
+@pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_NAIVE, P.METHOD_CD])
+def test_scaled_sign_message_rebuilt_from_bits_and_scales(method):
+    """What goes over the wire - one bit per coordinate and one scale per block - must rebuild the
+    oracle's compressed vectors C(.) of every worker (and of the server for CD-Adam) exactly."""
+    announce(f"sign message, method {method}")
+    d, n = 70_003, 3
+    offsets = np.array([0, 1, 2, 300, 4096, 4097, 9000, 30_000, 30_001, 65_536, d])
+    gpu, ora = make(d, n, P.BLOCKSIGN, d, method, offsets=offsets)
+    block_of = np.repeat(np.arange(offsets.size - 1), np.diff(offsets))
+
+    def rebuild(bits_packed, scales):
+        neg = np.unpackbits(bits_packed, bitorder="little")[:d].astype(bool)
+        return np.where(neg, -scales[block_of], scales[block_of]).astype(f32)
+
+    for t in range(3):
+        g = np.random.default_rng([55, t]).standard_normal((n, d)).astype(f32)
+        g[1, 100:200] = -0.0
+        gpu.step(torch_dev(g))
+        ora.step(g)
+        s = gpu.get_scales()
+        assert np.array_equal(bits(s), bits(ora.scales)), "scales are expected bit-identical on this input"
+        for i in range(n):
+            assert np.array_equal(bits(rebuild(gpu.get_signs(i), s[i])), bits(ora.compressed[i])), (t, i)
+        if method == P.METHOD_CD:
+            msg = rebuild(gpu.get_signs(n), gpu.get_server_scales())
+            assert np.array_equal(bits(msg), bits(ora.server_compressed)), t
+    with pytest.raises(P.CompAmsError) as ei:
+        gpu.get_signs(n if method != P.METHOD_CD else n + 1)
+    assert ei.value.code == P.EINVAL
+    gpu.destroy()
