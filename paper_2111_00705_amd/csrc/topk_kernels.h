@@ -679,22 +679,103 @@ constexpr int kMaxPieces = 2048;   // slices * parts * 4 never exceeds this (the
 constexpr int kFew = 256;         // at most this many elements are ranked directly instead of by further digits
 static_assert(kMaxPieces <= 2 * kResolveThreads, "two pieces per thread in the prefix sum");
 
-// Elements qb + u * kResolveThreads + tid (u < kScanUnroll) of the worker's dense set, found through
-// the prefix sums of the piece counts; the loads are independent, so they are all in flight at once.
-constexpr int kScanUnroll = 4;
-__device__ __forceinline__ void scan_load(uint64_t (&comp)[kScanUnroll], const uint64_t *__restrict__ wdense,
-                                          const uint32_t *rpre, const uint32_t *rstart, int pieces, uint32_t qb,
-                                          uint32_t cnt)
+constexpr int kScanUnroll = 4;    // independent loads per thread in the scans of the dense set
+
+// LDS of the digit search, shared by tk_resolve and tk_select.
+struct ResolveLds {
+    uint32_t lh[kBins2];
+    uint32_t part[kResolveThreads / kWave];
+    uint32_t res[4];
+    uint64_t few[kFew];
+    uint32_t n_few;
+    uint64_t tc_sh;
+};
+
+// The digits of Tc below `prefix` (which leaves s_hi low bits of comp open), 12 bits at a time, over the
+// cnt comp values get(q), q < cnt, of which the one of 1-based rank `rank` (from the top) among those
+// that carry the prefix is wanted.  Once at most kFew elements carry the prefix they are fetched and
+// ranked against each other directly.  All kResolveThreads threads call this; returns Tc.
+template <class Get>
+__device__ __forceinline__ uint64_t resolve_digits(Get get, uint32_t cnt, uint64_t prefix, uint32_t rank, int s_hi,
+                                                   ResolveLds &L)
 {
+    const int tid = threadIdx.x;
+    uint64_t tc = prefix << s_hi;
+    bool done = false;
+    while (!done) {
+        const int s_lo = max(s_hi - kDigitBits, 0);
+        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
+        for (int b = tid; b < kBins2; b += kResolveThreads) L.lh[b] = 0;
+        __syncthreads();
+        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+            uint64_t comp[kScanUnroll];
 #pragma unroll
-    for (int u = 0; u < kScanUnroll; ++u) {
-        const uint32_t q = qb + u * kResolveThreads + threadIdx.x;
-        comp[u] = 0;
-        if (q < cnt) {
-            const int r = owner_of(rpre, pieces, q);
-            comp[u] = wdense[rstart[r] + (q - rpre[r])];
+            for (int u = 0; u < kScanUnroll; ++u) {
+                const uint32_t q = qb + u * kResolveThreads + tid;
+                comp[u] = q < cnt ? get(q) : 0ull;          // independent loads: all in flight at once
+            }
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u)
+                if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                    atomicAdd(&L.lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
         }
+        __syncthreads();
+        find_rank_bin(L.lh, L.part, L.res, kBins2, rank);
+        if (!L.res[3]) break;                                  // cannot happen: rank <= matching elements
+        prefix = (prefix << (s_hi - s_lo)) | L.res[0];
+        rank -= L.res[1];
+        const uint32_t left = L.res[2];                        // elements that carry the new prefix
+        s_hi = s_lo;
+        if (s_lo == 0 || left == rank) {                       // last digit, or all under this prefix are kept
+            done = true;
+            tc = prefix << s_lo;
+        } else if (left <= (uint32_t)kFew) {
+            if (tid == 0) L.n_few = 0;
+            __syncthreads();
+            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+                uint64_t comp[kScanUnroll];
+#pragma unroll
+                for (int u = 0; u < kScanUnroll; ++u) {
+                    const uint32_t q = qb + u * kResolveThreads + tid;
+                    comp[u] = q < cnt ? get(q) : 0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < kScanUnroll; ++u)
+                    if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                        L.few[atomicAdd(&L.n_few, 1u)] = comp[u];
+            }
+            __syncthreads();
+            if ((uint32_t)tid < left) {
+                const uint64_t mine = L.few[tid];
+                uint32_t greater = 0;
+                for (uint32_t u = 0; u < left; ++u) greater += L.few[u] > mine ? 1u : 0u;
+                if (greater + 1 == rank) L.tc_sh = mine;      // comp values are unique: exactly one thread
+            }
+            __syncthreads();
+            done = true;
+            tc = L.tc_sh;
+        }
+        __syncthreads();
     }
+    return tc;
+}
+
+// Records the finished selection of a worker and prepares the next step's guess: a few fine bins
+// below this threshold - at least twice the distance the threshold just fell (a rising threshold needs
+// no slack), never less than kMinSlack, shrinking by one bin per quiet step, doubled after a miss.
+// One thread calls this.
+__device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorker &w, uint64_t tc, const TkGeom &ge,
+                                              bool missed)
+{
+    ws[i].tc = tc;
+    const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
+    const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
+    uint32_t slack = missed ? w.slack * 2u : w.slack - 1u;
+    slack = max(slack, 2u * fell + 2u);
+    slack = min(max(slack, kMinSlack), kMaxSlack);
+    ws[i].slack = slack;
+    ws[i].last_fine = fine;
+    ws[i].guess = fine > slack ? fine - slack : 0u;
 }
 
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
@@ -703,27 +784,18 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
                                                               uint32_t *__restrict__ cursor,
                                                               uint32_t *__restrict__ hist_full)
 {
-    __shared__ uint32_t lh[kBins2];
-    __shared__ uint32_t part[kResolveThreads / kWave];
-    __shared__ uint32_t res[4];
+    __shared__ ResolveLds L;
     __shared__ uint32_t rpre[kMaxPieces + 1];
     __shared__ uint32_t rstart[kMaxPieces];
-    __shared__ uint64_t few[kFew];
-    __shared__ uint32_t n_few;
-    __shared__ uint64_t tc_sh;
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const TkWorker w = ws[i];
-    uint64_t prefix = w.prefix;
-    uint32_t rank = w.rank;
-    int s_hi = (int)w.pshift + ge.idx_bits;
-    bool done = w.whole != 0;
-    uint64_t tc = prefix << s_hi;
-    const int pieces = ge.slices * ge.parts * 4;
-    const uint64_t *wdense = dense + region_base(ge, i, 0);
-    uint32_t cnt = 0;
-    if (!done) {
+    const int s_hi = (int)w.pshift + ge.idx_bits;
+    uint64_t tc = (uint64_t)w.prefix << s_hi;
+    if (!w.whole) {
+        const int pieces = ge.slices * ge.parts * 4;
+        const uint64_t *wdense = dense + region_base(ge, i, 0);
         // exclusive prefix sum of the piece counts, two pieces per thread
         const uint2 a = (2 * tid < pieces) ? dense_dir[(int64_t)i * pieces + 2 * tid] : make_uint2(0u, 0u);
         const uint2 b = (2 * tid + 1 < pieces) ? dense_dir[(int64_t)i * pieces + 2 * tid + 1] : make_uint2(0u, 0u);
@@ -733,10 +805,10 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             const uint32_t up = __shfl_up(incl, off, kWave);
             if (lane >= off) incl += up;
         }
-        if (lane == kWave - 1) part[wave] = incl;
+        if (lane == kWave - 1) L.part[wave] = incl;
         __syncthreads();
         uint32_t before = 0;
-        for (int q = 0; q < wave; ++q) before += part[q];
+        for (int q = 0; q < wave; ++q) before += L.part[q];
         const uint32_t excl = before + incl - (a.y + b.y);
         if (2 * tid < pieces) {
             rpre[2 * tid] = excl;
@@ -748,74 +820,18 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         }
         if (tid == kResolveThreads - 1) rpre[pieces] = before + incl;   // threads past the pieces add 0
         __syncthreads();
-        cnt = rpre[pieces];
-    }
-
-    while (!done) {
-        const int s_lo = max(s_hi - kDigitBits, 0);
-        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
-        for (int b = tid; b < kBins2; b += kResolveThreads) lh[b] = 0;
-        __syncthreads();
-        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
-            uint64_t comp[kScanUnroll];
-            scan_load(comp, wdense, rpre, rstart, pieces, qb, cnt);
-#pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u)
-                if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
-                    atomicAdd(&lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
-        }
-        __syncthreads();
-        find_rank_bin(lh, part, res, kBins2, rank);
-        if (!res[3]) break;                                    // cannot happen: rank <= matching elements
-        prefix = (prefix << (s_hi - s_lo)) | res[0];
-        rank -= res[1];
-        const uint32_t left = res[2];                          // elements that carry the new prefix
-        s_hi = s_lo;
-        if (s_lo == 0 || left == rank) {                       // last digit, or all under this prefix are kept
-            done = true;
-            tc = prefix << s_lo;
-        } else if (left <= (uint32_t)kFew) {
-            // few elements left: fetch them and rank them against each other (comp values are unique)
-            if (tid == 0) n_few = 0;
-            __syncthreads();
-            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
-                uint64_t comp[kScanUnroll];
-                scan_load(comp, wdense, rpre, rstart, pieces, qb, cnt);
-#pragma unroll
-                for (int u = 0; u < kScanUnroll; ++u)
-                    if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
-                        few[atomicAdd(&n_few, 1u)] = comp[u];
-            }
-            __syncthreads();
-            if ((uint32_t)tid < left) {
-                const uint64_t mine = few[tid];
-                uint32_t greater = 0;
-                for (uint32_t u = 0; u < left; ++u) greater += few[u] > mine ? 1u : 0u;
-                if (greater + 1 == rank) tc_sh = mine;
-            }
-            __syncthreads();
-            done = true;
-            tc = tc_sh;
-        }
-        __syncthreads();
+        const uint32_t cnt = rpre[pieces];
+        // element q of the worker's dense set, found through the prefix sums of the piece counts
+        auto get = [&](uint32_t q) {
+            const int r = owner_of(rpre, pieces, q);
+            return wdense[rstart[r] + (q - rpre[r])];
+        };
+        tc = resolve_digits(get, cnt, w.prefix, w.rank, s_hi, L);
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
         for (int q = tid; q < kBins1; q += kResolveThreads) hist_full[(int64_t)i * kBins1 + q] = 0;
-    if (tid == 0) {
-        ws[i].tc = tc;
-        // The next step lists from a few fine bins below this threshold: at least twice the distance
-        // the threshold just fell (a rising threshold needs no slack), never less than kMinSlack,
-        // shrinking by one bin per quiet step, doubled after a miss.
-        const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
-        const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
-        uint32_t slack = w.relisted ? w.slack * 2u : w.slack - 1u;
-        slack = max(slack, 2u * fell + 2u);
-        slack = min(max(slack, kMinSlack), kMaxSlack);
-        ws[i].slack = slack;
-        ws[i].last_fine = fine;
-        ws[i].guess = fine > slack ? fine - slack : 0u;
-    }
+    if (tid == 0) finish_worker(ws, i, w, tc, ge, w.relisted != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
