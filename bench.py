@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--method", choices=("ef", "cd", "naive", "none"), default="ef",
                     help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1; naive: compression "
                          "without memory; none: no compression")
+    ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
+                    help="f32: comp_ams_step (the headline metric); bf16: comp_ams_step_bf16 on the gradients "
+                         "rounded to bfloat16 (2 instead of 4 bytes read per gradient element)")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -105,7 +108,12 @@ def main() -> int:
     scales = w.scales()
     nbuf = max(1, min(args.buffers, args.steps))
     host_grads = [w.grads(t, scales=scales) for t in range(nbuf)]
-    dev_grads = [torch.from_numpy(g).cuda() for g in host_grads]
+    bf16 = args.grad_dtype == "bf16"
+    if bf16:
+        dev_grads = [torch.from_numpy(g).to(torch.bfloat16).cuda() for g in host_grads]
+        host_grads = [g.float().cpu().numpy() for g in dev_grads]      # what the oracle leg sees: the widened values
+    else:
+        dev_grads = [torch.from_numpy(g).cuda() for g in host_grads]
 
     kb = w.k if w.compressor == W.TOPK else (w.block if w.block else w.d)
     h = P.CompAms(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
@@ -123,10 +131,14 @@ def main() -> int:
         step_bytes += 20 * w.d - (4 * w.n * w.d if w.compressor == W.TOPK else 0)
     elif args.method != "ef":                 # g is read, nothing is stored per worker
         step_bytes -= 8 * w.n * w.d
+    if bf16:
+        step_bytes -= 2 * w.n * w.d
+
+    step_ptr = h.step_bf16_ptr if bf16 else h.step_ptr
 
     def run(k0, count):
         for t in range(k0, k0 + count):
-            h.step_ptr(dev_grads[t % nbuf].data_ptr(), stream)
+            step_ptr(dev_grads[t % nbuf].data_ptr(), stream)
 
     run(0, args.warmup)
     torch.cuda.synchronize()
@@ -146,12 +158,14 @@ def main() -> int:
                       "us_per_step": ms * 1e3 / args.steps} for name, (ms, cnt) in prof.items()}
     dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
     dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d, args.method)
+    if bf16 and dom in ("bs_pass", "tk_pass1", "plain_update"):
+        dom_bytes -= 2 * w.n * w.d
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get((w.name + ("/cd" if cd else ""), dom))
-                if args.method in ("ef", "cd") else None,
+                if args.method in ("ef", "cd") and not bf16 else None,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
     if roofline["traffic"]:
         # bytes the counters saw per launch over the same live duration: the rate the memory system ran at
@@ -217,7 +231,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "method": {"ef": "error_feedback", "cd": "cd_adam", "naive": "naive_compression",
-                                                   "none": "no_compression"}[args.method], "n_workers": w.n, "d": w.d,
+                                                   "none": "no_compression"}[args.method], "gradients": args.grad_dtype, "n_workers": w.n, "d": w.d,
                    "compressor": "topk" if w.compressor == W.TOPK else "blocksign",
                    "k": w.k, "block": w.block, "layer_blocks": w.layer_blocks, "gradient_buffers": nbuf},
         "roofline": roofline,

@@ -98,6 +98,14 @@ int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
  */
 int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream);
 
+/*
+ * The same step with the gradients handed over as bfloat16: grads_bf16_dev holds n*d 16-bit values,
+ * [n][d] row-major, each the upper half of an fp32 number (device memory, 2-byte aligned, borrowed
+ * and not modified).  They are widened exactly, so the step computes what comp_ams_step computes on
+ * the fp32 copy of the same numbers; it reads 2 instead of 4 bytes per gradient element.
+ */
+int comp_ams_step_bf16(comp_ams_t *h, const uint16_t *grads_bf16_dev, void *hip_stream);
+
 /* State getters: d floats each, copied to `out` (host or device memory per on_device). */
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device);
 int comp_ams_get_m(comp_ams_t *h, float *out, int on_device);

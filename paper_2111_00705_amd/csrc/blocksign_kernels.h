@@ -106,8 +106,9 @@ __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base,
 // compression (Section 4): x = g, nothing is read from or written to the stored rows.
 enum { kBsEf = 0, kBsCd = 1, kBsNaive = 2 };
 
-template <bool kPending, int kMode>
-__global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g, float *__restrict__ xs,
+// G: element type of the gradients, float or uint16_t (bfloat16 bits).
+template <bool kPending, int kMode, typename G>
+__global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, float *__restrict__ xs,
                                                     int64_t d, int64_t ld, BsTable tb,
                                                     const float *__restrict__ s_prev,
                                                     uint16_t *__restrict__ signs,
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const float *__restrict__ g,
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
-    const float *grow = g + (int64_t)i * d;
+    const G *grow = g + (int64_t)i * d;
     float *xrow = xs + (int64_t)i * ld;
     const bool uni = tb.uniform_tiles > 0;
     const int p0 = uni ? t : tb.tile_piece0[t], p1 = uni ? t + 1 : tb.tile_piece0[t + 1];

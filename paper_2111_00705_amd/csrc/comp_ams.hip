@@ -265,17 +265,18 @@ int copy_in(comp_ams *h, float *dst_dev, const float *src, size_t count, int on_
     return COMP_AMS_OK;
 }
 
-int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
-            bs_pass<false, kBsNaive><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, kBsNaive, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else if (h->pending)
-            bs_pass<true, kBsEf><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<true, kBsEf, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, kBsEf><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, kBsEf, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     if (!h->fused_scale)
         launch_timed(h, P_BS_SCALE, st, [&] {
@@ -300,15 +301,16 @@ int step_blocksign(comp_ams *h, const float *g, hipStream_t st)
 }
 
 // One iteration of Algorithm 1 (CD-Adam) with the block-wise scaled sign, five launches.
-int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            bs_pass<true, kBsCd><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<true, kBsCd, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, kBsCd><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            bs_pass<false, kBsCd, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     launch_timed(h, P_BS_SCALE, st, [&] {
         bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
@@ -333,10 +335,10 @@ int step_blocksign_cd(comp_ams *h, const float *g, hipStream_t st)
 // The five selection launches between the listing pass and the kernel that uses Tc: candidate
 // histograms, leading digits, second listing (rare), compaction of the threshold bin, last digits.
 // kSrc / a / b say how tk_relist forms the compressed vector again.
-template <int kSrc>
+template <int kSrc, typename G>
 void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
                    uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint64_t *dense,
-                   uint2 *dense_dir, const float *a, const float *b, const int (&slot)[5])
+                   uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5])
 {
     const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
     // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
@@ -344,10 +346,10 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
     const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
     launch_timed(h, slot[0], st, [&] { tk_hist<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, hist1, histf); });
     launch_timed(h, slot[1], st, [&] {
-        tk_pick<kSrc><<<pick, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, hist_full, a, b);
+        tk_pick<kSrc, G><<<pick, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, hist_full, a, b);
     });
     launch_timed(h, slot[2], st, [&] {
-        tk_relist<kSrc><<<sweep, kThreads, 0, st>>>(a, b, ge, ws, hist_full, cand, cursor, tile_dir);
+        tk_relist<kSrc, G><<<sweep, kThreads, 0, st>>>(a, b, ge, ws, hist_full, cand, cursor, tile_dir);
     });
     launch_timed(h, slot[3], st, [&] {
         tk_compact<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, dense, dense_dir);
@@ -361,14 +363,15 @@ constexpr int kWorkerSelectSlots[5] = {P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_C
 constexpr int kServerSelectSlots[5] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER,
                                        P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
 
-int step_topk(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_topk(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassEf><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        tk_pass1<kPassEf, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
-    launch_select<kSrcStored>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                               h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
@@ -378,14 +381,15 @@ int step_topk(comp_ams *h, const float *g, hipStream_t st)
 }
 
 // Naive compression (Section 4) with Top-k: as step_topk, on g itself.
-int step_topk_naive(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassNaive><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        tk_pass1<kPassNaive, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                           h->tile_dir);
     });
-    launch_select<kSrcGradOnly>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                                 h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
         tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
@@ -395,35 +399,37 @@ int step_topk_naive(comp_ams *h, const float *g, hipStream_t st)
 }
 
 // Vanilla distributed AMSGrad (Section 3): no compression.
-int step_plain(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_plain(comp_ams *h, const G *g, hipStream_t st)
 {
     launch_timed(h, P_PLAIN_UPDATE, st, [&] {
-        plain_update<<<(unsigned)(h->ld / kTile), kThreads, 0, st>>>(g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
+        plain_update<G><<<(unsigned)(h->ld / kTile), kThreads, 0, st>>>(g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
                                                                      h->params);
     });
     return COMP_AMS_OK;
 }
 
 // One iteration of Algorithm 1 (CD-Adam) with Top-k in both directions, fourteen launches.
-int step_topk_cd(comp_ams *h, const float *g, hipStream_t st)
+template <typename G>
+int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassCd><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        tk_pass1<kPassCd, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
-    launch_select<kSrcGrad>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                             h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         tk_merge<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
-        tk_pass1<kPassDiff><<<dim3(ge.n_tiles, 1), kThreads, 0, st>>>(h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
+        tk_pass1<kPassDiff, float><<<dim3(ge.n_tiles, 1), kThreads, 0, st>>>(h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
                                                                       sv.cursor, sv.tile_dir);
     });
-    launch_select<kSrcDiff>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
+    launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
                             h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         tk_apply<<<ge.n_tiles, kThreads, 0, st>>>(sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
@@ -492,6 +498,34 @@ void launch_materialize(comp_ams *h, int worker, float *dst)
     } else {
         bs_materialize_error<false><<<blocks, kThreads, 0, h->stream>>>(xrow, h->d, h->tb, h->scales, dst);
     }
+}
+
+template <typename G>
+int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (!grads_dev) return fail(h, COMP_AMS_EINVAL, "grads is NULL");
+    if (reinterpret_cast<uintptr_t>(grads_dev) & (sizeof(G) - 1))
+        return fail(h, COMP_AMS_EINVAL, "grads must be %zu-byte aligned", sizeof(G));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (st != h->stream) {
+        // work of earlier steps on another stream must be finished before this stream touches the state
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        h->stream = st;
+    }
+    if (h->method == COMP_AMS_METHOD_NONE)
+        rc = step_plain(h, grads_dev, st);
+    else if (h->compressor == COMP_AMS_TOPK)
+        rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
+             : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
+                                                    : step_topk(h, grads_dev, st);
+    else
+        rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
+    if (rc) return rc;
+    HIP_TRY(h, hipGetLastError());
+    ++h->steps;
+    return COMP_AMS_OK;
 }
 
 }  // namespace
@@ -661,30 +695,11 @@ int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode)
     return COMP_AMS_OK;
 }
 
-int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream)
+int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream) { return step_any(h, grads_dev, hip_stream); }
+
+int comp_ams_step_bf16(comp_ams_t *h, const uint16_t *grads_bf16_dev, void *hip_stream)
 {
-    int rc = check_handle(h);
-    if (rc) return rc;
-    if (!grads_dev) return fail(h, COMP_AMS_EINVAL, "grads is NULL");
-    if (reinterpret_cast<uintptr_t>(grads_dev) & 3u) return fail(h, COMP_AMS_EINVAL, "grads must be 4-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (st != h->stream) {
-        // work of earlier steps on another stream must be finished before this stream touches the state
-        HIP_TRY(h, hipStreamSynchronize(h->stream));
-        h->stream = st;
-    }
-    if (h->method == COMP_AMS_METHOD_NONE)
-        rc = step_plain(h, grads_dev, st);
-    else if (h->compressor == COMP_AMS_TOPK)
-        rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
-             : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
-                                                    : step_topk(h, grads_dev, st);
-    else
-        rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
-    if (rc) return rc;
-    HIP_TRY(h, hipGetLastError());
-    ++h->steps;
-    return COMP_AMS_OK;
+    return step_any(h, grads_bf16_dev, hip_stream);
 }
 
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device)

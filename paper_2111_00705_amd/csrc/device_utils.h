@@ -90,6 +90,39 @@ __device__ __forceinline__ float4 load_grad4(const float *__restrict__ row, int6
     return r;
 }
 
+// Gradients handed over as bfloat16 (the upper 16 bits of the fp32 value): widened exactly, so every
+// formula downstream sees the same fp32 numbers as with an fp32 copy of them.  Rows start at any 2-byte
+// alignment; 8-/4-/2-byte aligned groups of four take a 64-/32-/16-bit load path.
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf16_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ float4 load_grad4(const uint16_t *__restrict__ row, int64_t j, int64_t d)
+{
+    const uint16_t *p = row + j;
+    if (j + 4 <= d) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(p) & 7u;
+        if (a == 0) {
+            const v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u *>(p));
+            return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xffff0000u),
+                               __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xffff0000u));
+        }
+        if (a == 4) {
+            const uint32_t lo = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+            const uint32_t hi = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p + 2));
+            return make_float4(__uint_as_float(lo << 16), __uint_as_float(lo & 0xffff0000u),
+                               __uint_as_float(hi << 16), __uint_as_float(hi & 0xffff0000u));
+        }
+        return make_float4(bf16_to_float(p[0]), bf16_to_float(p[1]), bf16_to_float(p[2]), bf16_to_float(p[3]));
+    }
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d) r.x = bf16_to_float(p[0]);
+    if (j + 1 < d) r.y = bf16_to_float(p[1]);
+    if (j + 2 < d) r.z = bf16_to_float(p[2]);
+    if (j + 3 < d) r.w = bf16_to_float(p[3]);
+    return r;
+}
+
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ void st4(float *p, const float4 &v) { *reinterpret_cast<float4 *>(p) = v; }
 

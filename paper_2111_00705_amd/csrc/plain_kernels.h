@@ -8,7 +8,8 @@ namespace cams {
 
 constexpr int kPlainBatch = 4;   // workers whose gradients are in flight together
 
-__global__ __launch_bounds__(kThreads) void plain_update(const float *__restrict__ g, int64_t d, int n,
+template <typename G>   // float or uint16_t (bfloat16 bits)
+__global__ __launch_bounds__(kThreads) void plain_update(const G *__restrict__ g, int64_t d, int n,
                                                          float *__restrict__ theta, float *__restrict__ m,
                                                          float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {

@@ -251,8 +251,8 @@ __device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32
 //        kPassNaive  naive compression (Section 4): x = g, the stored rows are not touched.
 enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2, kPassNaive = 3 };
 
-template <bool kFull, int kMode>
-__device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, float *__restrict__ xrow,
+template <bool kFull, int kMode, typename G>
+__device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
                                                uint2 *stage)
 {
@@ -261,7 +261,10 @@ __device__ __forceinline__ uint32_t pass1_tile(const float *__restrict__ grow, f
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (tid + kThreads * r);
-        gv[r] = kMode == kPassDiff ? ld4(grow + j) : load_grad4(grow, j, d);
+        if constexpr (kMode == kPassDiff)
+            gv[r] = ld4(grow + j);
+        else
+            gv[r] = load_grad4(grow, j, d);
         xv[r] = kMode == kPassNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4(xrow + j);
     }
     uint32_t count = 0;
@@ -328,8 +331,9 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
     }
 }
 
-template <int kMode>
-__global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g, float *__restrict__ xs, TkGeom ge,
+// G: element type of g - float, or uint16_t (bfloat16 bits) for gradients handed over as bfloat16.
+template <int kMode, typename G>
+__global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, float *__restrict__ xs, TkGeom ge,
                                                      const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
@@ -346,11 +350,11 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const float *__restrict__ g
     if (tid == 0) sh[4] = 0;
     __syncthreads();
     uint32_t count;
-    const float *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
+    const G *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
-        count = pass1_tile<true, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
+        count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
     else
-        count = pass1_tile<false, kMode>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
+        count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
     finish_tile(stage, sh, count, ge, i, t, cand, cursor, tile_dir);
 }
 
@@ -425,14 +429,19 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
 enum { kSrcStored = 0, kSrcGrad = 1, kSrcDiff = 2, kSrcGradOnly = 3 };
 
 // The 16 values of this thread in the tile at `base` (coordinates base + 4 (tid + 256 r) + c).
-template <int kSrc>
-__device__ __forceinline__ void load_source_tile(float (&x)[4][4], const float *__restrict__ arow,
+// a: for kSrcGrad / kSrcGradOnly row i of the gradients (elements of type G), else a padded float row.
+template <int kSrc, typename G>
+__device__ __forceinline__ void load_source_tile(float (&x)[4][4], const void *__restrict__ a, int i, const TkGeom &ge,
                                                  const float *__restrict__ brow, uint32_t base, uint32_t d)
 {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (threadIdx.x + kThreads * r);
-        const float4 av = (kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? load_grad4(arow, j, d) : ld4(arow + j);
+        float4 av;
+        if constexpr (kSrc == kSrcGrad || kSrc == kSrcGradOnly)
+            av = load_grad4(static_cast<const G *>(a) + (int64_t)i * ge.d, j, d);
+        else
+            av = ld4(static_cast<const float *>(a) + (int64_t)i * ge.ld + j);
         x[r][0] = av.x;
         x[r][1] = av.y;
         x[r][2] = av.z;
@@ -456,11 +465,11 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const float *
 // Bin 0 (zeros and the smallest denormals) is not counted but taken as the remainder: in a sparse
 // vector it would draw most LDS atomics of a tile to one word.
 // Consumes (and clears) the candidate histograms.
-template <int kSrc>
+template <int kSrc, typename G>
 __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
                                                     uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
                                                     uint32_t *__restrict__ cursor, uint32_t *__restrict__ hist_full,
-                                                    const float *__restrict__ a, const float *__restrict__ b)
+                                                    const void *__restrict__ a, const float *__restrict__ b)
 {
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
@@ -537,12 +546,11 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
     for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
     __syncthreads();
     const uint32_t d = (uint32_t)ge.d;
-    const float *arow = a + (int64_t)i * ((kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? ge.d : ge.ld);
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
-        load_source_tile<kSrc>(x, arow, brow, base, d);
+        load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -569,8 +577,8 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
 // it) and lists the elements in that bin or above into the (emptied) regions of the worker.  A small
 // grid whose workgroups loop over tiles: in the usual case every workgroup returns at once, and a
 // small grid does that fast.
-template <int kSrc>
-__global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ a, const float *__restrict__ b,
+template <int kSrc, typename G>
+__global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a, const float *__restrict__ b,
                                                       TkGeom ge, TkWorker *__restrict__ ws,
                                                       const uint32_t *__restrict__ hist_full,
                                                       uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
@@ -608,12 +616,11 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const float *__restrict__ 
         ws[i].rank = ge.k - res[1];
         ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
     }
-    const float *arow = a + (int64_t)i * ((kSrc == kSrcGrad || kSrc == kSrcGradOnly) ? ge.d : ge.ld);
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
-        load_source_tile<kSrc>(x, arow, brow, base, d);
+        load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
         uint32_t count = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r)
