@@ -365,3 +365,16 @@ def test_cd_topk_resume_and_status_codes():
         ef.get_server_selected()
     assert ei.value.code == P.ESTATE
     a.destroy(); c.destroy(); ef.destroy()
+
+
+def test_cd_topk_long_run_with_a_wandering_gradient_scale():
+    announce("CD-Adam Top-k long run")
+    n, d, k, steps = 4, 200_003, 2000, 30
+    rng = np.random.default_rng(2025)
+    base_scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    walk = np.cumprod(1.0 + rng.uniform(-0.08, 0.08, steps))
+    walk[[9, 21]] *= 0.5
+    gpu, ora = make_cd_topk_pair(d, n, k, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    run_cd_topk(gpu, ora, lambda t: (np.random.default_rng([2025, t]).standard_normal((n, d)).astype(f32) * base_scale
+                                     * f32(walk[t])).astype(f32), steps=steps, tag="long run")
+    gpu.destroy()

@@ -385,3 +385,27 @@ def test_blocksign_many_workers():
         run_steps(gpu, ora, lambda t: (np.random.default_rng([70, t]).laplace(0, 1, (n, d)) * scale).astype(f32),
                   steps=3, tag=f"n=70 B={B}", offsets=off)
         gpu.destroy()
+
+
+def test_topk_long_run_with_a_wandering_gradient_scale():
+    """The guess and its slack are carried from step to step; over many steps with a gradient scale that
+    wanders (±8 % per step, with occasional drops) the threshold moves up and down, through the slack
+    and back.  Every step must still agree with the oracle, whichever path found the threshold."""
+    announce("topk long run")
+    import torch
+    n, d, k, steps = 4, 200_003, 2000, 40
+    rng = np.random.default_rng(2024)
+    base_scale = np.exp(rng.uniform(-5, 0, d)).astype(f32)
+    walk = np.cumprod(1.0 + rng.uniform(-0.08, 0.08, steps))
+    walk[[11, 23, 31]] *= 0.5
+    gpu, ora = make_pair(d, n, P.TOPK, k, theta0=(0.01 * rng.standard_normal(d)).astype(f32))
+    second_listings = 0
+    for t in range(steps):
+        g = (np.random.default_rng([2024, t]).standard_normal((n, d)).astype(f32) * base_scale * f32(walk[t])).astype(f32)
+        x = g + ora.error
+        gpu.step(torch.from_numpy(g).cuda())
+        ora.step(g)
+        compare(gpu, ora, x_for_values=x, tag=f"long run step {t}")
+        second_listings += sum(gpu.get_selection_info(i)["relisted"] for i in range(n))
+    assert n <= second_listings < n * steps // 2      # the first step always; later ones only now and then
+    gpu.destroy()
