@@ -206,9 +206,12 @@ constexpr int kSignBatch = 8;       // workers whose sign words are loaded toget
 // then; theta, m, v, vhat only otherwise.
 struct BsMarkov {
     float *ghat;            // [ld] the server's aggregate
-    const float *gtil;      // [ld] gtilde of the step before
+    float *gtil;            // [ld] gtilde of the step before (rewritten here only when whole_blocks is set)
     uint16_t *signs;        // [n_tiles][256] sign bits of w
     double *partial;        // [n_pieces] piece sums of |w|
+    float *scales;          // [n_blocks] scales of the server's message
+    int32_t whole_blocks;   // every tile is exactly one block: the block's scale of w is known inside the
+                            // workgroup, so lines 9-16 of Algorithm 1 follow at once (no bs_scale, no bs_apply)
 };
 
 template <bool kFusedScale, bool kEarlyState, bool kMarkov>
@@ -352,7 +355,38 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
         }
         mk.signs[(int64_t)t * kThreads + tid] = (uint16_t)sign_bits;
         __syncthreads();   // s_lds readers are done before scratch is used (separate arrays; keeps phases apart)
-        piece_sums(w, base, p0, p1, tb, scratch, mk.partial);
+        if (!mk.whole_blocks) {
+            piece_sums(w, base, p0, p1, tb, scratch, mk.partial);
+            return;
+        }
+        // c = C(w) with the scale of this tile's block, gtilde += c, AMSGrad with gtilde
+        double a64 = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) a64 += (double)fabsf(w[r][c]);
+        const double S = block_sum(a64, scratch);
+        const double blen = (double)min((int64_t)kTile, d - base);
+        const float s = (float)(S / blen);
+        if (tid == 0) mk.scales[b_single] = s;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t j = base + 4 * (tid + kThreads * r);
+            const float4 gt4 = ld4(mk.gtil + j);       // in cache: read a moment ago
+            const float gt[4] = {gt4.x, gt4.y, gt4.z, gt4.w};
+            float nt[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                nt[c] = (j + c < d) ? fadd(gt[c], signed_scale(s, sign_bits, r * 4 + c)) : gt[c];   // padding stays 0
+            const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
+            float4 th4 = ld4(theta + j), m4 = ld4(m + j), v4 = ld4(v + j), vh4 = ld4(vhat + j);
+            amsgrad_update4(th4, m4, v4, vh4, g4, p);
+            st4(mk.gtil + j, g4);
+            st4(theta + j, th4);
+            st4(m + j, m4);
+            st4(v + j, v4);
+            st4(vhat + j, vh4);
+        }
         return;
     }
     if (!kEarlyState) {

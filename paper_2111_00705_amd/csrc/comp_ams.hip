@@ -312,22 +312,33 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
         else
             bs_pass<false, kBsCd, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
-    launch_timed(h, P_BS_SCALE, st, [&] {
-        bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
-    });
+    // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
+    // scale are formed inside bs_update, which then also applies the server's message - two launches in all
+    const bool whole = h->fused_scale && tb.n_pieces == tb.n_blocks;
+    if (!whole)
+        launch_timed(h, P_BS_SCALE, st, [&] {
+            bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
+        });
     launch_timed(h, P_BS_SERVER, st, [&] {
-        const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv};
-        bs_update<false, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
-                                                                   h->signs, h->theta, h->m, h->v, h->vhat,
-                                                                   h->params, mk);
+        const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
+        if (whole)
+            bs_update<true, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
+                                                                      h->signs, h->theta, h->m, h->v, h->vhat,
+                                                                      h->params, mk);
+        else
+            bs_update<false, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
+                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
+                                                                       h->params, mk);
     });
-    launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
-        bs_scale<<<dim3(tb.n_blocks, 1), kWave, 0, st>>>(h->partial_srv, tb, h->scales_srv);
-    });
-    launch_timed(h, P_BS_APPLY, st, [&] {
-        bs_apply<<<grid.x, kThreads, 0, st>>>(h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m, h->v,
-                                              h->vhat, h->params);
-    });
+    if (!whole) {
+        launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
+            bs_scale<<<dim3(tb.n_blocks, 1), kWave, 0, st>>>(h->partial_srv, tb, h->scales_srv);
+        });
+        launch_timed(h, P_BS_APPLY, st, [&] {
+            bs_apply<<<grid.x, kThreads, 0, st>>>(h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
+                                                  h->v, h->vhat, h->params);
+        });
+    }
     h->pending = true;
     return COMP_AMS_OK;
 }
