@@ -74,8 +74,8 @@ def kernel_algorithmic_bytes(name: str, n: int, d: int, method: str = "ef") -> i
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)     # 1000 steps of the headline workload: about 60 ms timed
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the five named workloads")
     ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
