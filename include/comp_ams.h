@@ -95,6 +95,9 @@ int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
  * (worker i at grads_dev + i*d), read-only, owned by the caller and borrowed until the work
  * enqueued on `hip_stream` (a hipStream_t, NULL = the null stream) has completed.
  * The base pointer must be 4-byte aligned; 16-byte alignment gives the fast path.
+ * The call only launches kernels (no allocation, no memset, no wait while the stream stays the
+ * same), so it may be recorded into a HIP graph; record after at least one ordinary step on the same
+ * stream: the first step of a handle launches a different variant of the first kernel than the later ones.
  */
 int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream);
 

@@ -206,3 +206,44 @@ def test_scaled_sign_message_rebuilt_from_bits_and_scales(method):
         gpu.get_signs(n if method != P.METHOD_CD else n + 1)
     assert ei.value.code == P.EINVAL
     gpu.destroy()
+
+
+@pytest.mark.parametrize("comp,kb,method", [(P.TOPK, 300, P.METHOD_EF), (P.BLOCKSIGN, 4096, P.METHOD_EF),
+                                            (P.TOPK, 300, P.METHOD_CD), (P.BLOCKSIGN, 1000, P.METHOD_CD)])
+def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
+    """comp_ams_step allocates nothing and clears its counters in kernels, so a caller may capture it.
+    The captured step is replayed several times, with fresh gradients copied into the captured buffer
+    by ordinary eager work in between, and every replay is checked against the oracle."""
+    import torch
+    announce(f"graph capture comp={comp} method={method}")
+    d, n = 30_011, 4
+    gpu = P.CompAms(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR)
+    ora = O.Oracle(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR, method=method)
+    gpu.set_method(method)
+    grads = [np.random.default_rng([13, t]).standard_normal((n, d)).astype(f32) for t in range(7)]
+    side = torch.cuda.Stream()
+    gbuf = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(side):
+        for t in range(2):                                 # eager steps on the stream that will capture
+            gbuf.copy_(torch.from_numpy(grads[t]))
+            gpu.step(gbuf)
+            ora.step(grads[t])
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        gpu.step(gbuf)                                     # recorded, not run
+    for t in range(2, 7):
+        with torch.cuda.stream(side):
+            gbuf.copy_(torch.from_numpy(grads[t]))
+        side.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ora.step(grads[t])
+        for name, got, want in (("theta", gpu.get_theta(), ora.theta), ("vhat", gpu.get_vhat(), ora.vhat)):
+            ok = rel_close(got, want, STATE_RTOL)
+            assert ok.all(), f"replay {t} {name}: {np.count_nonzero(~ok)} coordinates differ"
+        if method == P.METHOD_EF:
+            assert np.array_equal(bits(gpu.get_error(1)), bits(ora.error[1])), t
+        else:
+            assert np.array_equal(bits(gpu.get_ghat_worker(1)), bits(ora.ghat_workers[1])), t
+    gpu.destroy()
