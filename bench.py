@@ -83,9 +83,9 @@ def main() -> int:
     ap.add_argument("--method", choices=("ef", "cd", "naive", "none"), default="ef",
                     help="ef: error feedback (the headline metric); cd: CD-Adam, Algorithm 1; naive: compression "
                          "without memory; none: no compression")
-    ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
-                    help="f32: comp_ams_step (the headline metric); bf16: comp_ams_step_bf16 on the gradients "
-                         "rounded to bfloat16 (2 instead of 4 bytes read per gradient element)")
+    ap.add_argument("--grad-dtype", choices=("f32", "bf16", "f16"), default="f32",
+                    help="f32: comp_ams_step (the headline metric); bf16 / f16: comp_ams_step_bf16 / _f16 on the "
+                         "gradients rounded to that type (2 instead of 4 bytes read per gradient element)")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -108,9 +108,10 @@ def main() -> int:
     scales = w.scales()
     nbuf = max(1, min(args.buffers, args.steps))
     host_grads = [w.grads(t, scales=scales) for t in range(nbuf)]
-    bf16 = args.grad_dtype == "bf16"
+    bf16 = args.grad_dtype != "f32"           # either 16-bit type
     if bf16:
-        dev_grads = [torch.from_numpy(g).to(torch.bfloat16).cuda() for g in host_grads]
+        narrow = torch.bfloat16 if args.grad_dtype == "bf16" else torch.float16
+        dev_grads = [torch.from_numpy(g).to(narrow).cuda() for g in host_grads]
         host_grads = [g.float().cpu().numpy() for g in dev_grads]      # what the oracle leg sees: the widened values
     else:
         dev_grads = [torch.from_numpy(g).cuda() for g in host_grads]
@@ -134,7 +135,7 @@ def main() -> int:
     if bf16:
         step_bytes -= 2 * w.n * w.d
 
-    step_ptr = h.step_bf16_ptr if bf16 else h.step_ptr
+    step_ptr = {"f32": h.step_ptr, "bf16": h.step_bf16_ptr, "f16": h.step_f16_ptr}[args.grad_dtype]
 
     def run(k0, count):
         for t in range(k0, k0 + count):

@@ -109,6 +109,13 @@ int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream);
  */
 int comp_ams_step_bf16(comp_ams_t *h, const uint16_t *grads_bf16_dev, void *hip_stream);
 
+/*
+ * The same with IEEE half precision gradients (1 sign, 5 exponent, 10 fraction bits, subnormals
+ * included; every finite half value is an fp32 value, so the widening is exact).  Same layout,
+ * alignment and ownership as comp_ams_step_bf16.
+ */
+int comp_ams_step_f16(comp_ams_t *h, const uint16_t *grads_f16_dev, void *hip_stream);
+
 /* State getters: d floats each, copied to `out` (host or device memory per on_device). */
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device);
 int comp_ams_get_m(comp_ams_t *h, float *out, int on_device);

@@ -31,7 +31,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
-    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16",
+    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16",
 ]
 
 
@@ -65,6 +65,7 @@ def lib():
         L.comp_ams_set_eps_mode.argtypes = [vp, C.c_int32]
         L.comp_ams_step.argtypes = [vp, fp, vp]
         L.comp_ams_step_bf16.argtypes = [vp, fp, vp]
+        L.comp_ams_step_f16.argtypes = [vp, vp, vp]
         for name in ("theta", "m", "v", "vhat"):
             getattr(L, "comp_ams_get_" + name).argtypes = [vp, fp, C.c_int]
         L.comp_ams_get_error.argtypes = [vp, C.c_int32, fp, C.c_int]
@@ -232,6 +233,18 @@ class CompAms:
 
     def step_bf16_ptr(self, grads_ptr, stream=0):
         self._check(lib().comp_ams_step_bf16(self._h, grads_ptr, stream))
+
+    def step_f16(self, grads, stream=None):
+        """grads: torch float16 tensor [n, d] on the GPU."""
+        import torch
+        assert grads.is_cuda and grads.dtype == torch.float16 and grads.is_contiguous()
+        assert grads.numel() == self.n * self.d
+        if stream is None:
+            stream = torch.cuda.current_stream(grads.device).cuda_stream
+        self._check(lib().comp_ams_step_f16(self._h, grads.data_ptr(), stream))
+
+    def step_f16_ptr(self, grads_ptr, stream=0):
+        self._check(lib().comp_ams_step_f16(self._h, grads_ptr, stream))
 
     def _get_vec(self, fn, out):
         if out is None:

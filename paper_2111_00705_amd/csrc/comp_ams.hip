@@ -713,6 +713,11 @@ int comp_ams_step_bf16(comp_ams_t *h, const uint16_t *grads_bf16_dev, void *hip_
     return step_any(h, grads_bf16_dev, hip_stream);
 }
 
+int comp_ams_step_f16(comp_ams_t *h, const uint16_t *grads_f16_dev, void *hip_stream)
+{
+    return step_any(h, reinterpret_cast<const f16bits *>(grads_f16_dev), hip_stream);
+}
+
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device)
 {
     int rc = check_handle(h);

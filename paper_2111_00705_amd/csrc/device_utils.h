@@ -2,6 +2,7 @@
 // of any alignment, wavefront reductions with a fixed tree, and the AMSGrad update line.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 namespace cams {
@@ -120,6 +121,43 @@ __device__ __forceinline__ float4 load_grad4(const uint16_t *__restrict__ row, i
     if (j + 1 < d) r.y = bf16_to_float(p[1]);
     if (j + 2 < d) r.z = bf16_to_float(p[2]);
     if (j + 3 < d) r.w = bf16_to_float(p[3]);
+    return r;
+}
+
+// Gradients handed over as IEEE half precision: same layout and load paths as bfloat16, widened exactly
+// by the hardware conversion.  The wrapper type only tells the two 16-bit formats apart.
+struct f16bits {
+    uint16_t v;
+};
+static_assert(sizeof(f16bits) == 2, "f16bits is a plain 16-bit value");
+
+__device__ __forceinline__ float f16_to_float(uint32_t h) { return __half2float(__ushort_as_half((unsigned short)h)); }
+
+__device__ __forceinline__ float4 load_grad4(const f16bits *__restrict__ row, int64_t j, int64_t d)
+{
+    const uint16_t *p = reinterpret_cast<const uint16_t *>(row) + j;
+    if (j + 4 <= d) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(p) & 7u;
+        uint32_t lo, hi;
+        if (a == 0) {
+            const v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u *>(p));
+            lo = t.x;
+            hi = t.y;
+        } else if (a == 4) {
+            lo = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+            hi = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p + 2));
+        } else {
+            lo = (uint32_t)p[0] | ((uint32_t)p[1] << 16);
+            hi = (uint32_t)p[2] | ((uint32_t)p[3] << 16);
+        }
+        return make_float4(f16_to_float(lo & 0xffffu), f16_to_float(lo >> 16), f16_to_float(hi & 0xffffu),
+                           f16_to_float(hi >> 16));
+    }
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d) r.x = f16_to_float(p[0]);
+    if (j + 1 < d) r.y = f16_to_float(p[1]);
+    if (j + 2 < d) r.z = f16_to_float(p[2]);
+    if (j + 3 < d) r.w = f16_to_float(p[3]);
     return r;
 }
 
