@@ -19,6 +19,8 @@
  *   AMSGrad             Section 3: m, v, vhat = max(vhat, v), x -= alpha Vhat^{-1/2} m
  *   naive compression   Section 4, "Naive compression": ghat_i = C(g_i), no memory
  *   no compression      Section 3: gbar = (1/n) sum_i g_i (vanilla distributed AMSGrad)
+ *   Rand-k              Appendix A, "Rand-k": keep a random set S of k coordinates, drawn
+ *                         anew for every (step, worker) by a counter-based generator
  *   CD-Adam             Section 5, Algorithm 1: Markov compression on the workers
  *                         (c_i = C(g_i - ghat_i), ghat_i += c_i), on the server
  *                         (ghat += mean c_i, c = C(ghat - gtilde), gtilde += c),
@@ -32,7 +34,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORACLE_TOPK = 0, ORACLE_BLOCKSIGN = 1 };
+enum { ORACLE_TOPK = 0, ORACLE_BLOCKSIGN = 1, ORACLE_RANDK = 2 };
 /* error feedback (Section 4) / CD-Adam (Algorithm 1) / naive compression (Section 4, first
  * paragraph, with AMSGrad in the place of SGD as in the paper's comparison) / no compression
  * (vanilla distributed AMSGrad, Section 3) */
@@ -42,7 +44,9 @@ typedef struct oracle {
     int64_t d;
     int32_t n;
     int32_t compressor;
-    int64_t k;          /* Top-k */
+    int64_t k;          /* Top-k, Rand-k */
+    uint64_t seed;      /* Rand-k: the generator's seed ... */
+    uint32_t draw;      /* ... and how many steps have drawn from it */
     int32_t n_blocks;   /* block sign */
     int64_t *offsets;   /* n_blocks + 1 */
     float beta1, beta2, eps, lr;
@@ -87,16 +91,15 @@ static int cmp_u32(const void *a, const void *b)
     return (x > y) - (x < y);
 }
 
-/* Top-k (Appendix A).  c[j] = x[j] on the k coordinates of largest magnitude and
- * +0.0 elsewhere.  The paper is silent on ties: the coordinate of lower index wins.
- * sel_out (may be NULL) receives the k selected indices in ascending order.
- * Method: sort all d (magnitude descending, index ascending) and take the first k. */
-void oracle_topk(const float *x, int64_t d, int64_t k, float *c, uint32_t *sel_out)
+/* c[j] = x[j] on the k coordinates of largest key and +0.0 elsewhere; among equal keys the
+ * coordinate of lower index wins.  sel_out (may be NULL) receives the k selected indices in
+ * ascending order.  Method: sort all d (key descending, index ascending) and take the first k. */
+static void keep_largest(const uint32_t *key, const float *x, int64_t d, int64_t k, float *c, uint32_t *sel_out)
 {
     uint64_t *rec = (uint64_t *)malloc((size_t)d * sizeof *rec);
     for (int64_t j = 0; j < d; ++j) {
         /* ascending order of (inverted key, index) == key descending, index ascending */
-        uint64_t inv = (uint64_t)(0x7fffffffu - magnitude_key(x[j]));
+        uint64_t inv = (uint64_t)(0xffffffffu - key[j]);
         rec[j] = (inv << 32) | (uint64_t)(uint32_t)j;
     }
     qsort(rec, (size_t)d, sizeof *rec, cmp_u64);
@@ -108,6 +111,52 @@ void oracle_topk(const float *x, int64_t d, int64_t k, float *c, uint32_t *sel_o
     }
     if (sel_out) qsort(sel_out, (size_t)k, sizeof *sel_out, cmp_u32);
     free(rec);
+}
+
+/* Top-k (Appendix A): the k coordinates of largest magnitude.  The paper is silent on ties:
+ * the coordinate of lower index wins. */
+void oracle_topk(const float *x, int64_t d, int64_t k, float *c, uint32_t *sel_out)
+{
+    uint32_t *key = (uint32_t *)malloc((size_t)d * sizeof *key);
+    for (int64_t j = 0; j < d; ++j) key[j] = magnitude_key(x[j]);
+    keep_largest(key, x, d, k, c, sel_out);
+    free(key);
+}
+
+/* ---- Rand-k (Appendix A) ---------------------------------------------------------
+ * C(x) = sum_{j in S} x_j e_j for a random S of k coordinates.  The paper does not say how S is
+ * drawn.  Reading: every coordinate gets a pseudo-random 31-bit score that depends on
+ * (seed, draw, who, j) only - draw counts the steps, who is the worker (n for the server of
+ * Algorithm 1) - and S is the k coordinates of largest score, lower index first among equal
+ * scores.  For fixed (seed, draw, who) the score is a bijection of the 32-bit index followed by a
+ * shift, so at most two coordinates share a score; S does not depend on x.
+ * The generator is counter-based (no state is carried from coordinate to coordinate) and built
+ * from the 32-bit finaliser of MurmurHash3 (public domain): two xor-shift-multiply rounds. */
+uint32_t oracle_mix32(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85ebca6bu;
+    h ^= h >> 13;
+    h *= 0xc2b2ae35u;
+    h ^= h >> 16;
+    return h;
+}
+
+uint32_t oracle_randk_score(uint64_t seed, uint32_t draw, uint32_t who, uint32_t j)
+{
+    const uint32_t per_step = oracle_mix32((uint32_t)seed + draw * 0x9e3779b9u);
+    const uint32_t a = oracle_mix32(per_step ^ (uint32_t)(seed >> 32) ^ (who * 0x85ebca6bu));
+    const uint32_t b = oracle_mix32(a + 0xc2b2ae35u);
+    return oracle_mix32(oracle_mix32(j + a) ^ b) >> 1;
+}
+
+void oracle_randk(const float *x, int64_t d, int64_t k, uint64_t seed, uint32_t draw, uint32_t who, float *c,
+                  uint32_t *sel_out)
+{
+    uint32_t *key = (uint32_t *)malloc((size_t)d * sizeof *key);
+    for (int64_t j = 0; j < d; ++j) key[j] = oracle_randk_score(seed, draw, who, (uint32_t)j);
+    keep_largest(key, x, d, k, c, sel_out);
+    free(key);
 }
 
 /* Scaled sign (Appendix A) on each contiguous block [off[b], off[b+1]):
@@ -167,7 +216,7 @@ oracle_t *oracle_create(int64_t d, int32_t n, int32_t compressor, int64_t k_or_b
     o->gbar = (float *)calloc((size_t)d, sizeof(float));
     o->e = (float *)calloc((size_t)n * (size_t)d, sizeof(float));
     o->c = (float *)calloc((size_t)n * (size_t)d, sizeof(float));
-    if (compressor == ORACLE_TOPK) {
+    if (compressor == ORACLE_TOPK || compressor == ORACLE_RANDK) {
         o->k = k_or_block;
         o->sel = (uint32_t *)calloc((size_t)n * (size_t)o->k, sizeof(uint32_t));
     } else {
@@ -207,7 +256,7 @@ void oracle_set_method(oracle_t *o, int32_t method)
     o->ghat_s = (float *)calloc((size_t)o->d, sizeof(float));
     o->gtil = (float *)calloc((size_t)o->d, sizeof(float));
     o->c_s = (float *)calloc((size_t)o->d, sizeof(float));
-    if (o->compressor == ORACLE_TOPK)
+    if (o->compressor != ORACLE_BLOCKSIGN)
         o->sel_s = (uint32_t *)calloc((size_t)o->k, sizeof(uint32_t));
     else
         o->scales_s = (float *)calloc((size_t)o->n_blocks, sizeof(float));
@@ -216,6 +265,12 @@ void oracle_set_method(oracle_t *o, int32_t method)
 void oracle_set_theta(oracle_t *o, const float *theta) { memcpy(o->theta, theta, (size_t)o->d * sizeof(float)); }
 void oracle_set_lr(oracle_t *o, float lr) { o->lr = lr; }
 void oracle_set_eps_mode(oracle_t *o, int32_t mode) { o->eps_mode = mode; }
+/* Rand-k: the seed, and the number of the next draw (= steps taken so far, for a resumed run) */
+void oracle_set_rand(oracle_t *o, uint64_t seed, uint32_t draw)
+{
+    o->seed = seed;
+    o->draw = draw;
+}
 
 /* One step on gradients g[n][d] (row-major).  Workers are independent until the
  * average, so the loop over workers may run on several threads; no sum is split
@@ -247,8 +302,11 @@ void oracle_step(oracle_t *o, const float *g)
             for (int64_t j = 0; j < d; ++j) e[j] = gi[j] + e[j];
         else
             memcpy(e, gi, (size_t)d * sizeof(float));
-        if (o->compressor == ORACLE_TOPK) {
-            oracle_topk(e, d, o->k, c, o->sel + (size_t)i * (size_t)o->k);
+        if (o->compressor != ORACLE_BLOCKSIGN) {
+            if (o->compressor == ORACLE_TOPK)
+                oracle_topk(e, d, o->k, c, o->sel + (size_t)i * (size_t)o->k);
+            else
+                oracle_randk(e, d, o->k, o->seed, o->draw, (uint32_t)i, c, o->sel + (size_t)i * (size_t)o->k);
             /* delta_i = x_i - C(x_i): +0.0 where selected (x - x), x elsewhere (x - 0) */
             const uint32_t *sel = o->sel + (size_t)i * (size_t)o->k;
             for (int64_t r = 0; r < o->k; ++r) e[sel[r]] = 0.0f;
@@ -277,13 +335,16 @@ void oracle_step(oracle_t *o, const float *g)
         oracle_amsgrad(o->theta + lo, o->m + lo, o->v + lo, o->vhat + lo, o->gbar + lo, len, o->beta1,
                        o->beta2, o->eps, o->lr, o->eps_mode);
     }
+    o->draw += 1;
 }
 
-/* C on one vector with this optimiser's compressor. */
-static void oracle_compress(oracle_t *o, const float *x, float *c, uint32_t *sel, float *scales)
+/* C on one vector with this optimiser's compressor; who: the worker, n for the server. */
+static void oracle_compress(oracle_t *o, uint32_t who, const float *x, float *c, uint32_t *sel, float *scales)
 {
     if (o->compressor == ORACLE_TOPK)
         oracle_topk(x, o->d, o->k, c, sel);
+    else if (o->compressor == ORACLE_RANDK)
+        oracle_randk(x, o->d, o->k, o->seed, o->draw, who, c, sel);
     else
         oracle_blocksign(x, o->offsets, o->n_blocks, c, scales);
 }
@@ -303,7 +364,7 @@ static void oracle_step_cd(oracle_t *o, const float *g)
         float *u = o->e + (size_t)i * (size_t)d;          /* scratch: the vector that is compressed */
         const float *gi = g + (size_t)i * (size_t)d;
         for (int64_t j = 0; j < d; ++j) u[j] = gi[j] - gh[j];
-        oracle_compress(o, u, c, o->sel ? o->sel + (size_t)i * (size_t)o->k : NULL,
+        oracle_compress(o, (uint32_t)i, u, c, o->sel ? o->sel + (size_t)i * (size_t)o->k : NULL,
                         o->scales ? o->scales + (size_t)i * (size_t)o->n_blocks : NULL);
         for (int64_t j = 0; j < d; ++j) gh[j] = gh[j] + c[j];
     }
@@ -320,7 +381,7 @@ static void oracle_step_cd(oracle_t *o, const float *g)
     {
         float *w = (float *)malloc((size_t)d * sizeof(float));
         for (int64_t j = 0; j < d; ++j) w[j] = o->ghat_s[j] - o->gtil[j];
-        oracle_compress(o, w, o->c_s, o->sel_s, o->scales_s);
+        oracle_compress(o, (uint32_t)n, w, o->c_s, o->sel_s, o->scales_s);
         for (int64_t j = 0; j < d; ++j) o->gtil[j] = o->gtil[j] + o->c_s[j];
         free(w);
     }
@@ -334,6 +395,7 @@ static void oracle_step_cd(oracle_t *o, const float *g)
         oracle_amsgrad(o->theta + lo, o->m + lo, o->v + lo, o->vhat + lo, o->gtil + lo, len, o->beta1,
                        o->beta2, o->eps, o->lr, o->eps_mode);
     }
+    o->draw += 1;
 }
 
 float *oracle_theta(oracle_t *o) { return o->theta; }

@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 TOPK = 0
 BLOCKSIGN = 1
+RANDK = 2   # Appendix A, "Rand-k"
 EF = 0      # error feedback (Section 4)
 CD = 1      # CD-Adam, Algorithm 1
 NAIVE = 2   # naive compression (Section 4), no memory
@@ -52,6 +53,12 @@ def lib():
         L.oracle_set_lr.argtypes = [C.c_void_p, C.c_float]
         L.oracle_set_eps_mode.argtypes = [C.c_void_p, C.c_int32]
         L.oracle_set_method.argtypes = [C.c_void_p, C.c_int32]
+        L.oracle_set_rand.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32]
+        L.oracle_mix32.restype = C.c_uint32
+        L.oracle_mix32.argtypes = [C.c_uint32]
+        L.oracle_randk_score.restype = C.c_uint32
+        L.oracle_randk_score.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.oracle_randk.argtypes = [fp, C.c_int64, C.c_int64, C.c_uint64, C.c_uint32, C.c_uint32, fp, u32p]
         L.oracle_step.argtypes = [C.c_void_p, fp]
         for name in ("theta", "m", "v", "vhat", "gbar", "error", "compressed", "scales", "ghat_workers",
                      "ghat_server", "gtilde", "server_compressed", "server_scales"):
@@ -91,6 +98,23 @@ def topk(x, k):
     return c, sel
 
 
+def randk(x, k, seed, draw, who):
+    """C_rand(x) for the draw (seed, draw, who): returns (c, selected indices ascending)."""
+    x = _f32(x)
+    c = np.empty_like(x)
+    sel = np.empty(k, dtype=np.uint32)
+    lib().oracle_randk(_fp(x), x.size, k, seed, draw, who, _fp(c), sel.ctypes.data_as(C.POINTER(C.c_uint32)))
+    return c, sel
+
+
+def randk_score(seed, draw, who, j):
+    return lib().oracle_randk_score(seed, draw, who, j)
+
+
+def mix32(h):
+    return lib().oracle_mix32(h)
+
+
 def blocksign(x, offsets):
     """Scaled sign per block: returns (c, scales)."""
     x = _f32(x)
@@ -115,7 +139,7 @@ class Oracle:
 
     def __init__(self, d, n, compressor, k_or_block, beta1, beta2, eps, lr, method=EF):
         self.d, self.n, self.compressor = int(d), int(n), int(compressor)
-        self.k = int(k_or_block) if compressor == TOPK else 0
+        self.k = int(k_or_block) if compressor != BLOCKSIGN else 0
         self.method = int(method)
         self._h = lib().oracle_create(d, n, compressor, k_or_block, beta1, beta2, eps, lr)
         if self.method != EF:
@@ -146,6 +170,10 @@ class Oracle:
 
     def set_eps_mode(self, mode):
         lib().oracle_set_eps_mode(self._h, mode)
+
+    def set_rand(self, seed, draw=0):
+        """Rand-k: the generator's seed and the number of the next draw (= steps taken so far)."""
+        lib().oracle_set_rand(self._h, seed, draw)
 
     def step(self, grads):
         g = _f32(grads)

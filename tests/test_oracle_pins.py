@@ -549,3 +549,188 @@ def test_case_study_ordering_of_the_four_strategies():
     assert norm["none"] < 1e-6
     assert norm["cd"] < 1e-2 * norm["ef"], norm
     assert norm["ef"] < 1e-1 * norm["naive"], norm
+
+
+# ---- Rand-k (Appendix A, "Rand-k") ------------------------------------------------------------
+# The paper fixes: S has exactly k elements, C(x) = x on S and 0 elsewhere, S is drawn at random
+# (so it cannot depend on x), and E||C(x) - x||^2 = (1 - k/d) ||x||^2 - which holds iff every
+# coordinate is in S with probability k/d.  How S is drawn is this build's reading; the generator
+# is pinned by an independent transcription of its published building block plus statistics.
+
+def py_mix32(h):
+    h &= 0xFFFFFFFF
+    h ^= h >> 16
+    h = (h * 0x85EBCA6B) & 0xFFFFFFFF
+    h ^= h >> 13
+    h = (h * 0xC2B2AE35) & 0xFFFFFFFF
+    h ^= h >> 16
+    return h
+
+
+def py_unmix32(h):
+    """Inverse of the finaliser: undo each xor-shift, multiply by the inverse constants mod 2^32."""
+    def unshift(v, s):
+        out = v
+        for _ in range(32 // s + 1):
+            out = v ^ (out >> s)
+        return out
+    h = unshift(h, 16)
+    h = (h * pow(0xC2B2AE35, -1, 1 << 32)) & 0xFFFFFFFF
+    h = unshift(h, 13)
+    h = (h * pow(0x85EBCA6B, -1, 1 << 32)) & 0xFFFFFFFF
+    return unshift(h, 16)
+
+
+def py_score(seed, draw, who, j):
+    M = 0xFFFFFFFF
+    per_step = py_mix32(((seed & M) + draw * 0x9E3779B9) & M)
+    a = py_mix32(per_step ^ (seed >> 32) ^ ((who * 0x85EBCA6B) & M))
+    b = py_mix32((a + 0xC2B2AE35) & M)
+    return py_mix32(py_mix32((j + a) & M) ^ b) >> 1
+
+
+def test_randk_generator_is_the_stated_one_and_a_bijection():
+    rng = np.random.default_rng(0)
+    words = [0, 1, 2, 0xFFFFFFFF, 0x80000000] + [int(w) for w in rng.integers(0, 1 << 32, 200)]
+    for w in words:
+        assert O.mix32(w) == py_mix32(w)
+        assert py_unmix32(O.mix32(w)) == w               # invertible: distinct words stay distinct
+    assert O.mix32(0) == 0 and O.mix32(1) == 0x514E28B7   # the finaliser's fixed point and a known value
+    for seed, draw, who, j in [(0, 0, 0, 0), (1, 2, 3, 4), (0xDEADBEEF12345678, 1000, 16, 11_173_961),
+                               (2 ** 64 - 1, 2 ** 32 - 1, 2 ** 32 - 1, 2 ** 32 - 1)]:
+        assert O.randk_score(seed, draw, who, j) == py_score(seed, draw, who, j)
+    # for a fixed draw the scores of all coordinates are distinct before the final shift: at most
+    # two coordinates share a 31-bit score
+    s = np.array([O.randk_score(5, 9, 2, j) for j in range(20_000)])
+    _, counts = np.unique(s, return_counts=True)
+    assert counts.max() <= 2
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (10, 1), (10, 10), (257, 31), (5000, 50)])
+def test_randk_keeps_exactly_k_values_unchanged_and_ignores_the_vector(d, k):
+    rng = np.random.default_rng(d + k)
+    x = rng.standard_normal(d).astype(f32)
+    x[x == 0] = 1.0
+    c, sel = O.randk(x, k, 42, 3, 1)
+    assert sel.size == k and np.all(np.diff(sel.astype(np.int64)) > 0) and sel.max() < d
+    mask = np.zeros(d, bool)
+    mask[sel] = True
+    assert np.array_equal(bits(c[mask]), bits(x[mask]))
+    assert np.array_equal(bits(c[~mask]), np.zeros(d - k, np.uint32))        # +0.0
+    # S is the k coordinates of largest score, lower index first among equals (brute force)
+    score = [py_score(42, 3, 1, j) for j in range(d)]
+    want = sorted(sorted(range(d), key=lambda j: (-score[j], j))[:k])
+    assert sel.tolist() == want
+    # S does not depend on x: another vector, the same draw
+    y = rng.standard_normal(d).astype(f32) * 1e3
+    assert np.array_equal(O.randk(y, k, 42, 3, 1)[1], sel)
+    # ... and depends on each of seed, draw, who (with d choose k > 1)
+    if 1 < k < d and d > 100:
+        for other in ((43, 3, 1), (42, 4, 1), (42, 3, 2), (42 + (1 << 32), 3, 1)):
+            assert not np.array_equal(O.randk(x, k, *other)[1], sel)
+
+
+def test_randk_inclusion_is_uniform_and_the_expected_error_is_the_papers():
+    """Appendix A, "Rand-k": E||C(x) - x||^2 = (1 - k/d) ||x||^2; every coordinate is kept with
+    probability k/d and pairs as in sampling without replacement."""
+    d, k, T = 120, 30, 6000
+    rng = np.random.default_rng(1)
+    x = (rng.standard_normal(d) * np.exp(rng.uniform(-3, 0, d))).astype(f32)
+    hits = np.zeros(d)
+    pair = 0
+    err = 0.0
+    for t in range(T):
+        c, sel = O.randk(x, k, 2024, t, t % 7)
+        hits[sel] += 1
+        pair += int(0 in sel and 1 in sel)
+        err += float(((c.astype(np.float64) - x) ** 2).sum())
+    p = k / d
+    # each count is Binomial(T, p): six standard deviations
+    assert np.all(np.abs(hits - T * p) <= 6 * math.sqrt(T * p * (1 - p)))
+    # chi-square over coordinates: mean d, standard deviation about sqrt(2 d) (slightly less: the counts sum to T k)
+    chi = ((hits - T * p) ** 2 / (T * p * (1 - p))).sum()
+    assert chi < d + 6 * math.sqrt(2 * d)
+    pp = k * (k - 1) / (d * (d - 1))
+    assert abs(pair - T * pp) <= 6 * math.sqrt(T * pp * (1 - pp))
+    want = (1 - p) * float((x.astype(np.float64) ** 2).sum())
+    assert abs(err / T - want) <= 0.02 * want
+
+
+def test_topk_error_never_exceeds_randk_error():
+    """Appendix A: ||C_top(x) - x|| <= ||C_rand(x) - x|| for every draw of S."""
+    rng = np.random.default_rng(2)
+    for t in range(50):
+        d = int(rng.integers(2, 400))
+        k = int(rng.integers(1, d + 1))
+        x = rng.standard_normal(d).astype(f32)
+        ct, _ = O.topk(x, k)
+        cr, _ = O.randk(x, k, 9, t, 0)
+        assert np.linalg.norm(ct.astype(np.float64) - x) <= np.linalg.norm(cr.astype(np.float64) - x)
+
+
+@pytest.mark.parametrize("method", [O.EF, O.NAIVE, O.CD])
+def test_randk_inside_the_methods_draws_per_step_and_worker(method):
+    """The optimiser uses draw = number of steps taken and who = worker index (n for the server of
+    Algorithm 1); the bookkeeping identities of each method hold with the random selection."""
+    rng = np.random.default_rng(5 + method)
+    n, d, k, T = 3, 400, 40, 6
+    o = O.Oracle(d, n, O.RANDK, k, 0.9, 0.999, 1e-8, 1e-3, method=method)
+    o.set_rand(77, 0)
+    e_prev = np.zeros((n, d), f32)
+    gh_prev = np.zeros((n, d), f32)
+    ghs_prev = np.zeros(d, f32)
+    gt_prev = np.zeros(d, f32)
+    for t in range(T):
+        g = rng.standard_normal((n, d)).astype(f32)
+        o.step(g)
+        for i in range(n):
+            x = {O.EF: g[i] + e_prev[i], O.NAIVE: g[i], O.CD: g[i] - gh_prev[i]}[method]
+            c, sel = O.randk(x, k, 77, t, i)
+            assert np.array_equal(o.selected[i], sel), (t, i)
+            assert np.array_equal(bits(o.compressed[i]), bits(c))
+            if method == O.EF:
+                assert np.array_equal(o.error[i] + c, x)              # one of the two is always zero
+            elif method == O.NAIVE:
+                assert not o.error[i].any()
+            else:
+                assert np.array_equal(bits(o.ghat_workers[i]), bits(gh_prev[i] + c))
+        if method == O.CD:
+            w = o.ghat_server - gt_prev
+            acc = np.zeros(d, f32)
+            for i in range(n):
+                acc = acc + o.compressed[i]
+            assert np.array_equal(bits(o.ghat_server), bits(ghs_prev + acc / f32(n)))
+            cs, sels = O.randk(w, k, 77, t, n)
+            assert np.array_equal(o.server_selected, sels)
+            assert np.array_equal(bits(o.gtilde), bits(gt_prev + cs))
+            gh_prev = o.ghat_workers.copy()
+            ghs_prev = o.ghat_server.copy()
+            gt_prev = o.gtilde.copy()
+        e_prev = o.error.copy()
+    o.close()
+
+
+def test_randk_resumes_from_a_given_draw_and_k_equal_d_is_vanilla():
+    rng = np.random.default_rng(8)
+    n, d, k = 2, 300, 30
+    gs = [rng.standard_normal((n, d)).astype(f32) for _ in range(5)]
+    a = O.Oracle(d, n, O.RANDK, k, 0.9, 0.999, 1e-8, 1e-3)
+    a.set_rand(5, 0)
+    for g in gs:
+        a.step(g)
+    b = O.Oracle(d, n, O.RANDK, k, 0.9, 0.999, 1e-8, 1e-3)
+    b.set_rand(5, 4)                       # only the last step, with the draw it had in the full run
+    b.step(gs[4])
+    # same kept sets at that draw, whatever the vectors were
+    assert np.array_equal(a.selected, b.selected)
+    a.close(); b.close()
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    o = O.Oracle(d, n, O.RANDK, d, 0.9, 0.999, 1e-8, 1e-3)
+    o.set_rand(1, 0)
+    o.set_theta(theta0)
+    for g in gs:
+        o.step(g)
+        assert not o.error.any()
+    th, m, v, vh = vanilla_amsgrad_numpy(theta0, gs, 0.9, 0.999, 1e-8, 1e-3)
+    assert np.array_equal(bits(o.theta), bits(th)) and np.array_equal(bits(o.vhat), bits(vh))
+    o.close()
