@@ -86,6 +86,8 @@ def main() -> int:
     ap.add_argument("--grad-dtype", choices=("f32", "bf16", "f16"), default="f32",
                     help="f32: comp_ams_step (the headline metric); bf16 / f16: comp_ams_step_bf16 / _f16 on the "
                          "gradients rounded to that type (2 instead of 4 bytes read per gradient element)")
+    ap.add_argument("--randk", action="store_true",
+                    help="on a Top-k workload: Rand-k (Appendix A) with the same k instead of Top-k")
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
@@ -117,7 +119,11 @@ def main() -> int:
         dev_grads = [torch.from_numpy(g).cuda() for g in host_grads]
 
     kb = w.k if w.compressor == W.TOPK else (w.block if w.block else w.d)
-    h = P.CompAms(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
+    if args.randk and w.compressor != W.TOPK:
+        print("bench.py: --randk needs a Top-k workload (--config 0, 2 or 4)", file=sys.stderr)
+        return 2
+    compressor = P.RANDK if args.randk else w.compressor          # the oracle uses the same numbers
+    h = P.CompAms(w.d, w.n, compressor, kb, w.beta1, w.beta2, w.eps, w.lr)
     if w.compressor == W.BLOCKSIGN and w.layer_blocks:
         h.set_blocks(w.block_offsets())
     h.set_theta(w.theta0())
@@ -196,7 +202,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu:
         from oracle import oracle as O
-        ora = O.Oracle(w.d, w.n, w.compressor, kb, w.beta1, w.beta2, w.eps, w.lr,
+        ora = O.Oracle(w.d, w.n, compressor, kb, w.beta1, w.beta2, w.eps, w.lr,
                        method={"ef": O.EF, "cd": O.CD, "naive": O.NAIVE, "none": O.NONE}[args.method])
         if w.compressor == W.BLOCKSIGN and w.layer_blocks:
             ora.set_blocks(w.block_offsets())
@@ -233,7 +239,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "method": {"ef": "error_feedback", "cd": "cd_adam", "naive": "naive_compression",
                                                    "none": "no_compression"}[args.method], "gradients": args.grad_dtype, "n_workers": w.n, "d": w.d,
-                   "compressor": "topk" if w.compressor == W.TOPK else "blocksign",
+                   "compressor": "randk" if args.randk else "topk" if w.compressor == W.TOPK else "blocksign",
                    "k": w.k, "block": w.block, "layer_blocks": w.layer_blocks, "gradient_buffers": nbuf},
         "roofline": roofline,
         "step_algorithmic_gbs": round(step_gbs, 1),

@@ -41,7 +41,7 @@ extern "C" {
 
 typedef struct comp_ams comp_ams_t;
 
-enum { COMP_AMS_TOPK = 0, COMP_AMS_BLOCKSIGN = 1 };
+enum { COMP_AMS_TOPK = 0, COMP_AMS_BLOCKSIGN = 1, COMP_AMS_RANDK = 2 };
 
 /* How the compressor is used: classical error feedback (Section 4; the step described above);
  * CD-Adam (Section 5, Algorithm 1): Markov compression in both directions; naive compression
@@ -63,7 +63,12 @@ enum {
  *   compressor = COMP_AMS_TOPK:      k_or_block = k, 1 <= k <= d  (Appendix A, "Top-k").
  *   compressor = COMP_AMS_BLOCKSIGN: k_or_block = B >= 1, contiguous blocks of B coordinates,
  *                                    the last one partial; B >= d is the whole-vector scaled
- *                                    sign of Appendix A.  d < 2^31 and n*d < 2^40.
+ *                                    sign of Appendix A.
+ *   compressor = COMP_AMS_RANDK:     k_or_block = k, 1 <= k <= d  (Appendix A, "Rand-k"): a random
+ *                                    set of k coordinates, drawn anew for every step and worker
+ *                                    (see comp_ams_set_rand).  Every call that names a TOPK handle
+ *                                    below also serves a RANDK handle.
+ * d < 2^31 and n*d < 2^40.
  * theta starts at zero until comp_ams_set_theta; m, v, vhat and every e_i start at zero.
  * On success *out receives the handle.
  */
@@ -89,6 +94,20 @@ int comp_ams_set_lr(comp_ams_t *h, float lr);
 
 /* 0 (default): theta -= lr m/(sqrt(vhat)+eps).  1: theta -= lr m/sqrt(vhat+eps), Section 3. */
 int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
+
+/*
+ * Rand-k (Appendix A, "Rand-k") only, before the first step: the seed of the draws and the number of
+ * the next draw (default 0, 0; a resumed run passes the number of steps already taken).  The paper
+ * leaves the drawing of S open.  Here coordinate j of the vector `who` (worker i: who = i; the
+ * server's vector in Algorithm 1: who = n) gets, at draw t (t grows by one per step), the 31-bit score
+ *     mix(mix(j + a) ^ b) >> 1,   a = mix(mix(lo(seed) + t * 0x9e3779b9) ^ hi(seed) ^ who * 0x85ebca6b),
+ *                                 b = mix(a + 0xc2b2ae35),
+ * mix = the 32-bit finaliser of MurmurHash3 (h ^= h >> 16; h *= 0x85ebca6b; h ^= h >> 13;
+ * h *= 0xc2b2ae35; h ^= h >> 16), all in arithmetic mod 2^32, and S is the k coordinates of largest
+ * score, the lower index first among equal scores.  S depends on (seed, t, who) only, so a receiver
+ * that knows them needs no indices.  A step recorded into a HIP graph repeats its draw when replayed.
+ */
+int comp_ams_set_rand(comp_ams_t *h, uint64_t seed, uint32_t draw);
 
 /*
  * One optimisation step on grads_dev: n*d floats in device memory, row-major [n][d]

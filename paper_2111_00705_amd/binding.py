@@ -16,6 +16,7 @@ from . import build as _build
 
 TOPK = 0
 BLOCKSIGN = 1
+RANDK = 2
 METHOD_EF = 0     # error feedback (Section 4)
 METHOD_CD = 1     # CD-Adam (Section 5, Algorithm 1)
 METHOD_NAIVE = 2  # naive compression (Section 4), no memory
@@ -31,7 +32,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
-    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16",
+    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand",
 ]
 
 
@@ -63,6 +64,7 @@ def lib():
         L.comp_ams_set_theta.argtypes = [vp, fp, C.c_int]
         L.comp_ams_set_lr.argtypes = [vp, C.c_float]
         L.comp_ams_set_eps_mode.argtypes = [vp, C.c_int32]
+        L.comp_ams_set_rand.argtypes = [vp, C.c_uint64, C.c_uint32]
         L.comp_ams_step.argtypes = [vp, fp, vp]
         L.comp_ams_step_bf16.argtypes = [vp, fp, vp]
         L.comp_ams_step_f16.argtypes = [vp, vp, vp]
@@ -123,7 +125,7 @@ class CompAms:
     def __init__(self, d, n, compressor, k_or_block, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3):
         self._h = C.c_void_p()
         self.d, self.n, self.compressor = int(d), int(n), int(compressor)
-        self.k = int(k_or_block) if compressor == TOPK else 0
+        self.k = int(k_or_block) if compressor != BLOCKSIGN else 0
         rc = lib().comp_ams_create(C.byref(self._h), d, n, compressor, k_or_block, beta1, beta2, eps, lr)
         if rc != OK:
             self._h = C.c_void_p()
@@ -154,6 +156,10 @@ class CompAms:
 
     def set_lr(self, lr):
         self._check(lib().comp_ams_set_lr(self._h, lr))
+
+    def set_rand(self, seed, draw=0):
+        """Rand-k: seed of the draws and number of the next draw (before the first step)."""
+        self._check(lib().comp_ams_set_rand(self._h, seed, draw))
 
     def set_eps_mode(self, mode):
         self._check(lib().comp_ams_set_eps_mode(self._h, mode))

@@ -36,6 +36,8 @@ struct comp_ams {
     int device = 0;
     hipStream_t stream = nullptr;
     uint64_t steps = 0;
+    uint64_t rand_seed = 0;                    // Rand-k: the generator's seed and the number of the next draw
+    uint32_t draw = 0;
     std::string err;
     std::vector<void *> allocs;
 
@@ -84,6 +86,22 @@ struct comp_ams {
     bool prof_on = false;
     std::vector<std::vector<std::pair<hipEvent_t, hipEvent_t>>> prof;   // [slot] -> recorded pairs
 };
+
+// Top-k and Rand-k share every buffer and kernel (the key differs, see SelKey).
+inline bool is_sparse(const comp_ams *h) { return h->compressor != COMP_AMS_BLOCKSIGN; }
+
+// Rand-k: fixes the draws of the step about to run (workers: who = 0..n-1; server of Algorithm 1: who = n)
+// and keeps the previous step's, which the deferred error memory still needs.
+inline uint32_t host_mix32(uint32_t h)
+{
+    h ^= h >> 16;
+    h *= 0x85ebca6bu;
+    h ^= h >> 13;
+    h *= 0xc2b2ae35u;
+    h ^= h >> 16;
+    return h;
+}
+inline uint32_t per_step_word(const comp_ams *h, uint32_t draw) { return host_mix32((uint32_t)h->rand_seed + draw * 0x9e3779b9u); }
 
 namespace {
 
@@ -491,11 +509,11 @@ void launch_materialize(comp_ams *h, int worker, float *dst)
 {
     const float *xrow = h->e + (size_t)worker * (size_t)h->ld;
     const unsigned blocks = (unsigned)((h->d + kThreads - 1) / kThreads);
-    if (h->compressor == COMP_AMS_TOPK && h->method == COMP_AMS_METHOD_CD) {
+    if (is_sparse(h) && h->method == COMP_AMS_METHOD_CD) {
         // ghat_i is stored as it is (tk_merge has already added c_i)
         (void)hipMemcpyAsync(dst, xrow, (size_t)h->d * sizeof(float), hipMemcpyDeviceToDevice, h->stream);
-    } else if (h->compressor == COMP_AMS_TOPK) {
-        tk_materialize_error<<<blocks, kThreads, 0, h->stream>>>(xrow, h->ge, h->ws + worker, dst);
+    } else if (is_sparse(h)) {
+        tk_materialize_error<<<blocks, kThreads, 0, h->stream>>>(xrow, h->ge, worker, h->ws + worker, dst);
     } else if (h->method == COMP_AMS_METHOD_CD) {
         const uint16_t *srow = h->signs + (size_t)worker * (size_t)(h->ld / kTile) * kThreads;
         if (h->pending)
@@ -525,9 +543,19 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         h->stream = st;
     }
+    if (h->compressor == COMP_AMS_RANDK) {
+        for (TkGeom *ge : {&h->ge, &h->srv.ge}) {
+            ge->rand.on = 1u;
+            ge->rand.seed_hi = (uint32_t)(h->rand_seed >> 32);
+            ge->rand.step_prev = per_step_word(h, h->draw - 1u);
+            ge->rand.step_now = per_step_word(h, h->draw);
+        }
+        h->ge.rand.who0 = 0u;
+        h->srv.ge.rand.who0 = (uint32_t)h->n;
+    }
     if (h->method == COMP_AMS_METHOD_NONE)
         rc = step_plain(h, grads_dev, st);
-    else if (h->compressor == COMP_AMS_TOPK)
+    else if (is_sparse(h))
         rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
              : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
                                                     : step_topk(h, grads_dev, st);
@@ -536,6 +564,7 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
     if (rc) return rc;
     HIP_TRY(h, hipGetLastError());
     ++h->steps;
+    ++h->draw;
     return COMP_AMS_OK;
 }
 
@@ -550,10 +579,10 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
     if (d < 1 || d >= (int64_t)1 << 31) return fail(nullptr, COMP_AMS_EINVAL, "d=%lld must be in [1, 2^31)", (long long)d);
     if (n < 1 || n > 65535) return fail(nullptr, COMP_AMS_EINVAL, "n=%d must be in [1, 65535]", n);
     if ((int64_t)n * d >= (int64_t)1 << 40) return fail(nullptr, COMP_AMS_EINVAL, "n*d must be below 2^40");
-    if (compressor != COMP_AMS_TOPK && compressor != COMP_AMS_BLOCKSIGN)
+    if (compressor != COMP_AMS_TOPK && compressor != COMP_AMS_BLOCKSIGN && compressor != COMP_AMS_RANDK)
         return fail(nullptr, COMP_AMS_EINVAL, "unknown compressor %d", compressor);
-    if (compressor == COMP_AMS_TOPK && (k_or_block < 1 || k_or_block > d))
-        return fail(nullptr, COMP_AMS_EINVAL, "Top-k needs 1 <= k <= d, got k=%lld d=%lld", (long long)k_or_block, (long long)d);
+    if (compressor != COMP_AMS_BLOCKSIGN && (k_or_block < 1 || k_or_block > d))
+        return fail(nullptr, COMP_AMS_EINVAL, "Top-k / Rand-k need 1 <= k <= d, got k=%lld d=%lld", (long long)k_or_block, (long long)d);
     if (compressor == COMP_AMS_BLOCKSIGN && k_or_block < 1)
         return fail(nullptr, COMP_AMS_EINVAL, "block length %lld must be >= 1", (long long)k_or_block);
     if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
@@ -698,6 +727,16 @@ int comp_ams_set_lr(comp_ams_t *h, float lr)
     return COMP_AMS_OK;
 }
 
+int comp_ams_set_rand(comp_ams_t *h, uint64_t seed, uint32_t draw)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    if (h->compressor != COMP_AMS_RANDK) return fail(h, COMP_AMS_ESTATE, "set_rand needs a RANDK handle");
+    if (h->steps != 0) return fail(h, COMP_AMS_ESTATE, "the draws can only be set before the first step");
+    h->rand_seed = seed;
+    h->draw = draw;
+    return COMP_AMS_OK;
+}
+
 int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode)
 {
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
@@ -787,7 +826,7 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
+    if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
@@ -798,7 +837,7 @@ int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_h
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    if (h->compressor != COMP_AMS_TOPK || h->method != COMP_AMS_METHOD_CD)
+    if (!is_sparse(h) || h->method != COMP_AMS_METHOD_CD)
         return fail(h, COMP_AMS_ESTATE, "get_server_selected needs a TOPK handle set to CD-Adam");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     return gather_selected(h, h->srv.ge, 0, h->srv.ws, h->srv.cand, h->srv.tile_dir, idx_host, val_host);
@@ -863,7 +902,7 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         // the rows now hold e itself: nothing is pending on them
         h->pending = false;
-        if (h->compressor == COMP_AMS_TOPK && (rc = reset_topk_workers(h))) return rc;
+        if (is_sparse(h) && (rc = reset_topk_workers(h))) return rc;
     }
     return COMP_AMS_OK;
 }
@@ -909,7 +948,7 @@ int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_hos
 {
     int rc = check_handle(h);
     if (rc) return rc;
-    if (h->compressor != COMP_AMS_TOPK) return fail(h, COMP_AMS_ESTATE, "get_selection_info needs a TOPK handle");
+    if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selection_info needs a TOPK handle");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     if (!out_host) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
     TkWorker w;
@@ -962,7 +1001,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
                 return rc;
         }
     }
-    if (h->compressor == COMP_AMS_TOPK && (rc = reset_topk_workers(h))) return rc;
+    if (is_sparse(h) && (rc = reset_topk_workers(h))) return rc;
     // the stored rows change their meaning (error memory <-> Markov sequence): start both from zero
     HIP_TRY(h, hipMemsetAsync(h->e, 0, (size_t)h->ld * (size_t)h->n * sizeof(float), h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
@@ -1036,7 +1075,7 @@ int comp_ams_message_bits(comp_ams_t *h, uint64_t *uplink_per_worker, uint64_t *
 {
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
     const uint64_t dense = 32ull * (uint64_t)h->d;
-    const uint64_t packed = h->compressor == COMP_AMS_TOPK ? 64ull * (uint64_t)h->k
+    const uint64_t packed = is_sparse(h) ? 64ull * (uint64_t)h->k
                                                            : (uint64_t)h->d + 32ull * (uint64_t)h->tb.n_blocks;
     if (uplink_per_worker) *uplink_per_worker = h->method == COMP_AMS_METHOD_NONE ? dense : packed;
     if (downlink) *downlink = h->method == COMP_AMS_METHOD_CD ? packed : dense;

@@ -37,6 +37,10 @@
 //
 // Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
 // (about 1.2 k per worker, 8 B each, written once, read three times).
+//
+// Rand-k (Appendix A, "Rand-k") runs through the same kernels: the 31 magnitude bits are replaced by a
+// 31-bit pseudo-random score of (seed, step, worker, index), see SelKey; everything after the key -
+// bins, digits, thresholds, the deferred error - is unchanged.
 #pragma once
 #include "device_utils.h"
 
@@ -72,6 +76,15 @@ struct TkWorker {
     uint32_t last_fine;     // fine bin of the previous threshold (to see how far thresholds move)
 };
 
+// Rand-k: what the score of a coordinate depends on besides its index and the vector's number.
+struct TkRand {
+    uint32_t on;          // 0: Top-k (keys are magnitudes)
+    uint32_t seed_hi;     // upper half of the 64-bit seed
+    uint32_t step_now;    // mix32(lower half of the seed + draw * 0x9e3779b9) for the running step's draw ...
+    uint32_t step_prev;   // ... and for the draw of the step whose selection is still pending
+    uint32_t who0;        // number of vector 0 of this geometry: 0 for the workers, n for CD-Adam's server
+};
+
 struct TkGeom {
     int64_t d, ld;
     int32_t n, n_tiles;
@@ -81,15 +94,45 @@ struct TkGeom {
     int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / slices)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
+    TkRand rand;
 };
 
-__device__ __forceinline__ uint64_t composite(float x, uint32_t j, int idx_bits)
+// The 31-bit key that orders the coordinates of one vector: the magnitude bits (Top-k), or the score
+//     mix32(mix32(j + a) ^ b) >> 1,   a = mix32(step ^ seed_hi ^ who * 0x85ebca6b),  b = mix32(a + 0xc2b2ae35)
+// (Rand-k), mix32 being the 32-bit finaliser of MurmurHash3.  For a fixed vector and step the score is a
+// bijection of the index followed by a shift, so at most two coordinates share it.
+struct SelKey {
+    uint32_t on, a, b;
+};
+__device__ __forceinline__ uint32_t mix32(uint32_t h)
 {
-    const uint64_t inv = ((1ull << idx_bits) - 1ull) - (uint64_t)j;
-    return ((uint64_t)mag_key(x) << idx_bits) | inv;
+    h ^= h >> 16;
+    h *= 0x85ebca6bu;
+    h ^= h >> 13;
+    h *= 0xc2b2ae35u;
+    h ^= h >> 16;
+    return h;
+}
+__device__ __forceinline__ SelKey sel_key_of(const TkRand &r, uint32_t per_step, int vec)
+{
+    SelKey s;
+    s.on = r.on;
+    s.a = mix32(per_step ^ r.seed_hi ^ ((r.who0 + (uint32_t)vec) * 0x85ebca6bu));
+    s.b = mix32(s.a + 0xc2b2ae35u);
+    return s;
+}
+__device__ __forceinline__ uint32_t sel_key(const SelKey &s, float x, uint32_t j)
+{
+    return s.on ? mix32(mix32(j + s.a) ^ s.b) >> 1 : mag_key(x);
 }
 
-// Pending selection of the previous step in 32-bit form: the coordinate j with magnitude bits
+__device__ __forceinline__ uint64_t composite(uint32_t key, uint32_t j, int idx_bits)
+{
+    const uint64_t inv = ((1ull << idx_bits) - 1ull) - (uint64_t)j;
+    return ((uint64_t)key << idx_bits) | inv;
+}
+
+// Pending selection of the previous step in 32-bit form: the coordinate j with key
 // `key` was kept iff  key > tkey  or  (key == tkey and j <= tj).
 struct KeptTest {
     uint32_t tkey, tj;
@@ -235,9 +278,10 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
 }
 
 // Stages one element of the vector that is compressed as a candidate if its fine bin reaches the guess.
-__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, uint2 *stage, uint32_t &count)
+__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, const SelKey &sk,
+                                         uint2 *stage, uint32_t &count)
 {
-    const bool hit = valid && (mag_key(x) >> kFineShift) >= guess;
+    const bool hit = valid && (sel_key(sk, x, j) >> kFineShift) >= guess;
     const uint32_t slot = wave_append(hit, count);
     if (hit) stage[slot] = make_uint2(j, __float_as_uint(x));
 }
@@ -254,7 +298,7 @@ enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2, kPassNaive = 3 };
 template <bool kFull, int kMode, typename G>
 __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
-                                               uint2 *stage)
+                                               const SelKey &sk, const SelKey &sk_prev, uint2 *stage)
 {
     const int tid = threadIdx.x;
     float4 gv[4], xv[4];
@@ -282,13 +326,13 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
                 x[c] = (kFull || j + c < d) ? fsub(gg[c], xo[c]) : 0.f;
             } else {
                 // e = x_old - C(x_old): +0 where the previous step kept the coordinate
-                const float e = was_kept(kt, mag_key(xo[c]), j + c) ? 0.f : xo[c];
+                const float e = was_kept(kt, sel_key(sk_prev, xo[c], j + c), j + c) ? 0.f : xo[c];
                 x[c] = (kFull || j + c < d) ? fadd(gg[c], e) : 0.f;
             }
         }
         if (kMode == kPassEf) st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
-        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, stage, count);
+        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, sk, stage, count);
     }
     return count;
 }
@@ -345,6 +389,8 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const int wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
     const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
+    const SelKey sk_prev = sel_key_of(ge.rand, ge.rand.step_prev, i);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
     if (tid == 0) sh[4] = 0;
@@ -352,9 +398,11 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     uint32_t count;
     const G *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
-        count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
+        count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
+                                           stage[wave]);
     else
-        count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, stage[wave]);
+        count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
+                                            stage[wave]);
     finish_tile(stage, sh, count, ge, i, t, cand, cursor, tile_dir);
 }
 
@@ -391,22 +439,23 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
     const Piece pc = piece_of(ge, cursor, i);
     if (pc.q0 >= pc.q1) return;
     const uint32_t guess = ws[i].guess;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
     if (tid < kFineWindow) lf[tid] = 0;
     __syncthreads();
     const uint2 *src = cand + region_base(ge, i, pc.slice);
     for (uint32_t qb = pc.q0; qb < pc.q1; qb += 4 * kThreads) {
-        uint32_t y[4];
+        uint2 y[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t q = qb + u * kThreads + tid;
-            y[u] = q < pc.q1 ? src[q].y : 0u;
+            y[u] = q < pc.q1 ? src[q] : make_uint2(0u, 0u);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             if (qb + u * kThreads + tid < pc.q1) {
-                const uint32_t fine = (y[u] & 0x7fffffffu) >> kFineShift;
+                const uint32_t fine = sel_key(sk, __uint_as_float(y[u].y), y[u].x) >> kFineShift;
                 atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
                 if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
             }
@@ -546,6 +595,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
     for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
     __syncthreads();
     const uint32_t d = (uint32_t)ge.d;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
@@ -555,8 +605,9 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const uint32_t bin = mag_key(x[r][c]) >> kShift1;
-                if (bin != 0 && base + 4 * (tid + kThreads * r) + c < d) atomicAdd(&lh[bin], 1u);
+                const uint32_t j = base + 4 * (tid + kThreads * r) + c;
+                const uint32_t bin = sel_key(sk, x[r][c], j) >> kShift1;
+                if (bin != 0 && j < d) atomicAdd(&lh[bin], 1u);
             }
     }
     __syncthreads();
@@ -610,6 +661,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
         find_rank_bin(lh, part, res, kBins1, ge.k);        // the histogram holds all d >= k elements
     }
     const uint32_t prefix = res[0];
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     if (blockIdx.x == 0 && tid == 0) {
         ws[i].prefix = prefix;
         ws[i].pshift = kShift1;
@@ -627,7 +679,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint32_t j = base + 4 * (tid + kThreads * r) + c;
-                const bool hit = j < d && (mag_key(x[r][c]) >> kShift1) >= prefix;
+                const bool hit = j < d && (sel_key(sk, x[r][c], j) >> kShift1) >= prefix;
                 const uint32_t slot = wave_append(hit, count);
                 if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
             }
@@ -651,6 +703,7 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const Piece pc = piece_of(ge, cursor, i);
     const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
     const uint32_t w0 = min(pc.q0 + wave * quarter, pc.q1), w1 = min(w0 + quarter, pc.q1);
@@ -667,9 +720,10 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool hit = qb + u * kWave + lane < w1 && ((c[u].y & 0x7fffffffu) >> pshift) == prefix;
+            const uint32_t key = sel_key(sk, __uint_as_float(c[u].y), c[u].x);
+            const bool hit = qb + u * kWave + lane < w1 && (key >> pshift) == prefix;
             const uint32_t slot = wave_append(hit, count);
-            if (hit) out[slot] = composite(__uint_as_float(c[u].y), c[u].x, ge.idx_bits);
+            if (hit) out[slot] = composite(key, c[u].x, ge.idx_bits);
         }
     }
     if (lane == 0) {
@@ -866,6 +920,7 @@ __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, cons
         // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
         uint32_t my_start = 0, my_count = 0;
         uint64_t my_tc = kNoThreshold;
+        const SelKey my_sk = sel_key_of(ge.rand, ge.rand.step_now, w0 + lane);
         if (lane < nw) {
             const uint4 rec = tile_dir[(int64_t)(w0 + lane) * ge.n_tiles + t];
             const uint32_t c[4] = {rec.y & 0xffffu, rec.y >> 16, rec.z & 0xffffu, rec.z >> 16};
@@ -893,7 +948,10 @@ __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, cons
                 const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
                 const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
                 const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
-                keep[u] = (uint32_t)lane < cnt[u] && composite(__uint_as_float(e[u].y), e[u].x, ge.idx_bits) >= tc;
+                SelKey sk = {0u, 0u, 0u};
+                if (ge.rand.on) sk = {1u, (uint32_t)__shfl((int)my_sk.a, w, kWave), (uint32_t)__shfl((int)my_sk.b, w, kWave)};
+                keep[u] = (uint32_t)lane < cnt[u] &&
+                          composite(sel_key(sk, __uint_as_float(e[u].y), e[u].x), e[u].x, ge.idx_bits) >= tc;
                 old[u] = 0.f;
                 if (kScatter && keep[u]) old[u] = rows[(int64_t)(w0 + w) * ge.ld + e[u].x];
             }
@@ -912,11 +970,13 @@ __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, cons
                     const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
                     const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
                     const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
+                    const SelKey sk = {ge.rand.on, (uint32_t)__shfl((int)my_sk.a, w, kWave),
+                                       (uint32_t)__shfl((int)my_sk.b, w, kWave)};
                     const uint2 *src = cand + region_base(ge, w0 + w, slice) + start;
                     for (uint32_t q = kWave + lane; q < cnt[u]; q += kWave) {
                         const uint2 c = src[q];
                         const float x = __uint_as_float(c.y);
-                        if (composite(x, c.x, ge.idx_bits) >= tc) {
+                        if (composite(sel_key(sk, x, c.x), c.x, ge.idx_bits) >= tc) {
                             const uint32_t l = c.x - base;
                             acc[l] = fadd(acc[l], x);
                             if (kScatter) {
@@ -1030,11 +1090,12 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
         uint32_t start = rec.x;
         for (int q = 0; q < wave; ++q) start += c[q];
         const uint64_t tc = sv.ws[0].tc;
+        const SelKey sk = sel_key_of(sv.ge.rand, sv.ge.rand.step_now, 0);
         const uint2 *src = sv.cand + region_base(sv.ge, 0, t & (sv.ge.slices - 1)) + start;
         for (uint32_t q = lane; q < c[wave]; q += kWave) {
             const uint2 e = src[q];
             const float x = __uint_as_float(e.y);
-            if (composite(x, e.x, sv.ge.idx_bits) >= tc) acc[e.x - (uint32_t)base] = x;   // distinct coordinates
+            if (composite(sel_key(sk, x, e.x), e.x, sv.ge.idx_bits) >= tc) acc[e.x - (uint32_t)base] = x;   // distinct coordinates
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1067,15 +1128,17 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
 
 // Getter support -------------------------------------------------------------------------------
 
-// e_i of one worker in its defined form, from the stored x and the pending threshold.
-__global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__restrict__ xrow, TkGeom ge,
+// e_i of one worker in its defined form, from the stored x and the pending threshold (ge.rand.step_now
+// is the draw of the step that left that threshold).
+__global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__restrict__ xrow, TkGeom ge, int worker,
                                                                  const TkWorker *__restrict__ w,
                                                                  float *__restrict__ out)
 {
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (j >= ge.d) return;
     const float x = xrow[j];
-    out[j] = was_kept(kept_test(w->tc, ge.idx_bits), mag_key(x), (uint32_t)j) ? 0.f : x;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, worker);
+    out[j] = was_kept(kept_test(w->tc, ge.idx_bits), sel_key(sk, x, (uint32_t)j), (uint32_t)j) ? 0.f : x;
 }
 
 // The kept (index, value) pairs of one worker, in no particular order: candidates with
@@ -1092,6 +1155,7 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x;
     const uint64_t tc = ws[worker].tc;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, worker);
     const uint4 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
     const uint2 *src = cand + region_base(ge, worker, t & (ge.slices - 1)) + rec.x;
     for (uint32_t q0 = 0; q0 < rec.w; q0 += kThreads) {      // uniform over the workgroup
@@ -1100,7 +1164,7 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
         bool keep = false;
         if (q < rec.w) {
             c = src[q];
-            keep = composite(__uint_as_float(c.y), c.x, ge.idx_bits) >= tc;
+            keep = composite(sel_key(sk, __uint_as_float(c.y), c.x), c.x, ge.idx_bits) >= tc;
         }
         const uint64_t km = __ballot(keep);
         if (km) {
