@@ -63,7 +63,7 @@ def compare(gpu: P.CompAms, ora: O.Oracle, x_for_values=None, check_error=True, 
         assert ok.all(), f"{tag} {name}: {np.count_nonzero(~ok)} coordinates beyond {STATE_RTOL} relative, " \
                          f"first at {int(np.argmin(ok))}: gpu={got[np.argmin(ok)]!r} oracle={want[np.argmin(ok)]!r}"
         stats[name + "_bit_identical"] = bool(np.array_equal(bits(got), bits(want)))
-    if gpu.compressor == P.TOPK:
+    if gpu.compressor != P.BLOCKSIGN:
         for i in range(gpu.n):
             idx, val = gpu.get_selected(i)
             assert np.array_equal(idx, ora.selected[i]), f"{tag} worker {i}: kept index set differs"

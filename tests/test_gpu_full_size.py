@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from parity_util import pair_for, run_steps
+from parity_util import make_pair, pair_for, run_steps
 
 pytestmark = pytest.mark.gpu
 
@@ -26,5 +26,21 @@ def test_full_size_workload_matches_oracle(idx, steps):
 
     stats = run_steps(gpu, ora, grads, steps=steps, tag=w.name, check_every=1, offsets=w.block_offsets())
     print(f"[case] {w.name}: {stats[-1]}", flush=True)
+    gpu.destroy()
+    ora.close()
+
+
+def test_full_size_randk_matches_oracle():
+    """Rand-k (Appendix A) at the size and launch configuration of the 11 M-coordinate workload: the
+    score threshold, the carried guess and the deferred error memory at scale, three steps."""
+    import paper_2111_00705_amd as P
+    w = W.get(2)
+    print(f"[case] full size Rand-k on {w.name}", flush=True)
+    gpu, ora = make_pair(w.d, w.n, P.RANDK, w.k, w.beta1, w.beta2, w.eps, w.lr, theta0=w.theta0())
+    gpu.set_rand(0x1234567887654321, 0)
+    ora.set_rand(0x1234567887654321, 0)
+    s = w.scales()
+    stats = run_steps(gpu, ora, lambda t: w.grads(t, scales=s, threads=16), steps=3, tag="randk " + w.name)
+    print(f"[case] randk {w.name}: {stats[-1]}", flush=True)
     gpu.destroy()
     ora.close()
