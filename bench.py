@@ -156,7 +156,7 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     coords_per_s = w.n * w.d / (ms_per_step * 1e-3)
 
-    # per-kernel durations: the same K steps again with HIP events around every launch
+    # per-kernel durations: the same K steps again, every launch stamping a pair of HIP events with its begin and end
     h.profile(True)
     run(args.warmup + args.steps, args.steps)
     prof = h.profile_read()

@@ -232,8 +232,10 @@ int comp_ams_sync(comp_ams_t *h);
 
 /*
  * Per-kernel timing for measurement (Section-independent; a benchmark aid).  While enabled, every
- * kernel that comp_ams_step launches is bracketed by two HIP events recorded on the step's
- * stream; event creation makes such steps slower and allocate, so keep it off otherwise.
+ * kernel that comp_ams_step launches carries two HIP events on the step's stream that are stamped
+ * with the kernel's own begin and end (hipExtLaunchKernel), so a slot's time is kernel time
+ * without the gaps between launches; event creation makes such steps slower and allocate, so
+ * keep it off otherwise.
  * Enabling or disabling waits for pending work and discards earlier recordings.
  */
 int comp_ams_profile(comp_ams_t *h, int enable);

@@ -4,6 +4,7 @@
 #include "../../include/comp_ams.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -13,6 +14,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <tuple>
 #include <utility>
 #include <vector>
 
@@ -113,10 +115,37 @@ const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk
                                          "bs_scale_server", "bs_apply", "tk_merge", "tk_pass1_server", "tk_select_server",
                                          "tk_apply", "plain_update"};
 
-// Runs `launch` (one kernel launch on st); with profiling on, brackets it with two events.
+// Kernel launches of a step go through KLAUNCH.  With profiling on, launch_timed hands the launch a
+// pair of events through t_ev0 / t_ev1 and the kernel is started with hipExtLaunchKernel, which stamps
+// them with the begin and end of the kernel itself (two hipEventRecord calls around a launch also time
+// the gaps before and after it, about 3 us); otherwise the launch is the ordinary one.
+thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
+
+template <typename... P, typename... A, size_t... I>
+void launch_ext_impl(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, std::index_sequence<I...>, A &&...args)
+{
+    std::tuple<P...> params{static_cast<P>(std::forward<A>(args))...};   // the kernel's own parameter types
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(params))...};
+    (void)hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, st, t_ev0, t_ev1, 0);
+}
+template <typename... P, typename... A>
+void launch_ext(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, A &&...args)
+{
+    launch_ext_impl(kernel, grid, block, st, std::index_sequence_for<P...>{}, std::forward<A>(args)...);
+}
+#define KLAUNCH(kern, grid, block, st, ...)                           \
+    do {                                                              \
+        if (t_ev0)                                                    \
+            launch_ext(kern, grid, block, st, __VA_ARGS__);           \
+        else                                                          \
+            kern<<<grid, block, 0, st>>>(__VA_ARGS__);                \
+    } while (0)
+
+// Runs `launch` (exactly one KLAUNCH on st); with profiling on, the kernel's begin and end are recorded.
 template <typename F>
 void launch_timed(comp_ams *h, int slot, hipStream_t st, F &&launch)
 {
+    (void)st;
     if (!h->prof_on) {
         launch();
         return;
@@ -127,9 +156,10 @@ void launch_timed(comp_ams *h, int slot, hipStream_t st, F &&launch)
         launch();
         return;
     }
-    (void)hipEventRecord(a, st);
+    t_ev0 = a;
+    t_ev1 = b;
     launch();
-    (void)hipEventRecord(b, st);
+    t_ev0 = t_ev1 = nullptr;
     h->prof[slot].emplace_back(a, b);
 }
 
@@ -290,22 +320,22 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
-            bs_pass<false, kBsNaive, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsNaive, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else if (h->pending)
-            bs_pass<true, kBsEf, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<true, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, kBsEf, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     if (!h->fused_scale)
         launch_timed(h, P_BS_SCALE, st, [&] {
-            bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
+            KLAUNCH((bs_scale), dim3(tb.n_blocks, h->n), kWave, st, h->partial, tb, h->scales);
         });
     launch_timed(h, P_BS_UPDATE, st, [&] {
         // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
         // workgroups per compute unit
         const bool early = grid.x < 2048;
 #define CAMS_BS_UPDATE(F, E)                                                                                  \
-    bs_update<F, E, false><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
+    KLAUNCH((bs_update<F, E, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
                                                         h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{})
         if (h->fused_scale) {
             if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
@@ -326,34 +356,34 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            bs_pass<true, kBsCd, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<true, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
         else
-            bs_pass<false, kBsCd, G><<<grid, kThreads, 0, st>>>(g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
     });
     // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
     // scale are formed inside bs_update, which then also applies the server's message - two launches in all
     const bool whole = h->fused_scale && tb.n_pieces == tb.n_blocks;
     if (!whole)
         launch_timed(h, P_BS_SCALE, st, [&] {
-            bs_scale<<<dim3(tb.n_blocks, h->n), kWave, 0, st>>>(h->partial, tb, h->scales);
+            KLAUNCH((bs_scale), dim3(tb.n_blocks, h->n), kWave, st, h->partial, tb, h->scales);
         });
     launch_timed(h, P_BS_SERVER, st, [&] {
         const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
         if (whole)
-            bs_update<true, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
+            KLAUNCH((bs_update<true, false, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
                                                                       h->params, mk);
         else
-            bs_update<false, false, true><<<grid.x, kThreads, 0, st>>>(h->d, h->ld, h->n, tb, h->partial, h->scales,
+            KLAUNCH((bs_update<false, false, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
                                                                        h->signs, h->theta, h->m, h->v, h->vhat,
                                                                        h->params, mk);
     });
     if (!whole) {
         launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
-            bs_scale<<<dim3(tb.n_blocks, 1), kWave, 0, st>>>(h->partial_srv, tb, h->scales_srv);
+            KLAUNCH((bs_scale), dim3(tb.n_blocks, 1), kWave, st, h->partial_srv, tb, h->scales_srv);
         });
         launch_timed(h, P_BS_APPLY, st, [&] {
-            bs_apply<<<grid.x, kThreads, 0, st>>>(h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
+            KLAUNCH((bs_apply), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
                                                   h->v, h->vhat, h->params);
         });
     }
@@ -373,18 +403,18 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
     // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
     // the whole vector after a miss) are kept to about two per compute unit in total
     const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
-    launch_timed(h, slot[0], st, [&] { tk_hist<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, hist1, histf); });
+    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1, histf); });
     launch_timed(h, slot[1], st, [&] {
-        tk_pick<kSrc, G><<<pick, kThreads, 0, st>>>(ge, ws, hist1, histf, cursor, hist_full, a, b);
+        KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, hist_full, a, b);
     });
     launch_timed(h, slot[2], st, [&] {
-        tk_relist<kSrc, G><<<sweep, kThreads, 0, st>>>(a, b, ge, ws, hist_full, cand, cursor, tile_dir);
+        KLAUNCH((tk_relist<kSrc, G>), sweep, kThreads, st, a, b, ge, ws, hist_full, cand, cursor, tile_dir);
     });
     launch_timed(h, slot[3], st, [&] {
-        tk_compact<<<shared, kThreads, 0, st>>>(ge, ws, cand, cursor, dense, dense_dir);
+        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir);
     });
     launch_timed(h, slot[4], st, [&] {
-        tk_resolve<<<ge.n, kResolveThreads, 0, st>>>(ge, ws, dense, dense_dir, cursor, hist_full);
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full);
     });
 }
 
@@ -397,13 +427,13 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassEf, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                               h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+        KLAUNCH((tk_final), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
     });
     return COMP_AMS_OK;
@@ -415,13 +445,13 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassNaive, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                           h->tile_dir);
     });
     launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                                 h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        tk_final<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+        KLAUNCH((tk_final), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
     });
     return COMP_AMS_OK;
@@ -432,7 +462,7 @@ template <typename G>
 int step_plain(comp_ams *h, const G *g, hipStream_t st)
 {
     launch_timed(h, P_PLAIN_UPDATE, st, [&] {
-        plain_update<G><<<(unsigned)(h->ld / kTile), kThreads, 0, st>>>(g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
+        KLAUNCH((plain_update<G>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
                                                                      h->params);
     });
     return COMP_AMS_OK;
@@ -445,23 +475,23 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        tk_pass1<kPassCd, G><<<dim3(ge.n_tiles, h->n), kThreads, 0, st>>>(g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassCd, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                             h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
-        tk_merge<<<ge.n_tiles, kThreads, 0, st>>>(ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
+        KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
-        tk_pass1<kPassDiff, float><<<dim3(ge.n_tiles, 1), kThreads, 0, st>>>(h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
+        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(ge.n_tiles, 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
                                                                       sv.cursor, sv.tile_dir);
     });
     launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
                             h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
-        tk_apply<<<ge.n_tiles, kThreads, 0, st>>>(sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+        KLAUNCH((tk_apply), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
     });
     return COMP_AMS_OK;
 }
