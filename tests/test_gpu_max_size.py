@@ -1,0 +1,134 @@
+"""The largest model the library accepts: d = 2^31 - 1 (one worker).  The oracle cannot run on two
+billion coordinates in test time, so the gradients are zero except for a few thousand planted
+values - at the first and last coordinates, around tile boundaries and at random places - and the
+oracle runs on the compacted problem, which has the same answer:
+
+  * Top-k with k below the number of non-zeros keeps only planted coordinates, and among those the
+    order (magnitude, then lower index) is the order of the compacted vector;
+  * block sign works block by block, and a block of zeros has scale 0 and leaves the state unchanged,
+    so the blocks that hold planted values (with the short last block last) form the compacted problem.
+
+What is checked is what index arithmetic near 2^31 could break: kept index sets and values, the
+error memory and theta, m, v, vhat at every planted coordinate (bit-exact / 1e-6 relative), and that
+nothing else moved."""
+import numpy as np
+import pytest
+
+import paper_2111_00705_amd as P
+import workloads as W
+from oracle import oracle as O
+from parity_util import STATE_RTOL, bits, rel_close
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+D_MAX = 2 ** 31 - 1
+TILE = 4096
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def planted_positions(rng, count):
+    fixed = [0, 1, 4095, 4096, 4097, D_MAX - 1, D_MAX - 2, D_MAX - 4095, D_MAX - 4096, D_MAX - 4097,
+             2 ** 30, 2 ** 30 - 1, 2 ** 30 + 1]
+    rnd = rng.integers(0, D_MAX, count - len(fixed))
+    return np.unique(np.concatenate([np.array(fixed, np.int64), rnd.astype(np.int64)]))
+
+
+def device_vector(torch, pos, vals):
+    g = torch.zeros(D_MAX, dtype=torch.float32, device="cuda")
+    g[torch.from_numpy(pos).cuda()] = torch.from_numpy(vals).cuda()
+    return g
+
+
+def read_at(torch, getter, pos_dev, buf, *args):
+    getter(*args, out=buf)
+    return buf[pos_dev].cpu().numpy()
+
+
+def test_topk_at_the_largest_dimension():
+    import torch
+    announce("Top-k at d = 2^31 - 1")
+    rng = np.random.default_rng(31)
+    k = 1000
+    gpu = P.CompAms(D_MAX, 1, P.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR)
+    buf = torch.empty(D_MAX, dtype=torch.float32, device="cuda")
+    steps = []
+    for t in range(3):
+        pos = planted_positions(rng, 1500)
+        vals = (rng.standard_normal(pos.size) * np.exp(rng.uniform(-3, 0, pos.size))).astype(f32)
+        vals[vals == 0] = 1.0
+        if t == 1:
+            vals[:40] = np.float32(0.5) * np.sign(vals[:40])          # ties, lower index wins
+        steps.append((pos, vals))
+    union = np.unique(np.concatenate([p for p, _ in steps]))
+    ora = O.Oracle(union.size, 1, O.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR)
+    union_dev = torch.from_numpy(union).cuda()
+    for t, (pos, vals) in enumerate(steps):
+        print(f"[case] step {t}", flush=True)
+        g = device_vector(torch, pos, vals)
+        gpu.step(g)
+        gpu.sync()
+        del g
+        gc = np.zeros((1, union.size), f32)
+        gc[0, np.searchsorted(union, pos)] = vals
+        ora.step(gc)
+        idx, val = gpu.get_selected(0)
+        assert np.array_equal(idx.astype(np.int64), union[ora.selected[0]]), f"step {t}: kept index set"
+        assert np.array_equal(bits(val), bits(ora.compressed[0][ora.selected[0]])), f"step {t}: kept values"
+        e = read_at(torch, gpu.get_error, union_dev, buf, 0)
+        assert np.array_equal(bits(e), bits(ora.error[0])), f"step {t}: error memory at the planted coordinates"
+        assert int(torch.count_nonzero(buf)) == int(np.count_nonzero(ora.error[0])), f"step {t}: error elsewhere"
+        for name in ("theta", "m", "v", "vhat"):
+            got = read_at(torch, getattr(gpu, "get_" + name), union_dev, buf)
+            assert rel_close(got, getattr(ora, name), STATE_RTOL).all(), f"step {t}: {name}"
+            assert int(torch.count_nonzero(buf)) == int(np.count_nonzero(getattr(ora, name))), \
+                f"step {t}: {name} moved away from the planted coordinates"
+    gpu.destroy()
+    ora.close()
+
+
+def test_block_sign_at_the_largest_dimension():
+    import torch
+    announce("block sign at d = 2^31 - 1")
+    rng = np.random.default_rng(32)
+    gpu = P.CompAms(D_MAX, 1, P.BLOCKSIGN, TILE, W.BETA1, W.BETA2, W.EPS, W.LR)
+    buf = torch.empty(D_MAX, dtype=torch.float32, device="cuda")
+    n_blocks = (D_MAX + TILE - 1) // TILE
+    assert gpu.n_blocks() == n_blocks
+    steps = []
+    for t in range(2):
+        pos = planted_positions(rng, 300)
+        vals = (rng.standard_normal(pos.size) * np.exp(rng.uniform(-3, 0, pos.size))).astype(f32)
+        steps.append((pos, vals))
+    blocks = np.unique(np.concatenate([p // TILE for p, _ in steps] + [np.array([n_blocks - 1])]))
+    # compacted problem: the planted blocks in order; the last block of the model (4095 long) comes last
+    starts = np.concatenate([[0], np.cumsum(np.minimum((blocks + 1) * TILE, D_MAX) - blocks * TILE)])
+    dc = int(starts[-1])
+    coords = np.concatenate([np.arange(b * TILE, min((b + 1) * TILE, D_MAX), dtype=np.int64) for b in blocks])
+    assert coords.size == dc and dc % TILE == TILE - 1
+    ora = O.Oracle(dc, 1, O.BLOCKSIGN, TILE, W.BETA1, W.BETA2, W.EPS, W.LR)
+    coords_dev = torch.from_numpy(coords).cuda()
+    for t, (pos, vals) in enumerate(steps):
+        print(f"[case] step {t}", flush=True)
+        g = device_vector(torch, pos, vals)
+        gpu.step(g)
+        gpu.sync()
+        del g
+        gc = np.zeros((1, dc), f32)
+        gc[0, np.searchsorted(coords, pos)] = vals
+        ora.step(gc)
+        s = gpu.get_scales()[0]
+        assert np.array_equal(bits(s[blocks]), bits(ora.scales[0])), f"step {t}: scales of the planted blocks"
+        assert np.count_nonzero(s) == np.count_nonzero(ora.scales[0]), f"step {t}: a block of zeros has scale 0"
+        e = read_at(torch, gpu.get_error, coords_dev, buf, 0)
+        assert np.array_equal(bits(e), bits(ora.error[0])), f"step {t}: error memory in the planted blocks"
+        assert int(torch.count_nonzero(buf)) == int(np.count_nonzero(ora.error[0])), f"step {t}: error elsewhere"
+        for name in ("theta", "m", "v", "vhat"):
+            got = read_at(torch, getattr(gpu, "get_" + name), coords_dev, buf)
+            assert rel_close(got, getattr(ora, name), STATE_RTOL).all(), f"step {t}: {name}"
+            assert int(torch.count_nonzero(buf)) == int(np.count_nonzero(getattr(ora, name))), \
+                f"step {t}: {name} moved outside the planted blocks"
+    gpu.destroy()
+    ora.close()
