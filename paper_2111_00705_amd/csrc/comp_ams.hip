@@ -677,7 +677,11 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int ib = 1;
         while (((int64_t)1 << ib) < d) ++ib;
         ge.idx_bits = ib;
-        set_slices(ge, kMinSlices);   // more regions per worker measured no faster (n workers already spread the cursors)
+        // more regions per worker measured no faster (n workers already spread the cursors); fewer when the
+        // vector has fewer tiles than that, so that many workers with a small model do not reserve 64 empty regions each
+        int slices = kMinSlices;
+        while (slices > 1 && slices / 2 >= ge.n_tiles) slices /= 2;
+        set_slices(ge, slices);
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
         const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.slice_tiles * kTile;

@@ -55,6 +55,7 @@ constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
 constexpr int kMinSlices = 64;    // candidate regions per vector: a power of two in [kMinSlices, kMaxSlices]
+                                  // (fewer for a vector of fewer tiles than that)
 constexpr int kMaxSlices = 512;
 constexpr int kMaxParts = 8;      // pieces a region is cut into for tk_hist / tk_compact, at most
 constexpr int kResolveThreads = 1024;

@@ -1,5 +1,6 @@
-"""The largest model the library accepts: d = 2^31 - 1 (one worker).  The oracle cannot run on two
-billion coordinates in test time, so the gradients are zero except for a few thousand planted
+"""The largest worker count (n = 65535) on tiny models, against the oracle in full, and the largest
+model the library accepts: d = 2^31 - 1 (one worker).  The oracle cannot run on two billion
+coordinates in test time, so the gradients are zero except for a few thousand planted
 values - at the first and last coordinates, around tile boundaries and at random places - and the
 oracle runs on the compacted problem, which has the same answer:
 
@@ -130,5 +131,28 @@ def test_block_sign_at_the_largest_dimension():
             assert rel_close(got, getattr(ora, name), STATE_RTOL).all(), f"step {t}: {name}"
             assert int(torch.count_nonzero(buf)) == int(np.count_nonzero(getattr(ora, name))), \
                 f"step {t}: {name} moved outside the planted blocks"
+    gpu.destroy()
+    ora.close()
+
+
+@pytest.mark.parametrize("comp,d,kb", [(P.TOPK, 5, 2), (P.TOPK, 4100, 7), (P.BLOCKSIGN, 5, 3), (P.RANDK, 9, 4)])
+def test_the_largest_worker_count(comp, d, kb):
+    import torch
+    n = 65535
+    announce(f"n = {n}, compressor {comp}, d = {d}")
+    gpu = P.CompAms(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR)
+    ora = O.Oracle(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR)
+    for t in range(3):
+        g = np.random.default_rng([65535, d, t]).standard_normal((n, d)).astype(f32)
+        gpu.step(torch.from_numpy(g).cuda())
+        ora.step(g)
+    for name in ("theta", "m", "v", "vhat"):
+        assert rel_close(getattr(gpu, "get_" + name)(), getattr(ora, name), STATE_RTOL).all(), name
+    for i in (0, 1, 63, 64, 4095, 4096, 32768, n - 2, n - 1):
+        assert np.array_equal(bits(gpu.get_error(i)), bits(ora.error[i])), i
+        if comp != P.BLOCKSIGN:
+            assert np.array_equal(gpu.get_selected(i)[0], ora.selected[i]), i
+    with pytest.raises(P.CompAmsError):
+        P.CompAms(d, n + 1, comp, kb)
     gpu.destroy()
     ora.close()
