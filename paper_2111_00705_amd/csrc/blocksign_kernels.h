@@ -51,6 +51,7 @@ struct BsTable {
     int32_t n_pieces;
     int32_t uniform_tiles;       // >0: every block spans this many whole tiles (the last block may be shorter),
                                  // so tile t is piece t of block t / uniform_tiles: no table look-ups needed
+    int32_t stream_rows;         // the stored rows are too large to stay cached between steps: bs_pass loads them as a stream
 };
 
 // Sign bits: per worker, per tile, one 16-bit word per thread of the workgroup.  Bit r*4 + c of
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gv[r] = load_grad4(grow, j, d);
-        xv[r] = kMode == kBsNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4(xrow + j);
+        xv[r] = kMode == kBsNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4_row(xrow + j, tb.stream_rows);
     }
     uint16_t *word = signs + ((int64_t)i * (ld / kTile) + t) * kThreads + tid;
     const uint32_t old_bits = (kMode == kBsCd && kPending) ? (uint32_t)*word : 0u;   // sign bits of the pending c_i
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
                 keep[c] = x[r][c];
             }
         }
-        if (kMode != kBsNaive) st4(xrow + j, make_float4(keep[0], keep[1], keep[2], keep[3]));
+        if (kMode != kBsNaive) st4_stream(xrow + j, make_float4(keep[0], keep[1], keep[2], keep[3]));
 #pragma unroll
         for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
     }
@@ -235,10 +236,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t j = base + 4 * (tid + kThreads * r);
-            th[r] = ld4(theta + j);
-            mm[r] = ld4(m + j);
-            vv[r] = ld4(v + j);
-            vh[r] = ld4(vhat + j);
+            th[r] = stream_load4(theta + j);
+            mm[r] = stream_load4(m + j);
+            vv[r] = stream_load4(v + j);
+            vh[r] = stream_load4(vhat + j);
         }
     }
     float acc[16];
@@ -379,13 +380,13 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             for (int c = 0; c < 4; ++c)
                 nt[c] = (j + c < d) ? fadd(gt[c], signed_scale(s, sign_bits, r * 4 + c)) : gt[c];   // padding stays 0
             const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
-            float4 th4 = ld4(theta + j), m4 = ld4(m + j), v4 = ld4(v + j), vh4 = ld4(vhat + j);
+            float4 th4 = stream_load4(theta + j), m4 = stream_load4(m + j), v4 = stream_load4(v + j), vh4 = stream_load4(vhat + j);
             amsgrad_update4(th4, m4, v4, vh4, g4, p);
             st4(mk.gtil + j, g4);
-            st4(theta + j, th4);
-            st4(m + j, m4);
-            st4(v + j, v4);
-            st4(vhat + j, vh4);
+            st4_stream(theta + j, th4);
+            st4_stream(m + j, m4);
+            st4_stream(v + j, v4);
+            st4_stream(vhat + j, vh4);
         }
         return;
     }
@@ -393,10 +394,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t j = base + 4 * (tid + kThreads * r);
-            th[r] = ld4(theta + j);
-            mm[r] = ld4(m + j);
-            vv[r] = ld4(v + j);
-            vh[r] = ld4(vhat + j);
+            th[r] = stream_load4(theta + j);
+            mm[r] = stream_load4(m + j);
+            vv[r] = stream_load4(v + j);
+            vh[r] = stream_load4(vhat + j);
         }
     }
 #pragma unroll
@@ -408,10 +409,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
                                         j + 2 < d ? fdiv(acc[r * 4 + 2], p.n_workers) : 0.f,
                                         j + 3 < d ? fdiv(acc[r * 4 + 3], p.n_workers) : 0.f);
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4(theta + j, th[r]);
-        st4(m + j, mm[r]);
-        st4(v + j, vv[r]);
-        st4(vhat + j, vh[r]);
+        st4_stream(theta + j, th[r]);
+        st4_stream(m + j, mm[r]);
+        st4_stream(v + j, vv[r]);
+        st4_stream(vhat + j, vh[r]);
     }
 }
 
@@ -450,10 +451,10 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gt[r] = ld4(gtil + j);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
+        th[r] = stream_load4(theta + j);
+        mm[r] = stream_load4(m + j);
+        vv[r] = stream_load4(v + j);
+        vh[r] = stream_load4(vhat + j);
     }
     int p0, p1;
     if (tb.uniform_tiles > 0) {
@@ -483,10 +484,10 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
         const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
         st4(gtil + j, g4);
-        st4(theta + j, th[r]);
-        st4(m + j, mm[r]);
-        st4(v + j, vv[r]);
-        st4(vhat + j, vh[r]);
+        st4_stream(theta + j, th[r]);
+        st4_stream(m + j, mm[r]);
+        st4_stream(v + j, vv[r]);
+        st4_stream(vhat + j, vh[r]);
     }
 }
 

@@ -89,6 +89,10 @@ struct comp_ams {
     std::vector<std::vector<std::pair<hipEvent_t, hipEvent_t>>> prof;   // [slot] -> recorded pairs
 };
 
+// Whether the n stored rows are read as a stream (see ld4_row): beyond 128 MB they cannot stay in the
+// 256 MB memory-side cache from one step to the next, next to the gradients and what else a step moves.
+inline bool rows_exceed_caches(const comp_ams *h) { return (size_t)h->n * (size_t)h->ld * sizeof(float) > ((size_t)128 << 20); }
+
 // Top-k and Rand-k share every buffer and kernel (the key differs, see SelKey).
 inline bool is_sparse(const comp_ams *h) { return h->compressor != COMP_AMS_BLOCKSIGN; }
 
@@ -275,6 +279,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
     h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
+    h->tb.stream_rows = rows_exceed_caches(h) ? 1 : 0;
     {
         bool ok = true;
         for (int64_t t = 0; t < n_tiles && ok; ++t) ok = (tile_piece0[t + 1] - tile_piece0[t] == 1);
@@ -682,6 +687,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int slices = kMinSlices;
         while (slices > 1 && slices / 2 >= ge.n_tiles) slices /= 2;
         set_slices(ge, slices);
+        ge.stream_rows = rows_exceed_caches(h) ? 1 : 0;
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
         const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.slice_tiles * kTile;
@@ -1016,6 +1022,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
             TkSide &sv = h->srv;
             sv.ge = h->ge;
             sv.ge.n = 1;
+            sv.ge.stream_rows = 0;       // ghat and gtilde are reused within the step
             sv.ge.relist_wgs = (int32_t)std::min<int64_t>(sv.ge.n_tiles, 2048);
             // one vector, all tiles: enough regions that a cursor sees few tens of atomic adds
             int slices = kMinSlices;

@@ -43,15 +43,15 @@ __global__ __launch_bounds__(kThreads) void plain_update(const G *__restrict__ g
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
-        float4 th = ld4(theta + j), mm = ld4(m + j), vv = ld4(v + j), vh = ld4(vhat + j);
+        float4 th = stream_load4(theta + j), mm = stream_load4(m + j), vv = stream_load4(v + j), vh = stream_load4(vhat + j);
         // padding coordinates take no gradient (load_grad4 gives 0 past d)
         const float4 gbar = make_float4(fdiv(acc[r][0], p.n_workers), fdiv(acc[r][1], p.n_workers),
                                         fdiv(acc[r][2], p.n_workers), fdiv(acc[r][3], p.n_workers));
         amsgrad_update4(th, mm, vv, vh, gbar, p);
-        st4(theta + j, th);
-        st4(m + j, mm);
-        st4(v + j, vv);
-        st4(vhat + j, vh);
+        st4_stream(theta + j, th);
+        st4_stream(m + j, mm);
+        st4_stream(v + j, vv);
+        st4_stream(vhat + j, vh);
     }
 }
 

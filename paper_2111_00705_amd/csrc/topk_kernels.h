@@ -95,6 +95,7 @@ struct TkGeom {
     int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / slices)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
+    int32_t stream_rows;    // the stored rows are too large to stay cached between steps: tk_pass1 loads them as a stream
     TkRand rand;
 };
 
@@ -299,7 +300,8 @@ enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2, kPassNaive = 3 };
 template <bool kFull, int kMode, typename G>
 __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
-                                               const SelKey &sk, const SelKey &sk_prev, uint2 *stage)
+                                               const SelKey &sk, const SelKey &sk_prev, uint2 *stage,
+                                               int stream_rows)
 {
     const int tid = threadIdx.x;
     float4 gv[4], xv[4];
@@ -310,7 +312,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
             gv[r] = ld4(grow + j);
         else
             gv[r] = load_grad4(grow, j, d);
-        xv[r] = kMode == kPassNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4(xrow + j);
+        xv[r] = kMode == kPassNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4_row(xrow + j, stream_rows);
     }
     uint32_t count = 0;
 #pragma unroll
@@ -331,7 +333,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
                 x[c] = (kFull || j + c < d) ? fadd(gg[c], e) : 0.f;
             }
         }
-        if (kMode == kPassEf) st4(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
+        if (kMode == kPassEf) st4_stream(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
         for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, sk, stage, count);
     }
@@ -400,10 +402,10 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const G *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
         count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                           stage[wave]);
+                                           stage[wave], ge.stream_rows);
     else
         count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                            stage[wave]);
+                                            stage[wave], ge.stream_rows);
     finish_tile(stage, sh, count, ge, i, t, cand, cursor, tile_dir);
 }
 
@@ -1015,10 +1017,10 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
+        th[r] = stream_load4(theta + j);
+        mm[r] = stream_load4(m + j);
+        vv[r] = stream_load4(v + j);
+        vh[r] = stream_load4(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1028,10 +1030,10 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
         const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
                                         fdiv(a.w, p.n_workers));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4(theta + j, th[r]);
-        st4(m + j, mm[r]);
-        st4(v + j, vv[r]);
-        st4(vhat + j, vh[r]);
+        st4_stream(theta + j, th[r]);
+        st4_stream(m + j, mm[r]);
+        st4_stream(v + j, vv[r]);
+        st4_stream(vhat + j, vh[r]);
     }
 }
 
@@ -1105,10 +1107,10 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gt[r] = ld4(gtil + j);
-        th[r] = ld4(theta + j);
-        mm[r] = ld4(m + j);
-        vv[r] = ld4(v + j);
-        vh[r] = ld4(vhat + j);
+        th[r] = stream_load4(theta + j);
+        mm[r] = stream_load4(m + j);
+        vv[r] = stream_load4(v + j);
+        vh[r] = stream_load4(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1120,10 +1122,10 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
                                       fadd(gt[r].w, c4.w));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
         st4(gtil + j, g4);
-        st4(theta + j, th[r]);
-        st4(m + j, mm[r]);
-        st4(v + j, vv[r]);
-        st4(vhat + j, vh[r]);
+        st4_stream(theta + j, th[r]);
+        st4_stream(m + j, mm[r]);
+        st4_stream(v + j, vv[r]);
+        st4_stream(vhat + j, vh[r]);
     }
 }
 
