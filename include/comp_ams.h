@@ -96,6 +96,16 @@ int comp_ams_set_lr(comp_ams_t *h, float lr);
 int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
 
 /*
+ * Cache policy, a tuning aid (no effect on results).  rows: how a step loads the stored rows (error
+ * memory / Markov sequences); state: how it loads and stores theta, m, v, vhat.  1 = as a stream
+ * (non-temporal: the data is not kept in the caches), 0 = ordinary accesses, -1 = chosen from the
+ * sizes (the default: each of the two streams when it exceeds 224 MB in total, i.e. when it could
+ * not stay in the 256 MB memory-side cache until the next step anyway; with CD-Adam the server's
+ * two vectors count with the state).  May be called between steps.
+ */
+int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
+
+/*
  * Rand-k (Appendix A, "Rand-k") only, before the first step: the seed of the draws and the number of
  * the next draw (default 0, 0; a resumed run passes the number of steps already taken).  The paper
  * leaves the drawing of S open.  Here coordinate j of the vector `who` (worker i: who = i; the

@@ -215,7 +215,7 @@ struct BsMarkov {
                             // workgroup, so lines 9-16 of Algorithm 1 follow at once (no bs_scale, no bs_apply)
 };
 
-template <bool kFusedScale, bool kEarlyState, bool kMarkov>
+template <bool kFusedScale, bool kEarlyState, bool kMarkov, bool kStreamState>
 __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int n, BsTable tb,
                                                       const double *__restrict__ partial,
                                                       float *__restrict__ scales,
@@ -236,10 +236,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t j = base + 4 * (tid + kThreads * r);
-            th[r] = stream_load4(theta + j);
-            mm[r] = stream_load4(m + j);
-            vv[r] = stream_load4(v + j);
-            vh[r] = stream_load4(vhat + j);
+            th[r] = ld4_state<kStreamState>(theta + j);
+            mm[r] = ld4_state<kStreamState>(m + j);
+            vv[r] = ld4_state<kStreamState>(v + j);
+            vh[r] = ld4_state<kStreamState>(vhat + j);
         }
     }
     float acc[16];
@@ -380,13 +380,13 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             for (int c = 0; c < 4; ++c)
                 nt[c] = (j + c < d) ? fadd(gt[c], signed_scale(s, sign_bits, r * 4 + c)) : gt[c];   // padding stays 0
             const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
-            float4 th4 = stream_load4(theta + j), m4 = stream_load4(m + j), v4 = stream_load4(v + j), vh4 = stream_load4(vhat + j);
+            float4 th4 = ld4_state<kStreamState>(theta + j), m4 = ld4_state<kStreamState>(m + j), v4 = ld4_state<kStreamState>(v + j), vh4 = ld4_state<kStreamState>(vhat + j);
             amsgrad_update4(th4, m4, v4, vh4, g4, p);
             st4(mk.gtil + j, g4);
-            st4_stream(theta + j, th4);
-            st4_stream(m + j, m4);
-            st4_stream(v + j, v4);
-            st4_stream(vhat + j, vh4);
+            st4_state<kStreamState>(theta + j, th4);
+            st4_state<kStreamState>(m + j, m4);
+            st4_state<kStreamState>(v + j, v4);
+            st4_state<kStreamState>(vhat + j, vh4);
         }
         return;
     }
@@ -394,10 +394,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int64_t j = base + 4 * (tid + kThreads * r);
-            th[r] = stream_load4(theta + j);
-            mm[r] = stream_load4(m + j);
-            vv[r] = stream_load4(v + j);
-            vh[r] = stream_load4(vhat + j);
+            th[r] = ld4_state<kStreamState>(theta + j);
+            mm[r] = ld4_state<kStreamState>(m + j);
+            vv[r] = ld4_state<kStreamState>(v + j);
+            vh[r] = ld4_state<kStreamState>(vhat + j);
         }
     }
 #pragma unroll
@@ -409,10 +409,10 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
                                         j + 2 < d ? fdiv(acc[r * 4 + 2], p.n_workers) : 0.f,
                                         j + 3 < d ? fdiv(acc[r * 4 + 3], p.n_workers) : 0.f);
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4_stream(theta + j, th[r]);
-        st4_stream(m + j, mm[r]);
-        st4_stream(v + j, vv[r]);
-        st4_stream(vhat + j, vh[r]);
+        st4_state<kStreamState>(theta + j, th[r]);
+        st4_state<kStreamState>(m + j, mm[r]);
+        st4_state<kStreamState>(v + j, vv[r]);
+        st4_state<kStreamState>(vhat + j, vh[r]);
     }
 }
 
@@ -437,6 +437,7 @@ __global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *__
 
 // CD-Adam, Algorithm 1, lines 10 and 12-16: gtilde += c with c = copysign(s[block], w) from the
 // server's sign bits and scales, then the AMSGrad update with gtilde.  One workgroup per tile.
+template <bool kStreamState>
 __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, const float *__restrict__ scales,
                                                      const uint16_t *__restrict__ signs, float *__restrict__ gtil,
                                                      float *__restrict__ theta, float *__restrict__ m,
@@ -451,10 +452,10 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gt[r] = ld4(gtil + j);
-        th[r] = stream_load4(theta + j);
-        mm[r] = stream_load4(m + j);
-        vv[r] = stream_load4(v + j);
-        vh[r] = stream_load4(vhat + j);
+        th[r] = ld4_state<kStreamState>(theta + j);
+        mm[r] = ld4_state<kStreamState>(m + j);
+        vv[r] = ld4_state<kStreamState>(v + j);
+        vh[r] = ld4_state<kStreamState>(vhat + j);
     }
     int p0, p1;
     if (tb.uniform_tiles > 0) {
@@ -484,10 +485,10 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
         const float4 g4 = make_float4(nt[0], nt[1], nt[2], nt[3]);
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
         st4(gtil + j, g4);
-        st4_stream(theta + j, th[r]);
-        st4_stream(m + j, mm[r]);
-        st4_stream(v + j, vv[r]);
-        st4_stream(vhat + j, vh[r]);
+        st4_state<kStreamState>(theta + j, th[r]);
+        st4_state<kStreamState>(m + j, mm[r]);
+        st4_state<kStreamState>(v + j, vv[r]);
+        st4_state<kStreamState>(vhat + j, vh[r]);
     }
 }
 

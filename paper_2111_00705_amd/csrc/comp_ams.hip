@@ -38,6 +38,7 @@ struct comp_ams {
     int device = 0;
     hipStream_t stream = nullptr;
     uint64_t steps = 0;
+    int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
     uint64_t rand_seed = 0;                    // Rand-k: the generator's seed and the number of the next draw
     uint32_t draw = 0;
     std::string err;
@@ -89,9 +90,28 @@ struct comp_ams {
     std::vector<std::vector<std::pair<hipEvent_t, hipEvent_t>>> prof;   // [slot] -> recorded pairs
 };
 
-// Whether the n stored rows are read as a stream (see ld4_row): beyond 128 MB they cannot stay in the
-// 256 MB memory-side cache from one step to the next, next to the gradients and what else a step moves.
-inline bool rows_exceed_caches(const comp_ams *h) { return (size_t)h->n * (size_t)h->ld * sizeof(float) > ((size_t)128 << 20); }
+// What a step touches once per step - the n stored rows; theta, m, v, vhat - is accessed as a stream
+// (see ld4_row, ld4_state) when it cannot stay in the 256 MB memory-side cache until the next step anyway.
+// Measured with 16 workers from 1.2 M to 25 M coordinates: rows of 183 MB in total are faster cached
+// (110 against 118 us per step), rows of 275 MB faster streamed (176 against 188 us); the state is a
+// wash up to 214 MB and faster streamed from 275 MB.  One threshold serves both.
+// With CD-Adam the server's ghat and gtilde are read and written next to the state; the six arrays then
+// compete for the cache together (11.2 M coordinates: 268 MB, and streaming the state is 8 % faster).
+constexpr size_t kCacheResidentBytes = (size_t)224 << 20;
+inline bool rows_exceed_caches(const comp_ams *h) { return (size_t)h->n * (size_t)h->ld * sizeof(float) > kCacheResidentBytes; }
+inline bool state_exceeds_caches(const comp_ams *h)
+{
+    const size_t arrays = h->method == COMP_AMS_METHOD_CD ? 6 : 4;
+    return arrays * (size_t)h->ld * sizeof(float) > kCacheResidentBytes;
+}
+// Applies the caller's choices (comp_ams_set_streaming; -1 = by size) to the kernel parameters.
+inline void apply_streaming(comp_ams *h)
+{
+    const int rows = h->rows_choice < 0 ? (rows_exceed_caches(h) ? 1 : 0) : h->rows_choice;
+    h->tb.stream_rows = rows;
+    h->ge.stream_rows = rows;
+    h->params.stream_state = h->state_choice < 0 ? (state_exceeds_caches(h) ? 1 : 0) : h->state_choice;
+}
 
 // Top-k and Rand-k share every buffer and kernel (the key differs, see SelKey).
 inline bool is_sparse(const comp_ams *h) { return h->compressor != COMP_AMS_BLOCKSIGN; }
@@ -279,7 +299,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
     h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
-    h->tb.stream_rows = rows_exceed_caches(h) ? 1 : 0;
+    apply_streaming(h);
     {
         bool ok = true;
         for (int64_t t = 0; t < n_tiles && ok; ++t) ok = (tile_piece0[t + 1] - tile_piece0[t] == 1);
@@ -340,7 +360,11 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
         // workgroups per compute unit
         const bool early = grid.x < 2048;
 #define CAMS_BS_UPDATE(F, E)                                                                                  \
-    KLAUNCH((bs_update<F, E, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
+    do {                                                                                                      \
+        if (h->params.stream_state) CAMS_BS_UPDATE_S(F, E, true); else CAMS_BS_UPDATE_S(F, E, false);          \
+    } while (0)
+#define CAMS_BS_UPDATE_S(F, E, S)                                                                             \
+    KLAUNCH((bs_update<F, E, false, S>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
                                                         h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{})
         if (h->fused_scale) {
             if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
@@ -348,6 +372,7 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
             if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
         }
 #undef CAMS_BS_UPDATE
+#undef CAMS_BS_UPDATE_S
     });
     h->pending = (h->method == COMP_AMS_METHOD_EF);
     return COMP_AMS_OK;
@@ -375,11 +400,21 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     launch_timed(h, P_BS_SERVER, st, [&] {
         const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
         if (whole)
-            KLAUNCH((bs_update<true, false, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
+            if (h->params.stream_state)
+                KLAUNCH((bs_update<true, false, true, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
+                                                                      h->signs, h->theta, h->m, h->v, h->vhat,
+                                                                      h->params, mk);
+            else
+                KLAUNCH((bs_update<true, false, true, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
                                                                       h->params, mk);
         else
-            KLAUNCH((bs_update<false, false, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
+            if (h->params.stream_state)
+                KLAUNCH((bs_update<false, false, true, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
+                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
+                                                                       h->params, mk);
+            else
+                KLAUNCH((bs_update<false, false, true, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
                                                                        h->signs, h->theta, h->m, h->v, h->vhat,
                                                                        h->params, mk);
     });
@@ -388,7 +423,11 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
             KLAUNCH((bs_scale), dim3(tb.n_blocks, 1), kWave, st, h->partial_srv, tb, h->scales_srv);
         });
         launch_timed(h, P_BS_APPLY, st, [&] {
-            KLAUNCH((bs_apply), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
+            if (h->params.stream_state)
+                KLAUNCH((bs_apply<true>), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
+                                                  h->v, h->vhat, h->params);
+            else
+                KLAUNCH((bs_apply<false>), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
                                                   h->v, h->vhat, h->params);
         });
     }
@@ -438,7 +477,11 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                               h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        KLAUNCH((tk_final), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+        if (h->params.stream_state)
+            KLAUNCH((tk_final<true>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+                                                  h->params);
+        else
+            KLAUNCH((tk_final<false>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
     });
     return COMP_AMS_OK;
@@ -456,7 +499,11 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
     launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                                 h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        KLAUNCH((tk_final), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+        if (h->params.stream_state)
+            KLAUNCH((tk_final<true>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
+                                                  h->params);
+        else
+            KLAUNCH((tk_final<false>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
                                                   h->params);
     });
     return COMP_AMS_OK;
@@ -467,7 +514,11 @@ template <typename G>
 int step_plain(comp_ams *h, const G *g, hipStream_t st)
 {
     launch_timed(h, P_PLAIN_UPDATE, st, [&] {
-        KLAUNCH((plain_update<G>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
+        if (h->params.stream_state)
+            KLAUNCH((plain_update<G, true>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
+                                                                     h->params);
+        else
+            KLAUNCH((plain_update<G, false>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
                                                                      h->params);
     });
     return COMP_AMS_OK;
@@ -496,7 +547,10 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
                             h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
-        KLAUNCH((tk_apply), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+        if (h->params.stream_state)
+            KLAUNCH((tk_apply<true>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+        else
+            KLAUNCH((tk_apply<false>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
     });
     return COMP_AMS_OK;
 }
@@ -687,7 +741,6 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         int slices = kMinSlices;
         while (slices > 1 && slices / 2 >= ge.n_tiles) slices /= 2;
         set_slices(ge, slices);
-        ge.stream_rows = rows_exceed_caches(h) ? 1 : 0;
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
         const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.slice_tiles * kTile;
@@ -706,6 +759,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
             return bail(rc);
         if ((rc = reset_topk_workers(h))) return bail(rc);
     }
+    apply_streaming(h);
     {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) {
@@ -764,6 +818,17 @@ int comp_ams_set_lr(comp_ams_t *h, float lr)
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
     if (!(lr > 0.f) || !std::isfinite(lr)) return fail(h, COMP_AMS_EINVAL, "lr must be positive and finite");
     h->params.lr = lr;
+    return COMP_AMS_OK;
+}
+
+int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    if (rows < -1 || rows > 1 || state < -1 || state > 1)
+        return fail(h, COMP_AMS_EINVAL, "streaming choices are -1 (automatic), 0 (cached) or 1 (streamed)");
+    h->rows_choice = rows;
+    h->state_choice = state;
+    apply_streaming(h);
     return COMP_AMS_OK;
 }
 
@@ -1048,6 +1113,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     h->pending = false;
     h->method = method;
+    apply_streaming(h);
     return COMP_AMS_OK;
 }
 

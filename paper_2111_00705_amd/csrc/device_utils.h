@@ -28,6 +28,8 @@ struct AmsParams {
     float eps, lr;
     int32_t eps_mode;                 // 0: sqrt(vhat)+eps   1: sqrt(vhat+eps)
     float n_workers;                  // divisor of the server average
+    int32_t stream_state;             // theta, m, v, vhat are loaded and stored as streams (non-temporal): the host
+                                      // launches the kStreamState = true variants of the update kernels
 };
 
 // m, v, vhat, theta update on one coordinate; every operation rounds to fp32 on its own
@@ -175,8 +177,22 @@ __device__ __forceinline__ void st4_stream(float *p, const float4 &v)
 }
 // A stored row (error memory / Markov sequence) is read once per step.  Rows that together are far
 // larger than the caches cannot survive from one step to the next, so they are loaded as a stream; small
-// ones (stream == 0) are loaded normally, since part of them is still cached from the step before.
+// ones (stream == 0) are loaded normally, since part of them is still cached from the step before.  (They
+// are stored as a stream in both cases: that measured faster or equal at every size.)
 __device__ __forceinline__ float4 ld4_row(const float *p, int stream) { return stream ? stream_load4(p) : ld4(p); }
+// theta, m, v, vhat are read and written once per step: streamed when they are too large to stay in the
+// memory-side cache until the next step (AmsParams::stream_state).
+// A compile-time choice: with a run-time flag the compiler merges the two stores and drops the hint.
+template <bool kStream>
+__device__ __forceinline__ float4 ld4_state(const float *p)
+{
+    if constexpr (kStream) return stream_load4(p); else return ld4(p);
+}
+template <bool kStream>
+__device__ __forceinline__ void st4_state(float *p, const float4 &v)
+{
+    if constexpr (kStream) st4_stream(p, v); else st4(p, v);
+}
 
 __device__ __forceinline__ uint32_t mag_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
 

@@ -8,7 +8,7 @@ namespace cams {
 
 constexpr int kPlainBatch = 4;   // workers whose gradients are in flight together
 
-template <typename G>   // float or uint16_t (bfloat16 bits)
+template <typename G, bool kStreamState>   // G: float, uint16_t (bfloat16 bits) or f16bits
 __global__ __launch_bounds__(kThreads) void plain_update(const G *__restrict__ g, int64_t d, int n,
                                                          float *__restrict__ theta, float *__restrict__ m,
                                                          float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
@@ -43,15 +43,15 @@ __global__ __launch_bounds__(kThreads) void plain_update(const G *__restrict__ g
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
-        float4 th = stream_load4(theta + j), mm = stream_load4(m + j), vv = stream_load4(v + j), vh = stream_load4(vhat + j);
+        float4 th = ld4_state<kStreamState>(theta + j), mm = ld4_state<kStreamState>(m + j), vv = ld4_state<kStreamState>(v + j), vh = ld4_state<kStreamState>(vhat + j);
         // padding coordinates take no gradient (load_grad4 gives 0 past d)
         const float4 gbar = make_float4(fdiv(acc[r][0], p.n_workers), fdiv(acc[r][1], p.n_workers),
                                         fdiv(acc[r][2], p.n_workers), fdiv(acc[r][3], p.n_workers));
         amsgrad_update4(th, mm, vv, vh, gbar, p);
-        st4_stream(theta + j, th);
-        st4_stream(m + j, mm);
-        st4_stream(v + j, vv);
-        st4_stream(vhat + j, vh);
+        st4_state<kStreamState>(theta + j, th);
+        st4_state<kStreamState>(m + j, mm);
+        st4_state<kStreamState>(v + j, vv);
+        st4_state<kStreamState>(vhat + j, vh);
     }
 }
 

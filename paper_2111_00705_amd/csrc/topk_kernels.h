@@ -995,6 +995,7 @@ __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, cons
     }
 }
 
+template <bool kStreamState>
 __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
                                                      const uint2 *__restrict__ cand,
                                                      const uint4 *__restrict__ tile_dir,
@@ -1017,10 +1018,10 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = stream_load4(theta + j);
-        mm[r] = stream_load4(m + j);
-        vv[r] = stream_load4(v + j);
-        vh[r] = stream_load4(vhat + j);
+        th[r] = ld4_state<kStreamState>(theta + j);
+        mm[r] = ld4_state<kStreamState>(m + j);
+        vv[r] = ld4_state<kStreamState>(v + j);
+        vh[r] = ld4_state<kStreamState>(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1030,10 +1031,10 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
         const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
                                         fdiv(a.w, p.n_workers));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4_stream(theta + j, th[r]);
-        st4_stream(m + j, mm[r]);
-        st4_stream(v + j, vv[r]);
-        st4_stream(vhat + j, vh[r]);
+        st4_state<kStreamState>(theta + j, th[r]);
+        st4_state<kStreamState>(m + j, mm[r]);
+        st4_state<kStreamState>(v + j, vv[r]);
+        st4_state<kStreamState>(vhat + j, vh[r]);
     }
 }
 
@@ -1075,6 +1076,7 @@ __global__ __launch_bounds__(kThreads) void tk_merge(TkGeom ge, const TkWorker *
 
 // CD-Adam (Algorithm 1), lines 10 and 12-16: gtilde += c, c = the kept coordinates of w, then the
 // AMSGrad update with gtilde.  Per tile; each wavefront handles its own coordinates.
+template <bool kStreamState>
 __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restrict__ gtil, float *__restrict__ theta,
                                                      float *__restrict__ m, float *__restrict__ v,
                                                      float *__restrict__ vhat, AmsParams p)
@@ -1107,10 +1109,10 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
         gt[r] = ld4(gtil + j);
-        th[r] = stream_load4(theta + j);
-        mm[r] = stream_load4(m + j);
-        vv[r] = stream_load4(v + j);
-        vh[r] = stream_load4(vhat + j);
+        th[r] = ld4_state<kStreamState>(theta + j);
+        mm[r] = ld4_state<kStreamState>(m + j);
+        vv[r] = ld4_state<kStreamState>(v + j);
+        vh[r] = ld4_state<kStreamState>(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1122,10 +1124,10 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
                                       fadd(gt[r].w, c4.w));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
         st4(gtil + j, g4);
-        st4_stream(theta + j, th[r]);
-        st4_stream(m + j, mm[r]);
-        st4_stream(v + j, vv[r]);
-        st4_stream(vhat + j, vh[r]);
+        st4_state<kStreamState>(theta + j, th[r]);
+        st4_state<kStreamState>(m + j, mm[r]);
+        st4_state<kStreamState>(v + j, vv[r]);
+        st4_state<kStreamState>(vhat + j, vh[r]);
     }
 }
 

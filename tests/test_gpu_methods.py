@@ -247,3 +247,34 @@ def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
         else:
             assert np.array_equal(bits(gpu.get_ghat_worker(1)), bits(ora.ghat_workers[1])), t
     gpu.destroy()
+
+
+@pytest.mark.parametrize("comp,kb", [(P.TOPK, 300), (P.BLOCKSIGN, 1000)])
+@pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_CD])
+def test_the_cache_policy_does_not_change_results(comp, kb, method):
+    """comp_ams_set_streaming only picks load / store flavours: every combination, also switched between
+    steps, must leave bit-identical state."""
+    import torch
+    announce(f"cache policy comp={comp} method={method}")
+    d, n = 30_011, 3
+    gs = [np.random.default_rng([77, t]).standard_normal((n, d)).astype(f32) for t in range(4)]
+    ref = None
+    for rows, state in ((-1, -1), (0, 0), (1, 1), (0, 1), (1, 0)):
+        h = P.CompAms(d, n, comp, kb)
+        h.set_method(method)
+        h.set_streaming(rows, state)
+        for t, g in enumerate(gs):
+            if t == 2:
+                h.set_streaming(state, rows)          # swapped, between steps
+            h.step(torch.from_numpy(g).cuda())
+        out = [bits(h.get_theta()), bits(h.get_m()), bits(h.get_v()), bits(h.get_vhat())]
+        out += [bits(h.get_error(i) if method == P.METHOD_EF else h.get_ghat_worker(i)) for i in range(n)]
+        h.destroy()
+        if ref is None:
+            ref = out
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(ref, out)), (rows, state)
+    h = P.CompAms(64, 1, comp, 8)
+    with pytest.raises(P.CompAmsError):
+        h.set_streaming(2, 0)
+    h.destroy()
