@@ -32,7 +32,7 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
     ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 234.4e6,
     ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.5e6,
     ("cfg2_topk_n16_d11173962", "tk_pass1"): 2178.7e6,
-    ("cfg2_topk_n16_d11173962", "tk_final"): 388.5e6,
+    ("cfg2_topk_n16_d11173962", "tk_final"): 389.2e6,
     ("cfg3_layersign_n32_d25557032", "bs_pass"): 9955.8e6,
     ("cfg3_layersign_n32_d25557032", "bs_update"): 921.5e6,
     ("cfg4_topk_n8_d110000000", "tk_pass1"): 10599.5e6,
