@@ -1087,7 +1087,8 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
             TkSide &sv = h->srv;
             sv.ge = h->ge;
             sv.ge.n = 1;
-            sv.ge.stream_rows = 0;       // ghat and gtilde are reused within the step
+            // ghat and gtilde are reused within the step if they are small enough to stay cached
+            sv.ge.stream_rows = 2 * (size_t)h->ld * sizeof(float) > kCacheResidentBytes ? 1 : 0;
             sv.ge.relist_wgs = (int32_t)std::min<int64_t>(sv.ge.n_tiles, 2048);
             // one vector, all tiles: enough regions that a cursor sees few tens of atomic adds
             int slices = kMinSlices;

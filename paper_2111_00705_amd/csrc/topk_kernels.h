@@ -309,7 +309,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
     for (int r = 0; r < 4; ++r) {
         const uint32_t j = base + 4 * (tid + kThreads * r);
         if constexpr (kMode == kPassDiff)
-            gv[r] = ld4(grow + j);
+            gv[r] = ld4_row(grow + j, stream_rows);
         else
             gv[r] = load_grad4(grow, j, d);
         xv[r] = kMode == kPassNaive ? make_float4(0.f, 0.f, 0.f, 0.f) : ld4_row(xrow + j, stream_rows);
