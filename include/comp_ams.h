@@ -99,9 +99,10 @@ int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
  * Cache policy, a tuning aid (no effect on results).  rows: how a step loads the stored rows (error
  * memory / Markov sequences); state: how it loads and stores theta, m, v, vhat.  1 = as a stream
  * (non-temporal: the data is not kept in the caches), 0 = ordinary accesses, -1 = chosen from the
- * sizes (the default: each of the two streams when it exceeds 224 MB in total, i.e. when it could
- * not stay in the 256 MB memory-side cache until the next step anyway; with CD-Adam the server's
- * two vectors count with the state).  May be called between steps.
+ * sizes (the default: the rows stream when they exceed 224 MB in total, i.e. when they could not
+ * stay in the 256 MB memory-side cache until the next step anyway; the state is left cached only
+ * if it fits likewise - with CD-Adam the server's two vectors count with it - and, under error
+ * feedback, only if the rows stream).  May be called between steps.
  */
 int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
 

@@ -93,8 +93,10 @@ struct comp_ams {
 // What a step touches once per step - the n stored rows; theta, m, v, vhat - is accessed as a stream
 // (see ld4_row, ld4_state) when it cannot stay in the 256 MB memory-side cache until the next step anyway.
 // Measured with 16 workers from 1.2 M to 25 M coordinates: rows of 183 MB in total are faster cached
-// (110 against 118 us per step), rows of 275 MB faster streamed (176 against 188 us); the state is a
-// wash up to 214 MB and faster streamed from 275 MB.  One threshold serves both.
+// (110 against 118 us per step), rows of 275 MB faster streamed (176 against 188 us).  The state is faster
+// cached when it fits and the rows stream past it (11.2 M coordinates, 179 MB: tk_final 70 -> 62 us), faster
+// streamed when it does not fit, and also when the rows are cached and it would compete with them (1.2 M
+// coordinates: 52.2 against 52.9 us per step).
 // With CD-Adam the server's ghat and gtilde are read and written next to the state; the six arrays then
 // compete for the cache together (11.2 M coordinates: 268 MB, and streaming the state is 8 % faster).
 constexpr size_t kCacheResidentBytes = (size_t)224 << 20;
@@ -110,7 +112,11 @@ inline void apply_streaming(comp_ams *h)
     const int rows = h->rows_choice < 0 ? (rows_exceed_caches(h) ? 1 : 0) : h->rows_choice;
     h->tb.stream_rows = rows;
     h->ge.stream_rows = rows;
-    h->params.stream_state = h->state_choice < 0 ? (state_exceeds_caches(h) ? 1 : 0) : h->state_choice;
+    // the state stays cached if it fits - except under error feedback with cached rows, where it would
+    // compete with them (CD-Adam with cached rows measured the other way: 55.9 against 58.0 us per step with
+    // 1.2 M coordinates; methods without memory do not touch the rows at all)
+    const bool rows_cached = rows == 0 && h->method == COMP_AMS_METHOD_EF;
+    h->params.stream_state = h->state_choice < 0 ? ((state_exceeds_caches(h) || rows_cached) ? 1 : 0) : h->state_choice;
 }
 
 // Top-k and Rand-k share every buffer and kernel (the key differs, see SelKey).
