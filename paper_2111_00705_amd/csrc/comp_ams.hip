@@ -1202,7 +1202,8 @@ int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, voi
     if (count < 4 || (count & 3) || ((reinterpret_cast<uintptr_t>(dst_dev) | reinterpret_cast<uintptr_t>(src_dev)) & 15u))
         return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: count must be a positive multiple of 4 and the pointers 16-byte aligned");
     const int64_t vecs = count / 4;
-    const unsigned blocks = (unsigned)std::min<int64_t>((vecs + kThreads - 1) / kThreads, 256 * 16);
+    if (vecs > (int64_t)1 << 40) return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: count too large");
+    const unsigned blocks = (unsigned)((vecs + 4 * kThreads - 1) / (4 * kThreads));
     probe_copy<<<blocks, kThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(dst_dev, src_dev, vecs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(nullptr, COMP_AMS_EDEVICE, "probe_copy launch failed: %s", hipGetErrorString(e));

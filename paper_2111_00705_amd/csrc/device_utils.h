@@ -217,14 +217,20 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return ((scratch[0] + scratch[1]) + scratch[2]) + scratch[3];
 }
 
-// Plain streaming copy, 16 bytes per lane, grid-stride: the yardstick for HBM counters and for the
-// bandwidth a simple kernel reaches on this chip.
+// Plain streaming copy, 16 bytes per lane, four independent loads per thread, one 16 KB piece per
+// workgroup, non-temporal on both sides: the yardstick for the HBM counters (it moves exactly the bytes it
+// is given) and for the bandwidth a simple kernel reaches on this chip.
 __global__ __launch_bounds__(kThreads) void probe_copy(float *__restrict__ dst, const float *__restrict__ src,
                                                        int64_t vecs)
 {
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < vecs; q += stride)
-        st4(dst + 4 * q, ld4(src + 4 * q));
+    const int64_t q0 = (int64_t)blockIdx.x * (4 * kThreads) + threadIdx.x;
+    float4 v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (q0 + r * kThreads < vecs) v[r] = stream_load4(src + 4 * (q0 + r * kThreads));
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (q0 + r * kThreads < vecs) st4_stream(dst + 4 * (q0 + r * kThreads), v[r]);
 }
 
 }  // namespace cams

@@ -278,3 +278,16 @@ def test_the_cache_policy_does_not_change_results(comp, kb, method):
     with pytest.raises(P.CompAmsError):
         h.set_streaming(2, 0)
     h.destroy()
+
+
+@pytest.mark.parametrize("count", [4, 1020, 4096, 4100, 1 << 20, (1 << 20) + 12])
+def test_probe_copy_copies_exactly_what_it_is_given(count):
+    """The plain copy that calibrates the HBM counters: dst == src, nothing written past the end."""
+    import torch
+    announce(f"probe_copy count={count}")
+    src = torch.randn(count, device="cuda")
+    dst = torch.full((count + 8,), -7.0, device="cuda")
+    P.probe_copy(dst[:count], src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:count], src)
+    assert bool((dst[count:] == -7.0).all())
