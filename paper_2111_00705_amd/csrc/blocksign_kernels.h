@@ -27,7 +27,7 @@
 //
 //   bs_pass<.., true>    ghat_i += pending c_i, u = g - ghat_i, store ghat_i, sign bits and piece sums of u
 //   bs_scale             as above
-//   bs_update<.., true>  mean of the c_i as above, ghat += mean, w = ghat - gtilde, sign bits and piece
+//   bs_update<.., kMarkov = true>  mean of the c_i as above, ghat += mean, w = ghat - gtilde, sign bits and piece
 //                        sums of w (the server's compression, lines 8-9 of Algorithm 1)
 //   bs_scale             once more, for the single vector w
 //   bs_apply             gtilde += copysign(s, w), then the AMSGrad update with gtilde
@@ -205,6 +205,7 @@ constexpr int kSignBatch = 8;       // workers whose sign words are loaded toget
 // ghat (Algorithm 1, line 8), w = ghat - gtilde is formed, and its sign bits and piece sums are
 // written for the second compression (line 9).  The arrays of the Markov struct are only touched
 // then; theta, m, v, vhat only otherwise.
+// kStreamState: theta, m, v, vhat are loaded and stored as streams (see ld4_state).
 struct BsMarkov {
     float *ghat;            // [ld] the server's aggregate
     float *gtil;            // [ld] gtilde of the step before (rewritten here only when whole_blocks is set)
