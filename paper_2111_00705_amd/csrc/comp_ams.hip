@@ -15,6 +15,7 @@
 #include <new>
 #include <string>
 #include <tuple>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -170,6 +171,13 @@ void launch_ext(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, A &
         else                                                          \
             kern<<<grid, block, 0, st>>>(__VA_ARGS__);                \
     } while (0)
+
+// Calls f with std::true_type or std::false_type: turns a run-time choice into a template argument.
+template <typename F>
+void by_flag(bool flag, F &&f)
+{
+    if (flag) f(std::true_type{}); else f(std::false_type{});
+}
 
 // Runs `launch` (exactly one KLAUNCH on st); with profiling on, the kernel's begin and end are recorded.
 template <typename F>
@@ -351,11 +359,14 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
-            KLAUNCH((bs_pass<false, kBsNaive, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsNaive, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales,
+                    h->signs, h->partial);
         else if (h->pending)
-            KLAUNCH((bs_pass<true, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<true, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+                    h->partial);
         else
-            KLAUNCH((bs_pass<false, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+                    h->partial);
     });
     if (!h->fused_scale)
         launch_timed(h, P_BS_SCALE, st, [&] {
@@ -366,19 +377,16 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
         // workgroups per compute unit
         const bool early = grid.x < 2048;
 #define CAMS_BS_UPDATE(F, E)                                                                                  \
-    do {                                                                                                      \
-        if (h->params.stream_state) CAMS_BS_UPDATE_S(F, E, true); else CAMS_BS_UPDATE_S(F, E, false);          \
-    } while (0)
-#define CAMS_BS_UPDATE_S(F, E, S)                                                                             \
-    KLAUNCH((bs_update<F, E, false, S>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales, h->signs,   \
-                                                        h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{})
+    by_flag(h->params.stream_state, [&](auto ss) {                                                            \
+        KLAUNCH((bs_update<F, E, false, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld, h->n, tb,   \
+                h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{});       \
+    })
         if (h->fused_scale) {
             if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
         } else {
             if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
         }
 #undef CAMS_BS_UPDATE
-#undef CAMS_BS_UPDATE_S
     });
     h->pending = (h->method == COMP_AMS_METHOD_EF);
     return COMP_AMS_OK;
@@ -392,9 +400,11 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            KLAUNCH((bs_pass<true, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<true, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+                    h->partial);
         else
-            KLAUNCH((bs_pass<false, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs, h->partial);
+            KLAUNCH((bs_pass<false, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+                    h->partial);
     });
     // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
     // scale are formed inside bs_update, which then also applies the server's message - two launches in all
@@ -406,35 +416,25 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     launch_timed(h, P_BS_SERVER, st, [&] {
         const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
         if (whole)
-            if (h->params.stream_state)
-                KLAUNCH((bs_update<true, false, true, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
-                                                                      h->signs, h->theta, h->m, h->v, h->vhat,
-                                                                      h->params, mk);
-            else
-                KLAUNCH((bs_update<true, false, true, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
-                                                                      h->signs, h->theta, h->m, h->v, h->vhat,
-                                                                      h->params, mk);
+            by_flag(h->params.stream_state, [&](auto ss) {
+                KLAUNCH((bs_update<true, false, true, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld,
+                        h->n, tb, h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, mk);
+            });
         else
-            if (h->params.stream_state)
-                KLAUNCH((bs_update<false, false, true, true>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
-                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
-                                                                       h->params, mk);
-            else
-                KLAUNCH((bs_update<false, false, true, false>), grid.x, kThreads, st, h->d, h->ld, h->n, tb, h->partial, h->scales,
-                                                                       h->signs, h->theta, h->m, h->v, h->vhat,
-                                                                       h->params, mk);
+            by_flag(h->params.stream_state, [&](auto ss) {
+                KLAUNCH((bs_update<false, false, true, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld,
+                        h->n, tb, h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, mk);
+            });
     });
     if (!whole) {
         launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
             KLAUNCH((bs_scale), dim3(tb.n_blocks, 1), kWave, st, h->partial_srv, tb, h->scales_srv);
         });
         launch_timed(h, P_BS_APPLY, st, [&] {
-            if (h->params.stream_state)
-                KLAUNCH((bs_apply<true>), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
-                                                  h->v, h->vhat, h->params);
-            else
-                KLAUNCH((bs_apply<false>), grid.x, kThreads, st, h->d, tb, h->scales_srv, h->signs_srv, h->gtil, h->theta, h->m,
-                                                  h->v, h->vhat, h->params);
+            by_flag(h->params.stream_state, [&](auto ss) {
+                KLAUNCH((bs_apply<decltype(ss)::value>), grid.x, kThreads, st, h->d, tb, h->scales_srv,
+                        h->signs_srv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+            });
         });
     }
     h->pending = true;
@@ -453,7 +453,8 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
     // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
     // the whole vector after a miss) are kept to about two per compute unit in total
     const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
-    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1, histf); });
+    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1,
+            histf); });
     launch_timed(h, slot[1], st, [&] {
         KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, hist_full, a, b);
     });
@@ -483,12 +484,10 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                               h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        if (h->params.stream_state)
-            KLAUNCH((tk_final<true>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
-                                                  h->params);
-        else
-            KLAUNCH((tk_final<false>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
-                                                  h->params);
+        by_flag(h->params.stream_state, [&](auto ss) {
+            KLAUNCH((tk_final<decltype(ss)::value>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir,
+                    h->theta, h->m, h->v, h->vhat, h->params);
+        });
     });
     return COMP_AMS_OK;
 }
@@ -499,18 +498,17 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand,
+                h->cursor,
                                                                           h->tile_dir);
     });
     launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
                                 h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_timed(h, P_TK_FINAL, st, [&] {
-        if (h->params.stream_state)
-            KLAUNCH((tk_final<true>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
-                                                  h->params);
-        else
-            KLAUNCH((tk_final<false>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->theta, h->m, h->v, h->vhat,
-                                                  h->params);
+        by_flag(h->params.stream_state, [&](auto ss) {
+            KLAUNCH((tk_final<decltype(ss)::value>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir,
+                    h->theta, h->m, h->v, h->vhat, h->params);
+        });
     });
     return COMP_AMS_OK;
 }
@@ -520,12 +518,10 @@ template <typename G>
 int step_plain(comp_ams *h, const G *g, hipStream_t st)
 {
     launch_timed(h, P_PLAIN_UPDATE, st, [&] {
-        if (h->params.stream_state)
-            KLAUNCH((plain_update<G, true>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
-                                                                     h->params);
-        else
-            KLAUNCH((plain_update<G, false>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n, h->theta, h->m, h->v, h->vhat,
-                                                                     h->params);
+        by_flag(h->params.stream_state, [&](auto ss) {
+            KLAUNCH((plain_update<G, decltype(ss)::value>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n,
+                    h->theta, h->m, h->v, h->vhat, h->params);
+        });
     });
     return COMP_AMS_OK;
 }
@@ -547,16 +543,17 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
-        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(ge.n_tiles, 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws, sv.cand,
+        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(ge.n_tiles, 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws,
+                sv.cand,
                                                                       sv.cursor, sv.tile_dir);
     });
     launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
                             h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
-        if (h->params.stream_state)
-            KLAUNCH((tk_apply<true>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
-        else
-            KLAUNCH((tk_apply<false>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
+        by_flag(h->params.stream_state, [&](auto ss) {
+            KLAUNCH((tk_apply<decltype(ss)::value>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v,
+                    h->vhat, h->params);
+        });
     });
     return COMP_AMS_OK;
 }
