@@ -644,6 +644,10 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
         }
         h->ge.rand.who0 = 0u;
         h->srv.ge.rand.who0 = (uint32_t)h->n;
+        // thresholds of independent draws differ by sqrt(2) standard deviations on average: six of those
+        const double kd = (double)h->k / (double)h->d;
+        const double sd_bins = std::sqrt((double)h->k * (1.0 - kd)) / (double)h->d * (double)(1u << 17);
+        h->ge.rand.min_slack = h->srv.ge.rand.min_slack = (uint32_t)std::min(512.0, std::ceil(6.0 * 1.4143 * sd_bins));
     }
     if (h->method == COMP_AMS_METHOD_NONE)
         rc = step_plain(h, grads_dev, st);

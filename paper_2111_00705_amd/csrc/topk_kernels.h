@@ -84,6 +84,8 @@ struct TkRand {
     uint32_t step_now;    // mix32(lower half of the seed + draw * 0x9e3779b9) for the running step's draw ...
     uint32_t step_prev;   // ... and for the draw of the step whose selection is still pending
     uint32_t who0;        // number of vector 0 of this geometry: 0 for the workers, n for CD-Adam's server
+    uint32_t min_slack;   // Rand-k: least slack of the guess, in fine bins (0: kMinSlack).  The k-th largest score
+                          // of a fresh draw scatters by sqrt(k (1 - k/d)) / d of the key range around (1 - k/d).
 };
 
 struct TkGeom {
@@ -836,7 +838,7 @@ __device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorke
     const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
     uint32_t slack = missed ? w.slack * 2u : w.slack - 1u;
     slack = max(slack, 2u * fell + 2u);
-    slack = min(max(slack, kMinSlack), kMaxSlack);
+    slack = min(max(slack, max(kMinSlack, ge.rand.min_slack)), kMaxSlack);
     ws[i].slack = slack;
     ws[i].last_fine = fine;
     ws[i].guess = fine > slack ? fine - slack : 0u;
