@@ -25,7 +25,7 @@
 // it.  The sign bits of c_i cannot be read off the stored vector here, so the step reads the old
 // sign word before it writes the new one.
 //
-//   bs_pass<.., true>    ghat_i += pending c_i, u = g - ghat_i, store ghat_i, sign bits and piece sums of u
+//   bs_pass<.., kBsCd>   ghat_i += pending c_i, u = g - ghat_i, store ghat_i, sign bits and piece sums of u
 //   bs_scale             as above
 //   bs_update<.., kMarkov = true>  mean of the c_i as above, ghat += mean, w = ghat - gtilde, sign bits and piece
 //                        sums of w (the server's compression, lines 8-9 of Algorithm 1)
