@@ -227,6 +227,22 @@ int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const fl
                               const float *gtilde, int on_device);
 
 /*
+ * One compressed message of the last step in its wire form, written to device memory (what a worker
+ * would hand to an all-gather; the paper's accounting of bits, Section 5 and the table of total
+ * bits, counts exactly these fields).  who = worker i in [0, n), or n on a CD handle for the
+ * server's message.  buf_dev: device memory, 8-byte aligned, `capacity` bytes; *bytes (may be NULL)
+ * receives the size of the message, also when the buffer is too small (EINVAL, nothing written).
+ *   BLOCKSIGN:     n_blocks fp32 scales, then (d + 31) / 32 words of sign bits in coordinate order
+ *                  (bit j % 32 of word j / 32 is set iff coordinate j is negative; zero past d):
+ *                  C(x)_j = (bit ? -1 : +1) * scale[block(j)].
+ *   TOPK / RANDK:  k pairs {uint32 index, fp32 value} in no particular order.
+ * comp_ams_message_bytes gives the size alone (4 d for a handle that does not compress) and needs no
+ * GPU.  Waits for the step to finish.
+ */
+int comp_ams_message_bytes(comp_ams_t *h, uint64_t *bytes);
+int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes);
+
+/*
  * Communication cost of one step in bits, by the accounting of Section 5 (footnote to the
  * algorithm overview) and of the table "Average runtime and total bits": a scaled-sign message costs
  * 1 bit per coordinate plus 32 bits per scale (32 + d for the whole vector), a Top-k message 32 bits

@@ -417,6 +417,26 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
     }
 }
 
+// Wire form of the sign bits of one vector: output word q holds the coordinates 32 q .. 32 q + 31, bit
+// j % 32 for coordinate j (set = negative), zero past d.  Those 32 coordinates are eight consecutive
+// float4 of one row r of the tile, i.e. the r-th nibble of eight consecutive sign words.
+__global__ __launch_bounds__(kThreads) void bs_pack_signs(const uint16_t *__restrict__ words, int64_t d,
+                                                          uint32_t *__restrict__ out)
+{
+    const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (q * 32 >= d) return;
+    const int64_t t = (q * 32) / kTile;
+    const int vec0 = (int)((q * 32) % kTile) / 4;            // first of the eight float4
+    const int r = vec0 / kThreads, tid0 = vec0 % kThreads;
+    uint32_t bits = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        bits |= (((uint32_t)words[t * kThreads + tid0 + u] >> (r * 4)) & 0xfu) << (4 * u);
+    const int64_t left = d - q * 32;
+    if (left < 32) bits &= (1u << left) - 1u;
+    out[q] = bits;
+}
+
 // e_i of one worker in its defined form, from the stored x and the pending scales.
 template <bool kPending>
 __global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *__restrict__ xrow, int64_t d,

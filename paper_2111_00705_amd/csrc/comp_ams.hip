@@ -991,6 +991,59 @@ int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host)
     return COMP_AMS_OK;
 }
 
+int comp_ams_message_bytes(comp_ams_t *h, uint64_t *bytes)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    if (!bytes) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    if (h->method == COMP_AMS_METHOD_NONE)
+        *bytes = 4ull * (uint64_t)h->d;
+    else if (is_sparse(h))
+        *bytes = 8ull * (uint64_t)h->k;
+    else
+        *bytes = 4ull * (uint64_t)h->tb.n_blocks + 4ull * (uint64_t)((h->d + 31) / 32);
+    return COMP_AMS_OK;
+}
+
+int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes)
+{
+    int rc = check_handle(h);
+    if (rc) return rc;
+    if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    const bool server = (h->method == COMP_AMS_METHOD_CD && who == h->n);
+    if (!server && (who < 0 || who >= h->n)) return fail(h, COMP_AMS_EINVAL, "vector %d out of range", who);
+    uint64_t need = 0;
+    (void)comp_ams_message_bytes(h, &need);
+    if (bytes) *bytes = need;
+    if (!buf_dev) return fail(h, COMP_AMS_EINVAL, "buffer is NULL");
+    if (reinterpret_cast<uintptr_t>(buf_dev) & 7u) return fail(h, COMP_AMS_EINVAL, "buffer must be 8-byte aligned");
+    if (capacity < need)
+        return fail(h, COMP_AMS_EINVAL, "buffer of %llu bytes, the message takes %llu", (unsigned long long)capacity,
+                    (unsigned long long)need);
+    if (is_sparse(h)) {
+        const TkGeom &ge = server ? h->srv.ge : h->ge;
+        HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
+        tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, server ? 0 : who, server ? h->srv.ws : h->ws,
+                                                                  server ? h->srv.cand : h->cand,
+                                                                  server ? h->srv.tile_dir : h->tile_dir, h->sel_count,
+                                                                  h->sel_out_idx, h->sel_out_val);
+        tk_pack_pairs<<<(unsigned)((ge.k + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+            h->sel_out_idx, h->sel_out_val, ge.k, static_cast<uint2 *>(buf_dev));
+    } else {
+        const size_t words = (size_t)h->ld / 16;
+        const size_t nb = (size_t)h->tb.n_blocks;
+        const float *sc = server ? h->scales_srv : h->scales + (size_t)who * nb;
+        const uint16_t *sw = server ? h->signs_srv : h->signs + (size_t)who * words;
+        HIP_TRY(h, hipMemcpyAsync(buf_dev, sc, nb * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+        const int64_t out_words = (h->d + 31) / 32;
+        bs_pack_signs<<<(unsigned)((out_words + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+            sw, h->d, reinterpret_cast<uint32_t *>(static_cast<float *>(buf_dev) + nb));
+    }
+    HIP_TRY(h, hipGetLastError());
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return COMP_AMS_OK;
+}
+
 int32_t comp_ams_n_blocks(comp_ams_t *h)
 {
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");

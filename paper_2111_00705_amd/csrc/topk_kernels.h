@@ -1186,4 +1186,12 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     }
 }
 
+// Wire form of a sparse message: (index, value bits) pairs.
+__global__ __launch_bounds__(kThreads) void tk_pack_pairs(const uint32_t *__restrict__ idx, const float *__restrict__ val,
+                                                          uint32_t k, uint2 *__restrict__ out)
+{
+    const uint32_t r = blockIdx.x * kThreads + threadIdx.x;
+    if (r < k) out[r] = make_uint2(idx[r], __float_as_uint(val[r]));
+}
+
 }  // namespace cams

@@ -291,3 +291,52 @@ def test_probe_copy_copies_exactly_what_it_is_given(count):
     torch.cuda.synchronize()
     assert torch.equal(dst[:count], src)
     assert bool((dst[count:] == -7.0).all())
+
+
+@pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_CD, P.METHOD_NAIVE])
+@pytest.mark.parametrize("comp,d,kb", [(P.BLOCKSIGN, 30_011, 1000), (P.BLOCKSIGN, 4096 * 3, 4096), (P.BLOCKSIGN, 37, 100),
+                                       (P.TOPK, 30_011, 300), (P.RANDK, 5_003, 77)])
+def test_packed_messages_decode_to_the_oracles_compressed_vectors(method, comp, d, kb):
+    """comp_ams_pack_message: the wire form of every worker's (and, for CD-Adam, the server's) message,
+    decoded on the host, is C(.) of the oracle bit for bit; its size is the paper's bit count rounded up
+    to whole 32-bit words."""
+    import torch
+    announce(f"pack method={method} comp={comp} d={d}")
+    n = 3
+    gpu = P.CompAms(d, n, comp, kb)
+    ora = O.Oracle(d, n, comp, kb, 0.9, 0.999, 1e-8, 1e-3, method=method)
+    gpu.set_method(method)
+    for t in range(3):
+        g = np.random.default_rng([d, comp, method, t]).standard_normal((n, d)).astype(f32)
+        gpu.step(torch.from_numpy(g).cuda())
+        ora.step(g)
+    nbytes = gpu.message_bytes()
+    up, down = gpu.message_bits()
+    assert up <= 8 * nbytes < up + 32
+    buf = torch.zeros(nbytes + 8, dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.CompAmsError):
+        gpu.pack_message(0, buf[: nbytes - 8])
+    vectors = [(i, ora.compressed[i]) for i in range(n)]
+    if method == P.METHOD_CD:
+        vectors.append((n, ora.server_compressed))
+    for who, want in vectors:
+        buf.fill_(0xAB)
+        assert gpu.pack_message(who, buf) == nbytes
+        raw = buf.cpu().numpy()
+        assert (raw[nbytes:] == 0xAB).all(), "written past the message"
+        got = np.zeros(d, f32)
+        if comp == P.BLOCKSIGN:
+            nb = gpu.n_blocks()
+            scales = raw[: 4 * nb].view(f32)
+            words = raw[4 * nb: nbytes].view(np.uint32)
+            neg = ((words[np.arange(d) // 32] >> (np.arange(d) % 32).astype(np.uint32)) & 1).astype(bool)
+            assert not (int(words[-1]) >> ((d - 1) % 32 + 1)) if d % 32 else True
+            blk = np.minimum(np.arange(d) // kb, nb - 1)
+            got = np.where(neg, -scales[blk], scales[blk]).astype(f32)
+        else:
+            pairs = raw[:nbytes].view(np.uint32).reshape(-1, 2)
+            assert len(set(pairs[:, 0].tolist())) == kb and pairs[:, 0].max() < d
+            got[pairs[:, 0]] = pairs[:, 1].copy().view(f32)
+        assert np.array_equal(bits(got), bits(want)), f"vector {who}"
+    gpu.destroy()
+    ora.close()
