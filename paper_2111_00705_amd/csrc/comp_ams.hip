@@ -465,7 +465,9 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
         KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir);
     });
     launch_timed(h, slot[4], st, [&] {
-        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full);
+        // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
+        const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, tile_dir, rows);
     });
 }
 
@@ -907,14 +909,34 @@ int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
 
 namespace {
 // The kept (index, value) pairs of one vector's last selection, sorted by index, to host arrays.
+// Leaves the kept (index, value) pairs of one vector in sel_out_idx / sel_out_val and their number in sel_count
+// (device memory), on the handle's stream.  worker_row: the worker whose stored row holds the vector under error
+// feedback with magnitude keys (zeros are then not among the candidates and come from the row), else -1.
+int launch_gather(comp_ams *h, const TkGeom &ge, int vec, const TkWorker *ws, const uint2 *cand,
+                  const uint4 *tile_dir, int worker_row)
+{
+    HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
+    tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, vec, ws, cand, tile_dir, h->sel_count,
+                                                              h->sel_out_idx, h->sel_out_val);
+    if (worker_row >= 0)
+        tk_gather_zero_tail<<<(unsigned)((h->d + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+            h->e + (size_t)worker_row * (size_t)h->ld, ge, ws + vec, h->sel_count, h->sel_out_idx, h->sel_out_val);
+    HIP_TRY(h, hipGetLastError());
+    return COMP_AMS_OK;
+}
+
+// The row that holds worker `w`'s compressed vector when zeros are counted instead of listed, else -1.
+int zero_row_of(const comp_ams *h, int w, bool server)
+{
+    return (!server && h->method == COMP_AMS_METHOD_EF && h->compressor == COMP_AMS_TOPK) ? w : -1;
+}
+
 int gather_selected(comp_ams *h, const TkGeom &ge, int worker, const TkWorker *ws, const uint2 *cand,
-                    const uint4 *tile_dir, uint32_t *idx_host, float *val_host)
+                    const uint4 *tile_dir, uint32_t *idx_host, float *val_host, int worker_row)
 {
     const size_t k = (size_t)ge.k;
-    HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
-    tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, worker, ws, cand, tile_dir, h->sel_count,
-                                                              h->sel_out_idx, h->sel_out_val);
-    HIP_TRY(h, hipGetLastError());
+    int rc = launch_gather(h, ge, worker, ws, cand, tile_dir, worker_row);
+    if (rc) return rc;
     uint32_t total = 0;
     std::vector<uint32_t> idx(k);
     std::vector<float> val(k);
@@ -942,7 +964,8 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
-    return gather_selected(h, h->ge, worker, h->ws, h->cand, h->tile_dir, idx_host, val_host);
+    return gather_selected(h, h->ge, worker, h->ws, h->cand, h->tile_dir, idx_host, val_host,
+                           zero_row_of(h, worker, false));
 }
 
 int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_host)
@@ -952,7 +975,7 @@ int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_h
     if (!is_sparse(h) || h->method != COMP_AMS_METHOD_CD)
         return fail(h, COMP_AMS_ESTATE, "get_server_selected needs a TOPK handle set to CD-Adam");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
-    return gather_selected(h, h->srv.ge, 0, h->srv.ws, h->srv.cand, h->srv.tile_dir, idx_host, val_host);
+    return gather_selected(h, h->srv.ge, 0, h->srv.ws, h->srv.cand, h->srv.tile_dir, idx_host, val_host, -1);
 }
 
 int comp_ams_get_scales(comp_ams_t *h, float *out_host)
@@ -1022,11 +1045,9 @@ int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t ca
                     (unsigned long long)need);
     if (is_sparse(h)) {
         const TkGeom &ge = server ? h->srv.ge : h->ge;
-        HIP_TRY(h, hipMemsetAsync(h->sel_count, 0, sizeof(uint32_t), h->stream));
-        tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, server ? 0 : who, server ? h->srv.ws : h->ws,
-                                                                  server ? h->srv.cand : h->cand,
-                                                                  server ? h->srv.tile_dir : h->tile_dir, h->sel_count,
-                                                                  h->sel_out_idx, h->sel_out_val);
+        if ((rc = launch_gather(h, ge, server ? 0 : who, server ? h->srv.ws : h->ws, server ? h->srv.cand : h->cand,
+                                server ? h->srv.tile_dir : h->tile_dir, zero_row_of(h, who, server))))
+            return rc;
         tk_pack_pairs<<<(unsigned)((ge.k + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
             h->sel_out_idx, h->sel_out_val, ge.k, static_cast<uint2 *>(buf_dev));
     } else {

@@ -62,6 +62,7 @@ constexpr int kResolveThreads = 1024;
 constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothing (before the first step)
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
+constexpr uint32_t kZeroTail = 2;            // value of TkWorker::whole
 
 
 struct TkWorker {
@@ -72,7 +73,8 @@ struct TkWorker {
     uint32_t prefix;        // magnitude bits above pshift
     uint32_t pshift;        // kFineShift or kShift1: how many low magnitude bits are still open
     uint32_t rank;          // 1-based rank (from the top) of the k-th largest among elements with this prefix
-    uint32_t whole;         // all elements with this prefix are kept: Tc needs no further digit
+    uint32_t whole;         // 1: all elements with this prefix are kept, Tc needs no further digit; kZeroTail: all
+                            // candidates are kept and `rank` zeros besides (see zero_tail_threshold)
     uint32_t relisted;      // the guess was above the threshold: candidates are listed again
     uint32_t last_fine;     // fine bin of the previous threshold (to see how far thresholds move)
 };
@@ -253,20 +255,25 @@ __device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int
 }
 
 // First half of moving a tile's staged candidates (count per wavefront, in LDS) to its region: the
-// thread `allocator` takes the space.  sh: 5 LDS words.  Ends before the barrier so that the caller
-// can put other work between the atomic and its use.
-__device__ __forceinline__ void flush_begin(uint32_t count, uint32_t *sh, int allocator, const TkGeom &ge, int i,
-                                            int t, uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
+// thread `allocator` takes the space.  sh: 9 LDS words.  zeros: the wavefront's count of exact zeros (the
+// tile's sum goes into the directory record).  Ends before the barrier so that the caller can put other
+// work between the atomic and its use.
+__device__ __forceinline__ void flush_begin(uint32_t count, uint32_t zeros, uint32_t *sh, int allocator, const TkGeom &ge,
+                                            int i, int t, uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     const int tid = threadIdx.x;
-    if ((tid & 63) == 0) sh[tid >> 6] = count;
+    if ((tid & 63) == 0) {
+        sh[tid >> 6] = count;
+        sh[5 + (tid >> 6)] = zeros;
+    }
     __syncthreads();
     if (tid == allocator) {
         const uint32_t total = sh[0] + sh[1] + sh[2] + sh[3];
         const uint32_t at = total ? atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total) : 0u;
         sh[4] = at;
         // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
-        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), total);
+        tile_dir[(int64_t)i * ge.n_tiles + t] =
+            make_uint4(at, sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), sh[5] + sh[6] + sh[7] + sh[8]);
     }
 }
 __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, const uint32_t *sh, const TkGeom &ge,
@@ -282,10 +289,19 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
 }
 
 // Stages one element of the vector that is compressed as a candidate if its fine bin reaches the guess.
+// kSkipZeros (error feedback with magnitude keys): exact zeros are never listed but counted (zeros, uniform
+// over the wavefront) - when fewer than k coordinates are non-zero the threshold lies among the zeros, which
+// are ordered by index alone, and is placed from these counts instead (see zero_tail_threshold).
+template <bool kSkipZeros>
 __device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, const SelKey &sk,
-                                         uint2 *stage, uint32_t &count)
+                                         uint2 *stage, uint32_t &count, uint32_t &zeros)
 {
-    const bool hit = valid && (sel_key(sk, x, j) >> kFineShift) >= guess;
+    bool hit = valid && (sel_key(sk, x, j) >> kFineShift) >= guess;
+    if (kSkipZeros && !sk.on) {
+        const bool zero = valid && mag_key(x) == 0u;
+        zeros += (uint32_t)__popcll(__ballot(zero));
+        hit = hit && !zero;
+    }
     const uint32_t slot = wave_append(hit, count);
     if (hit) stage[slot] = make_uint2(j, __float_as_uint(x));
 }
@@ -303,7 +319,7 @@ template <bool kFull, int kMode, typename G>
 __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
                                                const SelKey &sk, const SelKey &sk_prev, uint2 *stage,
-                                               int stream_rows)
+                                               int stream_rows, uint32_t &zeros)
 {
     const int tid = threadIdx.x;
     float4 gv[4], xv[4];
@@ -337,7 +353,8 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
         }
         if (kMode == kPassEf) st4_stream(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
-        for (int c = 0; c < 4; ++c) consider(x[c], j + c, kFull || j + c < d, guess, sk, stage, count);
+        for (int c = 0; c < 4; ++c)
+            consider<kMode == kPassEf>(x[c], j + c, kFull || j + c < d, guess, sk, stage, count, zeros);
     }
     return count;
 }
@@ -346,10 +363,11 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
 // whichever of the four comes last does the rest for the whole tile - takes the tile's space in its
 // region (one atomic add), writes the directory record and copies all staged candidates.  The other
 // three leave at once instead of waiting for the atomic.
-// sh: 5 LDS words, sh[4] zeroed (with a barrier after it) before the first wavefront can get here.
-__device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count, const TkGeom &ge,
-                                            int i, int t, uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                            uint4 *__restrict__ tile_dir)
+// sh: 9 LDS words, sh[4] zeroed (with a barrier after it) before the first wavefront can get here.
+// zeros: this wavefront's count of exact zeros; the tile's sum goes into the directory record's last word.
+__device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count, uint32_t zeros,
+                                            const TkGeom &ge, int i, int t, uint2 *__restrict__ cand,
+                                            uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // this wavefront's staged candidates are complete before it registers
@@ -357,6 +375,7 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
     uint32_t arrived = 0;
     if (lane == 0) {
         sh[wave] = count;
+        sh[5 + wave] = zeros;
         arrived = __hip_atomic_fetch_add(&sh[4], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     arrived = __builtin_amdgcn_readfirstlane(arrived);
@@ -369,7 +388,8 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
     if (lane == 0) {
         if (total) at = atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total);
         // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
-        tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), total);
+        tile_dir[(int64_t)i * ge.n_tiles + t] =
+            make_uint4(at, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), sh[5] + sh[6] + sh[7] + sh[8]);
     }
     at = __builtin_amdgcn_readfirstlane(at);
     uint2 *dst = cand + region_base(ge, i, t & (ge.slices - 1)) + at;
@@ -387,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     __shared__ uint2 stage[4][kSub];
-    __shared__ uint32_t sh[5];
+    __shared__ uint32_t sh[9];
     const int t = blockIdx.x;
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
@@ -400,15 +420,15 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const uint32_t base = (uint32_t)t * kTile;
     if (tid == 0) sh[4] = 0;
     __syncthreads();
-    uint32_t count;
+    uint32_t count, zeros = 0;
     const G *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
     if (base + kTile <= d)
         count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                           stage[wave], ge.stream_rows);
+                                           stage[wave], ge.stream_rows, zeros);
     else
         count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                            stage[wave], ge.stream_rows);
-    finish_tile(stage, sh, count, ge, i, t, cand, cursor, tile_dir);
+                                            stage[wave], ge.stream_rows, zeros);
+    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -596,6 +616,23 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         return;
     }
 
+    if (kSrc == kSrcStored && !ge.rand.on && guess == 0u) {
+        // error feedback with magnitude keys: a guess of 0 lists every non-zero element, and there are fewer
+        // than k of them - the k-th largest is a zero.  All candidates are kept; tk_resolve places the threshold
+        // among the zeros, which are ordered by index alone, from the zero counts of the tiles.
+        if (blockIdx.x != 0) return;
+        if (tid == 0) {
+            ws[i].prefix = 0u;
+            ws[i].pshift = kShift1;
+            ws[i].rank = ge.k - total;          // so many zeros are kept, the lowest indices first
+            ws[i].whole = kZeroTail;
+            ws[i].relisted = 0u;
+        }
+        for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
+        if (tid < kFineWindow) frow[tid] = 0;
+        return;
+    }
+
     // the guess was too high: count the whole vector (tk_relist continues from the full histogram)
     for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
     __syncthreads();
@@ -644,7 +681,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
     __shared__ uint32_t res[4];
-    __shared__ uint32_t sh[5];
+    __shared__ uint32_t sh[9];
     const int i = blockIdx.y;
     if (!ws[i].relisted) return;
     const int tid = threadIdx.x;
@@ -678,17 +715,22 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
         load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
-        uint32_t count = 0;
+        uint32_t count = 0, zeros = 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint32_t j = base + 4 * (tid + kThreads * r) + c;
-                const bool hit = j < d && (sel_key(sk, x[r][c], j) >> kShift1) >= prefix;
+                bool hit = j < d && (sel_key(sk, x[r][c], j) >> kShift1) >= prefix;
+                if (kSrc == kSrcStored && !sk.on) {          // zeros are counted, not listed (as in tk_pass1)
+                    const bool zero = j < d && mag_key(x[r][c]) == 0u;
+                    zeros += (uint32_t)__popcll(__ballot(zero));
+                    hit = hit && !zero;
+                }
                 const uint32_t slot = wave_append(hit, count);
                 if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
             }
-        flush_begin(count, sh, 0, ge, i, t, cursor, tile_dir);
+        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir);
         flush_end(stage[wave], count, sh, ge, i, t, cand);
         __syncthreads();   // sh and stage are reused by the next tile
     }
@@ -844,11 +886,84 @@ __device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorke
     ws[i].guess = fine > slack ? fine - slack : 0u;
 }
 
+// Exclusive prefix sum of one value per thread over the 1024 threads of tk_resolve; returns the exclusive sum,
+// leaves the total in *total_sh.  part: 16 LDS words.  Two barriers.
+__device__ __forceinline__ uint32_t resolve_scan(uint32_t v, uint32_t *part, uint32_t *total_sh)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();                       // readers of an earlier part are done
+    if (lane == kWave - 1) part[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int q = 0; q < wave; ++q) before += part[q];
+    if (threadIdx.x == kResolveThreads - 1) *total_sh = before + incl;
+    return before + incl - v;
+}
+
+// Error feedback with fewer than k non-zero coordinates: the threshold is the comp value of the R-th zero of
+// the stored row in index order (zeros tie, the lower index wins), found from the tiles' zero counts: first
+// the tile that holds it, then its place inside that tile.  All kResolveThreads threads call this; R >= 1 and
+// the row holds at least R zeros below d.
+__device__ __forceinline__ uint64_t zero_tail_threshold(const uint4 *__restrict__ dir_row, const float *__restrict__ xrow,
+                                                        const TkGeom &ge, uint32_t R, ResolveLds &L)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0) {                              // what is read below if the counts held fewer than R zeros
+        L.res[0] = 0u;
+        L.res[1] = 0u;
+        L.tc_sh = (1ull << ge.idx_bits) - 1ull;
+    }
+    const int chunk = (ge.n_tiles + kResolveThreads - 1) / kResolveThreads;
+    const int t0 = min(tid * chunk, ge.n_tiles), t1 = min(t0 + chunk, ge.n_tiles);
+    uint32_t mine = 0;
+    for (int t = t0; t < t1; ++t) mine += dir_row[t].w;
+    uint32_t before = resolve_scan(mine, L.part, &L.res[3]);
+    if (before < R && R <= before + mine) {
+        for (int t = t0; t < t1; ++t) {
+            const uint32_t z = dir_row[t].w;
+            if (before + z >= R) {
+                L.res[0] = (uint32_t)t;           // the tile of the R-th zero ...
+                L.res[1] = R - before;            // ... which is this tile's res[1]-th zero
+                break;
+            }
+            before += z;
+        }
+    }
+    __syncthreads();
+    const uint32_t base = L.res[0] * (uint32_t)kTile, r = L.res[1];
+    // the tile in coordinate order: thread tid holds the coordinates base + 4 tid .. + 3 (padding is not counted)
+    const float4 v = ld4(xrow + base + 4 * tid);
+    const float x[4] = {v.x, v.y, v.z, v.w};
+    uint32_t zc = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) zc += (base + 4 * tid + c < (uint32_t)ge.d && mag_key(x[c]) == 0u) ? 1u : 0u;
+    uint32_t seen = resolve_scan(zc, L.part, &L.res[3]);
+    if (seen < r && r <= seen + zc) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (base + 4 * tid + c < (uint32_t)ge.d && mag_key(x[c]) == 0u && ++seen == r)
+                L.tc_sh = ((1ull << ge.idx_bits) - 1ull) - (uint64_t)(base + 4 * tid + c);   // key part 0
+        }
+    }
+    __syncthreads();
+    return L.tc_sh;
+}
+
+// xs: the stored rows under error feedback with magnitude keys (where zeros are counted instead of listed and
+// the threshold may lie among them), else null.
 __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
                                                               const uint64_t *__restrict__ dense,
                                                               const uint2 *__restrict__ dense_dir,
                                                               uint32_t *__restrict__ cursor,
-                                                              uint32_t *__restrict__ hist_full)
+                                                              uint32_t *__restrict__ hist_full,
+                                                              const uint4 *__restrict__ tile_dir,
+                                                              const float *__restrict__ xs)
 {
     __shared__ ResolveLds L;
     __shared__ uint32_t rpre[kMaxPieces + 1];
@@ -859,7 +974,10 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     const TkWorker w = ws[i];
     const int s_hi = (int)w.pshift + ge.idx_bits;
     uint64_t tc = (uint64_t)w.prefix << s_hi;
-    if (!w.whole) {
+    const uint4 *dir_row = tile_dir + (int64_t)i * ge.n_tiles;
+    if (w.whole == kZeroTail) {
+        tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank, L);
+    } else if (!w.whole) {
         const int pieces = ge.slices * ge.parts * 4;
         const uint64_t *wdense = dense + region_base(ge, i, 0);
         // exclusive prefix sum of the piece counts, two pieces per thread
@@ -892,7 +1010,12 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             const int r = owner_of(rpre, pieces, q);
             return wdense[rstart[r] + (q - rpre[r])];
         };
-        tc = resolve_digits(get, cnt, w.prefix, w.rank, s_hi, L);
+        if (xs != nullptr && w.prefix == 0u && w.rank > cnt)
+            // the threshold bin is the one of the smallest keys and the k-th largest lies below its listed
+            // (non-zero) elements: among the zeros
+            tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank - cnt, L);
+        else
+            tc = resolve_digits(get, cnt, w.prefix, w.rank, s_hi, L);
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
@@ -1165,11 +1288,12 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, worker);
     const uint4 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
     const uint2 *src = cand + region_base(ge, worker, t & (ge.slices - 1)) + rec.x;
-    for (uint32_t q0 = 0; q0 < rec.w; q0 += kThreads) {      // uniform over the workgroup
+    const uint32_t total = (rec.y & 0xffffu) + (rec.y >> 16) + (rec.z & 0xffffu) + (rec.z >> 16);
+    for (uint32_t q0 = 0; q0 < total; q0 += kThreads) {      // uniform over the workgroup
         const uint32_t q = q0 + threadIdx.x;
         uint2 c = make_uint2(0u, 0u);
         bool keep = false;
-        if (q < rec.w) {
+        if (q < total) {
             c = src[q];
             keep = composite(sel_key(sk, __uint_as_float(c.y), c.x), c.x, ge.idx_bits) >= tc;
         }
@@ -1182,6 +1306,31 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
                 out_idx[at] = c.x;
                 out_val[at] = __uint_as_float(c.y);
             }
+        }
+    }
+}
+
+// The kept zeros of one worker's stored row when the threshold lies among them (key part of Tc is 0): the
+// zeros at indices up to Tc's, appended to the pairs tk_gather_selected has written.
+__global__ __launch_bounds__(kThreads) void tk_gather_zero_tail(const float *__restrict__ xrow, TkGeom ge,
+                                                                const TkWorker *__restrict__ w,
+                                                                uint32_t *__restrict__ count,
+                                                                uint32_t *__restrict__ out_idx,
+                                                                float *__restrict__ out_val)
+{
+    const KeptTest kt = kept_test(w->tc, ge.idx_bits);
+    if (kt.tkey != 0u) return;
+    const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool keep = j < ge.d && j <= (int64_t)kt.tj && mag_key(xrow[min(j, ge.d - 1)]) == 0u;
+    const uint64_t km = __ballot(keep);
+    if (km) {
+        const int lane = threadIdx.x & 63;
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(count, (uint32_t)__popcll(km));
+        at = __shfl(at, 0, kWave) + __popcll(km & ((1ull << lane) - 1ull));
+        if (keep && at < ge.k) {
+            out_idx[at] = (uint32_t)j;
+            out_val[at] = xrow[j];
         }
     }
 }

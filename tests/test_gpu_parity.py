@@ -409,3 +409,27 @@ def test_topk_long_run_with_a_wandering_gradient_scale():
         second_listings += sum(gpu.get_selection_info(i)["relisted"] for i in range(n))
     assert n <= second_listings < n * steps // 2      # the first step always; later ones only now and then
     gpu.destroy()
+
+
+@pytest.mark.parametrize("d,n,k,density", [(300_007, 3, 3000, 0.004), (300_007, 3, 3000, 0.02), (50_000, 2, 50_000, 0.3),
+                                           (9_000, 2, 4500, 0.0), (1_300_003, 2, 13_000, 0.005)])
+def test_topk_with_fewer_nonzeros_than_k(d, n, k, density):
+    """Sparse vectors: when fewer than k coordinates are non-zero the k-th largest is a zero, and zeros are
+    selected by lower index.  Gradients with a fixed sparse support (plus signed zeros) keep the error memory
+    sparse too, so the regime persists over the steps; density 0.02 crosses in and out of it."""
+    announce(f"sparse top-k d={d} k={k} density={density}")
+    rng = np.random.default_rng(d + k)
+    support = rng.random(d) < density
+    gpu, ora = make_pair(d, n, P.TOPK, k)
+
+    def grads(t):
+        r = np.random.default_rng([d, k, t])
+        g = r.standard_normal((n, d)).astype(f32) * support
+        g[:, ~support] = np.where(r.random((n, int((~support).sum()))) < 0.5, f32(0.0), f32(-0.0))
+        if t == 2:
+            g[0] = 0.0                                    # an all-zero gradient for one worker
+        return g
+
+    run_steps(gpu, ora, grads, steps=5, tag=f"sparse d={d}")
+    gpu.destroy()
+    ora.close()
