@@ -38,6 +38,11 @@
 // Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
 // (about 1.2 k per worker, 8 B each, written once, read three times).
 //
+// Exact zeros under error feedback: when fewer than k coordinates are non-zero the k-th largest is a zero and
+// zeros are selected by lower index.  They are never listed as candidates (millions of equal keys would be);
+// tk_pass1 counts them per tile, and tk_resolve places the threshold among them from those counts
+// (zero_tail_threshold).  The other methods list zeros like any other value.
+//
 // Rand-k (Appendix A, "Rand-k") runs through the same kernels: the 31 magnitude bits are replaced by a
 // 31-bit pseudo-random score of (seed, step, worker, index), see SelKey; everything after the key -
 // bins, digits, thresholds, the deferred error - is unchanged.
