@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomp_ams.so")
 SOURCES = [os.path.join(CSRC, "comp_ams.hip")]
-HEADERS = [os.path.join(CSRC, f) for f in ("device_utils.h", "blocksign_kernels.h", "topk_kernels.h")] + [
+HEADERS = [os.path.join(CSRC, f) for f in ("device_utils.h", "blocksign_kernels.h", "topk_kernels.h", "plain_kernels.h")] + [
     os.path.join(os.path.dirname(HERE), "include", "comp_ams.h")]
 
 HIPCC_FLAGS = [
