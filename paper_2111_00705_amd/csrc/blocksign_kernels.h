@@ -52,6 +52,8 @@ struct BsTable {
     int32_t uniform_tiles;       // >0: every block spans this many whole tiles (the last block may be shorter),
                                  // so tile t is piece t of block t / uniform_tiles: no table look-ups needed
     int32_t stream_rows;         // the stored rows are too large to stay cached between steps: bs_pass loads them as a stream
+    const int32_t *scale_list;   // [n_scale_list] the blocks whose scale bs_scale forms from the piece sums: all but
+    int32_t n_scale_list;        // those that lie inside one tile next to other pieces (bs_pass writes their scale)
 };
 
 // Sign bits: per worker, per tile, one 16-bit word per thread of the workgroup.  Bit r*4 + c of
@@ -71,10 +73,15 @@ __device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
     return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
 }
 
-// Fixed-order fp64 sums of |x| over the pieces p0 .. p1-1 of the tile at `base`, one result per
-// piece written to out[p] by thread 0.  x: the 16 values of this thread (padding holds 0).
+// Fixed-order fp64 sums of |x| over the pieces p0 .. p1-1 of the tile at `base`, one result per piece written
+// to out[p].  x: the 16 values of this thread (padding holds 0).
+// A tile that is one piece is summed by the whole workgroup.  A tile of several pieces stages |x| in LDS in
+// coordinate order (absx, kTile floats) and sums 16 pieces at a time, each by a team of 16 lanes (strided
+// partial sums, then a fixed butterfly) - one workgroup reduction per piece made tiles of many short blocks
+// tens of times slower.  scales_row (may be null): a block that is a single piece of such a tile lies inside
+// the tile, so its scale is complete here and is written at once (bs_scale does not visit it).
 __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base, int p0, int p1, const BsTable &tb,
-                                           double *scratch, double *__restrict__ out)
+                                           double *scratch, float *absx, double *__restrict__ out, float *scales_row)
 {
     const int tid = threadIdx.x;
     if (p1 - p0 == 1) {
@@ -85,20 +92,31 @@ __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base,
             for (int c = 0; c < 4; ++c) acc += (double)fabsf(x[r][c]);
         const double S = block_sum(acc, scratch);
         if (tid == 0) out[p0] = S;
-    } else {
-        for (int p = p0; p < p1; ++p) {
-            const int lo = (p == p0) ? (int)base : tb.piece_hi[p - 1];
-            const int hi = tb.piece_hi[p];
-            double acc = 0.0;
+        return;
+    }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = (int)base + 4 * (tid + kThreads * r);
+    for (int r = 0; r < 4; ++r)
+        st4(absx + 4 * (tid + kThreads * r), make_float4(fabsf(x[r][0]), fabsf(x[r][1]), fabsf(x[r][2]), fabsf(x[r][3])));
+    __syncthreads();
+    constexpr int kTeam = 16;
+    const int team = tid / kTeam, tl = tid % kTeam;
+    for (int pb = p0; pb < p1; pb += kThreads / kTeam) {          // uniform over the workgroup
+        const int p = pb + team;
+        double acc = 0.0;
+        if (p < p1) {
+            const int lo = ((p == p0) ? (int)base : tb.piece_hi[p - 1]) - (int)base;
+            const int hi = tb.piece_hi[p] - (int)base;
+            for (int j = lo + tl; j < hi; j += kTeam) acc += (double)absx[j];
+        }
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (j + c >= lo && j + c < hi) acc += (double)fabsf(x[r][c]);
+        for (int off = kTeam / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, kWave);   // stays inside the team
+        if (p < p1 && tl == 0) {
+            out[p] = acc;
+            if (scales_row) {
+                const int b = tb.piece_blk[p];
+                if (tb.block_piece0[b + 1] - tb.block_piece0[b] == 1)
+                    scales_row[b] = (float)(acc / (double)(tb.offsets[b + 1] - tb.offsets[b]));
             }
-            const double S = block_sum(acc, scratch);
-            if (tid == 0) out[p] = S;
         }
     }
 }
@@ -111,11 +129,14 @@ enum { kBsEf = 0, kBsCd = 1, kBsNaive = 2 };
 template <bool kPending, int kMode, typename G>
 __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, float *__restrict__ xs,
                                                     int64_t d, int64_t ld, BsTable tb,
-                                                    const float *__restrict__ s_prev,
+                                                    float *scales,          // [n][n_blocks]: the previous step's are
+                                                                            // read; blocks inside a tile get their new one
                                                     uint16_t *__restrict__ signs,
                                                     double *__restrict__ partial)
 {
     __shared__ double scratch[4];
+    __shared__ float absx[kTile];
+    const float *s_prev = scales;
     const int t = blockIdx.x;
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
@@ -173,14 +194,16 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
         for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
     }
     *word = (uint16_t)sign_bits;
-    piece_sums(x, base, p0, p1, tb, scratch, partial + (int64_t)i * tb.n_pieces);
+    // every thread has read the scales it needs (the loop above) before any is rewritten (after the barrier inside)
+    piece_sums(x, base, p0, p1, tb, scratch, absx, partial + (int64_t)i * tb.n_pieces,
+               scales + (int64_t)i * tb.n_blocks);
 }
 
-// One wavefront per (block, worker).
+// One wavefront per (listed block, worker): see BsTable::scale_list.
 __global__ __launch_bounds__(kWave) void bs_scale(const double *__restrict__ partial, BsTable tb,
                                                   float *__restrict__ scales)
 {
-    const int b = blockIdx.x;
+    const int b = tb.scale_list[blockIdx.x];
     const int i = blockIdx.y;
     const int q0 = tb.block_piece0[b], q1 = tb.block_piece0[b + 1];
     const double *row = partial + (int64_t)i * tb.n_pieces;
@@ -227,6 +250,7 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
 {
     __shared__ float s_lds[kScaleChunk];
     __shared__ double scratch[4];
+    __shared__ float absx[kMarkov ? kTile : 1];      // piece_sums of the server's vector
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
@@ -358,7 +382,7 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
         mk.signs[(int64_t)t * kThreads + tid] = (uint16_t)sign_bits;
         __syncthreads();   // s_lds readers are done before scratch is used (separate arrays; keeps phases apart)
         if (!mk.whole_blocks) {
-            piece_sums(w, base, p0, p1, tb, scratch, mk.partial);
+            piece_sums(w, base, p0, p1, tb, scratch, absx, mk.partial, mk.scales);
             return;
         }
         // c = C(w) with the scale of this tile's block, gtilde += c, AMSGrad with gtilde

@@ -283,8 +283,21 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
         tile_piece0[n_tiles] = (int32_t)piece_hi.size();
         block_piece0[nb] = (int32_t)piece_hi.size();
     }
+    // blocks whose scale bs_scale forms: all but those that are one piece of a tile with several pieces (the
+    // pass kernels write the scale of such a block themselves)
+    std::vector<int32_t> scale_list;
+    for (int b = 0; b < nb; ++b) {
+        bool direct = false;
+        if (block_piece0[b + 1] - block_piece0[b] == 1) {
+            const int64_t t = off[b] / kTile;
+            direct = tile_piece0[t + 1] - tile_piece0[t] > 1;
+        }
+        if (!direct) scale_list.push_back(b);
+    }
+    const int32_t n_scale_list = (int32_t)scale_list.size();
+    if (scale_list.empty()) scale_list.push_back(0);
     std::vector<void *> fresh;
-    int32_t *d_off = nullptr, *d_hi = nullptr, *d_blk = nullptr, *d_tp = nullptr, *d_bp = nullptr;
+    int32_t *d_off = nullptr, *d_hi = nullptr, *d_blk = nullptr, *d_tp = nullptr, *d_bp = nullptr, *d_sl = nullptr;
     double *d_partial = nullptr, *d_partial_srv = nullptr;
     float *d_scales = nullptr, *d_scales_srv = nullptr;
     int rc;
@@ -295,7 +308,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
         return COMP_AMS_OK;
     };
     if ((rc = upload(&d_off, off32)) || (rc = upload(&d_hi, piece_hi)) || (rc = upload(&d_blk, piece_blk)) ||
-        (rc = upload(&d_tp, tile_piece0)) || (rc = upload(&d_bp, block_piece0)) ||
+        (rc = upload(&d_tp, tile_piece0)) || (rc = upload(&d_bp, block_piece0)) || (rc = upload(&d_sl, scale_list)) ||
         (rc = dev_alloc_t(h, fresh, &d_partial, (size_t)h->n * piece_hi.size())) ||
         (rc = dev_alloc_t(h, fresh, &d_scales, (size_t)h->n * nb)) ||
         (rc = dev_alloc_t(h, fresh, &d_partial_srv, piece_hi.size())) ||
@@ -310,6 +323,8 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     h->tb.piece_blk = d_blk;
     h->tb.tile_piece0 = d_tp;
     h->tb.block_piece0 = d_bp;
+    h->tb.scale_list = d_sl;
+    h->tb.n_scale_list = n_scale_list;
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
     h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
@@ -368,9 +383,9 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
             KLAUNCH((bs_pass<false, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
     });
-    if (!h->fused_scale)
+    if (!h->fused_scale && tb.n_scale_list > 0)
         launch_timed(h, P_BS_SCALE, st, [&] {
-            KLAUNCH((bs_scale), dim3(tb.n_blocks, h->n), kWave, st, h->partial, tb, h->scales);
+            KLAUNCH((bs_scale), dim3(tb.n_scale_list, h->n), kWave, st, h->partial, tb, h->scales);
         });
     launch_timed(h, P_BS_UPDATE, st, [&] {
         // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
@@ -409,9 +424,9 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
     // scale are formed inside bs_update, which then also applies the server's message - two launches in all
     const bool whole = h->fused_scale && tb.n_pieces == tb.n_blocks;
-    if (!whole)
+    if (!whole && tb.n_scale_list > 0)
         launch_timed(h, P_BS_SCALE, st, [&] {
-            KLAUNCH((bs_scale), dim3(tb.n_blocks, h->n), kWave, st, h->partial, tb, h->scales);
+            KLAUNCH((bs_scale), dim3(tb.n_scale_list, h->n), kWave, st, h->partial, tb, h->scales);
         });
     launch_timed(h, P_BS_SERVER, st, [&] {
         const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
@@ -427,9 +442,10 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
             });
     });
     if (!whole) {
-        launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
-            KLAUNCH((bs_scale), dim3(tb.n_blocks, 1), kWave, st, h->partial_srv, tb, h->scales_srv);
-        });
+        if (tb.n_scale_list > 0)
+            launch_timed(h, P_BS_SCALE_SERVER, st, [&] {
+                KLAUNCH((bs_scale), dim3(tb.n_scale_list, 1), kWave, st, h->partial_srv, tb, h->scales_srv);
+            });
         launch_timed(h, P_BS_APPLY, st, [&] {
             by_flag(h->params.stream_state, [&](auto ss) {
                 KLAUNCH((bs_apply<decltype(ss)::value>), grid.x, kThreads, st, h->d, tb, h->scales_srv,

@@ -433,3 +433,21 @@ def test_topk_with_fewer_nonzeros_than_k(d, n, k, density):
     run_steps(gpu, ora, grads, steps=5, tag=f"sparse d={d}")
     gpu.destroy()
     ora.close()
+
+
+@pytest.mark.parametrize("block", [1, 3, 16, 64, 1000, 2048, 5000])
+def test_blocksign_with_blocks_shorter_and_longer_than_a_tile(block):
+    """Uniform blocks that cut every tile into several pieces (summed by teams of 16 lanes, scales written by
+    the pass itself) or span several tiles with a ragged cut."""
+    announce(f"blocksign block={block}")
+    d, n = 40_011, 3
+    gpu, ora = make_pair(d, n, P.BLOCKSIGN, block)
+    scale = np.exp(np.random.default_rng(block).uniform(-5, 0, d)).astype(f32)
+    run_steps(gpu, ora, lambda t: (np.random.default_rng([block, t]).standard_normal((n, d)) * scale).astype(f32),
+              steps=4, tag=f"block {block}", offsets=ora_offsets(d, block))
+    gpu.destroy()
+    ora.close()
+
+
+def ora_offsets(d, block):
+    return np.minimum(np.arange((d + block - 1) // block + 1, dtype=np.int64) * block, d)
