@@ -9,10 +9,11 @@
 //
 //   bs_pass     per (tile of 4096 coordinates, worker): e = stored x minus its sign compression
 //               (previous scales), x = g + e, store x, write the sign bits of x (1 bit per
-//               coordinate), fp64 partial sums of |x| per piece (tile x block)
-//   bs_scale    per (block, worker): fixed-order fp64 sum of the pieces, s = fl32(S / block length)
-//               (skipped when every tile lies in one block of at most 8 pieces: bs_update then
-//               adds the pieces itself)
+//               coordinate), fp64 partial sums of |x| per piece (tile x block); a block that lies
+//               inside one tile of several pieces gets its scale here
+//   bs_scale    per (other block, worker): fixed-order fp64 sum of the pieces, s = fl32(S / block
+//               length) (skipped when every tile lies in one block of at most 8 pieces: bs_update
+//               then adds the pieces itself)
 //   bs_update   per tile: gbar[j] = (sum_i +-s_i[block(j)]) / n, signs from the stored bits, workers
 //               in ascending order; then the AMSGrad update of theta, m, v, vhat
 //
@@ -61,6 +62,8 @@ struct BsTable {
 // component of the r-th float4 that thread tid handles in the tile (same mapping in bs_pass and
 // bs_update).
 constexpr int kMaxFusedPieces = 8;   // bs_update adds up to this many pieces of a block itself
+constexpr unsigned kPassTileLds = kTile * (sizeof(float) + sizeof(uint16_t));   // dynamic LDS bs_pass needs for a
+                                                                                // tile of several pieces
 
 __device__ __forceinline__ float deferred_sign_error(float xs, float s_prev)
 {
@@ -73,6 +76,27 @@ __device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
     return __uint_as_float(__float_as_uint(s) | ((bits << (31 - k)) & 0x80000000u));
 }
 
+// The pieces of a tile of several pieces, in LDS: bound[q] = end of piece p0 + q relative to the tile
+// (1 .. 4096), q < p1 - p0.  Inside a tile consecutive pieces belong to consecutive blocks (a new piece starts
+// where a block ends), so the block of piece p0 + q is piece_blk[p0] + q and no table is read per coordinate.
+// Ends with a barrier.
+__device__ __forceinline__ void stage_piece_bounds(uint16_t *bound, int p0, int p1, const BsTable &tb, int64_t base)
+{
+    for (int q = threadIdx.x; q < p1 - p0; q += kThreads) bound[q] = (uint16_t)(tb.piece_hi[p0 + q] - (int)base);
+    __syncthreads();
+}
+// Index of the piece that holds coordinate l of the tile: the first q with l < bound[q], the last piece for the
+// padding past d.  P >= 1 pieces.
+__device__ __forceinline__ int piece_index(const uint16_t *bound, int P, int l)
+{
+    int lo = 0, hi = P - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (l < (int)bound[mid]) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
 // Fixed-order fp64 sums of |x| over the pieces p0 .. p1-1 of the tile at `base`, one result per piece written
 // to out[p].  x: the 16 values of this thread (padding holds 0).
 // A tile that is one piece is summed by the whole workgroup.  A tile of several pieces stages |x| in LDS in
@@ -80,8 +104,10 @@ __device__ __forceinline__ float signed_scale(float s, uint32_t bits, int k)
 // partial sums, then a fixed butterfly) - one workgroup reduction per piece made tiles of many short blocks
 // tens of times slower.  scales_row (may be null): a block that is a single piece of such a tile lies inside
 // the tile, so its scale is complete here and is written at once (bs_scale does not visit it).
+// bound: the tile's piece ends as stage_piece_bounds leaves them (only read for a tile of several pieces).
 __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base, int p0, int p1, const BsTable &tb,
-                                           double *scratch, float *absx, double *__restrict__ out, float *scales_row)
+                                           double *scratch, float *absx, const uint16_t *bound,
+                                           double *__restrict__ out, float *scales_row)
 {
     const int tid = threadIdx.x;
     if (p1 - p0 == 1) {
@@ -100,12 +126,14 @@ __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base,
     __syncthreads();
     constexpr int kTeam = 16;
     const int team = tid / kTeam, tl = tid % kTeam;
+    const int b0 = tb.piece_blk[p0];
     for (int pb = p0; pb < p1; pb += kThreads / kTeam) {          // uniform over the workgroup
         const int p = pb + team;
         double acc = 0.0;
+        int lo = 0, hi = 0;
         if (p < p1) {
-            const int lo = ((p == p0) ? (int)base : tb.piece_hi[p - 1]) - (int)base;
-            const int hi = tb.piece_hi[p] - (int)base;
+            lo = (p == p0) ? 0 : (int)bound[p - p0 - 1];
+            hi = (int)bound[p - p0];
             for (int j = lo + tl; j < hi; j += kTeam) acc += (double)absx[j];
         }
 #pragma unroll
@@ -113,9 +141,10 @@ __device__ __forceinline__ void piece_sums(const float (&x)[4][4], int64_t base,
         if (p < p1 && tl == 0) {
             out[p] = acc;
             if (scales_row) {
-                const int b = tb.piece_blk[p];
-                if (tb.block_piece0[b + 1] - tb.block_piece0[b] == 1)
-                    scales_row[b] = (float)(acc / (double)(tb.offsets[b + 1] - tb.offsets[b]));
+                // a piece between two others is a whole block; the first and the last may be parts of longer ones
+                const int b = b0 + (p - p0);
+                const bool inner = p > p0 && p + 1 < p1;
+                if (inner || tb.block_piece0[b + 1] - tb.block_piece0[b] == 1) scales_row[b] = (float)(acc / (double)(hi - lo));
             }
         }
     }
@@ -135,7 +164,12 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
                                                     double *__restrict__ partial)
 {
     __shared__ double scratch[4];
-    __shared__ float absx[kTile];
+    // dynamic LDS, kPassTileLds bytes when the table has tiles of several pieces (only those use it): the staged
+    // |x| and the piece ends.  The host may ask for more: the amount also sets how many workgroups share a
+    // compute unit, which this kernel is sensitive to (see pass_lds_bytes in the host code).
+    extern __shared__ __align__(16) unsigned char pass_lds[];
+    float *absx = reinterpret_cast<float *>(pass_lds);
+    uint16_t *bound = reinterpret_cast<uint16_t *>(pass_lds + kTile * sizeof(float));
     const float *s_prev = scales;
     const int t = blockIdx.x;
     const int i = blockIdx.y;
@@ -159,20 +193,24 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
     float x[4][4];
     uint32_t sign_bits = 0;
     const bool single = (p1 - p0 == 1);
-    const float s_single = (kPending && single) ? sp[uni ? t / tb.uniform_tiles : tb.piece_blk[p0]] : 0.f;
+    const int P = p1 - p0;
+    const int b0 = (uni || (single && !kPending)) ? 0 : tb.piece_blk[p0];     // block of the tile's first piece
+    const float s_single = (kPending && single) ? sp[uni ? t / tb.uniform_tiles : b0] : 0.f;
+    if (!single) stage_piece_bounds(bound, p0, p1, tb, base);               // uniform over the workgroup
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
+        const int l0 = 4 * (tid + kThreads * r);
         const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
         const float xx[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
         float keep[4];     // what goes back to the stored vector
-        int p = p0;
+        int q = (kPending && !single) ? piece_index(bound, P, l0) : 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float s = s_single;
             if (kPending && !single) {
-                while (p + 1 < p1 && j + c >= tb.piece_hi[p]) ++p;
-                s = sp[tb.piece_blk[p]];
+                while (q + 1 < P && l0 + c >= (int)bound[q]) ++q;
+                s = sp[b0 + q];
             }
             if (kMode == kBsCd) {
                 // ghat_i = ghat_i + c_i (Algorithm 1, line 6, of the step before); u = g - ghat_i (line 5)
@@ -195,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
     }
     *word = (uint16_t)sign_bits;
     // every thread has read the scales it needs (the loop above) before any is rewritten (after the barrier inside)
-    piece_sums(x, base, p0, p1, tb, scratch, absx, partial + (int64_t)i * tb.n_pieces,
+    piece_sums(x, base, p0, p1, tb, scratch, absx, bound, partial + (int64_t)i * tb.n_pieces,
                scales + (int64_t)i * tb.n_blocks);
 }
 
@@ -251,6 +289,7 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
     __shared__ float s_lds[kScaleChunk];
     __shared__ double scratch[4];
     __shared__ float absx[kMarkov ? kTile : 1];      // piece_sums of the server's vector
+    __shared__ uint16_t bound[kTile];                // piece ends of a tile where several blocks meet
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
@@ -342,16 +381,18 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
             }
         }
     } else {
-        // several blocks meet in this tile: look up the block of every coordinate
+        // several blocks meet in this tile: find the block of every coordinate
+        stage_piece_bounds(bound, p0, p1, tb, base);
+        const int P = p1 - p0;
         int blk[16];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int j = (int)base + 4 * (tid + kThreads * r);
-            int q = p0;
+            const int l0 = 4 * (tid + kThreads * r);
+            int q = piece_index(bound, P, l0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
-                blk[r * 4 + c] = tb.piece_blk[q];
+                while (q + 1 < P && l0 + c >= (int)bound[q]) ++q;
+                blk[r * 4 + c] = b_single + q;            // b_single: the block of the tile's first piece
             }
         }
         for (int i = 0; i < n; ++i) {
@@ -382,7 +423,7 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
         mk.signs[(int64_t)t * kThreads + tid] = (uint16_t)sign_bits;
         __syncthreads();   // s_lds readers are done before scratch is used (separate arrays; keeps phases apart)
         if (!mk.whole_blocks) {
-            piece_sums(w, base, p0, p1, tb, scratch, absx, mk.partial, mk.scales);
+            piece_sums(w, base, p0, p1, tb, scratch, absx, bound, mk.partial, mk.scales);
             return;
         }
         // c = C(w) with the scale of this tile's block, gtilde += c, AMSGrad with gtilde
@@ -488,6 +529,7 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
                                                      float *__restrict__ theta, float *__restrict__ m,
                                                      float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
+    __shared__ uint16_t bound[kTile];                // piece ends of a tile where several blocks meet
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;
@@ -511,19 +553,23 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
         p1 = tb.tile_piece0[t + 1];
     }
     const bool single = (p1 - p0 == 1);
-    const float s_single = single ? scales[tb.uniform_tiles > 0 ? t / tb.uniform_tiles : tb.piece_blk[p0]] : 0.f;
+    const int P = p1 - p0;
+    const int b0 = tb.uniform_tiles > 0 ? t / tb.uniform_tiles : tb.piece_blk[p0];   // block of the tile's first piece
+    const float s_single = single ? scales[b0] : 0.f;
+    if (!single) stage_piece_bounds(bound, p0, p1, tb, base);                         // uniform over the workgroup
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
+        const int l0 = 4 * (tid + kThreads * r);
         const float old[4] = {gt[r].x, gt[r].y, gt[r].z, gt[r].w};
         float nt[4];
-        int q = p0;
+        int q = single ? 0 : piece_index(bound, P, l0);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             float s = s_single;
             if (!single) {
-                while (q + 1 < p1 && j + c >= tb.piece_hi[q]) ++q;
-                s = scales[tb.piece_blk[q]];
+                while (q + 1 < P && l0 + c >= (int)bound[q]) ++q;
+                s = scales[b0 + q];
             }
             nt[c] = (j + c < d) ? fadd(old[c], signed_scale(s, bits, r * 4 + c)) : old[c];   // padding stays 0
         }

@@ -40,6 +40,8 @@ struct comp_ams {
     hipStream_t stream = nullptr;
     uint64_t steps = 0;
     int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
+    unsigned pass_lds = 0;                         // dynamic LDS of bs_pass (see pass_lds_bytes)
+    bool has_split_tiles = false;                  // some tile holds several pieces
     uint64_t rand_seed = 0;                    // Rand-k: the generator's seed and the number of the next draw
     uint32_t draw = 0;
     std::string err;
@@ -107,12 +109,31 @@ inline bool state_exceeds_caches(const comp_ams *h)
     const size_t arrays = h->method == COMP_AMS_METHOD_CD ? 6 : 4;
     return arrays * (size_t)h->ld * sizeof(float) > kCacheResidentBytes;
 }
+// Dynamic LDS of bs_pass.  Tiles of several pieces need kPassTileLds, and such tables get exactly that: their tiles
+// pass through barriers, and more workgroups per compute unit hide those (n = 16, d = 11.2 M, blocks of 256:
+// pass 0.37 ms at 24 KB, 0.43 at 32 KB, 0.51 at 40 KB).  For tables of whole tiles the amount is a knob that sets
+// how many workgroups share a compute unit, and the pass responds to it by a few per cent (one session, same
+// build): once the rows are well beyond the caches, 40 KB - four workgroups per unit - measured best over n = 4
+// to 64 and d = 11 M to 110 M (n = 32, d = 25.6 M: 1.63 ms, against 1.70 ms at 16 KB and 1.77 ms at 64 KB); below
+// about a GiB of rows up to 16 KB is best (n = 16, d = 1.2 M: 36.4 us, against 37.7 at 24 KB and 42.1 at 40 KB;
+// n = 8, d = 11.2 M: 177 against 184 us).  CAMS_PASS_LDS in the environment overrides the amount, for such sweeps.
+inline unsigned pass_lds_bytes(const comp_ams *h)
+{
+    const unsigned need = h->has_split_tiles ? kPassTileLds : 0u;
+    static const char *env = getenv("CAMS_PASS_LDS");
+    if (env) return std::max(need, (unsigned)atoi(env));
+    if (need) return need;
+    const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
+    return far_beyond_caches ? 40u * 1024u : 16u * 1024u;
+}
+
 // Applies the caller's choices (comp_ams_set_streaming; -1 = by size) to the kernel parameters.
 inline void apply_streaming(comp_ams *h)
 {
     const int rows = h->rows_choice < 0 ? (rows_exceed_caches(h) ? 1 : 0) : h->rows_choice;
     h->tb.stream_rows = rows;
     h->ge.stream_rows = rows;
+    h->pass_lds = pass_lds_bytes(h);
     // the state stays cached if it fits - except under error feedback with cached rows, where it would
     // compete with them (CD-Adam with cached rows measured the other way: 55.9 against 58.0 us per step with
     // 1.2 M coordinates; methods without memory do not touch the rows at all)
@@ -153,24 +174,27 @@ const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk
 thread_local hipEvent_t t_ev0 = nullptr, t_ev1 = nullptr;
 
 template <typename... P, typename... A, size_t... I>
-void launch_ext_impl(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, std::index_sequence<I...>, A &&...args)
+void launch_ext_impl(void (*kernel)(P...), dim3 grid, dim3 block, unsigned lds, hipStream_t st,
+                     std::index_sequence<I...>, A &&...args)
 {
     std::tuple<P...> params{static_cast<P>(std::forward<A>(args))...};   // the kernel's own parameter types
     void *ptrs[] = {static_cast<void *>(&std::get<I>(params))...};
-    (void)hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, st, t_ev0, t_ev1, 0);
+    (void)hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, st, t_ev0, t_ev1, 0);
 }
 template <typename... P, typename... A>
-void launch_ext(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, A &&...args)
+void launch_ext(void (*kernel)(P...), dim3 grid, dim3 block, unsigned lds, hipStream_t st, A &&...args)
 {
-    launch_ext_impl(kernel, grid, block, st, std::index_sequence_for<P...>{}, std::forward<A>(args)...);
+    launch_ext_impl(kernel, grid, block, lds, st, std::index_sequence_for<P...>{}, std::forward<A>(args)...);
 }
-#define KLAUNCH(kern, grid, block, st, ...)                           \
+// lds: bytes of dynamic LDS
+#define KLAUNCH_LDS(kern, grid, block, lds, st, ...)                  \
     do {                                                              \
         if (t_ev0)                                                    \
-            launch_ext(kern, grid, block, st, __VA_ARGS__);           \
+            launch_ext(kern, grid, block, lds, st, __VA_ARGS__);      \
         else                                                          \
-            kern<<<grid, block, 0, st>>>(__VA_ARGS__);                \
+            kern<<<grid, block, lds, st>>>(__VA_ARGS__);              \
     } while (0)
+#define KLAUNCH(kern, grid, block, st, ...) KLAUNCH_LDS(kern, grid, block, 0u, st, __VA_ARGS__)
 
 // Calls f with std::true_type or std::false_type: turns a run-time choice into a template argument.
 template <typename F>
@@ -325,6 +349,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     h->tb.block_piece0 = d_bp;
     h->tb.scale_list = d_sl;
     h->tb.n_scale_list = n_scale_list;
+    h->has_split_tiles = (size_t)piece_hi.size() > (size_t)n_tiles;
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
     h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
@@ -374,13 +399,13 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
-            KLAUNCH((bs_pass<false, kBsNaive, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales,
+            KLAUNCH_LDS((bs_pass<false, kBsNaive, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales,
                     h->signs, h->partial);
         else if (h->pending)
-            KLAUNCH((bs_pass<true, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<true, kBsEf, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
         else
-            KLAUNCH((bs_pass<false, kBsEf, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<false, kBsEf, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
     });
     if (!h->fused_scale && tb.n_scale_list > 0)
@@ -415,10 +440,10 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     const dim3 grid((unsigned)(h->ld / kTile), h->n);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            KLAUNCH((bs_pass<true, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<true, kBsCd, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
         else
-            KLAUNCH((bs_pass<false, kBsCd, G>), grid, kThreads, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<false, kBsCd, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
     });
     // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
