@@ -42,6 +42,7 @@ struct comp_ams {
     int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
     unsigned pass_lds = 0;                         // dynamic LDS of bs_pass (see pass_lds_bytes)
     bool has_split_tiles = false;                  // some tile holds several pieces
+    bool mostly_split_tiles = false;               // more than one tile in eight does
     uint64_t rand_seed = 0;                    // Rand-k: the generator's seed and the number of the next draw
     uint32_t draw = 0;
     std::string err;
@@ -109,22 +110,25 @@ inline bool state_exceeds_caches(const comp_ams *h)
     const size_t arrays = h->method == COMP_AMS_METHOD_CD ? 6 : 4;
     return arrays * (size_t)h->ld * sizeof(float) > kCacheResidentBytes;
 }
-// Dynamic LDS of bs_pass.  Tiles of several pieces need kPassTileLds, and such tables get exactly that: their tiles
-// pass through barriers, and more workgroups per compute unit hide those (n = 16, d = 11.2 M, blocks of 256:
-// pass 0.37 ms at 24 KB, 0.43 at 32 KB, 0.51 at 40 KB).  For tables of whole tiles the amount is a knob that sets
+// Dynamic LDS of bs_pass.  Tiles of several pieces need kPassTileLds.  Beyond that the amount is a knob that sets
 // how many workgroups share a compute unit, and the pass responds to it by a few per cent (one session, same
-// build): once the rows are well beyond the caches, 40 KB - four workgroups per unit - measured best over n = 4
-// to 64 and d = 11 M to 110 M (n = 32, d = 25.6 M: 1.63 ms, against 1.70 ms at 16 KB and 1.77 ms at 64 KB); below
-// about a GiB of rows up to 16 KB is best (n = 16, d = 1.2 M: 36.4 us, against 37.7 at 24 KB and 42.1 at 40 KB;
-// n = 8, d = 11.2 M: 177 against 184 us).  CAMS_PASS_LDS in the environment overrides the amount, for such sweeps.
+// build).  Where most tiles are whole (blocks of a tile, or layers): once the rows are well beyond the caches,
+// 40 KB - three workgroups per unit - measured best over n = 4 to 64 and d = 11 M to 110 M (n = 32, d = 25.6 M:
+// 1.63 ms, against 1.70 ms at 16 KB, 1.65 ms at 32 KB and 1.77 ms at 64 KB; CD-Adam's worker stage on the same
+// workload: 1.63 ms at 32 KB, 1.65 ms at 24 and at 40 KB); below about a GiB of rows up to 16 KB is best (n = 16,
+// d = 1.2 M: 36.4 us, against 37.7 at 24 KB and 42.1 at 40 KB; n = 8, d = 11.2 M: 177 against 184 us).  Where many
+// tiles hold several pieces (short blocks) they pass through barriers, more workgroups per unit hide those, and
+// the table gets just what it needs (n = 16, d = 11.2 M, blocks of 256: 0.37 ms at 24 KB, 0.43 at 32 KB, 0.51 at
+// 40 KB).  CAMS_PASS_LDS in the environment overrides the amount, for such sweeps.
 inline unsigned pass_lds_bytes(const comp_ams *h)
 {
     const unsigned need = h->has_split_tiles ? kPassTileLds : 0u;
     static const char *env = getenv("CAMS_PASS_LDS");
     if (env) return std::max(need, (unsigned)atoi(env));
-    if (need) return need;
+    if (h->mostly_split_tiles) return need;
     const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
-    return far_beyond_caches ? 40u * 1024u : 16u * 1024u;
+    const unsigned large = h->method == COMP_AMS_METHOD_CD ? 32u * 1024u : 40u * 1024u;
+    return std::max(need, far_beyond_caches ? large : 16u * 1024u);
 }
 
 // Applies the caller's choices (comp_ams_set_streaming; -1 = by size) to the kernel parameters.
@@ -350,6 +354,9 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     h->tb.scale_list = d_sl;
     h->tb.n_scale_list = n_scale_list;
     h->has_split_tiles = (size_t)piece_hi.size() > (size_t)n_tiles;
+    int64_t split = 0;
+    for (int64_t t = 0; t < n_tiles; ++t) split += tile_piece0[t + 1] - tile_piece0[t] > 1;
+    h->mostly_split_tiles = split * 8 > n_tiles;
     h->tb.n_blocks = nb;
     h->tb.n_pieces = (int32_t)piece_hi.size();
     h->tb.uniform_tiles = (uniform_len > 0 && uniform_len % kTile == 0) ? (int32_t)(uniform_len / kTile) : 0;
