@@ -107,6 +107,15 @@ int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
 int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
 
 /*
+ * Order in which the workgroups of the streaming pass take the 4096-coordinate tiles of a row, a tuning
+ * aid (no effect on results).  The chip hands workgroups to its eight XCDs in turn; with chunk > 0
+ * every XCD works through `chunk` consecutive tiles of each group of 8 * chunk tiles, with chunk = 0
+ * consecutive tiles go to consecutive XCDs, -1 = chosen from the sizes (the default: 16 when the
+ * stored rows exceed 1 GiB in total, else 0).  chunk <= 65536.  May be called between steps.
+ */
+int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
+
+/*
  * Rand-k (Appendix A, "Rand-k") only, before the first step: the seed of the draws and the number of
  * the next draw (default 0, 0; a resumed run passes the number of steps already taken).  The paper
  * leaves the drawing of S open.  Here coordinate j of the vector `who` (worker i: who = i; the

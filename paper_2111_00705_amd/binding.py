@@ -32,7 +32,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
-    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_message_bytes", "comp_ams_pack_message",
+    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_set_tile_order", "comp_ams_message_bytes", "comp_ams_pack_message",
 ]
 
 
@@ -66,6 +66,7 @@ def lib():
         L.comp_ams_set_eps_mode.argtypes = [vp, C.c_int32]
         L.comp_ams_set_rand.argtypes = [vp, C.c_uint64, C.c_uint32]
         L.comp_ams_set_streaming.argtypes = [vp, C.c_int32, C.c_int32]
+        L.comp_ams_set_tile_order.argtypes = [vp, C.c_int32]
         L.comp_ams_message_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
         L.comp_ams_pack_message.argtypes = [vp, C.c_int32, vp, C.c_uint64, C.POINTER(C.c_uint64)]
         L.comp_ams_step.argtypes = [vp, fp, vp]
@@ -176,6 +177,10 @@ class CompAms:
     def set_streaming(self, rows=-1, state=-1):
         """Cache policy of the stored rows and of theta, m, v, vhat: 1 streamed, 0 cached, -1 automatic."""
         self._check(lib().comp_ams_set_streaming(self._h, rows, state))
+
+    def set_tile_order(self, chunk=-1):
+        """Tiles per XCD and group in the streaming pass: 0 plain order, -1 automatic."""
+        self._check(lib().comp_ams_set_tile_order(self._h, chunk))
 
     def set_rand(self, seed, draw=0):
         """Rand-k: seed of the draws and number of the next draw (before the first step)."""

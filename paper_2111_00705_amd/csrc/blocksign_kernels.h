@@ -55,6 +55,7 @@ struct BsTable {
     int32_t stream_rows;         // the stored rows are too large to stay cached between steps: bs_pass loads them as a stream
     const int32_t *scale_list;   // [n_scale_list] the blocks whose scale bs_scale forms from the piece sums: all but
     int32_t n_scale_list;        // those that lie inside one tile next to other pieces (bs_pass writes their scale)
+    int32_t xcd_chunk;           // bs_pass: tile_of_block's chunk
 };
 
 // Sign bits: per worker, per tile, one 16-bit word per thread of the workgroup.  Bit r*4 + c of
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(kThreads) void bs_pass(const G *__restrict__ g, flo
     float *absx = reinterpret_cast<float *>(pass_lds);
     uint16_t *bound = reinterpret_cast<uint16_t *>(pass_lds + kTile * sizeof(float));
     const float *s_prev = scales;
-    const int t = blockIdx.x;
+    const int t = tile_of_block(blockIdx.x, tb.xcd_chunk);
+    if (t >= (int)(ld / kTile)) return;
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)t * kTile;

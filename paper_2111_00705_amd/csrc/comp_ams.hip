@@ -40,6 +40,7 @@ struct comp_ams {
     hipStream_t stream = nullptr;
     uint64_t steps = 0;
     int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
+    int32_t chunk_choice = -1;                     // comp_ams_set_tile_order: -1 by size
     unsigned pass_lds = 0;                         // dynamic LDS of bs_pass (see pass_lds_bytes)
     bool has_split_tiles = false;                  // some tile holds several pieces
     bool mostly_split_tiles = false;               // more than one tile in eight does
@@ -119,16 +120,33 @@ inline bool state_exceeds_caches(const comp_ams *h)
 // d = 1.2 M: 36.4 us, against 37.7 at 24 KB and 42.1 at 40 KB; n = 8, d = 11.2 M: 177 against 184 us).  Where many
 // tiles hold several pieces (short blocks) they pass through barriers, more workgroups per unit hide those, and
 // the table gets just what it needs (n = 16, d = 11.2 M, blocks of 256: 0.37 ms at 24 KB, 0.43 at 32 KB, 0.51 at
-// 40 KB).  CAMS_PASS_LDS in the environment overrides the amount, for such sweeps.
+// 40 KB).  The block-to-tile mapping below does not move these optima.
 inline unsigned pass_lds_bytes(const comp_ams *h)
 {
     const unsigned need = h->has_split_tiles ? kPassTileLds : 0u;
-    static const char *env = getenv("CAMS_PASS_LDS");
-    if (env) return std::max(need, (unsigned)atoi(env));
     if (h->mostly_split_tiles) return need;
     const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
     const unsigned large = h->method == COMP_AMS_METHOD_CD ? 32u * 1024u : 40u * 1024u;
     return std::max(need, far_beyond_caches ? large : 16u * 1024u);
+}
+
+// The streaming passes' block-to-tile mapping (tile_of_block).  Measured with rows far beyond the caches (one
+// session; n = 32, d = 25.6 M block sign and n = 8, d = 110 M Top-k): chunks of 16 tiles - each XCD takes 256 KB of
+// every 2 MB in turn - make the pass 3 % faster (1.60 -> 1.55 ms, 1.72 -> 1.67 ms), 8 tiles 1.5-2.5 %, 32 tiles
+// 1-2 %, 12 and 24 tiles nothing, one eighth of the row per XCD 1.3 %, 512 tiles are 3-15 % slower.  Rows of
+// 715 MB (n = 16, d = 11.2 M) gain nothing (+-1 %), rows that stay cached lose 4-20 % (the few tiles of a short
+// row then also fall on few XCDs), and the kernels with one workgroup per tile (the updates) do not respond.
+inline int xcd_chunk_for(const comp_ams *h)
+{
+    return (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30) ? 16 : 0;
+}
+
+// Grid of a kernel with one workgroup per tile (in x) under tile_of_block's mapping.
+inline unsigned grid_blocks(int64_t n_tiles, int chunk)
+{
+    if (chunk <= 0) return (unsigned)n_tiles;
+    const int64_t span = 8 * (int64_t)chunk;
+    return (unsigned)((n_tiles + span - 1) / span * span);
 }
 
 // Applies the caller's choices (comp_ams_set_streaming; -1 = by size) to the kernel parameters.
@@ -138,6 +156,8 @@ inline void apply_streaming(comp_ams *h)
     h->tb.stream_rows = rows;
     h->ge.stream_rows = rows;
     h->pass_lds = pass_lds_bytes(h);
+    h->tb.xcd_chunk = h->ge.xcd_chunk = h->chunk_choice < 0 ? xcd_chunk_for(h) : h->chunk_choice;
+    h->srv.ge.xcd_chunk = 0;   // the server's single vector: not measured, left alone
     // the state stays cached if it fits - except under error feedback with cached rows, where it would
     // compete with them (CD-Adam with cached rows measured the other way: 55.9 against 58.0 us per step with
     // 1.2 M coordinates; methods without memory do not touch the rows at all)
@@ -403,7 +423,8 @@ template <typename G>
 int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
-    const dim3 grid((unsigned)(h->ld / kTile), h->n);
+    const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n);
+    const unsigned ugrid = (unsigned)(h->ld / kTile);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
             KLAUNCH_LDS((bs_pass<false, kBsNaive, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales,
@@ -422,10 +443,10 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
     launch_timed(h, P_BS_UPDATE, st, [&] {
         // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
         // workgroups per compute unit
-        const bool early = grid.x < 2048;
+        const bool early = h->ld / kTile < 2048;
 #define CAMS_BS_UPDATE(F, E)                                                                                  \
     by_flag(h->params.stream_state, [&](auto ss) {                                                            \
-        KLAUNCH((bs_update<F, E, false, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld, h->n, tb,   \
+        KLAUNCH((bs_update<F, E, false, decltype(ss)::value>), ugrid, kThreads, st, h->d, h->ld, h->n, tb,   \
                 h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{});       \
     })
         if (h->fused_scale) {
@@ -444,7 +465,8 @@ template <typename G>
 int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
-    const dim3 grid((unsigned)(h->ld / kTile), h->n);
+    const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n);
+    const unsigned ugrid = (unsigned)(h->ld / kTile);
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
             KLAUNCH_LDS((bs_pass<true, kBsCd, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
@@ -464,12 +486,12 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
         const BsMarkov mk{h->ghat_srv, h->gtil, h->signs_srv, h->partial_srv, h->scales_srv, whole ? 1 : 0};
         if (whole)
             by_flag(h->params.stream_state, [&](auto ss) {
-                KLAUNCH((bs_update<true, false, true, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld,
+                KLAUNCH((bs_update<true, false, true, decltype(ss)::value>), ugrid, kThreads, st, h->d, h->ld,
                         h->n, tb, h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, mk);
             });
         else
             by_flag(h->params.stream_state, [&](auto ss) {
-                KLAUNCH((bs_update<false, false, true, decltype(ss)::value>), grid.x, kThreads, st, h->d, h->ld,
+                KLAUNCH((bs_update<false, false, true, decltype(ss)::value>), ugrid, kThreads, st, h->d, h->ld,
                         h->n, tb, h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, mk);
             });
     });
@@ -480,7 +502,7 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
             });
         launch_timed(h, P_BS_APPLY, st, [&] {
             by_flag(h->params.stream_state, [&](auto ss) {
-                KLAUNCH((bs_apply<decltype(ss)::value>), grid.x, kThreads, st, h->d, tb, h->scales_srv,
+                KLAUNCH((bs_apply<decltype(ss)::value>), ugrid, kThreads, st, h->d, tb, h->scales_srv,
                         h->signs_srv, h->gtil, h->theta, h->m, h->v, h->vhat, h->params);
             });
         });
@@ -528,7 +550,7 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassEf, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
@@ -548,7 +570,7 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand,
+        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand,
                 h->cursor,
                                                                           h->tile_dir);
     });
@@ -583,7 +605,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassCd, G>), dim3(ge.n_tiles, h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
@@ -593,7 +615,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
-        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(ge.n_tiles, 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws,
+        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(grid_blocks(ge.n_tiles, sv.ge.xcd_chunk), 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws,
                 sv.cand,
                                                                       sv.cursor, sv.tile_dir);
     });
@@ -885,6 +907,15 @@ int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state)
         return fail(h, COMP_AMS_EINVAL, "streaming choices are -1 (automatic), 0 (cached) or 1 (streamed)");
     h->rows_choice = rows;
     h->state_choice = state;
+    apply_streaming(h);
+    return COMP_AMS_OK;
+}
+
+int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    if (chunk < -1 || chunk > 65536) return fail(h, COMP_AMS_EINVAL, "chunk is -1 (automatic) or 0 .. 65536 tiles");
+    h->chunk_choice = chunk;
     apply_streaming(h);
     return COMP_AMS_OK;
 }

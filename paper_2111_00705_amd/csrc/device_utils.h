@@ -7,6 +7,18 @@
 
 namespace cams {
 
+// Which tile a workgroup works on.  The hardware hands the workgroups of a launch to the chip's eight XCDs in
+// turn (linear workgroup id modulo 8), so with tile = block id every XCD walks over every page of a row.  With
+// chunk > 0 the blocks are taken in groups of 8 * chunk, and inside a group XCD x works through the contiguous
+// tiles [x * chunk, (x + 1) * chunk) of the group.  Such a grid has a multiple of 8 * chunk blocks in x
+// (grid_blocks); blocks whose tile is past the last one leave at once.  chunk = 0: tile = block id.
+__device__ __forceinline__ int tile_of_block(unsigned b, int chunk)
+{
+    if (chunk <= 0) return (int)b;
+    const unsigned span = 8u * (unsigned)chunk, within = b % span;
+    return (int)(b - within + (within & 7u) * (unsigned)chunk + (within >> 3));
+}
+
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kThreads = 256;      // workgroup size of every streaming kernel (4 waves)
 constexpr int kTile = 4096;        // coordinates per tile; rows of library-owned arrays are padded to it

@@ -105,6 +105,7 @@ struct TkGeom {
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
     int32_t stream_rows;    // the stored rows are too large to stay cached between steps: tk_pass1 loads them as a stream
+    int32_t xcd_chunk;      // tk_pass1: tile_of_block's chunk
     TkRand rand;
 };
 
@@ -413,7 +414,8 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
 {
     __shared__ uint2 stage[4][kSub];
     __shared__ uint32_t sh[9];
-    const int t = blockIdx.x;
+    const int t = tile_of_block(blockIdx.x, ge.xcd_chunk);
+    if (t >= ge.n_tiles) return;
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;

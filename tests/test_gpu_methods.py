@@ -280,6 +280,47 @@ def test_the_cache_policy_does_not_change_results(comp, kb, method):
     h.destroy()
 
 
+@pytest.mark.parametrize("comp,kb", [(P.TOPK, 3000), (P.RANDK, 3000), (P.BLOCKSIGN, 1000), (P.BLOCKSIGN, 4096)])
+@pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_CD, P.METHOD_NAIVE])
+def test_the_tile_order_does_not_change_results(comp, kb, method):
+    """comp_ams_set_tile_order only permutes which workgroup takes which tile: chunks that divide the
+    tile count, that do not, that exceed it, and a switch between steps must leave bit-identical state.
+    d = 300 007 is 74 tiles, the last one ragged."""
+    import torch
+    announce(f"tile order comp={comp} kb={kb} method={method}")
+    d, n = 300_007, 3
+    gs = [np.random.default_rng([78, t]).standard_normal((n, d)).astype(f32) for t in range(3)]
+    ref = None
+    for chunk in (0, 1, 2, 3, 5, 16, 37, 100, -1):
+        h = P.CompAms(d, n, comp, kb)
+        h.set_method(method)
+        h.set_tile_order(chunk)
+        for t, g in enumerate(gs):
+            if t == 2:
+                h.set_tile_order(7 if chunk else 4)          # changed between steps
+            h.step(torch.from_numpy(g).cuda())
+        out = [bits(h.get_theta()), bits(h.get_m()), bits(h.get_v()), bits(h.get_vhat())]
+        if method == P.METHOD_EF:
+            out += [bits(h.get_error(i)) for i in range(n)]
+        elif method == P.METHOD_CD:
+            out += [bits(h.get_ghat_worker(i)) for i in range(n)]
+        if comp != P.BLOCKSIGN:
+            out += [np.sort(h.get_selected(i)[0]) for i in range(n)]
+        else:
+            out += [bits(h.get_scales())]
+        h.destroy()
+        if ref is None:
+            ref = out
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(ref, out)), chunk
+    h = P.CompAms(64, 1, comp, 8)
+    with pytest.raises(P.CompAmsError):
+        h.set_tile_order(-2)
+    with pytest.raises(P.CompAmsError):
+        h.set_tile_order(65537)
+    h.destroy()
+
+
 @pytest.mark.parametrize("count", [4, 1020, 4096, 4100, 1 << 20, (1 << 20) + 12])
 def test_probe_copy_copies_exactly_what_it_is_given(count):
     """The plain copy that calibrates the HBM counters: dst == src, nothing written past the end."""
