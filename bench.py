@@ -32,16 +32,16 @@ MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
     ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 235.2e6,
     ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.5e6,
     ("cfg2_topk_n16_d11173962", "tk_pass1"): 2178.7e6,
-    ("cfg2_topk_n16_d11173962", "tk_final"): 389.2e6,
+    ("cfg2_topk_n16_d11173962", "tk_final"): 388.0e6,
     ("cfg3_layersign_n32_d25557032", "bs_pass"): 9931.6e6,
     ("cfg3_layersign_n32_d25557032", "bs_update"): 921.5e6,
     ("cfg4_topk_n8_d110000000", "tk_pass1"): 10598.7e6,
-    ("cfg4_topk_n8_d110000000", "tk_final"): 3574.5e6,
+    ("cfg4_topk_n8_d110000000", "tk_final"): 3226.5e6,
     ("cfg1_blocksign4096_n16_d1199882/cd", "bs_pass"): 237.4e6,
     ("cfg1_blocksign4096_n16_d1199882/cd", "bs_server"): 60.9e6,
     ("cfg2_topk_n16_d11173962/cd", "tk_pass1"): 1474.0e6,
-    ("cfg2_topk_n16_d11173962/cd", "tk_merge"): 383.5e6,
-    ("cfg2_topk_n16_d11173962/cd", "tk_apply"): 449.9e6,
+    ("cfg2_topk_n16_d11173962/cd", "tk_merge"): 382.3e6,
+    ("cfg2_topk_n16_d11173962/cd", "tk_apply"): 417.5e6,
     ("cfg3_layersign_n32_d25557032/cd", "bs_pass"): 10035.3e6,
     ("cfg3_layersign_n32_d25557032/cd", "bs_apply"): 1026.6e6,
 }

@@ -206,6 +206,21 @@ __device__ __forceinline__ void st4_state(float *p, const float4 &v)
     if constexpr (kStream) st4_stream(p, v); else st4(p, v);
 }
 
+// st4_state (kStream) or st4, unless the location already holds v: `old` is what this thread loaded from p.  Skipping such a
+// store leaves memory as it is, so results are the same bit for bit.  Lanes that share a line of kLineLanes * 16
+// bytes decide together, so that a line is written whole or not at all.  All lanes of the wavefront must call
+// this together (it uses a ballot).
+constexpr int kLineLanes = 8;
+template <bool kStream>
+__device__ __forceinline__ void st4_if_changed(float *p, const float4 &v, const float4 &old)
+{
+    const bool changed = __float_as_uint(v.x) != __float_as_uint(old.x) || __float_as_uint(v.y) != __float_as_uint(old.y) ||
+                         __float_as_uint(v.z) != __float_as_uint(old.z) || __float_as_uint(v.w) != __float_as_uint(old.w);
+    const uint64_t b = __ballot(changed);
+    const int lane = threadIdx.x & (kWave - 1);
+    if ((b >> (lane & ~(kLineLanes - 1))) & ((1ull << kLineLanes) - 1ull)) st4_state<kStream>(p, v);
+}
+
 __device__ __forceinline__ uint32_t mag_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
 
 // Sum over the 64 lanes with a fixed butterfly; every lane receives the same result, and the

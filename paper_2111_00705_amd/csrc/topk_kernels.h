@@ -1162,11 +1162,13 @@ __global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *
         const float4 a = ld4(acc + l);
         const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
                                         fdiv(a.w, p.n_workers));
+        const float4 vh0 = vh[r];
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
         st4_state<kStreamState>(theta + j, th[r]);
         st4_state<kStreamState>(m + j, mm[r]);
         st4_state<kStreamState>(v + j, vv[r]);
-        st4_state<kStreamState>(vhat + j, vh[r]);
+        // with a sparse average vhat = max(vhat, v) moves at few coordinates (v only decays elsewhere)
+        st4_if_changed<kStreamState>(vhat + j, vh[r], vh0);
     }
 }
 
@@ -1200,9 +1202,10 @@ __global__ __launch_bounds__(kThreads) void tk_merge(TkGeom ge, const TkWorker *
     for (int r = 0; r < 4; ++r) {
         const int l = 4 * (tid + kThreads * r);
         const float4 a = ld4(acc + l), gh = ld4(ghat + base + l);
-        // padding coordinates: 0 + 0 / n
-        st4(ghat + base + l, make_float4(fadd(gh.x, fdiv(a.x, n_workers)), fadd(gh.y, fdiv(a.y, n_workers)),
-                                         fadd(gh.z, fdiv(a.z, n_workers)), fadd(gh.w, fdiv(a.w, n_workers))));
+        // padding coordinates: 0 + 0 / n; ghat moves only where some worker kept a coordinate
+        st4_if_changed<false>(ghat + base + l,
+                              make_float4(fadd(gh.x, fdiv(a.x, n_workers)), fadd(gh.y, fdiv(a.y, n_workers)),
+                                          fadd(gh.z, fdiv(a.z, n_workers)), fadd(gh.w, fdiv(a.w, n_workers))), gh);
     }
 }
 
@@ -1255,7 +1258,7 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
         const float4 g4 = make_float4(fadd(gt[r].x, c4.x), fadd(gt[r].y, c4.y), fadd(gt[r].z, c4.z),
                                       fadd(gt[r].w, c4.w));
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], g4, p);
-        st4(gtil + j, g4);
+        st4_if_changed<false>(gtil + j, g4, gt[r]);      // gtilde moves at the k kept coordinates only
         st4_state<kStreamState>(theta + j, th[r]);
         st4_state<kStreamState>(m + j, mm[r]);
         st4_state<kStreamState>(v + j, vv[r]);
