@@ -41,7 +41,7 @@ struct comp_ams {
     uint64_t steps = 0;
     int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
     int32_t chunk_choice = -1;                     // comp_ams_set_tile_order: -1 by size
-    unsigned pass_lds = 0;                         // dynamic LDS of bs_pass (see pass_lds_bytes)
+    unsigned pass_lds = 0, pass_lds16 = 0;         // dynamic LDS of bs_pass for gradients of 32 / 16 bits (see pass_lds_bytes)
     bool has_split_tiles = false;                  // some tile holds several pieces
     bool mostly_split_tiles = false;               // more than one tile in eight does
     uint64_t rand_seed = 0;                    // Rand-k: the generator's seed and the number of the next draw
@@ -120,11 +120,14 @@ inline bool state_exceeds_caches(const comp_ams *h)
 // d = 1.2 M: 36.4 us, against 37.7 at 24 KB and 42.1 at 40 KB; n = 8, d = 11.2 M: 177 against 184 us).  Where many
 // tiles hold several pieces (short blocks) they pass through barriers, more workgroups per unit hide those, and
 // the table gets just what it needs (n = 16, d = 11.2 M, blocks of 256: 0.37 ms at 24 KB, 0.43 at 32 KB, 0.51 at
-// 40 KB).  The block-to-tile mapping below does not move these optima.
-inline unsigned pass_lds_bytes(const comp_ams *h)
+// 40 KB).  The block-to-tile mapping below does not move these optima.  Gradients of 16 bits are another matter:
+// that pass issues more instructions per byte and wants the workgroups (n = 32, d = 25.6 M, bfloat16 or half:
+// 1.32 ms up to 24 KB, 1.54 ms at 32 KB, 1.83 ms at 40 KB), so it never gets more than 16 KB beyond its need.
+inline unsigned pass_lds_bytes(const comp_ams *h, bool grads16)
 {
     const unsigned need = h->has_split_tiles ? kPassTileLds : 0u;
     if (h->mostly_split_tiles) return need;
+    if (grads16) return std::max(need, 16u * 1024u);
     const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
     const unsigned large = h->method == COMP_AMS_METHOD_CD ? 32u * 1024u : 40u * 1024u;
     return std::max(need, far_beyond_caches ? large : 16u * 1024u);
@@ -155,7 +158,8 @@ inline void apply_streaming(comp_ams *h)
     const int rows = h->rows_choice < 0 ? (rows_exceed_caches(h) ? 1 : 0) : h->rows_choice;
     h->tb.stream_rows = rows;
     h->ge.stream_rows = rows;
-    h->pass_lds = pass_lds_bytes(h);
+    h->pass_lds = pass_lds_bytes(h, false);
+    h->pass_lds16 = pass_lds_bytes(h, true);
     h->tb.xcd_chunk = h->ge.xcd_chunk = h->chunk_choice < 0 ? xcd_chunk_for(h) : h->chunk_choice;
     h->srv.ge.xcd_chunk = 0;   // the server's single vector: not measured, left alone
     // the state stays cached if it fits - except under error feedback with cached rows, where it would
@@ -425,15 +429,16 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
     const BsTable &tb = h->tb;
     const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n);
     const unsigned ugrid = (unsigned)(h->ld / kTile);
+    const unsigned lds = sizeof(G) == 2 ? h->pass_lds16 : h->pass_lds;
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
-            KLAUNCH_LDS((bs_pass<false, kBsNaive, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales,
+            KLAUNCH_LDS((bs_pass<false, kBsNaive, G>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, tb, h->scales,
                     h->signs, h->partial);
         else if (h->pending)
-            KLAUNCH_LDS((bs_pass<true, kBsEf, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<true, kBsEf, G>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
         else
-            KLAUNCH_LDS((bs_pass<false, kBsEf, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<false, kBsEf, G>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
     });
     if (!h->fused_scale && tb.n_scale_list > 0)
@@ -467,12 +472,13 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     const BsTable &tb = h->tb;
     const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n);
     const unsigned ugrid = (unsigned)(h->ld / kTile);
+    const unsigned lds = sizeof(G) == 2 ? h->pass_lds16 : h->pass_lds;
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->pending)
-            KLAUNCH_LDS((bs_pass<true, kBsCd, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<true, kBsCd, G>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
         else
-            KLAUNCH_LDS((bs_pass<false, kBsCd, G>), grid, kThreads, h->pass_lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
+            KLAUNCH_LDS((bs_pass<false, kBsCd, G>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, tb, h->scales, h->signs,
                     h->partial);
     });
     // every tile exactly one block (uniform blocks of one tile): the worker scales and the server's own
