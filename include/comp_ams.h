@@ -111,9 +111,19 @@ int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
  * aid (no effect on results).  The chip hands workgroups to its eight XCDs in turn; with chunk > 0
  * every XCD works through `chunk` consecutive tiles of each group of 8 * chunk tiles, with chunk = 0
  * consecutive tiles go to consecutive XCDs, -1 = chosen from the sizes (the default: 16 when the
- * stored rows exceed 1 GiB in total, else 0).  chunk <= 65536.  May be called between steps.
+ * stored rows exceed 1 GiB in total and the method keeps them - error feedback, CD-Adam - except for
+ * Top-k / Rand-k steps on 16-bit gradients; else 0).  chunk <= 65536.  May be called between steps.
  */
 int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
+
+/*
+ * Bytes of LDS a workgroup of the block-sign streaming pass reserves, a tuning aid (no effect on
+ * results): the amount decides how many workgroups share a compute unit (160 KB each), to which the pass
+ * responds by a few per cent.  -1 = chosen from the sizes, the method and the gradient type (the
+ * default), else 0 .. 61440; the pass always gets at least what its block table needs (24 KB when a
+ * tile holds several blocks' pieces).  No effect on TOPK / RANDK handles.  May be called between steps.
+ */
+int comp_ams_set_pass_lds(comp_ams_t *h, int32_t bytes);
 
 /*
  * Rand-k (Appendix A, "Rand-k") only, before the first step: the seed of the draws and the number of

@@ -32,7 +32,7 @@ EXPORTS = [
     "comp_ams_profile_read", "comp_ams_probe_copy", "comp_ams_get_selection_info",
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
-    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_set_tile_order", "comp_ams_message_bytes", "comp_ams_pack_message",
+    "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_set_tile_order", "comp_ams_set_pass_lds", "comp_ams_message_bytes", "comp_ams_pack_message",
 ]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.comp_ams_set_rand.argtypes = [vp, C.c_uint64, C.c_uint32]
         L.comp_ams_set_streaming.argtypes = [vp, C.c_int32, C.c_int32]
         L.comp_ams_set_tile_order.argtypes = [vp, C.c_int32]
+        L.comp_ams_set_pass_lds.argtypes = [vp, C.c_int32]
         L.comp_ams_message_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
         L.comp_ams_pack_message.argtypes = [vp, C.c_int32, vp, C.c_uint64, C.POINTER(C.c_uint64)]
         L.comp_ams_step.argtypes = [vp, fp, vp]
@@ -181,6 +182,10 @@ class CompAms:
     def set_tile_order(self, chunk=-1):
         """Tiles per XCD and group in the streaming pass: 0 plain order, -1 automatic."""
         self._check(lib().comp_ams_set_tile_order(self._h, chunk))
+
+    def set_pass_lds(self, nbytes=-1):
+        """LDS bytes per workgroup of the block-sign pass (sets workgroups per compute unit): -1 automatic."""
+        self._check(lib().comp_ams_set_pass_lds(self._h, nbytes))
 
     def set_rand(self, seed, draw=0):
         """Rand-k: seed of the draws and number of the next draw (before the first step)."""

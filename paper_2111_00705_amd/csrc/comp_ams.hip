@@ -41,6 +41,7 @@ struct comp_ams {
     uint64_t steps = 0;
     int32_t rows_choice = -1, state_choice = -1;   // comp_ams_set_streaming: -1 by size, 0 cached, 1 streamed
     int32_t chunk_choice = -1;                     // comp_ams_set_tile_order: -1 by size
+    int32_t lds_choice = -1;                       // comp_ams_set_pass_lds: -1 by size, method and gradient type
     unsigned pass_lds = 0, pass_lds16 = 0;         // dynamic LDS of bs_pass for gradients of 32 / 16 bits (see pass_lds_bytes)
     bool has_split_tiles = false;                  // some tile holds several pieces
     bool mostly_split_tiles = false;               // more than one tile in eight does
@@ -126,10 +127,14 @@ inline bool state_exceeds_caches(const comp_ams *h)
 inline unsigned pass_lds_bytes(const comp_ams *h, bool grads16)
 {
     const unsigned need = h->has_split_tiles ? kPassTileLds : 0u;
+    if (h->lds_choice >= 0) return std::max(need, (unsigned)h->lds_choice);
     if (h->mostly_split_tiles) return need;
     if (grads16) return std::max(need, 16u * 1024u);
     const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
-    const unsigned large = h->method == COMP_AMS_METHOD_CD ? 32u * 1024u : 40u * 1024u;
+    // naive compression reads g only and wants the workgroups as well (n = 32, d = 25.6 M: 0.55 ms up to 24 KB,
+    // 0.66 ms at 32 KB, 0.78 ms at 40 KB)
+    const unsigned large = h->method == COMP_AMS_METHOD_EF ? 40u * 1024u
+                           : h->method == COMP_AMS_METHOD_CD ? 32u * 1024u : 16u * 1024u;
     return std::max(need, far_beyond_caches ? large : 16u * 1024u);
 }
 
@@ -139,8 +144,11 @@ inline unsigned pass_lds_bytes(const comp_ams *h, bool grads16)
 // 1-2 %, 12 and 24 tiles nothing, one eighth of the row per XCD 1.3 %, 512 tiles are 3-15 % slower.  Rows of
 // 715 MB (n = 16, d = 11.2 M) gain nothing (+-1 %), rows that stay cached lose 4-20 % (the few tiles of a short
 // row then also fall on few XCDs), and the kernels with one workgroup per tile (the updates) do not respond.
+// CD-Adam's passes gain 0.5-2 %; naive compression (g only) gains nothing or loses 0.5-3 %, and so does the
+// Top-k pass with 16-bit gradients (block sign with 16-bit gradients gains 2 %): those keep the plain order.
 inline int xcd_chunk_for(const comp_ams *h)
 {
+    if (h->method != COMP_AMS_METHOD_EF && h->method != COMP_AMS_METHOD_CD) return 0;
     return (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30) ? 16 : 0;
 }
 
@@ -167,6 +175,16 @@ inline void apply_streaming(comp_ams *h)
     // 1.2 M coordinates; methods without memory do not touch the rows at all)
     const bool rows_cached = rows == 0 && h->method == COMP_AMS_METHOD_EF;
     h->params.stream_state = h->state_choice < 0 ? ((state_exceeds_caches(h) || rows_cached) ? 1 : 0) : h->state_choice;
+}
+
+// Geometry handed to tk_pass1 for gradients of type G: the automatic tile order is the plain one for 16-bit
+// gradients (see xcd_chunk_for); a caller's choice holds for every type.
+template <typename G>
+inline TkGeom pass_geometry(const comp_ams *h)
+{
+    TkGeom ge = h->ge;
+    if (sizeof(G) == 2 && h->chunk_choice < 0) ge.xcd_chunk = 0;
+    return ge;
 }
 
 // Top-k and Rand-k share every buffer and kernel (the key differs, see SelKey).
@@ -555,8 +573,9 @@ template <typename G>
 int step_topk(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
+    const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
@@ -575,8 +594,9 @@ template <typename G>
 int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
+    const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand,
+        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand,
                 h->cursor,
                                                                           h->tile_dir);
     });
@@ -609,9 +629,10 @@ template <typename G>
 int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
+    const TkGeom pge = pass_geometry<G>(h);
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, ge.xcd_chunk), h->n), kThreads, st, g, h->e, ge, h->ws, h->cand, h->cursor,
+        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand, h->cursor,
                                                                        h->tile_dir);
     });
     launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
@@ -922,6 +943,15 @@ int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk)
     if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
     if (chunk < -1 || chunk > 65536) return fail(h, COMP_AMS_EINVAL, "chunk is -1 (automatic) or 0 .. 65536 tiles");
     h->chunk_choice = chunk;
+    apply_streaming(h);
+    return COMP_AMS_OK;
+}
+
+int comp_ams_set_pass_lds(comp_ams_t *h, int32_t bytes)
+{
+    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+    if (bytes < -1 || bytes > 61440) return fail(h, COMP_AMS_EINVAL, "bytes is -1 (automatic) or 0 .. 61440");
+    h->lds_choice = bytes;
     apply_streaming(h);
     return COMP_AMS_OK;
 }

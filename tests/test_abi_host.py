@@ -58,6 +58,7 @@ def test_create_with_null_out_pointer_and_null_handles():
     assert L.comp_ams_set_rand(None, 1, 0) == P.EINVAL
     assert L.comp_ams_set_streaming(None, -1, -1) == P.EINVAL
     assert L.comp_ams_set_tile_order(None, -1) == P.EINVAL
+    assert L.comp_ams_set_pass_lds(None, -1) == P.EINVAL
     assert L.comp_ams_set_eps_mode(None, 1) == P.EINVAL
     L.comp_ams_destroy(None)                       # no-op
 

@@ -283,8 +283,9 @@ def test_the_cache_policy_does_not_change_results(comp, kb, method):
 @pytest.mark.parametrize("comp,kb", [(P.TOPK, 3000), (P.RANDK, 3000), (P.BLOCKSIGN, 1000), (P.BLOCKSIGN, 4096)])
 @pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_CD, P.METHOD_NAIVE])
 def test_the_tile_order_does_not_change_results(comp, kb, method):
-    """comp_ams_set_tile_order only permutes which workgroup takes which tile: chunks that divide the
-    tile count, that do not, that exceed it, and a switch between steps must leave bit-identical state.
+    """comp_ams_set_tile_order only permutes which workgroup takes which tile, comp_ams_set_pass_lds only
+    how many workgroups share a compute unit: chunks that divide the tile count, that do not, that exceed
+    it, several LDS amounts and a switch between steps must leave bit-identical state.
     d = 300 007 is 74 tiles, the last one ragged."""
     import torch
     announce(f"tile order comp={comp} kb={kb} method={method}")
@@ -295,6 +296,7 @@ def test_the_tile_order_does_not_change_results(comp, kb, method):
         h = P.CompAms(d, n, comp, kb)
         h.set_method(method)
         h.set_tile_order(chunk)
+        h.set_pass_lds({0: -1, 1: 0, 2: 8192, 3: 30000, 5: 61440}.get(chunk, -1))
         for t, g in enumerate(gs):
             if t == 2:
                 h.set_tile_order(7 if chunk else 4)          # changed between steps
@@ -318,6 +320,10 @@ def test_the_tile_order_does_not_change_results(comp, kb, method):
         h.set_tile_order(-2)
     with pytest.raises(P.CompAmsError):
         h.set_tile_order(65537)
+    with pytest.raises(P.CompAmsError):
+        h.set_pass_lds(-2)
+    with pytest.raises(P.CompAmsError):
+        h.set_pass_lds(61441)
     h.destroy()
 
 
