@@ -233,17 +233,6 @@ __device__ __forceinline__ void block_prefix(uint32_t v, uint32_t *pre, uint32_t
     __syncthreads();
 }
 
-// Largest l in [0, count) with pre[l] <= q, for a non-decreasing pre[0..count] with pre[count] > q.
-__device__ __forceinline__ int owner_of(const uint32_t *pre, int count, uint32_t q)
-{
-    int lo = 0, hi = count;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (pre[mid] <= q) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // ---------------------------------------------------------------------------------------------
 // Where candidates live.  Each worker owns ge.slices regions of the candidate array; tile t appends
 // to region t mod slices, so workgroups that run at the same time (neighbouring tiles) use different
@@ -807,11 +796,12 @@ struct ResolveLds {
 };
 
 // The digits of Tc below `prefix` (which leaves s_hi low bits of comp open), 12 bits at a time, over the
-// cnt comp values get(q), q < cnt, of which the one of 1-based rank `rank` (from the top) among those
-// that carry the prefix is wanted.  Once at most kFew elements carry the prefix they are fetched and
+// cnt comp values that fetch(q, comp) delivers kScanUnroll at a time (comp[u] = element q[u], anything for
+// q[u] >= cnt; q ascends with u), of which the one of 1-based rank `rank` (from the top) among those that
+// carry the prefix is wanted.  Once at most kFew elements carry the prefix they are fetched and
 // ranked against each other directly.  All kResolveThreads threads call this; returns Tc.
-template <class Get>
-__device__ __forceinline__ uint64_t resolve_digits(Get get, uint32_t cnt, uint64_t prefix, uint32_t rank, int s_hi,
+template <class Fetch>
+__device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, uint64_t prefix, uint32_t rank, int s_hi,
                                                    ResolveLds &L)
 {
     const int tid = threadIdx.x;
@@ -823,15 +813,14 @@ __device__ __forceinline__ uint64_t resolve_digits(Get get, uint32_t cnt, uint64
         for (int b = tid; b < kBins2; b += kResolveThreads) L.lh[b] = 0;
         __syncthreads();
         for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+            uint32_t q[kScanUnroll];
             uint64_t comp[kScanUnroll];
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u) {
-                const uint32_t q = qb + u * kResolveThreads + tid;
-                comp[u] = q < cnt ? get(q) : 0ull;          // independent loads: all in flight at once
-            }
+            for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * kResolveThreads + tid;
+            fetch(q, comp);                                 // independent loads: all in flight at once
 #pragma unroll
             for (int u = 0; u < kScanUnroll; ++u)
-                if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                if (q[u] < cnt && (comp[u] >> s_hi) == prefix)
                     atomicAdd(&L.lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
         }
         __syncthreads();
@@ -848,15 +837,14 @@ __device__ __forceinline__ uint64_t resolve_digits(Get get, uint32_t cnt, uint64
             if (tid == 0) L.n_few = 0;
             __syncthreads();
             for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+                uint32_t q[kScanUnroll];
                 uint64_t comp[kScanUnroll];
 #pragma unroll
-                for (int u = 0; u < kScanUnroll; ++u) {
-                    const uint32_t q = qb + u * kResolveThreads + tid;
-                    comp[u] = q < cnt ? get(q) : 0ull;
-                }
+                for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * kResolveThreads + tid;
+                fetch(q, comp);
 #pragma unroll
                 for (int u = 0; u < kScanUnroll; ++u)
-                    if (qb + u * kResolveThreads + tid < cnt && (comp[u] >> s_hi) == prefix)
+                    if (q[u] < cnt && (comp[u] >> s_hi) == prefix)
                         L.few[atomicAdd(&L.n_few, 1u)] = comp[u];
             }
             __syncthreads();
@@ -1012,17 +1000,36 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         if (tid == kResolveThreads - 1) rpre[pieces] = before + incl;   // threads past the pieces add 0
         __syncthreads();
         const uint32_t cnt = rpre[pieces];
-        // element q of the worker's dense set, found through the prefix sums of the piece counts
-        auto get = [&](uint32_t q) {
-            const int r = owner_of(rpre, pieces, q);
-            return wdense[rstart[r] + (q - rpre[r])];
+        // Elements q[u] of the worker's dense set, found through the prefix sums of the piece counts: the piece of
+        // q is the last one that starts at or before it.  The searches of a batch advance together, one bit of the
+        // piece number per round and without branches, so that a round's LDS reads are independent: one search
+        // after the other leaves a scan waiting on kScanUnroll chains of dependent LDS reads per batch.
+        int top = 1;
+        while (2 * top < pieces) top *= 2;
+        auto fetch = [&](const uint32_t (&q)[kScanUnroll], uint64_t (&comp)[kScanUnroll]) {
+            if (q[0] >= cnt) return;                       // nothing for this thread in the batch
+            int r[kScanUnroll];
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u) r[u] = 0;
+            for (int bit = top; bit > 0; bit >>= 1) {
+                uint32_t start[kScanUnroll];
+#pragma unroll
+                for (int u = 0; u < kScanUnroll; ++u) start[u] = rpre[min(r[u] + bit, pieces)];   // rpre[pieces] = cnt
+#pragma unroll
+                for (int u = 0; u < kScanUnroll; ++u) r[u] = (start[u] <= q[u] && r[u] + bit < pieces) ? r[u] + bit : r[u];
+            }
+            uint32_t at[kScanUnroll];
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u) at[u] = rstart[r[u]] + (q[u] - rpre[r[u]]);
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u) comp[u] = q[u] < cnt ? wdense[at[u]] : 0ull;
         };
         if (xs != nullptr && w.prefix == 0u && w.rank > cnt)
             // the threshold bin is the one of the smallest keys and the k-th largest lies below its listed
             // (non-zero) elements: among the zeros
             tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank - cnt, L);
         else
-            tc = resolve_digits(get, cnt, w.prefix, w.rank, s_hi, L);
+            tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L);
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
