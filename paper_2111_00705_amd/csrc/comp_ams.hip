@@ -1393,8 +1393,15 @@ int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, voi
         return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: count must be a positive multiple of 4 and the pointers 16-byte aligned");
     const int64_t vecs = count / 4;
     if (vecs > (int64_t)1 << 40) return fail(nullptr, COMP_AMS_EINVAL, "probe_copy: count too large");
-    const unsigned blocks = (unsigned)((vecs + 4 * kThreads - 1) / (4 * kThreads));
-    probe_copy<<<blocks, kThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(dst_dev, src_dev, vecs);
+    const int64_t pieces = (vecs + 4 * kThreads - 1) / (4 * kThreads);
+    // The launch shape a plain copy measured fastest with (1 GiB to 1 GiB, one session): two workgroups per compute
+    // unit (60 KB of LDS reserved, none used) and the XCD-aware piece order with chunks of 16 - 6.75 TB/s, against
+    // 6.0 TB/s with neither, 6.35 with the LDS alone and 5.7 with the order alone.  Small copies keep the plain shape.
+    const bool large = vecs * 16 >= ((int64_t)256 << 20);
+    const int chunk = large ? 16 : 0;
+    const unsigned lds = large ? 61440u : 0u;
+    probe_copy<<<grid_blocks(pieces, chunk), kThreads, lds, static_cast<hipStream_t>(hip_stream)>>>(dst_dev, src_dev,
+                                                                                                      vecs, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(nullptr, COMP_AMS_EDEVICE, "probe_copy launch failed: %s", hipGetErrorString(e));
     return COMP_AMS_OK;

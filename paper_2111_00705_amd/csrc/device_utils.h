@@ -246,11 +246,12 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
 
 // Plain streaming copy, 16 bytes per lane, four independent loads per thread, one 16 KB piece per
 // workgroup, non-temporal on both sides: the yardstick for the HBM counters (it moves exactly the bytes it
-// is given) and for the bandwidth a simple kernel reaches on this chip.
+// is given) and for the bandwidth a simple kernel reaches on this chip.  chunk: tile_of_block's, over the
+// pieces; blocks past the last piece do nothing.
 __global__ __launch_bounds__(kThreads) void probe_copy(float *__restrict__ dst, const float *__restrict__ src,
-                                                       int64_t vecs)
+                                                       int64_t vecs, int chunk)
 {
-    const int64_t q0 = (int64_t)blockIdx.x * (4 * kThreads) + threadIdx.x;
+    const int64_t q0 = (int64_t)tile_of_block(blockIdx.x, chunk) * (4 * kThreads) + threadIdx.x;
     float4 v[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r)

@@ -327,9 +327,11 @@ def test_the_tile_order_does_not_change_results(comp, kb, method):
     h.destroy()
 
 
-@pytest.mark.parametrize("count", [4, 1020, 4096, 4100, 1 << 20, (1 << 20) + 12])
+@pytest.mark.parametrize("count", [4, 1020, 4096, 4100, 1 << 20, (1 << 20) + 12, 64 << 20, (80 << 20) + 4100 + 12])
 def test_probe_copy_copies_exactly_what_it_is_given(count):
-    """The plain copy that calibrates the HBM counters: dst == src, nothing written past the end."""
+    """The plain copy that calibrates the HBM counters: dst == src, nothing written past the end.  From 256 MB
+    on it runs in another launch shape (chunked piece order, padded grid): the last two sizes, one a whole
+    number of chunk groups and one ragged."""
     import torch
     announce(f"probe_copy count={count}")
     src = torch.randn(count, device="cuda")
