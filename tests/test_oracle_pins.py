@@ -358,6 +358,154 @@ def test_result_does_not_depend_on_thread_count():
         assert np.array_equal(bits(a) if a.dtype == f32 else a, bits(b) if b.dtype == f32 else b)
 
 
+# ----------------------------------------------------------------------------- per-layer tables, step-size schedule
+
+def scaled_sign_by_definition(x, offsets):
+    """Appendix A's scaled sign on each block with the block's own length as divisor, written out
+    with Python floats (exact sums of fp32 values via math.fsum, one rounding to fp32)."""
+    c = np.empty_like(x)
+    s = np.empty(len(offsets) - 1, f32)
+    for b in range(len(offsets) - 1):
+        lo, hi = int(offsets[b]), int(offsets[b + 1])
+        s[b] = f32(math.fsum(abs(float(v)) for v in x[lo:hi]) / (hi - lo))
+        c[lo:hi] = np.copysign(s[b], x[lo:hi])
+    return c, s
+
+
+def test_layer_table_hand_example_in_the_stateful_optimiser():
+    """oracle_set_blocks: the table replaces the uniform blocks of create.  Hand example (Appendix A,
+    scaled sign per block): x = [1,-3 | 2,2 | -0,0 | 8] has scales 2, 2, 0, 8; under error feedback the
+    second step compresses g + e with the same table."""
+    x = np.array([[1, -3, 2, 2, -0.0, 0.0, 8]], f32)               # g + e with e = +0 turns the -0 into +0
+    o = O.Oracle(7, 1, O.BLOCKSIGN, 3, 0.9, 0.999, 1e-8, 1e-3)       # create says blocks of 3 ...
+    o.set_blocks([0, 2, 4, 6, 7])                                      # ... the table says otherwise
+    assert o.n_blocks == 4
+    o.step(x)
+    assert o.scales[0].tolist() == [2.0, 2.0, 0.0, 8.0]
+    assert np.array_equal(bits(o.compressed[0]), bits([2, -2, 2, 2, 0.0, 0.0, 8]))
+    assert np.array_equal(bits(o.error[0]), bits([-1, -1, 0, 0, 0.0, 0.0, 0]))      # x - C(x)
+    o.step(x)                                # x_2 = g + e = [0,-4 | 2,2 | 0,0 | 8]
+    assert o.scales[0].tolist() == [2.0, 2.0, 0.0, 8.0]
+    assert np.array_equal(bits(o.compressed[0]), bits([2, -2, 2, 2, 0.0, 0.0, 8]))
+    assert np.array_equal(bits(o.error[0]), bits([-2, -2, 0, 0, 0.0, 0.0, 0]))
+    o.close()
+
+
+@pytest.mark.parametrize("method", [O.EF, O.CD, O.NAIVE])
+def test_layer_table_in_every_method_matches_the_definition_per_worker_and_step(method):
+    """The stateful optimiser with a per-layer table (blocks of 1 to a few hundred coordinates, not
+    aligned to anything) against the definition written out in Python for every worker and step: the
+    compressed vector and scales are those of the block-wise scaled sign of g + e (error feedback),
+    g - ghat_i and ghat - gtilde (Algorithm 1) or g (naive); the memory follows Section 4 / Algorithm 1;
+    a table changed between steps applies from the next step on and leaves the memory as it is."""
+    rng = np.random.default_rng(23 + method)
+    n, d, T = 3, 613, 6
+    tables = [np.array([0, 1, 2, 66, 67, 300, 301, 555, 613]), np.array([0, 200, 613])]
+    o = O.Oracle(d, n, O.BLOCKSIGN, 64, 0.9, 0.999, 1e-8, 1e-3, method=method)
+    o.set_blocks(tables[0])
+    mem = np.zeros((n, d), f32)                 # e_i, or ghat_i for Algorithm 1
+    ghat_s = np.zeros(d, f32)
+    gtil = np.zeros(d, f32)
+    for t in range(T):
+        off = tables[0] if t < 4 else tables[1]
+        if t == 4:
+            o.set_blocks(off)
+        g = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-5, 0, d))).astype(f32)
+        g[0, 66] = 0.0
+        o.step(g)
+        assert o.n_blocks == off.size - 1
+        x = g + mem if method == O.EF else g - mem if method == O.CD else g
+        acc = np.zeros(d, f32)
+        for i in range(n):
+            c, s = scaled_sign_by_definition(x[i], off)
+            assert np.array_equal(bits(o.compressed[i]), bits(c)), (t, i)
+            assert np.array_equal(bits(o.scales[i]), bits(s)), (t, i)
+            # per-block L1 norm is preserved with the block's own length as divisor
+            for b in range(off.size - 1):
+                l1 = np.abs(x[i, off[b]:off[b + 1]].astype(np.float64)).sum()
+                assert abs(float(s[b]) * (off[b + 1] - off[b]) - l1) <= 1e-6 * l1
+            if method == O.EF:
+                mem[i] = x[i] - c
+                assert np.array_equal(bits(o.error[i]), bits(mem[i])), (t, i)
+            elif method == O.CD:
+                mem[i] = mem[i] + c
+                assert np.array_equal(bits(o.ghat_workers[i]), bits(mem[i])), (t, i)
+            acc = acc + c
+        gbar = acc / f32(n)
+        assert np.array_equal(bits(o.gbar), bits(gbar))
+        if method == O.CD:
+            ghat_s = ghat_s + gbar
+            cs, ss = scaled_sign_by_definition(ghat_s - gtil, off)
+            gtil = gtil + cs
+            assert np.array_equal(bits(o.server_scales), bits(ss)), t
+            assert np.array_equal(bits(o.server_compressed), bits(cs)), t
+            assert np.array_equal(bits(o.ghat_server), bits(ghat_s)), t
+            assert np.array_equal(bits(o.gtilde), bits(gtil)), t
+    o.close()
+
+
+def test_step_size_schedule_matches_independent_amsgrad():
+    """oracle_set_lr: Algorithm 1 takes a non-increasing sequence alpha_t.  With no compression the
+    optimiser is vanilla distributed AMSGrad (Section 3); changing the step size between steps must
+    give, bit for bit, an independent numpy recursion that uses alpha_t at step t - and m, v, vhat
+    must not depend on the schedule at all."""
+    rng = np.random.default_rng(29)
+    n, d, T = 4, 400, 12
+    b1, b2, eps = f32(0.9), f32(0.999), f32(1e-8)
+    omb1, omb2 = f32(1) - b1, f32(1) - b2
+    sched = [f32(1e-2 / math.sqrt(t + 1)) for t in range(T)]          # non-increasing
+    theta0 = (0.01 * rng.standard_normal(d)).astype(f32)
+    gs = [(rng.standard_normal((n, d)) * np.exp(rng.uniform(-6, 0, d))).astype(f32) for _ in range(T)]
+    th, m, v, vh = theta0.copy(), np.zeros(d, f32), np.zeros(d, f32), np.zeros(d, f32)
+    o = O.Oracle(d, n, O.TOPK, d, float(b1), float(b2), float(eps), 123.0, method=O.NONE)   # lr of create is never used
+    o.set_theta(theta0)
+    fixed = O.Oracle(d, n, O.TOPK, d, float(b1), float(b2), float(eps), float(sched[0]), method=O.NONE)
+    fixed.set_theta(theta0)
+    for t, g in enumerate(gs):
+        o.set_lr(float(sched[t]))
+        o.step(g)
+        fixed.step(g)
+        acc = np.zeros(d, f32)
+        for i in range(n):
+            acc = acc + g[i]
+        gb = acc / f32(n)
+        m = b1 * m + omb1 * gb
+        v = b2 * v + omb2 * (gb * gb)
+        vh = np.maximum(vh, v)
+        th = th - (sched[t] * m) / (np.sqrt(vh) + eps)
+        assert np.array_equal(bits(o.theta), bits(th)), t
+        assert np.array_equal(bits(o.m), bits(m)) and np.array_equal(bits(o.v), bits(v))
+        assert np.array_equal(bits(o.vhat), bits(vh))
+        assert np.array_equal(bits(fixed.m), bits(m)) and np.array_equal(bits(fixed.vhat), bits(vh))
+        if t == 0:
+            assert np.array_equal(bits(fixed.theta), bits(th))        # same alpha_1 ...
+        else:
+            assert not np.array_equal(bits(fixed.theta), bits(th))    # ... a constant step size differs later
+    o.close()
+    fixed.close()
+
+
+def test_step_size_schedule_under_error_feedback_leaves_compression_alone():
+    """alpha_t enters the last line of the update only: under error feedback the kept sets, the error
+    memory, m, v and vhat are those of a constant step size; theta moves by alpha_t * m / denominator."""
+    rng = np.random.default_rng(31)
+    n, d, T = 3, 257, 6
+    gs = [rng.standard_normal((n, d)).astype(f32) for _ in range(T)]
+    a = O.Oracle(d, n, O.TOPK, 9, 0.9, 0.999, 1e-8, 1e-3)
+    b = O.Oracle(d, n, O.TOPK, 9, 0.9, 0.999, 1e-8, 1e-3)
+    for t, g in enumerate(gs):
+        th_before = b.theta.copy()
+        b.set_lr(1e-3 / (t + 1))
+        a.step(g)
+        b.step(g)
+        assert np.array_equal(a.selected, b.selected) and np.array_equal(bits(a.error), bits(b.error))
+        assert np.array_equal(bits(a.m), bits(b.m)) and np.array_equal(bits(a.vhat), bits(b.vhat))
+        want = th_before - (f32(1e-3 / (t + 1)) * b.m) / (np.sqrt(b.vhat) + f32(1e-8))
+        assert np.array_equal(bits(b.theta), bits(want)), t
+    a.close()
+    b.close()
+
+
 # ----------------------------------------------------------------------------- CD-Adam (Algorithm 1)
 
 def test_cd_adam_golden_example_c_topk():
