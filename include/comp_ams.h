@@ -21,7 +21,8 @@
  *  - The handle owns all optimiser state and scratch in device memory.  It is allocated in
  *    comp_ams_create (and comp_ams_set_blocks); comp_ams_step allocates nothing.
  *  - "dev" pointers are device pointers on the GPU that was current when the handle was
- *    created; "host" pointers are ordinary host memory.  Where a function takes
+ *    created; "host" pointers are ordinary host memory.  An entry point that takes a handle makes
+ *    that GPU current while it runs and restores the caller's current device before it returns.  Where a function takes
  *    `on_device`, 0 means the buffer is host memory and non-zero means device memory.
  *  - comp_ams_step is asynchronous on the given HIP stream.  Getters and setters run on the
  *    stream of the most recent step (the null stream before the first) and return after

@@ -504,11 +504,11 @@ __global__ __launch_bounds__(kThreads) void bs_pack_signs(const uint16_t *__rest
     out[q] = bits;
 }
 
-// e_i of one worker in its defined form, from the stored x and the pending scales.
+// e_i of one worker in its defined form, from the stored x and the pending scales.  out may be xrow itself
+// (every thread reads its own element before it writes it).
 template <bool kPending>
-__global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *__restrict__ xrow, int64_t d,
-                                                                 BsTable tb, const float *__restrict__ sp,
-                                                                 float *__restrict__ out)
+__global__ __launch_bounds__(kThreads) void bs_materialize_error(const float *xrow, int64_t d, BsTable tb,
+                                                                 const float *__restrict__ sp, float *out)
 {
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (j >= d) return;
@@ -585,12 +585,11 @@ __global__ __launch_bounds__(kThreads) void bs_apply(int64_t d, BsTable tb, cons
     }
 }
 
-// ghat_i of one worker in its defined form: the stored vector plus the pending c_i.
+// ghat_i of one worker in its defined form: the stored vector plus the pending c_i.  out may be xrow itself.
 template <bool kPending>
-__global__ __launch_bounds__(kThreads) void bs_materialize_markov(const float *__restrict__ xrow, int64_t d,
-                                                                  BsTable tb, const float *__restrict__ sp,
-                                                                  const uint16_t *__restrict__ signs_row,
-                                                                  float *__restrict__ out)
+__global__ __launch_bounds__(kThreads) void bs_materialize_markov(const float *xrow, int64_t d, BsTable tb,
+                                                                  const float *__restrict__ sp,
+                                                                  const uint16_t *__restrict__ signs_row, float *out)
 {
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (j >= d) return;

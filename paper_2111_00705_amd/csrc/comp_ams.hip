@@ -416,13 +416,31 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     return COMP_AMS_OK;
 }
 
-int check_handle(comp_ams *h)
-{
-    if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
-    hipError_t e = hipSetDevice(h->device);
-    if (e != hipSuccess) return fail(h, COMP_AMS_EDEVICE, "hipSetDevice(%d) failed: %s", h->device, hipGetErrorString(e));
-    return COMP_AMS_OK;
-}
+// Makes the handle's GPU the current device for the duration of an entry point and gives the caller its
+// own current device back on the way out (also on every error return).
+struct DeviceScope {
+    int prev = -1;
+    bool switched = false;
+    int enter(comp_ams *h)
+    {
+        if (!h) return fail(nullptr, COMP_AMS_EINVAL, "handle is NULL");
+        hipError_t e = hipGetDevice(&prev);
+        if (e != hipSuccess) return fail(h, COMP_AMS_EDEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
+        if (prev == h->device) return COMP_AMS_OK;
+        e = hipSetDevice(h->device);
+        if (e != hipSuccess) return fail(h, COMP_AMS_EDEVICE, "hipSetDevice(%d) failed: %s", h->device, hipGetErrorString(e));
+        switched = true;
+        return COMP_AMS_OK;
+    }
+    ~DeviceScope()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+// First lines of an entry point that touches the device: validates the handle, selects its GPU.
+#define ENTER_DEVICE(h)        \
+    DeviceScope device_scope__; \
+    int rc = device_scope__.enter(h)
 
 int copy_out(comp_ams *h, float *dst, const float *src_dev, size_t count, int on_device)
 {
@@ -723,7 +741,7 @@ void launch_materialize(comp_ams *h, int worker, float *dst)
 template <typename G>
 int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (!grads_dev) return fail(h, COMP_AMS_EINVAL, "grads is NULL");
     if (reinterpret_cast<uintptr_t>(grads_dev) & (sizeof(G) - 1))
@@ -738,7 +756,6 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
         for (TkGeom *ge : {&h->ge, &h->srv.ge}) {
             ge->rand.on = 1u;
             ge->rand.seed_hi = (uint32_t)(h->rand_seed >> 32);
-            ge->rand.step_prev = per_step_word(h, h->draw - 1u);
             ge->rand.step_now = per_step_word(h, h->draw);
         }
         h->ge.rand.who0 = 0u;
@@ -880,18 +897,21 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
 void comp_ams_destroy(comp_ams_t *h)
 {
     if (!h) return;
-    if (hipSetDevice(h->device) == hipSuccess) {
-        (void)hipStreamSynchronize(h->stream);
-        prof_clear(h);
-        free_all(h->allocs);
-        free_all(h->tb_allocs);
+    {
+        DeviceScope scope;
+        if (scope.enter(h) == COMP_AMS_OK) {
+            (void)hipStreamSynchronize(h->stream);
+            prof_clear(h);
+            free_all(h->allocs);
+            free_all(h->tb_allocs);
+        }
     }
     delete h;
 }
 
 int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_blocks)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "set_blocks needs a BLOCKSIGN handle");
     if (!offsets_host) return fail(h, COMP_AMS_EINVAL, "offsets is NULL");
@@ -913,7 +933,7 @@ int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_bl
 
 int comp_ams_set_theta(comp_ams_t *h, const float *theta, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (!theta) return fail(h, COMP_AMS_EINVAL, "theta is NULL");
     return copy_in(h, h->theta, theta, (size_t)h->d, on_device);
@@ -988,28 +1008,28 @@ int comp_ams_step_f16(comp_ams_t *h, const uint16_t *grads_f16_dev, void *hip_st
 
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     return rc ? rc : copy_out(h, out, h->theta, (size_t)h->d, on_device);
 }
 int comp_ams_get_m(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     return rc ? rc : copy_out(h, out, h->m, (size_t)h->d, on_device);
 }
 int comp_ams_get_v(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     return rc ? rc : copy_out(h, out, h->v, (size_t)h->d, on_device);
 }
 int comp_ams_get_vhat(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     return rc ? rc : copy_out(h, out, h->vhat, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (h->method != COMP_AMS_METHOD_EF)
         return fail(h, COMP_AMS_ESTATE, "this method keeps no error memory (CD-Adam: see comp_ams_get_ghat_worker)");
@@ -1073,7 +1093,7 @@ int gather_selected(comp_ams *h, const TkGeom &ge, int worker, const TkWorker *w
 
 int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1085,7 +1105,7 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
 
 int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (!is_sparse(h) || h->method != COMP_AMS_METHOD_CD)
         return fail(h, COMP_AMS_ESTATE, "get_server_selected needs a TOPK handle set to CD-Adam");
@@ -1095,7 +1115,7 @@ int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_h
 
 int comp_ams_get_scales(comp_ams_t *h, float *out_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_scales needs a BLOCKSIGN handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1105,7 +1125,7 @@ int comp_ams_get_scales(comp_ams_t *h, float *out_host)
 
 int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_signs needs a BLOCKSIGN handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1113,19 +1133,16 @@ int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host)
     const bool server = (h->method == COMP_AMS_METHOD_CD && worker == h->n);
     if (!server && (worker < 0 || worker >= h->n)) return fail(h, COMP_AMS_EINVAL, "worker %d out of range", worker);
     if (!bits_host) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
+    // the wire order (bit j % 8 of byte j / 8 = coordinate j) is what bs_pack_signs writes as 32-bit words;
+    // row_tmp (d floats) holds the (d + 31) / 32 words
     const size_t words = (size_t)h->ld / 16;
-    std::vector<uint16_t> w(words);
     const uint16_t *src = server ? h->signs_srv : h->signs + (size_t)worker * words;
-    HIP_TRY(h, hipMemcpyAsync(w.data(), src, words * sizeof(uint16_t), hipMemcpyDeviceToHost, h->stream));
+    const int64_t out_words = (h->d + 31) / 32;
+    uint32_t *packed = reinterpret_cast<uint32_t *>(h->row_tmp);
+    bs_pack_signs<<<(unsigned)((out_words + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(src, h->d, packed);
+    HIP_TRY(h, hipGetLastError());
+    HIP_TRY(h, hipMemcpyAsync(bits_host, packed, ((size_t)h->d + 7) / 8, hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
-    // coordinate 4 * (tid + 256 * r) + c of a tile is bit r * 4 + c of the tile's word number tid
-    std::memset(bits_host, 0, ((size_t)h->d + 7) / 8);
-    for (int64_t j = 0; j < h->d; ++j) {
-        const int64_t t = j / kTile;
-        const int l = (int)(j - t * kTile), vec = l >> 2;
-        const uint16_t word = w[(size_t)t * kThreads + (size_t)(vec & (kThreads - 1))];
-        if ((word >> ((vec / kThreads) * 4 + (l & 3))) & 1u) bits_host[j >> 3] |= (uint8_t)(1u << (j & 7));
-    }
     return COMP_AMS_OK;
 }
 
@@ -1144,7 +1161,7 @@ int comp_ams_message_bytes(comp_ams_t *h, uint64_t *bytes)
 
 int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
@@ -1188,7 +1205,7 @@ int32_t comp_ams_n_blocks(comp_ams_t *h)
 
 int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const float *vhat, const float *e, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     const size_t d = (size_t)h->d;
     if (m && (rc = copy_in(h, h->m, m, d, on_device))) return rc;
@@ -1210,7 +1227,7 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
 
 int comp_ams_sync(comp_ams_t *h)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return COMP_AMS_OK;
@@ -1218,7 +1235,7 @@ int comp_ams_sync(comp_ams_t *h)
 
 int comp_ams_profile(comp_ams_t *h, int enable)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     prof_clear(h);
@@ -1228,7 +1245,7 @@ int comp_ams_profile(comp_ams_t *h, int enable)
 
 int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (slot < 0) return fail(h, COMP_AMS_EINVAL, "slot must be >= 0");
     if (slot >= P_SLOTS) return 1;
@@ -1247,7 +1264,7 @@ int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double
 
 int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selection_info needs a TOPK handle");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
@@ -1268,7 +1285,7 @@ int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_hos
 
 int comp_ams_set_method(comp_ams_t *h, int32_t method)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc) return rc;
     if (method < COMP_AMS_METHOD_EF || method > COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
     if (method == h->method) return COMP_AMS_OK;
@@ -1323,7 +1340,7 @@ int need_cd(comp_ams *h)
 
 int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc || (rc = need_cd(h))) return rc;
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
@@ -1336,21 +1353,21 @@ int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_d
 
 int comp_ams_get_ghat_server(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc || (rc = need_cd(h))) return rc;
     return copy_out(h, out, h->ghat_srv, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_gtilde(comp_ams_t *h, float *out, int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc || (rc = need_cd(h))) return rc;
     return copy_out(h, out, h->gtil, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc || (rc = need_cd(h))) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_server_scales needs a BLOCKSIGN handle");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
@@ -1360,7 +1377,7 @@ int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
 int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const float *ghat_server, const float *gtilde,
                               int on_device)
 {
-    int rc = check_handle(h);
+    ENTER_DEVICE(h);
     if (rc || (rc = need_cd(h))) return rc;
     const size_t d = (size_t)h->d;
     if (ghat_server && (rc = copy_in(h, h->ghat_srv, ghat_server, d, on_device))) return rc;

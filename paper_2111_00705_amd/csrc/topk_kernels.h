@@ -82,14 +82,17 @@ struct TkWorker {
                             // candidates are kept and `rank` zeros besides (see zero_tail_threshold)
     uint32_t relisted;      // the guess was above the threshold: candidates are listed again
     uint32_t last_fine;     // fine bin of the previous threshold (to see how far thresholds move)
+    uint32_t step_word;     // Rand-k: TkRand::step_now of the step that left tc - the draw the deferred error memory
+                            // must be read with.  Kept in device memory, not in a kernel argument, so that a step
+                            // replayed from a HIP graph (which repeats its draw) still reads its predecessor's.
 };
 
 // Rand-k: what the score of a coordinate depends on besides its index and the vector's number.
 struct TkRand {
     uint32_t on;          // 0: Top-k (keys are magnitudes)
     uint32_t seed_hi;     // upper half of the 64-bit seed
-    uint32_t step_now;    // mix32(lower half of the seed + draw * 0x9e3779b9) for the running step's draw ...
-    uint32_t step_prev;   // ... and for the draw of the step whose selection is still pending
+    uint32_t step_now;    // mix32(lower half of the seed + draw * 0x9e3779b9) for the running step's draw (the draw of
+                          // the step whose selection is still pending is TkWorker::step_word)
     uint32_t who0;        // number of vector 0 of this geometry: 0 for the workers, n for CD-Adam's server
     uint32_t min_slack;   // Rand-k: least slack of the guess, in fine bins (0: kMinSlack).  The k-th largest score
                           // of a fresh draw scatters by sqrt(k (1 - k/d)) / d of the key range around (1 - k/d).
@@ -411,7 +414,7 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const uint32_t guess = ws[i].guess;
     const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const SelKey sk_prev = sel_key_of(ge.rand, ge.rand.step_prev, i);
+    const SelKey sk_prev = sel_key_of(ge.rand, ws[i].step_word, i);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
     if (tid == 0) sh[4] = 0;
@@ -871,6 +874,7 @@ __device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorke
                                               bool missed)
 {
     ws[i].tc = tc;
+    ws[i].step_word = ge.rand.step_now;
     const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
     const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
     uint32_t slack = missed ? w.slack * 2u : w.slack - 1u;
@@ -1275,16 +1279,14 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
 
 // Getter support -------------------------------------------------------------------------------
 
-// e_i of one worker in its defined form, from the stored x and the pending threshold (ge.rand.step_now
-// is the draw of the step that left that threshold).
-__global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *__restrict__ xrow, TkGeom ge, int worker,
-                                                                 const TkWorker *__restrict__ w,
-                                                                 float *__restrict__ out)
+// e_i of one worker in its defined form, from the stored x and the pending threshold.
+__global__ __launch_bounds__(kThreads) void tk_materialize_error(const float *xrow, TkGeom ge, int worker,
+                                                                 const TkWorker *__restrict__ w, float *out)
 {
     const int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (j >= ge.d) return;
     const float x = xrow[j];
-    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, worker);
+    const SelKey sk = sel_key_of(ge.rand, w->step_word, worker);
     out[j] = was_kept(kept_test(w->tc, ge.idx_bits), sel_key(sk, x, (uint32_t)j), (uint32_t)j) ? 0.f : x;
 }
 

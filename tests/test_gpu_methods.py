@@ -209,17 +209,25 @@ def test_scaled_sign_message_rebuilt_from_bits_and_scales(method):
 
 
 @pytest.mark.parametrize("comp,kb,method", [(P.TOPK, 300, P.METHOD_EF), (P.BLOCKSIGN, 4096, P.METHOD_EF),
-                                            (P.TOPK, 300, P.METHOD_CD), (P.BLOCKSIGN, 1000, P.METHOD_CD)])
+                                            (P.TOPK, 300, P.METHOD_CD), (P.BLOCKSIGN, 1000, P.METHOD_CD),
+                                            (P.RANDK, 300, P.METHOD_EF), (P.RANDK, 300, P.METHOD_CD)])
 def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
     """comp_ams_step allocates nothing and clears its counters in kernels, so a caller may capture it.
     The captured step is replayed several times, with fresh gradients copied into the captured buffer
-    by ordinary eager work in between, and every replay is checked against the oracle."""
+    by ordinary eager work in between, and every replay is checked against the oracle.
+    Rand-k: a replayed step repeats the draw it was recorded with, so the oracle's draw is held at
+    that number; under error feedback the deferred error memory of each replay must then be read with
+    the draw of its predecessor - the same draw from the second replay on."""
     import torch
     announce(f"graph capture comp={comp} method={method}")
     d, n = 30_011, 4
     gpu = P.CompAms(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR)
     ora = O.Oracle(d, n, comp, kb, W.BETA1, W.BETA2, W.EPS, W.LR, method=method)
     gpu.set_method(method)
+    seed = 0xfeedface12345678
+    if comp == P.RANDK:
+        gpu.set_rand(seed, 0)
+        ora.set_rand(seed, 0)
     grads = [np.random.default_rng([13, t]).standard_normal((n, d)).astype(f32) for t in range(7)]
     side = torch.cuda.Stream()
     gbuf = torch.empty((n, d), dtype=torch.float32, device="cuda")
@@ -238,6 +246,8 @@ def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
         side.synchronize()
         graph.replay()
         torch.cuda.synchronize()
+        if comp == P.RANDK:
+            ora.set_rand(seed, 2)                          # the recorded step was the third: draw number 2
         ora.step(grads[t])
         for name, got, want in (("theta", gpu.get_theta(), ora.theta), ("vhat", gpu.get_vhat(), ora.vhat)):
             ok = rel_close(got, want, STATE_RTOL)
@@ -246,6 +256,8 @@ def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
             assert np.array_equal(bits(gpu.get_error(1)), bits(ora.error[1])), t
         else:
             assert np.array_equal(bits(gpu.get_ghat_worker(1)), bits(ora.ghat_workers[1])), t
+        if comp != P.BLOCKSIGN:
+            assert np.array_equal(gpu.get_selected(2)[0], ora.selected[2]), t
     gpu.destroy()
 
 
