@@ -3,6 +3,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config IDX]
 
+With no --config it runs the largest of the five workloads (cfg4: n = 8 workers, d = 110 M coordinates,
+Top-k with k = 110 000; every array streams from HBM); the other four are behind --config 0..3.
+
 One "step" is one pass of the whole hot path (error-feedback add, compression, error update,
 average over the n simulated workers, AMSGrad update) over one batch of synthetic gradients that
 is already resident in HBM.  Prints ONE JSON line:
@@ -25,26 +28,54 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
-# HBM-side bytes per launch (fetched + written) of the dominant kernels, from the rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (calibrated on probe_copy), keyed by
-# (workload name, kernel), CD-Adam runs by (workload name + "/cd", kernel); absent = not measured.
-MEASURED_TRAFFIC_BYTES: dict[tuple[str, str], float] = {
-    ("cfg1_blocksign4096_n16_d1199882", "bs_pass"): 235.2e6,
-    ("cfg1_blocksign4096_n16_d1199882", "bs_update"): 41.5e6,
-    ("cfg2_topk_n16_d11173962", "tk_pass1"): 2178.7e6,
-    ("cfg2_topk_n16_d11173962", "tk_final"): 388.0e6,
-    ("cfg3_layersign_n32_d25557032", "bs_pass"): 9931.6e6,
-    ("cfg3_layersign_n32_d25557032", "bs_update"): 921.5e6,
-    ("cfg4_topk_n8_d110000000", "tk_pass1"): 10598.7e6,
-    ("cfg4_topk_n8_d110000000", "tk_final"): 3226.5e6,
-    ("cfg1_blocksign4096_n16_d1199882/cd", "bs_pass"): 237.4e6,
-    ("cfg1_blocksign4096_n16_d1199882/cd", "bs_server"): 60.9e6,
-    ("cfg2_topk_n16_d11173962/cd", "tk_pass1"): 1474.0e6,
-    ("cfg2_topk_n16_d11173962/cd", "tk_merge"): 382.3e6,
-    ("cfg2_topk_n16_d11173962/cd", "tk_apply"): 417.5e6,
-    ("cfg3_layersign_n32_d25557032/cd", "bs_pass"): 10035.3e6,
-    ("cfg3_layersign_n32_d25557032/cd", "bs_apply"): 1026.6e6,
+PROFILES = os.path.join(ROOT, "profiles")
+CSRC = os.path.join(ROOT, "paper_2111_00705_amd", "csrc")
+
+# The templated kernel behind each timing slot, by method: which row of a rocprofv3 summary a slot reads.
+KERNEL_VARIANT = {
+    ("tk_pass1", "ef"): "cams::tk_pass1<0, float>", ("tk_pass1", "cd"): "cams::tk_pass1<1, float>",
+    ("tk_pass1", "naive"): "cams::tk_pass1<3, float>",
 }
+
+
+def library_fingerprint() -> str:
+    """Twelve hex digits of a SHA-1 over the library's sources (csrc/*): every rocprofv3 summary under
+    profiles/ records the fingerprint of the build it was taken with, and counter figures are quoted from
+    a summary only while it matches the sources in the tree."""
+    import hashlib
+    h = hashlib.sha1()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".h", ".hip")):
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def measured_traffic(workload: str, method: str, grad_dtype: str, slot: str):
+    """HBM-side bytes per launch (fetched + written) of one kernel from the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE summary of this workload under profiles/ (a separate run, calibrated on probe_copy).
+    Returns (bytes or None, source or reason).  None when there is no summary for this workload and
+    method, when it was taken with other sources than the tree holds, or when it has no row for the
+    kernel variant that ran."""
+    if grad_dtype != "f32" or method not in ("ef", "cd"):
+        return None, "no counter summary for this method / gradient type"
+    rel = os.path.join("profiles", workload + ("_cd_adam" if method == "cd" else "") + ".md")
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None, f"{rel} does not exist"
+    text = open(path).read()
+    import re
+    fp = re.search(r"Library source fingerprint: `([0-9a-f]{12})`", text)
+    have = library_fingerprint()
+    if not fp or fp.group(1) != have:
+        return None, f"{rel} was taken with sources {fp.group(1) if fp else 'unrecorded'}, the tree holds {have}"
+    want = KERNEL_VARIANT.get((slot, method), "cams::" + slot)
+    section = text.split("## HBM-side traffic", 1)[-1]
+    for line in section.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 7 and (cells[0].strip("`") == want or cells[0].strip("`").startswith(want + "<")):
+            return float(cells[6]) * 1e6, rel
+    return None, f"{rel} has no row for {want}"
 
 
 def kernel_algorithmic_bytes(name: str, n: int, d: int, method: str = "ef") -> int:
@@ -74,10 +105,17 @@ def kernel_algorithmic_bytes(name: str, n: int, d: int, method: str = "ef") -> i
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)     # 1000 steps of the headline workload: about 60 ms timed
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 200 on the three large workloads - under half a second of timed work "
+                         "on the largest - and 1000 on the two small ones)")
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="index into the five named workloads")
-    ap.add_argument("--buffers", type=int, default=4, help="distinct gradient batches cycled through")
+    ap.add_argument("--config", type=int, default=4,
+                    help="index into the five named workloads; the default, 4, is the largest (n = 8, d = 110 M, Top-k: "
+                         "14.08 GB of algorithmic traffic per step, far beyond every cache)")
+    ap.add_argument("--buffers", type=int, default=None,
+                    help="distinct gradient batches cycled through (default: 2 on the two largest workloads, "
+                         "3.3 - 3.5 GB each, else 4)")
+    ap.add_argument("--fingerprint", action="store_true", help="print the library source fingerprint and exit")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--method", choices=("ef", "cd", "naive", "none"), default="ef",
@@ -91,6 +129,13 @@ def main() -> int:
     ap.add_argument("--probe-mib", type=int, default=1024,
                     help="size of the plain-copy probe (MiB per buffer); 0 skips the copy ceiling")
     args = ap.parse_args()
+    if args.fingerprint:
+        print(library_fingerprint())
+        return 0
+    if args.steps is None:
+        args.steps = 200 if args.config >= 2 else 1000
+    if args.buffers is None:
+        args.buffers = 2 if args.config >= 3 else 4
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all n workers are simulated as a batch on it); "
               "--gpus must be 1", file=sys.stderr)
@@ -169,14 +214,15 @@ def main() -> int:
         dom_bytes -= 2 * w.n * w.d
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    traffic, traffic_source = measured_traffic(w.name, args.method, args.grad_dtype, dom)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name + ("/cd" if cd else ""), dom))
-                if args.method in ("ef", "cd") and not bf16 else None,
+                "traffic": traffic, "traffic_source": traffic_source,
                 "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
-    if roofline["traffic"]:
-        # bytes the counters saw per launch over the same live duration: the rate the memory system ran at
-        roofline["traffic_gbs"] = round(roofline["traffic"] / (dom_us * 1e-6) / 1e9, 1)
+    if traffic:
+        # bytes the counters saw per launch (in the separate counter run named above) over the duration measured
+        # live here: the rate the memory system ran at
+        roofline["traffic_gbs"] = round(traffic / (dom_us * 1e-6) / 1e9, 1)
         roofline["traffic_frac"] = round(roofline["traffic_gbs"] / HBM_PEAK_GBS, 4)
     step_gbs = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -246,6 +292,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "kernels": {k: {a: round(b, 3) for a, b in v.items()} for k, v in kernels.items()},
         "copy_ceiling": copy_ceiling,
+        "library_fingerprint": library_fingerprint(),
         "cpu_baseline": cpu,
     }
     h.destroy()

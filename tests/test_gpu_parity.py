@@ -271,7 +271,7 @@ def test_cfg1_full_all_steps():
     announce(w.name)
     gpu, ora = pair_for(w)
     s = w.scales()
-    stats = run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name, check_every=5,
+    stats = run_steps(gpu, ora, lambda t: w.grads(t, scales=s), steps=w.steps, tag=w.name, check_every=1,
                       offsets=w.block_offsets())
     print("cfg1 stats", stats[-1], flush=True)
     gpu.destroy()
