@@ -263,6 +263,20 @@ int comp_ams_message_bytes(comp_ams_t *h, uint64_t *bytes);
 int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes);
 
 /*
+ * comp_ams_pack_message for callers that cannot allocate or wait: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same bytes in buf_dev (the pairs of a TOPK / RANDK
+ * message again in no particular order).  It calls no hipMalloc / hipFree or other allocating routine and does
+ * not wait: the kernels are enqueued on the stream of the last step and the message is complete when that
+ * stream's work is (comp_ams_sync).  The gather of a TOPK / RANDK message works in a fixed array of device memory
+ * inside the library (8 MiB + 256 B, present on every GPU the library runs on until the process ends) instead
+ * of buffers of the handle; k above 2^20 = 1048576 pairs does not fit and is answered with COMP_AMS_EINVAL
+ * (nothing written).  All handles on one GPU share that array: two such calls that overlap in time on one GPU
+ * (different streams) race; calls on one stream, or separated by a wait, do not.  A BLOCKSIGN message needs no
+ * scratch and is copied straight from the handle's side buffers.
+ */
+int comp_ams_pack_message_noalloc(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes);
+
+/*
  * Communication cost of one step in bits, by the accounting of Section 5 (footnote to the
  * algorithm overview) and of the table "Average runtime and total bits": a scaled-sign message costs
  * 1 bit per coordinate plus 32 bits per scale (32 + d for the whole vector), a Top-k message 32 bits

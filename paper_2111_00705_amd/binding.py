@@ -33,6 +33,7 @@ EXPORTS = [
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
     "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_set_tile_order", "comp_ams_set_pass_lds", "comp_ams_message_bytes", "comp_ams_pack_message",
+    "comp_ams_pack_message_noalloc",
 ]
 
 
@@ -70,6 +71,7 @@ def lib():
         L.comp_ams_set_pass_lds.argtypes = [vp, C.c_int32]
         L.comp_ams_message_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
         L.comp_ams_pack_message.argtypes = [vp, C.c_int32, vp, C.c_uint64, C.POINTER(C.c_uint64)]
+        L.comp_ams_pack_message_noalloc.argtypes = [vp, C.c_int32, vp, C.c_uint64, C.POINTER(C.c_uint64)]
         L.comp_ams_step.argtypes = [vp, fp, vp]
         L.comp_ams_step_bf16.argtypes = [vp, fp, vp]
         L.comp_ams_step_f16.argtypes = [vp, vp, vp]
@@ -173,6 +175,15 @@ class CompAms:
         out = C.c_uint64(0)
         self._check(lib().comp_ams_pack_message(self._h, who, buf.data_ptr(), buf.numel() * buf.element_size(),
                                                 C.byref(out)))
+        return out.value
+
+    def pack_message_noalloc(self, who, buf):
+        """pack_message through the library's fixed scratch array: allocates nothing and does not wait
+        (call sync() before reading buf)."""
+        assert buf.is_cuda and buf.is_contiguous()
+        out = C.c_uint64(0)
+        self._check(lib().comp_ams_pack_message_noalloc(self._h, who, buf.data_ptr(),
+                                                        buf.numel() * buf.element_size(), C.byref(out)))
         return out.value
 
     def set_streaming(self, rows=-1, state=-1):

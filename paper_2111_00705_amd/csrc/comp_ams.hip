@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <tuple>
@@ -1194,6 +1195,103 @@ int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t ca
     }
     HIP_TRY(h, hipGetLastError());
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return COMP_AMS_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------------------
+// comp_ams_pack_message_noalloc: the gather of a Top-k / Rand-k message runs in a fixed array in device memory
+// instead of the handle's buffers.  Every GPU the library runs on holds its own copy of the array, at its own
+// address, until the process ends; the name below is only a host-side stand-in, and host code reaches the memory
+// through the per-device address from hipGetSymbolAddress (scratch_on_current_device).
+namespace {
+constexpr uint32_t kScratchMaxK = 1u << 20;                  // largest k the no-alloc entry point accepts
+constexpr size_t kScratchHeader = 256;                       // the kept-pairs counter, alone on its lines
+constexpr size_t kScratchBytes = kScratchHeader + 2 * sizeof(uint32_t) * (size_t)kScratchMaxK;   // 8 MiB + 256 B
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (which must be device `dev`); looked up once per device.
+int scratch_on_current_device(comp_ams *h, int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return fail(h, COMP_AMS_EDEVICE, "device %d: only devices 0..%d are supported here", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(h, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(h, COMP_AMS_EDEVICE, "hipGetSymbolAddress gave no address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char *>(g_scratch_ptr[dev]);
+    return COMP_AMS_OK;
+}
+
+__global__ void fill_words(uint32_t *dst, uint32_t value, uint32_t count)
+{
+    const uint32_t q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < count) dst[q] = value;
+}
+}  // namespace
+
+extern "C" {
+
+int comp_ams_pack_message_noalloc(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes)
+{
+    ENTER_DEVICE(h);
+    if (rc) return rc;
+    if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
+    if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
+    const bool server = (h->method == COMP_AMS_METHOD_CD && who == h->n);
+    if (!server && (who < 0 || who >= h->n)) return fail(h, COMP_AMS_EINVAL, "vector %d out of range", who);
+    uint64_t need = 0;
+    (void)comp_ams_message_bytes(h, &need);
+    if (bytes) *bytes = need;
+    if (!buf_dev) return fail(h, COMP_AMS_EINVAL, "buffer is NULL");
+    if (reinterpret_cast<uintptr_t>(buf_dev) & 7u) return fail(h, COMP_AMS_EINVAL, "buffer must be 8-byte aligned");
+    if (capacity < need)
+        return fail(h, COMP_AMS_EINVAL, "buffer of %llu bytes, the message takes %llu", (unsigned long long)capacity,
+                    (unsigned long long)need);
+    if (is_sparse(h)) {
+        if ((uint64_t)h->k > kScratchMaxK)
+            return fail(h, COMP_AMS_EINVAL, "k=%lld exceeds the %u pairs the fixed scratch array holds (use comp_ams_pack_message)",
+                        (long long)h->k, kScratchMaxK);
+        unsigned char *sp = nullptr;
+        if ((rc = scratch_on_current_device(h, h->device, &sp))) return rc;
+        uint32_t *count = reinterpret_cast<uint32_t *>(sp);
+        uint32_t *idx = reinterpret_cast<uint32_t *>(sp + kScratchHeader);
+        float *val = reinterpret_cast<float *>(sp + kScratchHeader + sizeof(uint32_t) * (size_t)kScratchMaxK);
+        const TkGeom &ge = server ? h->srv.ge : h->ge;
+        const int vec = server ? 0 : who;
+        const TkWorker *ws = server ? h->srv.ws : h->ws;
+        // the array keeps the last call's contents: the counter must start at zero (a kernel, not a memset node,
+        // so that the call can also be recorded into a graph)
+        fill_words<<<1, kWave, 0, h->stream>>>(count, 0u, 1u);
+        tk_gather_selected<<<ge.n_tiles, kThreads, 0, h->stream>>>(ge, vec, ws, server ? h->srv.cand : h->cand,
+                                                                  server ? h->srv.tile_dir : h->tile_dir, count, idx, val);
+        const int zrow = zero_row_of(h, who, server);
+        if (zrow >= 0)
+            tk_gather_zero_tail<<<(unsigned)((h->d + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+                h->e + (size_t)zrow * (size_t)h->ld, ge, ws + vec, count, idx, val);
+        tk_pack_pairs<<<(unsigned)((ge.k + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+            idx, val, ge.k, static_cast<uint2 *>(buf_dev));
+    } else {
+        // scaled sign: scales and sign words go straight from the handle's side buffers to the caller's buffer
+        const size_t words = (size_t)h->ld / 16;
+        const size_t nb = (size_t)h->tb.n_blocks;
+        const float *sc = server ? h->scales_srv : h->scales + (size_t)who * nb;
+        const uint16_t *sw = server ? h->signs_srv : h->signs + (size_t)who * words;
+        HIP_TRY(h, hipMemcpyAsync(buf_dev, sc, nb * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+        const int64_t out_words = (h->d + 31) / 32;
+        bs_pack_signs<<<(unsigned)((out_words + kThreads - 1) / kThreads), kThreads, 0, h->stream>>>(
+            sw, h->d, reinterpret_cast<uint32_t *>(static_cast<float *>(buf_dev) + nb));
+    }
+    HIP_TRY(h, hipGetLastError());
     return COMP_AMS_OK;
 }
 
