@@ -193,9 +193,11 @@ def main() -> int:
             step_ptr(dev_grads[t % nbuf].data_ptr(), stream)
 
     run(0, args.warmup)
+    h.sync()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(args.warmup, args.steps)
+    h.sync()                        # includes the update that the last step left to the next call
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps

@@ -73,16 +73,26 @@ struct comp_ams {
     double *partial_srv = nullptr;                // [n_pieces]
     float *scales_srv = nullptr;                  // [n_blocks]
 
-    // Top-k
+    // Top-k.  The records, candidate lists and tile directory exist twice: under error feedback the AMSGrad update of
+    // a step is deferred into the selection kernels of the next one (see step_topk), which fill the other set
+    // meanwhile.  ws / cand / tile_dir always point at the set of the most recent step.
     TkGeom ge{};
     TkWorker *ws = nullptr;
-    uint2 *cand = nullptr;                     // [n][64 regions][slice_tiles * 4096] candidate (index, value bits)
-    uint32_t *cursor = nullptr;                // [n][64] entries in each region (zero between steps)
-    uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in its region, counts per wavefront, total}
+    uint2 *cand = nullptr;                     // [n][slices][region_cap] candidate (index, value bits)
+    uint32_t *cursor = nullptr;                // [n][slices] entries in each region (zero between steps)
+    uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in the worker's space, counts per wavefront, zeros}
+    TkWorker *ws2[2] = {nullptr, nullptr};
+    uint2 *cand2[2] = {nullptr, nullptr};
+    uint4 *tile_dir2[2] = {nullptr, nullptr};
+    int par = 0;                               // which set ws / cand / tile_dir point at
+    bool final_pending = false;                // the update of the most recent step has not been launched yet ...
+    AmsParams pending_params{};                // ... and the hyper-parameters it must run with (those of its step)
     uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
+    uint16_t *signs2[2] = {nullptr, nullptr};  // block sign, deferred update: see step_blocksign
+    double *partial2[2] = {nullptr, nullptr};
     uint2 *dense_dir = nullptr;                // [n][64 * parts * 4] {start, count} of each wavefront's piece
     uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
@@ -442,6 +452,13 @@ struct DeviceScope {
 #define ENTER_DEVICE(h)        \
     DeviceScope device_scope__; \
     int rc = device_scope__.enter(h)
+// The same for an entry point that reads or replaces state: an update that the last step left pending is
+// launched first.
+int flush_pending(comp_ams *h);
+#define ENTER_STATE(h)          \
+    DeviceScope device_scope__; \
+    int rc = device_scope__.enter(h); \
+    if (!rc) rc = flush_pending(h)
 
 int copy_out(comp_ams *h, float *dst, const float *src_dev, size_t count, int on_device)
 {
@@ -555,32 +572,56 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 }
 
 // The five selection launches between the listing pass and the kernel that uses Tc: candidate
-// histograms, leading digits, second listing (rare), compaction of the threshold bin, last digits.
-// kSrc / a / b say how tk_relist forms the compressed vector again.
-template <int kSrc, typename G>
-void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
-                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint64_t *dense,
-                   uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5])
+// histograms, leading digits, second listing (rare), compaction of the threshold bin (or, rarer still, the
+// selection without lists), last digits.  kSrc / a / b say how tk_relist forms the compressed vector again.
+// wp / wc: the records of the step before and of the running step (the same array unless the update is deferred).
+// fill: an update that these kernels carry along as fillers (tiles == 0: none); kFill as in run_filler.
+constexpr int kFillWeights[5] = {2, 1, 1, 2, 3};   // shares of the deferred update's tiles, by kernel
+
+template <int kSrc, typename G, int kFill>
+void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, const TkWorker *wp, TkWorker *wc, uint2 *cand,
+                   uint32_t *cursor, uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full,
+                   uint64_t *dense, uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5],
+                   const FinalJob &fill)
 {
-    const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
-    // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
-    // the whole vector after a miss) are kept to about two per compute unit in total
-    const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
-    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1,
-            histf); });
+    // each kernel's share of the filler tiles
+    FinalJob job[5];
+    unsigned extra[5];
+    {
+        int wsum = 0, given = 0, acc = 0;
+        for (int q = 0; q < 5; ++q) wsum += kFillWeights[q];
+        for (int q = 0; q < 5; ++q) {
+            acc += kFillWeights[q];
+            const int upto = kFill ? (int)((int64_t)fill.tiles * acc / wsum) : 0;
+            job[q] = fill;
+            job[q].tile0 = fill.tile0 + given;
+            job[q].tiles = upto - given;
+            given = upto;
+            const int per_wg = (q == 4) ? kResolveThreads / kThreads : 1;
+            extra[q] = (unsigned)((job[q].tiles + per_wg - 1) / per_wg);
+        }
+    }
+    const unsigned shared = (unsigned)(ge.slices * ge.parts * ge.n);
+    launch_timed(h, slot[0], st, [&] {
+        KLAUNCH((tk_hist<kFill>), shared + extra[0], kThreads, st, ge, wp, wc, cand, cursor, hist1, histf, job[0]);
+    });
     launch_timed(h, slot[1], st, [&] {
-        KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, hist_full, a, b);
+        KLAUNCH((tk_pick<kSrc, G, kFill>), (unsigned)(ge.pick_wgs * ge.n) + extra[1], kThreads, st, ge, wp, wc, hist1, histf,
+                cursor, hist_full, a, b, job[1]);
     });
     launch_timed(h, slot[2], st, [&] {
-        KLAUNCH((tk_relist<kSrc, G>), sweep, kThreads, st, a, b, ge, ws, hist_full, cand, cursor, tile_dir);
+        KLAUNCH((tk_relist<kSrc, G, kFill>), (unsigned)(ge.relist_wgs * ge.n) + extra[2], kThreads, st, a, b, ge, wc, hist_full,
+                cand, cursor, tile_dir, job[2]);
     });
     launch_timed(h, slot[3], st, [&] {
-        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir);
+        KLAUNCH((tk_compact<kSrc, G, kFill>), shared + extra[3], kThreads, st, ge, wc, cand, cursor, tile_dir, dense, dense_dir,
+                a, b, job[3]);
     });
     launch_timed(h, slot[4], st, [&] {
         // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
         const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
-        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, tile_dir, rows);
+        KLAUNCH((tk_resolve<kFill>), (unsigned)ge.n + extra[4], kResolveThreads, st, ge, wp, wc, dense, dense_dir, cursor,
+                hist_full, tile_dir, rows, job[4]);
     });
 }
 
@@ -588,45 +629,86 @@ constexpr int kWorkerSelectSlots[5] = {P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_C
 constexpr int kServerSelectSlots[5] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER,
                                        P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
 
+// What tk_final needs for the update that follows the selection recorded in set `set` of the handle.
+FinalJob final_job(const comp_ams *h, int set, const AmsParams &params)
+{
+    FinalJob j{};
+    j.ws = h->ws2[set];
+    j.cand = h->cand2[set];
+    j.tile_dir = h->tile_dir2[set];
+    j.theta = h->theta;
+    j.m = h->m;
+    j.v = h->v;
+    j.vhat = h->vhat;
+    j.p = params;
+    j.tile0 = 0;
+    j.tiles = h->ge.n_tiles;
+    return j;
+}
+
+void launch_final(comp_ams *h, hipStream_t st, int set, const AmsParams &params)
+{
+    const FinalJob job = final_job(h, set, params);
+    launch_timed(h, P_TK_FINAL, st, [&] {
+        by_flag(h->params.stream_state, [&](auto ss) {
+            KLAUNCH((tk_final<decltype(ss)::value>), (unsigned)h->ge.n_tiles, kThreads, st, h->ge, job);
+        });
+    });
+}
+
+// Error feedback with Top-k / Rand-k.  The AMSGrad update of a step depends on its selection, and the selection
+// kernels are a chain of small launches that leave the chip idle; but nothing the NEXT step's listing pass and
+// selection read depends on the update.  So, outside graph capture, a step launches its listing pass and its
+// selection kernels and leaves its own update pending; the selection kernels of the next step carry that update
+// along as filler workgroups (run_filler), and whatever reads the state first - a getter, comp_ams_sync, a
+// checkpoint - launches a pending update on its own (flush_pending).  The two sets of records, lists and
+// directories alternate so that the lists an update still needs are not overwritten by the pass before it.
+// Recorded into a graph, a step is self-contained: pass, selection, update, all on one set.
 template <typename G>
-int step_topk(comp_ams *h, const G *g, hipStream_t st)
+int step_topk(comp_ams *h, const G *g, hipStream_t st, bool capturing)
 {
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
+    const int prev = h->par, cur = capturing ? prev : 1 - prev;
+    TkWorker *wp = h->ws2[prev], *wc = h->ws2[cur];
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand, h->cursor,
-                                                                       h->tile_dir);
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, wp, wc,
+                h->cand2[cur], h->cursor, h->tile_dir2[cur]);
     });
-    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
-                              h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
-    launch_timed(h, P_TK_FINAL, st, [&] {
-        by_flag(h->params.stream_state, [&](auto ss) {
-            KLAUNCH((tk_final<decltype(ss)::value>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir,
-                    h->theta, h->m, h->v, h->vhat, h->params);
-        });
+    FinalJob fill = final_job(h, prev, h->pending_params);
+    if (!h->final_pending) fill.tiles = 0;
+    by_flag(h->params.stream_state, [&](auto ss) {
+        launch_select<kSrcStored, float, decltype(ss)::value ? 2 : 1>(h, st, ge, wp, wc, h->cand2[cur], h->cursor,
+                                                                      h->tile_dir2[cur], h->hist1, h->histf, h->hist_full,
+                                                                      h->dense, h->dense_dir, h->e, nullptr,
+                                                                      kWorkerSelectSlots, fill);
     });
+    h->par = cur;
+    h->ws = h->ws2[cur];
+    h->cand = h->cand2[cur];
+    h->tile_dir = h->tile_dir2[cur];
+    if (capturing) {
+        launch_final(h, st, cur, h->params);
+    } else {
+        h->final_pending = true;
+        h->pending_params = h->params;
+    }
     return COMP_AMS_OK;
 }
 
-// Naive compression (Section 4) with Top-k: as step_topk, on g itself.
+// Naive compression (Section 4) with Top-k: pass, selection and update on g itself, one set of buffers.
 template <typename G>
 int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 {
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand,
-                h->cursor,
-                                                                          h->tile_dir);
+        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+                h->ws, h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
-                                h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
-    launch_timed(h, P_TK_FINAL, st, [&] {
-        by_flag(h->params.stream_state, [&](auto ss) {
-            KLAUNCH((tk_final<decltype(ss)::value>), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir,
-                    h->theta, h->m, h->v, h->vhat, h->params);
-        });
-    });
+    launch_select<kSrcGradOnly, G, 0>(h, st, ge, h->ws, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf,
+                                      h->hist_full, h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots, FinalJob{});
+    launch_final(h, st, h->par, h->params);
     return COMP_AMS_OK;
 }
 
@@ -651,22 +733,22 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom pge = pass_geometry<G>(h);
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws, h->cand, h->cursor,
-                                                                       h->tile_dir);
+        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+                h->ws, h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
-                            h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
+    launch_select<kSrcGrad, G, 0>(h, st, ge, h->ws, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                                  h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots, FinalJob{});
     launch_timed(h, P_TK_MERGE, st, [&] {
         KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
-        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(grid_blocks(ge.n_tiles, sv.ge.xcd_chunk), 1), kThreads, st, h->ghat_srv, h->gtil, sv.ge, sv.ws,
-                sv.cand,
-                                                                      sv.cursor, sv.tile_dir);
+        KLAUNCH((tk_pass1<kPassDiff, float>), dim3(grid_blocks(ge.n_tiles, sv.ge.xcd_chunk), 1), kThreads, st, h->ghat_srv,
+                h->gtil, sv.ge, sv.ws, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
     });
-    launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
-                            h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
+    launch_select<kSrcDiff, float, 0>(h, st, sv.ge, sv.ws, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
+                                      h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots,
+                                      FinalJob{});
     launch_timed(h, P_TK_APPLY, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
             KLAUNCH((tk_apply<decltype(ss)::value>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v,
@@ -685,6 +767,16 @@ void set_slices(TkGeom &ge, int slices)
     ge.slice_tiles = (ge.n_tiles + slices - 1) / slices;
     const int64_t want = (3 * (int64_t)ge.k / 2 + (int64_t)slices * 4096 - 1) / ((int64_t)slices * 4096);
     ge.parts = (int32_t)std::min<int64_t>({(int64_t)kMaxParts, (int64_t)kMaxPieces / (4 * slices), std::max<int64_t>(1, want)});
+    // Entries per region.  A vector's regions together hold twice max(4 k, d / 64) candidates: 1.2 k are listed in
+    // steady state (error feedback piles mass up just below the threshold), a first step or a step after a miss lists
+    // the coarse bin of the k-th largest and above (an eighth of an octave of magnitudes: about a hundredth of the
+    // coordinates of a gradient spread over several decades), and the factor two covers uneven regions.  What does
+    // not fit is found without lists (exact_select), which needs k entries in all: 8 k are there.  Never more than
+    // every coordinate of the region's tiles.
+    const int64_t full = (int64_t)ge.slice_tiles * kTile;
+    const int64_t cands = std::max<int64_t>(4 * (int64_t)ge.k, ge.d / 64);
+    const int64_t per_region = ((2 * cands + slices - 1) / slices + 1023) / 1024 * 1024;
+    ge.region_cap = (uint32_t)std::min<int64_t>(full, std::max<int64_t>(per_region, 2048));
 }
 
 // Initial selection records: no pending threshold, no guess.
@@ -704,12 +796,25 @@ int reset_topk_workers(comp_ams *h)
 {
     std::vector<TkWorker> init((size_t)h->n);
     fresh_tk_workers(init);
-    HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
+    for (int q = 0; q < 2; ++q)
+        HIP_TRY(h, hipMemcpy(h->ws2[q], init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
     HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * h->ge.slices * sizeof(uint32_t)));
     if (h->srv.ws) {
         HIP_TRY(h, hipMemcpy(h->srv.ws, init.data(), sizeof(TkWorker), hipMemcpyHostToDevice));
         HIP_TRY(h, hipMemset(h->srv.cursor, 0, (size_t)h->srv.ge.slices * sizeof(uint32_t)));
     }
+    return COMP_AMS_OK;
+}
+
+// Launches the update that the most recent step left pending (see step_topk, step_blocksign), on the handle's
+// stream.  Every entry point that reads or replaces state calls this first.
+int flush_pending(comp_ams *h)
+{
+    if (!h->final_pending) return COMP_AMS_OK;
+    if (is_sparse(h))
+        launch_final(h, h->stream, h->par, h->pending_params);
+    HIP_TRY(h, hipGetLastError());
+    h->final_pending = false;
     return COMP_AMS_OK;
 }
 
@@ -748,8 +853,20 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
     if (reinterpret_cast<uintptr_t>(grads_dev) & (sizeof(G) - 1))
         return fail(h, COMP_AMS_EINVAL, "grads must be %zu-byte aligned", sizeof(G));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    bool capturing = false;
+    {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cs) == hipSuccess)
+            capturing = (cs == hipStreamCaptureStatusActive);
+        else
+            (void)hipGetLastError();
+    }
+    if (capturing && h->final_pending)
+        return fail(h, COMP_AMS_ESTATE, "the update of the last step is still pending: call comp_ams_sync (or any getter) "
+                                        "before recording a step into a graph");
     if (st != h->stream) {
         // work of earlier steps on another stream must be finished before this stream touches the state
+        if ((rc = flush_pending(h))) return rc;
         HIP_TRY(h, hipStreamSynchronize(h->stream));
         h->stream = st;
     }
@@ -771,7 +888,7 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
     else if (is_sparse(h))
         rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
              : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
-                                                    : step_topk(h, grads_dev, st);
+                                                    : step_topk(h, grads_dev, st, capturing);
     else
         rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
     if (rc) return rc;
@@ -866,12 +983,16 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         while (slices > 1 && slices / 2 >= ge.n_tiles) slices /= 2;
         set_slices(ge, slices);
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
+        // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
+        // the whole vector after a miss) are kept to about two per compute unit in total
+        ge.pick_wgs = std::min<int32_t>(ge.relist_wgs, std::max(1, 512 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
-        const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.slice_tiles * kTile;
-        if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
+        const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.region_cap;
+        if ((rc = dev_alloc_t(h, h->allocs, &h->ws2[0], (size_t)n)) || (rc = dev_alloc_t(h, h->allocs, &h->ws2[1], (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand2[0], region_entries, false)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand2[1], region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * ge.slices)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->tile_dir2[0], segs)) || (rc = dev_alloc_t(h, h->allocs, &h->tile_dir2[1], segs)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist_full, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
@@ -881,6 +1002,9 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
             return bail(rc);
+        h->ws = h->ws2[0];
+        h->cand = h->cand2[0];
+        h->tile_dir = h->tile_dir2[0];
         if ((rc = reset_topk_workers(h))) return bail(rc);
     }
     apply_streaming(h);
@@ -912,7 +1036,7 @@ void comp_ams_destroy(comp_ams_t *h)
 
 int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_blocks)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "set_blocks needs a BLOCKSIGN handle");
     if (!offsets_host) return fail(h, COMP_AMS_EINVAL, "offsets is NULL");
@@ -934,7 +1058,7 @@ int comp_ams_set_blocks(comp_ams_t *h, const int64_t *offsets_host, int32_t n_bl
 
 int comp_ams_set_theta(comp_ams_t *h, const float *theta, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (!theta) return fail(h, COMP_AMS_EINVAL, "theta is NULL");
     return copy_in(h, h->theta, theta, (size_t)h->d, on_device);
@@ -1009,28 +1133,28 @@ int comp_ams_step_f16(comp_ams_t *h, const uint16_t *grads_f16_dev, void *hip_st
 
 int comp_ams_get_theta(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     return rc ? rc : copy_out(h, out, h->theta, (size_t)h->d, on_device);
 }
 int comp_ams_get_m(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     return rc ? rc : copy_out(h, out, h->m, (size_t)h->d, on_device);
 }
 int comp_ams_get_v(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     return rc ? rc : copy_out(h, out, h->v, (size_t)h->d, on_device);
 }
 int comp_ams_get_vhat(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     return rc ? rc : copy_out(h, out, h->vhat, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_error(comp_ams_t *h, int32_t worker, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->method != COMP_AMS_METHOD_EF)
         return fail(h, COMP_AMS_ESTATE, "this method keeps no error memory (CD-Adam: see comp_ams_get_ghat_worker)");
@@ -1094,7 +1218,7 @@ int gather_selected(comp_ams *h, const TkGeom &ge, int worker, const TkWorker *w
 
 int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, float *val_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selected needs a TOPK handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1106,7 +1230,7 @@ int comp_ams_get_selected(comp_ams_t *h, int32_t worker, uint32_t *idx_host, flo
 
 int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (!is_sparse(h) || h->method != COMP_AMS_METHOD_CD)
         return fail(h, COMP_AMS_ESTATE, "get_server_selected needs a TOPK handle set to CD-Adam");
@@ -1116,7 +1240,7 @@ int comp_ams_get_server_selected(comp_ams_t *h, uint32_t *idx_host, float *val_h
 
 int comp_ams_get_scales(comp_ams_t *h, float *out_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_scales needs a BLOCKSIGN handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1126,7 +1250,7 @@ int comp_ams_get_scales(comp_ams_t *h, float *out_host)
 
 int comp_ams_get_signs(comp_ams_t *h, int32_t worker, uint8_t *bits_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_signs needs a BLOCKSIGN handle");
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
@@ -1162,7 +1286,7 @@ int comp_ams_message_bytes(comp_ams_t *h, uint64_t *bytes)
 
 int comp_ams_pack_message(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
@@ -1243,7 +1367,7 @@ extern "C" {
 
 int comp_ams_pack_message_noalloc(comp_ams_t *h, int32_t who, void *buf_dev, uint64_t capacity, uint64_t *bytes)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (h->method == COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_ESTATE, "this handle does not compress");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
@@ -1303,7 +1427,7 @@ int32_t comp_ams_n_blocks(comp_ams_t *h)
 
 int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const float *vhat, const float *e, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     const size_t d = (size_t)h->d;
     if (m && (rc = copy_in(h, h->m, m, d, on_device))) return rc;
@@ -1325,7 +1449,7 @@ int comp_ams_set_state(comp_ams_t *h, const float *m, const float *v, const floa
 
 int comp_ams_sync(comp_ams_t *h)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return COMP_AMS_OK;
@@ -1333,7 +1457,7 @@ int comp_ams_sync(comp_ams_t *h)
 
 int comp_ams_profile(comp_ams_t *h, int enable)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     prof_clear(h);
@@ -1343,7 +1467,7 @@ int comp_ams_profile(comp_ams_t *h, int enable)
 
 int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (slot < 0) return fail(h, COMP_AMS_EINVAL, "slot must be >= 0");
     if (slot >= P_SLOTS) return 1;
@@ -1362,7 +1486,7 @@ int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double
 
 int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (!is_sparse(h)) return fail(h, COMP_AMS_ESTATE, "get_selection_info needs a TOPK handle");
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
@@ -1383,7 +1507,7 @@ int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_hos
 
 int comp_ams_set_method(comp_ams_t *h, int32_t method)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc) return rc;
     if (method < COMP_AMS_METHOD_EF || method > COMP_AMS_METHOD_NONE) return fail(h, COMP_AMS_EINVAL, "unknown method %d", method);
     if (method == h->method) return COMP_AMS_OK;
@@ -1401,12 +1525,13 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
             // ghat and gtilde are reused within the step if they are small enough to stay cached
             sv.ge.stream_rows = 2 * (size_t)h->ld * sizeof(float) > kCacheResidentBytes ? 1 : 0;
             sv.ge.relist_wgs = (int32_t)std::min<int64_t>(sv.ge.n_tiles, 2048);
+            sv.ge.pick_wgs = std::min<int32_t>(sv.ge.relist_wgs, 512);
             // one vector, all tiles: enough regions that a cursor sees few tens of atomic adds
             int slices = kMinSlices;
             while (slices < kMaxSlices && sv.ge.n_tiles / slices > 32) slices *= 2;
             set_slices(sv.ge, slices);
             const size_t tiles = (size_t)sv.ge.n_tiles;
-            const size_t region_entries = (size_t)sv.ge.slices * (size_t)sv.ge.slice_tiles * kTile;
+            const size_t region_entries = (size_t)sv.ge.slices * (size_t)sv.ge.region_cap;
             if ((rc = dev_alloc_t(h, h->allocs, &sv.ws, 1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.cand, region_entries, false)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.cursor, (size_t)sv.ge.slices)) ||
@@ -1438,7 +1563,7 @@ int need_cd(comp_ams *h)
 
 int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc || (rc = need_cd(h))) return rc;
     if (worker < 0 || worker >= h->n) return fail(h, COMP_AMS_EINVAL, "worker %d out of [0, %d)", worker, h->n);
     if (!out) return fail(h, COMP_AMS_EINVAL, "output pointer is NULL");
@@ -1451,21 +1576,21 @@ int comp_ams_get_ghat_worker(comp_ams_t *h, int32_t worker, float *out, int on_d
 
 int comp_ams_get_ghat_server(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc || (rc = need_cd(h))) return rc;
     return copy_out(h, out, h->ghat_srv, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_gtilde(comp_ams_t *h, float *out, int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc || (rc = need_cd(h))) return rc;
     return copy_out(h, out, h->gtil, (size_t)h->d, on_device);
 }
 
 int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc || (rc = need_cd(h))) return rc;
     if (h->compressor != COMP_AMS_BLOCKSIGN) return fail(h, COMP_AMS_ESTATE, "get_server_scales needs a BLOCKSIGN handle");
     if (h->steps == 0) return fail(h, COMP_AMS_ESTATE, "no step has run yet");
@@ -1475,7 +1600,7 @@ int comp_ams_get_server_scales(comp_ams_t *h, float *out_host)
 int comp_ams_set_markov_state(comp_ams_t *h, const float *ghat_workers, const float *ghat_server, const float *gtilde,
                               int on_device)
 {
-    ENTER_DEVICE(h);
+    ENTER_STATE(h);
     if (rc || (rc = need_cd(h))) return rc;
     const size_t d = (size_t)h->d;
     if (ghat_server && (rc = copy_in(h, h->ghat_srv, ghat_server, d, on_device))) return rc;

@@ -68,6 +68,7 @@ constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothin
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
 constexpr uint32_t kZeroTail = 2;            // value of TkWorker::whole
+constexpr uint32_t kExact = 3;               // value of TkWorker::whole: tk_exact has found Tc itself and listed the kept set
 
 
 struct TkWorker {
@@ -85,7 +86,12 @@ struct TkWorker {
     uint32_t step_word;     // Rand-k: TkRand::step_now of the step that left tc - the draw the deferred error memory
                             // must be read with.  Kept in device memory, not in a kernel argument, so that a step
                             // replayed from a HIP graph (which repeats its draw) still reads its predecessor's.
+    uint32_t overflow;      // tk_pass1 found a candidate region full: the lists are incomplete, tk_pick counts the
+                            // whole vector instead (as after a guess that was too high)
+    uint32_t overflow2;     // tk_relist found a region full as well: tk_exact takes over
+    uint32_t pad_;
 };
+static_assert(sizeof(TkWorker) == 56, "TkWorker is copied between host and device as plain bytes");
 
 // Rand-k: what the score of a coordinate depends on besides its index and the vector's number.
 struct TkRand {
@@ -104,9 +110,11 @@ struct TkGeom {
     int32_t idx_bits;       // IB
     uint32_t k;
     int32_t slices;         // candidate regions per vector (see region_base)
-    int32_t slice_tiles;    // tiles per candidate region = ceil(n_tiles / slices)
+    int32_t slice_tiles;    // tiles that append to one candidate region = ceil(n_tiles / slices)
+    uint32_t region_cap;    // entries a candidate region holds (see region_base)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
+    int32_t pick_wgs;       // workgroups per worker in tk_pick (one does the work unless the whole vector is counted)
     int32_t stream_rows;    // the stored rows are too large to stay cached between steps: tk_pass1 loads them as a stream
     int32_t xcd_chunk;      // tk_pass1: tile_of_block's chunk
     TkRand rand;
@@ -237,19 +245,55 @@ __device__ __forceinline__ void block_prefix(uint32_t v, uint32_t *pre, uint32_t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Where candidates live.  Each worker owns ge.slices regions of the candidate array; tile t appends
-// to region t mod slices, so workgroups that run at the same time (neighbouring tiles) use different
-// cursors.  Atomic adds on one cursor serialise at about a microsecond each, so a kernel of T tiles per
-// vector lasts at least T / slices microseconds: a single long vector (CD-Adam's server) takes more
-// regions than each of many workers.  A tile takes its space with one atomic add on the region's cursor and records
-// {offset, counts of its four wavefronts, total} in the tile directory; inside the tile's space the
-// candidates stand wavefront by wavefront.  A region can hold every coordinate of its tiles.  The order
-// of the tiles inside a region depends on timing; nothing downstream depends on it (comp values are
-// unique, the selection is a set).  Appending densely matters: per-tile fixed slots made the same
-// kernel 10 - 20 % slower (8-byte pieces scattered over gigabytes).
+// Where candidates live.  Each worker owns ge.slices regions of ge.region_cap entries in the candidate array,
+// one after the other; tile t appends to region t mod slices, so workgroups that run at the same time
+// (neighbouring tiles) use different cursors.  Atomic adds on one cursor serialise at about a microsecond
+// each, so a kernel of T tiles per vector lasts at least T / slices microseconds: a single long vector
+// (CD-Adam's server) takes more regions than each of many workers.  A tile takes its space with one atomic add
+// on the region's cursor and records {offset from the worker's first region, counts of its four wavefronts,
+// zeros} in the tile directory; inside the tile's space the candidates stand wavefront by wavefront.  The
+// order of the tiles inside a region depends on timing; nothing downstream depends on it (comp values are
+// unique, the selection is a set).  Appending densely matters: per-tile fixed slots made the same kernel
+// 10 - 20 % slower (8-byte pieces scattered over gigabytes).
+//
+// A region holds a bounded number of entries (the host sizes a worker's regions for twice max(4 k, d / 64)
+// candidates in all; 1.2 k are listed in steady state), not every coordinate of its tiles.  A tile that does not
+// fit sets the worker's overflow flag and stores nothing: the worker's lists are then incomplete and the step
+// goes on as after a guess that was too high - tk_pick counts the whole vector and tk_relist lists again with
+// the coarse bin of the k-th largest; if that does not fit either (thousands of equal magnitudes: nothing
+// narrower than the whole vector separates them), tk_exact selects without lists.
+__device__ __forceinline__ int64_t worker_base(const TkGeom &ge, int worker)
+{
+    return (int64_t)worker * ge.slices * ge.region_cap;
+}
 __device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int slice)
 {
-    return ((int64_t)worker * ge.slices + slice) * ge.slice_tiles * kTile;
+    return ((int64_t)worker * ge.slices + slice) * ge.region_cap;
+}
+
+// Takes `total` entries of region (i, t mod slices) for tile t and writes the tile's directory record; one
+// thread calls this.  cnt: the candidates of the tile's four wavefronts (each below 2^16: a wavefront owns
+// kSub = 1024 coordinates).  Returns the offset of the tile's space from the worker's first region, or
+// kNoSpace when the region is full - the record then says that nothing is stored and *overflow_flag is set.
+constexpr uint32_t kNoSpace = 0xffffffffu;
+__device__ __forceinline__ uint32_t take_space(const uint32_t (&cnt)[4], uint32_t zeros, const TkGeom &ge, int i, int t,
+                                               uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
+                                               uint32_t *overflow_flag)
+{
+    const uint32_t total = cnt[0] + cnt[1] + cnt[2] + cnt[3];
+    const int slice = t & (ge.slices - 1);
+    uint32_t at = 0;
+    if (total) {
+        at = atomicAdd(cursor + i * ge.slices + slice, total);
+        if (at > ge.region_cap || total > ge.region_cap - at) {
+            *overflow_flag = 1u;
+            tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(0u, 0u, 0u, zeros);
+            return kNoSpace;
+        }
+    }
+    at += (uint32_t)slice * ge.region_cap;
+    tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(at, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), zeros);
+    return at;
 }
 
 // First half of moving a tile's staged candidates (count per wavefront, in LDS) to its region: the
@@ -257,7 +301,8 @@ __device__ __forceinline__ int64_t region_base(const TkGeom &ge, int worker, int
 // tile's sum goes into the directory record).  Ends before the barrier so that the caller can put other
 // work between the atomic and its use.
 __device__ __forceinline__ void flush_begin(uint32_t count, uint32_t zeros, uint32_t *sh, int allocator, const TkGeom &ge,
-                                            int i, int t, uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
+                                            int i, int t, uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
+                                            uint32_t *overflow_flag)
 {
     const int tid = threadIdx.x;
     if ((tid & 63) == 0) {
@@ -266,22 +311,19 @@ __device__ __forceinline__ void flush_begin(uint32_t count, uint32_t zeros, uint
     }
     __syncthreads();
     if (tid == allocator) {
-        const uint32_t total = sh[0] + sh[1] + sh[2] + sh[3];
-        const uint32_t at = total ? atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total) : 0u;
-        sh[4] = at;
-        // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
-        tile_dir[(int64_t)i * ge.n_tiles + t] =
-            make_uint4(at, sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16), sh[5] + sh[6] + sh[7] + sh[8]);
+        const uint32_t cnt[4] = {sh[0], sh[1], sh[2], sh[3]};
+        sh[4] = take_space(cnt, sh[5] + sh[6] + sh[7] + sh[8], ge, i, t, cursor, tile_dir, overflow_flag);
     }
 }
 __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, const uint32_t *sh, const TkGeom &ge,
-                                          int i, int t, uint2 *__restrict__ cand)
+                                          int i, uint2 *__restrict__ cand)
 {
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint32_t off = sh[4];
+    if (off == kNoSpace) return;
     for (int w = 0; w < wave; ++w) off += sh[w];
-    uint2 *dst = cand + region_base(ge, i, t & (ge.slices - 1)) + off;
+    uint2 *dst = cand + worker_base(ge, i) + off;
     // the wavefront reads back its own LDS writes: no barrier needed for those
     for (uint32_t q = lane; q < count; q += kWave) dst[q] = stage[q];
 }
@@ -365,7 +407,8 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
 // zeros: this wavefront's count of exact zeros; the tile's sum goes into the directory record's last word.
 __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count, uint32_t zeros,
                                             const TkGeom &ge, int i, int t, uint2 *__restrict__ cand,
-                                            uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
+                                            uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
+                                            uint32_t *overflow_flag)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // this wavefront's staged candidates are complete before it registers
@@ -381,16 +424,11 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
     const uint32_t cnt[4] = {sh[0], sh[1], sh[2], sh[3]};
-    const uint32_t total = cnt[0] + cnt[1] + cnt[2] + cnt[3];
     uint32_t at = 0;
-    if (lane == 0) {
-        if (total) at = atomicAdd(cursor + i * ge.slices + (t & (ge.slices - 1)), total);
-        // the four counts fit 16 bits each: a wavefront owns kSub = 1024 coordinates
-        tile_dir[(int64_t)i * ge.n_tiles + t] =
-            make_uint4(at, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), sh[5] + sh[6] + sh[7] + sh[8]);
-    }
+    if (lane == 0) at = take_space(cnt, sh[5] + sh[6] + sh[7] + sh[8], ge, i, t, cursor, tile_dir, overflow_flag);
     at = __builtin_amdgcn_readfirstlane(at);
-    uint2 *dst = cand + region_base(ge, i, t & (ge.slices - 1)) + at;
+    if (at == kNoSpace) return;
+    uint2 *dst = cand + worker_base(ge, i) + at;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         for (uint32_t q = lane; q < cnt[w]; q += kWave) dst[q] = stage[w][q];
@@ -399,9 +437,12 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
 }
 
 // G: element type of g - float, or uint16_t (bfloat16 bits) for gradients handed over as bfloat16.
+// wp: the records the previous step left (its threshold, still pending on the stored rows, and the guess it
+// prepared); wc: the records of the running step (only the overflow flag is written here).  wp and wc may be
+// the same array.
 template <int kMode, typename G>
 __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, float *__restrict__ xs, TkGeom ge,
-                                                     const TkWorker *__restrict__ ws, uint2 *__restrict__ cand,
+                                                     const TkWorker *wp, TkWorker *wc, uint2 *__restrict__ cand,
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     __shared__ uint2 stage[4][kSub];
@@ -411,10 +452,10 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
-    const uint32_t guess = ws[i].guess;
-    const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
+    const uint32_t guess = wp[i].guess;
+    const KeptTest kt = kept_test(wp[i].tc, ge.idx_bits);
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const SelKey sk_prev = sel_key_of(ge.rand, ws[i].step_word, i);
+    const SelKey sk_prev = sel_key_of(ge.rand, wp[i].step_word, i);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
     if (tid == 0) sh[4] = 0;
@@ -427,22 +468,201 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     else
         count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
                                             stage[wave], ge.stream_rows, zeros);
-    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir);
+    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir, &wc[i].overflow);
 }
 
 // ---------------------------------------------------------------------------------------------
-// How the workgroups of tk_hist and tk_compact share a worker's candidates: blockIdx.x = slice *
-// parts + part, and a part is a contiguous piece of the slice's region.
+// The kept values of a tile, summed over the workers, and the AMSGrad update of the tile (tk_final's work).
+//
+// A coordinate of a tile belongs to one wavefront - the same one in tk_pass1, tk_relist and here -
+// and a tile's candidates are stored wavefront by wavefront, so each wavefront can sum the kept values
+// of its own coordinates without looking at the others: no workgroup barrier, and the ascending worker
+// order of the sum is just the order of its own instructions (within one worker the coordinates of
+// the kept candidates are distinct).
+constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in flight at a time
+
+// Adds, for the coordinates that wavefront `wave` (0..3) of a tile owns, the kept values (comp >= Tc_i) of all
+// workers into acc (LDS, kTile floats, zeroed by the caller for these coordinates) in ascending
+// worker order.  ws: the records that hold the selection's thresholds (and, for Rand-k, the draw they were made
+// with).  kScatter (CD-Adam, Algorithm 1, line 6): the kept value u = c_i[j] is also added to
+// ghat_i[j] in `rows` ([n][ld]); the old values are fetched for a whole batch before they are used.
+template <bool kScatter>
+__device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, const TkWorker *__restrict__ ws,
+                                              const uint2 *__restrict__ cand, const uint4 *__restrict__ tile_dir,
+                                              int t, float *__restrict__ rows, int wave)
+{
+    const uint32_t base = (uint32_t)t * kTile;
+    const int lane = threadIdx.x & 63;
+    for (int w0 = 0; w0 < ge.n; w0 += kWave) {
+        const int nw = min(kWave, ge.n - w0);
+        // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
+        uint32_t my_start = 0, my_count = 0;
+        uint64_t my_tc = kNoThreshold;
+        SelKey my_sk = {0u, 0u, 0u};
+        if (lane < nw) {
+            const uint4 rec = tile_dir[(int64_t)(w0 + lane) * ge.n_tiles + t];
+            const uint32_t c[4] = {rec.y & 0xffffu, rec.y >> 16, rec.z & 0xffffu, rec.z >> 16};
+            my_start = rec.x;
+            for (int q = 0; q < wave; ++q) my_start += c[q];
+            my_count = c[wave];
+            my_tc = ws[w0 + lane].tc;
+            my_sk = sel_key_of(ge.rand, ws[w0 + lane].step_word, w0 + lane);
+        }
+        for (int wb = 0; wb < nw; wb += kFinBatch) {
+            uint2 e[kFinBatch];
+            uint32_t cnt[kFinBatch];
+            bool keep[kFinBatch];
+            float old[kFinBatch];
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);           // clamped: the copies past nw are not used
+                cnt[u] = wb + u < nw ? (uint32_t)__shfl((int)my_count, w, kWave) : 0u;
+                const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
+                e[u] = make_uint2(0u, 0u);
+                if ((uint32_t)lane < cnt[u]) e[u] = cand[worker_base(ge, w0 + w) + start + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);
+                const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
+                const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
+                const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
+                SelKey sk = {0u, 0u, 0u};
+                if (ge.rand.on) sk = {1u, (uint32_t)__shfl((int)my_sk.a, w, kWave), (uint32_t)__shfl((int)my_sk.b, w, kWave)};
+                keep[u] = (uint32_t)lane < cnt[u] &&
+                          composite(sel_key(sk, __uint_as_float(e[u].y), e[u].x), e[u].x, ge.idx_bits) >= tc;
+                old[u] = 0.f;
+                if (kScatter && keep[u]) old[u] = rows[(int64_t)(w0 + w) * ge.ld + e[u].x];
+            }
+#pragma unroll
+            for (int u = 0; u < kFinBatch; ++u) {
+                const int w = min(wb + u, nw - 1);
+                if (keep[u]) {
+                    const float x = __uint_as_float(e[u].y);
+                    const uint32_t l = e[u].x - base;
+                    acc[l] = fadd(acc[l], x);
+                    if (kScatter) rows[(int64_t)(w0 + w) * ge.ld + e[u].x] = fadd(old[u], x);
+                }
+                if (cnt[u] > (uint32_t)kWave) {
+                    // more than 64 candidates of this worker in the wavefront's quarter of the tile (rare)
+                    const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
+                    const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
+                    const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
+                    const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
+                    const SelKey sk = {ge.rand.on, (uint32_t)__shfl((int)my_sk.a, w, kWave),
+                                       (uint32_t)__shfl((int)my_sk.b, w, kWave)};
+                    const uint2 *src = cand + worker_base(ge, w0 + w) + start;
+                    for (uint32_t q = kWave + lane; q < cnt[u]; q += kWave) {
+                        const uint2 c = src[q];
+                        const float x = __uint_as_float(c.y);
+                        if (composite(sel_key(sk, x, c.x), c.x, ge.idx_bits) >= tc) {
+                            const uint32_t l = c.x - base;
+                            acc[l] = fadd(acc[l], x);
+                            if (kScatter) {
+                                float *gh = rows + (int64_t)(w0 + w) * ge.ld + c.x;
+                                *gh = fadd(*gh, x);
+                            }
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // next worker's adds come after these
+            }
+        }
+    }
+}
+
+// What tk_final does for one tile: everything it reads besides the geometry.
+struct FinalJob {
+    const TkWorker *ws;          // records with the thresholds of the selection whose update this is
+    const uint2 *cand;
+    const uint4 *tile_dir;
+    float *theta, *m, *v, *vhat;
+    AmsParams p;
+    int32_t tile0, tiles;        // as a filler (see run_filler): the kernel's share is the tiles [tile0, tile0 + tiles)
+};
+
+// Server average and AMSGrad update of tile t by 256 threads (tid = 0..255, four wavefronts `wave` = tid / 64, which
+// need not start a workgroup).  acc: kTile floats of LDS of their own.  No workgroup barrier inside.
+template <bool kStreamState>
+__device__ __forceinline__ void final_tile(const FinalJob &job, const TkGeom &ge, int t, int tid, float *acc)
+{
+    const int64_t base = (int64_t)t * kTile;
+    const AmsParams &p = job.p;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    sum_kept_tile<false>(acc, ge, job.ws, job.cand, job.tile_dir, t, nullptr, tid >> 6);
+
+    // the state is loaded only now: fewer live registers above (more workgroups per compute unit),
+    // which measured faster than loading it first
+    float4 th[4], mm[4], vv[4], vh[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        th[r] = ld4_state<kStreamState>(job.theta + j);
+        mm[r] = ld4_state<kStreamState>(job.m + j);
+        vv[r] = ld4_state<kStreamState>(job.v + j);
+        vh[r] = ld4_state<kStreamState>(job.vhat + j);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int l = 4 * (tid + kThreads * r);
+        const int64_t j = base + l;
+        const float4 a = ld4(acc + l);
+        const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
+                                        fdiv(a.w, p.n_workers));
+        const float4 vh0 = vh[r];
+        amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
+        st4_state<kStreamState>(job.theta + j, th[r]);
+        st4_state<kStreamState>(job.m + j, mm[r]);
+        st4_state<kStreamState>(job.v + j, vv[r]);
+        // with a sparse average vhat = max(vhat, v) moves at few coordinates (v only decays elsewhere)
+        st4_if_changed<kStreamState>(job.vhat + j, vh[r], vh0);
+    }
+}
+
+template <bool kStreamState>
+__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, FinalJob job)
+{
+    __shared__ float acc[kTile];
+    final_tile<kStreamState>(job, ge, blockIdx.x, threadIdx.x, acc);
+}
+
+// The selection kernels of a step are small and bound by latency: launched alone they leave the chip idle for
+// tens of microseconds.  Under error feedback the AMSGrad update of the step BEFORE depends on nothing they
+// compute (and nothing they or tk_pass1 read depends on it), so the library defers it: each selection kernel of
+// step t + 1 is launched with extra workgroups - after its own, so that those start first - which work through a
+// share of the tiles of step t's update while the selection runs.  kFill: 0 no filler code, 1 filler with cached
+// state accesses, 2 filler with streamed state accesses.
+// own_blocks: the kernel's own workgroups.  acc: kTile floats of LDS per 256 threads of the workgroup.  Returns
+// true in the workgroups that are fillers (they have done their tiles and must leave).
+template <int kFill>
+__device__ __forceinline__ bool run_filler(const FinalJob &job, const TkGeom &ge, unsigned own_blocks, float *acc)
+{
+    if constexpr (kFill == 0) {
+        return false;
+    } else {
+        if (blockIdx.x < own_blocks) return false;
+        const int groups = blockDim.x / kThreads, group = threadIdx.x / kThreads;
+        const int q = (int)(blockIdx.x - own_blocks) * groups + group;
+        if (q < job.tiles) final_tile<kFill == 2>(job, ge, job.tile0 + q, threadIdx.x % kThreads, acc + group * kTile);
+        return true;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// How the workgroups of tk_hist and tk_compact share a worker's candidates: workgroup x = slice *
+// parts + part of the worker, and a part is a contiguous piece of the slice's region.
 struct Piece {
     int slice;
     uint32_t q0, q1;     // entries [q0, q1) of the region
 };
-__device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__restrict__ cursor, int worker)
+__device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__restrict__ cursor, int worker, int x)
 {
     Piece p;
-    p.slice = blockIdx.x / ge.parts;
-    const uint32_t part = blockIdx.x % ge.parts;
-    const uint32_t count = cursor[worker * ge.slices + p.slice];
+    p.slice = x / ge.parts;
+    const uint32_t part = x % ge.parts;
+    const uint32_t count = min(cursor[worker * ge.slices + p.slice], ge.region_cap);
     const uint32_t chunk = (count + ge.parts - 1) / ge.parts;
     p.q0 = min(part * chunk, count);
     p.q1 = min(p.q0 + chunk, count);
@@ -450,19 +670,32 @@ __device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__re
 }
 
 // Histograms of the candidates of a worker: coarse bins, and the fine bins of the two coarse bins
-// that start with the guess's.  Loads are issued four at a time.
-__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *__restrict__ ws,
+// that start with the guess's.  Loads are issued four at a time.  Grid: slices * parts workgroups per worker,
+// worker-major, then the fillers.
+template <int kFill>
+__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *wp, const TkWorker *wc,
                                                     const uint2 *__restrict__ cand,
                                                     const uint32_t *__restrict__ cursor,
-                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf)
+                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
+                                                    FinalJob job)
 {
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t lf[kFineWindow];
-    const int i = blockIdx.y;
+    union Lds {
+        struct {
+            uint32_t lh[kBins1];
+            uint32_t lf[kFineWindow];
+        } o;
+        float acc[kFill ? kTile : 1];
+    };
+    __shared__ Lds L;
+    const int per = ge.slices * ge.parts;
+    if (run_filler<kFill>(job, ge, (unsigned)(per * ge.n), L.acc)) return;
+    uint32_t *lh = L.o.lh, *lf = L.o.lf;
+    const int i = blockIdx.x / per;
     const int tid = threadIdx.x;
-    const Piece pc = piece_of(ge, cursor, i);
+    if (wc[i].overflow) return;                     // the lists are incomplete: tk_pick counts the vector itself
+    const Piece pc = piece_of(ge, cursor, i, blockIdx.x % per);
     if (pc.q0 >= pc.q1) return;
-    const uint32_t guess = ws[i].guess;
+    const uint32_t guess = wp[i].guess;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
@@ -529,45 +762,56 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const void *_
     }
 }
 
-// The leading digits of Tc.  Grid (P, n).  In the usual case the worker's candidates number at least k,
-// so the k-th largest is among them: workgroup 0 finds its coarse and (if the window covers it) fine
-// bin from the candidate histograms, and the other workgroups return at once.  With fewer than k
-// candidates (always on the first step, else when the threshold fell through the slack) the guess was
-// too high and nothing below it is known: then all P workgroups count the whole vector into the
-// worker's full coarse histogram, and tk_relist, which runs next, takes the coarse bin from it.
+// The leading digits of Tc.  P workgroups per worker (ge.pick_wgs), worker-major, then the fillers.  In the usual
+// case the worker's candidates number at least k, so the k-th largest is among them: workgroup 0 finds its coarse
+// and (if the window covers it) fine bin from the candidate histograms, and the other workgroups return at once.
+// With fewer than k candidates (always on the first step, else when the threshold fell through the slack) the guess
+// was too high and nothing below it is known, and when a region was full the lists are incomplete: then all P
+// workgroups count the whole vector into the worker's full coarse histogram, and tk_relist, which runs next, takes
+// the coarse bin from it.
 // Bin 0 (zeros and the smallest denormals) is not counted but taken as the remainder: in a sparse
 // vector it would draw most LDS atomics of a tile to one word.
 // Consumes (and clears) the candidate histograms.
-template <int kSrc, typename G>
-__global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
+template <int kSrc, typename G, int kFill>
+__global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *wp, TkWorker *wc,
                                                     uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
                                                     uint32_t *__restrict__ cursor, uint32_t *__restrict__ hist_full,
-                                                    const void *__restrict__ a, const float *__restrict__ b)
+                                                    const void *__restrict__ a, const float *__restrict__ b, FinalJob job)
 {
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t part[kThreads / kWave];
-    __shared__ uint32_t res[4];
-    __shared__ uint32_t fres[3];
-    __shared__ uint32_t total_sh;
-    const int i = blockIdx.y;
+    union Lds {
+        struct {
+            uint32_t lh[kBins1];
+            uint32_t part[kThreads / kWave];
+            uint32_t res[4];
+            uint32_t fres[3];
+            uint32_t total_sh;
+        } o;
+        float acc[kFill ? kTile : 1];
+    };
+    __shared__ Lds L;
+    if (run_filler<kFill>(job, ge, (unsigned)(ge.pick_wgs * ge.n), L.acc)) return;
+    uint32_t *lh = L.o.lh, *part = L.o.part, *res = L.o.res, *fres = L.o.fres;
+    const int i = blockIdx.x / ge.pick_wgs;
+    const int bx = blockIdx.x % ge.pick_wgs;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t guess = ws[i].guess;
+    const uint32_t guess = wp[i].guess;
+    const bool overflow = wc[i].overflow != 0u;
     if (wave == 0) {
         // number of candidates of this worker = sum of its region cursors
         uint32_t c = 0;
         for (int q = lane; q < ge.slices; q += kWave) c += cursor[i * ge.slices + q];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
-        if (lane == 0) total_sh = c;
+        if (lane == 0) L.o.total_sh = c;
     }
     __syncthreads();
-    const uint32_t total = total_sh;
+    const uint32_t total = L.o.total_sh;
     uint32_t *row = hist1 + (int64_t)i * kBins1;
     uint32_t *frow = histf + (int64_t)i * kFineWindow;
 
-    if (total >= ge.k) {
-        if (blockIdx.x != 0) return;
+    if (total >= ge.k && !overflow) {
+        if (bx != 0) return;
         // every element at or above the guess is listed and there are at least k of them: the k-th
         // largest is a candidate and the candidate histograms locate it
         for (int q = tid; q < kBins1; q += kThreads) lh[q] = row[q];
@@ -604,41 +848,42 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         }
         __syncthreads();   // every thread has read the histograms before they are cleared
         if (tid == 0) {
-            ws[i].prefix = prefix;
-            ws[i].pshift = pshift;
-            ws[i].rank = rank;
-            ws[i].whole = (count == rank) ? 1u : 0u;
-            ws[i].relisted = 0u;
+            wc[i].prefix = prefix;
+            wc[i].pshift = pshift;
+            wc[i].rank = rank;
+            wc[i].whole = (count == rank) ? 1u : 0u;
+            wc[i].relisted = 0u;
         }
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
         return;
     }
 
-    if (kSrc == kSrcStored && !ge.rand.on && guess == 0u) {
+    if (kSrc == kSrcStored && !ge.rand.on && guess == 0u && !overflow) {
         // error feedback with magnitude keys: a guess of 0 lists every non-zero element, and there are fewer
         // than k of them - the k-th largest is a zero.  All candidates are kept; tk_resolve places the threshold
         // among the zeros, which are ordered by index alone, from the zero counts of the tiles.
-        if (blockIdx.x != 0) return;
+        if (bx != 0) return;
         if (tid == 0) {
-            ws[i].prefix = 0u;
-            ws[i].pshift = kShift1;
-            ws[i].rank = ge.k - total;          // so many zeros are kept, the lowest indices first
-            ws[i].whole = kZeroTail;
-            ws[i].relisted = 0u;
+            wc[i].prefix = 0u;
+            wc[i].pshift = kShift1;
+            wc[i].rank = ge.k - total;          // so many zeros are kept, the lowest indices first
+            wc[i].whole = kZeroTail;
+            wc[i].relisted = 0u;
         }
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
         return;
     }
 
-    // the guess was too high: count the whole vector (tk_relist continues from the full histogram)
+    // the guess was too high (or the lists did not fit): count the whole vector (tk_relist continues from the
+    // full histogram)
     for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
     __syncthreads();
     const uint32_t d = (uint32_t)ge.d;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
+    for (int t = bx; t < ge.n_tiles; t += ge.pick_wgs) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
         load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
@@ -656,8 +901,8 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         const uint32_t c = lh[q];
         if (c) atomicAdd(hist_full + (int64_t)i * kBins1 + q, c);
     }
-    if (blockIdx.x == 0) {
-        if (tid == 0) ws[i].relisted = 1u;
+    if (bx == 0) {
+        if (tid == 0) wc[i].relisted = 1u;
         for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
@@ -667,22 +912,32 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
 // Only for workers whose guess was too high: takes the coarse bin of the k-th largest from the full
 // histogram tk_pick has just counted (every workgroup works it out for itself; workgroup 0 records
 // it) and lists the elements in that bin or above into the (emptied) regions of the worker.  A small
-// grid whose workgroups loop over tiles: in the usual case every workgroup returns at once, and a
-// small grid does that fast.
-template <int kSrc, typename G>
+// grid (ge.relist_wgs workgroups per worker, worker-major, then the fillers) whose workgroups loop over tiles:
+// in the usual case every workgroup returns at once, and a small grid does that fast.  A region that fills up
+// sets overflow2: tk_compact's first workgroup of the worker then selects without lists (exact_select).
+template <int kSrc, typename G, int kFill>
 __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a, const float *__restrict__ b,
-                                                      TkGeom ge, TkWorker *__restrict__ ws,
+                                                      TkGeom ge, TkWorker *wc,
                                                       const uint32_t *__restrict__ hist_full,
                                                       uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                                      uint4 *__restrict__ tile_dir)
+                                                      uint4 *__restrict__ tile_dir, FinalJob job)
 {
-    __shared__ uint2 stage[4][kSub];
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t part[kThreads / kWave];
-    __shared__ uint32_t res[4];
-    __shared__ uint32_t sh[9];
-    const int i = blockIdx.y;
-    if (!ws[i].relisted) return;
+    union Lds {
+        struct {
+            uint2 stage[4][kSub];
+            uint32_t lh[kBins1];
+            uint32_t part[kThreads / kWave];
+            uint32_t res[4];
+            uint32_t sh[9];
+        } o;
+        float acc[kFill ? kTile : 1];
+    };
+    __shared__ Lds L;
+    if (run_filler<kFill>(job, ge, (unsigned)(ge.relist_wgs * ge.n), L.acc)) return;
+    uint32_t *lh = L.o.lh, *part = L.o.part, *res = L.o.res, *sh = L.o.sh;
+    const int i = blockIdx.x / ge.relist_wgs;
+    const int bx = blockIdx.x % ge.relist_wgs;
+    if (!wc[i].relisted) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t d = (uint32_t)ge.d;
@@ -703,14 +958,14 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
     }
     const uint32_t prefix = res[0];
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    if (blockIdx.x == 0 && tid == 0) {
-        ws[i].prefix = prefix;
-        ws[i].pshift = kShift1;
-        ws[i].rank = ge.k - res[1];
-        ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
+    if (bx == 0 && tid == 0) {
+        wc[i].prefix = prefix;
+        wc[i].pshift = kShift1;
+        wc[i].rank = ge.k - res[1];
+        wc[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
     }
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
+    for (int t = bx; t < ge.n_tiles; t += ge.relist_wgs) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
         load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
@@ -727,30 +982,153 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
                     hit = hit && !zero;
                 }
                 const uint32_t slot = wave_append(hit, count);
-                if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
+                if (hit) L.o.stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
             }
-        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir);
-        flush_end(stage[wave], count, sh, ge, i, t, cand);
+        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir, &wc[i].overflow2);
+        flush_end(L.o.stage[wave], count, sh, ge, i, cand);
         __syncthreads();   // sh and stage are reused by the next tile
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Selection without lists, for a vector whose candidates fit no region even after tk_relist (so many elements
+// share the leading bits of the k-th largest that only the whole composite key tells them apart - all-equal
+// input is the extreme).  One workgroup of 256 threads: the digits of Tc by counting over the whole vector,
+// re-formed tile by tile from what is stored (kDigit bits per sweep), then one more sweep that lists exactly the
+// kept elements - k of them, which always fit: a worker's regions hold at least 8 k entries in all, and this
+// list is written as one run from the worker's first region (no cursors, no atomics; a tile's record holds its
+// offset in that run).  Slow (one compute unit reads the vector up to seven times) and meant to be: it only has
+// to be right.  Leaves Tc in wc[i].tc and whole = kExact; tk_resolve takes it from there.
+constexpr int kExactDigit = 11;
+struct ExactLds {
+    uint2 stage[4][kSub];
+    uint32_t lh[kBins1];
+    uint32_t part[kThreads / kWave];
+    uint32_t res[4];
+    uint32_t sh[9];
+};
+static_assert((1 << kExactDigit) == kBins1, "exact_select counts into kBins1 bins");
+
+template <int kSrc, typename G>
+__device__ __forceinline__ void exact_select(const void *__restrict__ a, const float *__restrict__ b, const TkGeom &ge,
+                                             int i, TkWorker *wc, uint2 *__restrict__ cand,
+                                             uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir, ExactLds &L)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const uint32_t d = (uint32_t)ge.d;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
+    const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
+    int s_hi = 31 + ge.idx_bits;                     // bits of comp still open
+    uint64_t prefix = 0;
+    uint32_t rank = ge.k;
+    uint64_t tc = 0;
+    while (true) {
+        const int s_lo = max(s_hi - kExactDigit, 0);
+        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
+        for (int q = tid; q < kBins1; q += kThreads) L.lh[q] = 0;
+        __syncthreads();
+        for (int t = 0; t < ge.n_tiles; ++t) {
+            const uint32_t base = (uint32_t)t * kTile;
+            float x[4][4];
+            load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t j = base + 4 * (tid + kThreads * r) + c;
+                    const uint64_t comp = composite(sel_key(sk, x[r][c], j), j, ge.idx_bits);
+                    if (j < d && (comp >> s_hi) == prefix) atomicAdd(&L.lh[(uint32_t)(comp >> s_lo) & mask], 1u);
+                }
+        }
+        __syncthreads();
+        find_rank_bin(L.lh, L.part, L.res, kBins1, rank);          // rank <= elements under the prefix
+        prefix = (prefix << (s_hi - s_lo)) | L.res[0];
+        rank -= L.res[1];
+        const uint32_t left = L.res[2];
+        __syncthreads();
+        if (s_lo == 0 || left == rank) {                            // last digit, or all under this prefix are kept
+            tc = prefix << s_lo;
+            break;
+        }
+        s_hi = s_lo;
+    }
+    // the kept elements, tile by tile, as one run from the start of the worker's space
+    uint32_t run = 0;                                               // uniform over the workgroup
+    for (int t = 0; t < ge.n_tiles; ++t) {
+        const uint32_t base = (uint32_t)t * kTile;
+        float x[4][4];
+        load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
+        uint32_t count = 0, zeros = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t j = base + 4 * (tid + kThreads * r) + c;
+                bool hit = j < d && composite(sel_key(sk, x[r][c], j), j, ge.idx_bits) >= tc;
+                if (kSrc == kSrcStored && !sk.on) {          // zeros are counted, not listed (as in tk_pass1)
+                    const bool zero = j < d && mag_key(x[r][c]) == 0u;
+                    zeros += (uint32_t)__popcll(__ballot(zero));
+                    hit = hit && !zero;
+                }
+                const uint32_t slot = wave_append(hit, count);
+                if (hit) L.stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
+            }
+        if (lane == 0) {
+            L.sh[wave] = count;
+            L.sh[5 + wave] = zeros;
+        }
+        __syncthreads();
+        const uint32_t cnt[4] = {L.sh[0], L.sh[1], L.sh[2], L.sh[3]};
+        if (tid == 0)
+            tile_dir[(int64_t)i * ge.n_tiles + t] =
+                make_uint4(run, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), L.sh[5] + L.sh[6] + L.sh[7] + L.sh[8]);
+        uint32_t off = run;
+        for (int w = 0; w < wave; ++w) off += cnt[w];
+        uint2 *dst = cand + worker_base(ge, i) + off;
+        for (uint32_t q = lane; q < count; q += kWave) dst[q] = L.stage[wave][q];
+        run += cnt[0] + cnt[1] + cnt[2] + cnt[3];
+        __syncthreads();   // sh and stage are reused by the next tile
+    }
+    if (tid == 0) {
+        wc[i].tc = tc;
+        wc[i].whole = kExact;
+    }
+    (void)cursor;
 }
 
 // Copies the candidates that carry the prefix, as comp values, to the dense storage.  Each wavefront
 // takes a quarter of the workgroup's piece and writes its hits from the start of that quarter
 // onwards (as many slots as it reads, so it cannot overflow), and records {start, count} relative to
-// the worker's first region; no atomics, tk_resolve walks the records.
-__global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
-                                                       const uint2 *__restrict__ cand,
-                                                       const uint32_t *__restrict__ cursor,
-                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir)
+// the worker's first region; no atomics, tk_resolve walks the records.  Grid: slices * parts workgroups per
+// worker, worker-major, then the fillers.  For a worker whose lists did not fit (overflow2) there is nothing to
+// copy: its first workgroup runs exact_select instead, the others leave.
+template <int kSrc, typename G, int kFill>
+__global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, TkWorker *wc, uint2 *__restrict__ cand,
+                                                       uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
+                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir,
+                                                       const void *__restrict__ a, const float *__restrict__ b,
+                                                       FinalJob job)
 {
-    const int i = blockIdx.y;
-    if (ws[i].whole) return;
+    union Lds {
+        ExactLds o;
+        float acc[kFill ? kTile : 1];
+    };
+    __shared__ Lds L;
+    const int per = ge.slices * ge.parts;
+    if (run_filler<kFill>(job, ge, (unsigned)(per * ge.n), L.acc)) return;
+    const int i = blockIdx.x / per;
+    const int bx = blockIdx.x % per;
+    if (wc[i].overflow2) {
+        if (bx == 0) exact_select<kSrc, G>(a, b, ge, i, wc, cand, cursor, tile_dir, L.o);
+        return;
+    }
+    if (wc[i].whole) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    const uint32_t prefix = wc[i].prefix, pshift = wc[i].pshift;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const Piece pc = piece_of(ge, cursor, i);
+    const Piece pc = piece_of(ge, cursor, i, bx);
     const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
     const uint32_t w0 = min(pc.q0 + wave * quarter, pc.q1), w1 = min(w0 + quarter, pc.q1);
     const int64_t rbase = region_base(ge, i, pc.slice);
@@ -773,8 +1151,8 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
         }
     }
     if (lane == 0) {
-        const int64_t rec = ((int64_t)i * gridDim.x + blockIdx.x) * 4 + wave;
-        dense_dir[rec] = make_uint2((uint32_t)(rbase - region_base(ge, i, 0)) + w0, count);
+        const int64_t rec = ((int64_t)i * per + bx) * 4 + wave;
+        dense_dir[rec] = make_uint2((uint32_t)(rbase - worker_base(ge, i)) + w0, count);
     }
 }
 
@@ -869,20 +1247,23 @@ __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, ui
 // Records the finished selection of a worker and prepares the next step's guess: a few fine bins
 // below this threshold - at least twice the distance the threshold just fell (a rising threshold needs
 // no slack), never less than kMinSlack, shrinking by one bin per quiet step, doubled after a miss.
-// One thread calls this.
-__device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorker &w, uint64_t tc, const TkGeom &ge,
+// prev: the record the step before left (its slack and threshold bin).  Writes the whole record wc[i] - the
+// flags of the running step are cleared for the step that uses this record next.  One thread calls this.
+__device__ __forceinline__ void finish_worker(TkWorker *wc, int i, const TkWorker &prev, uint64_t tc, const TkGeom &ge,
                                               bool missed)
 {
-    ws[i].tc = tc;
-    ws[i].step_word = ge.rand.step_now;
+    wc[i].tc = tc;
+    wc[i].step_word = ge.rand.step_now;
     const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
-    const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
-    uint32_t slack = missed ? w.slack * 2u : w.slack - 1u;
+    const uint32_t fell = (prev.last_fine != kNoGuess && prev.last_fine > fine) ? prev.last_fine - fine : 0u;
+    uint32_t slack = missed ? prev.slack * 2u : prev.slack - 1u;
     slack = max(slack, 2u * fell + 2u);
     slack = min(max(slack, max(kMinSlack, ge.rand.min_slack)), kMaxSlack);
-    ws[i].slack = slack;
-    ws[i].last_fine = fine;
-    ws[i].guess = fine > slack ? fine - slack : 0u;
+    wc[i].slack = slack;
+    wc[i].last_fine = fine;
+    wc[i].guess = fine > slack ? fine - slack : 0u;
+    wc[i].overflow = 0u;
+    wc[i].overflow2 = 0u;
 }
 
 // Exclusive prefix sum of one value per thread over the 1024 threads of tk_resolve; returns the exclusive sum,
@@ -955,26 +1336,42 @@ __device__ __forceinline__ uint64_t zero_tail_threshold(const uint4 *__restrict_
 }
 
 // xs: the stored rows under error feedback with magnitude keys (where zeros are counted instead of listed and
-// the threshold may lie among them), else null.
-__global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
+// the threshold may lie among them), else null.  wp: the records of the step before (slack, last threshold bin);
+// wc: those of the running step, completed here.  Grid: one workgroup per worker, then the fillers (four tiles
+// per workgroup of 1024 threads).
+struct ResolveOwn {
+    ResolveLds L;
+    uint32_t rpre[kMaxPieces + 1];
+    uint32_t rstart[kMaxPieces];
+};
+template <int kFill>
+__global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, const TkWorker *wp, TkWorker *wc,
                                                               const uint64_t *__restrict__ dense,
                                                               const uint2 *__restrict__ dense_dir,
                                                               uint32_t *__restrict__ cursor,
                                                               uint32_t *__restrict__ hist_full,
                                                               const uint4 *__restrict__ tile_dir,
-                                                              const float *__restrict__ xs)
+                                                              const float *__restrict__ xs, FinalJob job)
 {
-    __shared__ ResolveLds L;
-    __shared__ uint32_t rpre[kMaxPieces + 1];
-    __shared__ uint32_t rstart[kMaxPieces];
+    union Lds {
+        ResolveOwn o;
+        float acc[kFill ? (kResolveThreads / kThreads) * kTile : 1];
+    };
+    __shared__ Lds S;
+    if (run_filler<kFill>(job, ge, (unsigned)ge.n, S.acc)) return;
+    ResolveLds &L = S.o.L;
+    uint32_t *rpre = S.o.rpre, *rstart = S.o.rstart;
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const TkWorker w = ws[i];
+    const TkWorker w = wc[i];
+    const TkWorker prev = wp[i];
     const int s_hi = (int)w.pshift + ge.idx_bits;
     uint64_t tc = (uint64_t)w.prefix << s_hi;
     const uint4 *dir_row = tile_dir + (int64_t)i * ge.n_tiles;
-    if (w.whole == kZeroTail) {
+    if (w.whole == kExact) {
+        tc = w.tc;                                   // exact_select has found it
+    } else if (w.whole == kZeroTail) {
         tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank, L);
     } else if (!w.whole) {
         const int pieces = ge.slices * ge.parts * 4;
@@ -1038,150 +1435,9 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
         for (int q = tid; q < kBins1; q += kResolveThreads) hist_full[(int64_t)i * kBins1 + q] = 0;
-    if (tid == 0) finish_worker(ws, i, w, tc, ge, w.relisted != 0);
+    if (tid == 0) finish_worker(wc, i, prev, tc, ge, w.relisted != 0);
 }
 
-// ---------------------------------------------------------------------------------------------
-// A coordinate of a tile belongs to one wavefront - the same one in tk_pass1, tk_relist and here -
-// and a tile's candidates are stored wavefront by wavefront, so each wavefront can sum the kept values
-// of its own coordinates without looking at the others: no workgroup barrier, and the ascending worker
-// order of the sum is just the order of its own instructions (within one worker the coordinates of
-// the kept candidates are distinct).
-constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in flight at a time
-
-// Adds, for the calling wavefront's coordinates of tile t, the kept values (comp >= Tc_i) of all
-// workers into acc (LDS, kTile floats, zeroed by the caller for these coordinates) in ascending
-// worker order.  kScatter (CD-Adam, Algorithm 1, line 6): the kept value u = c_i[j] is also added to
-// ghat_i[j] in `rows` ([n][ld]); the old values are fetched for a whole batch before they are used.
-template <bool kScatter>
-__device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, const TkWorker *__restrict__ ws,
-                                              const uint2 *__restrict__ cand, const uint4 *__restrict__ tile_dir,
-                                              int t, float *__restrict__ rows)
-{
-    const int slice = t & (ge.slices - 1);
-    const uint32_t base = (uint32_t)t * kTile;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int w0 = 0; w0 < ge.n; w0 += kWave) {
-        const int nw = min(kWave, ge.n - w0);
-        // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
-        uint32_t my_start = 0, my_count = 0;
-        uint64_t my_tc = kNoThreshold;
-        const SelKey my_sk = sel_key_of(ge.rand, ge.rand.step_now, w0 + lane);
-        if (lane < nw) {
-            const uint4 rec = tile_dir[(int64_t)(w0 + lane) * ge.n_tiles + t];
-            const uint32_t c[4] = {rec.y & 0xffffu, rec.y >> 16, rec.z & 0xffffu, rec.z >> 16};
-            my_start = rec.x;
-            for (int q = 0; q < wave; ++q) my_start += c[q];
-            my_count = c[wave];
-            my_tc = ws[w0 + lane].tc;
-        }
-        for (int wb = 0; wb < nw; wb += kFinBatch) {
-            uint2 e[kFinBatch];
-            uint32_t cnt[kFinBatch];
-            bool keep[kFinBatch];
-            float old[kFinBatch];
-#pragma unroll
-            for (int u = 0; u < kFinBatch; ++u) {
-                const int w = min(wb + u, nw - 1);           // clamped: the copies past nw are not used
-                cnt[u] = wb + u < nw ? (uint32_t)__shfl((int)my_count, w, kWave) : 0u;
-                const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
-                e[u] = make_uint2(0u, 0u);
-                if ((uint32_t)lane < cnt[u]) e[u] = cand[region_base(ge, w0 + w, slice) + start + lane];
-            }
-#pragma unroll
-            for (int u = 0; u < kFinBatch; ++u) {
-                const int w = min(wb + u, nw - 1);
-                const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
-                const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
-                const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
-                SelKey sk = {0u, 0u, 0u};
-                if (ge.rand.on) sk = {1u, (uint32_t)__shfl((int)my_sk.a, w, kWave), (uint32_t)__shfl((int)my_sk.b, w, kWave)};
-                keep[u] = (uint32_t)lane < cnt[u] &&
-                          composite(sel_key(sk, __uint_as_float(e[u].y), e[u].x), e[u].x, ge.idx_bits) >= tc;
-                old[u] = 0.f;
-                if (kScatter && keep[u]) old[u] = rows[(int64_t)(w0 + w) * ge.ld + e[u].x];
-            }
-#pragma unroll
-            for (int u = 0; u < kFinBatch; ++u) {
-                const int w = min(wb + u, nw - 1);
-                if (keep[u]) {
-                    const float x = __uint_as_float(e[u].y);
-                    const uint32_t l = e[u].x - base;
-                    acc[l] = fadd(acc[l], x);
-                    if (kScatter) rows[(int64_t)(w0 + w) * ge.ld + e[u].x] = fadd(old[u], x);
-                }
-                if (cnt[u] > (uint32_t)kWave) {
-                    // more than 64 candidates of this worker in the wavefront's quarter of the tile (rare)
-                    const uint32_t tc_lo = (uint32_t)__shfl((int)(uint32_t)my_tc, w, kWave);
-                    const uint32_t tc_hi = (uint32_t)__shfl((int)(uint32_t)(my_tc >> 32), w, kWave);
-                    const uint64_t tc = ((uint64_t)tc_hi << 32) | tc_lo;
-                    const uint32_t start = (uint32_t)__shfl((int)my_start, w, kWave);
-                    const SelKey sk = {ge.rand.on, (uint32_t)__shfl((int)my_sk.a, w, kWave),
-                                       (uint32_t)__shfl((int)my_sk.b, w, kWave)};
-                    const uint2 *src = cand + region_base(ge, w0 + w, slice) + start;
-                    for (uint32_t q = kWave + lane; q < cnt[u]; q += kWave) {
-                        const uint2 c = src[q];
-                        const float x = __uint_as_float(c.y);
-                        if (composite(sel_key(sk, x, c.x), c.x, ge.idx_bits) >= tc) {
-                            const uint32_t l = c.x - base;
-                            acc[l] = fadd(acc[l], x);
-                            if (kScatter) {
-                                float *gh = rows + (int64_t)(w0 + w) * ge.ld + c.x;
-                                *gh = fadd(*gh, x);
-                            }
-                        }
-                    }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // next worker's adds come after these
-            }
-        }
-    }
-}
-
-template <bool kStreamState>
-__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
-                                                     const uint2 *__restrict__ cand,
-                                                     const uint4 *__restrict__ tile_dir,
-                                                     float *__restrict__ theta, float *__restrict__ m,
-                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
-{
-    __shared__ float acc[kTile];
-    const int t = blockIdx.x;
-    const int64_t base = (int64_t)t * kTile;
-    const int tid = threadIdx.x;
-
-#pragma unroll
-    for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    sum_kept_tile<false>(acc, ge, ws, cand, tile_dir, t, nullptr);
-
-    // the state is loaded only now: fewer live registers above (more workgroups per compute unit),
-    // which measured faster than loading it first
-    float4 th[4], mm[4], vv[4], vh[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4_state<kStreamState>(theta + j);
-        mm[r] = ld4_state<kStreamState>(m + j);
-        vv[r] = ld4_state<kStreamState>(v + j);
-        vh[r] = ld4_state<kStreamState>(vhat + j);
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int l = 4 * (tid + kThreads * r);
-        const int64_t j = base + l;
-        const float4 a = ld4(acc + l);
-        const float4 gbar = make_float4(fdiv(a.x, p.n_workers), fdiv(a.y, p.n_workers), fdiv(a.z, p.n_workers),
-                                        fdiv(a.w, p.n_workers));
-        const float4 vh0 = vh[r];
-        amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4_state<kStreamState>(theta + j, th[r]);
-        st4_state<kStreamState>(m + j, mm[r]);
-        st4_state<kStreamState>(v + j, vv[r]);
-        // with a sparse average vhat = max(vhat, v) moves at few coordinates (v only decays elsewhere)
-        st4_if_changed<kStreamState>(vhat + j, vh[r], vh0);
-    }
-}
 
 // CD-Adam (Algorithm 1): selection buffers of the server's own Top-k - the same structures as the
 // workers', for a single vector.
@@ -1208,7 +1464,7 @@ __global__ __launch_bounds__(kThreads) void tk_merge(TkGeom ge, const TkWorker *
 #pragma unroll
     for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    sum_kept_tile<true>(acc, ge, ws, cand, tile_dir, t, ghat_rows);
+    sum_kept_tile<true>(acc, ge, ws, cand, tile_dir, t, ghat_rows, tid >> 6);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int l = 4 * (tid + kThreads * r);
@@ -1241,8 +1497,8 @@ __global__ __launch_bounds__(kThreads) void tk_apply(TkSide sv, float *__restric
         uint32_t start = rec.x;
         for (int q = 0; q < wave; ++q) start += c[q];
         const uint64_t tc = sv.ws[0].tc;
-        const SelKey sk = sel_key_of(sv.ge.rand, sv.ge.rand.step_now, 0);
-        const uint2 *src = sv.cand + region_base(sv.ge, 0, t & (sv.ge.slices - 1)) + start;
+        const SelKey sk = sel_key_of(sv.ge.rand, sv.ws[0].step_word, 0);
+        const uint2 *src = sv.cand + start;          // a single vector: its space starts the array
         for (uint32_t q = lane; q < c[wave]; q += kWave) {
             const uint2 e = src[q];
             const float x = __uint_as_float(e.y);
@@ -1304,9 +1560,9 @@ __global__ __launch_bounds__(kThreads) void tk_gather_selected(TkGeom ge, int wo
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x;
     const uint64_t tc = ws[worker].tc;
-    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, worker);
+    const SelKey sk = sel_key_of(ge.rand, ws[worker].step_word, worker);
     const uint4 rec = tile_dir[(int64_t)worker * ge.n_tiles + t];
-    const uint2 *src = cand + region_base(ge, worker, t & (ge.slices - 1)) + rec.x;
+    const uint2 *src = cand + worker_base(ge, worker) + rec.x;
     const uint32_t total = (rec.y & 0xffffu) + (rec.y >> 16) + (rec.z & 0xffffu) + (rec.z >> 16);
     for (uint32_t q0 = 0; q0 < total; q0 += kThreads) {      // uniform over the workgroup
         const uint32_t q = q0 + threadIdx.x;

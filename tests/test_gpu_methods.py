@@ -237,6 +237,7 @@ def test_a_step_can_be_captured_in_a_graph_and_replayed(comp, kb, method):
             gpu.step(gbuf)
             ora.step(grads[t])
     side.synchronize()
+    gpu.sync()                                             # nothing of the eager steps may be pending at capture
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
         gpu.step(gbuf)                                     # recorded, not run
