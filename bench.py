@@ -89,6 +89,8 @@ def kernel_algorithmic_bytes(name: str, n: int, d: int, method: str = "ef") -> i
     naive = method == "naive"         # naive compression reads g only
     return {
         "bs_pass": (4 if naive else 12) * nd,
+        # one launch: the pass of this step and the deferred update of the step before
+        "bs_pass_update": 12 * nd + 32 * d,
         "bs_update": 32 * d,
         # CD-Adam with Top-k only reads g and ghat_i in the pass (ghat_i changes on the k kept coordinates)
         "tk_pass1": (4 if naive else 8 if method == "cd" else 12) * nd,
@@ -212,7 +214,7 @@ def main() -> int:
                       "us_per_step": ms * 1e3 / args.steps} for name, (ms, cnt) in prof.items()}
     dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
     dom_bytes = kernel_algorithmic_bytes(dom, w.n, w.d, args.method)
-    if bf16 and dom in ("bs_pass", "tk_pass1", "plain_update"):
+    if bf16 and dom in ("bs_pass", "bs_pass_update", "tk_pass1", "plain_update"):
         dom_bytes -= 2 * w.n * w.d
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9

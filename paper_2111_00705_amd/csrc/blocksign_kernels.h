@@ -484,6 +484,137 @@ __global__ __launch_bounds__(kThreads) void bs_update(int64_t d, int64_t ld, int
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Error feedback with uniform blocks of whole tiles (at most kMaxFusedPieces each), one launch per step.
+// The AMSGrad update of a step depends on nothing but that step's sign words and piece sums, and the next step's
+// pass reads neither theta, m, v nor vhat: so the update of step t is deferred and runs inside the pass kernel of
+// step t + 1, as extra workgroups that are dispatched first (blockIdx.y < 4: the four quarters of every tile;
+// blockIdx.y >= 4: the pass of worker blockIdx.y - 4).  On small models the update alone is a chain of latencies
+// on a mostly idle chip (293 workgroups for 1.2 M coordinates); inside the pass it costs its bytes.  Sign words
+// and piece sums exist twice and alternate: the pass of step t + 1 writes one set while the update of step t reads
+// the other.  The scales of step t are formed from its piece sums where they are needed - by the pass (the
+// deferred error of the stored rows) and by the update - with the same arithmetic: the fp64 sum of the block's
+// pieces in coordinate order, one division, one rounding.
+struct BsDeferred {
+    const uint16_t *signs_prev;     // [n][n_tiles][256] sign words of the step whose update is pending
+    const double *partial_prev;     // [n][n_pieces] its piece sums (also what the pass takes the pending scales from)
+    float *scales_out;              // [n][n_blocks] the update writes that step's scales here (for the getters)
+    float *theta, *m, *v, *vhat;
+    AmsParams p;                    // hyper-parameters of the step whose update is pending
+    int32_t do_update;              // 0: nothing is pending (first step, or the update has been run on its own)
+};
+
+// The scale of block b = the tile's block for worker i from that worker's piece sums (uniform tiles).
+__device__ __forceinline__ float fused_block_scale(const double *__restrict__ prow, int b, const BsTable &tb, int n_tiles,
+                                                   int64_t d)
+{
+    const int q0 = b * tb.uniform_tiles, q1 = min(q0 + tb.uniform_tiles, n_tiles);
+    const double len = (double)min((int64_t)tb.uniform_tiles * kTile, d - (int64_t)q0 * kTile);
+    double S = 0.0;
+    for (int q = q0; q < q1; ++q) S += prow[q];
+    return (float)(S / len);
+}
+
+template <bool kPending, typename G, bool kStreamState>
+__global__ __launch_bounds__(kThreads) void bs_pass_update(const G *__restrict__ g, float *__restrict__ xs, int64_t d,
+                                                           int64_t ld, int n, BsTable tb,
+                                                           uint16_t *__restrict__ signs, double *__restrict__ partial,
+                                                           BsDeferred df)
+{
+    __shared__ double scratch[4];
+    __shared__ float s_lds[kScaleChunk];
+    // dynamic LDS: none is used; the amount only sets how many workgroups share a compute unit (see bs_pass)
+    const int n_tiles = (int)(ld / kTile);
+    const int t = tile_of_block(blockIdx.x, tb.xcd_chunk);
+    if (t >= n_tiles) return;
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)t * kTile;
+    const int b = t / tb.uniform_tiles;
+
+    if (blockIdx.y < 4) {
+        // ---- the pending update of quarter r of tile t: coordinates base + 4 (tid + 256 r) + c
+        if (!df.do_update) return;
+        const int r = blockIdx.y;
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        const float4 th0 = ld4_state<kStreamState>(df.theta + j), m0 = ld4_state<kStreamState>(df.m + j),
+                     v0 = ld4_state<kStreamState>(df.v + j), vh0 = ld4_state<kStreamState>(df.vhat + j);
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        const uint16_t *srow = df.signs_prev + (int64_t)t * kThreads + tid;
+        const int64_t sstride = (int64_t)n_tiles * kThreads;
+        const bool first_tile = (t == b * tb.uniform_tiles);
+        for (int c0 = 0; c0 < n; c0 += kScaleChunk) {
+            const int cn = min(kScaleChunk, n - c0);
+            __syncthreads();
+            for (int u = tid; u < cn; u += kThreads) {          // one thread per worker: the scale of this tile's block
+                const float s = fused_block_scale(df.partial_prev + (int64_t)(c0 + u) * tb.n_pieces, b, tb, n_tiles, d);
+                s_lds[u] = s;
+                if (first_tile && r == 0) df.scales_out[(int64_t)(c0 + u) * tb.n_blocks + b] = s;
+            }
+            __syncthreads();
+            for (int u0 = 0; u0 < cn; u0 += kSignBatch) {
+                uint32_t bits[kSignBatch];
+#pragma unroll
+                for (int u = 0; u < kSignBatch; ++u) bits[u] = (u0 + u < cn) ? (uint32_t)srow[(c0 + u0 + u) * sstride] : 0u;
+#pragma unroll
+                for (int u = 0; u < kSignBatch; ++u) {
+                    if (u0 + u < cn) {
+                        const float s = s_lds[u0 + u];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[c] = fadd(acc[c], signed_scale(s, bits[u], r * 4 + c));
+                    }
+                }
+            }
+        }
+        // padding coordinates take no gradient
+        const float4 gbar = make_float4(j < d ? fdiv(acc[0], df.p.n_workers) : 0.f, j + 1 < d ? fdiv(acc[1], df.p.n_workers) : 0.f,
+                                        j + 2 < d ? fdiv(acc[2], df.p.n_workers) : 0.f, j + 3 < d ? fdiv(acc[3], df.p.n_workers) : 0.f);
+        float4 th = th0, mm = m0, vv = v0, vh = vh0;
+        amsgrad_update4(th, mm, vv, vh, gbar, df.p);
+        st4_state<kStreamState>(df.theta + j, th);
+        st4_state<kStreamState>(df.m + j, mm);
+        st4_state<kStreamState>(df.v + j, vv);
+        st4_state<kStreamState>(df.vhat + j, vh);
+        return;
+    }
+
+    // ---- the pass of worker i over tile t (one piece: the tile lies inside block b)
+    const int i = blockIdx.y - 4;
+    const G *grow = g + (int64_t)i * d;
+    float *xrow = xs + (int64_t)i * ld;
+    float4 gv[4], xv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        gv[r] = load_grad4(grow, j, d);
+        xv[r] = ld4_row(xrow + j, tb.stream_rows);
+    }
+    const float s_prev = kPending ? fused_block_scale(df.partial_prev + (int64_t)i * tb.n_pieces, b, tb, n_tiles, d) : 0.f;
+    float x[4][4];
+    uint32_t sign_bits = 0;
+    double a64 = 0.0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = base + 4 * (tid + kThreads * r);
+        const float gg[4] = {gv[r].x, gv[r].y, gv[r].z, gv[r].w};
+        const float xx[4] = {xv[r].x, xv[r].y, xv[r].z, xv[r].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float e = kPending ? deferred_sign_error(xx[c], s_prev) : xx[c];
+            x[r][c] = (j + c < d) ? fadd(gg[c], e) : 0.f;
+        }
+        st4_stream(xrow + j, make_float4(x[r][0], x[r][1], x[r][2], x[r][3]));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) sign_bits |= (__float_as_uint(x[r][c]) >> 31) << (r * 4 + c);
+    }
+    signs[((int64_t)i * n_tiles + t) * kThreads + tid] = (uint16_t)sign_bits;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a64 += (double)fabsf(x[r][c]);
+    const double S = block_sum(a64, scratch);
+    if (tid == 0) partial[(int64_t)i * tb.n_pieces + t] = S;
+}
+
 // Wire form of the sign bits of one vector: output word q holds the coordinates 32 q .. 32 q + 31, bit
 // j % 32 for coordinate j (set = negative), zero past d.  Those 32 coordinates are eight consecutive
 // float4 of one row r of the tile, i.e. the r-th nibble of eight consecutive sign words.

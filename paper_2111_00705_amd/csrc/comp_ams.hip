@@ -62,6 +62,11 @@ struct comp_ams {
     double *partial = nullptr;
     float *scales = nullptr;
     uint16_t *signs = nullptr;                 // [n][n_tiles][256] sign bits of the stored x
+    // sign words and piece sums exist twice and alternate while the update is deferred (step_blocksign_deferred);
+    // signs / partial always point at the set of the most recent step
+    uint16_t *signs2[2] = {nullptr, nullptr};
+    double *partial2[2] = {nullptr, nullptr};
+    int bs_set = 0;
     bool pending = false;
     bool fused_scale = false;                  // bs_update forms the scales itself (see kMaxFusedPieces)
 
@@ -73,27 +78,24 @@ struct comp_ams {
     double *partial_srv = nullptr;                // [n_pieces]
     float *scales_srv = nullptr;                  // [n_blocks]
 
-    // Top-k.  The records, candidate lists and tile directory exist twice: under error feedback the AMSGrad update of
-    // a step is deferred into the selection kernels of the next one (see step_topk), which fill the other set
-    // meanwhile.  ws / cand / tile_dir always point at the set of the most recent step.
+    // An update that the most recent step left to the next one (see step_blocksign), and the hyper-parameters it
+    // must run with (those of its own step)
+    bool final_pending = false;
+    AmsParams pending_params{};
+
+    // Top-k
     TkGeom ge{};
     TkWorker *ws = nullptr;
     uint2 *cand = nullptr;                     // [n][slices][region_cap] candidate (index, value bits)
     uint32_t *cursor = nullptr;                // [n][slices] entries in each region (zero between steps)
     uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in the worker's space, counts per wavefront, zeros}
-    TkWorker *ws2[2] = {nullptr, nullptr};
-    uint2 *cand2[2] = {nullptr, nullptr};
-    uint4 *tile_dir2[2] = {nullptr, nullptr};
-    int par = 0;                               // which set ws / cand / tile_dir point at
-    bool final_pending = false;                // the update of the most recent step has not been launched yet ...
-    AmsParams pending_params{};                // ... and the hyper-parameters it must run with (those of its step)
     uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
-    uint16_t *signs2[2] = {nullptr, nullptr};  // block sign, deferred update: see step_blocksign
-    double *partial2[2] = {nullptr, nullptr};
+
     uint2 *dense_dir = nullptr;                // [n][64 * parts * 4] {start, count} of each wavefront's piece
+    uint32_t *small_ctr = nullptr;             // [n] short vectors (step_topk_small): entries listed
     uint32_t *sel_count = nullptr, *sel_out_idx = nullptr;
     float *sel_out_val = nullptr;
     // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
@@ -218,11 +220,11 @@ namespace {
 
 enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
                 P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_TK_MERGE, P_TK_PASS1_SERVER,
-                P_TK_SELECT_SERVER, P_TK_APPLY, P_PLAIN_UPDATE, P_SLOTS };
+                P_TK_SELECT_SERVER, P_TK_APPLY, P_PLAIN_UPDATE, P_BS_PASS_UPDATE, P_SLOTS };
 const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
                                          "tk_relist", "tk_compact", "tk_resolve", "tk_final", "bs_server",
                                          "bs_scale_server", "bs_apply", "tk_merge", "tk_pass1_server", "tk_select_server",
-                                         "tk_apply", "plain_update"};
+                                         "tk_apply", "plain_update", "bs_pass_update"};
 
 // Kernel launches of a step go through KLAUNCH.  With profiling on, launch_timed hands the launch a
 // pair of events through t_ev0 / t_ev1 and the kernel is started with hipExtLaunchKernel, which stamps
@@ -379,7 +381,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     if (scale_list.empty()) scale_list.push_back(0);
     std::vector<void *> fresh;
     int32_t *d_off = nullptr, *d_hi = nullptr, *d_blk = nullptr, *d_tp = nullptr, *d_bp = nullptr, *d_sl = nullptr;
-    double *d_partial = nullptr, *d_partial_srv = nullptr;
+    double *d_partial = nullptr, *d_partial_b = nullptr, *d_partial_srv = nullptr;
     float *d_scales = nullptr, *d_scales_srv = nullptr;
     int rc;
     auto upload = [&](int32_t **dst, const std::vector<int32_t> &src) -> int {
@@ -391,6 +393,7 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
     if ((rc = upload(&d_off, off32)) || (rc = upload(&d_hi, piece_hi)) || (rc = upload(&d_blk, piece_blk)) ||
         (rc = upload(&d_tp, tile_piece0)) || (rc = upload(&d_bp, block_piece0)) || (rc = upload(&d_sl, scale_list)) ||
         (rc = dev_alloc_t(h, fresh, &d_partial, (size_t)h->n * piece_hi.size())) ||
+        (rc = dev_alloc_t(h, fresh, &d_partial_b, (size_t)h->n * piece_hi.size())) ||
         (rc = dev_alloc_t(h, fresh, &d_scales, (size_t)h->n * nb)) ||
         (rc = dev_alloc_t(h, fresh, &d_partial_srv, piece_hi.size())) ||
         (rc = dev_alloc_t(h, fresh, &d_scales_srv, (size_t)nb))) {
@@ -420,7 +423,9 @@ int build_block_table(comp_ams *h, const std::vector<int64_t> &off, int64_t unif
         for (int b = 0; b < nb && ok; ++b) ok = (block_piece0[b + 1] - block_piece0[b] <= kMaxFusedPieces);
         h->fused_scale = ok;
     }
-    h->partial = d_partial;
+    h->partial2[0] = d_partial;
+    h->partial2[1] = d_partial_b;
+    h->partial = h->partial2[h->bs_set];
     h->scales = d_scales;
     h->partial_srv = d_partial_srv;
     h->scales_srv = d_scales_srv;
@@ -477,12 +482,34 @@ int copy_in(comp_ams *h, float *dst_dev, const float *src, size_t count, int on_
     return COMP_AMS_OK;
 }
 
+// bs_update for the sign words, piece sums and scales of the most recent step, with the hyper-parameters p.
+void launch_bs_update(comp_ams *h, hipStream_t st, const AmsParams &p)
+{
+    const BsTable &tb = h->tb;
+    const unsigned ugrid = (unsigned)(h->ld / kTile);
+    launch_timed(h, P_BS_UPDATE, st, [&] {
+        // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
+        // workgroups per compute unit
+        const bool early = h->ld / kTile < 2048;
+#define CAMS_BS_UPDATE(F, E)                                                                                  \
+    by_flag(h->params.stream_state, [&](auto ss) {                                                            \
+        KLAUNCH((bs_update<F, E, false, decltype(ss)::value>), ugrid, kThreads, st, h->d, h->ld, h->n, tb,   \
+                h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, p, BsMarkov{});               \
+    })
+        if (h->fused_scale) {
+            if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
+        } else {
+            if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
+        }
+#undef CAMS_BS_UPDATE
+    });
+}
+
 template <typename G>
 int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
 {
     const BsTable &tb = h->tb;
     const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n);
-    const unsigned ugrid = (unsigned)(h->ld / kTile);
     const unsigned lds = sizeof(G) == 2 ? h->pass_lds16 : h->pass_lds;
     launch_timed(h, P_BS_PASS, st, [&] {
         if (h->method == COMP_AMS_METHOD_NAIVE)   // C(g_i) itself: the stored rows are not touched
@@ -499,23 +526,53 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
         launch_timed(h, P_BS_SCALE, st, [&] {
             KLAUNCH((bs_scale), dim3(tb.n_scale_list, h->n), kWave, st, h->partial, tb, h->scales);
         });
-    launch_timed(h, P_BS_UPDATE, st, [&] {
-        // few tiles: nothing hides the state loads, so issue them first; many tiles: load late, run more
-        // workgroups per compute unit
-        const bool early = h->ld / kTile < 2048;
-#define CAMS_BS_UPDATE(F, E)                                                                                  \
-    by_flag(h->params.stream_state, [&](auto ss) {                                                            \
-        KLAUNCH((bs_update<F, E, false, decltype(ss)::value>), ugrid, kThreads, st, h->d, h->ld, h->n, tb,   \
-                h->partial, h->scales, h->signs, h->theta, h->m, h->v, h->vhat, h->params, BsMarkov{});       \
-    })
-        if (h->fused_scale) {
-            if (early) CAMS_BS_UPDATE(true, true); else CAMS_BS_UPDATE(true, false);
-        } else {
-            if (early) CAMS_BS_UPDATE(false, true); else CAMS_BS_UPDATE(false, false);
-        }
-#undef CAMS_BS_UPDATE
-    });
+    launch_bs_update(h, st, h->params);
     h->pending = (h->method == COMP_AMS_METHOD_EF);
+    return COMP_AMS_OK;
+}
+
+// Error feedback where every block is a run of at most kMaxFusedPieces whole tiles (uniform blocks of a multiple of
+// 4096 coordinates): one launch per step.  The update of a step is left pending and runs inside the next step's
+// pass kernel (bs_pass_update); whatever reads the state first launches a pending update on its own
+// (flush_pending).  Not used while the stream is being captured: a recorded step must be self-contained.
+inline bool can_defer_blocksign(const comp_ams *h)
+{
+    return h->method == COMP_AMS_METHOD_EF && h->fused_scale && h->tb.uniform_tiles > 0;
+}
+
+template <typename G>
+int step_blocksign_deferred(comp_ams *h, const G *g, hipStream_t st)
+{
+    const BsTable &tb = h->tb;
+    const int prev = h->bs_set, cur = 1 - prev;
+    const dim3 grid(grid_blocks(h->ld / kTile, tb.xcd_chunk), h->n + 4);
+    const unsigned lds = sizeof(G) == 2 ? h->pass_lds16 : h->pass_lds;
+    BsDeferred df{};
+    df.signs_prev = h->signs2[prev];
+    df.partial_prev = h->partial2[prev];
+    df.scales_out = h->scales;
+    df.theta = h->theta;
+    df.m = h->m;
+    df.v = h->v;
+    df.vhat = h->vhat;
+    df.p = h->pending_params;
+    df.do_update = h->final_pending ? 1 : 0;
+    launch_timed(h, P_BS_PASS_UPDATE, st, [&] {
+        by_flag(h->params.stream_state, [&](auto ss) {
+            if (h->pending)
+                KLAUNCH_LDS((bs_pass_update<true, G, decltype(ss)::value>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, h->n,
+                            tb, h->signs2[cur], h->partial2[cur], df);
+            else
+                KLAUNCH_LDS((bs_pass_update<false, G, decltype(ss)::value>), grid, kThreads, lds, st, g, h->e, h->d, h->ld, h->n,
+                            tb, h->signs2[cur], h->partial2[cur], df);
+        });
+    });
+    h->bs_set = cur;
+    h->signs = h->signs2[cur];
+    h->partial = h->partial2[cur];
+    h->pending = true;
+    h->final_pending = true;
+    h->pending_params = h->params;
     return COMP_AMS_OK;
 }
 
@@ -574,54 +631,32 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 // The five selection launches between the listing pass and the kernel that uses Tc: candidate
 // histograms, leading digits, second listing (rare), compaction of the threshold bin (or, rarer still, the
 // selection without lists), last digits.  kSrc / a / b say how tk_relist forms the compressed vector again.
-// wp / wc: the records of the step before and of the running step (the same array unless the update is deferred).
-// fill: an update that these kernels carry along as fillers (tiles == 0: none); kFill as in run_filler.
-constexpr int kFillWeights[5] = {2, 1, 1, 2, 3};   // shares of the deferred update's tiles, by kernel
-
-template <int kSrc, typename G, int kFill>
-void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, const TkWorker *wp, TkWorker *wc, uint2 *cand,
-                   uint32_t *cursor, uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full,
-                   uint64_t *dense, uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5],
-                   const FinalJob &fill)
+template <int kSrc, typename G>
+void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
+                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint64_t *dense,
+                   uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5])
 {
-    // each kernel's share of the filler tiles
-    FinalJob job[5];
-    unsigned extra[5];
-    {
-        int wsum = 0, given = 0, acc = 0;
-        for (int q = 0; q < 5; ++q) wsum += kFillWeights[q];
-        for (int q = 0; q < 5; ++q) {
-            acc += kFillWeights[q];
-            const int upto = kFill ? (int)((int64_t)fill.tiles * acc / wsum) : 0;
-            job[q] = fill;
-            job[q].tile0 = fill.tile0 + given;
-            job[q].tiles = upto - given;
-            given = upto;
-            const int per_wg = (q == 4) ? kResolveThreads / kThreads : 1;
-            extra[q] = (unsigned)((job[q].tiles + per_wg - 1) / per_wg);
-        }
-    }
-    const unsigned shared = (unsigned)(ge.slices * ge.parts * ge.n);
-    launch_timed(h, slot[0], st, [&] {
-        KLAUNCH((tk_hist<kFill>), shared + extra[0], kThreads, st, ge, wp, wc, cand, cursor, hist1, histf, job[0]);
-    });
+    const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
+    // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
+    // the whole vector after a miss) are kept to about two per compute unit in total
+    const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
+    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1,
+            histf); });
     launch_timed(h, slot[1], st, [&] {
-        KLAUNCH((tk_pick<kSrc, G, kFill>), (unsigned)(ge.pick_wgs * ge.n) + extra[1], kThreads, st, ge, wp, wc, hist1, histf,
-                cursor, hist_full, a, b, job[1]);
+        KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, hist_full, a, b);
     });
     launch_timed(h, slot[2], st, [&] {
-        KLAUNCH((tk_relist<kSrc, G, kFill>), (unsigned)(ge.relist_wgs * ge.n) + extra[2], kThreads, st, a, b, ge, wc, hist_full,
-                cand, cursor, tile_dir, job[2]);
+        KLAUNCH((tk_relist<kSrc, G>), sweep, kThreads, st, a, b, ge, ws, hist_full, cand, cursor, tile_dir);
     });
     launch_timed(h, slot[3], st, [&] {
-        KLAUNCH((tk_compact<kSrc, G, kFill>), shared + extra[3], kThreads, st, ge, wc, cand, cursor, tile_dir, dense, dense_dir,
-                a, b, job[3]);
+        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir);
     });
     launch_timed(h, slot[4], st, [&] {
         // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
         const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
-        KLAUNCH((tk_resolve<kFill>), (unsigned)ge.n + extra[4], kResolveThreads, st, ge, wp, wc, dense, dense_dir, cursor,
-                hist_full, tile_dir, rows, job[4]);
+        const ExactSource es{kSrc, std::is_same<G, float>::value ? 0 : std::is_same<G, uint16_t>::value ? 1 : 2, a, b};
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, cand, tile_dir, rows,
+                es);
     });
 }
 
@@ -629,70 +664,49 @@ constexpr int kWorkerSelectSlots[5] = {P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_C
 constexpr int kServerSelectSlots[5] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER,
                                        P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
 
-// What tk_final needs for the update that follows the selection recorded in set `set` of the handle.
-FinalJob final_job(const comp_ams *h, int set, const AmsParams &params)
+void launch_final(comp_ams *h, hipStream_t st)
 {
-    FinalJob j{};
-    j.ws = h->ws2[set];
-    j.cand = h->cand2[set];
-    j.tile_dir = h->tile_dir2[set];
-    j.theta = h->theta;
-    j.m = h->m;
-    j.v = h->v;
-    j.vhat = h->vhat;
-    j.p = params;
-    j.tile0 = 0;
-    j.tiles = h->ge.n_tiles;
-    return j;
-}
-
-void launch_final(comp_ams *h, hipStream_t st, int set, const AmsParams &params)
-{
-    const FinalJob job = final_job(h, set, params);
     launch_timed(h, P_TK_FINAL, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
-            KLAUNCH((tk_final<decltype(ss)::value>), (unsigned)h->ge.n_tiles, kThreads, st, h->ge, job);
+            KLAUNCH((tk_final<decltype(ss)::value>), h->ge.n_tiles, kThreads, st, h->ge, h->ws, h->cand, h->tile_dir,
+                    h->theta, h->m, h->v, h->vhat, h->params);
         });
     });
 }
 
-// Error feedback with Top-k / Rand-k.  The AMSGrad update of a step depends on its selection, and the selection
-// kernels are a chain of small launches that leave the chip idle; but nothing the NEXT step's listing pass and
-// selection read depends on the update.  So, outside graph capture, a step launches its listing pass and its
-// selection kernels and leaves its own update pending; the selection kernels of the next step carry that update
-// along as filler workgroups (run_filler), and whatever reads the state first - a getter, comp_ams_sync, a
-// checkpoint - launches a pending update on its own (flush_pending).  The two sets of records, lists and
-// directories alternate so that the lists an update still needs are not overwritten by the pass before it.
-// Recorded into a graph, a step is self-contained: pass, selection, update, all on one set.
+// Error feedback on a short vector: listing pass, one selection kernel (tk_small_select), update - three launches.
 template <typename G>
-int step_topk(comp_ams *h, const G *g, hipStream_t st, bool capturing)
+int step_topk_small(comp_ams *h, const G *g, hipStream_t st)
 {
+    TkGeom sge = h->ge;
+    sge.region_cap = (uint32_t)sge.slices * sge.region_cap;      // one region per worker: all of its space
+    sge.slices = 1;
+    sge.slice_tiles = sge.n_tiles;
+    sge.xcd_chunk = 0;
+    launch_timed(h, P_TK_PASS1, st, [&] {
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(sge.n_tiles, h->n), kThreads, st, g, h->e, sge, h->ws, h->cand, h->small_ctr,
+                h->tile_dir);
+    });
+    launch_timed(h, P_TK_RESOLVE, st, [&] {
+        KLAUNCH((tk_small_select), (unsigned)h->n, kResolveThreads, st, sge, h->ws, h->cand, h->small_ctr, h->tile_dir, h->e);
+    });
+    launch_final(h, st);
+    return COMP_AMS_OK;
+}
+
+template <typename G>
+int step_topk(comp_ams *h, const G *g, hipStream_t st)
+{
+    if (h->ge.n_tiles <= kSmallTiles) return step_topk_small(h, g, st);
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
-    const int prev = h->par, cur = capturing ? prev : 1 - prev;
-    TkWorker *wp = h->ws2[prev], *wc = h->ws2[cur];
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, wp, wc,
-                h->cand2[cur], h->cursor, h->tile_dir2[cur]);
+        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+                h->cand, h->cursor, h->tile_dir);
     });
-    FinalJob fill = final_job(h, prev, h->pending_params);
-    if (!h->final_pending) fill.tiles = 0;
-    by_flag(h->params.stream_state, [&](auto ss) {
-        launch_select<kSrcStored, float, decltype(ss)::value ? 2 : 1>(h, st, ge, wp, wc, h->cand2[cur], h->cursor,
-                                                                      h->tile_dir2[cur], h->hist1, h->histf, h->hist_full,
-                                                                      h->dense, h->dense_dir, h->e, nullptr,
-                                                                      kWorkerSelectSlots, fill);
-    });
-    h->par = cur;
-    h->ws = h->ws2[cur];
-    h->cand = h->cand2[cur];
-    h->tile_dir = h->tile_dir2[cur];
-    if (capturing) {
-        launch_final(h, st, cur, h->params);
-    } else {
-        h->final_pending = true;
-        h->pending_params = h->params;
-    }
+    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                                     h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
+    launch_final(h, st);
     return COMP_AMS_OK;
 }
 
@@ -704,11 +718,11 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
         KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
-                h->ws, h->cand, h->cursor, h->tile_dir);
+                h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGradOnly, G, 0>(h, st, ge, h->ws, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf,
-                                      h->hist_full, h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots, FinalJob{});
-    launch_final(h, st, h->par, h->params);
+    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                                   h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
+    launch_final(h, st);
     return COMP_AMS_OK;
 }
 
@@ -734,21 +748,20 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
         KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
-                h->ws, h->cand, h->cursor, h->tile_dir);
+                h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGrad, G, 0>(h, st, ge, h->ws, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
-                                  h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots, FinalJob{});
+    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+                               h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
     });
     launch_timed(h, P_TK_PASS1_SERVER, st, [&] {
         KLAUNCH((tk_pass1<kPassDiff, float>), dim3(grid_blocks(ge.n_tiles, sv.ge.xcd_chunk), 1), kThreads, st, h->ghat_srv,
-                h->gtil, sv.ge, sv.ws, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
+                h->gtil, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
     });
-    launch_select<kSrcDiff, float, 0>(h, st, sv.ge, sv.ws, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
-                                      h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots,
-                                      FinalJob{});
+    launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
+                                   h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
             KLAUNCH((tk_apply<decltype(ss)::value>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v,
@@ -796,9 +809,9 @@ int reset_topk_workers(comp_ams *h)
 {
     std::vector<TkWorker> init((size_t)h->n);
     fresh_tk_workers(init);
-    for (int q = 0; q < 2; ++q)
-        HIP_TRY(h, hipMemcpy(h->ws2[q], init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
+    HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
     HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * h->ge.slices * sizeof(uint32_t)));
+    HIP_TRY(h, hipMemset(h->small_ctr, 0, (size_t)h->n * sizeof(uint32_t)));
     if (h->srv.ws) {
         HIP_TRY(h, hipMemcpy(h->srv.ws, init.data(), sizeof(TkWorker), hipMemcpyHostToDevice));
         HIP_TRY(h, hipMemset(h->srv.cursor, 0, (size_t)h->srv.ge.slices * sizeof(uint32_t)));
@@ -811,8 +824,7 @@ int reset_topk_workers(comp_ams *h)
 int flush_pending(comp_ams *h)
 {
     if (!h->final_pending) return COMP_AMS_OK;
-    if (is_sparse(h))
-        launch_final(h, h->stream, h->par, h->pending_params);
+    launch_bs_update(h, h->stream, h->pending_params);
     HIP_TRY(h, hipGetLastError());
     h->final_pending = false;
     return COMP_AMS_OK;
@@ -888,9 +900,11 @@ int step_any(comp_ams *h, const G *grads_dev, void *hip_stream)
     else if (is_sparse(h))
         rc = (h->method == COMP_AMS_METHOD_CD)      ? step_topk_cd(h, grads_dev, st)
              : (h->method == COMP_AMS_METHOD_NAIVE) ? step_topk_naive(h, grads_dev, st)
-                                                    : step_topk(h, grads_dev, st, capturing);
+                                                    : step_topk(h, grads_dev, st);
     else
-        rc = (h->method == COMP_AMS_METHOD_CD) ? step_blocksign_cd(h, grads_dev, st) : step_blocksign(h, grads_dev, st);
+        rc = (h->method == COMP_AMS_METHOD_CD)            ? step_blocksign_cd(h, grads_dev, st)
+             : (!capturing && can_defer_blocksign(h))     ? step_blocksign_deferred(h, grads_dev, st)
+                                                           : step_blocksign(h, grads_dev, st);
     if (rc) return rc;
     HIP_TRY(h, hipGetLastError());
     ++h->steps;
@@ -964,7 +978,10 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         std::vector<int64_t> off;
         for (int64_t s = 0; s < d; s += B) off.push_back(s);
         off.push_back(d);
-        if ((rc = dev_alloc_t(h, h->allocs, &h->signs, ld / 16 * (size_t)n))) return bail(rc);
+        if ((rc = dev_alloc_t(h, h->allocs, &h->signs2[0], ld / 16 * (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->signs2[1], ld / 16 * (size_t)n)))
+            return bail(rc);
+        h->signs = h->signs2[0];
         if ((rc = build_block_table(h, off, B))) return bail(rc);
     } else {
         h->k = k_or_block;
@@ -983,28 +1000,22 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         while (slices > 1 && slices / 2 >= ge.n_tiles) slices /= 2;
         set_slices(ge, slices);
         ge.relist_wgs = (int32_t)std::min<int64_t>(ge.n_tiles, std::max(1, 2048 / n));
-        // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
-        // the whole vector after a miss) are kept to about two per compute unit in total
-        ge.pick_wgs = std::min<int32_t>(ge.relist_wgs, std::max(1, 512 / n));
         const size_t segs = (size_t)n * ge.n_tiles;
         const size_t region_entries = (size_t)n * ge.slices * (size_t)ge.region_cap;
-        if ((rc = dev_alloc_t(h, h->allocs, &h->ws2[0], (size_t)n)) || (rc = dev_alloc_t(h, h->allocs, &h->ws2[1], (size_t)n)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand2[0], region_entries, false)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->cand2[1], region_entries, false)) ||
+        if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * ge.slices)) ||
-            (rc = dev_alloc_t(h, h->allocs, &h->tile_dir2[0], segs)) || (rc = dev_alloc_t(h, h->allocs, &h->tile_dir2[1], segs)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist_full, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * ge.slices * ge.parts * 4)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->small_ctr, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_val, (size_t)ge.k)))
             return bail(rc);
-        h->ws = h->ws2[0];
-        h->cand = h->cand2[0];
-        h->tile_dir = h->tile_dir2[0];
         if ((rc = reset_topk_workers(h))) return bail(rc);
     }
     apply_streaming(h);
@@ -1525,7 +1536,6 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
             // ghat and gtilde are reused within the step if they are small enough to stay cached
             sv.ge.stream_rows = 2 * (size_t)h->ld * sizeof(float) > kCacheResidentBytes ? 1 : 0;
             sv.ge.relist_wgs = (int32_t)std::min<int64_t>(sv.ge.n_tiles, 2048);
-            sv.ge.pick_wgs = std::min<int32_t>(sv.ge.relist_wgs, 512);
             // one vector, all tiles: enough regions that a cursor sees few tens of atomic adds
             int slices = kMinSlices;
             while (slices < kMaxSlices && sv.ge.n_tiles / slices > 32) slices *= 2;

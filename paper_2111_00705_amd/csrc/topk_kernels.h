@@ -68,7 +68,7 @@ constexpr uint32_t kNoGuess = 1u << 17;      // fine-bin guess that lists nothin
 constexpr uint64_t kNoThreshold = ~0ull;     // Tc that keeps nothing (no pending selection)
 constexpr uint32_t kMinSlack = 8, kMaxSlack = 512, kFirstSlack = 8;   // in fine bins (0.2 % each)
 constexpr uint32_t kZeroTail = 2;            // value of TkWorker::whole
-constexpr uint32_t kExact = 3;               // value of TkWorker::whole: tk_exact has found Tc itself and listed the kept set
+constexpr uint32_t kExact = 3;               // value of TkWorker::whole: exact_select has found Tc and listed the kept set
 
 
 struct TkWorker {
@@ -114,7 +114,6 @@ struct TkGeom {
     uint32_t region_cap;    // entries a candidate region holds (see region_base)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
     int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
-    int32_t pick_wgs;       // workgroups per worker in tk_pick (one does the work unless the whole vector is counted)
     int32_t stream_rows;    // the stored rows are too large to stay cached between steps: tk_pass1 loads them as a stream
     int32_t xcd_chunk;      // tk_pass1: tile_of_block's chunk
     TkRand rand;
@@ -437,12 +436,9 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
 }
 
 // G: element type of g - float, or uint16_t (bfloat16 bits) for gradients handed over as bfloat16.
-// wp: the records the previous step left (its threshold, still pending on the stored rows, and the guess it
-// prepared); wc: the records of the running step (only the overflow flag is written here).  wp and wc may be
-// the same array.
 template <int kMode, typename G>
 __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, float *__restrict__ xs, TkGeom ge,
-                                                     const TkWorker *wp, TkWorker *wc, uint2 *__restrict__ cand,
+                                                     TkWorker *ws, uint2 *__restrict__ cand,
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
     __shared__ uint2 stage[4][kSub];
@@ -452,10 +448,10 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     const int i = blockIdx.y;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
-    const uint32_t guess = wp[i].guess;
-    const KeptTest kt = kept_test(wp[i].tc, ge.idx_bits);
+    const uint32_t guess = ws[i].guess;
+    const KeptTest kt = kept_test(ws[i].tc, ge.idx_bits);
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const SelKey sk_prev = sel_key_of(ge.rand, wp[i].step_word, i);
+    const SelKey sk_prev = sel_key_of(ge.rand, ws[i].step_word, i);
     const uint32_t d = (uint32_t)ge.d;
     const uint32_t base = (uint32_t)t * kTile;
     if (tid == 0) sh[4] = 0;
@@ -468,7 +464,7 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     else
         count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
                                             stage[wave], ge.stream_rows, zeros);
-    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir, &wc[i].overflow);
+    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir, &ws[i].overflow);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -481,7 +477,7 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
 // the kept candidates are distinct).
 constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in flight at a time
 
-// Adds, for the coordinates that wavefront `wave` (0..3) of a tile owns, the kept values (comp >= Tc_i) of all
+// Adds, for the calling wavefront's coordinates of tile t, the kept values (comp >= Tc_i) of all
 // workers into acc (LDS, kTile floats, zeroed by the caller for these coordinates) in ascending
 // worker order.  ws: the records that hold the selection's thresholds (and, for Rand-k, the draw they were made
 // with).  kScatter (CD-Adam, Algorithm 1, line 6): the kept value u = c_i[j] is also added to
@@ -489,10 +485,10 @@ constexpr int kFinBatch = 8;   // workers whose candidates a wavefront has in fl
 template <bool kScatter>
 __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, const TkWorker *__restrict__ ws,
                                               const uint2 *__restrict__ cand, const uint4 *__restrict__ tile_dir,
-                                              int t, float *__restrict__ rows, int wave)
+                                              int t, float *__restrict__ rows)
 {
     const uint32_t base = (uint32_t)t * kTile;
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int w0 = 0; w0 < ge.n; w0 += kWave) {
         const int nw = min(kWave, ge.n - w0);
         // lane l: where worker w0 + l keeps this wavefront's candidates of the tile, and its threshold
@@ -571,27 +567,23 @@ __device__ __forceinline__ void sum_kept_tile(float *acc, const TkGeom &ge, cons
     }
 }
 
-// What tk_final does for one tile: everything it reads besides the geometry.
-struct FinalJob {
-    const TkWorker *ws;          // records with the thresholds of the selection whose update this is
-    const uint2 *cand;
-    const uint4 *tile_dir;
-    float *theta, *m, *v, *vhat;
-    AmsParams p;
-    int32_t tile0, tiles;        // as a filler (see run_filler): the kernel's share is the tiles [tile0, tile0 + tiles)
-};
-
-// Server average and AMSGrad update of tile t by 256 threads (tid = 0..255, four wavefronts `wave` = tid / 64, which
-// need not start a workgroup).  acc: kTile floats of LDS of their own.  No workgroup barrier inside.
+// Server average and AMSGrad update, one workgroup per tile.
 template <bool kStreamState>
-__device__ __forceinline__ void final_tile(const FinalJob &job, const TkGeom &ge, int t, int tid, float *acc)
+__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                     const uint2 *__restrict__ cand,
+                                                     const uint4 *__restrict__ tile_dir,
+                                                     float *__restrict__ theta, float *__restrict__ m,
+                                                     float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
 {
+    __shared__ float acc[kTile];
+    const int t = blockIdx.x;
     const int64_t base = (int64_t)t * kTile;
-    const AmsParams &p = job.p;
+    const int tid = threadIdx.x;
+
 #pragma unroll
     for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    sum_kept_tile<false>(acc, ge, job.ws, job.cand, job.tile_dir, t, nullptr, tid >> 6);
+    sum_kept_tile<false>(acc, ge, ws, cand, tile_dir, t, nullptr);
 
     // the state is loaded only now: fewer live registers above (more workgroups per compute unit),
     // which measured faster than loading it first
@@ -599,10 +591,10 @@ __device__ __forceinline__ void final_tile(const FinalJob &job, const TkGeom &ge
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int64_t j = base + 4 * (tid + kThreads * r);
-        th[r] = ld4_state<kStreamState>(job.theta + j);
-        mm[r] = ld4_state<kStreamState>(job.m + j);
-        vv[r] = ld4_state<kStreamState>(job.v + j);
-        vh[r] = ld4_state<kStreamState>(job.vhat + j);
+        th[r] = ld4_state<kStreamState>(theta + j);
+        mm[r] = ld4_state<kStreamState>(m + j);
+        vv[r] = ld4_state<kStreamState>(v + j);
+        vh[r] = ld4_state<kStreamState>(vhat + j);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -613,55 +605,26 @@ __device__ __forceinline__ void final_tile(const FinalJob &job, const TkGeom &ge
                                         fdiv(a.w, p.n_workers));
         const float4 vh0 = vh[r];
         amsgrad_update4(th[r], mm[r], vv[r], vh[r], gbar, p);
-        st4_state<kStreamState>(job.theta + j, th[r]);
-        st4_state<kStreamState>(job.m + j, mm[r]);
-        st4_state<kStreamState>(job.v + j, vv[r]);
+        st4_state<kStreamState>(theta + j, th[r]);
+        st4_state<kStreamState>(m + j, mm[r]);
+        st4_state<kStreamState>(v + j, vv[r]);
         // with a sparse average vhat = max(vhat, v) moves at few coordinates (v only decays elsewhere)
-        st4_if_changed<kStreamState>(job.vhat + j, vh[r], vh0);
-    }
-}
-
-template <bool kStreamState>
-__global__ __launch_bounds__(kThreads) void tk_final(TkGeom ge, FinalJob job)
-{
-    __shared__ float acc[kTile];
-    final_tile<kStreamState>(job, ge, blockIdx.x, threadIdx.x, acc);
-}
-
-// The selection kernels of a step are small and bound by latency: launched alone they leave the chip idle for
-// tens of microseconds.  Under error feedback the AMSGrad update of the step BEFORE depends on nothing they
-// compute (and nothing they or tk_pass1 read depends on it), so the library defers it: each selection kernel of
-// step t + 1 is launched with extra workgroups - after its own, so that those start first - which work through a
-// share of the tiles of step t's update while the selection runs.  kFill: 0 no filler code, 1 filler with cached
-// state accesses, 2 filler with streamed state accesses.
-// own_blocks: the kernel's own workgroups.  acc: kTile floats of LDS per 256 threads of the workgroup.  Returns
-// true in the workgroups that are fillers (they have done their tiles and must leave).
-template <int kFill>
-__device__ __forceinline__ bool run_filler(const FinalJob &job, const TkGeom &ge, unsigned own_blocks, float *acc)
-{
-    if constexpr (kFill == 0) {
-        return false;
-    } else {
-        if (blockIdx.x < own_blocks) return false;
-        const int groups = blockDim.x / kThreads, group = threadIdx.x / kThreads;
-        const int q = (int)(blockIdx.x - own_blocks) * groups + group;
-        if (q < job.tiles) final_tile<kFill == 2>(job, ge, job.tile0 + q, threadIdx.x % kThreads, acc + group * kTile);
-        return true;
+        st4_if_changed<kStreamState>(vhat + j, vh[r], vh0);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// How the workgroups of tk_hist and tk_compact share a worker's candidates: workgroup x = slice *
-// parts + part of the worker, and a part is a contiguous piece of the slice's region.
+// How the workgroups of tk_hist and tk_compact share a worker's candidates: blockIdx.x = slice *
+// parts + part, and a part is a contiguous piece of the slice's region.
 struct Piece {
     int slice;
     uint32_t q0, q1;     // entries [q0, q1) of the region
 };
-__device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__restrict__ cursor, int worker, int x)
+__device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__restrict__ cursor, int worker)
 {
     Piece p;
-    p.slice = x / ge.parts;
-    const uint32_t part = x % ge.parts;
+    p.slice = blockIdx.x / ge.parts;
+    const uint32_t part = blockIdx.x % ge.parts;
     const uint32_t count = min(cursor[worker * ge.slices + p.slice], ge.region_cap);
     const uint32_t chunk = (count + ge.parts - 1) / ge.parts;
     p.q0 = min(part * chunk, count);
@@ -670,32 +633,20 @@ __device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__re
 }
 
 // Histograms of the candidates of a worker: coarse bins, and the fine bins of the two coarse bins
-// that start with the guess's.  Loads are issued four at a time.  Grid: slices * parts workgroups per worker,
-// worker-major, then the fillers.
-template <int kFill>
-__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *wp, const TkWorker *wc,
+// that start with the guess's.  Loads are issued four at a time.  Grid (slices * parts, n).
+__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *__restrict__ ws,
                                                     const uint2 *__restrict__ cand,
                                                     const uint32_t *__restrict__ cursor,
-                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
-                                                    FinalJob job)
+                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf)
 {
-    union Lds {
-        struct {
-            uint32_t lh[kBins1];
-            uint32_t lf[kFineWindow];
-        } o;
-        float acc[kFill ? kTile : 1];
-    };
-    __shared__ Lds L;
-    const int per = ge.slices * ge.parts;
-    if (run_filler<kFill>(job, ge, (unsigned)(per * ge.n), L.acc)) return;
-    uint32_t *lh = L.o.lh, *lf = L.o.lf;
-    const int i = blockIdx.x / per;
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t lf[kFineWindow];
+    const int i = blockIdx.y;
     const int tid = threadIdx.x;
-    if (wc[i].overflow) return;                     // the lists are incomplete: tk_pick counts the vector itself
-    const Piece pc = piece_of(ge, cursor, i, blockIdx.x % per);
+    if (ws[i].overflow) return;                     // the lists are incomplete: tk_pick counts the vector itself
+    const Piece pc = piece_of(ge, cursor, i);
     if (pc.q0 >= pc.q1) return;
-    const uint32_t guess = wp[i].guess;
+    const uint32_t guess = ws[i].guess;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
     for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
@@ -762,7 +713,7 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const void *_
     }
 }
 
-// The leading digits of Tc.  P workgroups per worker (ge.pick_wgs), worker-major, then the fillers.  In the usual
+// The leading digits of Tc.  Grid (P, n).  In the usual
 // case the worker's candidates number at least k, so the k-th largest is among them: workgroup 0 finds its coarse
 // and (if the window covers it) fine bin from the candidate histograms, and the other workgroups return at once.
 // With fewer than k candidates (always on the first step, else when the threshold fell through the slack) the guess
@@ -772,41 +723,33 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const void *_
 // Bin 0 (zeros and the smallest denormals) is not counted but taken as the remainder: in a sparse
 // vector it would draw most LDS atomics of a tile to one word.
 // Consumes (and clears) the candidate histograms.
-template <int kSrc, typename G, int kFill>
-__global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *wp, TkWorker *wc,
+template <int kSrc, typename G>
+__global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
                                                     uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
                                                     uint32_t *__restrict__ cursor, uint32_t *__restrict__ hist_full,
-                                                    const void *__restrict__ a, const float *__restrict__ b, FinalJob job)
+                                                    const void *__restrict__ a, const float *__restrict__ b)
 {
-    union Lds {
-        struct {
-            uint32_t lh[kBins1];
-            uint32_t part[kThreads / kWave];
-            uint32_t res[4];
-            uint32_t fres[3];
-            uint32_t total_sh;
-        } o;
-        float acc[kFill ? kTile : 1];
-    };
-    __shared__ Lds L;
-    if (run_filler<kFill>(job, ge, (unsigned)(ge.pick_wgs * ge.n), L.acc)) return;
-    uint32_t *lh = L.o.lh, *part = L.o.part, *res = L.o.res, *fres = L.o.fres;
-    const int i = blockIdx.x / ge.pick_wgs;
-    const int bx = blockIdx.x % ge.pick_wgs;
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t part[kThreads / kWave];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t fres[3];
+    __shared__ uint32_t total_sh;
+    const int i = blockIdx.y;
+    const int bx = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t guess = wp[i].guess;
-    const bool overflow = wc[i].overflow != 0u;
+    const uint32_t guess = ws[i].guess;
+    const bool overflow = ws[i].overflow != 0u;
     if (wave == 0) {
         // number of candidates of this worker = sum of its region cursors
         uint32_t c = 0;
         for (int q = lane; q < ge.slices; q += kWave) c += cursor[i * ge.slices + q];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
-        if (lane == 0) L.o.total_sh = c;
+        if (lane == 0) total_sh = c;
     }
     __syncthreads();
-    const uint32_t total = L.o.total_sh;
+    const uint32_t total = total_sh;
     uint32_t *row = hist1 + (int64_t)i * kBins1;
     uint32_t *frow = histf + (int64_t)i * kFineWindow;
 
@@ -848,11 +791,11 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *w
         }
         __syncthreads();   // every thread has read the histograms before they are cleared
         if (tid == 0) {
-            wc[i].prefix = prefix;
-            wc[i].pshift = pshift;
-            wc[i].rank = rank;
-            wc[i].whole = (count == rank) ? 1u : 0u;
-            wc[i].relisted = 0u;
+            ws[i].prefix = prefix;
+            ws[i].pshift = pshift;
+            ws[i].rank = rank;
+            ws[i].whole = (count == rank) ? 1u : 0u;
+            ws[i].relisted = 0u;
         }
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
@@ -865,11 +808,11 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *w
         // among the zeros, which are ordered by index alone, from the zero counts of the tiles.
         if (bx != 0) return;
         if (tid == 0) {
-            wc[i].prefix = 0u;
-            wc[i].pshift = kShift1;
-            wc[i].rank = ge.k - total;          // so many zeros are kept, the lowest indices first
-            wc[i].whole = kZeroTail;
-            wc[i].relisted = 0u;
+            ws[i].prefix = 0u;
+            ws[i].pshift = kShift1;
+            ws[i].rank = ge.k - total;          // so many zeros are kept, the lowest indices first
+            ws[i].whole = kZeroTail;
+            ws[i].relisted = 0u;
         }
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
@@ -883,7 +826,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *w
     const uint32_t d = (uint32_t)ge.d;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    for (int t = bx; t < ge.n_tiles; t += ge.pick_wgs) {
+    for (int t = bx; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
         load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
@@ -902,7 +845,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *w
         if (c) atomicAdd(hist_full + (int64_t)i * kBins1 + q, c);
     }
     if (bx == 0) {
-        if (tid == 0) wc[i].relisted = 1u;
+        if (tid == 0) ws[i].relisted = 1u;
         for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
         if (tid < kFineWindow) frow[tid] = 0;
@@ -912,32 +855,24 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, const TkWorker *w
 // Only for workers whose guess was too high: takes the coarse bin of the k-th largest from the full
 // histogram tk_pick has just counted (every workgroup works it out for itself; workgroup 0 records
 // it) and lists the elements in that bin or above into the (emptied) regions of the worker.  A small
-// grid (ge.relist_wgs workgroups per worker, worker-major, then the fillers) whose workgroups loop over tiles:
-// in the usual case every workgroup returns at once, and a small grid does that fast.  A region that fills up
+// grid (ge.relist_wgs, n) whose workgroups loop over tiles: in the usual case every workgroup returns at once,
+// and a small grid does that fast.  A region that fills up
 // sets overflow2: tk_compact's first workgroup of the worker then selects without lists (exact_select).
-template <int kSrc, typename G, int kFill>
+template <int kSrc, typename G>
 __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a, const float *__restrict__ b,
-                                                      TkGeom ge, TkWorker *wc,
+                                                      TkGeom ge, TkWorker *__restrict__ ws,
                                                       const uint32_t *__restrict__ hist_full,
                                                       uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                                      uint4 *__restrict__ tile_dir, FinalJob job)
+                                                      uint4 *__restrict__ tile_dir)
 {
-    union Lds {
-        struct {
-            uint2 stage[4][kSub];
-            uint32_t lh[kBins1];
-            uint32_t part[kThreads / kWave];
-            uint32_t res[4];
-            uint32_t sh[9];
-        } o;
-        float acc[kFill ? kTile : 1];
-    };
-    __shared__ Lds L;
-    if (run_filler<kFill>(job, ge, (unsigned)(ge.relist_wgs * ge.n), L.acc)) return;
-    uint32_t *lh = L.o.lh, *part = L.o.part, *res = L.o.res, *sh = L.o.sh;
-    const int i = blockIdx.x / ge.relist_wgs;
-    const int bx = blockIdx.x % ge.relist_wgs;
-    if (!wc[i].relisted) return;
+    __shared__ uint2 stage[4][kSub];
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t part[kThreads / kWave];
+    __shared__ uint32_t res[4];
+    __shared__ uint32_t sh[9];
+    const int i = blockIdx.y;
+    const int bx = blockIdx.x;
+    if (!ws[i].relisted) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t d = (uint32_t)ge.d;
@@ -959,13 +894,13 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
     const uint32_t prefix = res[0];
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     if (bx == 0 && tid == 0) {
-        wc[i].prefix = prefix;
-        wc[i].pshift = kShift1;
-        wc[i].rank = ge.k - res[1];
-        wc[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
+        ws[i].prefix = prefix;
+        ws[i].pshift = kShift1;
+        ws[i].rank = ge.k - res[1];
+        ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
     }
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    for (int t = bx; t < ge.n_tiles; t += ge.relist_wgs) {
+    for (int t = bx; t < ge.n_tiles; t += gridDim.x) {
         const uint32_t base = (uint32_t)t * kTile;
         float x[4][4];
         load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
@@ -982,153 +917,34 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
                     hit = hit && !zero;
                 }
                 const uint32_t slot = wave_append(hit, count);
-                if (hit) L.o.stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
+                if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
             }
-        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir, &wc[i].overflow2);
-        flush_end(L.o.stage[wave], count, sh, ge, i, cand);
+        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir, &ws[i].overflow2);
+        flush_end(stage[wave], count, sh, ge, i, cand);
         __syncthreads();   // sh and stage are reused by the next tile
     }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Selection without lists, for a vector whose candidates fit no region even after tk_relist (so many elements
-// share the leading bits of the k-th largest that only the whole composite key tells them apart - all-equal
-// input is the extreme).  One workgroup of 256 threads: the digits of Tc by counting over the whole vector,
-// re-formed tile by tile from what is stored (kDigit bits per sweep), then one more sweep that lists exactly the
-// kept elements - k of them, which always fit: a worker's regions hold at least 8 k entries in all, and this
-// list is written as one run from the worker's first region (no cursors, no atomics; a tile's record holds its
-// offset in that run).  Slow (one compute unit reads the vector up to seven times) and meant to be: it only has
-// to be right.  Leaves Tc in wc[i].tc and whole = kExact; tk_resolve takes it from there.
-constexpr int kExactDigit = 11;
-struct ExactLds {
-    uint2 stage[4][kSub];
-    uint32_t lh[kBins1];
-    uint32_t part[kThreads / kWave];
-    uint32_t res[4];
-    uint32_t sh[9];
-};
-static_assert((1 << kExactDigit) == kBins1, "exact_select counts into kBins1 bins");
-
-template <int kSrc, typename G>
-__device__ __forceinline__ void exact_select(const void *__restrict__ a, const float *__restrict__ b, const TkGeom &ge,
-                                             int i, TkWorker *wc, uint2 *__restrict__ cand,
-                                             uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir, ExactLds &L)
-{
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t d = (uint32_t)ge.d;
-    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    int s_hi = 31 + ge.idx_bits;                     // bits of comp still open
-    uint64_t prefix = 0;
-    uint32_t rank = ge.k;
-    uint64_t tc = 0;
-    while (true) {
-        const int s_lo = max(s_hi - kExactDigit, 0);
-        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
-        for (int q = tid; q < kBins1; q += kThreads) L.lh[q] = 0;
-        __syncthreads();
-        for (int t = 0; t < ge.n_tiles; ++t) {
-            const uint32_t base = (uint32_t)t * kTile;
-            float x[4][4];
-            load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t j = base + 4 * (tid + kThreads * r) + c;
-                    const uint64_t comp = composite(sel_key(sk, x[r][c], j), j, ge.idx_bits);
-                    if (j < d && (comp >> s_hi) == prefix) atomicAdd(&L.lh[(uint32_t)(comp >> s_lo) & mask], 1u);
-                }
-        }
-        __syncthreads();
-        find_rank_bin(L.lh, L.part, L.res, kBins1, rank);          // rank <= elements under the prefix
-        prefix = (prefix << (s_hi - s_lo)) | L.res[0];
-        rank -= L.res[1];
-        const uint32_t left = L.res[2];
-        __syncthreads();
-        if (s_lo == 0 || left == rank) {                            // last digit, or all under this prefix are kept
-            tc = prefix << s_lo;
-            break;
-        }
-        s_hi = s_lo;
-    }
-    // the kept elements, tile by tile, as one run from the start of the worker's space
-    uint32_t run = 0;                                               // uniform over the workgroup
-    for (int t = 0; t < ge.n_tiles; ++t) {
-        const uint32_t base = (uint32_t)t * kTile;
-        float x[4][4];
-        load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
-        uint32_t count = 0, zeros = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t j = base + 4 * (tid + kThreads * r) + c;
-                bool hit = j < d && composite(sel_key(sk, x[r][c], j), j, ge.idx_bits) >= tc;
-                if (kSrc == kSrcStored && !sk.on) {          // zeros are counted, not listed (as in tk_pass1)
-                    const bool zero = j < d && mag_key(x[r][c]) == 0u;
-                    zeros += (uint32_t)__popcll(__ballot(zero));
-                    hit = hit && !zero;
-                }
-                const uint32_t slot = wave_append(hit, count);
-                if (hit) L.stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
-            }
-        if (lane == 0) {
-            L.sh[wave] = count;
-            L.sh[5 + wave] = zeros;
-        }
-        __syncthreads();
-        const uint32_t cnt[4] = {L.sh[0], L.sh[1], L.sh[2], L.sh[3]};
-        if (tid == 0)
-            tile_dir[(int64_t)i * ge.n_tiles + t] =
-                make_uint4(run, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), L.sh[5] + L.sh[6] + L.sh[7] + L.sh[8]);
-        uint32_t off = run;
-        for (int w = 0; w < wave; ++w) off += cnt[w];
-        uint2 *dst = cand + worker_base(ge, i) + off;
-        for (uint32_t q = lane; q < count; q += kWave) dst[q] = L.stage[wave][q];
-        run += cnt[0] + cnt[1] + cnt[2] + cnt[3];
-        __syncthreads();   // sh and stage are reused by the next tile
-    }
-    if (tid == 0) {
-        wc[i].tc = tc;
-        wc[i].whole = kExact;
-    }
-    (void)cursor;
 }
 
 // Copies the candidates that carry the prefix, as comp values, to the dense storage.  Each wavefront
 // takes a quarter of the workgroup's piece and writes its hits from the start of that quarter
 // onwards (as many slots as it reads, so it cannot overflow), and records {start, count} relative to
-// the worker's first region; no atomics, tk_resolve walks the records.  Grid: slices * parts workgroups per
-// worker, worker-major, then the fillers.  For a worker whose lists did not fit (overflow2) there is nothing to
-// copy: its first workgroup runs exact_select instead, the others leave.
-template <int kSrc, typename G, int kFill>
-__global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, TkWorker *wc, uint2 *__restrict__ cand,
-                                                       uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
-                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir,
-                                                       const void *__restrict__ a, const float *__restrict__ b,
-                                                       FinalJob job)
+// the worker's first region; no atomics, tk_resolve walks the records.  Grid (slices * parts, n).  Nothing to do
+// for a worker whose threshold needs no further digit, or whose lists did not fit (tk_resolve then selects
+// without lists).
+__global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                       const uint2 *__restrict__ cand,
+                                                       const uint32_t *__restrict__ cursor,
+                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir)
 {
-    union Lds {
-        ExactLds o;
-        float acc[kFill ? kTile : 1];
-    };
-    __shared__ Lds L;
-    const int per = ge.slices * ge.parts;
-    if (run_filler<kFill>(job, ge, (unsigned)(per * ge.n), L.acc)) return;
-    const int i = blockIdx.x / per;
-    const int bx = blockIdx.x % per;
-    if (wc[i].overflow2) {
-        if (bx == 0) exact_select<kSrc, G>(a, b, ge, i, wc, cand, cursor, tile_dir, L.o);
-        return;
-    }
-    if (wc[i].whole) return;
+    const int per = gridDim.x;
+    const int i = blockIdx.y;
+    const int bx = blockIdx.x;
+    if (ws[i].whole || ws[i].overflow2) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint32_t prefix = wc[i].prefix, pshift = wc[i].pshift;
+    const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const Piece pc = piece_of(ge, cursor, i, bx);
+    const Piece pc = piece_of(ge, cursor, i);
     const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
     const uint32_t w0 = min(pc.q0 + wave * quarter, pc.q1), w1 = min(w0 + quarter, pc.q1);
     const int64_t rbase = region_base(ge, i, pc.slice);
@@ -1180,24 +996,29 @@ struct ResolveLds {
 // cnt comp values that fetch(q, comp) delivers kScanUnroll at a time (comp[u] = element q[u], anything for
 // q[u] >= cnt; q ascends with u), of which the one of 1-based rank `rank` (from the top) among those that
 // carry the prefix is wanted.  Once at most kFew elements carry the prefix they are fetched and
-// ranked against each other directly.  All kResolveThreads threads call this; returns Tc.
-template <class Fetch>
+// ranked against each other directly.  All threads of the workgroup (256 or 1024) call this; returns Tc.
+// kWholeBins: a digit whose bin holds exactly the elements still wanted ends the search with the bin's lower edge as
+// Tc - right when every element of the vector that could fall into that bin is among the cnt delivered (the
+// threshold bin of tk_compact is), wrong when the elements are only those above some bound that may cut the bin
+// (the candidate list of tk_small_pass): then the search goes on to the k-th largest comp value itself.
+template <bool kWholeBins = true, class Fetch>
 __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, uint64_t prefix, uint32_t rank, int s_hi,
                                                    ResolveLds &L)
 {
     const int tid = threadIdx.x;
+    const int nt = (int)blockDim.x;
     uint64_t tc = prefix << s_hi;
     bool done = false;
     while (!done) {
         const int s_lo = max(s_hi - kDigitBits, 0);
         const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
-        for (int b = tid; b < kBins2; b += kResolveThreads) L.lh[b] = 0;
+        for (int b = tid; b < kBins2; b += nt) L.lh[b] = 0;
         __syncthreads();
-        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * nt) {
             uint32_t q[kScanUnroll];
             uint64_t comp[kScanUnroll];
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * kResolveThreads + tid;
+            for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * nt + tid;
             fetch(q, comp);                                 // independent loads: all in flight at once
 #pragma unroll
             for (int u = 0; u < kScanUnroll; ++u)
@@ -1211,17 +1032,17 @@ __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, ui
         rank -= L.res[1];
         const uint32_t left = L.res[2];                        // elements that carry the new prefix
         s_hi = s_lo;
-        if (s_lo == 0 || left == rank) {                       // last digit, or all under this prefix are kept
+        if (s_lo == 0 || (kWholeBins && left == rank)) {       // last digit, or all under this prefix are kept
             done = true;
             tc = prefix << s_lo;
         } else if (left <= (uint32_t)kFew) {
             if (tid == 0) L.n_few = 0;
             __syncthreads();
-            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * kResolveThreads) {
+            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * nt) {
                 uint32_t q[kScanUnroll];
                 uint64_t comp[kScanUnroll];
 #pragma unroll
-                for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * kResolveThreads + tid;
+                for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * nt + tid;
                 fetch(q, comp);
 #pragma unroll
                 for (int u = 0; u < kScanUnroll; ++u)
@@ -1247,23 +1068,23 @@ __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, ui
 // Records the finished selection of a worker and prepares the next step's guess: a few fine bins
 // below this threshold - at least twice the distance the threshold just fell (a rising threshold needs
 // no slack), never less than kMinSlack, shrinking by one bin per quiet step, doubled after a miss.
-// prev: the record the step before left (its slack and threshold bin).  Writes the whole record wc[i] - the
-// flags of the running step are cleared for the step that uses this record next.  One thread calls this.
-__device__ __forceinline__ void finish_worker(TkWorker *wc, int i, const TkWorker &prev, uint64_t tc, const TkGeom &ge,
+// w: the record as the step found it (its slack and last threshold bin).  The flags of the running step are
+// cleared for the next one.  One thread calls this.
+__device__ __forceinline__ void finish_worker(TkWorker *ws, int i, const TkWorker &w, uint64_t tc, const TkGeom &ge,
                                               bool missed)
 {
-    wc[i].tc = tc;
-    wc[i].step_word = ge.rand.step_now;
+    ws[i].tc = tc;
+    ws[i].step_word = ge.rand.step_now;
     const uint32_t fine = (uint32_t)(tc >> ge.idx_bits) >> kFineShift;
-    const uint32_t fell = (prev.last_fine != kNoGuess && prev.last_fine > fine) ? prev.last_fine - fine : 0u;
-    uint32_t slack = missed ? prev.slack * 2u : prev.slack - 1u;
+    const uint32_t fell = (w.last_fine != kNoGuess && w.last_fine > fine) ? w.last_fine - fine : 0u;
+    uint32_t slack = missed ? w.slack * 2u : w.slack - 1u;
     slack = max(slack, 2u * fell + 2u);
     slack = min(max(slack, max(kMinSlack, ge.rand.min_slack)), kMaxSlack);
-    wc[i].slack = slack;
-    wc[i].last_fine = fine;
-    wc[i].guess = fine > slack ? fine - slack : 0u;
-    wc[i].overflow = 0u;
-    wc[i].overflow2 = 0u;
+    ws[i].slack = slack;
+    ws[i].last_fine = fine;
+    ws[i].guess = fine > slack ? fine - slack : 0u;
+    ws[i].overflow = 0u;
+    ws[i].overflow2 = 0u;
 }
 
 // Exclusive prefix sum of one value per thread over the 1024 threads of tk_resolve; returns the exclusive sum,
@@ -1335,42 +1156,179 @@ __device__ __forceinline__ uint64_t zero_tail_threshold(const uint4 *__restrict_
     return L.tc_sh;
 }
 
-// xs: the stored rows under error feedback with magnitude keys (where zeros are counted instead of listed and
-// the threshold may lie among them), else null.  wp: the records of the step before (slack, last threshold bin);
-// wc: those of the running step, completed here.  Grid: one workgroup per worker, then the fillers (four tiles
-// per workgroup of 1024 threads).
-struct ResolveOwn {
-    ResolveLds L;
-    uint32_t rpre[kMaxPieces + 1];
-    uint32_t rstart[kMaxPieces];
+// ---------------------------------------------------------------------------------------------
+// Selection without lists, for a vector whose candidates fit no region even after tk_relist (so many elements
+// share the leading bits of the k-th largest that only the whole composite key tells them apart - all-equal
+// input is the extreme).  The worker's workgroup of tk_resolve does it alone: the digits of Tc by counting over
+// the whole vector, re-formed element by element from what is stored (kDigitBits bits per sweep), then one more
+// sweep that lists exactly the kept elements - k of them, which always fit: a worker's regions hold at least 8 k
+// entries in all, and this list is written as one run from the worker's first region (no cursors; a tile's
+// record holds its offset in that run, its candidates stand by owning wavefront as everywhere).  Slow - one
+// compute unit reads the vector up to six times - and meant to be: it only has to be right.
+//
+// How the vector is re-formed (src: kSrcStored ... kSrcGradOnly; gtype: element type of the gradients, 0 fp32,
+// 1 bfloat16, 2 half) is decided at run time here: one scalar load per element and operand.
+struct ExactSource {
+    int32_t src, gtype;
+    const void *a;
+    const float *b;
 };
-template <int kFill>
-__global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, const TkWorker *wp, TkWorker *wc,
+__device__ __forceinline__ float exact_value(const ExactSource &e, const TkGeom &ge, int i, uint32_t j)
+{
+    float av;
+    if (e.src == kSrcGrad || e.src == kSrcGradOnly) {
+        const int64_t at = (int64_t)i * ge.d + j;
+        av = e.gtype == 0   ? static_cast<const float *>(e.a)[at]
+             : e.gtype == 1 ? bf16_to_float(static_cast<const uint16_t *>(e.a)[at])
+                            : f16_to_float(static_cast<const uint16_t *>(e.a)[at]);
+    } else {
+        av = static_cast<const float *>(e.a)[(int64_t)i * ge.ld + j];
+    }
+    if (e.src == kSrcGrad || e.src == kSrcDiff) av = fsub(av, e.b[(int64_t)i * ge.ld + j]);
+    return av;
+}
+
+struct ExactLds {
+    uint2 stage[4][kSub];      // the kept elements of a tile by owning wavefront
+    uint32_t cnt[4];
+    uint32_t zeros;
+};
+
+// The digits of Tc by counting over the whole vector.  All threads of the workgroup (256 or 1024) call this.
+__device__ __forceinline__ uint64_t exact_threshold(const ExactSource &es, const TkGeom &ge, int i, ResolveLds &L)
+{
+    const int tid = threadIdx.x, nt = (int)blockDim.x;
+    const uint32_t d = (uint32_t)ge.d;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
+    int s_hi = 31 + ge.idx_bits;                                    // bits of comp still open
+    uint64_t prefix = 0;
+    uint32_t rank = ge.k;
+    while (true) {
+        const int s_lo = max(s_hi - kDigitBits, 0);
+        const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
+        for (int q = tid; q < kBins2; q += nt) L.lh[q] = 0;
+        __syncthreads();
+        for (int t = 0; t < ge.n_tiles; ++t) {
+            for (int T = tid; T < kTile / 4; T += nt) {
+                const uint32_t j0 = (uint32_t)t * kTile + 4u * (uint32_t)T;
+                float x[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) x[c] = j0 + c < d ? exact_value(es, ge, i, j0 + c) : 0.f;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint64_t comp = composite(sel_key(sk, x[c], j0 + c), j0 + c, ge.idx_bits);
+                    if (j0 + c < d && (comp >> s_hi) == prefix) atomicAdd(&L.lh[(uint32_t)(comp >> s_lo) & mask], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        find_rank_bin(L.lh, L.part, L.res, kBins2, rank);          // rank <= elements under the prefix
+        prefix = (prefix << (s_hi - s_lo)) | L.res[0];
+        rank -= L.res[1];
+        const uint32_t left = L.res[2];
+        __syncthreads();
+        if (s_lo == 0 || left == rank) return prefix << s_lo;      // last digit, or all under this prefix are kept
+        s_hi = s_lo;
+    }
+}
+
+// Lists the kept elements (comp >= tc) of the vector, tile by tile, as one run from the start of the worker's
+// space, and writes every tile's record.  Coordinate 4 T + c of a tile (T = 0 .. 1023) belongs to the wavefront
+// (T mod 256) / 64 of the listing pass.  All threads of the workgroup (256 or 1024) call this.
+__device__ __forceinline__ void list_kept(const ExactSource &es, const TkGeom &ge, int i, uint64_t tc,
+                                          uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir, ExactLds &E)
+{
+    const int tid = threadIdx.x, nt = (int)blockDim.x;
+    const int lane = tid & 63;
+    const uint32_t d = (uint32_t)ge.d;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
+    const bool skip_zeros = (es.src == kSrcStored && !sk.on);      // zeros are counted, not listed (as in tk_pass1)
+    uint32_t run = 0;                                               // uniform over the workgroup
+    if (tid < 4) E.cnt[tid] = 0;
+    if (tid == 0) E.zeros = 0;
+    __syncthreads();
+    for (int t = 0; t < ge.n_tiles; ++t) {
+        for (int T = tid; T < kTile / 4; T += nt) {                 // the same number of rounds for every thread
+            const int owner = (T & (kThreads - 1)) >> 6;            // uniform over a wavefront
+            const uint32_t j0 = (uint32_t)t * kTile + 4u * (uint32_t)T;
+            float x[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[c] = j0 + c < d ? exact_value(es, ge, i, j0 + c) : 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t j = j0 + c;
+                bool hit = j < d && composite(sel_key(sk, x[c], j), j, ge.idx_bits) >= tc;
+                if (skip_zeros) {
+                    const bool zero = j < d && mag_key(x[c]) == 0u;
+                    const uint64_t zm = __ballot(zero);
+                    if (lane == 0 && zm) atomicAdd(&E.zeros, (uint32_t)__popcll(zm));
+                    hit = hit && !zero;
+                }
+                const uint64_t hm = __ballot(hit);
+                uint32_t at = 0;
+                if (lane == 0 && hm) at = atomicAdd(&E.cnt[owner], (uint32_t)__popcll(hm));
+                at = __builtin_amdgcn_readfirstlane(at) + __popcll(hm & ((1ull << lane) - 1ull));
+                if (hit) E.stage[owner][at] = make_uint2(j, __float_as_uint(x[c]));
+            }
+        }
+        __syncthreads();
+        const uint32_t cnt[4] = {E.cnt[0], E.cnt[1], E.cnt[2], E.cnt[3]};
+        if (tid == 0)
+            tile_dir[(int64_t)i * ge.n_tiles + t] = make_uint4(run, cnt[0] | (cnt[1] << 16), cnt[2] | (cnt[3] << 16), E.zeros);
+        uint2 *dst = cand + worker_base(ge, i) + run;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            for (uint32_t q = tid; q < cnt[w]; q += nt) dst[q] = E.stage[w][q];
+            dst += cnt[w];
+        }
+        run += cnt[0] + cnt[1] + cnt[2] + cnt[3];
+        __syncthreads();
+        if (tid < 4) E.cnt[tid] = 0;
+        if (tid == 0) E.zeros = 0;
+        __syncthreads();
+    }
+}
+
+__device__ __forceinline__ uint64_t exact_select(const ExactSource &es, const TkGeom &ge, int i, uint2 *__restrict__ cand,
+                                                 uint4 *__restrict__ tile_dir, ResolveLds &L, ExactLds &E)
+{
+    const uint64_t tc = exact_threshold(es, ge, i, L);
+    list_kept(es, ge, i, tc, cand, tile_dir, E);
+    return tc;
+}
+
+// xs: the stored rows under error feedback with magnitude keys (where zeros are counted instead of listed and
+// the threshold may lie among them), else null.  es: how the compressed vector is re-formed, for a worker whose
+// lists did not fit.
+__global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorker *__restrict__ ws,
                                                               const uint64_t *__restrict__ dense,
                                                               const uint2 *__restrict__ dense_dir,
                                                               uint32_t *__restrict__ cursor,
                                                               uint32_t *__restrict__ hist_full,
-                                                              const uint4 *__restrict__ tile_dir,
-                                                              const float *__restrict__ xs, FinalJob job)
+                                                              uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir,
+                                                              const float *__restrict__ xs, ExactSource es)
 {
-    union Lds {
-        ResolveOwn o;
-        float acc[kFill ? (kResolveThreads / kThreads) * kTile : 1];
+    __shared__ ResolveLds L;
+    // the piece table of the usual path and the staging lists of exact_select are never needed together
+    union Either {
+        struct {
+            uint32_t rpre[kMaxPieces + 1];
+            uint32_t rstart[kMaxPieces];
+        } pieces;
+        ExactLds exact;
     };
-    __shared__ Lds S;
-    if (run_filler<kFill>(job, ge, (unsigned)ge.n, S.acc)) return;
-    ResolveLds &L = S.o.L;
-    uint32_t *rpre = S.o.rpre, *rstart = S.o.rstart;
+    __shared__ Either U;
+    uint32_t *rpre = U.pieces.rpre, *rstart = U.pieces.rstart;
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const TkWorker w = wc[i];
-    const TkWorker prev = wp[i];
+    const TkWorker w = ws[i];
     const int s_hi = (int)w.pshift + ge.idx_bits;
     uint64_t tc = (uint64_t)w.prefix << s_hi;
     const uint4 *dir_row = tile_dir + (int64_t)i * ge.n_tiles;
-    if (w.whole == kExact) {
-        tc = w.tc;                                   // exact_select has found it
+    if (w.overflow2) {
+        tc = exact_select(es, ge, i, cand, tile_dir, L, U.exact);
+        if (tid == 0) ws[i].whole = kExact;          // for the records (comp_ams_get_selection_info)
     } else if (w.whole == kZeroTail) {
         tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank, L);
     } else if (!w.whole) {
@@ -1435,9 +1393,68 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, const T
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
         for (int q = tid; q < kBins1; q += kResolveThreads) hist_full[(int64_t)i * kBins1 + q] = 0;
-    if (tid == 0) finish_worker(wc, i, prev, tc, ge, w.relisted != 0);
+    if (tid == 0) finish_worker(ws, i, w, tc, ge, w.relisted != 0);
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Short vectors (at most kSmallTiles tiles) under error feedback: the selection in one launch.
+// On such a vector every kernel of the selection chain is a launch on an idle chip, and five of them cost more
+// than the work.  The listing pass is tk_pass1 itself with a single candidate region per worker (few tiles share
+// its cursor); then one workgroup per worker finds the threshold from the list by itself - the digits of Tc over
+// the listed comp values, or, when the list does not hold the k-th largest (first step, a guess that was too high,
+// a full region), by counting over the stored row (exact_select).  The tile directory and the list have the
+// usual form, so tk_final and the getters follow unchanged.  (Finding the threshold inside the listing pass, by
+// the workgroup that finishes a worker's last tile, was built and measured: the device-scope fences it needs on
+// this multi-XCD part cost more than the launch they save - 21.6 us against 6 + 5.)
+constexpr int kSmallTiles = 16;
+
+// sge: the handle's geometry with slices = 1 and region_cap = all of a worker's space.  count: [n] entries listed
+// (cleared here for the next step).
+__global__ __launch_bounds__(kResolveThreads) void tk_small_select(TkGeom sge, TkWorker *__restrict__ ws,
+                                                                   uint2 *__restrict__ cand, uint32_t *__restrict__ count,
+                                                                   uint4 *__restrict__ tile_dir, const float *__restrict__ xs)
+{
+    __shared__ ResolveLds L;
+    __shared__ ExactLds E;
+    const int i = blockIdx.x;
+    const int tid = threadIdx.x;
+    const TkWorker w = ws[i];
+    const SelKey sk = sel_key_of(sge.rand, sge.rand.step_now, i);
+    const uint32_t total = count[i];
+    const ExactSource es{kSrcStored, 0, xs, nullptr};
+    uint64_t tc;
+    bool missed = false;
+    if (!w.overflow && total >= sge.k) {
+        // every element at or above the guess is listed and there are at least k: Tc is the k-th largest of the
+        // list (the comp value itself: a digit's bin may reach below the guess, where nothing is listed)
+        const uint2 *list = cand + worker_base(sge, i);
+        auto fetch = [&](const uint32_t (&q)[kScanUnroll], uint64_t (&comp)[kScanUnroll]) {
+#pragma unroll
+            for (int u = 0; u < kScanUnroll; ++u) {
+                comp[u] = 0ull;
+                if (q[u] < total) {
+                    const uint2 e = list[q[u]];
+                    comp[u] = composite(sel_key(sk, __uint_as_float(e.y), e.x), e.x, sge.idx_bits);
+                }
+            }
+        };
+        tc = resolve_digits<false>(fetch, total, 0ull, sge.k, 31 + sge.idx_bits, L);
+    } else if (!w.overflow && !sk.on && w.guess == 0u) {
+        // magnitude keys, every non-zero element is listed and they are fewer than k: the threshold lies among the
+        // zeros, which the list leaves out - all candidates are kept, and Tc comes from counting over the row
+        tc = exact_threshold(es, sge, i, L);
+    } else {
+        missed = true;
+        tc = exact_select(es, sge, i, cand, tile_dir, L, E);
+    }
+    if (tid == 0) {
+        ws[i].relisted = missed ? 1u : 0u;
+        ws[i].whole = missed ? kExact : 0u;
+        finish_worker(ws, i, w, tc, sge, missed);
+        count[i] = 0;
+    }
+}
 
 // CD-Adam (Algorithm 1): selection buffers of the server's own Top-k - the same structures as the
 // workers', for a single vector.
@@ -1464,7 +1481,7 @@ __global__ __launch_bounds__(kThreads) void tk_merge(TkGeom ge, const TkWorker *
 #pragma unroll
     for (int r = 0; r < 4; ++r) st4(acc + 4 * (tid + kThreads * r), make_float4(0.f, 0.f, 0.f, 0.f));
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    sum_kept_tile<true>(acc, ge, ws, cand, tile_dir, t, ghat_rows, tid >> 6);
+    sum_kept_tile<true>(acc, ge, ws, cand, tile_dir, t, ghat_rows);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int l = 4 * (tid + kThreads * r);
