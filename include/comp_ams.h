@@ -27,6 +27,13 @@
  *  - comp_ams_step is asynchronous on the given HIP stream.  Getters and setters run on the
  *    stream of the most recent step (the null stream before the first) and return after
  *    their copy has completed.
+ *  - A step may leave the last part of its work - the AMSGrad update, which nothing in the next
+ *    step's compression depends on - to be launched together with the next step (block sign with
+ *    uniform blocks of a multiple of 4096 coordinates does: one launch per step instead of two).
+ *    The difference cannot be observed through this interface: every call that reads or replaces
+ *    state first launches what is pending, with the hyper-parameters of the step it belongs to,
+ *    and comp_ams_sync waits for it.  A caller that only synchronises its own stream has waited
+ *    for everything but that pending update.
  *  - A handle must not be used from two threads at once.
  *  - Arguments are validated on the host before any device call, so invalid arguments are
  *    reported as COMP_AMS_EINVAL also on a machine without a GPU.
@@ -147,7 +154,9 @@ int comp_ams_set_rand(comp_ams_t *h, uint64_t seed, uint32_t draw);
  * The base pointer must be 4-byte aligned; 16-byte alignment gives the fast path.
  * The call only launches kernels (no allocation, no memset, no wait while the stream stays the
  * same), so it may be recorded into a HIP graph; record after at least one ordinary step on the same
- * stream: the first step of a handle launches a different variant of the first kernel than the later ones.
+ * stream (the first step of a handle launches a different variant of the first kernel than the later
+ * ones) and after comp_ams_sync or any getter (a recorded step is self-contained, so nothing of an
+ * earlier step may be pending when recording starts: COMP_AMS_ESTATE otherwise).
  */
 int comp_ams_step(comp_ams_t *h, const float *grads_dev, void *hip_stream);
 
@@ -288,7 +297,8 @@ int comp_ams_pack_message_noalloc(comp_ams_t *h, int32_t who, void *buf_dev, uin
  */
 int comp_ams_message_bits(comp_ams_t *h, uint64_t *uplink_per_worker, uint64_t *downlink);
 
-/* Waits until all work enqueued by this handle has completed. */
+/* Launches an update that the last step left pending and waits until all work enqueued by this handle has
+ * completed. */
 int comp_ams_sync(comp_ams_t *h);
 
 /*

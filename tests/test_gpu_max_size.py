@@ -156,3 +156,25 @@ def test_the_largest_worker_count(comp, d, kb):
         P.CompAms(d, n + 1, comp, kb)
     gpu.destroy()
     ora.close()
+
+
+@pytest.mark.parametrize("comp,kb", [(P.TOPK, 1000), (P.BLOCKSIGN, 4096)])
+def test_a_handle_that_does_not_fit_the_device_reports_enomem_and_leaves_nothing_behind(comp, kb):
+    """comp_ams_create allocates everything the handle will ever need; when the device cannot hold it the call
+    answers COMP_AMS_ENOMEM, frees what it had taken, and a handle of ordinary size can be created right after."""
+    import torch
+    announce(f"allocation failure, compressor {comp}")
+    torch.cuda.synchronize()
+    free0, total = torch.cuda.mem_get_info()
+    d = 2 ** 31 - 1
+    n = int(total // (4 * d)) + 8                 # the error rows alone exceed the device memory
+    with pytest.raises(P.CompAmsError) as ei:
+        P.CompAms(d, n, comp, kb)
+    assert ei.value.code == P.ENOMEM, str(ei.value)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (64 << 20), f"{(free0 - free1) >> 20} MiB still held after the failed create"
+    h = P.CompAms(100_000, 4, comp, kb)
+    h.step(torch.randn(4, 100_000, device="cuda"))
+    assert np.isfinite(h.get_theta()).all()
+    h.destroy()
