@@ -35,6 +35,7 @@ CSRC = os.path.join(ROOT, "paper_2111_00705_amd", "csrc")
 KERNEL_VARIANT = {
     ("tk_pass1", "ef"): "cams::tk_pass1<0, float>", ("tk_pass1", "cd"): "cams::tk_pass1<1, float>",
     ("tk_pass1", "naive"): "cams::tk_pass1<3, float>",
+    ("bs_pass_update", "ef"): "cams::bs_pass_update<true, float",      # the steady-state variant (stored rows pending)
 }
 
 
@@ -73,7 +74,8 @@ def measured_traffic(workload: str, method: str, grad_dtype: str, slot: str):
     section = text.split("## HBM-side traffic", 1)[-1]
     for line in section.splitlines():
         cells = [c.strip() for c in line.strip().strip("|").split("|")]
-        if len(cells) == 7 and (cells[0].strip("`") == want or cells[0].strip("`").startswith(want + "<")):
+        name = cells[0].strip("`")
+        if len(cells) == 7 and (name == want or name.startswith(want + "<") or ("<" in want and name.startswith(want))):
             return float(cells[6]) * 1e6, rel
     return None, f"{rel} has no row for {want}"
 
