@@ -38,6 +38,11 @@
 // Traffic per (worker, coordinate): 4 B g + 4 B stored x read + 4 B x written, plus the candidates
 // (about 1.2 k per worker, 8 B each, written once, read three times).
 //
+// The candidate regions are bounded (see region_base): a region that fills up is detected, and the step then
+// goes the way of a guess that was too high (tk_pick, tk_relist) and, if the lists still do not fit, selects
+// without lists inside tk_resolve (exact_select).  Vectors of at most 16 tiles take three launches: tk_pass1,
+// tk_small_select, tk_final.
+//
 // Exact zeros under error feedback: when fewer than k coordinates are non-zero the k-th largest is a zero and
 // zeros are selected by lower index.  They are never listed as candidates (millions of equal keys would be);
 // tk_pass1 counts them per tile, and tk_resolve places the threshold among them from those counts
@@ -88,7 +93,7 @@ struct TkWorker {
                             // replayed from a HIP graph (which repeats its draw) still reads its predecessor's.
     uint32_t overflow;      // tk_pass1 found a candidate region full: the lists are incomplete, tk_pick counts the
                             // whole vector instead (as after a guess that was too high)
-    uint32_t overflow2;     // tk_relist found a region full as well: tk_exact takes over
+    uint32_t overflow2;     // tk_relist found a region full as well: tk_resolve selects without lists (exact_select)
     uint32_t pad_;
 };
 static_assert(sizeof(TkWorker) == 56, "TkWorker is copied between host and device as plain bytes");
@@ -260,7 +265,7 @@ __device__ __forceinline__ void block_prefix(uint32_t v, uint32_t *pre, uint32_t
 // fit sets the worker's overflow flag and stores nothing: the worker's lists are then incomplete and the step
 // goes on as after a guess that was too high - tk_pick counts the whole vector and tk_relist lists again with
 // the coarse bin of the k-th largest; if that does not fit either (thousands of equal magnitudes: nothing
-// narrower than the whole vector separates them), tk_exact selects without lists.
+// narrower than the whole composite key separates them), tk_resolve selects without lists (exact_select).
 __device__ __forceinline__ int64_t worker_base(const TkGeom &ge, int worker)
 {
     return (int64_t)worker * ge.slices * ge.region_cap;
