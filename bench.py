@@ -40,15 +40,20 @@ KERNEL_VARIANT = {
 
 
 def library_fingerprint() -> str:
-    """Twelve hex digits of a SHA-1 over the library's sources (csrc/*): every rocprofv3 summary under
+    """Twelve hex digits of a SHA-1 over the library's sources (csrc/*, comments and white space removed): every rocprofv3 summary under
     profiles/ records the fingerprint of the build it was taken with, and counter figures are quoted from
     a summary only while it matches the sources in the tree."""
     import hashlib
+    import re
     h = hashlib.sha1()
     for name in sorted(os.listdir(CSRC)):
         if name.endswith((".h", ".hip")):
+            text = open(os.path.join(CSRC, name), encoding="utf-8").read()
+            # comments and layout do not change what is compiled: they are left out of the fingerprint
+            text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+            text = re.sub(r"//[^\n]*", " ", text)
             h.update(name.encode())
-            h.update(open(os.path.join(CSRC, name), "rb").read())
+            h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:12]
 
 

@@ -309,6 +309,9 @@ int fail(comp_ams *h, int code, const char *fmt, ...)
     do {                                                                                              \
         hipError_t err__ = (call);                                                                    \
         if (err__ != hipSuccess) {                                                                    \
+            /* the failure is reported through the status code: the runtime's "last error" is cleared, */ \
+            /* or the caller's next HIP call (or its framework's error check) would trip over it */    \
+            (void)hipGetLastError();                                                                  \
             int code__ = (err__ == hipErrorOutOfMemory) ? COMP_AMS_ENOMEM : COMP_AMS_EDEVICE;         \
             return fail(h, code__, "%s failed: %s", #call, hipGetErrorString(err__));                 \
         }                                                                                             \
