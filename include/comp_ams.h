@@ -104,36 +104,6 @@ int comp_ams_set_lr(comp_ams_t *h, float lr);
 int comp_ams_set_eps_mode(comp_ams_t *h, int32_t mode);
 
 /*
- * Cache policy, a tuning aid (no effect on results).  rows: how a step loads the stored rows (error
- * memory / Markov sequences); state: how it loads and stores theta, m, v, vhat.  1 = as a stream
- * (non-temporal: the data is not kept in the caches), 0 = ordinary accesses, -1 = chosen from the
- * sizes (the default: the rows stream when they exceed 224 MB in total, i.e. when they could not
- * stay in the 256 MB memory-side cache until the next step anyway; the state is left cached only
- * if it fits likewise - with CD-Adam the server's two vectors count with it - and, under error
- * feedback, only if the rows stream).  May be called between steps.
- */
-int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
-
-/*
- * Order in which the workgroups of the streaming pass take the 4096-coordinate tiles of a row, a tuning
- * aid (no effect on results).  The chip hands workgroups to its eight XCDs in turn; with chunk > 0
- * every XCD works through `chunk` consecutive tiles of each group of 8 * chunk tiles, with chunk = 0
- * consecutive tiles go to consecutive XCDs, -1 = chosen from the sizes (the default: 16 when the
- * stored rows exceed 1 GiB in total and the method keeps them - error feedback, CD-Adam - except for
- * Top-k / Rand-k steps on 16-bit gradients; else 0).  chunk <= 65536.  May be called between steps.
- */
-int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
-
-/*
- * Bytes of LDS a workgroup of the block-sign streaming pass reserves, a tuning aid (no effect on
- * results): the amount decides how many workgroups share a compute unit (160 KB each), to which the pass
- * responds by a few per cent.  -1 = chosen from the sizes, the method and the gradient type (the
- * default), else 0 .. 61440; the pass always gets at least what its block table needs (24 KB when a
- * tile holds several blocks' pieces).  No effect on TOPK / RANDK handles.  May be called between steps.
- */
-int comp_ams_set_pass_lds(comp_ams_t *h, int32_t bytes);
-
-/*
  * Rand-k (Appendix A, "Rand-k") only, before the first step: the seed of the draws and the number of
  * the next draw (default 0, 0; a resumed run passes the number of steps already taken).  The paper
  * leaves the drawing of S open.  Here coordinate j of the vector `who` (worker i: who = i; the
@@ -300,40 +270,6 @@ int comp_ams_message_bits(comp_ams_t *h, uint64_t *uplink_per_worker, uint64_t *
 /* Launches an update that the last step left pending and waits until all work enqueued by this handle has
  * completed. */
 int comp_ams_sync(comp_ams_t *h);
-
-/*
- * Per-kernel timing for measurement (Section-independent; a benchmark aid).  While enabled, every
- * kernel that comp_ams_step launches carries two HIP events on the step's stream that are stamped
- * with the kernel's own begin and end (hipExtLaunchKernel), so a slot's time is kernel time
- * without the gaps between launches; event creation makes such steps slower and allocate, so
- * keep it off otherwise.
- * Enabling or disabling waits for pending work and discards earlier recordings.
- */
-int comp_ams_profile(comp_ams_t *h, int enable);
-
-/*
- * Reads one timing slot (slots are numbered from 0; one per kernel of the library): *name
- * receives a static string, *total_ms the summed event time of all recorded launches,
- * *launches their count; any output pointer may be NULL.  Waits for pending work.  Returns 1 (not
- * an error) when slot is past the last one.
- */
-int comp_ams_profile_read(comp_ams_t *h, int32_t slot, const char **name, double *total_ms, int64_t *launches);
-
-/*
- * TOPK handles: how the last step found worker i's threshold, as 8 host words - the fine-bin
- * guess prepared for the next step, the slack (fine bins) behind it, whether the last step's guess
- * was too high (candidates listed twice), the number of magnitude bits left open by the histogram
- * stage, the magnitude prefix, the rank inside it, whether a whole bin was kept, and the fine bin
- * (top 17 magnitude bits) of the threshold.  For diagnosis and tuning; not needed to use the library.
- */
-int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_host);
-
-/*
- * Measurement aid, no handle needed: a plain 16-bytes-per-lane copy of `count` floats
- * (a positive multiple of 4, both pointers 16-byte aligned, device memory) dst <- src, enqueued on
- * hip_stream.  Benchmarks use it to calibrate HBM traffic counters and as the copy ceiling.
- */
-int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream);
 
 /* Message of the last failure on this handle (or of the last failed comp_ams_create when
  * h is NULL).  The string stays valid until the next failing call. */

@@ -9,7 +9,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcomp_ams.so")
 SOURCES = [os.path.join(CSRC, "comp_ams.hip")]
 HEADERS = [os.path.join(CSRC, f) for f in ("device_utils.h", "blocksign_kernels.h", "topk_kernels.h", "plain_kernels.h")] + [
-    os.path.join(os.path.dirname(HERE), "include", "comp_ams.h")]
+    os.path.join(os.path.dirname(HERE), "include", "comp_ams.h"),
+    os.path.join(os.path.dirname(HERE), "include", "comp_ams_tuning.h")]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -2,6 +2,7 @@
 // memory, kernel launches.  Every step of the method runs in the kernels of the two *_kernels.h
 // files; nothing is computed on the host.
 #include "../../include/comp_ams.h"
+#include "../../include/comp_ams_tuning.h"
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>

@@ -5,6 +5,7 @@
  * Returns 0 when every call answered as the header says.
  */
 #include "comp_ams.h"
+#include "comp_ams_tuning.h"
 
 #include <math.h>
 #include <stdio.h>
