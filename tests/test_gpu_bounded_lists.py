@@ -78,6 +78,32 @@ def test_inputs_that_overflow_the_candidate_lists(method, d, n, k):
     ora.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("method", [P.METHOD_NAIVE, P.METHOD_CD])
+def test_selection_without_lists_reforms_the_vector_from_16_bit_gradients(method, dtype):
+    """Naive compression and the workers of CD-Adam compress a vector that is not stored (g, g - ghat_i): the
+    selection without lists re-forms it from the gradients, which may be bfloat16 or half."""
+    import torch
+    print(f"[case] bounded lists, 16-bit gradients method={method} {dtype}", flush=True)
+    d, n, k = 120_001, 2, 1_200
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float16
+    gpu = P.CompAms(d, n, P.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR)
+    ora = O.Oracle(d, n, O.TOPK, k, W.BETA1, W.BETA2, W.EPS, W.LR, method=method)
+    gpu.set_method(method)
+    rng = np.random.default_rng(9)
+    seq = [np.full((n, d), 0.25, f32), rng.standard_normal((n, d)).astype(f32), np.full((n, d), -3.0, f32),
+           rng.standard_normal((n, d)).astype(f32)]
+    for t, g in enumerate(seq):
+        g16 = torch.from_numpy(g).to(tt)
+        (gpu.step_bf16 if dtype == "bf16" else gpu.step_f16)(g16.cuda())
+        ora.step(g16.float().numpy())
+        check(gpu, ora, method, f"step {t}")
+        if t == 0 or (method == P.METHOD_NAIVE and t == 2):
+            assert gpu.get_selection_info(0)["whole_bin"] == 3, f"step {t}: expected the selection without lists"
+    gpu.destroy()
+    ora.close()
+
+
 def test_all_equal_input_over_many_steps_without_reading_state_in_between():
     """The deferred update and the fallbacks together: ten steps in a row with nothing read back, every second
     one all-equal, compared at the end."""
@@ -96,11 +122,12 @@ def test_all_equal_input_over_many_steps_without_reading_state_in_between():
     ora.close()
 
 
-def test_handle_memory_is_bounded():
+@pytest.mark.parametrize("d,n,k", [(8_000_000, 8, 8_000), (110_000_000, 8, 110_000)])
+def test_handle_memory_is_bounded(d, n, k):
     """What the handle allocates besides state and error memory stays a fraction of the error memory: the lists are
-    sized for a multiple of the steady-state candidate count, not for every coordinate."""
+    sized for a multiple of the steady-state candidate count, not for every coordinate.  The second case is the
+    largest of the five workloads: 3.52 GB of error memory, 1.76 GB of state, and the whole handle under 6.5 GB."""
     import torch
-    d, n, k = 8_000_000, 8, 8_000
     torch.cuda.synchronize()
     free0, _ = torch.cuda.mem_get_info()
     gpu = P.CompAms(d, n, P.TOPK, k)
@@ -111,4 +138,6 @@ def test_handle_memory_is_bounded():
     state = 4 * 4 * d
     print(f"[case] handle memory: {used / 1e6:.0f} MB for rows {rows / 1e6:.0f} MB + state {state / 1e6:.0f} MB", flush=True)
     assert used < rows + state + rows // 4 + (64 << 20)
+    if d == 110_000_000:
+        assert used < 6.5e9
     gpu.destroy()

@@ -373,21 +373,18 @@ def scaled_sign_by_definition(x, offsets):
 
 
 def test_layer_table_hand_example_in_the_stateful_optimiser():
-    """oracle_set_blocks: the table replaces the uniform blocks of create.  Hand example (Appendix A,
-    scaled sign per block): x = [1,-3 | 2,2 | -0,0 | 8] has scales 2, 2, 0, 8; under error feedback the
-    second step compresses g + e with the same table."""
-    x = np.array([[1, -3, 2, 2, -0.0, 0.0, 8]], f32)               # g + e with e = +0 turns the -0 into +0
-    o = O.Oracle(7, 1, O.BLOCKSIGN, 3, 0.9, 0.999, 1e-8, 1e-3)       # create says blocks of 3 ...
-    o.set_blocks([0, 2, 4, 6, 7])                                      # ... the table says otherwise
-    assert o.n_blocks == 4
-    o.step(x)
-    assert o.scales[0].tolist() == [2.0, 2.0, 0.0, 8.0]
-    assert np.array_equal(bits(o.compressed[0]), bits([2, -2, 2, 2, 0.0, 0.0, 8]))
-    assert np.array_equal(bits(o.error[0]), bits([-1, -1, 0, 0, 0.0, 0.0, 0]))      # x - C(x)
-    o.step(x)                                # x_2 = g + e = [0,-4 | 2,2 | 0,0 | 8]
-    assert o.scales[0].tolist() == [2.0, 2.0, 0.0, 8.0]
-    assert np.array_equal(bits(o.compressed[0]), bits([2, -2, 2, 2, 0.0, 0.0, 8]))
-    assert np.array_equal(bits(o.error[0]), bits([-2, -2, 0, 0, 0.0, 0.0, 0]))
+    """oracle_set_blocks: the table replaces the uniform blocks of create.  Hand example (tests/golden/example_e...:
+    Appendix A's scaled sign per block; under error feedback the second step compresses g + e with the same table)."""
+    ex = json.load(open(os.path.join(GOLD, "example_e_layer_table_scaled_sign.json")))
+    g = np.array([ex["g_every_step"]], f32)
+    o = O.Oracle(ex["d"], ex["n"], O.BLOCKSIGN, 3, 0.9, 0.999, 1e-8, 1e-3)       # create says blocks of 3 ...
+    o.set_blocks(ex["offsets"])                                                    # ... the table says otherwise
+    assert o.n_blocks == len(ex["offsets"]) - 1
+    for t, want in enumerate(ex["steps"]):
+        o.step(g)
+        assert o.scales[0].tolist() == want["scales"], t
+        assert np.array_equal(bits(o.compressed[0]), bits(want["compressed"])), t
+        assert np.array_equal(bits(o.error[0]), bits(want["error"])), t          # x - C(x)
     o.close()
 
 
