@@ -25,12 +25,19 @@ NAIVE = 2   # naive compression (Section 4), no memory
 NONE = 3    # no compression: vanilla distributed AMSGrad (Section 3)
 
 
+_SWEEP_SRC = os.path.join(_HERE, "sanitize_sweep.c")
+_SWEEP = os.path.join(_HERE, "sanitize_sweep.bin")
+
+
 def build(force: bool = True) -> str:
-    """Compile the oracle with gcc: -O2, no FMA contraction, no fast-math."""
+    """Compile the oracle with gcc: -O2, no FMA contraction, no fast-math.  A forced build also compiles the
+    sweep driver (oracle/sanitize_sweep.c) with the same flags, as a check that it builds; the sanitizer run
+    itself is tests/test_sanitizers.py's, with its own instrumented binary."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC",
-               "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
+        flags = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-Wall", "-Wextra"]
+        subprocess.run(flags + ["-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"], check=True)
+        if force:
+            subprocess.run(flags + ["-o", _SWEEP, _SWEEP_SRC, _SRC, "-lm"], check=True)
     return _LIB
 
 
