@@ -20,6 +20,24 @@ HIPCC_FLAGS = [
 ]
 
 
+# A plain-C caller of the ABI (tests/c/abi_roundtrip.c), built next to the library so that the GPU tests can run it:
+# gcc, the HIP runtime API header for device memory, the library by its path.
+C_CALLER_SRC = os.path.join(os.path.dirname(HERE), "tests", "c", "abi_roundtrip.c")
+C_CALLER = os.path.join(os.path.dirname(HERE), "tests", "c", "abi_roundtrip.bin")
+
+
+def build_c_caller(verbose: bool = False) -> str:
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-Wextra", "-I", os.path.join(os.path.dirname(HERE), "include"),
+           "-I", os.path.join(rocm, "include"), "-o", C_CALLER, C_CALLER_SRC, "-L", HERE, "-lcomp_ams",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2111_00705_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_CALLER
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -34,6 +52,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+        build_c_caller(verbose)
     return LIB
 
 
