@@ -240,6 +240,7 @@ def main() -> int:
     # plain float4 copy on the same stream: what a trivial streaming kernel reaches on this chip, and
     # the launch that calibrates the HBM byte counters (it moves exactly 2 * probe bytes)
     copy_ceiling = None
+    stream_ceiling = None
     if args.probe_mib > 0:
         count = args.probe_mib * (1 << 20) // 4
         src = torch.empty(count, dtype=torch.float32, device="cuda").normal_()
@@ -254,7 +255,20 @@ def main() -> int:
         torch.cuda.synchronize()
         copy_ceiling = {"gbs": round(2 * count * 4 * reps / (time.perf_counter() - c0) / 1e9, 1),
                         "bytes_per_launch": 2 * count * 4, "kernel": "probe_copy"}
-        del src, dst
+        # the passes' own access pattern with nothing else (two arrays read, one of them written back in place):
+        # the practical ceiling for the dominant kernel on this chip
+        xs, gs = dst.view(8, count // 8), src.view(8, count // 8)
+        for _ in range(3):
+            P.probe_update(xs, gs)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            P.probe_update(xs, gs)
+        torch.cuda.synchronize()
+        stream_ceiling = {"gbs": round(3 * count * 4 * reps / (time.perf_counter() - c0) / 1e9, 1),
+                          "bytes_per_launch": 3 * count * 4, "kernel": "probe_update",
+                          "pattern": "x[i][j] += g[i][j] in place, 8 rows"}
+        del src, dst, xs, gs
 
     cpu = None
     if not args.no_cpu:
@@ -303,6 +317,7 @@ def main() -> int:
         "step_frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "kernels": {k: {a: round(b, 3) for a, b in v.items()} for k, v in kernels.items()},
         "copy_ceiling": copy_ceiling,
+        "stream_ceiling": stream_ceiling,
         "library_fingerprint": library_fingerprint(),
         "cpu_baseline": cpu,
     }

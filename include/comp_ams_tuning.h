@@ -79,6 +79,15 @@ int comp_ams_get_selection_info(comp_ams_t *h, int32_t worker, uint32_t *out_hos
  */
 int comp_ams_probe_copy(float *dst_dev, const float *src_dev, int64_t count, void *hip_stream);
 
+/*
+ * Measurement aid, no handle needed: the access pattern of the library's streaming passes with nothing else -
+ * x[i][j] = x[i][j] + g[i][j] in place for `rows` rows of d floats each (row-major, d a positive multiple of 4,
+ * both pointers 16-byte aligned, device memory), enqueued on hip_stream.  It moves exactly 12 bytes per element;
+ * what it reaches is the practical ceiling on this chip for a kernel that reads two arrays and writes one of them
+ * back, which benchmarks report next to the passes' own rate.
+ */
+int comp_ams_probe_update(float *x_dev, const float *g_dev, int64_t rows, int64_t d, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,7 @@ EXPORTS = [
     "comp_ams_set_method", "comp_ams_get_ghat_worker", "comp_ams_get_ghat_server", "comp_ams_get_gtilde",
     "comp_ams_get_server_scales", "comp_ams_set_markov_state", "comp_ams_get_server_selected",
     "comp_ams_message_bits", "comp_ams_get_signs", "comp_ams_step_bf16", "comp_ams_step_f16", "comp_ams_set_rand", "comp_ams_set_streaming", "comp_ams_set_tile_order", "comp_ams_set_pass_lds", "comp_ams_message_bytes", "comp_ams_pack_message",
-    "comp_ams_pack_message_noalloc",
+    "comp_ams_pack_message_noalloc", "comp_ams_probe_update",
 ]
 
 
@@ -88,6 +88,7 @@ def lib():
         L.comp_ams_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                             C.POINTER(C.c_int64)]
         L.comp_ams_probe_copy.argtypes = [fp, fp, C.c_int64, vp]
+        L.comp_ams_probe_update.argtypes = [fp, fp, C.c_int64, C.c_int64, vp]
         L.comp_ams_get_selection_info.argtypes = [vp, C.c_int32, u32p]
         L.comp_ams_set_method.argtypes = [vp, C.c_int32]
         L.comp_ams_get_ghat_worker.argtypes = [vp, C.c_int32, fp, C.c_int]
@@ -113,6 +114,17 @@ def _ptr(a):
         return a.ctypes.data, 0
     assert a.dtype.is_floating_point and a.element_size() == 4 and a.is_contiguous()
     return a.data_ptr(), 1 if a.is_cuda else 0
+
+
+def probe_update(x, g, stream=None):
+    """x += g in place (torch float32 CUDA tensors [rows, d], d a multiple of 4): the passes' access pattern alone."""
+    import torch
+    assert x.is_cuda and g.is_cuda and x.shape == g.shape and x.dim() == 2 and x.is_contiguous() and g.is_contiguous()
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    rc = lib().comp_ams_probe_update(x.data_ptr(), g.data_ptr(), x.shape[0], x.shape[1], stream)
+    if rc != OK:
+        raise CompAmsError(rc, lib().comp_ams_last_error(None).decode())
 
 
 def probe_copy(dst, src, stream=None):

@@ -261,4 +261,32 @@ __global__ __launch_bounds__(kThreads) void probe_copy(float *__restrict__ dst, 
         if (q0 + r * kThreads < vecs) st4_stream(dst + 4 * (q0 + r * kThreads), v[r]);
 }
 
+// The access pattern of the streaming passes with nothing else: x[i][j] = x[i][j] + g[i][j] in place, rows of d
+// floats (d a multiple of 4, rows 16-byte aligned), one 16 KB piece of a row per workgroup, non-temporal on all
+// three streams.  What this reaches is the practical ceiling for a kernel that reads two arrays and writes one of
+// them back on this chip; the passes are measured against it.  chunk: tile_of_block's, over the pieces of a row.
+__global__ __launch_bounds__(kThreads) void probe_update(float *__restrict__ x, const float *__restrict__ g, int64_t d,
+                                                         int pieces, int chunk)
+{
+    const int t = tile_of_block(blockIdx.x, chunk);
+    if (t >= pieces) return;
+    const int64_t row = (int64_t)blockIdx.y * d;
+    const int64_t j0 = (int64_t)t * kTile + 4 * threadIdx.x;
+    float4 a[4], b[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = j0 + 4 * kThreads * r;
+        if (j < d) {
+            a[r] = stream_load4(g + row + j);
+            b[r] = stream_load4(x + row + j);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t j = j0 + 4 * kThreads * r;
+        if (j < d) st4_stream(x + row + j, make_float4(fadd(a[r].x, b[r].x), fadd(a[r].y, b[r].y), fadd(a[r].z, b[r].z),
+                                                       fadd(a[r].w, b[r].w)));
+    }
+}
+
 }  // namespace cams

@@ -72,6 +72,8 @@ int main(void)
     EXPECT(comp_ams_sync(NULL), COMP_AMS_EINVAL);
     EXPECT(comp_ams_probe_copy(NULL, buf, 4, NULL), COMP_AMS_EINVAL);
     EXPECT(comp_ams_probe_copy(buf, buf, 3, NULL), COMP_AMS_EINVAL);
+    EXPECT(comp_ams_probe_update(NULL, buf, 1, 4, NULL), COMP_AMS_EINVAL);
+    EXPECT(comp_ams_probe_update(buf, buf, 1, 6, NULL), COMP_AMS_EINVAL);
     comp_ams_destroy(NULL);
 
     /* valid arguments: a handle on a machine with a GPU, a device error (not a crash) without one */

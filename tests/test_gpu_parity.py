@@ -451,3 +451,21 @@ def test_blocksign_with_blocks_shorter_and_longer_than_a_tile(block):
 
 def ora_offsets(d, block):
     return np.minimum(np.arange((d + block - 1) // block + 1, dtype=np.int64) * block, d)
+
+
+def test_probe_update_adds_in_place_in_both_launch_shapes():
+    """comp_ams_probe_update (a measurement aid): x += g, exactly, for a small problem (plain launch shape) and
+    for one beyond a GiB (three workgroups per compute unit, XCD-aware piece order), ragged row lengths included."""
+    import torch
+    announce("probe_update")
+    for rows, d in ((3, 4 * 1237), (5, 4 * 13_500_001)):
+        g = torch.randn(rows, d, device="cuda")
+        x = torch.randn(rows, d, device="cuda")
+        want = x + g
+        P.probe_update(x, g)
+        torch.cuda.synchronize()
+        assert torch.equal(x, want)
+        del g, x, want
+    with pytest.raises(P.CompAmsError) as ei:
+        P.probe_update(torch.zeros(2, 6, device="cuda"), torch.zeros(2, 6, device="cuda"))      # d not a multiple of 4
+    assert ei.value.code == P.EINVAL
