@@ -541,7 +541,8 @@ int step_blocksign(comp_ams *h, const G *g, hipStream_t st)
 // (flush_pending).  Not used while the stream is being captured: a recorded step must be self-contained.
 inline bool can_defer_blocksign(const comp_ams *h)
 {
-    return h->method == COMP_AMS_METHOD_EF && h->fused_scale && h->tb.uniform_tiles > 0;
+    // the grid's second dimension holds the workers and four rows of update workgroups
+    return h->method == COMP_AMS_METHOD_EF && h->fused_scale && h->tb.uniform_tiles > 0 && h->n + 4 <= 65535;
 }
 
 template <typename G>

@@ -135,7 +135,8 @@ def test_block_sign_at_the_largest_dimension():
     ora.close()
 
 
-@pytest.mark.parametrize("comp,d,kb", [(P.TOPK, 5, 2), (P.TOPK, 4100, 7), (P.BLOCKSIGN, 5, 3), (P.RANDK, 9, 4)])
+@pytest.mark.parametrize("comp,d,kb", [(P.TOPK, 5, 2), (P.TOPK, 4100, 7), (P.BLOCKSIGN, 5, 3), (P.RANDK, 9, 4),
+                                       (P.BLOCKSIGN, 4100, 4096)])
 def test_the_largest_worker_count(comp, d, kb):
     import torch
     n = 65535

@@ -469,3 +469,24 @@ def test_probe_update_adds_in_place_in_both_launch_shapes():
     with pytest.raises(P.CompAmsError) as ei:
         P.probe_update(torch.zeros(2, 6, device="cuda"), torch.zeros(2, 6, device="cuda"))      # d not a multiple of 4
     assert ei.value.code == P.EINVAL
+
+
+@pytest.mark.parametrize("n,d,block", [(3000, 8200, 4096), (1100, 20_000, 8192), (65_531, 4100, 4096)])
+def test_block_sign_with_uniform_tile_blocks_and_many_workers(n, d, block):
+    """The one-launch path of block sign (the pass kernel carries the previous step's update): more workers than
+    the 1024 whose scales the update stages at a time, blocks of one and of two tiles, a partial last block, and
+    the largest worker count the path takes; steps back to back, then compared, then one more step."""
+    import torch
+    announce(f"block sign, uniform tile blocks, n={n} d={d} B={block}")
+    gpu, ora = make_pair(d, n, P.BLOCKSIGN, block)
+    off = np.minimum(np.arange((d + block - 1) // block + 1, dtype=np.int64) * block, d)
+    rng = np.random.default_rng(n)
+    for t in range(4):
+        g = rng.standard_normal((n, d)).astype(f32)
+        gpu.step(torch.from_numpy(g).cuda())
+        ora.step(g)
+        if t == 2:
+            compare(gpu, ora, tag=f"n={n} step {t}", check_error=(n <= 4000), offsets=off)
+    compare(gpu, ora, tag=f"n={n} after the last step", check_error=(n <= 4000), offsets=off)
+    gpu.destroy()
+    ora.close()
