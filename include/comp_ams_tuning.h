@@ -37,11 +37,13 @@ int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
 int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
 
 /*
- * Bytes of LDS a workgroup of the block-sign streaming pass reserves, a tuning aid (no effect on
- * results): the amount decides how many workgroups share a compute unit (160 KB each), to which the pass
- * responds by a few per cent.  -1 = chosen from the sizes, the method and the gradient type (the
- * default), else 0 .. 61440; the pass always gets at least what its block table needs (24 KB when a
- * tile holds several blocks' pieces).  No effect on TOPK / RANDK handles.  May be called between steps.
+ * Bytes of LDS a workgroup of the streaming pass reserves, a tuning aid (no effect on results): the
+ * amount decides how many workgroups share a compute unit (160 KB each), to which the pass responds by a
+ * few per cent.  -1 = chosen from the sizes, the method and the gradient type (the default), else
+ * 0 .. 61440.  BLOCKSIGN: the pass always gets at least what its block table needs (24 KB when a tile
+ * holds several blocks' pieces).  TOPK / RANDK: the amount is added to the 24 KB of candidate staging
+ * lists the pass always holds (default: 9 KB under error feedback, else none); no effect on vectors of
+ * at most 16 tiles.  May be called between steps.
  */
 int comp_ams_set_pass_lds(comp_ams_t *h, int32_t bytes);
 

@@ -93,6 +93,7 @@ struct comp_ams {
     uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
+    uint32_t *hist2 = nullptr;                 // [n][1024] threshold bin: counts of the first digit below the prefix
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
 
     uint2 *dense_dir = nullptr;                // [n][64 * parts * 4] {start, count} of each wavefront's piece
@@ -101,7 +102,7 @@ struct comp_ams {
     float *sel_out_val = nullptr;
     // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
     TkSide srv{};
-    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr;
+    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr, *hist2_s = nullptr;
     uint64_t *dense_s = nullptr;
     uint2 *dense_dir_s = nullptr;
 
@@ -638,7 +639,7 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 // selection without lists), last digits.  kSrc / a / b say how tk_relist forms the compressed vector again.
 template <int kSrc, typename G>
 void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
-                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint64_t *dense,
+                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint32_t *hist2, uint64_t *dense,
                    uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5])
 {
     const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
@@ -654,13 +655,13 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
         KLAUNCH((tk_relist<kSrc, G>), sweep, kThreads, st, a, b, ge, ws, hist_full, cand, cursor, tile_dir);
     });
     launch_timed(h, slot[3], st, [&] {
-        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir);
+        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir, hist2);
     });
     launch_timed(h, slot[4], st, [&] {
         // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
         const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
         const ExactSource es{kSrc, std::is_same<G, float>::value ? 0 : std::is_same<G, uint16_t>::value ? 1 : 2, a, b};
-        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, cand, tile_dir, rows,
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, hist2, cand, tile_dir, rows,
                 es);
     });
 }
@@ -677,6 +678,17 @@ void launch_final(comp_ams *h, hipStream_t st)
                     h->theta, h->m, h->v, h->vhat, h->params);
         });
     });
+}
+
+// Dynamic LDS handed to tk_pass1 beyond its own 24 KB of staging lists: unused by the kernel, it only sets how many
+// workgroups share a compute unit (six without it).  The passes that only read want all six (n = 16, d = 11.2 M,
+// CD-Adam: 245 against 257 us with four; n = 8, d = 110 M: 1.134 against 1.173 ms).  The error-feedback pass, which
+// also writes the row back, is best with four or five (n = 8, d = 110 M: 1.67-1.68 ms, 1.70 with six, 1.74 with
+// eight) and gets 9 KB, which leaves four.  comp_ams_set_pass_lds overrides.
+inline unsigned tk_pass_lds(const comp_ams *h)
+{
+    if (h->lds_choice >= 0) return (unsigned)h->lds_choice;
+    return h->method == COMP_AMS_METHOD_EF ? 9u * 1024u : 0u;
 }
 
 // Error feedback on a short vector: listing pass, one selection kernel (tk_small_select), update - three launches.
@@ -706,10 +718,10 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
                                      h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
@@ -722,10 +734,10 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
                                    h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
@@ -752,10 +764,10 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom pge = pass_geometry<G>(h);
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full,
+    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
                                h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
@@ -766,7 +778,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
                 h->gtil, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
     });
     launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
-                                   h->hist_full_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
+                                   h->hist_full_s, h->hist2_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
             KLAUNCH((tk_apply<decltype(ss)::value>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v,
@@ -1014,6 +1026,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
             (rc = dev_alloc_t(h, h->allocs, &h->hist_full, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->histf, (size_t)n * kFineWindow)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->hist2, (size_t)n * kBinsFirst)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * ge.slices * ge.parts * 4)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->small_ctr, (size_t)n)) ||
@@ -1554,6 +1567,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
                 (rc = dev_alloc_t(h, h->allocs, &h->hist_full_s, (size_t)kBins1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->hist1_s, (size_t)kBins1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->histf_s, (size_t)kFineWindow)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->hist2_s, (size_t)kBinsFirst)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->dense_s, region_entries, false)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->dense_dir_s, (size_t)sv.ge.slices * sv.ge.parts * 4)))
                 return rc;

@@ -16,8 +16,8 @@
 //   tk_pass1    one workgroup per (tile, worker): streams g and the stored x once and writes the new
 //               x; lists "candidates" - elements whose fine magnitude bin (top 17 bits, 0.2 % wide)
 //               is >= the worker's guess, which is the previous step's threshold minus a little
-//               slack - as (index, value) pairs, staged in LDS and appended densely to one of 64
-//               regions of the worker (one atomic add per tile).
+//               slack - as (index, value) pairs, staged in LDS (value and place in the tile, 6 bytes)
+//               and appended densely to one of 64 regions of the worker (one atomic add per tile).
 //               A workgroup per tile (instead of a loop over tiles) matters: on this chip a wave
 //               that loops must wait for its stores before it can use its next loads.
 //   tk_hist     histograms of the candidates: coarse bins (top 11 bits) and the fine bins of the
@@ -63,6 +63,9 @@ constexpr int kFinePerCoarse = 1 << (kShift1 - kFineShift);
 constexpr int kFineWindow = 2 * kFinePerCoarse;   // fine bins counted: the guess's coarse bin and the next
 constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
+constexpr int kFirstBits = 10;    // first digit below the prefix, counted by tk_compact while it copies: narrower,
+                                  // since every one of its workgroups clears and flushes the bins
+constexpr int kBinsFirst = 1 << kFirstBits;
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
 constexpr int kMinSlices = 64;    // candidate regions per vector: a power of two in [kMinSlices, kMaxSlices]
                                   // (fewer for a vector of fewer tiles than that)
@@ -332,13 +335,23 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
     for (uint32_t q = lane; q < count; q += kWave) dst[q] = stage[q];
 }
 
+// A wavefront's staged candidates in tk_pass1: the value and the coordinate's place inside the tile, 6 bytes per
+// entry instead of the 8 of an (index, value) pair.  With room for every coordinate of the wavefront (so the list
+// cannot overflow) a workgroup's four lists take 24 KB, and six workgroups fit a compute unit where 32 KB allowed
+// four: the passes that only read (CD-Adam, naive compression) run 3-5 % faster with the additional loads in flight.
+struct Stage {
+    float *val;          // [kSub]
+    uint16_t *at;        // [kSub] index - first index of the tile
+};
+
 // Stages one element of the vector that is compressed as a candidate if its fine bin reaches the guess.
+// base: first index of the tile.
 // kSkipZeros (error feedback with magnitude keys): exact zeros are never listed but counted (zeros, uniform
 // over the wavefront) - when fewer than k coordinates are non-zero the threshold lies among the zeros, which
 // are ordered by index alone, and is placed from these counts instead (see zero_tail_threshold).
 template <bool kSkipZeros>
-__device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32_t guess, const SelKey &sk,
-                                         uint2 *stage, uint32_t &count, uint32_t &zeros)
+__device__ __forceinline__ void consider(float x, uint32_t j, uint32_t base, bool valid, uint32_t guess, const SelKey &sk,
+                                         const Stage &stage, uint32_t &count, uint32_t &zeros)
 {
     bool hit = valid && (sel_key(sk, x, j) >> kFineShift) >= guess;
     if (kSkipZeros && !sk.on) {
@@ -347,7 +360,10 @@ __device__ __forceinline__ void consider(float x, uint32_t j, bool valid, uint32
         hit = hit && !zero;
     }
     const uint32_t slot = wave_append(hit, count);
-    if (hit) stage[slot] = make_uint2(j, __float_as_uint(x));
+    if (hit) {
+        stage.val[slot] = x;
+        stage.at[slot] = (uint16_t)(j - base);
+    }
 }
 
 // One tile of one worker.  kFull: the whole tile lies below d.  Candidates are staged in LDS (one
@@ -362,7 +378,7 @@ enum { kPassEf = 0, kPassCd = 1, kPassDiff = 2, kPassNaive = 3 };
 template <bool kFull, int kMode, typename G>
 __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float *__restrict__ xrow,
                                                uint32_t base, uint32_t d, const KeptTest &kt, uint32_t guess,
-                                               const SelKey &sk, const SelKey &sk_prev, uint2 *stage,
+                                               const SelKey &sk, const SelKey &sk_prev, const Stage &stage,
                                                int stream_rows, uint32_t &zeros)
 {
     const int tid = threadIdx.x;
@@ -398,7 +414,7 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
         if (kMode == kPassEf) st4_stream(xrow + j, make_float4(x[0], x[1], x[2], x[3]));
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-            consider<kMode == kPassEf>(x[c], j + c, kFull || j + c < d, guess, sk, stage, count, zeros);
+            consider<kMode == kPassEf>(x[c], j + c, base, kFull || j + c < d, guess, sk, stage, count, zeros);
     }
     return count;
 }
@@ -409,7 +425,8 @@ __device__ __forceinline__ uint32_t pass1_tile(const G *__restrict__ grow, float
 // three leave at once instead of waiting for the atomic.
 // sh: 9 LDS words, sh[4] zeroed (with a barrier after it) before the first wavefront can get here.
 // zeros: this wavefront's count of exact zeros; the tile's sum goes into the directory record's last word.
-__device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t *sh, uint32_t count, uint32_t zeros,
+__device__ __forceinline__ void finish_tile(const float (*stage_val)[kSub], const uint16_t (*stage_at)[kSub], uint32_t *sh,
+                                            uint32_t count, uint32_t zeros,
                                             const TkGeom &ge, int i, int t, uint2 *__restrict__ cand,
                                             uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir,
                                             uint32_t *overflow_flag)
@@ -433,9 +450,11 @@ __device__ __forceinline__ void finish_tile(const uint2 (*stage)[kSub], uint32_t
     at = __builtin_amdgcn_readfirstlane(at);
     if (at == kNoSpace) return;
     uint2 *dst = cand + worker_base(ge, i) + at;
+    const uint32_t base = (uint32_t)t * kTile;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-        for (uint32_t q = lane; q < cnt[w]; q += kWave) dst[q] = stage[w][q];
+        for (uint32_t q = lane; q < cnt[w]; q += kWave)
+            dst[q] = make_uint2(base + stage_at[w][q], __float_as_uint(stage_val[w][q]));
         dst += cnt[w];
     }
 }
@@ -446,7 +465,8 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
                                                      TkWorker *ws, uint2 *__restrict__ cand,
                                                      uint32_t *__restrict__ cursor, uint4 *__restrict__ tile_dir)
 {
-    __shared__ uint2 stage[4][kSub];
+    __shared__ float stage_val[4][kSub];
+    __shared__ uint16_t stage_at[4][kSub];
     __shared__ uint32_t sh[9];
     const int t = tile_of_block(blockIdx.x, ge.xcd_chunk);
     if (t >= ge.n_tiles) return;
@@ -463,13 +483,14 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
     __syncthreads();
     uint32_t count, zeros = 0;
     const G *grow = g + (int64_t)i * (kMode == kPassDiff ? ge.ld : ge.d);
+    const Stage stage{stage_val[wave], stage_at[wave]};
     if (base + kTile <= d)
         count = pass1_tile<true, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                           stage[wave], ge.stream_rows, zeros);
+                                           stage, ge.stream_rows, zeros);
     else
         count = pass1_tile<false, kMode, G>(grow, xs + (int64_t)i * ge.ld, base, d, kt, guess, sk, sk_prev,
-                                            stage[wave], ge.stream_rows, zeros);
-    finish_tile(stage, sh, count, zeros, ge, i, t, cand, cursor, tile_dir, &ws[i].overflow);
+                                            stage, ge.stream_rows, zeros);
+    finish_tile(stage_val, stage_at, sh, count, zeros, ge, i, t, cand, cursor, tile_dir, &ws[i].overflow);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -939,8 +960,10 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
 __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
                                                        const uint2 *__restrict__ cand,
                                                        const uint32_t *__restrict__ cursor,
-                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir)
+                                                       uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir,
+                                                       uint32_t *__restrict__ hist2)
 {
+    __shared__ uint32_t lh2[kBinsFirst];
     const int per = gridDim.x;
     const int i = blockIdx.y;
     const int bx = blockIdx.x;
@@ -948,6 +971,10 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t prefix = ws[i].prefix, pshift = ws[i].pshift;
+    // the digit of comp right below the prefix (tk_resolve's first digit)
+    const int s_lo = (int)pshift + ge.idx_bits - kFirstBits;      // pshift >= kFineShift > kFirstBits
+    for (int b = tid; b < kBinsFirst; b += kThreads) lh2[b] = 0;
+    __syncthreads();
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const Piece pc = piece_of(ge, cursor, i);
     const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
@@ -968,12 +995,21 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
             const uint32_t key = sel_key(sk, __uint_as_float(c[u].y), c[u].x);
             const bool hit = qb + u * kWave + lane < w1 && (key >> pshift) == prefix;
             const uint32_t slot = wave_append(hit, count);
-            if (hit) out[slot] = composite(key, c[u].x, ge.idx_bits);
+            if (hit) {
+                const uint64_t comp = composite(key, c[u].x, ge.idx_bits);
+                out[slot] = comp;
+                atomicAdd(&lh2[(uint32_t)(comp >> s_lo) & (uint32_t)(kBinsFirst - 1)], 1u);
+            }
         }
     }
     if (lane == 0) {
         const int64_t rec = ((int64_t)i * per + bx) * 4 + wave;
         dense_dir[rec] = make_uint2((uint32_t)(rbase - worker_base(ge, i)) + w0, count);
+    }
+    __syncthreads();
+    for (int b = tid; b < kBinsFirst; b += kThreads) {
+        const uint32_t c = lh2[b];
+        if (c) atomicAdd(hist2 + (int64_t)i * kBinsFirst + b, c);
     }
 }
 
@@ -1006,32 +1042,37 @@ struct ResolveLds {
 // Tc - right when every element of the vector that could fall into that bin is among the cnt delivered (the
 // threshold bin of tk_compact is), wrong when the elements are only those above some bound that may cut the bin
 // (the candidate list of tk_small_pass): then the search goes on to the k-th largest comp value itself.
+// have_first: the first digit has kFirstBits bits and its counts are in L.lh[0 .. kBinsFirst) already (with a
+// barrier after them); the first scan is not made.
 template <bool kWholeBins = true, class Fetch>
 __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, uint64_t prefix, uint32_t rank, int s_hi,
-                                                   ResolveLds &L)
+                                                   ResolveLds &L, bool have_first = false)
 {
     const int tid = threadIdx.x;
     const int nt = (int)blockDim.x;
     uint64_t tc = prefix << s_hi;
     bool done = false;
     while (!done) {
-        const int s_lo = max(s_hi - kDigitBits, 0);
+        const int s_lo = max(s_hi - (have_first ? kFirstBits : kDigitBits), 0);
         const uint32_t mask = (1u << (s_hi - s_lo)) - 1u;
-        for (int b = tid; b < kBins2; b += nt) L.lh[b] = 0;
-        __syncthreads();
-        for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * nt) {
-            uint32_t q[kScanUnroll];
-            uint64_t comp[kScanUnroll];
+        if (!have_first) {
+            for (int b = tid; b < kBins2; b += nt) L.lh[b] = 0;
+            __syncthreads();
+            for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * nt) {
+                uint32_t q[kScanUnroll];
+                uint64_t comp[kScanUnroll];
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * nt + tid;
-            fetch(q, comp);                                 // independent loads: all in flight at once
+                for (int u = 0; u < kScanUnroll; ++u) q[u] = qb + u * nt + tid;
+                fetch(q, comp);                                 // independent loads: all in flight at once
 #pragma unroll
-            for (int u = 0; u < kScanUnroll; ++u)
-                if (q[u] < cnt && (comp[u] >> s_hi) == prefix)
-                    atomicAdd(&L.lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
+                for (int u = 0; u < kScanUnroll; ++u)
+                    if (q[u] < cnt && (comp[u] >> s_hi) == prefix)
+                        atomicAdd(&L.lh[(uint32_t)(comp[u] >> s_lo) & mask], 1u);
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        find_rank_bin(L.lh, L.part, L.res, kBins2, rank);
+        find_rank_bin(L.lh, L.part, L.res, have_first ? kBinsFirst : kBins2, rank);
+        have_first = false;
         if (!L.res[3]) break;                                  // cannot happen: rank <= matching elements
         prefix = (prefix << (s_hi - s_lo)) | L.res[0];
         rank -= L.res[1];
@@ -1310,6 +1351,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
                                                               const uint2 *__restrict__ dense_dir,
                                                               uint32_t *__restrict__ cursor,
                                                               uint32_t *__restrict__ hist_full,
+                                                              uint32_t *__restrict__ hist2,
                                                               uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir,
                                                               const float *__restrict__ xs, ExactSource es)
 {
@@ -1337,6 +1379,13 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
     } else if (w.whole == kZeroTail) {
         tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank, L);
     } else if (!w.whole) {
+        // tk_compact counted the first digit below the prefix while it copied: take its counts (and leave the
+        // worker's row of hist2 empty for the next step)
+        for (int b = tid; b < kBinsFirst; b += kResolveThreads) {
+            uint32_t *at = hist2 + (int64_t)i * kBinsFirst + b;
+            L.lh[b] = *at;
+            *at = 0u;
+        }
         const int pieces = ge.slices * ge.parts * 4;
         const uint64_t *wdense = dense + region_base(ge, i, 0);
         // exclusive prefix sum of the piece counts, two pieces per thread
@@ -1393,7 +1442,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             // (non-zero) elements: among the zeros
             tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank - cnt, L);
         else
-            tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L);
+            tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L, true);   // barriers since L.lh was filled
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted)                                            // tk_relist was its last reader
