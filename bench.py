@@ -31,12 +31,28 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 PROFILES = os.path.join(ROOT, "profiles")
 CSRC = os.path.join(ROOT, "paper_2111_00705_amd", "csrc")
 
-# The templated kernel behind each timing slot, by method: which row of a rocprofv3 summary a slot reads.
+# rocprofv3 summaries under profiles/ exist per workload and variant of the run; a variant's file name suffix:
+PROFILE_SUFFIX = {"ef": "", "cd": "_cd_adam", "naive": "_naive", "none": "_uncompressed", "bf16": "_bf16",
+                  "randk": "_randk"}
+
+# The templated kernel behind each timing slot, by variant: which row of a rocprofv3 summary a slot reads.
 KERNEL_VARIANT = {
     ("tk_pass1", "ef"): "cams::tk_pass1<0, float>", ("tk_pass1", "cd"): "cams::tk_pass1<1, float>",
-    ("tk_pass1", "naive"): "cams::tk_pass1<3, float>",
+    ("tk_pass1", "naive"): "cams::tk_pass1<3, float>", ("tk_pass1", "randk"): "cams::tk_pass1<0, float>",
+    ("tk_pass1", "bf16"): "cams::tk_pass1<0, unsigned short>",
     ("bs_pass_update", "ef"): "cams::bs_pass_update<true, float",      # the steady-state variant (stored rows pending)
 }
+
+
+def run_variant(method: str, grad_dtype: str, randk: bool):
+    """Which profiles/ summary a run corresponds to (None: there is none for this combination)."""
+    if grad_dtype == "bf16" and method == "ef" and not randk:
+        return "bf16"
+    if grad_dtype != "f32":
+        return None
+    if randk:
+        return "randk" if method == "ef" else None
+    return method
 
 
 def library_fingerprint() -> str:
@@ -57,15 +73,16 @@ def library_fingerprint() -> str:
     return h.hexdigest()[:12]
 
 
-def measured_traffic(workload: str, method: str, grad_dtype: str, slot: str):
+def measured_traffic(workload: str, variant, slot: str):
     """HBM-side bytes per launch (fetched + written) of one kernel from the rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE summary of this workload under profiles/ (a separate run, calibrated on probe_copy).
+    WRITE_SIZE summary of this workload and variant (see run_variant) under profiles/ (a separate run,
+    calibrated on probe_copy).
     Returns (bytes or None, source or reason).  None when there is no summary for this workload and
-    method, when it was taken with other sources than the tree holds, or when it has no row for the
+    variant, when it was taken with other sources than the tree holds, or when it has no row for the
     kernel variant that ran."""
-    if grad_dtype != "f32" or method not in ("ef", "cd"):
+    if variant is None:
         return None, "no counter summary for this method / gradient type"
-    rel = os.path.join("profiles", workload + ("_cd_adam" if method == "cd" else "") + ".md")
+    rel = os.path.join("profiles", workload + PROFILE_SUFFIX[variant] + ".md")
     path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
         return None, f"{rel} does not exist"
@@ -75,7 +92,7 @@ def measured_traffic(workload: str, method: str, grad_dtype: str, slot: str):
     have = library_fingerprint()
     if not fp or fp.group(1) != have:
         return None, f"{rel} was taken with sources {fp.group(1) if fp else 'unrecorded'}, the tree holds {have}"
-    want = KERNEL_VARIANT.get((slot, method), "cams::" + slot)
+    want = KERNEL_VARIANT.get((slot, variant), "cams::" + slot)
     section = text.split("## HBM-side traffic", 1)[-1]
     for line in section.splitlines():
         cells = [c.strip() for c in line.strip().strip("|").split("|")]
@@ -225,7 +242,7 @@ def main() -> int:
         dom_bytes -= 2 * w.n * w.d
     dom_us = kernels[dom]["avg_us"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    traffic, traffic_source = measured_traffic(w.name, args.method, args.grad_dtype, dom)
+    traffic, traffic_source = measured_traffic(w.name, run_variant(args.method, args.grad_dtype, args.randk), dom)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "traffic_source": traffic_source,

@@ -192,13 +192,14 @@ inline void apply_streaming(comp_ams *h)
     h->params.stream_state = h->state_choice < 0 ? ((state_exceeds_caches(h) || rows_cached) ? 1 : 0) : h->state_choice;
 }
 
-// Geometry handed to tk_pass1 for gradients of type G: the automatic tile order is the plain one for 16-bit
-// gradients (see xcd_chunk_for); a caller's choice holds for every type.
+// Geometry handed to tk_pass1 for gradients of type G: with 16-bit gradients the automatic tile order is the
+// plain one unless the method is error feedback (n = 8, d = 110 M, bfloat16: error feedback 1.44 -> 1.38 ms with
+// chunks of 16, CD-Adam 1.09 -> 1.10 ms); a caller's choice holds for every type.
 template <typename G>
 inline TkGeom pass_geometry(const comp_ams *h)
 {
     TkGeom ge = h->ge;
-    if (sizeof(G) == 2 && h->chunk_choice < 0) ge.xcd_chunk = 0;
+    if (sizeof(G) == 2 && h->chunk_choice < 0 && h->method != COMP_AMS_METHOD_EF) ge.xcd_chunk = 0;
     return ge;
 }
 
@@ -683,12 +684,13 @@ void launch_final(comp_ams *h, hipStream_t st)
 // Dynamic LDS handed to tk_pass1 beyond its own 24 KB of staging lists: unused by the kernel, it only sets how many
 // workgroups share a compute unit (six without it).  The passes that only read want all six (n = 16, d = 11.2 M,
 // CD-Adam: 245 against 257 us with four; n = 8, d = 110 M: 1.134 against 1.173 ms).  The error-feedback pass, which
-// also writes the row back, is best with four or five (n = 8, d = 110 M: 1.67-1.68 ms, 1.70 with six, 1.74 with
-// eight) and gets 9 KB, which leaves four.  comp_ams_set_pass_lds overrides.
-inline unsigned tk_pass_lds(const comp_ams *h)
+// also writes the row back, is best with four or five on 32-bit gradients (n = 8, d = 110 M: 1.67-1.68 ms, 1.70 with
+// six, 1.74 with eight) and gets 9 KB, which leaves four; on 16-bit gradients it issues more instructions per byte
+// and wants the six as well (same shape, bfloat16: 1.44 against 1.76 ms).  comp_ams_set_pass_lds overrides.
+inline unsigned tk_pass_lds(const comp_ams *h, size_t grad_bytes)
 {
     if (h->lds_choice >= 0) return (unsigned)h->lds_choice;
-    return h->method == COMP_AMS_METHOD_EF ? 9u * 1024u : 0u;
+    return h->method == COMP_AMS_METHOD_EF && grad_bytes == 4 ? 9u * 1024u : 0u;
 }
 
 // Error feedback on a short vector: listing pass, one selection kernel (tk_small_select), update - three launches.
@@ -718,7 +720,7 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH_LDS((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
@@ -734,7 +736,7 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom &ge = h->ge;
     const TkGeom pge = pass_geometry<G>(h);
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH_LDS((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
@@ -747,10 +749,17 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
 template <typename G>
 int step_plain(comp_ams *h, const G *g, hipStream_t st)
 {
+    // Tile order: with many gradient rows far beyond the caches each XCD working through 16 consecutive tiles of
+    // every row measured 9 % faster (n = 32, d = 25.6 M: 797 -> 726 us); n = 16, d = 11.2 M does not respond, and
+    // with n = 8, d = 110 M chunks of 16 to 256 tiles gave -3 to +5 % without a pattern, so few rows keep the plain
+    // order.
+    const int n_tiles = (int)(h->ld / kTile);
+    const bool many_long_rows = h->n >= 16 && (size_t)h->n * (size_t)h->d * sizeof(G) > ((size_t)1 << 30);
+    const int chunk = h->chunk_choice >= 0 ? h->chunk_choice : many_long_rows ? 16 : 0;
     launch_timed(h, P_PLAIN_UPDATE, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
-            KLAUNCH((plain_update<G, decltype(ss)::value>), (unsigned)(h->ld / kTile), kThreads, st, g, h->d, h->n,
-                    h->theta, h->m, h->v, h->vhat, h->params);
+            KLAUNCH((plain_update<G, decltype(ss)::value>), grid_blocks(n_tiles, chunk), kThreads, st, g, h->d, h->n,
+                    h->theta, h->m, h->v, h->vhat, h->params, chunk, n_tiles);
         });
     });
     return COMP_AMS_OK;
@@ -764,7 +773,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
     const TkGeom pge = pass_geometry<G>(h);
     const TkSide &sv = h->srv;
     launch_timed(h, P_TK_PASS1, st, [&] {
-        KLAUNCH_LDS((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h), st, g, h->e, pge, h->ws,
+        KLAUNCH_LDS((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,

@@ -1,5 +1,6 @@
 // Vanilla distributed AMSGrad without compression (Section 3): gbar = (1/n) sum_i g_i in ascending
-// worker order, then the AMSGrad update.  One workgroup per tile of 4096 coordinates.
+// worker order, then the AMSGrad update.  One workgroup per tile of 4096 coordinates (chunk: tile_of_block's;
+// workgroups past the last tile leave at once).
 // Traffic: 4 B per (worker, coordinate) + 32 B per coordinate.
 #pragma once
 #include "device_utils.h"
@@ -11,10 +12,13 @@ constexpr int kPlainBatch = 4;   // workers whose gradients are in flight togeth
 template <typename G, bool kStreamState>   // G: float, uint16_t (bfloat16 bits) or f16bits
 __global__ __launch_bounds__(kThreads) void plain_update(const G *__restrict__ g, int64_t d, int n,
                                                          float *__restrict__ theta, float *__restrict__ m,
-                                                         float *__restrict__ v, float *__restrict__ vhat, AmsParams p)
+                                                         float *__restrict__ v, float *__restrict__ vhat, AmsParams p, int chunk,
+                                                         int n_tiles)
 {
     const int tid = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * kTile;
+    const int t = tile_of_block(blockIdx.x, chunk);
+    if (t >= n_tiles) return;
+    const int64_t base = (int64_t)t * kTile;
     float acc[4][4];
 #pragma unroll
     for (int r = 0; r < 4; ++r)

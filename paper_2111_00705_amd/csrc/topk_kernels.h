@@ -339,6 +339,9 @@ __device__ __forceinline__ void flush_end(const uint2 *stage, uint32_t count, co
 // entry instead of the 8 of an (index, value) pair.  With room for every coordinate of the wavefront (so the list
 // cannot overflow) a workgroup's four lists take 24 KB, and six workgroups fit a compute unit where 32 KB allowed
 // four: the passes that only read (CD-Adam, naive compression) run 3-5 % faster with the additional loads in flight.
+// (Staging the places alone and reading the values again when the list is copied out - possible where the vector is
+// g itself, naive compression - was built: eight workgroups per unit, and slower, n = 16, d = 11.2 M 158 -> 202 us:
+// the scattered re-reads cost more than the workgroups bring.)
 struct Stage {
     float *val;          // [kSub]
     uint16_t *at;        // [kSub] index - first index of the tile

@@ -293,6 +293,30 @@ def test_the_cache_policy_does_not_change_results(comp, kb, method):
     h.destroy()
 
 
+def test_the_tile_order_does_not_change_the_uncompressed_update():
+    """The update without compression takes its tiles in the order comp_ams_set_tile_order names as well: any
+    chunk, and a change between steps, must leave bit-identical state (74 tiles, the last one ragged)."""
+    import torch
+    announce("tile order, no compression")
+    d, n = 300_007, 5
+    gs = [np.random.default_rng([79, t]).standard_normal((n, d)).astype(f32) for t in range(3)]
+    ref = None
+    for chunk in (0, 1, 3, 16, 37, 100, -1):
+        h = P.CompAms(d, n, P.TOPK, 10)
+        h.set_method(P.METHOD_NONE)
+        h.set_tile_order(chunk)
+        for t, g in enumerate(gs):
+            if t == 2:
+                h.set_tile_order(7 if chunk else 4)
+            h.step(torch.from_numpy(g).cuda())
+        out = [bits(h.get_theta()), bits(h.get_m()), bits(h.get_v()), bits(h.get_vhat())]
+        h.destroy()
+        if ref is None:
+            ref = out
+        else:
+            assert all(np.array_equal(a, b) for a, b in zip(ref, out)), chunk
+
+
 @pytest.mark.parametrize("comp,kb", [(P.TOPK, 3000), (P.RANDK, 3000), (P.BLOCKSIGN, 1000), (P.BLOCKSIGN, 4096)])
 @pytest.mark.parametrize("method", [P.METHOD_EF, P.METHOD_CD, P.METHOD_NAIVE])
 def test_the_tile_order_does_not_change_results(comp, kb, method):
