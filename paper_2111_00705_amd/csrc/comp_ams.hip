@@ -93,6 +93,7 @@ struct comp_ams {
     uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
     uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
+    uint32_t *cursor_b = nullptr;              // [n][slices] the cursors that lists made anew after a miss count in
     uint32_t *hist2 = nullptr;                 // [n][1024] threshold bin: counts of the first digit below the prefix
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
 
@@ -102,7 +103,7 @@ struct comp_ams {
     float *sel_out_val = nullptr;
     // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
     TkSide srv{};
-    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr, *hist2_s = nullptr;
+    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr, *hist2_s = nullptr, *cursor_b_s = nullptr;
     uint64_t *dense_s = nullptr;
     uint2 *dense_dir_s = nullptr;
 
@@ -221,11 +222,11 @@ inline uint32_t per_step_word(const comp_ams *h, uint32_t draw) { return host_mi
 
 namespace {
 
-enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT,
+enum ProfSlot { P_BS_PASS, P_BS_SCALE, P_BS_UPDATE, P_TK_PASS1, P_TK_HIST, P_TK_PICK, P_TK_COMPACT,
                 P_TK_RESOLVE, P_TK_FINAL, P_BS_SERVER, P_BS_SCALE_SERVER, P_BS_APPLY, P_TK_MERGE, P_TK_PASS1_SERVER,
                 P_TK_SELECT_SERVER, P_TK_APPLY, P_PLAIN_UPDATE, P_BS_PASS_UPDATE, P_SLOTS };
 const char *const kProfNames[P_SLOTS] = {"bs_pass", "bs_scale", "bs_update", "tk_pass1", "tk_hist", "tk_pick",
-                                         "tk_relist", "tk_compact", "tk_resolve", "tk_final", "bs_server",
+                                         "tk_compact", "tk_resolve", "tk_final", "bs_server",
                                          "bs_scale_server", "bs_apply", "tk_merge", "tk_pass1_server", "tk_select_server",
                                          "tk_apply", "plain_update", "bs_pass_update"};
 
@@ -635,41 +636,41 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
     return COMP_AMS_OK;
 }
 
-// The five selection launches between the listing pass and the kernel that uses Tc: candidate
-// histograms, leading digits, second listing (rare), compaction of the threshold bin (or, rarer still, the
-// selection without lists), last digits.  kSrc / a / b say how tk_relist forms the compressed vector again.
+// The four selection launches between the listing pass and the kernel that uses Tc: candidate histograms (after
+// a miss: the whole vector's), leading digits (after a miss: and the lists anew), compaction of the threshold bin,
+// last digits (or, rarest, the selection without lists).  kSrc / a / b say how the compressed vector is formed
+// again where that is needed.  cursor_b: the second set of region cursors, which the lists made anew count in.
 template <int kSrc, typename G>
 void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
-                   uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full, uint32_t *hist2, uint64_t *dense,
-                   uint2 *dense_dir, const void *a, const float *b, const int (&slot)[5])
+                   uint32_t *cursor_b, uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full,
+                   uint32_t *hist2, uint64_t *dense, uint2 *dense_dir, const void *a, const float *b,
+                   const int (&slot)[4])
 {
-    const dim3 shared(ge.slices * ge.parts, ge.n), sweep(ge.relist_wgs, ge.n);
-    // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to count
-    // the whole vector after a miss) are kept to about two per compute unit in total
-    const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 512 / ge.n)), ge.n);
-    launch_timed(h, slot[0], st, [&] { KLAUNCH((tk_hist), shared, kThreads, st, ge, ws, cand, cursor, hist1,
-            histf); });
+    const dim3 shared(ge.slices * ge.parts, ge.n);
+    // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to list the
+    // vector again after a miss) are kept to about four per compute unit in total
+    const dim3 pick((unsigned)std::min<int>(ge.relist_wgs, std::max(1, 1024 / ge.n)), ge.n);
+    launch_timed(h, slot[0], st, [&] {
+        KLAUNCH((tk_hist<kSrc, G>), shared, kThreads, st, ge, ws, cand, cursor, hist1, histf, hist_full, a, b);
+    });
     launch_timed(h, slot[1], st, [&] {
-        KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, hist_full, a, b);
+        KLAUNCH((tk_pick<kSrc, G>), pick, kThreads, st, ge, ws, hist1, histf, cursor, cursor_b, hist_full, a, b, cand,
+                tile_dir);
     });
     launch_timed(h, slot[2], st, [&] {
-        KLAUNCH((tk_relist<kSrc, G>), sweep, kThreads, st, a, b, ge, ws, hist_full, cand, cursor, tile_dir);
+        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, cursor_b, dense, dense_dir, hist2);
     });
     launch_timed(h, slot[3], st, [&] {
-        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, dense, dense_dir, hist2);
-    });
-    launch_timed(h, slot[4], st, [&] {
         // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
         const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
         const ExactSource es{kSrc, std::is_same<G, float>::value ? 0 : std::is_same<G, uint16_t>::value ? 1 : 2, a, b};
-        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, hist_full, hist2, cand, tile_dir, rows,
-                es);
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, cursor_b, hist_full, hist2, cand,
+                tile_dir, rows, es);
     });
 }
 
-constexpr int kWorkerSelectSlots[5] = {P_TK_HIST, P_TK_PICK, P_TK_RELIST, P_TK_COMPACT, P_TK_RESOLVE};
-constexpr int kServerSelectSlots[5] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER,
-                                       P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
+constexpr int kWorkerSelectSlots[4] = {P_TK_HIST, P_TK_PICK, P_TK_COMPACT, P_TK_RESOLVE};
+constexpr int kServerSelectSlots[4] = {P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER, P_TK_SELECT_SERVER};
 
 void launch_final(comp_ams *h, hipStream_t st)
 {
@@ -723,8 +724,8 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
         KLAUNCH_LDS((tk_pass1<kPassEf, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
-                                     h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
+    launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
+                                     h->hist_full, h->hist2, h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
 }
@@ -739,8 +740,8 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
         KLAUNCH_LDS((tk_pass1<kPassNaive, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
-                                   h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
+    launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
+                                   h->hist_full, h->hist2, h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
 }
@@ -765,7 +766,7 @@ int step_plain(comp_ams *h, const G *g, hipStream_t st)
     return COMP_AMS_OK;
 }
 
-// One iteration of Algorithm 1 (CD-Adam) with Top-k in both directions, fourteen launches.
+// One iteration of Algorithm 1 (CD-Adam) with Top-k in both directions, twelve launches.
 template <typename G>
 int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
 {
@@ -776,8 +777,8 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
         KLAUNCH_LDS((tk_pass1<kPassCd, G>), dim3(grid_blocks(ge.n_tiles, pge.xcd_chunk), h->n), kThreads, tk_pass_lds(h, sizeof(G)), st, g, h->e, pge, h->ws,
                 h->cand, h->cursor, h->tile_dir);
     });
-    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->tile_dir, h->hist1, h->histf, h->hist_full, h->hist2,
-                               h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
+    launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
+                               h->hist_full, h->hist2, h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
@@ -786,8 +787,9 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
         KLAUNCH((tk_pass1<kPassDiff, float>), dim3(grid_blocks(ge.n_tiles, sv.ge.xcd_chunk), 1), kThreads, st, h->ghat_srv,
                 h->gtil, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
     });
-    launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir, h->hist1_s, h->histf_s,
-                                   h->hist_full_s, h->hist2_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil, kServerSelectSlots);
+    launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, h->cursor_b_s, sv.tile_dir, h->hist1_s, h->histf_s,
+                                   h->hist_full_s, h->hist2_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil,
+                                   kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
             KLAUNCH((tk_apply<decltype(ss)::value>), ge.n_tiles, kThreads, st, sv, h->gtil, h->theta, h->m, h->v,
@@ -837,10 +839,12 @@ int reset_topk_workers(comp_ams *h)
     fresh_tk_workers(init);
     HIP_TRY(h, hipMemcpy(h->ws, init.data(), init.size() * sizeof(TkWorker), hipMemcpyHostToDevice));
     HIP_TRY(h, hipMemset(h->cursor, 0, (size_t)h->n * h->ge.slices * sizeof(uint32_t)));
+    HIP_TRY(h, hipMemset(h->cursor_b, 0, (size_t)h->n * h->ge.slices * sizeof(uint32_t)));
     HIP_TRY(h, hipMemset(h->small_ctr, 0, (size_t)h->n * sizeof(uint32_t)));
     if (h->srv.ws) {
         HIP_TRY(h, hipMemcpy(h->srv.ws, init.data(), sizeof(TkWorker), hipMemcpyHostToDevice));
         HIP_TRY(h, hipMemset(h->srv.cursor, 0, (size_t)h->srv.ge.slices * sizeof(uint32_t)));
+        HIP_TRY(h, hipMemset(h->cursor_b_s, 0, (size_t)h->srv.ge.slices * sizeof(uint32_t)));
     }
     return COMP_AMS_OK;
 }
@@ -1031,6 +1035,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
         if ((rc = dev_alloc_t(h, h->allocs, &h->ws, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cand, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->cursor, (size_t)n * ge.slices)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->cursor_b, (size_t)n * ge.slices)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->tile_dir, segs)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist_full, (size_t)n * kBins1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->hist1, (size_t)n * kBins1)) ||
@@ -1572,6 +1577,7 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
             if ((rc = dev_alloc_t(h, h->allocs, &sv.ws, 1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.cand, region_entries, false)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.cursor, (size_t)sv.ge.slices)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->cursor_b_s, (size_t)sv.ge.slices)) ||
                 (rc = dev_alloc_t(h, h->allocs, &sv.tile_dir, tiles)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->hist_full_s, (size_t)kBins1)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->hist1_s, (size_t)kBins1)) ||

@@ -10,7 +10,7 @@
 // The error memory is kept in deferred form: after a step the library stores x_i = g_i + e_i and
 // the worker's threshold Tc_i; e_i[j] = (comp(x_i[j], j) >= Tc_i) ? +0 : x_i[j] is formed on the fly
 // when the next step (or a getter) reads x_i, so kept coordinates are never zeroed by scattered
-// writes and one step needs a single pass over g and the stored vector.  Seven launches per step,
+// writes and one step needs a single pass over g and the stored vector.  Six launches per step,
 // ordered only by kernel boundaries (no fences, no waiting inside a kernel):
 //
 //   tk_pass1    one workgroup per (tile, worker): streams g and the stored x once and writes the new
@@ -21,12 +21,12 @@
 //               A workgroup per tile (instead of a loop over tiles) matters: on this chip a wave
 //               that loops must wait for its stores before it can use its next loads.
 //   tk_hist     histograms of the candidates: coarse bins (top 11 bits) and the fine bins of the
-//               two coarse bins around the guess
-//   tk_pick     coarse and fine bin of the k-th largest (one workgroup per worker); with fewer than
-//               k candidates (always on the first step) the guess was too high: then many workgroups
-//               count the whole vector into a full coarse histogram instead
-//   tk_relist   only for such workers: the coarse bin from that histogram, and the candidates are
-//               listed again from the stored x
+//               two coarse bins around the guess; with fewer than k candidates (always on the first
+//               step) the guess was too high: then the workgroups count the whole vector into a
+//               full coarse histogram instead
+//   tk_pick     coarse and fine bin of the k-th largest (one workgroup per worker); after such a
+//               miss: the coarse bin from the full histogram, and the candidates are listed again
+//               from the stored x (many workgroups)
 //   tk_compact  candidates in the threshold bin are copied, as comp values, to dense pieces (one
 //               per wavefront)
 //   tk_resolve  one workgroup per worker: the remaining digits of Tc over those pieces, and the
@@ -39,7 +39,7 @@
 // (about 1.2 k per worker, 8 B each, written once, read three times).
 //
 // The candidate regions are bounded (see region_base): a region that fills up is detected, and the step then
-// goes the way of a guess that was too high (tk_pick, tk_relist) and, if the lists still do not fit, selects
+// goes the way of a guess that was too high (whole-vector count, lists made anew) and, if the lists still do not fit, selects
 // without lists inside tk_resolve (exact_select).  Vectors of at most 16 tiles take three launches: tk_pass1,
 // tk_small_select, tk_final.
 //
@@ -96,7 +96,7 @@ struct TkWorker {
                             // replayed from a HIP graph (which repeats its draw) still reads its predecessor's.
     uint32_t overflow;      // tk_pass1 found a candidate region full: the lists are incomplete, tk_pick counts the
                             // whole vector instead (as after a guess that was too high)
-    uint32_t overflow2;     // tk_relist found a region full as well: tk_resolve selects without lists (exact_select)
+    uint32_t overflow2;     // listing anew, tk_pick found a region full as well: tk_resolve selects without lists (exact_select)
     uint32_t pad_;
 };
 static_assert(sizeof(TkWorker) == 56, "TkWorker is copied between host and device as plain bytes");
@@ -121,7 +121,7 @@ struct TkGeom {
     int32_t slice_tiles;    // tiles that append to one candidate region = ceil(n_tiles / slices)
     uint32_t region_cap;    // entries a candidate region holds (see region_base)
     int32_t parts;          // tk_hist / tk_compact: workgroups per region
-    int32_t relist_wgs;     // workgroups per worker in tk_relist (each loops over tiles; rarely does anything)
+    int32_t relist_wgs;     // workgroups per worker in tk_pick (after a miss each loops over tiles; else all but one leave)
     int32_t stream_rows;    // the stored rows are too large to stay cached between steps: tk_pass1 loads them as a stream
     int32_t xcd_chunk;      // tk_pass1: tile_of_block's chunk
     TkRand rand;
@@ -266,7 +266,7 @@ __device__ __forceinline__ void block_prefix(uint32_t v, uint32_t *pre, uint32_t
 // A region holds a bounded number of entries (the host sizes a worker's regions for twice max(4 k, d / 64)
 // candidates in all; 1.2 k are listed in steady state), not every coordinate of its tiles.  A tile that does not
 // fit sets the worker's overflow flag and stores nothing: the worker's lists are then incomplete and the step
-// goes on as after a guess that was too high - tk_pick counts the whole vector and tk_relist lists again with
+// goes on as after a guess that was too high - tk_hist counts the whole vector and tk_pick lists again with
 // the coarse bin of the k-th largest; if that does not fit either (thousands of equal magnitudes: nothing
 // narrower than the whole composite key separates them), tk_resolve selects without lists (exact_select).
 __device__ __forceinline__ int64_t worker_base(const TkGeom &ge, int worker)
@@ -499,7 +499,7 @@ __global__ __launch_bounds__(kThreads) void tk_pass1(const G *__restrict__ g, fl
 // ---------------------------------------------------------------------------------------------
 // The kept values of a tile, summed over the workers, and the AMSGrad update of the tile (tk_final's work).
 //
-// A coordinate of a tile belongs to one wavefront - the same one in tk_pass1, tk_relist and here -
+// A coordinate of a tile belongs to one wavefront - the same one in tk_pass1, tk_pick's listing and here -
 // and a tile's candidates are stored wavefront by wavefront, so each wavefront can sum the kept values
 // of its own coordinates without looking at the others: no workgroup barrier, and the ascending worker
 // order of the sum is just the order of its own instructions (within one worker the coordinates of
@@ -661,51 +661,6 @@ __device__ __forceinline__ Piece piece_of(const TkGeom &ge, const uint32_t *__re
     return p;
 }
 
-// Histograms of the candidates of a worker: coarse bins, and the fine bins of the two coarse bins
-// that start with the guess's.  Loads are issued four at a time.  Grid (slices * parts, n).
-__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *__restrict__ ws,
-                                                    const uint2 *__restrict__ cand,
-                                                    const uint32_t *__restrict__ cursor,
-                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf)
-{
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t lf[kFineWindow];
-    const int i = blockIdx.y;
-    const int tid = threadIdx.x;
-    if (ws[i].overflow) return;                     // the lists are incomplete: tk_pick counts the vector itself
-    const Piece pc = piece_of(ge, cursor, i);
-    if (pc.q0 >= pc.q1) return;
-    const uint32_t guess = ws[i].guess;
-    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
-    for (int b = tid; b < kBins1; b += kThreads) lh[b] = 0;
-    if (tid < kFineWindow) lf[tid] = 0;
-    __syncthreads();
-    const uint2 *src = cand + region_base(ge, i, pc.slice);
-    for (uint32_t qb = pc.q0; qb < pc.q1; qb += 4 * kThreads) {
-        uint2 y[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t q = qb + u * kThreads + tid;
-            y[u] = q < pc.q1 ? src[q] : make_uint2(0u, 0u);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (qb + u * kThreads + tid < pc.q1) {
-                const uint32_t fine = sel_key(sk, __uint_as_float(y[u].y), y[u].x) >> kFineShift;
-                atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
-                if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
-            }
-        }
-    }
-    __syncthreads();
-    for (int b = tid; b < kBins1; b += kThreads) {
-        const uint32_t c = lh[b];
-        if (c) atomicAdd(hist1 + (int64_t)i * kBins1 + b, c);
-    }
-    if (tid < kFineWindow && lf[tid]) atomicAdd(histf + (int64_t)i * kFineWindow + tid, lf[tid]);
-}
-
 // ---------------------------------------------------------------------------------------------
 // How a kernel forms the vector that is compressed again from what is stored:
 //   kSrcStored  the stored x itself (error feedback)
@@ -742,50 +697,158 @@ __device__ __forceinline__ void load_source_tile(float (&x)[4][4], const void *_
     }
 }
 
-// The leading digits of Tc.  Grid (P, n).  In the usual
-// case the worker's candidates number at least k, so the k-th largest is among them: workgroup 0 finds its coarse
-// and (if the window covers it) fine bin from the candidate histograms, and the other workgroups return at once.
-// With fewer than k candidates (always on the first step, else when the threshold fell through the slack) the guess
-// was too high and nothing below it is known, and when a region was full the lists are incomplete: then all P
-// workgroups count the whole vector into the worker's full coarse histogram, and tk_relist, which runs next, takes
-// the coarse bin from it.
-// Bin 0 (zeros and the smallest denormals) is not counted but taken as the remainder: in a sparse
-// vector it would draw most LDS atomics of a tile to one word.
+// Which way a worker's selection goes in this step, from what the listing pass left (the same test in tk_hist and
+// tk_pick, which see the same cursors and flags):
+//   kCaseListed    every element at or above the guess is listed and there are at least k of them: the k-th largest
+//                  is a candidate, the candidate histograms locate it;
+//   kCaseZeroTail  error feedback with magnitude keys, a guess of 0 (every non-zero element is listed) and fewer
+//                  than k candidates: the k-th largest is a zero (see zero_tail_threshold);
+//   kCaseMiss      the guess was too high (always on the first step, else when the threshold fell through the slack),
+//                  or a candidate region was full: nothing below the guess is known, the whole vector is counted.
+enum { kCaseListed = 0, kCaseZeroTail = 1, kCaseMiss = 2 };
+template <int kSrc>
+__device__ __forceinline__ int selection_case(const TkGeom &ge, uint32_t total, uint32_t guess, bool overflow)
+{
+    if (total >= ge.k && !overflow) return kCaseListed;
+    if (kSrc == kSrcStored && !ge.rand.on && guess == 0u && !overflow) return kCaseZeroTail;
+    return kCaseMiss;
+}
+
+// Number of candidates of worker i = sum of its region cursors.  Wavefront 0 adds them up; total_sh: one LDS
+// word; ends with a barrier.  All threads of the workgroup call this.
+__device__ __forceinline__ uint32_t candidates_listed(const TkGeom &ge, const uint32_t *__restrict__ cursor, int i,
+                                                      uint32_t *total_sh)
+{
+    const int lane = threadIdx.x & 63;
+    if ((threadIdx.x >> 6) == 0) {
+        uint32_t c = 0;
+        for (int q = lane; q < ge.slices; q += kWave) c += cursor[i * ge.slices + q];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
+        if (lane == 0) *total_sh = c;
+    }
+    __syncthreads();
+    return *total_sh;
+}
+
+// First kernel of the selection.  Grid (slices * parts, n).
+// Usual case (kCaseListed): histograms of the candidates of a worker - coarse bins, and the fine bins of the two
+// coarse bins that start with the guess's.  Loads are issued four at a time.
+// After a miss (kCaseMiss) the workgroups of the worker count the whole vector, re-formed from what is stored
+// (a, b: see load_source_tile), into the worker's full coarse histogram instead; tk_pick takes the coarse bin of
+// the k-th largest from it and lists again.  Bin 0 (zeros and the smallest denormals) is not counted there but
+// taken as the remainder: in a sparse vector it would draw most LDS atomics of a tile to one word.
+template <int kSrc, typename G>
+__global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *__restrict__ ws,
+                                                    const uint2 *__restrict__ cand,
+                                                    const uint32_t *__restrict__ cursor,
+                                                    uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
+                                                    uint32_t *__restrict__ hist_full, const void *__restrict__ a,
+                                                    const float *__restrict__ b)
+{
+    __shared__ uint32_t lh[kBins1];
+    __shared__ uint32_t lf[kFineWindow];
+    __shared__ uint32_t total_sh;
+    const int i = blockIdx.y;
+    const int tid = threadIdx.x;
+    const uint32_t guess = ws[i].guess;
+    const uint32_t total = candidates_listed(ge, cursor, i, &total_sh);
+    const int which = selection_case<kSrc>(ge, total, guess, ws[i].overflow != 0u);
+    if (which == kCaseZeroTail) return;
+    const Piece pc = piece_of(ge, cursor, i);
+    if (which == kCaseListed && pc.q0 >= pc.q1) return;
+    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
+    for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
+    if (which == kCaseMiss) {
+        __syncthreads();
+        const uint32_t d = (uint32_t)ge.d;
+        const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
+        for (int t = blockIdx.x; t < ge.n_tiles; t += gridDim.x) {
+            const uint32_t base = (uint32_t)t * kTile;
+            float x[4][4];
+            load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t j = base + 4 * (tid + kThreads * r) + c;
+                    const uint32_t bin = sel_key(sk, x[r][c], j) >> kShift1;
+                    if (bin != 0 && j < d) atomicAdd(&lh[bin], 1u);
+                }
+        }
+        __syncthreads();
+        for (int q = tid; q < kBins1; q += kThreads) {
+            const uint32_t c = lh[q];
+            if (c) atomicAdd(hist_full + (int64_t)i * kBins1 + q, c);
+        }
+        return;
+    }
+    if (tid < kFineWindow) lf[tid] = 0;
+    __syncthreads();
+    const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
+    const uint2 *src = cand + region_base(ge, i, pc.slice);
+    for (uint32_t qb = pc.q0; qb < pc.q1; qb += 4 * kThreads) {
+        uint2 y[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t q = qb + u * kThreads + tid;
+            y[u] = q < pc.q1 ? src[q] : make_uint2(0u, 0u);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (qb + u * kThreads + tid < pc.q1) {
+                const uint32_t fine = sel_key(sk, __uint_as_float(y[u].y), y[u].x) >> kFineShift;
+                atomicAdd(&lh[fine >> (kShift1 - kFineShift)], 1u);
+                if (fine - wbase < (uint32_t)kFineWindow) atomicAdd(&lf[fine - wbase], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    for (int b1 = tid; b1 < kBins1; b1 += kThreads) {
+        const uint32_t c = lh[b1];
+        if (c) atomicAdd(hist1 + (int64_t)i * kBins1 + b1, c);
+    }
+    if (tid < kFineWindow && lf[tid]) atomicAdd(histf + (int64_t)i * kFineWindow + tid, lf[tid]);
+}
+
+// Second kernel of the selection: the leading digits of Tc.  Grid (ge.relist_wgs, n).
+// Usual case (kCaseListed): workgroup 0 of the worker finds the coarse and (if the window covers it) fine bin of
+// the k-th largest from the candidate histograms, and the other workgroups return at once.
+// After a miss tk_hist has counted the whole vector into the worker's full coarse histogram: every workgroup takes
+// the coarse bin of the k-th largest from it (each works it out for itself; workgroup 0 records it) and lists the
+// elements in that bin or above, tile by tile, into the worker's regions - through the second set of cursors
+// (cursor_b, all zero here), since the first still holds the counts this kernel's workgroups decide by.  The
+// worker is flagged `relisted`: tk_compact then reads cursor_b, and tk_resolve clears both.  A region that fills up
+// there as well sets overflow2: tk_resolve then selects without lists (exact_select).
 // Consumes (and clears) the candidate histograms.
 template <int kSrc, typename G>
 __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restrict__ ws,
                                                     uint32_t *__restrict__ hist1, uint32_t *__restrict__ histf,
-                                                    uint32_t *__restrict__ cursor, uint32_t *__restrict__ hist_full,
-                                                    const void *__restrict__ a, const float *__restrict__ b)
+                                                    const uint32_t *__restrict__ cursor,
+                                                    uint32_t *__restrict__ cursor_b,
+                                                    const uint32_t *__restrict__ hist_full,
+                                                    const void *__restrict__ a, const float *__restrict__ b,
+                                                    uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir)
 {
+    __shared__ uint2 stage[4][kSub];
     __shared__ uint32_t lh[kBins1];
     __shared__ uint32_t part[kThreads / kWave];
     __shared__ uint32_t res[4];
     __shared__ uint32_t fres[3];
+    __shared__ uint32_t sh[9];
     __shared__ uint32_t total_sh;
     const int i = blockIdx.y;
     const int bx = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const uint32_t guess = ws[i].guess;
-    const bool overflow = ws[i].overflow != 0u;
-    if (wave == 0) {
-        // number of candidates of this worker = sum of its region cursors
-        uint32_t c = 0;
-        for (int q = lane; q < ge.slices; q += kWave) c += cursor[i * ge.slices + q];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, kWave);
-        if (lane == 0) total_sh = c;
-    }
-    __syncthreads();
-    const uint32_t total = total_sh;
+    const uint32_t total = candidates_listed(ge, cursor, i, &total_sh);
+    const int which = selection_case<kSrc>(ge, total, guess, ws[i].overflow != 0u);
     uint32_t *row = hist1 + (int64_t)i * kBins1;
     uint32_t *frow = histf + (int64_t)i * kFineWindow;
 
-    if (total >= ge.k && !overflow) {
+    if (which == kCaseListed) {
         if (bx != 0) return;
-        // every element at or above the guess is listed and there are at least k of them: the k-th
-        // largest is a candidate and the candidate histograms locate it
         for (int q = tid; q < kBins1; q += kThreads) lh[q] = row[q];
         __syncthreads();
         find_rank_bin(lh, part, res, kBins1, ge.k);
@@ -831,10 +894,9 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         return;
     }
 
-    if (kSrc == kSrcStored && !ge.rand.on && guess == 0u && !overflow) {
-        // error feedback with magnitude keys: a guess of 0 lists every non-zero element, and there are fewer
-        // than k of them - the k-th largest is a zero.  All candidates are kept; tk_resolve places the threshold
-        // among the zeros, which are ordered by index alone, from the zero counts of the tiles.
+    if (which == kCaseZeroTail) {
+        // all candidates are kept; tk_resolve places the threshold among the zeros, which are ordered by index
+        // alone, from the zero counts of the tiles
         if (bx != 0) return;
         if (tid == 0) {
             ws[i].prefix = 0u;
@@ -843,67 +905,10 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
             ws[i].whole = kZeroTail;
             ws[i].relisted = 0u;
         }
-        for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
-        if (tid < kFineWindow) frow[tid] = 0;
         return;
     }
 
-    // the guess was too high (or the lists did not fit): count the whole vector (tk_relist continues from the
-    // full histogram)
-    for (int q = tid; q < kBins1; q += kThreads) lh[q] = 0;
-    __syncthreads();
-    const uint32_t d = (uint32_t)ge.d;
-    const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
-    for (int t = bx; t < ge.n_tiles; t += gridDim.x) {
-        const uint32_t base = (uint32_t)t * kTile;
-        float x[4][4];
-        load_source_tile<kSrc, G>(x, a, i, ge, brow, base, d);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t j = base + 4 * (tid + kThreads * r) + c;
-                const uint32_t bin = sel_key(sk, x[r][c], j) >> kShift1;
-                if (bin != 0 && j < d) atomicAdd(&lh[bin], 1u);
-            }
-    }
-    __syncthreads();
-    for (int q = tid; q < kBins1; q += kThreads) {
-        const uint32_t c = lh[q];
-        if (c) atomicAdd(hist_full + (int64_t)i * kBins1 + q, c);
-    }
-    if (bx == 0) {
-        if (tid == 0) ws[i].relisted = 1u;
-        for (int q = tid; q < ge.slices; q += kThreads) cursor[i * ge.slices + q] = 0;   // tk_relist fills the regions anew
-        for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
-        if (tid < kFineWindow) frow[tid] = 0;
-    }
-}
-
-// Only for workers whose guess was too high: takes the coarse bin of the k-th largest from the full
-// histogram tk_pick has just counted (every workgroup works it out for itself; workgroup 0 records
-// it) and lists the elements in that bin or above into the (emptied) regions of the worker.  A small
-// grid (ge.relist_wgs, n) whose workgroups loop over tiles: in the usual case every workgroup returns at once,
-// and a small grid does that fast.  A region that fills up
-// sets overflow2: tk_compact's first workgroup of the worker then selects without lists (exact_select).
-template <int kSrc, typename G>
-__global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a, const float *__restrict__ b,
-                                                      TkGeom ge, TkWorker *__restrict__ ws,
-                                                      const uint32_t *__restrict__ hist_full,
-                                                      uint2 *__restrict__ cand, uint32_t *__restrict__ cursor,
-                                                      uint4 *__restrict__ tile_dir)
-{
-    __shared__ uint2 stage[4][kSub];
-    __shared__ uint32_t lh[kBins1];
-    __shared__ uint32_t part[kThreads / kWave];
-    __shared__ uint32_t res[4];
-    __shared__ uint32_t sh[9];
-    const int i = blockIdx.y;
-    const int bx = blockIdx.x;
-    if (!ws[i].relisted) return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    // after a miss: the coarse bin of the k-th largest from the full histogram, and the lists anew
     const uint32_t d = (uint32_t)ge.d;
     {
         uint32_t counted = 0;
@@ -927,6 +932,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
         ws[i].pshift = kShift1;
         ws[i].rank = ge.k - res[1];
         ws[i].whole = (res[2] == ge.k - res[1]) ? 1u : 0u;
+        ws[i].relisted = 1u;
     }
     const float *brow = (kSrc == kSrcGrad || kSrc == kSrcDiff) ? b + (int64_t)i * ge.ld : nullptr;
     for (int t = bx; t < ge.n_tiles; t += gridDim.x) {
@@ -948,7 +954,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
                 const uint32_t slot = wave_append(hit, count);
                 if (hit) stage[wave][slot] = make_uint2(j, __float_as_uint(x[r][c]));
             }
-        flush_begin(count, zeros, sh, 0, ge, i, t, cursor, tile_dir, &ws[i].overflow2);
+        flush_begin(count, zeros, sh, 0, ge, i, t, cursor_b, tile_dir, &ws[i].overflow2);
         flush_end(stage[wave], count, sh, ge, i, cand);
         __syncthreads();   // sh and stage are reused by the next tile
     }
@@ -963,6 +969,7 @@ __global__ __launch_bounds__(kThreads) void tk_relist(const void *__restrict__ a
 __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
                                                        const uint2 *__restrict__ cand,
                                                        const uint32_t *__restrict__ cursor,
+                                                       const uint32_t *__restrict__ cursor_b,
                                                        uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir,
                                                        uint32_t *__restrict__ hist2)
 {
@@ -979,7 +986,7 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
     for (int b = tid; b < kBinsFirst; b += kThreads) lh2[b] = 0;
     __syncthreads();
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
-    const Piece pc = piece_of(ge, cursor, i);
+    const Piece pc = piece_of(ge, ws[i].relisted ? cursor_b : cursor, i);   // lists made anew count in cursor_b
     const uint32_t quarter = (pc.q1 - pc.q0 + 3) / 4;
     const uint32_t w0 = min(pc.q0 + wave * quarter, pc.q1), w1 = min(w0 + quarter, pc.q1);
     const int64_t rbase = region_base(ge, i, pc.slice);
@@ -1206,7 +1213,7 @@ __device__ __forceinline__ uint64_t zero_tail_threshold(const uint4 *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Selection without lists, for a vector whose candidates fit no region even after tk_relist (so many elements
+// Selection without lists, for a vector whose candidates fit no region even when listed anew (so many elements
 // share the leading bits of the k-th largest that only the whole composite key tells them apart - all-equal
 // input is the extreme).  The worker's workgroup of tk_resolve does it alone: the digits of Tc by counting over
 // the whole vector, re-formed element by element from what is stored (kDigitBits bits per sweep), then one more
@@ -1353,6 +1360,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
                                                               const uint64_t *__restrict__ dense,
                                                               const uint2 *__restrict__ dense_dir,
                                                               uint32_t *__restrict__ cursor,
+                                                              uint32_t *__restrict__ cursor_b,
                                                               uint32_t *__restrict__ hist_full,
                                                               uint32_t *__restrict__ hist2,
                                                               uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir,
@@ -1448,8 +1456,10 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L, true);   // barriers since L.lh was filled
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
-    if (w.relisted)                                            // tk_relist was its last reader
+    if (w.relisted) {                                          // tk_pick was the last reader of the full histogram
+        if (tid < ge.slices) cursor_b[i * ge.slices + tid] = 0;
         for (int q = tid; q < kBins1; q += kResolveThreads) hist_full[(int64_t)i * kBins1 + q] = 0;
+    }
     if (tid == 0) finish_worker(ws, i, w, tc, ge, w.relisted != 0);
 }
 
