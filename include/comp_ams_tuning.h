@@ -32,9 +32,10 @@ int comp_ams_set_streaming(comp_ams_t *h, int32_t rows, int32_t state);
  * every XCD works through `chunk` consecutive tiles of each group of 8 * chunk tiles, with chunk = 0
  * consecutive tiles go to consecutive XCDs, -1 = chosen from the sizes (the default: 16 when the
  * stored rows exceed 1 GiB in total and the method keeps them - error feedback, CD-Adam - except for
- * CD-Adam's Top-k / Rand-k steps on 16-bit gradients; else 0; the update without compression, which takes
- * its tiles the same way: 16 with at least 16 workers whose gradients exceed 1 GiB in total).  chunk <= 65536.
- * May be called between steps.
+ * CD-Adam's Top-k / Rand-k steps on 16-bit gradients; else 0; Top-k / Rand-k under error feedback: 0 while
+ * the rows stay in the caches, else 8, or 16 for rows of 64 Mi coordinates or more; the update without
+ * compression, which takes its tiles the same way: 16 with at least 16 workers whose gradients exceed 1 GiB
+ * in total).  chunk <= 65536.  May be called between steps.
  */
 int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
 
@@ -44,7 +45,8 @@ int comp_ams_set_tile_order(comp_ams_t *h, int32_t chunk);
  * few per cent.  -1 = chosen from the sizes, the method and the gradient type (the default), else
  * 0 .. 61440.  BLOCKSIGN: the pass always gets at least what its block table needs (24 KB when a tile
  * holds several blocks' pieces).  TOPK / RANDK: the amount is added to the 24 KB of candidate staging
- * lists the pass always holds (default: 9 KB under error feedback with 32-bit gradients, else none);
+ * lists the pass always holds (default under error feedback with 32-bit gradients: 9 KB, or 7000 bytes
+ * for rows under 64 Mi coordinates that do not stay in the caches; else none);
  * no effect on vectors of at most 16 tiles.  May be called between steps.
  */
 int comp_ams_set_pass_lds(comp_ams_t *h, int32_t bytes);

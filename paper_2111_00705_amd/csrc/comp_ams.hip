@@ -146,7 +146,9 @@ inline unsigned pass_lds_bytes(const comp_ams *h, bool grads16)
     if (h->lds_choice >= 0) return std::max(need, (unsigned)h->lds_choice);
     if (h->mostly_split_tiles) return need;
     if (grads16) return std::max(need, 16u * 1024u);
-    const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30);
+    // (with the tile order of xcd_chunk_for the larger amount pays from about half a GiB of rows: n = 16, d = 11.2 M
+    // 354 against 358-360 us, n = 8, d = 25.6 M 393-395 against 410 us)
+    const bool far_beyond_caches = (size_t)h->n * h->ld * sizeof(float) > ((size_t)512 << 20);
     // naive compression reads g only and wants the workgroups as well (n = 32, d = 25.6 M: 0.55 ms up to 24 KB,
     // 0.66 ms at 32 KB, 0.78 ms at 40 KB)
     const unsigned large = h->method == COMP_AMS_METHOD_EF ? 40u * 1024u
@@ -162,10 +164,27 @@ inline unsigned pass_lds_bytes(const comp_ams *h, bool grads16)
 // row then also fall on few XCDs), and the kernels with one workgroup per tile (the updates) do not respond.
 // CD-Adam's passes gain 0.5-2 %; naive compression (g only) gains nothing or loses 0.5-3 %, and so does the
 // Top-k pass with 16-bit gradients (block sign with 16-bit gradients gains 2 %): those keep the plain order.
+// Rows of 11 M coordinates, half a GiB to 1.5 GiB in all, do gain 1-3 % with chunks of 8 tiles once the pass runs
+// three workgroups per unit (block sign, n = 16: 354 against 358 us; n = 32: 697 against 709 us with chunks of 16;
+// Top-k under CD-Adam, n = 16: 254 against 257 us), so shorter rows get 8 from half a GiB on.
 inline int xcd_chunk_for(const comp_ams *h)
 {
     if (h->method != COMP_AMS_METHOD_EF && h->method != COMP_AMS_METHOD_CD) return 0;
-    return (size_t)h->n * h->ld * sizeof(float) > ((size_t)1 << 30) ? 16 : 0;
+    if ((size_t)h->n * h->ld * sizeof(float) <= ((size_t)512 << 20)) return 0;
+    return h->d < ((int64_t)16 << 20) ? 8 : 16;
+}
+
+// The error-feedback listing pass of Top-k / Rand-k on 32-bit gradients has its own optimum, which goes with the
+// length of a row rather than with the total (one session; pass times with four workgroups per unit and no chunks /
+// the choice below): rows of 11 M coordinates, n = 8, 12, 16, 24, 32: 179 / 173, 266 / 259, 353 / 341, 527 / 513,
+// 700 / 688 us with five workgroups per unit and chunks of 8 tiles (chunks of 4, 12 or 32 lose, 16 gains half as
+// much); 25 M coordinates, n = 16: 783 / 763 us; rows of 110 M coordinates want four workgroups and chunks of 16
+// or 8 (n = 8: 1.68 ms against 1.69-1.71 ms with five; n = 4: 846-850 against 860 us).
+inline bool tk_long_rows(const comp_ams *h) { return h->d >= ((int64_t)64 << 20); }
+inline int tk_ef_chunk_for(const comp_ams *h)
+{
+    if (!rows_exceed_caches(h)) return 0;
+    return tk_long_rows(h) ? 16 : 8;
 }
 
 // Grid of a kernel with one workgroup per tile (in x) under tile_of_block's mapping.
@@ -185,6 +204,7 @@ inline void apply_streaming(comp_ams *h)
     h->pass_lds = pass_lds_bytes(h, false);
     h->pass_lds16 = pass_lds_bytes(h, true);
     h->tb.xcd_chunk = h->ge.xcd_chunk = h->chunk_choice < 0 ? xcd_chunk_for(h) : h->chunk_choice;
+    if (h->chunk_choice < 0 && h->method == COMP_AMS_METHOD_EF) h->ge.xcd_chunk = tk_ef_chunk_for(h);
     h->srv.ge.xcd_chunk = 0;   // the server's single vector: not measured, left alone
     // the state stays cached if it fits - except under error feedback with cached rows, where it would
     // compete with them (CD-Adam with cached rows measured the other way: 55.9 against 58.0 us per step with
@@ -686,12 +706,15 @@ void launch_final(comp_ams *h, hipStream_t st)
 // workgroups share a compute unit (six without it).  The passes that only read want all six (n = 16, d = 11.2 M,
 // CD-Adam: 245 against 257 us with four; n = 8, d = 110 M: 1.134 against 1.173 ms).  The error-feedback pass, which
 // also writes the row back, is best with four or five on 32-bit gradients (n = 8, d = 110 M: 1.67-1.68 ms, 1.70 with
-// six, 1.74 with eight) and gets 9 KB, which leaves four; on 16-bit gradients it issues more instructions per byte
-// and wants the six as well (same shape, bfloat16: 1.44 against 1.76 ms).  comp_ams_set_pass_lds overrides.
+// six, 1.74 with eight) and gets 9 KB, which leaves four (five for shorter rows, see tk_ef_chunk_for); on 16-bit
+// gradients it issues more instructions per byte and wants the six as well (same shape, bfloat16: 1.44 against
+// 1.76 ms).  comp_ams_set_pass_lds overrides.
 inline unsigned tk_pass_lds(const comp_ams *h, size_t grad_bytes)
 {
     if (h->lds_choice >= 0) return (unsigned)h->lds_choice;
-    return h->method == COMP_AMS_METHOD_EF && grad_bytes == 4 ? 9u * 1024u : 0u;
+    if (h->method != COMP_AMS_METHOD_EF || grad_bytes != 4) return 0u;
+    // five workgroups per unit for rows that stream and are not long (see tk_ef_chunk_for), else four
+    return rows_exceed_caches(h) && !tk_long_rows(h) ? 7000u : 9u * 1024u;
 }
 
 // Error feedback on a short vector: listing pass, one selection kernel (tk_small_select), update - three launches.
