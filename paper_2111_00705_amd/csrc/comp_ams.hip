@@ -92,8 +92,9 @@ struct comp_ams {
     uint4 *tile_dir = nullptr;                 // [n][n_tiles] {offset in the worker's space, counts per wavefront, zeros}
     uint32_t *hist_full = nullptr;             // [n][2048] coarse-bin counts of the whole vector (only after a miss)
     uint32_t *hist1 = nullptr;                 // [n][2048] coarse-bin counts of the candidates
-    uint32_t *histf = nullptr;                 // [n][128] fine-bin counts around the guess
+    uint32_t *histf = nullptr;                 // [n][512] fine-bin counts from the guess's coarse bin on
     uint32_t *cursor_b = nullptr;              // [n][slices] the cursors that lists made anew after a miss count in
+    uint32_t *piece_bits = nullptr;            // [n][64 * parts * 4][32] which first digits occur in each dense piece
     uint32_t *hist2 = nullptr;                 // [n][1024] threshold bin: counts of the first digit below the prefix
     uint64_t *dense = nullptr;                 // laid out like cand: comp of the candidates in the threshold bin
 
@@ -103,7 +104,8 @@ struct comp_ams {
     float *sel_out_val = nullptr;
     // CD-Adam with Top-k: the same selection structures once more, for the server's single vector
     TkSide srv{};
-    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr, *hist2_s = nullptr, *cursor_b_s = nullptr;
+    uint32_t *hist1_s = nullptr, *histf_s = nullptr, *hist_full_s = nullptr, *hist2_s = nullptr, *cursor_b_s = nullptr,
+             *piece_bits_s = nullptr;
     uint64_t *dense_s = nullptr;
     uint2 *dense_dir_s = nullptr;
 
@@ -663,8 +665,8 @@ int step_blocksign_cd(comp_ams *h, const G *g, hipStream_t st)
 template <int kSrc, typename G>
 void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, uint2 *cand, uint32_t *cursor,
                    uint32_t *cursor_b, uint4 *tile_dir, uint32_t *hist1, uint32_t *histf, uint32_t *hist_full,
-                   uint32_t *hist2, uint64_t *dense, uint2 *dense_dir, const void *a, const float *b,
-                   const int (&slot)[4])
+                   uint32_t *hist2, uint32_t *piece_bits, uint64_t *dense, uint2 *dense_dir, const void *a,
+                   const float *b, const int (&slot)[4])
 {
     const dim3 shared(ge.slices * ge.parts, ge.n);
     // tk_pick: one workgroup per vector does the work in the usual case; the others (needed only to list the
@@ -678,14 +680,14 @@ void launch_select(comp_ams *h, hipStream_t st, const TkGeom &ge, TkWorker *ws, 
                 tile_dir);
     });
     launch_timed(h, slot[2], st, [&] {
-        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, cursor_b, dense, dense_dir, hist2);
+        KLAUNCH((tk_compact), shared, kThreads, st, ge, ws, cand, cursor, cursor_b, dense, dense_dir, hist2, piece_bits);
     });
     launch_timed(h, slot[3], st, [&] {
         // error feedback with magnitude keys counts zeros instead of listing them: tk_resolve may need the rows
         const float *rows = (kSrc == kSrcStored && !ge.rand.on) ? static_cast<const float *>(a) : nullptr;
         const ExactSource es{kSrc, std::is_same<G, float>::value ? 0 : std::is_same<G, uint16_t>::value ? 1 : 2, a, b};
-        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, cursor_b, hist_full, hist2, cand,
-                tile_dir, rows, es);
+        KLAUNCH((tk_resolve), ge.n, kResolveThreads, st, ge, ws, dense, dense_dir, cursor, cursor_b, hist_full, hist2,
+                piece_bits, cand, tile_dir, rows, es);
     });
 }
 
@@ -748,7 +750,7 @@ int step_topk(comp_ams *h, const G *g, hipStream_t st)
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcStored, float>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
-                                     h->hist_full, h->hist2, h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
+                                     h->hist_full, h->hist2, h->piece_bits, h->dense, h->dense_dir, h->e, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
 }
@@ -764,7 +766,7 @@ int step_topk_naive(comp_ams *h, const G *g, hipStream_t st)
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcGradOnly, G>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
-                                   h->hist_full, h->hist2, h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
+                                   h->hist_full, h->hist2, h->piece_bits, h->dense, h->dense_dir, g, nullptr, kWorkerSelectSlots);
     launch_final(h, st);
     return COMP_AMS_OK;
 }
@@ -801,7 +803,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
                 h->cand, h->cursor, h->tile_dir);
     });
     launch_select<kSrcGrad, G>(h, st, ge, h->ws, h->cand, h->cursor, h->cursor_b, h->tile_dir, h->hist1, h->histf,
-                               h->hist_full, h->hist2, h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
+                               h->hist_full, h->hist2, h->piece_bits, h->dense, h->dense_dir, g, h->e, kWorkerSelectSlots);
     launch_timed(h, P_TK_MERGE, st, [&] {
         KLAUNCH((tk_merge), ge.n_tiles, kThreads, st, ge, h->ws, h->cand, h->tile_dir, h->e, h->ghat_srv,
                                                   h->params.n_workers);
@@ -811,7 +813,7 @@ int step_topk_cd(comp_ams *h, const G *g, hipStream_t st)
                 h->gtil, sv.ge, sv.ws, sv.cand, sv.cursor, sv.tile_dir);
     });
     launch_select<kSrcDiff, float>(h, st, sv.ge, sv.ws, sv.cand, sv.cursor, h->cursor_b_s, sv.tile_dir, h->hist1_s, h->histf_s,
-                                   h->hist_full_s, h->hist2_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil,
+                                   h->hist_full_s, h->hist2_s, h->piece_bits_s, h->dense_s, h->dense_dir_s, h->ghat_srv, h->gtil,
                                    kServerSelectSlots);
     launch_timed(h, P_TK_APPLY, st, [&] {
         by_flag(h->params.stream_state, [&](auto ss) {
@@ -1066,6 +1068,7 @@ int comp_ams_create(comp_ams_t **out, int64_t d, int32_t n, int32_t compressor, 
             (rc = dev_alloc_t(h, h->allocs, &h->hist2, (size_t)n * kBinsFirst)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense, region_entries, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->dense_dir, (size_t)n * ge.slices * ge.parts * 4)) ||
+            (rc = dev_alloc_t(h, h->allocs, &h->piece_bits, (size_t)n * ge.slices * ge.parts * 4 * kPieceWords, false)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->small_ctr, (size_t)n)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_count, 1)) ||
             (rc = dev_alloc_t(h, h->allocs, &h->sel_out_idx, (size_t)ge.k)) ||
@@ -1607,7 +1610,9 @@ int comp_ams_set_method(comp_ams_t *h, int32_t method)
                 (rc = dev_alloc_t(h, h->allocs, &h->histf_s, (size_t)kFineWindow)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->hist2_s, (size_t)kBinsFirst)) ||
                 (rc = dev_alloc_t(h, h->allocs, &h->dense_s, region_entries, false)) ||
-                (rc = dev_alloc_t(h, h->allocs, &h->dense_dir_s, (size_t)sv.ge.slices * sv.ge.parts * 4)))
+                (rc = dev_alloc_t(h, h->allocs, &h->dense_dir_s, (size_t)sv.ge.slices * sv.ge.parts * 4)) ||
+                (rc = dev_alloc_t(h, h->allocs, &h->piece_bits_s, (size_t)sv.ge.slices * sv.ge.parts * 4 * kPieceWords,
+                                  false)))
                 return rc;
         }
     }

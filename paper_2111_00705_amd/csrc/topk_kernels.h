@@ -21,7 +21,7 @@
 //               A workgroup per tile (instead of a loop over tiles) matters: on this chip a wave
 //               that loops must wait for its stores before it can use its next loads.
 //   tk_hist     histograms of the candidates: coarse bins (top 11 bits) and the fine bins of the
-//               two coarse bins around the guess; with fewer than k candidates (always on the first
+//               eight coarse bins from the guess's on; with fewer than k candidates (always on the first
 //               step) the guess was too high: then the workgroups count the whole vector into a
 //               full coarse histogram instead
 //   tk_pick     coarse and fine bin of the k-th largest (one workgroup per worker); after such a
@@ -39,8 +39,8 @@
 // (about 1.2 k per worker, 8 B each, written once, read three times).
 //
 // The candidate regions are bounded (see region_base): a region that fills up is detected, and the step then
-// goes the way of a guess that was too high (whole-vector count, lists made anew) and, if the lists still do not fit, selects
-// without lists inside tk_resolve (exact_select).  Vectors of at most 16 tiles take three launches: tk_pass1,
+// goes the way of a guess that was too high (whole-vector count, lists made anew) and, if the lists still do not
+// fit, selects without lists inside tk_resolve (exact_select).  Vectors of at most 16 tiles take three launches: tk_pass1,
 // tk_small_select, tk_final.
 //
 // Exact zeros under error feedback: when fewer than k coordinates are non-zero the k-th largest is a zero and
@@ -60,12 +60,18 @@ constexpr int kBins1 = 2048;      // coarse bin: top 11 of the 31 magnitude bits
 constexpr int kShift1 = 20;
 constexpr int kFineShift = 14;    // fine bin: top 17 bits; 64 fine bins per coarse bin
 constexpr int kFinePerCoarse = 1 << (kShift1 - kFineShift);
-constexpr int kFineWindow = 2 * kFinePerCoarse;   // fine bins counted: the guess's coarse bin and the next
+constexpr int kWindowCoarse = 8;  // coarse bins whose fine bins are counted, from the guess's on: one octave of
+                                  // magnitudes.  In the first steps of a run the threshold climbs by tens of fine
+                                  // bins per step; beyond the window only the coarse bin is known and the threshold
+                                  // bin holds 64 times the elements (with two coarse bins, n = 8, d = 110 M: steps
+                                  // 1 to 6 spent 65-200 us in tk_resolve instead of 15)
+constexpr int kFineWindow = kWindowCoarse * kFinePerCoarse;
 constexpr int kDigitBits = 12;    // digits of the dense-array search
 constexpr int kBins2 = 1 << kDigitBits;
 constexpr int kFirstBits = 10;    // first digit below the prefix, counted by tk_compact while it copies: narrower,
                                   // since every one of its workgroups clears and flushes the bins
 constexpr int kBinsFirst = 1 << kFirstBits;
+constexpr int kPieceWords = kBinsFirst / 32;   // words of a dense piece's bitmap: which first digits occur in it
 constexpr int kSub = kTile / 4;   // coordinates of a tile that one wavefront handles = capacity of its staged list
 constexpr int kMinSlices = 64;    // candidate regions per vector: a power of two in [kMinSlices, kMaxSlices]
                                   // (fewer for a vector of fewer tiles than that)
@@ -94,9 +100,10 @@ struct TkWorker {
     uint32_t step_word;     // Rand-k: TkRand::step_now of the step that left tc - the draw the deferred error memory
                             // must be read with.  Kept in device memory, not in a kernel argument, so that a step
                             // replayed from a HIP graph (which repeats its draw) still reads its predecessor's.
-    uint32_t overflow;      // tk_pass1 found a candidate region full: the lists are incomplete, tk_pick counts the
+    uint32_t overflow;      // tk_pass1 found a candidate region full: the lists are incomplete, tk_hist counts the
                             // whole vector instead (as after a guess that was too high)
-    uint32_t overflow2;     // listing anew, tk_pick found a region full as well: tk_resolve selects without lists (exact_select)
+    uint32_t overflow2;     // listing anew, tk_pick found a region full as well: tk_resolve selects without lists
+                            // (exact_select)
     uint32_t pad_;
 };
 static_assert(sizeof(TkWorker) == 56, "TkWorker is copied between host and device as plain bytes");
@@ -732,8 +739,8 @@ __device__ __forceinline__ uint32_t candidates_listed(const TkGeom &ge, const ui
 }
 
 // First kernel of the selection.  Grid (slices * parts, n).
-// Usual case (kCaseListed): histograms of the candidates of a worker - coarse bins, and the fine bins of the two
-// coarse bins that start with the guess's.  Loads are issued four at a time.
+// Usual case (kCaseListed): histograms of the candidates of a worker - coarse bins, and the fine bins of the
+// kWindowCoarse coarse bins that start with the guess's.  Loads are issued four at a time.
 // After a miss (kCaseMiss) the workgroups of the worker count the whole vector, re-formed from what is stored
 // (a, b: see load_source_tile), into the worker's full coarse histogram instead; tk_pick takes the coarse bin of
 // the k-th largest from it and lists again.  Bin 0 (zeros and the smallest denormals) is not counted there but
@@ -783,7 +790,7 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
         }
         return;
     }
-    if (tid < kFineWindow) lf[tid] = 0;
+    for (int q = tid; q < kFineWindow; q += kThreads) lf[q] = 0;
     __syncthreads();
     const uint32_t wbase = guess & ~(uint32_t)(kFinePerCoarse - 1);   // first fine bin of the guess's coarse bin
     const uint2 *src = cand + region_base(ge, i, pc.slice);
@@ -808,7 +815,8 @@ __global__ __launch_bounds__(kThreads) void tk_hist(TkGeom ge, const TkWorker *_
         const uint32_t c = lh[b1];
         if (c) atomicAdd(hist1 + (int64_t)i * kBins1 + b1, c);
     }
-    if (tid < kFineWindow && lf[tid]) atomicAdd(histf + (int64_t)i * kFineWindow + tid, lf[tid]);
+    for (int q = tid; q < kFineWindow; q += kThreads)
+        if (lf[q]) atomicAdd(histf + (int64_t)i * kFineWindow + q, lf[q]);
 }
 
 // Second kernel of the selection: the leading digits of Tc.  Grid (ge.relist_wgs, n).
@@ -857,7 +865,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
         uint32_t rank = ge.k - res[1];
         uint32_t count = res[2];
         const uint32_t wb = guess >> (kShift1 - kFineShift);      // first coarse bin of the fine window
-        if (prefix - wb < 2u) {
+        if (prefix - wb < (uint32_t)kWindowCoarse) {
             // the fine histogram covers this coarse bin: pick the fine bin as well (one wavefront)
             if (wave == 0) {
                 const uint32_t c = frow[(prefix - wb) * kFinePerCoarse + lane];
@@ -890,7 +898,7 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
             ws[i].relisted = 0u;
         }
         for (int q = tid; q < kBins1; q += kThreads) row[q] = 0;
-        if (tid < kFineWindow) frow[tid] = 0;
+        for (int q = tid; q < kFineWindow; q += kThreads) frow[q] = 0;
         return;
     }
 
@@ -963,17 +971,20 @@ __global__ __launch_bounds__(kThreads) void tk_pick(TkGeom ge, TkWorker *__restr
 // Copies the candidates that carry the prefix, as comp values, to the dense storage.  Each wavefront
 // takes a quarter of the workgroup's piece and writes its hits from the start of that quarter
 // onwards (as many slots as it reads, so it cannot overflow), and records {start, count} relative to
-// the worker's first region; no atomics, tk_resolve walks the records.  Grid (slices * parts, n).  Nothing to do
-// for a worker whose threshold needs no further digit, or whose lists did not fit (tk_resolve then selects
-// without lists).
+// the worker's first region; no atomics, tk_resolve walks the records.  While copying, the workgroup counts the
+// next kFirstBits bits of comp below the prefix (hist2: [n][kBinsFirst], added to with atomics, emptied by
+// tk_resolve) and every wavefront notes which of those digits occur in its piece (piece_bits: kPieceWords words
+// per piece, written whole).  Grid (slices * parts, n).  Nothing to do for a worker whose threshold needs no
+// further digit, or whose lists did not fit (tk_resolve then selects without lists).
 __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker *__restrict__ ws,
                                                        const uint2 *__restrict__ cand,
                                                        const uint32_t *__restrict__ cursor,
                                                        const uint32_t *__restrict__ cursor_b,
                                                        uint64_t *__restrict__ dense, uint2 *__restrict__ dense_dir,
-                                                       uint32_t *__restrict__ hist2)
+                                                       uint32_t *__restrict__ hist2, uint32_t *__restrict__ piece_bits)
 {
     __shared__ uint32_t lh2[kBinsFirst];
+    __shared__ uint32_t bits[kThreads / kWave][kPieceWords];
     const int per = gridDim.x;
     const int i = blockIdx.y;
     const int bx = blockIdx.x;
@@ -984,6 +995,7 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
     // the digit of comp right below the prefix (tk_resolve's first digit)
     const int s_lo = (int)pshift + ge.idx_bits - kFirstBits;      // pshift >= kFineShift > kFirstBits
     for (int b = tid; b < kBinsFirst; b += kThreads) lh2[b] = 0;
+    if (lane < kPieceWords) bits[wave][lane] = 0;
     __syncthreads();
     const SelKey sk = sel_key_of(ge.rand, ge.rand.step_now, i);
     const Piece pc = piece_of(ge, ws[i].relisted ? cursor_b : cursor, i);   // lists made anew count in cursor_b
@@ -1008,14 +1020,16 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
             if (hit) {
                 const uint64_t comp = composite(key, c[u].x, ge.idx_bits);
                 out[slot] = comp;
-                atomicAdd(&lh2[(uint32_t)(comp >> s_lo) & (uint32_t)(kBinsFirst - 1)], 1u);
+                const uint32_t digit = (uint32_t)(comp >> s_lo) & (uint32_t)(kBinsFirst - 1);
+                atomicAdd(&lh2[digit], 1u);
+                atomicOr(&bits[wave][digit >> 5], 1u << (digit & 31u));
             }
         }
     }
-    if (lane == 0) {
-        const int64_t rec = ((int64_t)i * per + bx) * 4 + wave;
-        dense_dir[rec] = make_uint2((uint32_t)(rbase - worker_base(ge, i)) + w0, count);
-    }
+    const int64_t rec = ((int64_t)i * per + bx) * 4 + wave;
+    if (lane == 0) dense_dir[rec] = make_uint2((uint32_t)(rbase - worker_base(ge, i)) + w0, count);
+    // the piece's bitmap, written whole every step (the wavefront reads back its own LDS atomics)
+    if (lane < kPieceWords) piece_bits[rec * kPieceWords + lane] = bits[wave][lane];
     __syncthreads();
     for (int b = tid; b < kBinsFirst; b += kThreads) {
         const uint32_t c = lh2[b];
@@ -1029,6 +1043,8 @@ __global__ __launch_bounds__(kThreads) void tk_compact(TkGeom ge, const TkWorker
 // guess and empties the worker's region cursors for it.
 constexpr int kMaxPieces = 2048;   // slices * parts * 4 never exceeds this (the host picks parts accordingly)
 constexpr int kFew = 256;         // at most this many elements are ranked directly instead of by further digits
+                                  // (1024 measured slower: ranking a thousand elements against each other costs
+                                  // more than one more digit over a threshold bin of a few thousand)
 static_assert(kMaxPieces <= 2 * kResolveThreads, "two pieces per thread in the prefix sum");
 
 constexpr int kScanUnroll = 4;    // independent loads per thread in the scans of the dense set
@@ -1091,7 +1107,7 @@ __device__ __forceinline__ uint64_t resolve_digits(Fetch fetch, uint32_t cnt, ui
         if (s_lo == 0 || (kWholeBins && left == rank)) {       // last digit, or all under this prefix are kept
             done = true;
             tc = prefix << s_lo;
-        } else if (left <= (uint32_t)kFew) {
+        } else if (left <= (uint32_t)min(kFew, nt)) {
             if (tid == 0) L.n_few = 0;
             __syncthreads();
             for (uint32_t qb = 0; qb < cnt; qb += kScanUnroll * nt) {
@@ -1363,6 +1379,7 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
                                                               uint32_t *__restrict__ cursor_b,
                                                               uint32_t *__restrict__ hist_full,
                                                               uint32_t *__restrict__ hist2,
+                                                              const uint32_t *__restrict__ piece_bits,
                                                               uint2 *__restrict__ cand, uint4 *__restrict__ tile_dir,
                                                               const float *__restrict__ xs, ExactSource es)
 {
@@ -1372,6 +1389,8 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
         struct {
             uint32_t rpre[kMaxPieces + 1];
             uint32_t rstart[kMaxPieces];
+            uint32_t plist[kFew];        // pieces that hold an element with the first digit of Tc
+            uint32_t n_plist;
         } pieces;
         ExactLds exact;
     };
@@ -1452,8 +1471,56 @@ __global__ __launch_bounds__(kResolveThreads) void tk_resolve(TkGeom ge, TkWorke
             // the threshold bin is the one of the smallest keys and the k-th largest lies below its listed
             // (non-zero) elements: among the zeros
             tc = zero_tail_threshold(dir_row, xs + (int64_t)i * ge.ld, ge, w.rank - cnt, L);
-        else
-            tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L, true);   // barriers since L.lh was filled
+        else {
+            // The first digit below the prefix from tk_compact's counts.  Usually at most kFew elements carry it:
+            // they sit in at most as many pieces, which the pieces' bitmaps name, so only those pieces are read
+            // (a few hundred elements instead of the whole threshold bin) and the elements ranked directly.
+            const int s_lo = s_hi - kFirstBits;
+            find_rank_bin(L.lh, L.part, L.res, kBinsFirst, w.rank);          // barriers since L.lh was filled
+            const uint32_t digit = L.res[0], left = L.res[2], rank1 = w.rank - L.res[1];
+            const bool found = L.res[3] != 0u;
+            const uint64_t prefix1 = ((uint64_t)w.prefix << kFirstBits) | digit;
+            if (found && left == rank1) {
+                tc = prefix1 << s_lo;                                         // all under this prefix are kept
+            } else if (found && left <= (uint32_t)min(kFew, kResolveThreads)) {
+                if (tid == 0) {
+                    U.pieces.n_plist = 0;
+                    L.n_few = 0;
+                }
+                __syncthreads();
+                for (int p = tid; p < pieces; p += kResolveThreads) {
+                    const uint32_t word = piece_bits[((int64_t)i * pieces + p) * kPieceWords + (digit >> 5)];
+                    if ((word >> (digit & 31u)) & 1u) {
+                        const uint32_t slot = atomicAdd(&U.pieces.n_plist, 1u);
+                        if (slot < (uint32_t)kFew) U.pieces.plist[slot] = (uint32_t)p;     // always: see n_listed
+                    }
+                }
+                __syncthreads();
+                const uint32_t n_listed = min(U.pieces.n_plist, (uint32_t)kFew);   // <= left: each names an element
+                for (uint32_t q = wave; q < n_listed; q += kResolveThreads / kWave) {
+                    const uint32_t p = U.pieces.plist[q];
+                    const uint32_t first = rstart[p], count = rpre[p + 1] - rpre[p];
+                    for (uint32_t e = lane; e < count; e += kWave) {
+                        const uint64_t comp = wdense[first + e];
+                        if ((comp >> s_lo) == prefix1) {
+                            const uint32_t slot = atomicAdd(&L.n_few, 1u);
+                            if (slot < (uint32_t)kFew) L.few[slot] = comp;
+                        }
+                    }
+                }
+                __syncthreads();
+                if ((uint32_t)tid < left) {
+                    const uint64_t mine = L.few[tid];
+                    uint32_t greater = 0;
+                    for (uint32_t u = 0; u < left; ++u) greater += L.few[u] > mine ? 1u : 0u;
+                    if (greater + 1 == rank1) L.tc_sh = mine;                 // comp values are unique: exactly one thread
+                }
+                __syncthreads();
+                tc = L.tc_sh;
+            } else {
+                tc = resolve_digits(fetch, cnt, w.prefix, w.rank, s_hi, L, true);
+            }
+        }
     }
     if (tid < ge.slices) cursor[i * ge.slices + tid] = 0;      // tk_compact was their last reader (slices <= 1024 threads)
     if (w.relisted) {                                          // tk_pick was the last reader of the full histogram
