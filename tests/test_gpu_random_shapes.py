@@ -8,6 +8,8 @@ thresholds among zeros, short and long vectors, the pass that carries the previo
 Bars as everywhere: kept sets, kept values and error memory bit-exact; theta, m, v, vhat within 1e-6 relative;
 block scales within 1e-5 relative.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -19,6 +21,8 @@ from test_gpu_methods import make as make_method_pair, run as run_method
 
 pytestmark = pytest.mark.gpu
 f32 = np.float32
+# other draws than the committed ones: COMP_AMS_SEED_BASE=1000 python -m pytest tests/test_gpu_random_shapes.py
+BASE = int(os.environ.get("COMP_AMS_SEED_BASE", "0"))
 
 
 def announce(msg):
@@ -97,6 +101,7 @@ def gradient_stream(seed, n, d):
 
 @pytest.mark.parametrize("seed", range(72))
 def test_error_feedback_random_case(seed):
+    seed += BASE
     rng = np.random.default_rng([seed, 0])
     n, d = draw_shape(rng, 5_000_000)
     comp = [P.TOPK, P.BLOCKSIGN, P.RANDK][int(rng.integers(0, 3))]
@@ -116,6 +121,7 @@ def test_error_feedback_random_case(seed):
 
 @pytest.mark.parametrize("seed", range(100, 130))
 def test_cd_adam_random_case(seed):
+    seed += BASE
     rng = np.random.default_rng([seed, 0])
     n, d = draw_shape(rng, 3_000_000)
     grads = gradient_stream(seed, n, d)
@@ -135,6 +141,7 @@ def test_cd_adam_random_case(seed):
 
 @pytest.mark.parametrize("seed", range(200, 224))
 def test_naive_compression_random_case(seed):
+    seed += BASE
     rng = np.random.default_rng([seed, 0])
     n, d = draw_shape(rng, 3_000_000)
     comp = [P.TOPK, P.BLOCKSIGN][int(rng.integers(0, 2))]
