@@ -15,7 +15,7 @@ import pytest
 
 import paper_2111_00705_amd as P
 from oracle import oracle as O
-from parity_util import make_pair, run_steps
+from parity_util import compare, make_pair, run_steps
 from test_gpu_cd_adam import make_cd_pair, make_cd_topk_pair, run_cd, run_cd_topk
 from test_gpu_methods import make as make_method_pair, run as run_method
 
@@ -149,5 +149,36 @@ def test_naive_compression_random_case(seed):
     announce(f"naive compression, seed {seed}: compressor {comp}, n={n}, d={d}, k or block={kb}")
     gpu, ora = make_method_pair(d, n, comp, kb, O.NAIVE, theta0=rng.standard_normal(d).astype(f32))
     run_method(gpu, ora, gradient_stream(seed, n, d), 5, f"seed {seed}")
+    gpu.destroy()
+    ora.close()
+
+
+@pytest.mark.parametrize("seed", range(300, 330))
+def test_error_feedback_random_case_with_16_bit_gradients(seed):
+    """The same draws with the gradients handed over as bfloat16 or half precision: the step must equal the step on
+    the widened values (which is what the oracle gets)."""
+    import torch
+    seed += BASE
+    rng = np.random.default_rng([seed, 0])
+    n, d = draw_shape(rng, 3_000_000)
+    comp = [P.TOPK, P.BLOCKSIGN, P.RANDK][int(rng.integers(0, 3))]
+    kb = draw_block(rng, d) if comp == P.BLOCKSIGN else draw_k(rng, d)
+    narrow = [torch.bfloat16, torch.float16][int(rng.integers(0, 2))]
+    announce(f"error feedback, {narrow}, seed {seed}: compressor {comp}, n={n}, d={d}, k or block={kb}")
+    gpu, ora = make_pair(d, n, comp, kb, theta0=rng.standard_normal(d).astype(f32))
+    if comp == P.RANDK:
+        gpu.set_rand(99 + seed, 0)
+        ora.set_rand(99 + seed, 0)
+    offsets = None
+    if comp == P.BLOCKSIGN:
+        offsets = np.minimum(np.arange((d + kb - 1) // kb + 1, dtype=np.int64) * kb, d)
+    grads = gradient_stream(seed, n, d)
+    for t in range(5):
+        g16 = torch.from_numpy(np.clip(grads(t), -6e4, 6e4)).to(narrow).cuda()        # half precision ends at 65504
+        wide = g16.float().cpu().numpy()
+        e_prev = ora.error.copy()
+        (gpu.step_bf16 if narrow == torch.bfloat16 else gpu.step_f16)(g16)
+        ora.step(wide)
+        compare(gpu, ora, x_for_values=wide + e_prev, tag=f"seed {seed} step {t}", offsets=offsets)
     gpu.destroy()
     ora.close()
