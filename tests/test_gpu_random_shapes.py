@@ -23,6 +23,8 @@ pytestmark = pytest.mark.gpu
 f32 = np.float32
 # other draws than the committed ones: COMP_AMS_SEED_BASE=1000 python -m pytest tests/test_gpu_random_shapes.py
 BASE = int(os.environ.get("COMP_AMS_SEED_BASE", "0"))
+# larger shapes (the oracle then takes seconds per step): COMP_AMS_SHAPE_SCALE=16
+SCALE = int(os.environ.get("COMP_AMS_SHAPE_SCALE", "1"))
 
 
 def announce(msg):
@@ -33,7 +35,7 @@ def draw_shape(rng, budget):
     """n and d with n * d <= budget; d log-uniform so that short vectors (one tile, a few tiles) are as likely as
     long ones."""
     n = int(rng.choice([1, 2, 3, 4, 7, 8, 16, 33]))
-    d_max = max(2, budget // n)
+    d_max = max(2, budget * SCALE // n)
     d = int(np.exp(rng.uniform(np.log(1.0) if rng.random() < 0.25 else np.log(min(3000.0, d_max)), np.log(d_max))))
     d = max(1, min(d, d_max))
     if rng.random() < 0.3:                          # a tile boundary, one short of it or one beyond
